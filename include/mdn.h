@@ -1,0 +1,129 @@
+/*
+ * C ABI of the MI355X (gfx950) Momentum DeltaNet (MDN) library.
+ *
+ * The operation is the stepwise-momentum delta rule of Sec. 3.1 (Eq. Mt.recurrent /
+ * St.recurrent).  Per (batch b, head h), with states S, M in R^{dk x dv}:
+ *
+ *     p_t = alpha_t k_t                      v~_t = v_t - S_{t-1}^T p_t
+ *     M_t = mu_t M_{t-1} - eta_t k_t v~_t^T  S_t  = alpha_t S_{t-1} - beta_t M_t
+ *     o_t = scale * S_t^T q_t                (read-out of the post-update state)
+ *
+ * mdn_chunk_fwd / mdn_chunk_bwd evaluate it (and its reverse-mode adjoint) with the exact
+ * chunkwise-parallel algorithm of Sec. 3.1 "Chunkwise Algorithm" / Appendix C-D;
+ * mdn_recurrent_step evaluates it token by token (decoding, Appendix E recurrent form).
+ *
+ * Conventions shared by every entry point
+ *   - Every pointer is a DEVICE pointer unless stated otherwise; the caller owns all buffers,
+ *     the library allocates nothing and keeps no state between calls.
+ *   - Token tensors are contiguous [B, T, H, D] (D = dk for q, k; dv for v, o), gates are
+ *     contiguous [B, T, H] fp32 in the LINEAR domain (alpha, mu in [0,1], beta step size;
+ *     mu = 0 is allowed), states are contiguous [B, H, dk, dv] fp32.
+ *   - shape.dtype selects the storage type of q, k, v, o, dO, dq, dk, dv and of every
+ *     intermediate the library stores: MDN_DTYPE_BF16 (bf16 MFMA operands, fp32 accumulation
+ *     and fp32 states) or MDN_DTYPE_F32 (fp32 MFMA throughout).
+ *   - All pointers must be 16-byte aligned.  dk, dv in {64, 128}; C = 64; T % C == 0.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
+ *     enqueued asynchronously on it; no call synchronises.
+ *   - Return value: MDN_OK (0) or a negative MDN_ERR_* code; nothing is launched when an
+ *     error is returned from validation.  NaN/Inf in the inputs propagate, they are not detected.
+ */
+#ifndef MDN_H
+#define MDN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { MDN_DTYPE_BF16 = 0, MDN_DTYPE_F32 = 1 };
+
+enum {
+    MDN_OK = 0,
+    MDN_ERR_NULL = -1,      /* a required pointer is NULL */
+    MDN_ERR_SHAPE = -2,     /* unsupported B/T/H/dk/dv/C (T % C != 0, dk or dv not in {64,128}, C != 64, ...) */
+    MDN_ERR_DTYPE = -3,     /* dtype is neither MDN_DTYPE_BF16 nor MDN_DTYPE_F32 */
+    MDN_ERR_WORKSPACE = -4, /* workspace_bytes smaller than mdn_workspace_bytes() reports */
+    MDN_ERR_ALIGN = -5,     /* a pointer is not 16-byte aligned */
+    MDN_ERR_LAUNCH = -6,    /* a kernel launch failed (hipGetLastError) */
+    MDN_ERR_DEVICE = -7     /* the current device is not a gfx950 GPU */
+};
+
+enum { MDN_WS_FWD = 0, MDN_WS_BWD = 1 };
+
+typedef struct mdn_shape {
+    int32_t B, T, H;  /* batch, sequence length, heads */
+    int32_t dk, dv;   /* key / value head dimensions */
+    int32_t C;        /* chunk size (64); ignored by mdn_recurrent_step */
+    int32_t dtype;    /* MDN_DTYPE_* */
+    float scale;      /* multiplies q; the paper's default is dk^-1/2 (Appendix E) */
+} mdn_shape;
+
+/* Bytes of scratch `workspace` that mdn_chunk_fwd (which = MDN_WS_FWD) or mdn_chunk_bwd
+ * (MDN_WS_BWD) needs for this shape.  Host-only; touches no device. */
+int mdn_workspace_bytes(const mdn_shape *shape, int which, size_t *bytes_out);
+
+/* Bytes of the optional `states_saved` buffer: the states S, M at the start of every chunk,
+ * [B, H, T/C, 2, dk, dv] in the storage dtype. */
+int mdn_saved_states_bytes(const mdn_shape *shape, size_t *bytes_out);
+
+/*
+ * Chunkwise forward (Sec. 3.1 "Chunkwise Algorithm"; Appendix C, D).
+ *   in : q, k [B,T,H,dk], v [B,T,H,dv] (storage dtype); beta, alpha, mu [B,T,H] fp32;
+ *        eta [B,T,H] fp32 or NULL (= 1); S0, M0 [B,H,dk,dv] fp32 or NULL (= 0).
+ *   out: o [B,T,H,dv] (storage dtype);
+ *        S_final, M_final [B,H,dk,dv] fp32, each may be NULL (not written);
+ *        vt_saved [B,T,H,dv] (storage dtype) or NULL: the correction values V~ that
+ *        mdn_chunk_bwd needs (Sec. 3.1 "Practical Considerations");
+ *        states_saved (see mdn_saved_states_bytes) or NULL: chunk-start states; when given to
+ *        mdn_chunk_bwd it skips their reconstruction from V~.
+ *   workspace: at least mdn_workspace_bytes(MDN_WS_FWD); contents are scratch.
+ */
+int mdn_chunk_fwd(const mdn_shape *shape, const void *q, const void *k, const void *v, const float *beta,
+                  const float *alpha, const float *mu, const float *eta, const float *S0, const float *M0,
+                  void *o, float *S_final, float *M_final, void *vt_saved, void *states_saved,
+                  void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Chunkwise backward: adjoint of mdn_chunk_fwd for the scalar
+ *     L = <o, dO> + <S_final, dS_final> + <M_final, dM_final>.
+ * The forward keeps V~ only (Sec. 3.1 "Practical Considerations"); the chunk-start states
+ * are reconstructed from it unless states_saved is given.
+ *   in : the forward inputs (same pointers/values as in the forward call), vt_saved (required),
+ *        states_saved or NULL, dO [B,T,H,dv] (storage dtype),
+ *        dS_final, dM_final [B,H,dk,dv] fp32 or NULL (= 0).
+ *   out: dq, dk [B,T,H,dk], dv [B,T,H,dv] (storage dtype); dbeta, dalpha, dmu [B,T,H] fp32;
+ *        deta [B,T,H] fp32 or NULL; dS0, dM0 [B,H,dk,dv] fp32 or NULL.
+ *        Gradients are with respect to the linear gate values.
+ *   workspace: at least mdn_workspace_bytes(MDN_WS_BWD).
+ */
+int mdn_chunk_bwd(const mdn_shape *shape, const void *q, const void *k, const void *v, const float *beta,
+                  const float *alpha, const float *mu, const float *eta, const float *S0, const float *M0,
+                  const void *vt_saved, const void *states_saved, const void *dO, const float *dS_final,
+                  const float *dM_final, void *dq, void *dk, void *dv, float *dbeta, float *dalpha,
+                  float *dmu, float *deta, float *dS0, float *dM0, void *workspace, size_t workspace_bytes,
+                  void *stream);
+
+/*
+ * Recurrent (decoding) form, Eq. Mt.recurrent / St.recurrent, Appendix E recurrent form:
+ * advances S, M in place over the shape.T tokens given (usually T = 1) and writes o.
+ *   in : q, k, v, beta, alpha, mu, eta as for mdn_chunk_fwd (T tokens);
+ *   io : S, M [B,H,dk,dv] fp32, updated in place;
+ *   out: o [B,T,H,dv] (storage dtype).
+ * No chunk-size restriction on T (T >= 1).
+ */
+int mdn_recurrent_step(const mdn_shape *shape, const void *q, const void *k, const void *v, const float *beta,
+                       const float *alpha, const float *mu, const float *eta, float *S, float *M, void *o,
+                       void *stream);
+
+/* Static, human-readable text for a return code. */
+const char *mdn_strerror(int code);
+
+/* Library version (major * 100 + minor). */
+int mdn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MDN_H */

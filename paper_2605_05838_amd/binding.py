@@ -1,0 +1,197 @@
+"""Thin ctypes binding of the MDN C-ABI library (include/mdn.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels of libmdn_hip.so.
+PyTorch supplies device memory and the HIP stream.  There is no CPU fallback: a missing
+library or a non-CUDA tensor raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmdn_hip.so")
+
+MDN_DTYPE_BF16, MDN_DTYPE_F32 = 0, 1
+MDN_WS_FWD, MDN_WS_BWD = 0, 1
+
+EXPORTS = ("mdn_version", "mdn_strerror", "mdn_workspace_bytes", "mdn_saved_states_bytes", "mdn_chunk_fwd",
+           "mdn_chunk_bwd", "mdn_recurrent_step")
+
+
+class MdnShape(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("T", ctypes.c_int32), ("H", ctypes.c_int32), ("dk", ctypes.c_int32),
+                ("dv", ctypes.c_int32), ("C", ctypes.c_int32), ("dtype", ctypes.c_int32), ("scale", ctypes.c_float)]
+
+
+class MdnError(RuntimeError):
+    pass
+
+
+_lib = None
+
+
+def load_library():
+    """dlopen libmdn_hip.so (built by __graft_entry__.build()) and declare the prototypes."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise MdnError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` first")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, sp, fp = ctypes.c_void_p, ctypes.POINTER(MdnShape), ctypes.c_void_p
+    lib.mdn_version.restype = ctypes.c_int
+    lib.mdn_strerror.restype = ctypes.c_char_p
+    lib.mdn_strerror.argtypes = [ctypes.c_int]
+    lib.mdn_workspace_bytes.restype = ctypes.c_int
+    lib.mdn_workspace_bytes.argtypes = [sp, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t)]
+    lib.mdn_saved_states_bytes.restype = ctypes.c_int
+    lib.mdn_saved_states_bytes.argtypes = [sp, ctypes.POINTER(ctypes.c_size_t)]
+    lib.mdn_chunk_fwd.restype = ctypes.c_int
+    lib.mdn_chunk_fwd.argtypes = [sp] + [vp] * 3 + [fp] * 6 + [vp, fp, fp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.mdn_chunk_bwd.restype = ctypes.c_int
+    lib.mdn_chunk_bwd.argtypes = [sp] + [vp] * 3 + [fp] * 6 + [vp] * 3 + [fp] * 2 + [vp] * 3 + [fp] * 6 + \
+        [vp, ctypes.c_size_t, vp]
+    lib.mdn_recurrent_step.restype = ctypes.c_int
+    lib.mdn_recurrent_step.argtypes = [sp] + [vp] * 3 + [fp] * 4 + [fp, fp, vp, vp]
+    _lib = lib
+    return lib
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise MdnError(f"{what}: {load_library().mdn_strerror(rc).decode()} (code {rc})")
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise MdnError("MDN tensors must live on the GPU (no CPU path exists)")
+    if not t.is_contiguous():
+        raise MdnError("MDN tensors must be contiguous")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _f32(t, name):
+    if t is not None and t.dtype != torch.float32:
+        raise MdnError(f"{name} must be float32")
+    return _ptr(t)
+
+
+def _dtype_code(t):
+    if t.dtype == torch.bfloat16:
+        return MDN_DTYPE_BF16
+    if t.dtype == torch.float32:
+        return MDN_DTYPE_F32
+    raise MdnError("q/k/v must be bfloat16 or float32")
+
+
+def make_shape(q, v, scale=None, C=64) -> MdnShape:
+    B, T, H, dk = q.shape
+    return MdnShape(B, T, H, dk, v.shape[-1], C, _dtype_code(q), float(dk ** -0.5 if scale is None else scale))
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def workspace_bytes(shape: MdnShape, which: int) -> int:
+    n = ctypes.c_size_t(0)
+    _check(load_library().mdn_workspace_bytes(ctypes.byref(shape), which, ctypes.byref(n)), "mdn_workspace_bytes")
+    return n.value
+
+
+def saved_states_bytes(shape: MdnShape) -> int:
+    n = ctypes.c_size_t(0)
+    _check(load_library().mdn_saved_states_bytes(ctypes.byref(shape), ctypes.byref(n)), "mdn_saved_states_bytes")
+    return n.value
+
+
+def _workspace(shape, which, workspace, device):
+    need = workspace_bytes(shape, which)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=device)
+    return workspace, workspace.numel() * workspace.element_size()
+
+
+def mdn_chunk_fwd(q, k, v, beta, alpha, mu, eta=None, S0=None, M0=None, scale=None, save_vt=False,
+                  save_states=False, output_final_state=True, workspace=None, out=None):
+    """Chunkwise forward.  Returns a dict: o, S, M (final states or None), vt, states (or None)."""
+    lib = load_library()
+    shape = make_shape(q, v, scale)
+    for t in (k, v):
+        if t.dtype != q.dtype:
+            raise MdnError("q, k, v must share one dtype")
+    out = {} if out is None else out
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    dev = q.device
+    o = out.get("o")
+    if o is None:
+        o = torch.empty((B, T, H, dv), dtype=q.dtype, device=dev)
+    S = M = vt = states = None
+    if output_final_state:
+        S = out.get("S") if out.get("S") is not None else torch.empty((B, H, dk, dv), dtype=torch.float32, device=dev)
+        M = out.get("M") if out.get("M") is not None else torch.empty((B, H, dk, dv), dtype=torch.float32, device=dev)
+    if save_vt:
+        vt = out.get("vt") if out.get("vt") is not None else torch.empty((B, T, H, dv), dtype=q.dtype, device=dev)
+    if save_states:
+        states = out.get("states")
+        if states is None:
+            states = torch.empty((B, H, T // 64, 2, dk, dv), dtype=q.dtype, device=dev)
+    workspace, wbytes = _workspace(shape, MDN_WS_FWD, workspace, dev)
+    rc = lib.mdn_chunk_fwd(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _f32(beta, "beta"), _f32(alpha, "alpha"),
+                           _f32(mu, "mu"), _f32(eta, "eta"), _f32(S0, "S0"), _f32(M0, "M0"), _ptr(o), _ptr(S),
+                           _ptr(M), _ptr(vt), _ptr(states), _ptr(workspace), wbytes, _stream())
+    _check(rc, "mdn_chunk_fwd")
+    return {"o": o, "S": S, "M": M, "vt": vt, "states": states, "workspace": workspace}
+
+
+def mdn_chunk_bwd(q, k, v, beta, alpha, mu, vt, dO, eta=None, S0=None, M0=None, states=None, dS_final=None,
+                  dM_final=None, scale=None, want_deta=False, want_dstates=True, workspace=None, out=None):
+    """Chunkwise backward.  Returns a dict: dq, dk, dv, dbeta, dalpha, dmu, deta, dS0, dM0."""
+    lib = load_library()
+    shape = make_shape(q, v, scale)
+    out = {} if out is None else out
+    B, T, H, dk = q.shape
+    dv_ = v.shape[-1]
+    dev = q.device
+
+    def get(name, shp, dt):
+        t = out.get(name)
+        return t if t is not None else torch.empty(shp, dtype=dt, device=dev)
+
+    dq = get("dq", (B, T, H, dk), q.dtype)
+    dk_t = get("dk", (B, T, H, dk), q.dtype)
+    dv_t = get("dv", (B, T, H, dv_), q.dtype)
+    dbeta = get("dbeta", (B, T, H), torch.float32)
+    dalpha = get("dalpha", (B, T, H), torch.float32)
+    dmu = get("dmu", (B, T, H), torch.float32)
+    deta = get("deta", (B, T, H), torch.float32) if want_deta else None
+    dS0 = get("dS0", (B, H, dk, dv_), torch.float32) if want_dstates else None
+    dM0 = get("dM0", (B, H, dk, dv_), torch.float32) if want_dstates else None
+    workspace, wbytes = _workspace(shape, MDN_WS_BWD, workspace, dev)
+    rc = lib.mdn_chunk_bwd(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _f32(beta, "beta"), _f32(alpha, "alpha"),
+                           _f32(mu, "mu"), _f32(eta, "eta"), _f32(S0, "S0"), _f32(M0, "M0"), _ptr(vt), _ptr(states),
+                           _ptr(dO), _f32(dS_final, "dS_final"), _f32(dM_final, "dM_final"), _ptr(dq), _ptr(dk_t),
+                           _ptr(dv_t), _f32(dbeta, "dbeta"), _f32(dalpha, "dalpha"), _f32(dmu, "dmu"),
+                           _f32(deta, "deta"), _f32(dS0, "dS0"), _f32(dM0, "dM0"), _ptr(workspace), wbytes, _stream())
+    _check(rc, "mdn_chunk_bwd")
+    return {"dq": dq, "dk": dk_t, "dv": dv_t, "dbeta": dbeta, "dalpha": dalpha, "dmu": dmu, "deta": deta,
+            "dS0": dS0, "dM0": dM0, "workspace": workspace}
+
+
+def mdn_recurrent_step(q, k, v, beta, alpha, mu, S, M, eta=None, scale=None, out=None):
+    """Recurrent form over the T tokens given; S, M [B,H,dk,dv] fp32 are updated in place.  Returns o."""
+    lib = load_library()
+    shape = make_shape(q, v, scale)
+    B, T, H, _ = q.shape
+    o = out if out is not None else torch.empty((B, T, H, v.shape[-1]), dtype=q.dtype, device=q.device)
+    rc = lib.mdn_recurrent_step(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _f32(beta, "beta"),
+                                _f32(alpha, "alpha"), _f32(mu, "mu"), _f32(eta, "eta"), _f32(S, "S"), _f32(M, "M"),
+                                _ptr(o), _stream())
+    _check(rc, "mdn_recurrent_step")
+    return o

@@ -1,0 +1,142 @@
+// Device-side building blocks shared by the MDN kernels (gfx950 / CDNA4, wave64).
+//
+// All dense contractions go through one 16x16 MFMA tile primitive:
+//   bf16 storage -> v_mfma_f32_16x16x32_bf16 (8 bf16 per lane per operand, K step 32)
+//   fp32 storage -> 4 x v_mfma_f32_16x16x4_f32 (4 floats per lane per operand, K step 16)
+// Operand fragments are always read as ONE 16-byte vector of K-contiguous elements, so every
+// operand matrix must be laid out with the contraction index fastest.
+//
+// Register layouts (lane = 0..63, r = lane % 16, kg = lane / 16):
+//   A fragment: row r of the 16-row tile, K elements [kg*EPL, kg*EPL + EPL) of the K step
+//   B fragment: column r of the 16-column tile, same K elements
+//   accumulator f32x4: D[m = kg*4 + x][n = r], x = 0..3
+// The K index inside a step is permuted identically for A and B in the fp32 variant (lane group
+// kg feeds k = 4*kg + s to the s-th instruction); a contraction does not care.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mdn {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16_t;
+
+constexpr int kC = 64;        // chunk size
+constexpr int kThreads = 256; // 4 waves per workgroup
+constexpr int kCoefRows = 6;  // per-chunk coefficient block: [kCoefRows][64] floats
+
+// rows of the coefficient block
+enum { COEF_A = 0, COEF_B = 1, COEF_GC = 2, COEF_RC = 3, COEF_SCALAR = 4, COEF_ETA = 5 };
+// COEF_SCALAR row: [0] = a_C, [1] = b_C, [2] = m_C
+
+template <typename T> struct Op;
+
+template <> struct Op<bf16_t> {
+    static constexpr int EPL = 8;    // elements per lane per fragment
+    static constexpr int KSTEP = 32; // contraction elements per mma()
+    static constexpr int PAD = 8;    // LDS row padding (elements) that keeps 16-byte row alignment
+    typedef bf16x8 Frag;
+    static __device__ __forceinline__ Frag load(const bf16_t *p) { return *reinterpret_cast<const Frag *>(p); }
+    static __device__ __forceinline__ f32x4 mma(Frag a, Frag b, f32x4 c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+    }
+};
+
+template <> struct Op<float> {
+    static constexpr int EPL = 4;
+    static constexpr int KSTEP = 16;
+    static constexpr int PAD = 4;
+    typedef f32x4 Frag;
+    static __device__ __forceinline__ Frag load(const float *p) { return *reinterpret_cast<const Frag *>(p); }
+    static __device__ __forceinline__ f32x4 mma(Frag a, Frag b, f32x4 c) {
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(a[0], b[0], c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(a[1], b[1], c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(a[2], b[2], c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(a[3], b[3], c, 0, 0, 0);
+        return c;
+    }
+};
+
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(bf16_t x) { return (float)x; }
+template <typename T> __device__ __forceinline__ T from_f32(float x) { return (T)x; }
+// value of x after a round trip through the storage type
+template <typename T> __device__ __forceinline__ float rounded(float x) { return to_f32(from_f32<T>(x)); }
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+__device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
+
+// acc[nt] += A(16 x K) * B(K x 16*NT)
+//   A(m, k)  = A[m * lda + k]          (16 rows starting at A)
+//   B(k, n)  = Bt[n * ldb + k]         (16*NT columns starting at Bt)
+template <typename T, int NT, int K>
+__device__ __forceinline__ void mma_rows(f32x4 (&acc)[NT], const T *__restrict__ A, int lda,
+                                         const T *__restrict__ Bt, int ldb) {
+    typedef Op<T> O;
+    const int r = lane_id() & 15, kg = lane_id() >> 4;
+    const T *ap = A + r * lda + kg * O::EPL;
+    const T *bp = Bt + r * ldb + kg * O::EPL;
+#pragma unroll
+    for (int k0 = 0; k0 < K; k0 += O::KSTEP) {
+        typename O::Frag a = O::load(ap + k0);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            typename O::Frag b = O::load(bp + nt * 16 * ldb + k0);
+            acc[nt] = O::mma(a, b, acc[nt]);
+        }
+    }
+}
+
+template <int NT> __device__ __forceinline__ void zero_acc(f32x4 (&acc)[NT]) {
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+}
+
+// dst[(m) * ld + n] = sgn * D(m, n) for the 16 x 16*NT block held in acc (row-major destination)
+template <typename T, int NT>
+__device__ __forceinline__ void store_rows(const f32x4 (&acc)[NT], T *dst, int ld, float sgn) {
+    const int r = lane_id() & 15, kg = lane_id() >> 4;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int x = 0; x < 4; ++x) dst[(kg * 4 + x) * ld + nt * 16 + r] = from_f32<T>(sgn * acc[nt][x]);
+}
+
+// dst[(n) * ld + m] = sgn * D(m, n): transposed destination, 4 consecutive m per lane
+template <typename T, int NT>
+__device__ __forceinline__ void store_rows_t(const f32x4 (&acc)[NT], T *dst, int ld, float sgn) {
+    const int r = lane_id() & 15, kg = lane_id() >> 4;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int x = 0; x < 4; ++x) dst[(nt * 16 + r) * ld + kg * 4 + x] = from_f32<T>(sgn * acc[nt][x]);
+}
+
+// sum over the 16 lanes that share kg (i.e. over the column index r of an accumulator row)
+__device__ __forceinline__ float reduce16(float v) {
+    v += __shfl_xor(v, 1);
+    v += __shfl_xor(v, 2);
+    v += __shfl_xor(v, 4);
+    v += __shfl_xor(v, 8);
+    return v;
+}
+
+// sum over the whole wave
+__device__ __forceinline__ float reduce64(float v) {
+    v = reduce16(v);
+    v += __shfl_xor(v, 16);
+    v += __shfl_xor(v, 32);
+    return v;
+}
+
+// Workgroup id -> (bh, sub) with all `nsub` workgroups of one bh on the same XCD (workgroups are
+// dealt round-robin to the 8 XCDs, each with its own L2).  Grid must be 8 * ceil(BH/8) * nsub.
+__device__ __forceinline__ void xcd_map(int bid, int nsub, int &bh, int &sub) {
+    const int xcd = bid & 7, slot = bid >> 3;
+    bh = (slot / nsub) * 8 + xcd;
+    sub = slot % nsub;
+}
+
+} // namespace mdn

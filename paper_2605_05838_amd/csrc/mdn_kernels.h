@@ -1,0 +1,90 @@
+// Host-side launch interface between the C ABI (mdn_api.hip) and the kernel translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace mdn {
+
+struct Dims {
+    int B, T, H, N, BH; // N = T / 64 chunks, BH = B * H
+    int dk, dv;
+    int dtype; // MDN_DTYPE_*
+    float scale;
+};
+
+// Chunk-parallel precompute ("intra") kernel arguments.  Workspace tensors are chunk-blocked:
+// [BH][N][rows][cols] in the storage dtype unless noted.
+struct IntraArgs {
+    const void *q, *k, *v;                  // [B,T,H,D]
+    const float *alpha, *beta, *mu, *eta;   // [B,T,H]; eta may be null
+    float *coef;                            // [BH][N][6][64] fp32
+    void *KT;                               // [dk][64]   raw k, transposed
+    // forward mode
+    void *U;                                // [64][dv]   T V
+    void *nY;                               // [64][dk]  -T diag(a^-) P
+    void *Z;                                // [64][dk]   T diag(b^-) P
+    void *Bm;                               // [64][64]   (Q~ K~^T) .* Gamma
+    // backward mode
+    void *QT;                               // [dk][64]   raw q, transposed
+    void *nYT, *ZT;                         // [dk][64]   transposes of -Y, Z
+    void *BmT;                              // [64][64]   Bm transposed
+    void *TmT;                              // [64][64]   T transposed
+};
+
+struct ScanFwdArgs {
+    const void *q;                          // [B,T,H,dk]
+    const float *coef;
+    const void *KT, *U, *nY, *Z, *Bm;
+    const float *S0, *M0;                   // [B,H,dk,dv] or null
+    void *o;                                // [B,T,H,dv]
+    void *vt_saved;                         // [B,T,H,dv] or null
+    void *states_saved;                     // [BH][N][2][dk][dv] or null
+    float *S_final, *M_final;               // or null
+};
+
+// State reconstruction from saved V~ (backward, when the forward did not keep the states).
+struct RebuildArgs {
+    const float *coef;
+    const void *KT;
+    const void *vt_saved;                   // [B,T,H,dv]
+    const float *S0, *M0;
+    void *states;                           // [BH][N][2][dk][dv]
+};
+
+struct ScanBwdArgs {
+    const void *k;                          // [B,T,H,dk]
+    const void *dO;                         // [B,T,H,dv]
+    const float *coef;
+    const void *QT, *nYT, *ZT, *BmT;
+    const float *dS_final, *dM_final;       // or null
+    void *dVtT;                             // [BH][N][dv][64]  adjoint of V~, transposed per chunk
+    void *dstates;                          // [BH][N][2][dk][dv] adjoints of the chunk-END states
+    float *dS0, *dM0;                       // or null
+};
+
+struct GradArgs {
+    const void *q, *k;                      // [B,T,H,dk]
+    const float *alpha, *beta, *mu, *eta;
+    const void *vt_saved, *dO;              // [B,T,H,dv]
+    const void *KT, *QT, *TmT, *dVtT;
+    const void *states, *dstates;           // [BH][N][2][dk][dv]
+    void *dq, *dk, *dv;
+    float *dalpha, *dbeta, *dmu, *deta;     // deta may be null
+};
+
+struct RecurrentArgs {
+    const void *q, *k, *v;
+    const float *alpha, *beta, *mu, *eta;
+    float *S, *M;
+    void *o;
+};
+
+hipError_t launch_intra(const Dims &d, bool bwd, const IntraArgs &a, hipStream_t s);
+hipError_t launch_scan_fwd(const Dims &d, const ScanFwdArgs &a, hipStream_t s);
+hipError_t launch_rebuild(const Dims &d, const RebuildArgs &a, hipStream_t s);
+hipError_t launch_scan_bwd(const Dims &d, const ScanBwdArgs &a, hipStream_t s);
+hipError_t launch_grad(const Dims &d, const GradArgs &a, hipStream_t s);
+hipError_t launch_recurrent(const Dims &d, const RecurrentArgs &a, hipStream_t s);
+
+} // namespace mdn

@@ -1,0 +1,77 @@
+"""CPU checks of the boundary: the library loads, exports every symbol include/mdn.h declares,
+and the host-side entry points (no device access) validate their arguments."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2605_05838_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "mdn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mdn_[a-z_]+)\s*\(", text)))
+
+
+def test_header_and_binding_agree_on_the_export_list():
+    assert declared_symbols() == sorted(binding.EXPORTS)
+
+
+def test_library_exports_every_declared_symbol():
+    lib = binding.load_library()
+    for name in declared_symbols():
+        assert hasattr(lib, name), name
+    assert lib.mdn_version() >= 100
+    assert lib.mdn_strerror(0) == b"ok"
+    assert b"workspace" in lib.mdn_strerror(-4)
+
+
+def shape(**kw):
+    base = dict(B=2, T=128, H=3, dk=128, dv=128, C=64, dtype=0, scale=0.1)
+    base.update(kw)
+    return binding.MdnShape(**base)
+
+
+def test_workspace_query_validates_shapes():
+    lib = binding.load_library()
+    n = ctypes.c_size_t(0)
+    assert lib.mdn_workspace_bytes(ctypes.byref(shape()), 0, ctypes.byref(n)) == 0 and n.value > 0
+    fwd = n.value
+    assert lib.mdn_workspace_bytes(ctypes.byref(shape()), 1, ctypes.byref(n)) == 0 and n.value > fwd
+    assert lib.mdn_workspace_bytes(ctypes.byref(shape(T=100)), 0, ctypes.byref(n)) == -2      # T % C
+    assert lib.mdn_workspace_bytes(ctypes.byref(shape(dk=96, dv=96)), 0, ctypes.byref(n)) == -2
+    assert lib.mdn_workspace_bytes(ctypes.byref(shape(C=32)), 0, ctypes.byref(n)) == -2
+    assert lib.mdn_workspace_bytes(ctypes.byref(shape(dtype=7)), 0, ctypes.byref(n)) == -3
+    assert lib.mdn_workspace_bytes(ctypes.byref(shape()), 0, None) == -1
+    assert lib.mdn_workspace_bytes(None, 0, ctypes.byref(n)) == -1
+    assert lib.mdn_saved_states_bytes(ctypes.byref(shape()), ctypes.byref(n)) == 0
+    assert n.value == 2 * 3 * 2 * 2 * 128 * 128 * 2
+    # fp32 storage doubles every stored intermediate except the fp32 coefficient block
+    assert binding.workspace_bytes(shape(dtype=1), 0) > 1.9 * fwd - 4 * 6 * 64 * 2 * 3 * 2
+
+
+def test_entry_points_reject_null_and_misaligned_pointers_before_touching_a_device():
+    lib = binding.load_library()
+    s = shape()
+    null = [None] * 17
+    assert lib.mdn_chunk_fwd(ctypes.byref(s), *null[:14], None, 0, None) == -1
+    assert lib.mdn_recurrent_step(ctypes.byref(s), *[None] * 10, None) == -1
+    good = ctypes.c_void_p(4096)
+    bad = ctypes.c_void_p(4098)
+    args = [good, good, good, good, good, good, None, None, None, bad, None, None, None, None, good, 1 << 40, None]
+    assert lib.mdn_chunk_fwd(ctypes.byref(s), *args) == -5
+    args[9] = good
+    args[15] = 16
+    assert lib.mdn_chunk_fwd(ctypes.byref(s), *args) == -4
+
+
+def test_cpu_tensors_are_refused():
+    import torch
+    x = torch.zeros(1, 64, 1, 64)
+    g = torch.zeros(1, 64, 1)
+    with pytest.raises(binding.MdnError):
+        binding.mdn_chunk_fwd(x, x, x, g, g, g)
