@@ -1,0 +1,155 @@
+#!/usr/bin/env python3
+"""Benchmark of the MDN chunkwise hot path on one MI355X.
+
+A step = one forward (keeping the correction values for the backward) + one backward of the whole
+layer-shaped batch, through the C ABI.  Default workload: the 1.3B-layer training shape
+(B=4, T=4096, H=16, dk=dv=128, C=64, bf16 storage, fp32 states), the configuration the headline
+metric (fwd+bwd tokens/s, % of bf16 MFMA peak) is quoted on.  Inputs are synthetic and resident
+in HBM before the timed region.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_F32_TFLOPS = 157.3     # fp32 matrix
+PEAK_HBM_GBS = 8000.0
+
+
+def flops_per_tokhd(C, dk, dv):
+    """Algorithmic flops per token per head of each kernel (dense C x C tiles, causal half not
+    exploited), following the step list of the chunkwise algorithm."""
+    tri = 2.0 * C * C / 3.0
+    return {
+        "intra_fwd": 8 * C * dk + 2 * C * dv + tri,      # masked products, solve, U/Y/Z
+        "scan_fwd": 12 * dk * dv + 2 * C * dv,           # V~, inter read-out, S'/M' update, intra output
+        "intra_bwd": 8 * C * dk + tri,                   # recomputed products, solve, Y/Z
+        "rebuild": 4 * dk * dv,                          # S'/M' update lines only
+        "scan_bwd": 12 * dk * dv + 2 * C * dv,           # dV~, dS, dM
+        "grad": 8 * C * dk + 6 * C * dv + 12 * dk * dv,  # chunk-parallel gradients
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=3, help="measurement configuration 0..4 (default: 1.3B fwd+bwd)")
+    ap.add_argument("--forward-only", action="store_true")
+    ap.add_argument("--save-states", action="store_true",
+                    help="forward keeps the chunk-start states (skips their reconstruction in the backward)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket kernels with HIP events")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (the path has no multi-GPU part); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from gpu_util import to_dev
+    from paper_2605_05838_amd import binding, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    w = synth.config(args.config)
+    do_bwd = w.backward and not args.forward_only
+    t = to_dev(w)
+
+    fout, bout = {}, {}
+    fws = bws = None
+
+    def step():
+        nonlocal fout, bout, fws, bws
+        f = binding.mdn_chunk_fwd(t["q"], t["k"], t["v"], t["beta"], t["alpha"], t["mu"], eta=t["eta"], S0=t["S0"],
+                                  M0=t["M0"], scale=w.scale, save_vt=do_bwd, save_states=do_bwd and args.save_states,
+                                  workspace=fws, out=fout)
+        fws, fout = f["workspace"], f
+        if do_bwd:
+            g = binding.mdn_chunk_bwd(t["q"], t["k"], t["v"], t["beta"], t["alpha"], t["mu"], f["vt"], t["dO"],
+                                      eta=t["eta"], S0=t["S0"], M0=t["M0"], states=f["states"], scale=w.scale,
+                                      workspace=bws, out=bout)
+            bws, bout = g["workspace"], g
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    if not args.no_kernel_events:
+        binding.profile_begin()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(args.steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kern = {} if args.no_kernel_events else binding.profile_end()
+    ms_per_step = wall * 1e3 / args.steps
+    tokens_per_s = w.tokens * args.steps / wall
+
+    # ---- roofline of the dominant kernel (algorithmic flops / live-measured average duration)
+    tokhd = w.B * w.T * w.H
+    fl = flops_per_tokhd(w.C, w.dk, w.dv)
+    peak = PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_F32_TFLOPS
+    kernels = {}
+    for name, (ms, cnt) in kern.items():
+        if cnt and name in fl:
+            avg = ms / cnt
+            kernels[name] = {"avg_ms": round(avg, 4), "launches": cnt,
+                             "gflop_per_launch": round(fl[name] * tokhd / 1e9, 3),
+                             "tflops": round(fl[name] * tokhd / (avg * 1e-3) / 1e12, 2)}
+    roofline = None
+    if kernels:
+        dom = max(kernels, key=lambda k: kernels[k]["avg_ms"])
+        roofline = {"kernel": dom, "bound": "mfma", "achieved": kernels[dom]["tflops"], "peak": peak,
+                    "unit": "TFLOP/s", "frac": round(kernels[dom]["tflops"] / peak, 5), "traffic": None}
+    total_flops = sum(fl[k] for k in (("intra_fwd", "scan_fwd") + (("intra_bwd", "rebuild", "scan_bwd", "grad")
+                                                                   if do_bwd else ()))) * tokhd
+    path_tflops = total_flops / (ms_per_step * 1e-3) / 1e12
+
+    # ---- CPU baseline: the fp64 oracle as it stands, same workload, on the host cores
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import mdn_oracle as orc
+        a = {k: (None if v is None else np.asarray(v, dtype=np.float64)) for k, v in w.arrays.items()}
+        c0 = time.perf_counter()
+        r = orc.forward(a["q"], a["k"], a["v"], a["alpha"], a["beta"], a["mu"], eta=a["eta"], S0=a["S0"], M0=a["M0"],
+                        scale=w.scale)
+        threads = r["threads"]
+        if do_bwd:
+            orc.backward(a["q"], a["k"], a["v"], a["alpha"], a["beta"], a["mu"], a["dO"], eta=a["eta"], S0=a["S0"],
+                         M0=a["M0"], scale=w.scale)
+        csec = time.perf_counter() - c0
+        cpu = {"value": round(w.tokens / csec, 1), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+               "sample": f"the full workload once ({w.B}x{w.T} tokens, {w.H} heads, fp64, "
+                         f"{'forward+backward' if do_bwd else 'forward'}), {csec:.1f} s"}
+
+    line = {
+        "metric": "MDN layer fwd+bwd tokens/sec at 1.3B shape; % bf16 MFMA peak" if do_bwd and args.config == 3
+        else f"MDN layer {'fwd+bwd' if do_bwd else 'fwd'} tokens/sec",
+        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "T": w.T, "H": w.H, "dk": w.dk, "dv": w.dv, "C": w.C,
+                   "pass": "fwd+bwd" if do_bwd else "fwd", "states_saved_by_forward": bool(args.save_states)},
+        "path_tflops": round(path_tflops, 2), "path_frac_of_mfma_peak": round(path_tflops / peak, 5),
+        "gpu_event_ms_per_step": round(ev0.elapsed_time(ev1) / args.steps, 4),
+        "roofline": roofline, "kernels": kernels, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -14,7 +14,8 @@
  *
  * Conventions shared by every entry point
  *   - Every pointer is a DEVICE pointer unless stated otherwise; the caller owns all buffers,
- *     the library allocates nothing and keeps no state between calls.
+ *     the library allocates no device memory and keeps no state between calls (the optional
+ *     per-kernel timing facility at the end of this header is the one exception).
  *   - Token tensors are contiguous [B, T, H, D] (D = dk for q, k; dv for v, o), gates are
  *     contiguous [B, T, H] fp32 in the LINEAR domain (alpha, mu in [0,1], beta step size;
  *     mu = 0 is allowed), states are contiguous [B, H, dk, dv] fp32.
@@ -116,6 +117,27 @@ int mdn_chunk_bwd(const mdn_shape *shape, const void *q, const void *k, const vo
 int mdn_recurrent_step(const mdn_shape *shape, const void *q, const void *k, const void *v, const float *beta,
                        const float *alpha, const float *mu, const float *eta, float *S, float *M, void *o,
                        void *stream);
+
+/*
+ * Optional per-kernel timing (used by the benchmark to attribute time to kernels).
+ * Between mdn_profile_begin() and mdn_profile_end() every kernel the library launches is
+ * bracketed by a pair of HIP events recorded on the launch stream.  mdn_profile_end()
+ * synchronises those events and adds, per kernel id, the elapsed milliseconds into ms[id] and
+ * the number of launches into launches[id] (HOST arrays of n entries; ids >= n are dropped),
+ * then releases the events.  Not thread-safe; meant for one benchmarking thread.
+ */
+enum {
+    MDN_KERNEL_INTRA_FWD = 0, /* chunk-local coefficients, masked products, triangular solve, U/Y/Z */
+    MDN_KERNEL_SCAN_FWD = 1,  /* sequential inter-chunk propagation of S and M, outputs */
+    MDN_KERNEL_INTRA_BWD = 2, /* same as 0 in the operand layouts of the reverse pass */
+    MDN_KERNEL_REBUILD = 3,   /* chunk-start states reconstructed from V~ */
+    MDN_KERNEL_SCAN_BWD = 4,  /* reverse inter-chunk scan of dS, dM */
+    MDN_KERNEL_GRAD = 5,      /* chunk-parallel gradients dq, dk, dv, dalpha, dbeta, dmu, deta */
+    MDN_KERNEL_RECURRENT = 6, /* token-by-token recurrent form */
+    MDN_KERNEL_COUNT = 7
+};
+int mdn_profile_begin(void);
+int mdn_profile_end(float *ms, int *launches, int n);
 
 /* Static, human-readable text for a return code. */
 const char *mdn_strerror(int code);

@@ -18,7 +18,9 @@ MDN_DTYPE_BF16, MDN_DTYPE_F32 = 0, 1
 MDN_WS_FWD, MDN_WS_BWD = 0, 1
 
 EXPORTS = ("mdn_version", "mdn_strerror", "mdn_workspace_bytes", "mdn_saved_states_bytes", "mdn_chunk_fwd",
-           "mdn_chunk_bwd", "mdn_recurrent_step")
+           "mdn_chunk_bwd", "mdn_recurrent_step", "mdn_profile_begin", "mdn_profile_end")
+
+KERNEL_NAMES = ("intra_fwd", "scan_fwd", "intra_bwd", "rebuild", "scan_bwd", "grad", "recurrent")
 
 
 class MdnShape(ctypes.Structure):
@@ -56,6 +58,9 @@ def load_library():
         [vp, ctypes.c_size_t, vp]
     lib.mdn_recurrent_step.restype = ctypes.c_int
     lib.mdn_recurrent_step.argtypes = [sp] + [vp] * 3 + [fp] * 4 + [fp, fp, vp, vp]
+    lib.mdn_profile_begin.restype = ctypes.c_int
+    lib.mdn_profile_end.restype = ctypes.c_int
+    lib.mdn_profile_end.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int), ctypes.c_int]
     _lib = lib
     return lib
 
@@ -195,3 +200,16 @@ def mdn_recurrent_step(q, k, v, beta, alpha, mu, S, M, eta=None, scale=None, out
                                 _ptr(o), _stream())
     _check(rc, "mdn_recurrent_step")
     return o
+
+
+def profile_begin():
+    _check(load_library().mdn_profile_begin(), "mdn_profile_begin")
+
+
+def profile_end():
+    """Per-kernel {name: (total_ms, launches)} since profile_begin(); synchronises the recorded events."""
+    n = len(KERNEL_NAMES)
+    ms = (ctypes.c_float * n)()
+    cnt = (ctypes.c_int * n)()
+    _check(load_library().mdn_profile_end(ms, cnt, n), "mdn_profile_end")
+    return {KERNEL_NAMES[i]: (float(ms[i]), int(cnt[i])) for i in range(n)}

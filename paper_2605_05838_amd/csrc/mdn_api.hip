@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 #include <string.h>
+#include <vector>
 
 using namespace mdn;
 
@@ -76,11 +77,50 @@ BwdWs carve_bwd(const Dims &d, void *ws) {
 
 int launch_status(hipError_t e) { return e == hipSuccess ? MDN_OK : MDN_ERR_LAUNCH; }
 
+// ---- optional per-kernel timing: event pairs around every launch while enabled
+struct TimedLaunch { int id; hipEvent_t start, stop; };
+bool g_profiling = false;
+std::vector<TimedLaunch> g_timed;
+
+template <typename F> int timed(int id, hipStream_t s, F &&launch) {
+    if (!g_profiling) return launch_status(launch());
+    TimedLaunch t{id, nullptr, nullptr};
+    if (hipEventCreate(&t.start) != hipSuccess || hipEventCreate(&t.stop) != hipSuccess) return MDN_ERR_LAUNCH;
+    hipEventRecord(t.start, s);
+    const int rc = launch_status(launch());
+    hipEventRecord(t.stop, s);
+    g_timed.push_back(t);
+    return rc;
+}
+
 } // namespace
 
 extern "C" {
 
 int mdn_version(void) { return 100; }
+
+int mdn_profile_begin(void) {
+    g_profiling = true;
+    return MDN_OK;
+}
+
+int mdn_profile_end(float *ms, int *launches, int n) {
+    g_profiling = false;
+    int rc = MDN_OK;
+    for (const TimedLaunch &t : g_timed) {
+        float e = 0.f;
+        if (hipEventSynchronize(t.stop) != hipSuccess || hipEventElapsedTime(&e, t.start, t.stop) != hipSuccess)
+            rc = MDN_ERR_LAUNCH;
+        else if (t.id < n) {
+            if (ms) ms[t.id] += e;
+            if (launches) launches[t.id] += 1;
+        }
+        hipEventDestroy(t.start);
+        hipEventDestroy(t.stop);
+    }
+    g_timed.clear();
+    return rc;
+}
 
 const char *mdn_strerror(int code) {
     switch (code) {
@@ -135,14 +175,14 @@ int mdn_chunk_fwd(const mdn_shape *shape, const void *q, const void *k, const vo
     IntraArgs ia = {};
     ia.q = q; ia.k = k; ia.v = v; ia.alpha = alpha; ia.beta = beta; ia.mu = mu; ia.eta = eta;
     ia.coef = w.coef; ia.KT = w.KT; ia.U = w.U; ia.nY = w.nY; ia.Z = w.Z; ia.Bm = w.Bm;
-    rc = launch_status(launch_intra(d, false, ia, s));
+    rc = timed(MDN_KERNEL_INTRA_FWD, s, [&] { return launch_intra(d, false, ia, s); });
     if (rc) return rc;
 
     ScanFwdArgs sa = {};
     sa.q = q; sa.coef = w.coef; sa.KT = w.KT; sa.U = w.U; sa.nY = w.nY; sa.Z = w.Z; sa.Bm = w.Bm;
     sa.S0 = S0; sa.M0 = M0; sa.o = o; sa.vt_saved = vt_saved; sa.states_saved = states_saved;
     sa.S_final = S_final; sa.M_final = M_final;
-    return launch_status(launch_scan_fwd(d, sa, s));
+    return timed(MDN_KERNEL_SCAN_FWD, s, [&] { return launch_scan_fwd(d, sa, s); });
 }
 
 int mdn_chunk_bwd(const mdn_shape *shape, const void *q, const void *k, const void *v, const float *beta,
@@ -169,7 +209,7 @@ int mdn_chunk_bwd(const mdn_shape *shape, const void *q, const void *k, const vo
     IntraArgs ia = {};
     ia.q = q; ia.k = k; ia.v = v; ia.alpha = alpha; ia.beta = beta; ia.mu = mu; ia.eta = eta;
     ia.coef = w.coef; ia.KT = w.KT; ia.QT = w.QT; ia.nYT = w.nYT; ia.ZT = w.ZT; ia.BmT = w.BmT; ia.TmT = w.TmT;
-    rc = launch_status(launch_intra(d, true, ia, s));
+    rc = timed(MDN_KERNEL_INTRA_BWD, s, [&] { return launch_intra(d, true, ia, s); });
     if (rc) return rc;
 
     // chunk-start states: given by the forward, or reconstructed from V~
@@ -177,7 +217,7 @@ int mdn_chunk_bwd(const mdn_shape *shape, const void *q, const void *k, const vo
     if (!states) {
         RebuildArgs ra = {};
         ra.coef = w.coef; ra.KT = w.KT; ra.vt_saved = vt_saved; ra.S0 = S0; ra.M0 = M0; ra.states = w.states;
-        rc = launch_status(launch_rebuild(d, ra, s));
+        rc = timed(MDN_KERNEL_REBUILD, s, [&] { return launch_rebuild(d, ra, s); });
         if (rc) return rc;
         states = w.states;
     }
@@ -186,7 +226,7 @@ int mdn_chunk_bwd(const mdn_shape *shape, const void *q, const void *k, const vo
     sb.k = k; sb.dO = dO; sb.coef = w.coef; sb.QT = w.QT; sb.nYT = w.nYT; sb.ZT = w.ZT; sb.BmT = w.BmT;
     sb.dS_final = dS_final; sb.dM_final = dM_final; sb.dVtT = w.dVtT; sb.dstates = w.dstates;
     sb.dS0 = dS0; sb.dM0 = dM0;
-    rc = launch_status(launch_scan_bwd(d, sb, s));
+    rc = timed(MDN_KERNEL_SCAN_BWD, s, [&] { return launch_scan_bwd(d, sb, s); });
     if (rc) return rc;
 
     GradArgs ga = {};
@@ -194,7 +234,7 @@ int mdn_chunk_bwd(const mdn_shape *shape, const void *q, const void *k, const vo
     ga.vt_saved = vt_saved; ga.dO = dO; ga.KT = w.KT; ga.QT = w.QT; ga.TmT = w.TmT; ga.dVtT = w.dVtT;
     ga.states = states; ga.dstates = w.dstates;
     ga.dq = dq; ga.dk = dk; ga.dv = dv; ga.dalpha = dalpha; ga.dbeta = dbeta; ga.dmu = dmu; ga.deta = deta;
-    return launch_status(launch_grad(d, ga, s));
+    return timed(MDN_KERNEL_GRAD, s, [&] { return launch_grad(d, ga, s); });
 }
 
 int mdn_recurrent_step(const mdn_shape *shape, const void *q, const void *k, const void *v, const float *beta,
@@ -210,7 +250,8 @@ int mdn_recurrent_step(const mdn_shape *shape, const void *q, const void *k, con
     RecurrentArgs ra = {};
     ra.q = q; ra.k = k; ra.v = v; ra.alpha = alpha; ra.beta = beta; ra.mu = mu; ra.eta = eta;
     ra.S = S; ra.M = M; ra.o = o;
-    return launch_status(launch_recurrent(d, ra, static_cast<hipStream_t>(stream)));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    return timed(MDN_KERNEL_RECURRENT, s, [&] { return launch_recurrent(d, ra, s); });
 }
 
 } // extern "C"
