@@ -41,7 +41,7 @@ struct Carver {
 };
 
 struct FwdWs { float *coef; void *KT, *U, *nY, *Z, *Bm; size_t total; };
-struct BwdWs { float *coef; void *KT, *QT, *nYT, *ZT, *BmT, *TmT, *dVtT, *dstates, *states; size_t total; };
+struct BwdWs { float *coef; void *KT, *QT, *nYT, *ZT, *BmT, *TmT, *dstates, *states; size_t total; };
 
 FwdWs carve_fwd(const Dims &d, void *ws) {
     const size_t es = d.dtype == MDN_DTYPE_F32 ? 4 : 2, nb = (size_t)d.BH * d.N;
@@ -68,7 +68,6 @@ BwdWs carve_bwd(const Dims &d, void *ws) {
     w.ZT = c.take(nb * d.dk * 64 * es);
     w.BmT = c.take(nb * 4096 * es);
     w.TmT = c.take(nb * 4096 * es);
-    w.dVtT = c.take(nb * d.dv * 64 * es);
     w.dstates = c.take(nb * 2 * d.dk * d.dv * es);
     w.states = c.take(nb * 2 * d.dk * d.dv * es);
     w.total = c.off;
@@ -224,16 +223,16 @@ int mdn_chunk_bwd(const mdn_shape *shape, const void *q, const void *k, const vo
 
     ScanBwdArgs sb = {};
     sb.k = k; sb.dO = dO; sb.coef = w.coef; sb.QT = w.QT; sb.nYT = w.nYT; sb.ZT = w.ZT; sb.BmT = w.BmT;
-    sb.dS_final = dS_final; sb.dM_final = dM_final; sb.dVtT = w.dVtT; sb.dstates = w.dstates;
+    sb.TmT = w.TmT; sb.dS_final = dS_final; sb.dM_final = dM_final; sb.dv = dv; sb.dstates = w.dstates;
     sb.dS0 = dS0; sb.dM0 = dM0;
     rc = timed(MDN_KERNEL_SCAN_BWD, s, [&] { return launch_scan_bwd(d, sb, s); });
     if (rc) return rc;
 
     GradArgs ga = {};
     ga.q = q; ga.k = k; ga.alpha = alpha; ga.beta = beta; ga.mu = mu; ga.eta = eta;
-    ga.vt_saved = vt_saved; ga.dO = dO; ga.KT = w.KT; ga.QT = w.QT; ga.TmT = w.TmT; ga.dVtT = w.dVtT;
+    ga.vt_saved = vt_saved; ga.dO = dO; ga.dv = dv; ga.KT = w.KT; ga.QT = w.QT;
     ga.states = states; ga.dstates = w.dstates;
-    ga.dq = dq; ga.dk = dk; ga.dv = dv; ga.dalpha = dalpha; ga.dbeta = dbeta; ga.dmu = dmu; ga.deta = deta;
+    ga.dq = dq; ga.dk = dk; ga.dalpha = dalpha; ga.dbeta = dbeta; ga.dmu = dmu; ga.deta = deta;
     return timed(MDN_KERNEL_GRAD, s, [&] { return launch_grad(d, ga, s); });
 }
 

@@ -89,6 +89,36 @@ __device__ __forceinline__ void mma_rows(f32x4 (&acc)[NT], const T *__restrict__
     }
 }
 
+// four consecutive storage elements from four floats, as one vector store / load
+__device__ __forceinline__ void store4(bf16_t *p, f32x4 v) {
+    bf16x4 o = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
+    *reinterpret_cast<bf16x4 *>(p) = o;
+}
+__device__ __forceinline__ void store4(float *p, f32x4 v) { *reinterpret_cast<f32x4 *>(p) = v; }
+__device__ __forceinline__ f32x4 load4(const bf16_t *p) {
+    const bf16x4 v = *reinterpret_cast<const bf16x4 *>(p);
+    return f32x4{(float)v[0], (float)v[1], (float)v[2], (float)v[3]};
+}
+__device__ __forceinline__ f32x4 load4(const float *p) { return *reinterpret_cast<const f32x4 *>(p); }
+
+// 16 bytes of storage elements
+template <typename T> struct Vec16 {
+    T e[Op<T>::EPL];
+};
+
+// Blocked layouts of the chunk-local tensors that the library itself produces and consumes.
+// kblk: a [R][K] MFMA operand (fragment = row, KSTEP consecutive k) is stored as [K/KSTEP][R][KSTEP],
+//       so the 16 rows x KSTEP elements one wave-level fragment load touches are contiguous.
+// vblk: a [R][dv] tensor exchanged in accumulator layout (a lane holds 4 consecutive dv of one row)
+//       is stored as [dv/16][R][16], so the 16 rows x 16 dv of one accumulator tile are contiguous.
+template <typename T> __device__ __forceinline__ size_t kblk(int R, int row, int k) {
+    constexpr int S = Op<T>::KSTEP;
+    return ((size_t)(k / S) * R + row) * S + (k % S);
+}
+__device__ __forceinline__ size_t vblk(int R, int row, int dv) {
+    return ((size_t)(dv >> 4) * R + row) * 16 + (dv & 15);
+}
+
 template <int NT> __device__ __forceinline__ void zero_acc(f32x4 (&acc)[NT]) {
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -110,8 +140,43 @@ __device__ __forceinline__ void store_rows_t(const f32x4 (&acc)[NT], T *dst, int
     const int r = lane_id() & 15, kg = lane_id() >> 4;
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
+        store4(dst + (nt * 16 + r) * ld + kg * 4, sgn * acc[nt]);
+}
+
+// as mma_rows, with B stored in the vblk layout of a [R][K] tensor: B(k, n) = Bv[vblk(R, n, k)]
+template <typename T, int NT, int K>
+__device__ __forceinline__ void mma_rows_vblk(f32x4 (&acc)[NT], const T *__restrict__ A, int lda,
+                                              const T *__restrict__ Bv, int R) {
+    typedef Op<T> O;
+    const int r = lane_id() & 15, kg = lane_id() >> 4;
+    const T *ap = A + r * lda + kg * O::EPL;
 #pragma unroll
-        for (int x = 0; x < 4; ++x) dst[(nt * 16 + r) * ld + kg * 4 + x] = from_f32<T>(sgn * acc[nt][x]);
+    for (int k0 = 0; k0 < K; k0 += O::KSTEP) {
+        typename O::Frag a = O::load(ap + k0);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            typename O::Frag b = O::load(Bv + vblk(R, nt * 16 + r, k0 + kg * O::EPL));
+            acc[nt] = O::mma(a, b, acc[nt]);
+        }
+    }
+}
+
+// as mma_rows, with B stored in the kblk layout of a [R][K] operand
+template <typename T, int NT, int K>
+__device__ __forceinline__ void mma_rows_kblk(f32x4 (&acc)[NT], const T *__restrict__ A, int lda,
+                                              const T *__restrict__ Bk, int R) {
+    typedef Op<T> O;
+    const int r = lane_id() & 15, kg = lane_id() >> 4;
+    const T *ap = A + r * lda + kg * O::EPL;
+#pragma unroll
+    for (int k0 = 0; k0 < K; k0 += O::KSTEP) {
+        typename O::Frag a = O::load(ap + k0);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            typename O::Frag b = O::load(Bk + kblk<T>(R, nt * 16 + r, k0 + kg * O::EPL));
+            acc[nt] = O::mma(a, b, acc[nt]);
+        }
+    }
 }
 
 // sum over the 16 lanes that share kg (i.e. over the column index r of an accumulator row)

@@ -4,7 +4,7 @@
 // chunk formulas of Sec. 3.1 / Appendix C, with S, M the chunk-START states, dS', dM' the adjoints
 // of the chunk-END states, dV~ from the reverse scan, K~ = eta k, P = alpha k, Q~ = scale q:
 //
-//   dR  = T^T dV~   (= dV)              dBm = tril(dO V~^T)           dA = -tril_strict(dR V~^T)
+//   dR  = T^T dV~   (= dV, formed by the reverse scan)   dBm = tril(dO V~^T)   dA = -tril_strict(dR V~^T)
 //   W1  = dBm .* Gamma                  W2  = dA .* Gamma^-
 //   dQ~ = W1 K~ + a.(dO S^T) - b.(dO M^T)
 //   dK~ = W1^T Q~ + W2^T P + Gamma_C.(V~ dS'^T) - Rho_C.(V~ dM'^T)
@@ -47,10 +47,9 @@ __device__ __forceinline__ f32x4 rowdot(const f32x4 (&t)[NT], const T *X, size_t
 template <typename T, int DK, int DV>
 __global__ __launch_bounds__(kThreads) void grad_kernel(Dims d, GradArgs a) {
     typedef Op<T> O;
-    constexpr int LDW = 64 + O::PAD, LDR = DV + O::PAD;
-    constexpr int NK = DK / 16, NV = DV / 16;
-    constexpr size_t DR_BYTES = sizeof(T) * 64 * LDR, RHO_BYTES = sizeof(float) * 64 * LDG;
-    constexpr size_t ALIAS_BYTES = DR_BYTES > RHO_BYTES ? DR_BYTES : RHO_BYTES;
+    constexpr int LDW = 64 + O::PAD;
+    constexpr int NK = DK / 16;
+    constexpr size_t ALIAS_BYTES = sizeof(float) * 64 * LDG;
 
     __shared__ float sG[64 * LDG];     // Gamma; recycled as the per-entry products of dmu
     __shared__ float sDG1[64 * LDG];   // direct dGamma from Bm; recycled as the products of dalpha
@@ -65,7 +64,6 @@ __global__ __launch_bounds__(kThreads) void grad_kernel(Dims d, GradArgs a) {
     __shared__ float s_ga[64], s_gb[64], s_gm[64];
     __shared__ float s_red[4][3];
 
-    T *sDR = reinterpret_cast<T *>(sAlias);          // dR, natural [64][LDR]        (phases 1-3)
     float *sRho = reinterpret_cast<float *>(sAlias); // Rho [64][LDG]                (phase 4)
 
     const int tid = threadIdx.x, lane = lane_id(), w = wave_id(), r = lane & 15, kg = lane >> 4, i0 = w * 16;
@@ -77,6 +75,7 @@ __global__ __launch_bounds__(kThreads) void grad_kernel(Dims d, GradArgs a) {
     const T *kgl = static_cast<const T *>(a.k) + tok0 * DK;
     const T *vtg = static_cast<const T *>(a.vt_saved) + tok0 * DV;
     const T *dog = static_cast<const T *>(a.dO) + tok0 * DV;
+    const T *drg = static_cast<const T *>(a.dv) + tok0 * DV; // dR = T^T dV~ (= dV), from the reverse scan
     const T *KTg = static_cast<const T *>(a.KT) + blk * (DK * 64);
     const T *QTg = static_cast<const T *>(a.QT) + blk * (DK * 64);
     const T *Sg = static_cast<const T *>(a.states) + blk * (2 * DK * DV), *Mg = Sg + DK * DV;
@@ -109,23 +108,6 @@ __global__ __launch_bounds__(kThreads) void grad_kernel(Dims d, GradArgs a) {
         s_drc[j] = rho; // Rho_{C,j}
     }
 
-    // ---------------- phase 1: dR = T^T dV~ for rows j = i0..i0+15; this is dV
-    {
-        f32x4 accR[NV];
-        zero_acc(accR);
-        mma_rows<T, NV, 64>(accR, static_cast<const T *>(a.TmT) + blk * 4096 + i0 * 64, 64,
-                            static_cast<const T *>(a.dVtT) + blk * (DV * 64), 64);
-        T *dvg = static_cast<T *>(a.dv) + tok0 * DV;
-#pragma unroll
-        for (int nt = 0; nt < NV; ++nt)
-#pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                const int j = i0 + kg * 4 + x, c = nt * 16 + r;
-                const T v = from_f32<T>(accR[nt][x]);
-                sDR[j * LDR + c] = v;
-                dvg[(size_t)j * rsv + c] = v;
-            }
-    }
     __syncthreads();
 
     // ---------------- phase 2: the four 64x64 products and the masked matrices built from them
@@ -136,7 +118,7 @@ __global__ __launch_bounds__(kThreads) void grad_kernel(Dims d, GradArgs a) {
         zero_acc(accQK);
         zero_acc(accKK);
         mma_rows<T, 4, DV>(accB, dog + (size_t)i0 * rsv, (int)rsv, vtg, (int)rsv);
-        mma_rows<T, 4, DV>(accA, sDR + i0 * LDR, LDR, vtg, (int)rsv);
+        mma_rows<T, 4, DV>(accA, drg + (size_t)i0 * rsv, (int)rsv, vtg, (int)rsv);
         mma_rows<T, 4, DK>(accQK, qg + (size_t)i0 * rsk, (int)rsk, kgl, (int)rsk);
         mma_rows<T, 4, DK>(accKK, kgl + (size_t)i0 * rsk, (int)rsk, kgl, (int)rsk);
 #pragma unroll
@@ -164,10 +146,10 @@ __global__ __launch_bounds__(kThreads) void grad_kernel(Dims d, GradArgs a) {
     {
         f32x4 accQ[NK], t[NK];
         zero_acc(accQ);
-        mma_rows<T, NK, 64>(accQ, sW1e + i0 * LDW, LDW, KTg, 64);
+        mma_rows_kblk<T, NK, 64>(accQ, sW1e + i0 * LDW, LDW, KTg, DK);
         // a . (dO S^T), b . (dO M^T)
         zero_acc(t);
-        mma_rows<T, NK, DV>(t, dog + (size_t)i0 * rsv, (int)rsv, Sg, DV);
+        mma_rows_vblk<T, NK, DV>(t, dog + (size_t)i0 * rsv, (int)rsv, Sg, DK);
         f32x4 da = rowdot<T, NK>(t, qg + (size_t)i0 * rsk, rsk);
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
@@ -176,7 +158,7 @@ __global__ __launch_bounds__(kThreads) void grad_kernel(Dims d, GradArgs a) {
             for (int nt = 0; nt < NK; ++nt) accQ[nt][x] += ai * t[nt][x];
         }
         zero_acc(t);
-        mma_rows<T, NK, DV>(t, dog + (size_t)i0 * rsv, (int)rsv, Mg, DV);
+        mma_rows_vblk<T, NK, DV>(t, dog + (size_t)i0 * rsv, (int)rsv, Mg, DK);
         f32x4 db = rowdot<T, NK>(t, qg + (size_t)i0 * rsk, rsk);
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
@@ -199,9 +181,9 @@ __global__ __launch_bounds__(kThreads) void grad_kernel(Dims d, GradArgs a) {
 
         // dP = W2 K~ - a^- . (dR S^T) + b^- . (dR M^T)
         zero_acc(accP);
-        mma_rows<T, NK, 64>(accP, sW2e + i0 * LDW, LDW, KTg, 64);
+        mma_rows_kblk<T, NK, 64>(accP, sW2e + i0 * LDW, LDW, KTg, DK);
         zero_acc(t);
-        mma_rows<T, NK, DV>(t, sDR + i0 * LDR, LDR, Sg, DV);
+        mma_rows_vblk<T, NK, DV>(t, drg + (size_t)i0 * rsv, (int)rsv, Sg, DK);
         f32x4 dam = rowdot<T, NK>(t, kgl + (size_t)i0 * rsk, rsk); // k_i . (S dR_i); P_i = alpha_i k_i
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
@@ -211,7 +193,7 @@ __global__ __launch_bounds__(kThreads) void grad_kernel(Dims d, GradArgs a) {
             for (int nt = 0; nt < NK; ++nt) accP[nt][x] -= am * t[nt][x];
         }
         zero_acc(t);
-        mma_rows<T, NK, DV>(t, sDR + i0 * LDR, LDR, Mg, DV);
+        mma_rows_vblk<T, NK, DV>(t, drg + (size_t)i0 * rsv, (int)rsv, Mg, DK);
         f32x4 dbm = rowdot<T, NK>(t, kgl + (size_t)i0 * rsk, rsk);
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
@@ -234,10 +216,10 @@ __global__ __launch_bounds__(kThreads) void grad_kernel(Dims d, GradArgs a) {
         // dK~ = W1^T Q~ + W2^T P + Gamma_C . (V~ dS'^T) - Rho_C . (V~ dM'^T), rows j = i0..i0+15
         f32x4 accK[NK], t[NK];
         zero_acc(accK);
-        mma_rows<T, NK, 64>(accK, sW1T + i0 * LDW, LDW, QTg, 64);
-        mma_rows<T, NK, 64>(accK, sW2T + i0 * LDW, LDW, KTg, 64);
+        mma_rows_kblk<T, NK, 64>(accK, sW1T + i0 * LDW, LDW, QTg, DK);
+        mma_rows_kblk<T, NK, 64>(accK, sW2T + i0 * LDW, LDW, KTg, DK);
         zero_acc(t);
-        mma_rows<T, NK, DV>(t, vtg + (size_t)i0 * rsv, (int)rsv, dSg, DV);
+        mma_rows_vblk<T, NK, DV>(t, vtg + (size_t)i0 * rsv, (int)rsv, dSg, DK);
         f32x4 dgc = rowdot<T, NK>(t, kgl + (size_t)i0 * rsk, rsk);
         float gC[4], rC[4];
 #pragma unroll
@@ -248,7 +230,7 @@ __global__ __launch_bounds__(kThreads) void grad_kernel(Dims d, GradArgs a) {
             for (int nt = 0; nt < NK; ++nt) accK[nt][x] += gC[x] * t[nt][x];
         }
         zero_acc(t);
-        mma_rows<T, NK, DV>(t, vtg + (size_t)i0 * rsv, (int)rsv, dMg, DV);
+        mma_rows_vblk<T, NK, DV>(t, vtg + (size_t)i0 * rsv, (int)rsv, dMg, DK);
         f32x4 drc = rowdot<T, NK>(t, kgl + (size_t)i0 * rsk, rsk);
 #pragma unroll
         for (int x = 0; x < 4; ++x)
@@ -292,7 +274,7 @@ __global__ __launch_bounds__(kThreads) void grad_kernel(Dims d, GradArgs a) {
         p3 = reduce64(p3);
         if (lane == 0) { s_red[w][0] = p1; s_red[w][1] = p2; s_red[w][2] = p3; }
     }
-    __syncthreads(); // also: all reads of sDR are done, its space becomes Rho
+    __syncthreads();
 
     // ---------------- phase 4: reverse of the coefficient scans (wave 0)
     if (w == 0) {

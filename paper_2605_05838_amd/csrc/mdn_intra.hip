@@ -13,6 +13,8 @@
 //
 // One workgroup (4 waves) per (chunk, batch*head).  Forward mode writes U, -Y, Z, Bm and K^T;
 // backward mode writes the transposed operands the reverse scan needs (-Y^T, Z^T, Bm^T, T^T, K^T, Q^T).
+// Everything is written in the blocked layouts of mdn_device.h (kblk / vblk), in which the serial
+// scans' fragment loads are contiguous.
 #include "mdn_device.h"
 #include "mdn_kernels.h"
 
@@ -21,10 +23,7 @@ namespace mdn {
 namespace {
 
 constexpr int LDA = 68; // row stride (floats) of the fp32 A / T matrix in LDS
-
-template <typename T> struct Vec16 { // 16 bytes of storage elements
-    T e[Op<T>::EPL];
-};
+constexpr int LDG = 65; // row stride (floats) of Gamma in LDS
 
 // natural [64][D] tile: rows of the chunk -> LDS [64][ld]
 template <typename T, int D>
@@ -51,13 +50,13 @@ __device__ __forceinline__ void load_tile_transposed(T *dst, int ld, const T *sr
     }
 }
 
-// LDS [R][ld] (first 64 columns) -> global [R][64]
+// LDS [R][ld] (first 64 columns) -> global, kblk layout of an [R][64] operand
 template <typename T>
 __device__ __forceinline__ void store_tile_64cols(T *dst, const T *src, int ld, int rows, int tid) {
     constexpr int E = Op<T>::EPL, CPR = 64 / E;
     for (int c = tid; c < rows * CPR; c += kThreads) {
-        const int row = c / CPR, cc = c % CPR;
-        *reinterpret_cast<Vec16<T> *>(dst + row * 64 + cc * E) =
+        const int row = c % rows, cc = c / rows;
+        *reinterpret_cast<Vec16<T> *>(dst + kblk<T>(rows, row, cc * E)) =
             *reinterpret_cast<const Vec16<T> *>(src + row * ld + cc * E);
     }
 }
@@ -72,7 +71,7 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
     constexpr int REGION = REG_NAT > REG_TR ? REG_NAT : REG_TR;
 
     __shared__ __align__(16) T sR[REGION];
-    __shared__ __align__(16) float sG[64 * 64];
+    __shared__ __align__(16) float sG[64 * LDG];
     __shared__ __align__(16) float sA[64 * LDA];
     __shared__ __align__(16) T sTop[64 * LDT];
     __shared__ float s_al[64], s_be[64], s_mu[64], s_et[64], s_a[64], s_b[64], s_cs[64];
@@ -115,7 +114,7 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
             if (i == j) { my_a = pa; my_b = pb; }
             rho = (i == j) ? 1.f : rho * mu;
             g = al * g + be * rho;
-            sG[i * 64 + j] = g;
+            sG[i * LDG + j] = g;
         }
         s_a[j] = my_a;
         s_b[j] = my_b;
@@ -129,28 +128,54 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
     }
     __syncthreads();
 
-    // ---- masked intra-chunk products: wave w owns rows i0..i0+15
+    // ---- masked intra-chunk products: wave w owns rows i0..i0+15.
+    //      The Q K^T product is formed in the orientation whose accumulator lanes hold 4 consecutive
+    //      entries along the contraction index of the consumer (j for Bm, i for Bm^T).
     const int r = lane & 15, kq = lane >> 4, i0 = w * 16;
     {
         f32x4 kk[4], qk[4];
         zero_acc(kk);
         zero_acc(qk);
         mma_rows<T, 4, DK>(kk, sK + i0 * LDN, LDN, sK, LDN);
-        mma_rows<T, 4, DK>(qk, sQ + i0 * LDN, LDN, sK, LDN);
-        T *bm_out = static_cast<T *>(BWD ? a.BmT : a.Bm) + blk * 4096;
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
             for (int x = 0; x < 4; ++x) {
                 const int i = i0 + kq * 4 + x, j = nt * 16 + r;
-                const float gam = sG[i * 64 + j];
-                const float gprev = (i > 0) ? sG[(i - 1) * 64 + j] : 0.f;
-                const float et = s_et[j];
-                sA[i * LDA + j] = (j < i) ? s_al[i] * et * gprev * kk[nt][x] : 0.f;
-                const float bij = (j <= i) ? d.scale * et * gam * qk[nt][x] : 0.f;
-                if (BWD) bm_out[j * 64 + i] = from_f32<T>(bij);
-                else bm_out[i * 64 + j] = from_f32<T>(bij);
+                const float gprev = (i > 0) ? sG[(i - 1) * LDG + j] : 0.f;
+                sA[i * LDA + j] = (j < i) ? s_al[i] * s_et[j] * gprev * kk[nt][x] : 0.f;
             }
+        if (BWD) {
+            // qk[nt][x] = q_i . k_j, i = i0 + kq*4 + x, j = nt*16 + r  ->  Bm^T row j, k = i
+            mma_rows<T, 4, DK>(qk, sQ + i0 * LDN, LDN, sK, LDN);
+            T *out = static_cast<T *>(a.BmT) + blk * 4096;
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) {
+                const int j = nt * 16 + r;
+                f32x4 v;
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    const int i = i0 + kq * 4 + x;
+                    v[x] = (j <= i) ? d.scale * s_et[j] * sG[i * LDG + j] * qk[nt][x] : 0.f;
+                }
+                store4(out + kblk<T>(64, j, i0 + kq * 4), v);
+            }
+        } else {
+            // qk[nt][x] = k_j . q_i, j = i0 + kq*4 + x, i = nt*16 + r  ->  Bm row i, k = j
+            mma_rows<T, 4, DK>(qk, sK + i0 * LDN, LDN, sQ, LDN);
+            T *out = static_cast<T *>(a.Bm) + blk * 4096;
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) {
+                const int i = nt * 16 + r;
+                f32x4 v;
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    const int j = i0 + kq * 4 + x;
+                    v[x] = (j <= i) ? d.scale * s_et[j] * sG[i * LDG + j] * qk[nt][x] : 0.f;
+                }
+                store4(out + kblk<T>(64, i, i0 + kq * 4), v);
+            }
+        }
     }
     __syncthreads();
 
@@ -188,14 +213,20 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
     store_tile_64cols<T>(static_cast<T *>(a.KT) + blk * (DK * 64), sKT, LDT, DK, tid);
     if (BWD) {
         store_tile_64cols<T>(static_cast<T *>(a.QT) + blk * (DK * 64), sXT, LDT, DK, tid);
-        T *tt = static_cast<T *>(a.TmT) + blk * 4096;
-        for (int c = tid; c < 4096; c += kThreads) {
-            const int jj = c >> 6, ii = c & 63;
-            tt[c] = from_f32<T>(sA[ii * LDA + jj]);
+        T *tt = static_cast<T *>(a.TmT) + blk * 4096; // T^T: row j, k = i
+        constexpr int E = O::EPL;
+        for (int c = tid; c < 64 * (64 / E); c += kThreads) {
+            const int jj = c & 63, cc = c >> 6;
+            Vec16<T> v;
+#pragma unroll
+            for (int e = 0; e < E; ++e) v.e[e] = from_f32<T>(sA[(cc * E + e) * LDA + jj]);
+            *reinterpret_cast<Vec16<T> *>(tt + kblk<T>(64, jj, cc * E)) = v;
         }
     }
 
-    // ---- WY-style factors.  pass 0: U = T V (forward only); pass 1: Y; pass 2: Z
+    // ---- WY-style factors.  pass 0: U = T V (forward only); pass 1: Y; pass 2: Z.
+    //      Each product is formed in the orientation whose accumulator lanes hold 4 consecutive
+    //      entries along the index that is contiguous in the consumer's layout.
     for (int pass = BWD ? 1 : 0; pass < 3; ++pass) {
         if (tid < 64) {
             const float bprev = (tid > 0) ? s_b[tid - 1] : 0.f;
@@ -207,30 +238,41 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
             sTop[ii * LDT + jj] = from_f32<T>(sA[ii * LDA + jj] * s_cs[jj]);
         }
         __syncthreads();
+        const float sgn = pass == 1 ? -1.f : 1.f;
         if (!BWD) {
             if (pass == 0) {
-                f32x4 u[DV / 16];
-                zero_acc(u);
-                mma_rows<T, DV / 16, 64>(u, sTop + i0 * LDT, LDT, sXT, LDT);
-                store_rows<T, DV / 16>(u, static_cast<T *>(a.U) + blk * (64 * DV) + i0 * DV, DV, 1.f);
+                // U^T[dv][i] = sum_j V^T[dv][j] T[i][j]  ->  vblk [dv/16][token][16]
+#pragma unroll
+                for (int mt = 0; mt < DV / 64; ++mt) {
+                    const int m0 = (w * (DV / 64) + mt) * 16;
+                    f32x4 u[4];
+                    zero_acc(u);
+                    mma_rows<T, 4, 64>(u, sXT + m0 * LDT, LDT, sTop, LDT);
+                    T *out = static_cast<T *>(a.U) + blk * (64 * DV);
+#pragma unroll
+                    for (int nt = 0; nt < 4; ++nt) store4(out + vblk(64, nt * 16 + r, m0 + kq * 4), u[nt]);
+                }
             } else {
-                f32x4 y[DK / 16];
-                zero_acc(y);
-                mma_rows<T, DK / 16, 64>(y, sTop + i0 * LDT, LDT, sKT, LDT);
-                T *out = static_cast<T *>(pass == 1 ? a.nY : a.Z) + blk * (64 * DK) + i0 * DK;
-                store_rows<T, DK / 16>(y, out, DK, pass == 1 ? -1.f : 1.f);
+                // Y^T[dk][i] = sum_j K^T[dk][j] (T diag(cs))[i][j]  ->  kblk: row i, k = dk
+#pragma unroll
+                for (int mt = 0; mt < DK / 64; ++mt) {
+                    const int m0 = (w * (DK / 64) + mt) * 16;
+                    f32x4 y[4];
+                    zero_acc(y);
+                    mma_rows<T, 4, 64>(y, sKT + m0 * LDT, LDT, sTop, LDT);
+                    T *out = static_cast<T *>(pass == 1 ? a.nY : a.Z) + blk * (64 * DK);
+#pragma unroll
+                    for (int nt = 0; nt < 4; ++nt) store4(out + kblk<T>(64, nt * 16 + r, m0 + kq * 4), sgn * y[nt]);
+                }
             }
         } else {
-            // Y^T[dk][i] = sum_j K^T[dk][j] (T diag(cs))[i][j]
+            // Y[i][dk] = sum_j (T diag(cs))[i][j] K^T[dk][j]  ->  Y^T in kblk: row dk, k = i
+            f32x4 y[DK / 16];
+            zero_acc(y);
+            mma_rows<T, DK / 16, 64>(y, sTop + i0 * LDT, LDT, sKT, LDT);
+            T *out = static_cast<T *>(pass == 1 ? a.nYT : a.ZT) + blk * (DK * 64);
 #pragma unroll
-            for (int mt = 0; mt < DK / 64; ++mt) {
-                const int m0 = (w * (DK / 64) + mt) * 16;
-                f32x4 y[4];
-                zero_acc(y);
-                mma_rows<T, 4, 64>(y, sKT + m0 * LDT, LDT, sTop, LDT);
-                T *out = static_cast<T *>(pass == 1 ? a.nYT : a.ZT) + blk * (DK * 64) + m0 * 64;
-                store_rows<T, 4>(y, out, 64, pass == 1 ? -1.f : 1.f);
-            }
+            for (int nt = 0; nt < DK / 16; ++nt) store4(out + kblk<T>(DK, nt * 16 + r, i0 + kq * 4), sgn * y[nt]);
         }
         __syncthreads();
     }

@@ -13,23 +13,24 @@ struct Dims {
     float scale;
 };
 
-// Chunk-parallel precompute ("intra") kernel arguments.  Workspace tensors are chunk-blocked:
-// [BH][N][rows][cols] in the storage dtype unless noted.
+// Chunk-parallel precompute ("intra") kernel arguments.  Workspace tensors are chunk-blocked,
+// [BH][N][tile], in the storage dtype unless noted; inside a tile, an MFMA operand [rows][k] is in
+// the kblk layout and a [rows][dv] tensor in the vblk layout of mdn_device.h.
 struct IntraArgs {
     const void *q, *k, *v;                  // [B,T,H,D]
     const float *alpha, *beta, *mu, *eta;   // [B,T,H]; eta may be null
     float *coef;                            // [BH][N][6][64] fp32
-    void *KT;                               // [dk][64]   raw k, transposed
+    void *KT;                               // kblk [dk][64]   raw k, transposed
     // forward mode
-    void *U;                                // [64][dv]   T V
-    void *nY;                               // [64][dk]  -T diag(a^-) P
-    void *Z;                                // [64][dk]   T diag(b^-) P
-    void *Bm;                               // [64][64]   (Q~ K~^T) .* Gamma
+    void *U;                                // vblk [64][dv]   T V
+    void *nY;                               // kblk [64][dk]  -T diag(a^-) P
+    void *Z;                                // kblk [64][dk]   T diag(b^-) P
+    void *Bm;                               // kblk [64][64]   (Q~ K~^T) .* Gamma
     // backward mode
-    void *QT;                               // [dk][64]   raw q, transposed
-    void *nYT, *ZT;                         // [dk][64]   transposes of -Y, Z
-    void *BmT;                              // [64][64]   Bm transposed
-    void *TmT;                              // [64][64]   T transposed
+    void *QT;                               // kblk [dk][64]   raw q, transposed
+    void *nYT, *ZT;                         // kblk [dk][64]   transposes of -Y, Z
+    void *BmT;                              // kblk [64][64]   Bm transposed
+    void *TmT;                              // kblk [64][64]   T transposed
 };
 
 struct ScanFwdArgs {
@@ -39,7 +40,7 @@ struct ScanFwdArgs {
     const float *S0, *M0;                   // [B,H,dk,dv] or null
     void *o;                                // [B,T,H,dv]
     void *vt_saved;                         // [B,T,H,dv] or null
-    void *states_saved;                     // [BH][N][2][dk][dv] or null
+    void *states_saved;                     // [BH][N][2] x vblk [dk][dv], or null
     float *S_final, *M_final;               // or null
 };
 
@@ -49,27 +50,27 @@ struct RebuildArgs {
     const void *KT;
     const void *vt_saved;                   // [B,T,H,dv]
     const float *S0, *M0;
-    void *states;                           // [BH][N][2][dk][dv]
+    void *states;                           // [BH][N][2] x vblk [dk][dv]
 };
 
 struct ScanBwdArgs {
     const void *k;                          // [B,T,H,dk]
     const void *dO;                         // [B,T,H,dv]
     const float *coef;
-    const void *QT, *nYT, *ZT, *BmT;
+    const void *QT, *nYT, *ZT, *BmT, *TmT;
     const float *dS_final, *dM_final;       // or null
-    void *dVtT;                             // [BH][N][dv][64]  adjoint of V~, transposed per chunk
-    void *dstates;                          // [BH][N][2][dk][dv] adjoints of the chunk-END states
+    void *dv;                               // [B,T,H,dv]  dV = T^T dV~
+    void *dstates;                          // [BH][N][2] x vblk [dk][dv]: adjoints of the chunk-END states
     float *dS0, *dM0;                       // or null
 };
 
 struct GradArgs {
     const void *q, *k;                      // [B,T,H,dk]
     const float *alpha, *beta, *mu, *eta;
-    const void *vt_saved, *dO;              // [B,T,H,dv]
-    const void *KT, *QT, *TmT, *dVtT;
-    const void *states, *dstates;           // [BH][N][2][dk][dv]
-    void *dq, *dk, *dv;
+    const void *vt_saved, *dO, *dv;         // [B,T,H,dv]; dv (= dR, from the reverse scan) is read
+    const void *KT, *QT;
+    const void *states, *dstates;           // [BH][N][2] x vblk [dk][dv]
+    void *dq, *dk;
     float *dalpha, *dbeta, *dmu, *deta;     // deta may be null
 };
 

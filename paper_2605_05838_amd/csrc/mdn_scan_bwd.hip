@@ -5,12 +5,15 @@
 //     dV~ = Bm^T dO + (Gamma_C eta . K) dS' - (Rho_C eta . K) dM'
 //     dS  = a_C dS' + (a . Q~)^T dO - Y^T dV~
 //     dM  = m_C dM' - b_C dS' - (b . Q~)^T dO + Z^T dV~
-// Same decomposition as the forward scan: one workgroup per (batch*head, DVB dv-columns), states in
-// fp32 accumulators (wave w owns dk rows [w*dk/4, (w+1)*dk/4)), a storage-type copy transposed in
-// LDS as B operand, the per-token scalings along the contraction index folded into the LDS copies
-// of dO, so that the A operands are the raw Q^T, -Y^T, Z^T, Bm^T and K.
-// It writes dV~ (transposed per chunk) and the chunk-end adjoint states for the chunk-parallel
-// gradient kernel.
+// Same decomposition as the forward scan: one workgroup per (batch*head, DVB dv-columns); every
+// product is formed transposed (dv = MFMA row index) so that an accumulator lane holds 4 consecutive
+// dv of one token or one dk row; dS'^T, dM'^T in fp32 accumulators (wave w owns dk columns
+// [w*dk/4, (w+1)*dk/4)), a storage-type copy [dv][dk | dk] in LDS as A operand; the per-token
+// scalings along the contraction index folded into the LDS copies of dO^T, so that the B operands
+// are raw rows of Q^T, -Y^T, Z^T, Bm^T and K; all of a chunk's fragments, its dO tile and
+// coefficients are fetched into registers one chunk ahead.
+// It also forms dV = T^T dV~ from the LDS copy of dV~ (not on the chain) and writes the chunk-end
+// adjoint states for the chunk-parallel gradient kernel.
 #include "mdn_device.h"
 #include "mdn_kernels.h"
 
@@ -18,10 +21,62 @@ namespace mdn {
 
 namespace {
 
+template <typename T, int DK, int MV> struct RevOps {
+    typedef Op<T> O;
+    static constexpr int KS = DK / O::KSTEP, KS2 = 64 / O::KSTEP, ND = DK / 64;
+    typename O::Frag k[KS];            // stage 1: K row (token i0 + r)
+    typename O::Frag bmT[KS2];         // stage 1: Bm^T row i0 + r
+    typename O::Frag tT[KS2];          // stage 2: T^T row i0 + r
+    typename O::Frag qT[ND][KS2], yT[ND][KS2], zT[ND][KS2]; // stage 2: rows (dk) of this wave's state columns
+    f32x4 dO[MV];                      // dO[token i0 + r][4 consecutive dv]
+    float sa, sb, gc, rc;
+    float aC, bC, mC;
+};
+
+template <typename T, int DK, int DV, int DVB>
+__device__ __forceinline__ void fetch_chunk(RevOps<T, DK, DVB / 16> &c, const Dims &d, const ScanBwdArgs &a, int bh,
+                                            int b, int h, int n, int dv0) {
+    typedef Op<T> O;
+    typedef RevOps<T, DK, DVB / 16> CO;
+    const int lane = lane_id(), w = wave_id(), r = lane & 15, kg = lane >> 4, i = w * 16 + r;
+    const size_t blk = (size_t)bh * d.N + n;
+    const size_t tok = ((size_t)b * d.T + (size_t)n * 64 + i) * d.H + h;
+    const float *coef = a.coef + blk * (kCoefRows * 64);
+    c.sa = d.scale * coef[COEF_A * 64 + i];
+    c.sb = d.scale * coef[COEF_B * 64 + i];
+    c.gc = coef[COEF_GC * 64 + i];
+    c.rc = coef[COEF_RC * 64 + i];
+    c.aC = coef[COEF_SCALAR * 64 + 0];
+    c.bC = coef[COEF_SCALAR * 64 + 1];
+    c.mC = coef[COEF_SCALAR * 64 + 2];
+    const T *kp = static_cast<const T *>(a.k) + tok * DK + kg * O::EPL;
+#pragma unroll
+    for (int s = 0; s < CO::KS; ++s) c.k[s] = O::load(kp + s * O::KSTEP);
+    const T *bp = static_cast<const T *>(a.BmT) + blk * 4096, *tp = static_cast<const T *>(a.TmT) + blk * 4096;
+#pragma unroll
+    for (int s = 0; s < CO::KS2; ++s) {
+        c.bmT[s] = O::load(bp + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL));
+        c.tT[s] = O::load(tp + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL));
+    }
+#pragma unroll
+    for (int nd = 0; nd < CO::ND; ++nd)
+#pragma unroll
+        for (int s = 0; s < CO::KS2; ++s) {
+            const size_t off = blk * (DK * 64) + kblk<T>(DK, (w * CO::ND + nd) * 16 + r, s * O::KSTEP + kg * O::EPL);
+            c.qT[nd][s] = O::load(static_cast<const T *>(a.QT) + off);
+            c.yT[nd][s] = O::load(static_cast<const T *>(a.nYT) + off);
+            c.zT[nd][s] = O::load(static_cast<const T *>(a.ZT) + off);
+        }
+    const T *og = static_cast<const T *>(a.dO) + tok * DV + dv0 + kg * 4;
+#pragma unroll
+    for (int mv = 0; mv < DVB / 16; ++mv) c.dO[mv] = load4(og + mv * 16);
+}
+
 template <typename T, int DK, int DV, int DVB>
 __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs a) {
     typedef Op<T> O;
-    constexpr int NT = DVB / 16, MT = DK / 64, G = DV / DVB;
+    typedef RevOps<T, DK, DVB / 16> CO;
+    constexpr int MV = DVB / 16, ND = DK / 64, G = DV / DVB;
     constexpr int LDST = 2 * DK + O::PAD, LDV = 64 + O::PAD;
     __shared__ __align__(16) T sD[DVB * LDST];  // [dv][dS'(dk) | dM'(dk)]
     __shared__ __align__(16) T sO0[DVB * LDV];  // dO^T
@@ -33,155 +88,160 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
     xcd_map(blockIdx.x, G, bh, blkv);
     if (bh >= d.BH) return;
     const int b = bh / d.H, h = bh % d.H, dv0 = blkv * DVB;
-    const int lane = lane_id(), w = wave_id(), r = lane & 15, kg = lane >> 4, i0 = w * 16;
+    const int lane = lane_id(), w = wave_id(), r = lane & 15, kg = lane >> 4, i = w * 16 + r;
 
-    f32x4 accS[MT][NT], accM[MT][NT];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                const int row = (w * MT + mt) * 16 + kg * 4 + x, col = dv0 + nt * 16 + r;
-                const size_t g = ((size_t)bh * DK + row) * DV + col;
-                accS[mt][nt][x] = a.dS_final ? a.dS_final[g] : 0.f;
-                accM[mt][nt][x] = a.dM_final ? a.dM_final[g] : 0.f;
-            }
+    CO cur;
+    fetch_chunk<T, DK, DV, DVB>(cur, d, a, bh, b, h, d.N - 1, dv0);
 
-    const size_t rsk = (size_t)d.H * DK, rsv = (size_t)d.H * DV;
+    // element x of tile (mv, nd): dS[dk = (w*ND + nd)*16 + r][dv = mv*16 + kg*4 + x]
+    f32x4 accS[MV][ND], accM[MV][ND];
+#pragma unroll
+    for (int mv = 0; mv < MV; ++mv)
+#pragma unroll
+        for (int nd = 0; nd < ND; ++nd) {
+            const size_t g = ((size_t)bh * DK + (w * ND + nd) * 16 + r) * DV + dv0 + mv * 16 + kg * 4;
+            accS[mv][nd] = a.dS_final ? *reinterpret_cast<const f32x4 *>(a.dS_final + g) : f32x4{0.f, 0.f, 0.f, 0.f};
+            accM[mv][nd] = a.dM_final ? *reinterpret_cast<const f32x4 *>(a.dM_final + g) : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+
     for (int n = d.N - 1; n >= 0; --n) {
         const size_t blk = (size_t)bh * d.N + n;
-        const size_t tok0 = ((size_t)b * d.T + (size_t)n * 64) * d.H + h;
-        const float *coef = a.coef + blk * (kCoefRows * 64);
+        CO nxt;
+        fetch_chunk<T, DK, DV, DVB>(nxt, d, a, bh, b, h, n > 0 ? n - 1 : 0, dv0);
 
         // adjoints of this chunk's END states: operand copy to LDS, storage copy to HBM
         {
             T *ds = static_cast<T *>(a.dstates) + blk * (2 * DK * DV);
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
+            for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt)
+                for (int nd = 0; nd < ND; ++nd) {
+                    const int dk = (w * ND + nd) * 16 + r;
+                    const size_t off = vblk(DK, dk, dv0 + mv * 16 + kg * 4);
+                    store4(ds + off, accS[mv][nd]);
+                    store4(ds + DK * DV + off, accM[mv][nd]);
 #pragma unroll
                     for (int x = 0; x < 4; ++x) {
-                        const int row = (w * MT + mt) * 16 + kg * 4 + x, col = nt * 16 + r;
-                        const T s = from_f32<T>(accS[mt][nt][x]), m = from_f32<T>(accM[mt][nt][x]);
-                        sD[col * LDST + row] = s;
-                        sD[col * LDST + DK + row] = m;
-                        ds[row * DV + dv0 + col] = s;
-                        ds[DK * DV + row * DV + dv0 + col] = m;
+                        const int dv = mv * 16 + kg * 4 + x;
+                        sD[dv * LDST + dk] = from_f32<T>(accS[mv][nd][x]);
+                        sD[dv * LDST + DK + dk] = from_f32<T>(accM[mv][nd][x]);
                     }
+                }
         }
-        // dO slice of this chunk, transposed, in three scalings
-        {
-            const T *og = static_cast<const T *>(a.dO) + tok0 * DV + dv0;
+        // dO^T slice of this chunk in three scalings
+#pragma unroll
+        for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
             for (int x = 0; x < 4; ++x) {
-                const int i = i0 + kg * 4 + x;
-                const float sa = d.scale * coef[COEF_A * 64 + i], sb = d.scale * coef[COEF_B * 64 + i];
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    const int col = nt * 16 + r;
-                    const T raw = og[(size_t)i * rsv + col];
-                    const float v = to_f32(raw);
-                    sO0[col * LDV + i] = raw;
-                    sOa[col * LDV + i] = from_f32<T>(sa * v);
-                    sOb[col * LDV + i] = from_f32<T>(-sb * v);
-                }
+                const int dv = mv * 16 + kg * 4 + x;
+                const float v = cur.dO[mv][x];
+                sO0[dv * LDV + i] = from_f32<T>(v);
+                sOa[dv * LDV + i] = from_f32<T>(cur.sa * v);
+                sOb[dv * LDV + i] = from_f32<T>(-cur.sb * v);
             }
-        }
         __syncthreads();
 
-        // ---------------- stage 1: dV~ for tokens j = i0..i0+15
+        // ---------------- stage 1: dV~^T for token j = i
         {
-            f32x4 accD[NT], x1[NT], x2[NT];
+            f32x4 accD[MV], x1[MV], x2[MV];
             zero_acc(accD);
             zero_acc(x1);
             zero_acc(x2);
-            mma_rows<T, NT, 64>(accD, static_cast<const T *>(a.BmT) + blk * 4096 + i0 * 64, 64, sO0, LDV);
-            const T *kp = static_cast<const T *>(a.k) + (tok0 + (size_t)(i0 + r) * d.H) * DK + kg * O::EPL;
+            const T *op = sO0 + r * LDV + kg * O::EPL;
+#pragma unroll
+            for (int s = 0; s < CO::KS2; ++s)
+#pragma unroll
+                for (int mv = 0; mv < MV; ++mv)
+                    accD[mv] = O::mma(O::load(op + mv * 16 * LDV + s * O::KSTEP), cur.bmT[s], accD[mv]);
             const T *sp = sD + r * LDST + kg * O::EPL;
 #pragma unroll
-            for (int k0 = 0; k0 < DK; k0 += O::KSTEP) {
-                const typename O::Frag fk = O::load(kp + k0);
+            for (int s = 0; s < CO::KS; ++s)
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    x1[nt] = O::mma(fk, O::load(sp + nt * 16 * LDST + k0), x1[nt]);
-                    x2[nt] = O::mma(fk, O::load(sp + nt * 16 * LDST + DK + k0), x2[nt]);
+                for (int mv = 0; mv < MV; ++mv) {
+                    x1[mv] = O::mma(O::load(sp + mv * 16 * LDST + s * O::KSTEP), cur.k[s], x1[mv]);
+                    x2[mv] = O::mma(O::load(sp + mv * 16 * LDST + DK + s * O::KSTEP), cur.k[s], x2[mv]);
                 }
-            }
-            T *dvt = static_cast<T *>(a.dVtT) + blk * (DV * 64) + (size_t)dv0 * 64;
 #pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                const int j = i0 + kg * 4 + x;
-                const float gc = coef[COEF_GC * 64 + j], rc = coef[COEF_RC * 64 + j];
+            for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    const int col = nt * 16 + r;
-                    const T v = from_f32<T>(accD[nt][x] + gc * x1[nt][x] - rc * x2[nt][x]);
-                    sDV[col * LDV + j] = v;
-                    dvt[col * 64 + j] = v;
+                for (int x = 0; x < 4; ++x) {
+                    const int dv = mv * 16 + kg * 4 + x;
+                    sDV[dv * LDV + i] = from_f32<T>(accD[mv][x] + cur.gc * x1[mv][x] - cur.rc * x2[mv][x]);
                 }
-            }
         }
         __syncthreads();
 
-        // ---------------- stage 2: adjoints of the chunk-START states
+        // ---------------- stage 2: dV = T^T dV~ (off the chain) and the adjoints of the chunk-START states
         {
-            const float aC = coef[COEF_SCALAR * 64 + 0], bC = coef[COEF_SCALAR * 64 + 1],
-                        mC = coef[COEF_SCALAR * 64 + 2];
-            const T *QTg = static_cast<const T *>(a.QT) + blk * (DK * 64);
-            const T *YTg = static_cast<const T *>(a.nYT) + blk * (DK * 64);
-            const T *ZTg = static_cast<const T *>(a.ZT) + blk * (DK * 64);
+            f32x4 dR[MV];
+            zero_acc(dR);
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
+            for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt)
+                for (int nd = 0; nd < ND; ++nd) {
+                    const f32x4 s = accS[mv][nd], m = accM[mv][nd];
+                    accS[mv][nd] = cur.aC * s;
+                    accM[mv][nd] = cur.mC * m - cur.bC * s;
+                }
+            const T *oap = sOa + r * LDV + kg * O::EPL, *obp = sOb + r * LDV + kg * O::EPL,
+                    *dvp = sDV + r * LDV + kg * O::EPL;
 #pragma unroll
-                    for (int x = 0; x < 4; ++x) {
-                        const float s = accS[mt][nt][x], m = accM[mt][nt][x];
-                        accS[mt][nt][x] = aC * s;
-                        accM[mt][nt][x] = mC * m - bC * s;
+            for (int s = 0; s < CO::KS2; ++s)
+#pragma unroll
+                for (int mv = 0; mv < MV; ++mv) {
+                    const typename O::Frag fa = O::load(oap + mv * 16 * LDV + s * O::KSTEP);
+                    const typename O::Frag fb = O::load(obp + mv * 16 * LDV + s * O::KSTEP);
+                    const typename O::Frag fd = O::load(dvp + mv * 16 * LDV + s * O::KSTEP);
+                    dR[mv] = O::mma(fd, cur.tT[s], dR[mv]);
+#pragma unroll
+                    for (int nd = 0; nd < ND; ++nd) {
+                        accS[mv][nd] = O::mma(fa, cur.qT[nd][s], accS[mv][nd]);
+                        accS[mv][nd] = O::mma(fd, cur.yT[nd][s], accS[mv][nd]);
+                        accM[mv][nd] = O::mma(fb, cur.qT[nd][s], accM[mv][nd]);
+                        accM[mv][nd] = O::mma(fd, cur.zT[nd][s], accM[mv][nd]);
                     }
-                const int m0 = (w * MT + mt) * 16 * 64;
-                mma_rows<T, NT, 64>(accS[mt], QTg + m0, 64, sOa, LDV);
-                mma_rows<T, NT, 64>(accS[mt], YTg + m0, 64, sDV, LDV);
-                mma_rows<T, NT, 64>(accM[mt], QTg + m0, 64, sOb, LDV);
-                mma_rows<T, NT, 64>(accM[mt], ZTg + m0, 64, sDV, LDV);
-            }
+                }
+            const size_t tok = ((size_t)b * d.T + (size_t)n * 64 + i) * d.H + h;
+            T *dvg = static_cast<T *>(a.dv) + tok * DV + dv0 + kg * 4;
+#pragma unroll
+            for (int mv = 0; mv < MV; ++mv) store4(dvg + mv * 16, dR[mv]);
         }
         __syncthreads();
+        cur = nxt;
     }
 
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+    for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                const int row = (w * MT + mt) * 16 + kg * 4 + x, col = dv0 + nt * 16 + r;
-                const size_t g = ((size_t)bh * DK + row) * DV + col;
-                if (a.dS0) a.dS0[g] = accS[mt][nt][x];
-                if (a.dM0) a.dM0[g] = accM[mt][nt][x];
-            }
+        for (int nd = 0; nd < ND; ++nd) {
+            const size_t g = ((size_t)bh * DK + (w * ND + nd) * 16 + r) * DV + dv0 + mv * 16 + kg * 4;
+            if (a.dS0) *reinterpret_cast<f32x4 *>(a.dS0 + g) = accS[mv][nd];
+            if (a.dM0) *reinterpret_cast<f32x4 *>(a.dM0 + g) = accM[mv][nd];
+        }
 }
 
-constexpr int kDVB = 32;
-
-template <typename T, int DK, int DV>
+template <typename T, int DK, int DV, int DVB>
 hipError_t launch_t(const Dims &d, const ScanBwdArgs &a, hipStream_t s) {
-    constexpr int G = DV / kDVB;
+    constexpr int G = DV / DVB;
     dim3 grid(((d.BH + 7) / 8) * 8 * G), block(kThreads);
-    hipLaunchKernelGGL((scan_bwd_kernel<T, DK, DV, kDVB>), grid, block, 0, s, d, a);
+    hipLaunchKernelGGL((scan_bwd_kernel<T, DK, DV, DVB>), grid, block, 0, s, d, a);
     return hipGetLastError();
+}
+
+// 32 dv columns per workgroup unless that leaves most of the 256 CUs without a workgroup
+// (fp32 storage at d = 128 always takes 16: the prefetched fragments of 32 columns do not fit the registers)
+template <typename T, int DK, int DV> hipError_t pick_dvb(const Dims &d, const ScanBwdArgs &a, hipStream_t s) {
+    if (d.BH * (DV / 32) < 192 || (sizeof(T) == 4 && DK == 128)) return launch_t<T, DK, DV, 16>(d, a, s);
+    return launch_t<T, DK, DV, 32>(d, a, s);
 }
 
 } // namespace
 
 hipError_t launch_scan_bwd(const Dims &d, const ScanBwdArgs &a, hipStream_t s) {
     const bool f32 = d.dtype == 1;
-    if (d.dk == 64 && d.dv == 64) return f32 ? launch_t<float, 64, 64>(d, a, s) : launch_t<bf16_t, 64, 64>(d, a, s);
+    if (d.dk == 64 && d.dv == 64) return f32 ? pick_dvb<float, 64, 64>(d, a, s) : pick_dvb<bf16_t, 64, 64>(d, a, s);
     if (d.dk == 128 && d.dv == 128)
-        return f32 ? launch_t<float, 128, 128>(d, a, s) : launch_t<bf16_t, 128, 128>(d, a, s);
+        return f32 ? pick_dvb<float, 128, 128>(d, a, s) : pick_dvb<bf16_t, 128, 128>(d, a, s);
     return hipErrorInvalidValue;
 }
 

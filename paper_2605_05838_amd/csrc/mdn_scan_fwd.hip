@@ -8,13 +8,18 @@
 // (batch, head) and walks the chunks in order: grid = batch*head x dv/DVB, all workgroups of one
 // (batch, head) on the same XCD so that the chunk operands they share are served by one L2.
 //
-// Inside a workgroup (4 waves): S, M live in fp32 MFMA accumulators (wave w owns dk rows
-// [w*dk/4, (w+1)*dk/4)); a storage-type copy sits in LDS, transposed ([dv][dk | dk]), as the B
-// operand of the dk-contractions.  Stage 1 (wave w owns tokens 16w..16w+15) forms V~ and the two
-// inter-chunk read-outs; V~ goes to LDS transposed ([dv][token]) in three scalings (raw, Gamma_C eta,
-// -Rho_C eta) and is the B operand of the token-contractions of stage 2.  The row scalings along
-// the contraction index are folded into those copies, so the A operands are the raw K^T, Q.
-// Two barriers per chunk.
+// Inside a workgroup (4 waves) every product is formed TRANSPOSED, with the dv index as the MFMA
+// row index: an accumulator lane then holds 4 consecutive dv of one token (or of one dk row), which
+// is 8 contiguous bytes of V~, O, U and of the saved states in HBM.
+//   S^T, M^T live in fp32 accumulators (wave w owns dk columns [w*dk/4, (w+1)*dk/4)); a storage-type
+//   copy sits in LDS as [dv][dk | dk] and is the A operand of the dk-contractions of stage 1
+//   (wave w owns tokens 16w..16w+15): V~^T and the two inter-chunk read-outs.  V~^T goes to LDS as
+//   [dv][token] in three scalings (raw, Gamma_C eta, -Rho_C eta): the A operand of the token-contractions
+//   of stage 2 (intra-chunk output, state update).  Scalings along a contraction index are folded
+//   into those copies, so the B operands are raw rows of -Y, Z, Q, Bm, K^T straight from HBM.
+// Two barriers per chunk.  Nothing a chunk reads from HBM depends on the state, so all of a chunk's
+// fragments, its U tile and its coefficients are fetched into registers one whole chunk ahead; the
+// serial chain then only waits on LDS and MFMA latency.
 #include "mdn_device.h"
 #include "mdn_kernels.h"
 
@@ -22,25 +27,80 @@ namespace mdn {
 
 namespace {
 
-template <typename T, int DK, int DVB> struct ScanSmem {
-    static constexpr int LDS_ST = 2 * DK + Op<T>::PAD; // state copy: [DVB][S(dk) | M(dk)]
-    static constexpr int LDV = 64 + Op<T>::PAD;        // V~ copies: [DVB][64 tokens]
+// Operands of one chunk held by one lane.
+template <typename T, int DK, int MV> struct ChunkOps {
+    typedef Op<T> O;
+    static constexpr int KS = DK / O::KSTEP, KS2 = 64 / O::KSTEP, ND = DK / 64;
+    typename O::Frag y[KS], z[KS], q[KS]; // stage 1: rows (token i0 + r) of -Y, Z, Q
+    typename O::Frag bm[KS2];             // stage 2: Bm row i0 + r
+    typename O::Frag kt[ND][KS2];         // stage 2: K^T rows (dk) of this wave's state columns
+    f32x4 u[MV];                          // U[token i0 + r][4 consecutive dv] (V~ in reconstruction)
+    float sa, sb, gc, rc;                 // scale a_i, scale b_i, Gamma_C eta, Rho_C eta for token i0 + r
+    float aC, bC, mC;
 };
 
-// write the accumulator tiles of this wave's state rows into the LDS operand copy
-template <typename T, int DK, int NT>
-__device__ __forceinline__ void publish_state(T *sSt, int ldst, const f32x4 (&accS)[DK / 64][NT],
-                                              const f32x4 (&accM)[DK / 64][NT]) {
+template <typename T, int DK, int DV, int DVB, bool REBUILD>
+__device__ __forceinline__ void fetch_chunk(ChunkOps<T, DK, DVB / 16> &c, const Dims &d, const ScanFwdArgs &a,
+                                            int bh, int b, int h, int n, int dv0) {
+    typedef Op<T> O;
+    typedef ChunkOps<T, DK, DVB / 16> CO;
+    const int lane = lane_id(), w = wave_id(), r = lane & 15, kg = lane >> 4, i = w * 16 + r;
+    const size_t blk = (size_t)bh * d.N + n;
+    const size_t tok = ((size_t)b * d.T + (size_t)n * 64 + i) * d.H + h;
+    const float *coef = a.coef + blk * (kCoefRows * 64);
+    c.gc = coef[COEF_GC * 64 + i];
+    c.rc = coef[COEF_RC * 64 + i];
+    if (!REBUILD) {
+        c.sa = d.scale * coef[COEF_A * 64 + i];
+        c.sb = d.scale * coef[COEF_B * 64 + i];
+    }
+    c.aC = coef[COEF_SCALAR * 64 + 0];
+    c.bC = coef[COEF_SCALAR * 64 + 1];
+    c.mC = coef[COEF_SCALAR * 64 + 2];
+    const T *KTg = static_cast<const T *>(a.KT) + blk * (DK * 64);
+#pragma unroll
+    for (int nd = 0; nd < CO::ND; ++nd)
+#pragma unroll
+        for (int s = 0; s < CO::KS2; ++s)
+            c.kt[nd][s] = O::load(KTg + kblk<T>(DK, (w * CO::ND + nd) * 16 + r, s * O::KSTEP + kg * O::EPL));
+    if (!REBUILD) {
+        const T *Yg = static_cast<const T *>(a.nY) + blk * (64 * DK);
+        const T *Zg = static_cast<const T *>(a.Z) + blk * (64 * DK);
+        const T *Qg = static_cast<const T *>(a.q) + tok * DK + kg * O::EPL;
+#pragma unroll
+        for (int s = 0; s < CO::KS; ++s) {
+            c.y[s] = O::load(Yg + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL));
+            c.z[s] = O::load(Zg + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL));
+            c.q[s] = O::load(Qg + s * O::KSTEP);
+        }
+        const T *Bg = static_cast<const T *>(a.Bm) + blk * 4096;
+#pragma unroll
+        for (int s = 0; s < CO::KS2; ++s) c.bm[s] = O::load(Bg + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL));
+        const T *Ug = static_cast<const T *>(a.U) + blk * (64 * DV);
+#pragma unroll
+        for (int mv = 0; mv < DVB / 16; ++mv) c.u[mv] = load4(Ug + vblk(64, i, dv0 + mv * 16 + kg * 4));
+    } else {
+        // reconstruction reads the saved V~ where the forward reads U
+        const T *vs = static_cast<const T *>(a.vt_saved) + tok * DV + dv0 + kg * 4;
+#pragma unroll
+        for (int mv = 0; mv < DVB / 16; ++mv) c.u[mv] = load4(vs + mv * 16);
+    }
+}
+
+// accumulator element x of tile (mv, nd) of wave w is S[dk = (w*ND + nd)*16 + r][dv = mv*16 + kg*4 + x]
+template <typename T, int DK, int MV>
+__device__ __forceinline__ void publish_state(T *sSt, int ldst, const f32x4 (&accS)[MV][DK / 64],
+                                              const f32x4 (&accM)[MV][DK / 64]) {
     const int r = lane_id() & 15, kg = lane_id() >> 4, w = wave_id();
 #pragma unroll
-    for (int mt = 0; mt < DK / 64; ++mt)
+    for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
+        for (int nd = 0; nd < DK / 64; ++nd)
 #pragma unroll
             for (int x = 0; x < 4; ++x) {
-                const int row = (w * (DK / 64) + mt) * 16 + kg * 4 + x, col = nt * 16 + r;
-                sSt[col * ldst + row] = from_f32<T>(accS[mt][nt][x]);
-                sSt[col * ldst + DK + row] = from_f32<T>(accM[mt][nt][x]);
+                const int dv = mv * 16 + kg * 4 + x, dk = (w * (DK / 64) + nd) * 16 + r;
+                sSt[dv * ldst + dk] = from_f32<T>(accS[mv][nd][x]);
+                sSt[dv * ldst + DK + dk] = from_f32<T>(accM[mv][nd][x]);
             }
 }
 
@@ -49,191 +109,174 @@ __device__ __forceinline__ void publish_state(T *sSt, int ldst, const f32x4 (&ac
 template <typename T, int DK, int DV, int DVB, bool REBUILD>
 __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs a) {
     typedef Op<T> O;
-    typedef ScanSmem<T, DK, DVB> SM;
-    constexpr int NT = DVB / 16, MT = DK / 64, G = DV / DVB;
-    __shared__ __align__(16) T sSt[DVB * SM::LDS_ST];
-    __shared__ __align__(16) T sV0[DVB * SM::LDV];
-    __shared__ __align__(16) T sVg[DVB * SM::LDV];
-    __shared__ __align__(16) T sVr[DVB * SM::LDV];
+    typedef ChunkOps<T, DK, DVB / 16> CO;
+    constexpr int MV = DVB / 16, ND = DK / 64, G = DV / DVB;
+    constexpr int LDST = 2 * DK + O::PAD; // state copy: [DVB][S(dk) | M(dk)]
+    constexpr int LDV = 64 + O::PAD;      // V~ copies: [DVB][64 tokens]
+    __shared__ __align__(16) T sSt[DVB * LDST];
+    __shared__ __align__(16) T sV0[DVB * LDV];
+    __shared__ __align__(16) T sVg[DVB * LDV];
+    __shared__ __align__(16) T sVr[DVB * LDV];
 
     int bh, blkv;
     xcd_map(blockIdx.x, G, bh, blkv);
     if (bh >= d.BH) return;
     const int b = bh / d.H, h = bh % d.H, dv0 = blkv * DVB;
-    const int lane = lane_id(), w = wave_id(), r = lane & 15, kg = lane >> 4, i0 = w * 16;
+    const int lane = lane_id(), w = wave_id(), r = lane & 15, kg = lane >> 4, i = w * 16 + r;
 
-    f32x4 accS[MT][NT], accM[MT][NT];
+    CO cur;
+    fetch_chunk<T, DK, DV, DVB, REBUILD>(cur, d, a, bh, b, h, 0, dv0);
+
+    f32x4 accS[MV][ND], accM[MV][ND];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+    for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                const int row = (w * MT + mt) * 16 + kg * 4 + x, col = dv0 + nt * 16 + r;
-                const size_t g = ((size_t)bh * DK + row) * DV + col;
-                accS[mt][nt][x] = a.S0 ? a.S0[g] : 0.f;
-                accM[mt][nt][x] = a.M0 ? a.M0[g] : 0.f;
-            }
-    if (!REBUILD) publish_state<T, DK, NT>(sSt, SM::LDS_ST, accS, accM);
+        for (int nd = 0; nd < ND; ++nd) {
+            const size_t g = ((size_t)bh * DK + (w * ND + nd) * 16 + r) * DV + dv0 + mv * 16 + kg * 4;
+            accS[mv][nd] = a.S0 ? *reinterpret_cast<const f32x4 *>(a.S0 + g) : f32x4{0.f, 0.f, 0.f, 0.f};
+            accM[mv][nd] = a.M0 ? *reinterpret_cast<const f32x4 *>(a.M0 + g) : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+    if (!REBUILD) publish_state<T, DK, MV>(sSt, LDST, accS, accM);
     __syncthreads();
 
-    const size_t rsk = (size_t)d.H * DK, rsv = (size_t)d.H * DV;
     for (int n = 0; n < d.N; ++n) {
         const size_t blk = (size_t)bh * d.N + n;
-        const size_t tok0 = ((size_t)b * d.T + (size_t)n * 64) * d.H + h;
-        const float *coef = a.coef + blk * (kCoefRows * 64);
+        const size_t tok = ((size_t)b * d.T + (size_t)n * 64 + i) * d.H + h;
+
+        // next chunk's operands: in flight while this chunk computes
+        CO nxt;
+        fetch_chunk<T, DK, DV, DVB, REBUILD>(nxt, d, a, bh, b, h, (n + 1 < d.N) ? n + 1 : n, dv0);
 
         if (a.states_saved) {
             T *st = static_cast<T *>(a.states_saved) + blk * (2 * DK * DV);
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
+            for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                    for (int x = 0; x < 4; ++x) {
-                        const int row = (w * MT + mt) * 16 + kg * 4 + x, col = dv0 + nt * 16 + r;
-                        st[row * DV + col] = from_f32<T>(accS[mt][nt][x]);
-                        st[DK * DV + row * DV + col] = from_f32<T>(accM[mt][nt][x]);
-                    }
+                for (int nd = 0; nd < ND; ++nd) {
+                    const size_t off = vblk(DK, (w * ND + nd) * 16 + r, dv0 + mv * 16 + kg * 4);
+                    store4(st + off, accS[mv][nd]);
+                    store4(st + DK * DV + off, accM[mv][nd]);
+                }
         }
 
-        // ---------------- stage 1: V~ and the inter-chunk read-outs for tokens i0..i0+15
-        f32x4 accO[NT];
-        float vt[NT][4]; // V~ rounded to the storage type
+        // ---------------- stage 1: V~^T and the inter-chunk read-outs for token i
+        f32x4 accO[MV], vt[MV]; // vt = V~ rounded to the storage type
         if (!REBUILD) {
-            const T *Ug = static_cast<const T *>(a.U) + blk * (64 * DV) + dv0;
-            const T *Yg = static_cast<const T *>(a.nY) + blk * (64 * DK) + i0 * DK;
-            const T *Zg = static_cast<const T *>(a.Z) + blk * (64 * DK) + i0 * DK;
-            const T *Qg = static_cast<const T *>(a.q) + (tok0 + (size_t)i0 * d.H) * DK;
-            f32x4 accV[NT], accOS[NT], accOM[NT];
+            f32x4 accV[MV], accOS[MV], accOM[MV];
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                for (int x = 0; x < 4; ++x)
-                    accV[nt][x] = to_f32(Ug[(i0 + kg * 4 + x) * DV + nt * 16 + r]);
+            for (int mv = 0; mv < MV; ++mv) accV[mv] = cur.u[mv];
             zero_acc(accOS);
             zero_acc(accOM);
-            const T *yp = Yg + r * DK + kg * O::EPL, *zp = Zg + r * DK + kg * O::EPL;
-            const T *qp = Qg + (size_t)r * rsk + kg * O::EPL;
-            const T *sp = sSt + r * SM::LDS_ST + kg * O::EPL;
+            const T *sp = sSt + r * LDST + kg * O::EPL;
 #pragma unroll
-            for (int k0 = 0; k0 < DK; k0 += O::KSTEP) {
-                const typename O::Frag fy = O::load(yp + k0), fz = O::load(zp + k0), fq = O::load(qp + k0);
+            for (int s = 0; s < CO::KS; ++s) {
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    const typename O::Frag fs = O::load(sp + nt * 16 * SM::LDS_ST + k0);
-                    const typename O::Frag fm = O::load(sp + nt * 16 * SM::LDS_ST + DK + k0);
-                    accV[nt] = O::mma(fy, fs, accV[nt]);
-                    accV[nt] = O::mma(fz, fm, accV[nt]);
-                    accOS[nt] = O::mma(fq, fs, accOS[nt]);
-                    accOM[nt] = O::mma(fq, fm, accOM[nt]);
+                for (int mv = 0; mv < MV; ++mv) {
+                    const typename O::Frag fs = O::load(sp + mv * 16 * LDST + s * O::KSTEP);
+                    const typename O::Frag fm = O::load(sp + mv * 16 * LDST + DK + s * O::KSTEP);
+                    accV[mv] = O::mma(fs, cur.y[s], accV[mv]);
+                    accOS[mv] = O::mma(fs, cur.q[s], accOS[mv]);
+                    accV[mv] = O::mma(fm, cur.z[s], accV[mv]);
+                    accOM[mv] = O::mma(fm, cur.q[s], accOM[mv]);
                 }
             }
 #pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                const int i = i0 + kg * 4 + x;
-                const float sa = d.scale * coef[COEF_A * 64 + i], sb = d.scale * coef[COEF_B * 64 + i];
+            for (int mv = 0; mv < MV; ++mv) {
+                accO[mv] = cur.sa * accOS[mv] - cur.sb * accOM[mv];
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    accO[nt][x] = sa * accOS[nt][x] - sb * accOM[nt][x];
-                    vt[nt][x] = rounded<T>(accV[nt][x]);
-                }
+                for (int x = 0; x < 4; ++x) vt[mv][x] = rounded<T>(accV[mv][x]);
             }
             if (a.vt_saved) {
-                T *vs = static_cast<T *>(a.vt_saved) + tok0 * DV + dv0;
+                T *vs = static_cast<T *>(a.vt_saved) + tok * DV + dv0 + kg * 4;
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                    for (int x = 0; x < 4; ++x)
-                        vs[(size_t)(i0 + kg * 4 + x) * rsv + nt * 16 + r] = from_f32<T>(vt[nt][x]);
+                for (int mv = 0; mv < MV; ++mv) store4(vs + mv * 16, vt[mv]);
             }
         } else {
-            const T *vs = static_cast<const T *>(a.vt_saved) + tok0 * DV + dv0;
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                for (int x = 0; x < 4; ++x) vt[nt][x] = to_f32(vs[(size_t)(i0 + kg * 4 + x) * rsv + nt * 16 + r]);
+            for (int mv = 0; mv < MV; ++mv) vt[mv] = cur.u[mv];
         }
-        // V~ to LDS, transposed, in the three scalings of stage 2
+        // V~^T to LDS in the three scalings of stage 2
 #pragma unroll
-        for (int x = 0; x < 4; ++x) {
-            const int i = i0 + kg * 4 + x;
-            const float gc = coef[COEF_GC * 64 + i], rc = coef[COEF_RC * 64 + i];
+        for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                const int col = nt * 16 + r;
-                if (!REBUILD) sV0[col * SM::LDV + i] = from_f32<T>(vt[nt][x]);
-                sVg[col * SM::LDV + i] = from_f32<T>(gc * vt[nt][x]);
-                sVr[col * SM::LDV + i] = from_f32<T>(-rc * vt[nt][x]);
+            for (int x = 0; x < 4; ++x) {
+                const int dv = mv * 16 + kg * 4 + x;
+                if (!REBUILD) sV0[dv * LDV + i] = from_f32<T>(vt[mv][x]);
+                sVg[dv * LDV + i] = from_f32<T>(cur.gc * vt[mv][x]);
+                sVr[dv * LDV + i] = from_f32<T>(-cur.rc * vt[mv][x]);
             }
-        }
         __syncthreads();
 
         // ---------------- stage 2: intra-chunk output and the state update
-        if (!REBUILD) {
-            const T *Bg = static_cast<const T *>(a.Bm) + blk * 4096 + i0 * 64;
-            mma_rows<T, NT, 64>(accO, Bg, 64, sV0, SM::LDV);
-            T *og = static_cast<T *>(a.o) + tok0 * DV + dv0;
+        const T *v0p = sV0 + r * LDV + kg * O::EPL, *vgp = sVg + r * LDV + kg * O::EPL,
+                *vrp = sVr + r * LDV + kg * O::EPL;
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
+        for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
-                for (int x = 0; x < 4; ++x)
-                    og[(size_t)(i0 + kg * 4 + x) * rsv + nt * 16 + r] = from_f32<T>(accO[nt][x]);
-        }
-        {
-            const float aC = coef[COEF_SCALAR * 64 + 0], bC = coef[COEF_SCALAR * 64 + 1],
-                        mC = coef[COEF_SCALAR * 64 + 2];
-            const T *KTg = static_cast<const T *>(a.KT) + blk * (DK * 64);
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                    for (int x = 0; x < 4; ++x) {
-                        accS[mt][nt][x] = aC * accS[mt][nt][x] - bC * accM[mt][nt][x];
-                        accM[mt][nt][x] = mC * accM[mt][nt][x];
-                    }
-                const T *Ka = KTg + ((w * MT + mt) * 16) * 64;
-                mma_rows<T, NT, 64>(accS[mt], Ka, 64, sVg, SM::LDV);
-                mma_rows<T, NT, 64>(accM[mt], Ka, 64, sVr, SM::LDV);
+            for (int nd = 0; nd < ND; ++nd) {
+                accS[mv][nd] = cur.aC * accS[mv][nd] - cur.bC * accM[mv][nd];
+                accM[mv][nd] = cur.mC * accM[mv][nd];
             }
+#pragma unroll
+        for (int s = 0; s < CO::KS2; ++s)
+#pragma unroll
+            for (int mv = 0; mv < MV; ++mv) {
+                const typename O::Frag fg = O::load(vgp + mv * 16 * LDV + s * O::KSTEP);
+                const typename O::Frag fr = O::load(vrp + mv * 16 * LDV + s * O::KSTEP);
+#pragma unroll
+                for (int nd = 0; nd < ND; ++nd) {
+                    accS[mv][nd] = O::mma(fg, cur.kt[nd][s], accS[mv][nd]);
+                    accM[mv][nd] = O::mma(fr, cur.kt[nd][s], accM[mv][nd]);
+                }
+                if (!REBUILD) {
+                    const typename O::Frag f0 = O::load(v0p + mv * 16 * LDV + s * O::KSTEP);
+                    accO[mv] = O::mma(f0, cur.bm[s], accO[mv]);
+                }
+            }
+        if (!REBUILD) {
+            publish_state<T, DK, MV>(sSt, LDST, accS, accM);
+            T *og = static_cast<T *>(a.o) + tok * DV + dv0 + kg * 4;
+#pragma unroll
+            for (int mv = 0; mv < MV; ++mv) store4(og + mv * 16, accO[mv]);
         }
-        if (!REBUILD) publish_state<T, DK, NT>(sSt, SM::LDS_ST, accS, accM);
         __syncthreads();
+        cur = nxt;
     }
 
     if (!REBUILD) {
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+        for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                for (int x = 0; x < 4; ++x) {
-                    const int row = (w * MT + mt) * 16 + kg * 4 + x, col = dv0 + nt * 16 + r;
-                    const size_t g = ((size_t)bh * DK + row) * DV + col;
-                    if (a.S_final) a.S_final[g] = accS[mt][nt][x];
-                    if (a.M_final) a.M_final[g] = accM[mt][nt][x];
-                }
+            for (int nd = 0; nd < ND; ++nd) {
+                const size_t g = ((size_t)bh * DK + (w * ND + nd) * 16 + r) * DV + dv0 + mv * 16 + kg * 4;
+                if (a.S_final) *reinterpret_cast<f32x4 *>(a.S_final + g) = accS[mv][nd];
+                if (a.M_final) *reinterpret_cast<f32x4 *>(a.M_final + g) = accM[mv][nd];
+            }
     }
 }
 
-constexpr int kDVB = 32;
-
-template <typename T, int DK, int DV, bool REBUILD>
+template <typename T, int DK, int DV, int DVB, bool REBUILD>
 hipError_t launch_scan_t(const Dims &d, const ScanFwdArgs &a, hipStream_t s) {
-    constexpr int G = DV / kDVB;
+    constexpr int G = DV / DVB;
     dim3 grid(((d.BH + 7) / 8) * 8 * G), block(kThreads);
-    hipLaunchKernelGGL((scan_fwd_kernel<T, DK, DV, kDVB, REBUILD>), grid, block, 0, s, d, a);
+    hipLaunchKernelGGL((scan_fwd_kernel<T, DK, DV, DVB, REBUILD>), grid, block, 0, s, d, a);
     return hipGetLastError();
+}
+
+// 32 dv columns per workgroup unless that leaves most of the 256 CUs without a workgroup
+// (fp32 storage at d = 128 always takes 16: the prefetched fragments of 32 columns do not fit the registers)
+template <typename T, int DK, int DV, bool REBUILD>
+hipError_t pick_dvb(const Dims &d, const ScanFwdArgs &a, hipStream_t s) {
+    if (d.BH * (DV / 32) < 192 || (sizeof(T) == 4 && DK == 128)) return launch_scan_t<T, DK, DV, 16, REBUILD>(d, a, s);
+    return launch_scan_t<T, DK, DV, 32, REBUILD>(d, a, s);
 }
 
 template <bool REBUILD> hipError_t dispatch_scan(const Dims &d, const ScanFwdArgs &a, hipStream_t s) {
     const bool f32 = d.dtype == 1;
     if (d.dk == 64 && d.dv == 64)
-        return f32 ? launch_scan_t<float, 64, 64, REBUILD>(d, a, s) : launch_scan_t<bf16_t, 64, 64, REBUILD>(d, a, s);
+        return f32 ? pick_dvb<float, 64, 64, REBUILD>(d, a, s) : pick_dvb<bf16_t, 64, 64, REBUILD>(d, a, s);
     if (d.dk == 128 && d.dv == 128)
-        return f32 ? launch_scan_t<float, 128, 128, REBUILD>(d, a, s)
-                   : launch_scan_t<bf16_t, 128, 128, REBUILD>(d, a, s);
+        return f32 ? pick_dvb<float, 128, 128, REBUILD>(d, a, s) : pick_dvb<bf16_t, 128, 128, REBUILD>(d, a, s);
     return hipErrorInvalidValue;
 }
 
