@@ -17,39 +17,58 @@
 //   a_i = alpha_i a_{i-1}, m_i = mu_i m_{i-1}, Rho_ij = mu_i Rho_{i-1,j},
 //   b_i = alpha_i b_{i-1} + beta_i m_i, Gamma_ij = alpha_i Gamma_{i-1,j} + beta_i Rho_ij.
 //
-// One workgroup (4 waves) per (chunk, batch*head); wave w owns token rows 16w..16w+15 of every
-// row-parallel product.
+// One workgroup (8 waves) per (chunk, batch*head).  A wave owns 16 tokens and half of the dk (or j)
+// tiles of every product, and every product is formed transposed, tokens as the MFMA column index: the operands all waves share
+// (V~, K, K^T, Q^T, S, M, dS', dM') are the A operands and go through one LDS staging buffer,
+// tile after tile, each fetched from HBM with coalesced 16-byte loads while the previous tile is
+// being consumed; the wave's own rows of dO, dR, V~, q, k are B fragments held in registers.
+// An accumulator lane then holds 4 consecutive dk of one token: dq, dk leave as 8-byte stores and
+// the row dots against q, k need two shuffles.  (fp32 storage does not fit the staging buffer in
+// LDS: it reads the shared operands straight from HBM/L2 with the same code.)
 #include "mdn_device.h"
 #include "mdn_kernels.h"
+
+#include <type_traits>
 
 namespace mdn {
 
 namespace {
 
 constexpr int LDG = 65; // row stride of the fp32 64x64 coefficient matrices in LDS
+constexpr int GT = 512;  // threads per workgroup: 8 waves = 4 token tiles x 2 halves of the dk (or j) tiles
 
-// out[x] = sum over the columns of row (kg*4+x) of t .* X, X(m, c) = X[m*ldx + c]; every lane of a
-// 16-lane group ends up with the row sums of its 4 rows.
-template <typename T, int NT>
-__device__ __forceinline__ f32x4 rowdot(const f32x4 (&t)[NT], const T *X, size_t ldx) {
-    const int r = lane_id() & 15, kg = lane_id() >> 4;
-    f32x4 out;
-#pragma unroll
-    for (int x = 0; x < 4; ++x) {
-        float s = 0.f;
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) s += t[nt][x] * to_f32(X[(size_t)(kg * 4 + x) * ldx + nt * 16 + r]);
-        out[x] = reduce16(s);
-    }
-    return out;
+// sum over the 4 lanes (kg = 0..3) that hold the same token column r
+__device__ __forceinline__ float reduce_kg(float v) {
+    v += __shfl_xor(v, 16);
+    v += __shfl_xor(v, 32);
+    return v;
 }
 
-template <typename T, int DK, int DV>
-__global__ __launch_bounds__(kThreads) void grad_kernel(Dims d, GradArgs a) {
+// sum over dk of t^T[dk][i] * X[i][dk] for this lane's token; t tile mt holds dk = mt*16 + kg*4 + x
+template <int NK> __device__ __forceinline__ float coldot(const f32x4 (&t)[NK], const f32x4 (&xv)[NK]) {
+    float s = 0.f;
+#pragma unroll
+    for (int mt = 0; mt < NK; ++mt)
+#pragma unroll
+        for (int x = 0; x < 4; ++x) s += t[mt][x] * xv[mt][x];
+    return reduce_kg(s);
+}
+
+template <typename T, int DK, int DV, bool STAGED>
+__global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     typedef Op<T> O;
-    constexpr int LDW = 64 + O::PAD;
-    constexpr int NK = DK / 16;
-    constexpr size_t ALIAS_BYTES = sizeof(float) * 64 * LDG;
+    typedef typename O::Frag Frag;
+    constexpr int E = O::EPL;
+    constexpr int LDW = 64 + O::PAD, LDNV = DV + O::PAD, LDNK = DK + O::PAD;
+    constexpr int NK = DK / 16, KSV = DV / O::KSTEP, KSK = DK / O::KSTEP, KS2 = 64 / O::KSTEP;
+    constexpr int NAT_ELEMS = 64 * LDNV + 64 * LDNK, BLK_ELEMS = 2 * DK * 64, ST_ELEMS = DK * DV;
+    constexpr int SB_ELEMS0 = NAT_ELEMS > BLK_ELEMS ? NAT_ELEMS : BLK_ELEMS;
+    constexpr int SB_ELEMS = STAGED ? (SB_ELEMS0 > ST_ELEMS ? SB_ELEMS0 : ST_ELEMS) : 8;
+    // 16-byte vectors per thread of each staged tile
+    constexpr int NV_V = 64 * DV / E / GT, NV_K = 64 * DK / E / GT, NV_B = DK * 64 / E / GT, NV_S = DK * DV / E / GT;
+    constexpr int NH = NK / 2; // dk tiles per wave
+    constexpr int NREG0 = (NV_V + NV_K) > 2 * NV_B ? (NV_V + NV_K) : 2 * NV_B;
+    constexpr int NREG = NREG0 > NV_S ? NREG0 : NV_S;
 
     __shared__ float sG[64 * LDG];     // Gamma; recycled as the per-entry products of dmu
     __shared__ float sDG1[64 * LDG];   // direct dGamma from Bm; recycled as the products of dalpha
@@ -58,15 +77,18 @@ __global__ __launch_bounds__(kThreads) void grad_kernel(Dims d, GradArgs a) {
     __shared__ __align__(16) T sW2e[64 * LDW]; // W2 . eta_j         [i][j]
     __shared__ __align__(16) T sW1T[64 * LDW]; // scale W1^T         [j][i]
     __shared__ __align__(16) T sW2T[64 * LDW]; // (W2 . alpha_i)^T   [j][i]
-    __shared__ __align__(16) unsigned char sAlias[ALIAS_BYTES];
+    __shared__ __align__(16) T sB[SB_ELEMS];   // staging buffer of the shared operands
     __shared__ float s_al[64], s_be[64], s_mu[64], s_et[64], s_a[64], s_b[64], s_m[64];
-    __shared__ float s_da[64], s_db[64], s_dam[64], s_dbm[64], s_dgc[64], s_drc[64], s_dalk[64], s_detk[64];
+    // row dots come in two halves (one per dk half): [hf][token]
+    __shared__ float s_da[2][64], s_db[2][64], s_dam[2][64], s_dbm[2][64], s_dgc[2][64], s_drc[2][64], s_dalk[2][64], s_detk[2][64];
+    __shared__ float s_gC[64], s_rC[64];
     __shared__ float s_ga[64], s_gb[64], s_gm[64];
-    __shared__ float s_red[4][3];
+    __shared__ float s_red[8][3];
+    __shared__ float sRho[64 * LDG];   // Rho, rebuilt for the reverse scan
 
-    float *sRho = reinterpret_cast<float *>(sAlias); // Rho [64][LDG]                (phase 4)
-
-    const int tid = threadIdx.x, lane = lane_id(), w = wave_id(), r = lane & 15, kg = lane >> 4, i0 = w * 16;
+    const int tid = threadIdx.x, lane = lane_id(), w = wave_id(), r = lane & 15, kg = lane >> 4;
+    const int wt = w & 3, hf = w >> 2;
+    const int i = wt * 16 + r; // this lane's token (MFMA column)
     const int n = blockIdx.x, bh = blockIdx.y, b = bh / d.H, h = bh % d.H;
     const size_t tok0 = ((size_t)b * d.T + (size_t)n * 64) * d.H + h;
     const size_t blk = (size_t)bh * d.N + n;
@@ -81,7 +103,55 @@ __global__ __launch_bounds__(kThreads) void grad_kernel(Dims d, GradArgs a) {
     const T *Sg = static_cast<const T *>(a.states) + blk * (2 * DK * DV), *Mg = Sg + DK * DV;
     const T *dSg = static_cast<const T *>(a.dstates) + blk * (2 * DK * DV), *dMg = dSg + DK * DV;
 
-    // ---------------- phase 0: gates and the forward coefficient scan (Gamma, a, b, m)
+    // ---- cooperative tile movement: HBM -> registers (issue), registers -> LDS (commit)
+    Vec16<T> P[NREG], Q[NREG];
+    auto issue_natural = [&](Vec16<T> *dst, const T *src, size_t rs, auto D_, auto NV_) {
+        // [64][D] rows of the chunk; D/E vectors per row
+        constexpr int cpr = decltype(D_)::value / E;
+#pragma unroll
+        for (int u = 0; u < decltype(NV_)::value; ++u) {
+            const int c = tid + u * GT, row = c / cpr, cc = c % cpr;
+            dst[u] = *reinterpret_cast<const Vec16<T> *>(src + row * rs + cc * E);
+        }
+    };
+    auto commit_natural = [&](const Vec16<T> *src, T *dstl, int ld, auto D_, auto NV_) {
+        constexpr int cpr = decltype(D_)::value / E;
+#pragma unroll
+        for (int u = 0; u < decltype(NV_)::value; ++u) {
+            const int c = tid + u * GT, row = c / cpr, cc = c % cpr;
+            *reinterpret_cast<Vec16<T> *>(dstl + row * ld + cc * E) = src[u];
+        }
+    };
+    auto issue_linear = [&](Vec16<T> *dst, const T *src, auto NV_) {
+#pragma unroll
+        for (int u = 0; u < decltype(NV_)::value; ++u)
+            dst[u] = *reinterpret_cast<const Vec16<T> *>(src + (size_t)(tid + u * GT) * E);
+    };
+    auto commit_linear = [&](const Vec16<T> *src, T *dstl, auto NV_) {
+#pragma unroll
+        for (int u = 0; u < decltype(NV_)::value; ++u)
+            *reinterpret_cast<Vec16<T> *>(dstl + (size_t)(tid + u * GT) * E) = src[u];
+    };
+    typedef std::integral_constant<int, DV> cDV;
+    typedef std::integral_constant<int, DK> cDK;
+    typedef std::integral_constant<int, NV_V> cNV_V;
+    typedef std::integral_constant<int, NV_K> cNV_K;
+    typedef std::integral_constant<int, NV_B> cNV_B;
+    typedef std::integral_constant<int, NV_S> cNV_S;
+    auto dot_regs = [&](const Vec16<T> *x, const Vec16<T> *y) {
+        float s = 0.f;
+#pragma unroll
+        for (int u = 0; u < NV_S; ++u)
+#pragma unroll
+            for (int e = 0; e < E; ++e) s += to_f32(x[u].e[e]) * to_f32(y[u].e[e]);
+        return s;
+    };
+
+    // ---------------- prologue: first tiles in flight, gates, this wave's own rows
+    if (STAGED) {
+        issue_natural(P, vtg, rsv, cDV{}, cNV_V{});
+        issue_natural(P + NV_V, kgl, rsk, cDK{}, cNV_K{});
+    }
     if (tid < 64) {
         const size_t g = tok0 + (size_t)tid * d.H;
         s_al[tid] = a.alpha[g];
@@ -89,179 +159,237 @@ __global__ __launch_bounds__(kThreads) void grad_kernel(Dims d, GradArgs a) {
         s_mu[tid] = a.mu[g];
         s_et[tid] = a.eta ? a.eta[g] : 1.f;
     }
-    for (int c = tid; c < LDG; c += kThreads) sDG2[64 * LDG + c] = 0.f;
+    for (int c = tid; c < LDG; c += GT) sDG2[64 * LDG + c] = 0.f;
+    Frag fdO[KSV], fdR[KSV], fq[KSK], fk[KSK]; // B fragments: row = token i
+#pragma unroll
+    for (int s = 0; s < KSV; ++s) {
+        fdO[s] = O::load(dog + (size_t)i * rsv + s * O::KSTEP + kg * E);
+        fdR[s] = O::load(drg + (size_t)i * rsv + s * O::KSTEP + kg * E);
+    }
+#pragma unroll
+    for (int s = 0; s < KSK; ++s) {
+        fq[s] = O::load(qg + (size_t)i * rsk + s * O::KSTEP + kg * E);
+        fk[s] = O::load(kgl + (size_t)i * rsk + s * O::KSTEP + kg * E);
+    }
+    // k_i and q_i in accumulator layout: element x of tile mt is dk = mt*16 + kg*4 + x
+    f32x4 kv[NH];
+#pragma unroll
+    for (int mt = 0; mt < NH; ++mt) kv[mt] = load4(kgl + (size_t)i * rsk + (hf * NH + mt) * 16 + kg * 4);
+
+    const T *tVt = STAGED ? sB : vtg;
+    const T *tK = STAGED ? sB + 64 * LDNV : kgl;
+    const int ldVt = STAGED ? LDNV : (int)rsv, ldK = STAGED ? LDNK : (int)rsk;
+    if (STAGED) {
+        commit_natural(P, sB, LDNV, cDV{}, cNV_V{});
+        commit_natural(P + NV_V, sB + 64 * LDNV, LDNK, cDK{}, cNV_K{});
+        issue_linear(P, KTg, cNV_B{});
+        issue_linear(P + NV_B, QTg, cNV_B{});
+    }
     __syncthreads();
+
+    // ---------------- phase 0: forward coefficient scan (Gamma, a, b, m): wave 0, lane j = column j
     if (w == 0) {
         const int j = lane;
         float pa = 1.f, pm = 1.f, pb = 0.f, g = 0.f, rho = 0.f;
-        for (int i = 0; i < 64; ++i) {
-            const float al = s_al[i], be = s_be[i], mu = s_mu[i];
+#pragma unroll 8
+        for (int ii = 0; ii < 64; ++ii) {
+            const float al = s_al[ii], be = s_be[ii], mu = s_mu[ii];
             pa *= al;
             pm *= mu;
             pb = al * pb + be * pm;
-            if (i == j) { s_a[j] = pa; s_b[j] = pb; s_m[j] = pm; }
-            rho = (i == j) ? 1.f : rho * mu;
+            if (ii == j) { s_a[j] = pa; s_b[j] = pb; s_m[j] = pm; }
+            rho = (ii == j) ? 1.f : rho * mu;
             g = al * g + be * rho;
-            sG[i * LDG + j] = g;
+            sG[ii * LDG + j] = g;
         }
-        s_dgc[j] = g;   // Gamma_{C,j} for now (the adjoint replaces it later)
-        s_drc[j] = rho; // Rho_{C,j}
+        s_gC[j] = g;   // Gamma_{C,j}
+        s_rC[j] = rho; // Rho_{C,j}
     }
-
     __syncthreads();
 
-    // ---------------- phase 2: the four 64x64 products and the masked matrices built from them
+    // ---------------- phase A: the four 64x64 products (transposed: rows j, column i) and the
+    //                  masked matrices built from them
     {
-        f32x4 accB[4], accA[4], accQK[4], accKK[4];
-        zero_acc(accB);
-        zero_acc(accA);
-        zero_acc(accQK);
-        zero_acc(accKK);
-        mma_rows<T, 4, DV>(accB, dog + (size_t)i0 * rsv, (int)rsv, vtg, (int)rsv);
-        mma_rows<T, 4, DV>(accA, drg + (size_t)i0 * rsv, (int)rsv, vtg, (int)rsv);
-        mma_rows<T, 4, DK>(accQK, qg + (size_t)i0 * rsk, (int)rsk, kgl, (int)rsk);
-        mma_rows<T, 4, DK>(accKK, kgl + (size_t)i0 * rsk, (int)rsk, kgl, (int)rsk);
+        const float al_i = s_al[i];
 #pragma unroll
-        for (int nt = 0; nt < 4; ++nt)
+        for (int mh = 0; mh < 2; ++mh) {
+            const int mt = hf * 2 + mh;
+            f32x4 accB = {0.f, 0.f, 0.f, 0.f}, accA = accB, accQK = accB, accKK = accB;
+            const T *vp = tVt + (size_t)(mt * 16 + r) * ldVt + kg * E;
+            const T *kp = tK + (size_t)(mt * 16 + r) * ldK + kg * E;
+#pragma unroll
+            for (int s = 0; s < KSV; ++s) {
+                const Frag fv = O::load(vp + s * O::KSTEP);
+                accB = O::mma(fv, fdO[s], accB);
+                accA = O::mma(fv, fdR[s], accA);
+            }
+#pragma unroll
+            for (int s = 0; s < KSK; ++s) {
+                const Frag fkk = O::load(kp + s * O::KSTEP);
+                accQK = O::mma(fkk, fq[s], accQK);
+                accKK = O::mma(fkk, fk[s], accKK);
+            }
+            f32x4 w1e, w2e;
 #pragma unroll
             for (int x = 0; x < 4; ++x) {
-                const int i = i0 + kg * 4 + x, j = nt * 16 + r;
+                const int j = mt * 16 + kg * 4 + x;
                 const float gam = sG[i * LDG + j], gprev = (i > 0) ? sG[(i - 1) * LDG + j] : 0.f;
-                const float et = s_et[j], al = s_al[i];
-                const float dBm = (j <= i) ? accB[nt][x] : 0.f;
-                const float dA = (j < i) ? -accA[nt][x] : 0.f;
-                sDG1[i * LDG + j] = dBm * (d.scale * et * accQK[nt][x]);
-                sDG2[i * LDG + j] = dA * (al * et * accKK[nt][x]);
+                const float et = s_et[j];
+                const float dBm = (j <= i) ? accB[x] : 0.f;
+                const float dA = (j < i) ? -accA[x] : 0.f;
+                sDG1[i * LDG + j] = dBm * (d.scale * et * accQK[x]);
+                sDG2[i * LDG + j] = dA * (al_i * et * accKK[x]);
                 const float w1 = dBm * gam, w2 = dA * gprev;
-                sW1e[i * LDW + j] = from_f32<T>(w1 * et);
-                sW2e[i * LDW + j] = from_f32<T>(w2 * et);
+                w1e[x] = w1 * et;
+                w2e[x] = w2 * et;
                 sW1T[j * LDW + i] = from_f32<T>(w1 * d.scale);
-                sW2T[j * LDW + i] = from_f32<T>(w2 * al);
+                sW2T[j * LDW + i] = from_f32<T>(w2 * al_i);
             }
+            store4(sW1e + i * LDW + mt * 16 + kg * 4, w1e);
+            store4(sW2e + i * LDW + mt * 16 + kg * 4, w2e);
+        }
     }
     __syncthreads();
 
-    // ---------------- phase 3: products with the states; dq, dk and the direct coefficient adjoints
-    f32x4 accP[NK]; // dP rows i0..i0+15
-    {
-        f32x4 accQ[NK], t[NK];
-        zero_acc(accQ);
-        mma_rows_kblk<T, NK, 64>(accQ, sW1e + i0 * LDW, LDW, KTg, DK);
-        // a . (dO S^T), b . (dO M^T)
-        zero_acc(t);
-        mma_rows_vblk<T, NK, DV>(t, dog + (size_t)i0 * rsv, (int)rsv, Sg, DK);
-        f32x4 da = rowdot<T, NK>(t, qg + (size_t)i0 * rsk, rsk);
+    // ---------------- phase B: the token-contractions W1 K~, W2 K~, W1^T Q~, W2^T P
+    const T *tKT = STAGED ? sB : KTg, *tQT = STAGED ? sB + DK * 64 : QTg;
+    if (STAGED) {
+        commit_linear(P, sB, cNV_B{});
+        commit_linear(P + NV_B, sB + DK * 64, cNV_B{});
+        issue_linear(Q, Sg, cNV_S{});
+        __syncthreads();
+    }
+    f32x4 accQ[NH], accP[NH], accK[NH]; // dQ~^T, dP^T, dK~^T: [dk tile of this half][token i]
+    zero_acc(accQ);
+    zero_acc(accP);
+    zero_acc(accK);
 #pragma unroll
-        for (int x = 0; x < 4; ++x) {
-            const float ai = s_a[i0 + kg * 4 + x];
+    for (int s = 0; s < KS2; ++s) {
+        const Frag b1e = O::load(sW1e + i * LDW + s * O::KSTEP + kg * E);
+        const Frag b2e = O::load(sW2e + i * LDW + s * O::KSTEP + kg * E);
+        const Frag b1t = O::load(sW1T + i * LDW + s * O::KSTEP + kg * E);
+        const Frag b2t = O::load(sW2T + i * LDW + s * O::KSTEP + kg * E);
 #pragma unroll
-            for (int nt = 0; nt < NK; ++nt) accQ[nt][x] += ai * t[nt][x];
+        for (int mt = 0; mt < NH; ++mt) {
+            const Frag aK = O::load(tKT + kblk<T>(DK, (hf * NH + mt) * 16 + r, s * O::KSTEP + kg * E));
+            const Frag aQ = O::load(tQT + kblk<T>(DK, (hf * NH + mt) * 16 + r, s * O::KSTEP + kg * E));
+            accQ[mt] = O::mma(aK, b1e, accQ[mt]);
+            accP[mt] = O::mma(aK, b2e, accP[mt]);
+            accK[mt] = O::mma(aQ, b1t, accK[mt]);
+            accK[mt] = O::mma(aK, b2t, accK[mt]);
         }
-        zero_acc(t);
-        mma_rows_vblk<T, NK, DV>(t, dog + (size_t)i0 * rsv, (int)rsv, Mg, DK);
-        f32x4 db = rowdot<T, NK>(t, qg + (size_t)i0 * rsk, rsk);
-#pragma unroll
-        for (int x = 0; x < 4; ++x) {
-            const float bi = s_b[i0 + kg * 4 + x];
-#pragma unroll
-            for (int nt = 0; nt < NK; ++nt) accQ[nt][x] -= bi * t[nt][x];
-        }
-        if (r == 0)
-#pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                s_da[i0 + kg * 4 + x] = d.scale * da[x];
-                s_db[i0 + kg * 4 + x] = -d.scale * db[x];
-            }
-        T *dqg = static_cast<T *>(a.dq) + (tok0 + (size_t)i0 * d.H) * DK;
-#pragma unroll
-        for (int nt = 0; nt < NK; ++nt)
-#pragma unroll
-            for (int x = 0; x < 4; ++x)
-                dqg[(size_t)(kg * 4 + x) * rsk + nt * 16 + r] = from_f32<T>(d.scale * accQ[nt][x]);
+    }
 
-        // dP = W2 K~ - a^- . (dR S^T) + b^- . (dR M^T)
-        zero_acc(accP);
-        mma_rows_kblk<T, NK, 64>(accP, sW2e + i0 * LDW, LDW, KTg, DK);
-        zero_acc(t);
-        mma_rows_vblk<T, NK, DV>(t, drg + (size_t)i0 * rsv, (int)rsv, Sg, DK);
-        f32x4 dam = rowdot<T, NK>(t, kgl + (size_t)i0 * rsk, rsk); // k_i . (S dR_i); P_i = alpha_i k_i
+    // ---------------- phases C-F: products with the four state matrices, one staged tile each
+    // two products X^T[dk][i] = sum_dv St[dk][dv] f[i][dv] sharing the A fragments of one state tile
+    auto state_products = [&](const T *tile, const Frag (&f1)[KSV], const Frag (&f2)[KSV], f32x4 (&t1)[NH],
+                              f32x4 (&t2)[NH], bool second) {
+        zero_acc(t1);
+        zero_acc(t2);
 #pragma unroll
-        for (int x = 0; x < 4; ++x) {
-            const int i = i0 + kg * 4 + x;
-            const float am = (i > 0) ? s_a[i - 1] : 1.f;
+        for (int s = 0; s < KSV; ++s)
 #pragma unroll
-            for (int nt = 0; nt < NK; ++nt) accP[nt][x] -= am * t[nt][x];
-        }
-        zero_acc(t);
-        mma_rows_vblk<T, NK, DV>(t, drg + (size_t)i0 * rsv, (int)rsv, Mg, DK);
-        f32x4 dbm = rowdot<T, NK>(t, kgl + (size_t)i0 * rsk, rsk);
-#pragma unroll
-        for (int x = 0; x < 4; ++x) {
-            const int i = i0 + kg * 4 + x;
-            const float bm = (i > 0) ? s_b[i - 1] : 0.f;
-#pragma unroll
-            for (int nt = 0; nt < NK; ++nt) accP[nt][x] += bm * t[nt][x];
-        }
-        f32x4 dalk = rowdot<T, NK>(accP, kgl + (size_t)i0 * rsk, rsk);
-        if (r == 0)
-#pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                const int i = i0 + kg * 4 + x;
-                s_dam[i] = -s_al[i] * dam[x];
-                s_dbm[i] = s_al[i] * dbm[x];
-                s_dalk[i] = dalk[x];
+            for (int mt = 0; mt < NH; ++mt) {
+                const Frag as = O::load(tile + vblk(DK, (hf * NH + mt) * 16 + r, s * O::KSTEP + kg * E));
+                t1[mt] = O::mma(as, f1[s], t1[mt]);
+                if (second) t2[mt] = O::mma(as, f2[s], t2[mt]);
             }
+    };
+    float p1 = 0.f, p2 = 0.f, p3 = 0.f; // partial <dS',S>, <dS',M>, <dM',M>
+    f32x4 t1[NH], t2[NH];
+    const float a_i = s_a[i], b_i = s_b[i], am_i = (i > 0) ? s_a[i - 1] : 1.f, bm_i = (i > 0) ? s_b[i - 1] : 0.f;
+    const float al_i = s_al[i], et_i = s_et[i];
+
+    // C: S
+    if (STAGED) {
+        __syncthreads(); // phase B done with the staging buffer
+        commit_linear(Q, sB, cNV_S{});
+        issue_linear(P, dSg, cNV_S{});
+        __syncthreads();
     }
+    state_products(STAGED ? sB : Sg, fdO, fdR, t1, t2, true);
     {
-        // dK~ = W1^T Q~ + W2^T P + Gamma_C . (V~ dS'^T) - Rho_C . (V~ dM'^T), rows j = i0..i0+15
-        f32x4 accK[NK], t[NK];
-        zero_acc(accK);
-        mma_rows_kblk<T, NK, 64>(accK, sW1T + i0 * LDW, LDW, QTg, DK);
-        mma_rows_kblk<T, NK, 64>(accK, sW2T + i0 * LDW, LDW, KTg, DK);
-        zero_acc(t);
-        mma_rows_vblk<T, NK, DV>(t, vtg + (size_t)i0 * rsv, (int)rsv, dSg, DK);
-        f32x4 dgc = rowdot<T, NK>(t, kgl + (size_t)i0 * rsk, rsk);
-        float gC[4], rC[4];
+        f32x4 qv[NH];
 #pragma unroll
-        for (int x = 0; x < 4; ++x) {
-            gC[x] = s_dgc[i0 + kg * 4 + x];
-            rC[x] = s_drc[i0 + kg * 4 + x];
+        for (int mt = 0; mt < NH; ++mt) qv[mt] = load4(qg + (size_t)i * rsk + (hf * NH + mt) * 16 + kg * 4);
+        const float da = d.scale * coldot<NH>(t1, qv);
+        const float dam = -al_i * coldot<NH>(t2, kv);
+        if (kg == 0) { s_da[hf][i] = da; s_dam[hf][i] = dam; }
 #pragma unroll
-            for (int nt = 0; nt < NK; ++nt) accK[nt][x] += gC[x] * t[nt][x];
-        }
-        zero_acc(t);
-        mma_rows_vblk<T, NK, DV>(t, vtg + (size_t)i0 * rsv, (int)rsv, dMg, DK);
-        f32x4 drc = rowdot<T, NK>(t, kgl + (size_t)i0 * rsk, rsk);
-#pragma unroll
-        for (int x = 0; x < 4; ++x)
-#pragma unroll
-            for (int nt = 0; nt < NK; ++nt) accK[nt][x] -= rC[x] * t[nt][x];
-        f32x4 detk = rowdot<T, NK>(accK, kgl + (size_t)i0 * rsk, rsk);
-        __syncthreads(); // every wave has read Gamma_C / Rho_C out of s_dgc / s_drc
-        if (r == 0)
-#pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                const int j = i0 + kg * 4 + x;
-                s_dgc[j] = s_et[j] * dgc[x];   // adjoint of Gamma_{C,j}
-                s_drc[j] = -s_et[j] * drc[x];  // adjoint of Rho_{C,j}
-                s_detk[j] = detk[x];
-            }
-        T *dkg = static_cast<T *>(a.dk) + (tok0 + (size_t)i0 * d.H) * DK;
-#pragma unroll
-        for (int x = 0; x < 4; ++x) {
-            const int j = i0 + kg * 4 + x;
-            const float et = s_et[j], al = s_al[j];
-#pragma unroll
-            for (int nt = 0; nt < NK; ++nt)
-                dkg[(size_t)(kg * 4 + x) * rsk + nt * 16 + r] = from_f32<T>(et * accK[nt][x] + al * accP[nt][x]);
+        for (int mt = 0; mt < NH; ++mt) {
+            accQ[mt] += a_i * t1[mt];
+            accP[mt] -= am_i * t2[mt];
         }
     }
-    // <dS',S>, <dS',M>, <dM',M>
-    {
-        float p1 = 0.f, p2 = 0.f, p3 = 0.f;
-        for (int c = tid * O::EPL; c < DK * DV; c += kThreads * O::EPL) {
+    // E: dS'
+    Frag fVt[KSV];
 #pragma unroll
-            for (int e = 0; e < O::EPL; ++e) {
+    for (int s = 0; s < KSV; ++s) fVt[s] = O::load(vtg + (size_t)i * rsv + s * O::KSTEP + kg * E);
+    if (STAGED) {
+        __syncthreads();
+        p1 = dot_regs(P, Q);
+        commit_linear(P, sB, cNV_S{});
+        issue_linear(Q, Mg, cNV_S{});
+        __syncthreads();
+    }
+    state_products(STAGED ? sB : dSg, fVt, fVt, t1, t2, false);
+    const float gC_i = s_gC[i], rC_i = s_rC[i];
+    {
+        const float dgc = et_i * coldot<NH>(t1, kv);
+        if (kg == 0) s_dgc[hf][i] = dgc;
+#pragma unroll
+        for (int mt = 0; mt < NH; ++mt) accK[mt] += gC_i * t1[mt];
+    }
+    // D: M
+    if (STAGED) {
+        __syncthreads();
+        p2 = dot_regs(P, Q);
+        commit_linear(Q, sB, cNV_S{});
+        issue_linear(P, dMg, cNV_S{});
+        __syncthreads();
+    }
+    state_products(STAGED ? sB : Mg, fdO, fdR, t1, t2, true);
+    {
+        f32x4 qv[NH];
+#pragma unroll
+        for (int mt = 0; mt < NH; ++mt) qv[mt] = load4(qg + (size_t)i * rsk + (hf * NH + mt) * 16 + kg * 4);
+        const float db = -d.scale * coldot<NH>(t1, qv);
+        const float dbm = al_i * coldot<NH>(t2, kv);
+        if (kg == 0) { s_db[hf][i] = db; s_dbm[hf][i] = dbm; }
+#pragma unroll
+        for (int mt = 0; mt < NH; ++mt) {
+            accQ[mt] -= b_i * t1[mt];
+            accP[mt] += bm_i * t2[mt];
+        }
+        T *dqg = static_cast<T *>(a.dq) + (tok0 + (size_t)i * d.H) * DK + hf * NH * 16 + kg * 4;
+#pragma unroll
+        for (int mt = 0; mt < NH; ++mt) store4(dqg + mt * 16, d.scale * accQ[mt]);
+        const float dalk = coldot<NH>(accP, kv);
+        if (kg == 0) s_dalk[hf][i] = dalk;
+    }
+    // F: dM'
+    if (STAGED) {
+        __syncthreads();
+        p3 = dot_regs(P, Q);
+        commit_linear(P, sB, cNV_S{});
+        __syncthreads();
+    }
+    state_products(STAGED ? sB : dMg, fVt, fVt, t1, t2, false);
+    {
+        const float drc = -et_i * coldot<NH>(t1, kv);
+#pragma unroll
+        for (int mt = 0; mt < NH; ++mt) accK[mt] -= rC_i * t1[mt];
+        const float detk = coldot<NH>(accK, kv);
+        if (kg == 0) { s_drc[hf][i] = drc; s_detk[hf][i] = detk; }
+        T *dkg = static_cast<T *>(a.dk) + (tok0 + (size_t)i * d.H) * DK + hf * NH * 16 + kg * 4;
+#pragma unroll
+        for (int mt = 0; mt < NH; ++mt) store4(dkg + mt * 16, et_i * accK[mt] + al_i * accP[mt]);
+    }
+    if (!STAGED) {
+        // <dS',S>, <dS',M>, <dM',M> straight from memory
+        for (int c = tid * E; c < DK * DV; c += GT * E) {
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
                 const float s = to_f32(Sg[c + e]), m = to_f32(Mg[c + e]);
                 const float ds = to_f32(dSg[c + e]), dm = to_f32(dMg[c + e]);
                 p1 += ds * s;
@@ -269,11 +397,11 @@ __global__ __launch_bounds__(kThreads) void grad_kernel(Dims d, GradArgs a) {
                 p3 += dm * m;
             }
         }
-        p1 = reduce64(p1);
-        p2 = reduce64(p2);
-        p3 = reduce64(p3);
-        if (lane == 0) { s_red[w][0] = p1; s_red[w][1] = p2; s_red[w][2] = p3; }
     }
+    p1 = reduce64(p1);
+    p2 = reduce64(p2);
+    p3 = reduce64(p3);
+    if (lane == 0) { s_red[w][0] = p1; s_red[w][1] = p2; s_red[w][2] = p3; }
     __syncthreads();
 
     // ---------------- phase 4: reverse of the coefficient scans (wave 0)
@@ -281,78 +409,87 @@ __global__ __launch_bounds__(kThreads) void grad_kernel(Dims d, GradArgs a) {
         const int j = lane;
         {
             float rho = 0.f;
-            for (int i = 0; i < 64; ++i) {
-                rho = (i == j) ? 1.f : rho * s_mu[i];
-                sRho[i * LDG + j] = rho;
+#pragma unroll 8
+            for (int ii = 0; ii < 64; ++ii) {
+                rho = (ii == j) ? 1.f : rho * s_mu[ii];
+                sRho[ii * LDG + j] = rho;
             }
         }
         // column j of the accumulated adjoints G^ (of Gamma) and R^ (of Rho), rows 63 .. j
         float carryG = 0.f, carryR = 0.f;
-        for (int i = 63; i >= 0; --i) {
-            if (i >= j) {
-                const float G = sDG1[i * LDG + j] + sDG2[(i + 1) * LDG + j] + (i == 63 ? s_dgc[j] : 0.f) + carryG;
-                const float R = (i == 63 ? s_drc[j] : 0.f) + s_be[i] * G + carryR;
-                const float gprev = (i > j) ? sG[(i - 1) * LDG + j] : 0.f;
-                const float rprev = (i > j) ? sRho[(i - 1) * LDG + j] : 0.f;
-                sDG1[i * LDG + j] = G * gprev;                    // -> dalpha_i
-                sDG2[(i + 1) * LDG + j] = G * sRho[i * LDG + j];  // -> dbeta_i
-                sG[i * LDG + j] = R * rprev;                      // -> dmu_i
-                carryG = s_al[i] * G;
-                carryR = s_mu[i] * R;
+#pragma unroll 4
+        for (int ii = 63; ii >= 0; --ii) {
+            if (ii >= j) {
+                const float G = sDG1[ii * LDG + j] + sDG2[(ii + 1) * LDG + j] + (ii == 63 ? s_dgc[0][j] + s_dgc[1][j] : 0.f) + carryG;
+                const float R = (ii == 63 ? s_drc[0][j] + s_drc[1][j] : 0.f) + s_be[ii] * G + carryR;
+                const float gprev = (ii > j) ? sG[(ii - 1) * LDG + j] : 0.f;
+                const float rprev = (ii > j) ? sRho[(ii - 1) * LDG + j] : 0.f;
+                sDG1[ii * LDG + j] = G * gprev;                     // -> dalpha_i
+                sDG2[(ii + 1) * LDG + j] = G * sRho[ii * LDG + j];  // -> dbeta_i
+                sG[ii * LDG + j] = R * rprev;                       // -> dmu_i
+                carryG = s_al[ii] * G;
+                carryR = s_mu[ii] * R;
             }
         }
     }
     __syncthreads();
-    if (tid < 64) {
-        const int i = tid;
+    {
+        // row sums of the per-entry products: 8 threads per row
+        const int row = tid >> 3, part = tid & 7;
         float ga = 0.f, gb = 0.f, gm = 0.f;
-        for (int j = 0; j <= i; ++j) {
-            gb += sDG2[(i + 1) * LDG + j];
-            if (j < i) {
-                ga += sDG1[i * LDG + j];
-                gm += sG[i * LDG + j];
+        for (int j = part; j <= row; j += 8) {
+            gb += sDG2[(row + 1) * LDG + j];
+            if (j < row) {
+                ga += sDG1[row * LDG + j];
+                gm += sG[row * LDG + j];
             }
         }
-        s_ga[i] = ga;
-        s_gb[i] = gb;
-        s_gm[i] = gm;
+        ga += __shfl_xor(ga, 1); ga += __shfl_xor(ga, 2); ga += __shfl_xor(ga, 4);
+        gb += __shfl_xor(gb, 1); gb += __shfl_xor(gb, 2); gb += __shfl_xor(gb, 4);
+        gm += __shfl_xor(gm, 1); gm += __shfl_xor(gm, 2); gm += __shfl_xor(gm, 4);
+        if (part == 0) { s_ga[row] = ga; s_gb[row] = gb; s_gm[row] = gm; }
     }
     __syncthreads();
     if (w == 0) {
         // vectors: b_i = alpha_i b_{i-1} + beta_i m_i, a_i = alpha_i a_{i-1}, m_i = mu_i m_{i-1};
         // a^-_i = a_{i-1}, b^-_i = b_{i-1}.  Every lane runs the same 64 steps, lane i keeps step i.
-        const float dS_S = s_red[0][0] + s_red[1][0] + s_red[2][0] + s_red[3][0];
-        const float dS_M = s_red[0][1] + s_red[1][1] + s_red[2][1] + s_red[3][1];
-        const float dM_M = s_red[0][2] + s_red[1][2] + s_red[2][2] + s_red[3][2];
+        float dS_S = 0.f, dS_M = 0.f, dM_M = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < 8; ++ww) {
+            dS_S += s_red[ww][0];
+            dS_M += s_red[ww][1];
+            dM_M += s_red[ww][2];
+        }
         float cb = 0.f, ca = 0.f, cm = 0.f; // carried adjoints arriving from step i+1
         float my_al = 0.f, my_be = 0.f, my_mu = 0.f;
-        for (int i = 63; i >= 0; --i) {
-            const float al = s_al[i], be = s_be[i], mu = s_mu[i];
-            const float aprev = (i > 0) ? s_a[i - 1] : 1.f, bprev = (i > 0) ? s_b[i - 1] : 0.f;
-            const float mprev = (i > 0) ? s_m[i - 1] : 1.f;
-            float db = s_db[i] + (i < 63 ? s_dbm[i + 1] : -dS_M) + cb;
-            float da = s_da[i] + (i < 63 ? s_dam[i + 1] : dS_S) + ca;
-            float dm = (i == 63 ? dM_M : 0.f) + be * db + cm;
-            const float g_al = s_ga[i] + db * bprev + da * aprev;
-            const float g_be = s_gb[i] + db * s_m[i];
-            const float g_mu = s_gm[i] + dm * mprev;
-            if (i == lane) { my_al = g_al; my_be = g_be; my_mu = g_mu; }
+#pragma unroll 8
+        for (int ii = 63; ii >= 0; --ii) {
+            const float al = s_al[ii], be = s_be[ii], mu = s_mu[ii];
+            const float aprev = (ii > 0) ? s_a[ii - 1] : 1.f, bprev = (ii > 0) ? s_b[ii - 1] : 0.f;
+            const float mprev = (ii > 0) ? s_m[ii - 1] : 1.f;
+            const float db = s_db[0][ii] + s_db[1][ii] + (ii < 63 ? s_dbm[0][ii + 1] + s_dbm[1][ii + 1] : -dS_M) + cb;
+            const float da = s_da[0][ii] + s_da[1][ii] + (ii < 63 ? s_dam[0][ii + 1] + s_dam[1][ii + 1] : dS_S) + ca;
+            const float dm = (ii == 63 ? dM_M : 0.f) + be * db + cm;
+            const float g_al = s_ga[ii] + db * bprev + da * aprev;
+            const float g_be = s_gb[ii] + db * s_m[ii];
+            const float g_mu = s_gm[ii] + dm * mprev;
+            if (ii == lane) { my_al = g_al; my_be = g_be; my_mu = g_mu; }
             cb = al * db;
             ca = al * da;
             cm = mu * dm;
         }
         const size_t g = tok0 + (size_t)lane * d.H;
-        a.dalpha[g] = my_al + s_dalk[lane];
+        a.dalpha[g] = my_al + s_dalk[0][lane] + s_dalk[1][lane];
         a.dbeta[g] = my_be;
         a.dmu[g] = my_mu;
-        if (a.deta) a.deta[g] = s_detk[lane];
+        if (a.deta) a.deta[g] = s_detk[0][lane] + s_detk[1][lane];
     }
 }
 
-template <typename T, int DK, int DV>
+template <typename T, int DK, int DV, bool STAGED>
 hipError_t launch_t(const Dims &d, const GradArgs &a, hipStream_t s) {
-    dim3 grid(d.N, d.BH), block(kThreads);
-    hipLaunchKernelGGL((grad_kernel<T, DK, DV>), grid, block, 0, s, d, a);
+    dim3 grid(d.N, d.BH), block(GT);
+    hipLaunchKernelGGL((grad_kernel<T, DK, DV, STAGED>), grid, block, 0, s, d, a);
     return hipGetLastError();
 }
 
@@ -360,9 +497,10 @@ hipError_t launch_t(const Dims &d, const GradArgs &a, hipStream_t s) {
 
 hipError_t launch_grad(const Dims &d, const GradArgs &a, hipStream_t s) {
     const bool f32 = d.dtype == 1;
-    if (d.dk == 64 && d.dv == 64) return f32 ? launch_t<float, 64, 64>(d, a, s) : launch_t<bf16_t, 64, 64>(d, a, s);
+    if (d.dk == 64 && d.dv == 64)
+        return f32 ? launch_t<float, 64, 64, false>(d, a, s) : launch_t<bf16_t, 64, 64, true>(d, a, s);
     if (d.dk == 128 && d.dv == 128)
-        return f32 ? launch_t<float, 128, 128>(d, a, s) : launch_t<bf16_t, 128, 128>(d, a, s);
+        return f32 ? launch_t<float, 128, 128, false>(d, a, s) : launch_t<bf16_t, 128, 128, true>(d, a, s);
     return hipErrorInvalidValue;
 }
 
