@@ -1,0 +1,147 @@
+// Wave-level building blocks for the per-chunk gate coefficients of Sec. 3.1 (Eq. "coefficients")
+// in their division-free form, and for the 64x64 unit-lower-triangular solve T = (I + A)^{-1}.
+//
+//   a_i = prod_{l<=i} alpha_l,  m_i = prod_{l<=i} mu_l,  b_i = alpha_i b_{i-1} + beta_i m_i
+//   Rho_ij = prod_{l=j+1..i} mu_l,  Am_ij = prod_{l=j+1..i} alpha_l   (i >= j, 1 on the diagonal)
+//   Gamma_ij = alpha_i Gamma_{i-1,j} + beta_i Rho_ij  ( = sum_l Am_il beta_l Rho_lj )
+#pragma once
+#include "mdn_device.h"
+
+namespace mdn {
+
+// ---- scans across the 64 lanes of a wave (Kogge-Stone); lane i holds element i
+
+// inclusive prefix product
+__device__ __forceinline__ float scan_prod(float v) {
+    const int lane = lane_id();
+#pragma unroll
+    for (int dlt = 1; dlt < 64; dlt <<= 1) {
+        const float o = __shfl_up(v, dlt);
+        if (lane >= dlt) v *= o;
+    }
+    return v;
+}
+
+// x_i = c_i x_{i-1} + d_i with x_{-1} = 0: on return d holds x_i (c holds prod_{l<=i} c_l)
+__device__ __forceinline__ void scan_affine_fwd(float &c, float &d) {
+    const int lane = lane_id();
+#pragma unroll
+    for (int dlt = 1; dlt < 64; dlt <<= 1) {
+        const float oc = __shfl_up(c, dlt), od = __shfl_up(d, dlt);
+        if (lane >= dlt) {
+            d = c * od + d;
+            c = c * oc;
+        }
+    }
+}
+
+// x_i = c_i x_{i+1} + d_i with x_64 = 0: on return d holds x_i
+__device__ __forceinline__ void scan_affine_rev(float &c, float &d) {
+    const int lane = lane_id();
+#pragma unroll
+    for (int dlt = 1; dlt < 64; dlt <<= 1) {
+        const float oc = __shfl_down(c, dlt), od = __shfl_down(d, dlt);
+        if (lane + dlt < 64) {
+            d = c * od + d;
+            c = c * oc;
+        }
+    }
+}
+
+// ---- column scans of the 64x64 coefficient matrices; one wave, lane j owns column j, the gates of
+//      row i are wave-uniform (read through `al`, `be`, `mu` with a uniform index).
+//      sG[i*ldg + j] = Gamma_ij (0 above the diagonal).  The final values (row 63) are returned.
+//      If TRANSPOSED: sRhoT[j*ldt + i] = Rho_ij and sAmT[j*ldt + i] = Am_ij for i >= j (0 below j).
+template <bool TRANSPOSED>
+__device__ __forceinline__ void coef_column_scan(const float *__restrict__ al, const float *__restrict__ be,
+                                                 const float *__restrict__ mu, size_t stride, float *sG, int ldg,
+                                                 float *sRhoT, float *sAmT, int ldt, float &gC, float &rC) {
+    const int j = lane_id();
+    float g = 0.f, rho = 0.f, am = 0.f;
+#pragma unroll 16
+    for (int i = 0; i < 64; ++i) {
+        const float a_i = al[(size_t)i * stride], b_i = be[(size_t)i * stride], m_i = mu[(size_t)i * stride];
+        rho = (i == j) ? 1.f : rho * m_i;
+        g = a_i * g + b_i * rho;
+        sG[i * ldg + j] = g;
+        if (TRANSPOSED) {
+            am = (i == j) ? 1.f : am * a_i;
+            sRhoT[j * ldt + i] = rho;
+            sAmT[j * ldt + i] = am;
+        }
+    }
+    gC = g;
+    rC = rho;
+}
+
+// ---- T = (I + A)^{-1}, A strictly lower triangular 64x64 fp32 in LDS (row-major, stride lda, zeros on
+//      and above the diagonal), by 16x16 blocks.  Called by 4 waves (w = 0..3); wave w owns block row w.
+//      On return sA holds T (row-major).  sTT is scratch of 64*lda floats.
+//        T_ii = (I + A_ii)^{-1}                              (forward substitution, lane = column)
+//        T_ij = -T_ii * sum_{k=j..i-1} A_ik T_kj   (i > j)    (fp32 MFMA; levels i - j = 1, 2, 3)
+//      The accumulator of the inner sum is, lane for lane, the B fragment of the product with T_ii.
+__device__ __forceinline__ void tri_inverse_blocked(float *sA, float *sTT, int lda, int w) {
+    typedef Op<float> O;
+    const int lane = lane_id(), r = lane & 15, kg = lane >> 4;
+    const int b0 = w * 16;
+    // diagonal block: lanes 0..15, lane r solves column r of block w; t[k] = T_ww[k][r]
+    if (lane < 16) {
+        float t[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) t[i] = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            float acc = (i == r) ? 1.f : 0.f;
+#pragma unroll
+            for (int k4 = 0; k4 < (i + 3) / 4; ++k4) {
+                const f32x4 av = *reinterpret_cast<const f32x4 *>(&sA[(b0 + i) * lda + b0 + 4 * k4]);
+                acc -= av[0] * t[4 * k4 + 0];
+                acc -= av[1] * t[4 * k4 + 1];
+                acc -= av[2] * t[4 * k4 + 2];
+                acc -= av[3] * t[4 * k4 + 3];
+            }
+            t[i] = acc;
+        }
+        // T^T storage: sTT[col * lda + row]
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4)
+            *reinterpret_cast<f32x4 *>(&sTT[(b0 + r) * lda + b0 + 4 * i4]) =
+                f32x4{t[4 * i4], t[4 * i4 + 1], t[4 * i4 + 2], t[4 * i4 + 3]};
+    }
+    __syncthreads();
+    // own diagonal block as A fragments: row r, k = 4*kg + s  ->  sTT[(b0 + k) * lda + b0 + r]
+    f32x4 tii;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) tii[s] = sTT[(b0 + 4 * kg + s) * lda + b0 + r];
+    // write the diagonal block of T row-major (replacing A_ww, which is no longer needed)
+#pragma unroll
+    for (int s = 0; s < 4; ++s) sA[(b0 + r) * lda + b0 + 4 * kg + s] = tii[s];
+
+    for (int dlt = 1; dlt < 4; ++dlt) {
+        const int jb = w - dlt; // block column handled at this level
+        if (jb >= 0) {
+            f32x4 x = {0.f, 0.f, 0.f, 0.f};
+            for (int kb = jb; kb < w; ++kb) {
+                // A_{w,kb} (row-major, k contiguous) times T_{kb,jb} (from sTT: column-major, k contiguous)
+                const f32x4 fa = *reinterpret_cast<const f32x4 *>(&sA[(b0 + r) * lda + kb * 16 + 4 * kg]);
+                const f32x4 fb = *reinterpret_cast<const f32x4 *>(&sTT[(jb * 16 + r) * lda + kb * 16 + 4 * kg]);
+                x = O::mma(fa, fb, x);
+            }
+            f32x4 t = {0.f, 0.f, 0.f, 0.f};
+            t = O::mma(tii, x, t); // x is, lane for lane, the B fragment (k = 4*kg + s, n = r)
+            // t[xx] = -T_{w,jb}[row 4*kg + xx][col r]
+#pragma unroll
+            for (int xx = 0; xx < 4; ++xx) {
+                sTT[(jb * 16 + r) * lda + b0 + 4 * kg + xx] = -t[xx];
+            }
+        }
+        __syncthreads();
+    }
+    // T_{w,jb} row-major into sA for the off-diagonal blocks of this block row
+    for (int jb = 0; jb < w; ++jb) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) sA[(b0 + 4 * kg + s) * lda + jb * 16 + r] = sTT[(jb * 16 + r) * lda + b0 + 4 * kg + s];
+    }
+}
+
+} // namespace mdn

@@ -15,6 +15,7 @@
 // backward mode writes the transposed operands the reverse scan needs (-Y^T, Z^T, Bm^T, T^T, K^T, Q^T).
 // Everything is written in the blocked layouts of mdn_device.h (kblk / vblk), in which the serial
 // scans' fragment loads are contiguous.
+#include "mdn_coef.h"
 #include "mdn_device.h"
 #include "mdn_kernels.h"
 
@@ -24,31 +25,6 @@ namespace {
 
 constexpr int LDA = 68; // row stride (floats) of the fp32 A / T matrix in LDS
 constexpr int LDG = 65; // row stride (floats) of Gamma in LDS
-
-// natural [64][D] tile: rows of the chunk -> LDS [64][ld]
-template <typename T, int D>
-__device__ __forceinline__ void load_tile_natural(T *dst, int ld, const T *src, size_t row_stride, int tid,
-                                                  int nthreads) {
-    constexpr int E = Op<T>::EPL, CPR = D / E;
-    for (int c = tid; c < 64 * CPR; c += nthreads) {
-        const int row = c / CPR, cc = c % CPR;
-        const Vec16<T> v = *reinterpret_cast<const Vec16<T> *>(src + row * row_stride + cc * E);
-        *reinterpret_cast<Vec16<T> *>(dst + row * ld + cc * E) = v;
-    }
-}
-
-// transposed: LDS [D][ld] with dst[d][row] = src[row][d]
-template <typename T, int D>
-__device__ __forceinline__ void load_tile_transposed(T *dst, int ld, const T *src, size_t row_stride, int tid,
-                                                     int nthreads) {
-    constexpr int E = Op<T>::EPL, CPR = D / E;
-    for (int c = tid; c < 64 * CPR; c += nthreads) {
-        const int row = c % 64, cc = c / 64; // consecutive threads -> consecutive rows (LDS-friendly)
-        const Vec16<T> v = *reinterpret_cast<const Vec16<T> *>(src + row * row_stride + cc * E);
-#pragma unroll
-        for (int e = 0; e < E; ++e) dst[(cc * E + e) * ld + row] = v.e[e];
-    }
-}
 
 // LDS [R][ld] (first 64 columns) -> global, kblk layout of an [R][64] operand
 template <typename T>
@@ -64,17 +40,22 @@ __device__ __forceinline__ void store_tile_64cols(T *dst, const T *src, int ld, 
 template <typename T, int DK, int DV, bool BWD>
 __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
     typedef Op<T> O;
+    constexpr int E = O::EPL;
     constexpr int LDN = DK + O::PAD; // natural tiles
     constexpr int LDT = 64 + O::PAD; // transposed tiles and the operand copy of T
     constexpr int DX = BWD ? DK : DV;
     constexpr int REG_NAT = 2 * 64 * LDN, REG_TR = (DK + DX) * LDT;
     constexpr int REGION = REG_NAT > REG_TR ? REG_NAT : REG_TR;
+    constexpr int NVK = 64 * DK / E / kThreads, NVX = 64 * DX / E / kThreads; // 16-byte vectors per thread
 
     __shared__ __align__(16) T sR[REGION];
-    __shared__ __align__(16) float sG[64 * LDG];
+    // Gamma (row stride LDG); later scratch of the block inverse; later the operand copy of T
+    __shared__ __align__(16) float sG[64 * LDA];
     __shared__ __align__(16) float sA[64 * LDA];
-    __shared__ __align__(16) T sTop[64 * LDT];
-    __shared__ float s_al[64], s_be[64], s_mu[64], s_et[64], s_a[64], s_b[64], s_cs[64];
+    float *sTT = sG;
+    T *sTop = reinterpret_cast<T *>(sG);
+    static_assert(sizeof(T) * 64 * LDT <= sizeof(float) * 64 * LDA, "operand copy of T does not fit");
+    __shared__ float s_al[64], s_be[64], s_et[64], s_a[64], s_b[64], s_cs[64];
 
     T *sK = sR, *sQ = sR + 64 * LDN;      // phase A
     T *sKT = sR, *sXT = sR + DK * LDT;    // phase B (aliases phase A)
@@ -90,41 +71,62 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
     const size_t rsk = (size_t)d.H * DK, rsv = (size_t)d.H * DV;
     float *coef = a.coef + blk * (kCoefRows * 64);
 
-    if (tid < 64) {
-        const size_t g = tok0 + (size_t)tid * d.H;
-        s_al[tid] = a.alpha[g];
-        s_be[tid] = a.beta[g];
-        s_mu[tid] = a.mu[g];
-        s_et[tid] = a.eta ? a.eta[g] : 1.f;
-    }
-    load_tile_natural<T, DK>(sK, LDN, kg_, rsk, tid, kThreads);
-    load_tile_natural<T, DK>(sQ, LDN, qg, rsk, tid, kThreads);
-    __syncthreads();
-
-    // ---- gate coefficients: wave 0, lane j owns column j of Gamma / Rho
-    if (w == 0) {
-        const int j = lane;
-        float pa = 1.f, pm = 1.f, pb = 0.f, my_a = 0.f, my_b = 0.f;
-        float g = 0.f, rho = 0.f;
-        for (int i = 0; i < 64; ++i) {
-            const float al = s_al[i], be = s_be[i], mu = s_mu[i];
-            pa *= al;
-            pm *= mu;
-            pb = al * pb + be * pm;
-            if (i == j) { my_a = pa; my_b = pb; }
-            rho = (i == j) ? 1.f : rho * mu;
-            g = al * g + be * rho;
-            sG[i * LDG + j] = g;
+    // ---- K, Q tiles: all loads in flight at once, then to LDS
+    {
+        Vec16<T> rk[NVK], rq[NVK];
+        constexpr int CPR = DK / E;
+#pragma unroll
+        for (int u = 0; u < NVK; ++u) {
+            const int c = tid + u * kThreads, row = c / CPR, cc = c % CPR;
+            rk[u] = *reinterpret_cast<const Vec16<T> *>(kg_ + row * rsk + cc * E);
+            rq[u] = *reinterpret_cast<const Vec16<T> *>(qg + row * rsk + cc * E);
         }
-        s_a[j] = my_a;
-        s_b[j] = my_b;
-        const float et = s_et[j];
-        coef[COEF_A * 64 + j] = my_a;
-        coef[COEF_B * 64 + j] = my_b;
-        coef[COEF_GC * 64 + j] = g * et;
-        coef[COEF_RC * 64 + j] = rho * et;
-        coef[COEF_ETA * 64 + j] = et;
-        if (j < 3) coef[COEF_SCALAR * 64 + j] = (j == 0) ? pa : (j == 1) ? pb : pm;
+#pragma unroll
+        for (int u = 0; u < NVK; ++u) {
+            const int c = tid + u * kThreads, row = c / CPR, cc = c % CPR;
+            *reinterpret_cast<Vec16<T> *>(sK + row * LDN + cc * E) = rk[u];
+            *reinterpret_cast<Vec16<T> *>(sQ + row * LDN + cc * E) = rq[u];
+        }
+    }
+    // sources of the transposed tiles: in flight until the K, Q tiles are no longer needed
+    Vec16<T> rkt[NVK], rxt[NVX];
+#pragma unroll
+    for (int u = 0; u < NVK; ++u) {
+        const int c = tid + u * kThreads, row = c % 64, cc = c / 64;
+        rkt[u] = *reinterpret_cast<const Vec16<T> *>(kg_ + row * rsk + cc * E);
+    }
+#pragma unroll
+    for (int u = 0; u < NVX; ++u) {
+        const int c = tid + u * kThreads, row = c % 64, cc = c / 64;
+        rxt[u] = BWD ? *reinterpret_cast<const Vec16<T> *>(qg + row * rsk + cc * E)
+                     : *reinterpret_cast<const Vec16<T> *>(vg + row * rsv + cc * E);
+    }
+
+    // ---- gate coefficients: wave 0.  Vectors by wave scans (lane i = token i), matrices by a column scan.
+    if (w == 0) {
+        const size_t g = tok0 + (size_t)lane * d.H;
+        const float al = a.alpha[g], be = a.beta[g], mu = a.mu[g], et = a.eta ? a.eta[g] : 1.f;
+        const float pa = scan_prod(al), pm = scan_prod(mu);
+        float c = al, pb = be * pm;
+        scan_affine_fwd(c, pb); // b_i = alpha_i b_{i-1} + beta_i m_i
+        s_al[lane] = al;
+        s_be[lane] = be;
+        s_et[lane] = et;
+        s_a[lane] = pa;
+        s_b[lane] = pb;
+        float gC, rC;
+        coef_column_scan<false>(a.alpha + tok0, a.beta + tok0, a.mu + tok0, (size_t)d.H, sG, LDG, nullptr, nullptr, 0,
+                                gC, rC);
+        coef[COEF_A * 64 + lane] = pa;
+        coef[COEF_B * 64 + lane] = pb;
+        coef[COEF_GC * 64 + lane] = gC * et;
+        coef[COEF_RC * 64 + lane] = rC * et;
+        coef[COEF_ETA * 64 + lane] = et;
+        if (lane == 63) {
+            coef[COEF_SCALAR * 64 + 0] = pa;
+            coef[COEF_SCALAR * 64 + 1] = pb;
+            coef[COEF_SCALAR * 64 + 2] = pm;
+        }
     }
     __syncthreads();
 
@@ -179,34 +181,21 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
     }
     __syncthreads();
 
-    // ---- T = (I + A)^{-1}: wave 0, lane j solves column j by forward substitution
-    //      t_i = [i == j] - sum_{k < i} A_ik t_k   (entries above the diagonal come out as 0);
-    //      meanwhile waves 1..3 stage the transposed tiles.
-    if (w == 0) {
-        const int j = lane;
-        float t[64];
+    // ---- transposed tiles into the space of the K, Q tiles (dst[d][row] = src[row][d])
 #pragma unroll
-        for (int i = 0; i < 64; ++i) t[i] = 0.f;
+    for (int u = 0; u < NVK; ++u) {
+        const int c = tid + u * kThreads, row = c % 64, cc = c / 64;
 #pragma unroll
-        for (int i = 0; i < 64; ++i) {
-            float acc = (i == j) ? 1.f : 0.f;
-#pragma unroll
-            for (int k4 = 0; k4 < (i + 3) / 4; ++k4) {
-                const f32x4 av = *reinterpret_cast<const f32x4 *>(&sA[i * LDA + 4 * k4]);
-                acc -= av[0] * t[4 * k4 + 0];
-                acc -= av[1] * t[4 * k4 + 1];
-                acc -= av[2] * t[4 * k4 + 2];
-                acc -= av[3] * t[4 * k4 + 3];
-            }
-            t[i] = acc;
-        }
-#pragma unroll
-        for (int i = 0; i < 64; ++i) sA[i * LDA + j] = t[i];
-    } else {
-        load_tile_transposed<T, DK>(sKT, LDT, kg_, rsk, tid - 64, kThreads - 64);
-        if (BWD) load_tile_transposed<T, DK>(sXT, LDT, qg, rsk, tid - 64, kThreads - 64);
-        else load_tile_transposed<T, DV>(sXT, LDT, vg, rsv, tid - 64, kThreads - 64);
+        for (int e = 0; e < E; ++e) sKT[(cc * E + e) * LDT + row] = rkt[u].e[e];
     }
+#pragma unroll
+    for (int u = 0; u < NVX; ++u) {
+        const int c = tid + u * kThreads, row = c % 64, cc = c / 64;
+#pragma unroll
+        for (int e = 0; e < E; ++e) sXT[(cc * E + e) * LDT + row] = rxt[u].e[e];
+    }
+    // ---- T = (I + A)^{-1} by 16x16 blocks, wave w = block row w
+    tri_inverse_blocked(sA, sTT, LDA, w);
     __syncthreads();
 
     // raw transposed copies for the scans
