@@ -48,30 +48,52 @@ __device__ __forceinline__ void scan_affine_rev(float &c, float &d) {
     }
 }
 
-// ---- column scans of the 64x64 coefficient matrices; one wave, lane j owns column j, the gates of
-//      row i are wave-uniform (read through `al`, `be`, `mu` with a uniform index).
+// value held by lane `src` (compile-time constant after unrolling) as a wave-uniform scalar
+__device__ __forceinline__ float lane_bcast(float v, int src) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), src));
+}
+
+// ---- column scans of the 64x64 coefficient matrices; one wave, lane j owns column j and also HOLDS
+//      the gates of token j (al, be, mu); the gates of row i reach all lanes through v_readlane.
 //      sG[i*ldg + j] = Gamma_ij (0 above the diagonal).  The final values (row 63) are returned.
-//      If TRANSPOSED: sRhoT[j*ldt + i] = Rho_ij and sAmT[j*ldt + i] = Am_ij for i >= j (0 below j).
-template <bool TRANSPOSED>
-__device__ __forceinline__ void coef_column_scan(const float *__restrict__ al, const float *__restrict__ be,
-                                                 const float *__restrict__ mu, size_t stride, float *sG, int ldg,
-                                                 float *sRhoT, float *sAmT, int ldt, float &gC, float &rC) {
+//      If WANT_RHO: sRho[i*ldg + j] = Rho_ij as well.
+template <bool WANT_RHO>
+__device__ __forceinline__ void coef_column_scan(float al, float be, float mu, float *sG, float *sRho, int ldg,
+                                                 float &gC, float &rC) {
     const int j = lane_id();
-    float g = 0.f, rho = 0.f, am = 0.f;
-#pragma unroll 16
+    float g = 0.f, rho = 0.f;
+#pragma unroll
     for (int i = 0; i < 64; ++i) {
-        const float a_i = al[(size_t)i * stride], b_i = be[(size_t)i * stride], m_i = mu[(size_t)i * stride];
+        const float a_i = lane_bcast(al, i), b_i = lane_bcast(be, i), m_i = lane_bcast(mu, i);
         rho = (i == j) ? 1.f : rho * m_i;
         g = a_i * g + b_i * rho;
         sG[i * ldg + j] = g;
-        if (TRANSPOSED) {
-            am = (i == j) ? 1.f : am * a_i;
-            sRhoT[j * ldt + i] = rho;
-            sAmT[j * ldt + i] = am;
-        }
+        if (WANT_RHO) sRho[i * ldg + j] = rho;
     }
     gC = g;
     rC = rho;
+}
+
+// ---- reverse of the column scans (adjoint): lane j owns column j.  With D_ij the direct adjoint of
+//      Gamma_ij (sD1[i][j] + sD2[i+1][j], plus dgc_j in row 63) and drc_j the direct adjoint of Rho_63,j:
+//        G_ij = D_ij + alpha_{i+1} G_{i+1,j}            R_ij = [i = 63] drc_j + beta_i G_ij + mu_{i+1} R_{i+1,j}
+//      for i = 63 .. j.  Writes sGa[i][j] = G_ij, sRa[i][j] = R_ij (entries with i < j are not written).
+__device__ __forceinline__ void coef_column_scan_reverse(float al, float be, float mu, const float *sD1,
+                                                         const float *sD2, float dgc, float drc, float *sGa,
+                                                         float *sRa, int ldg) {
+    const int j = lane_id();
+    float cg = 0.f, cr = 0.f; // alpha_{i+1} G_{i+1,j}, mu_{i+1} R_{i+1,j}
+#pragma unroll
+    for (int i = 63; i >= 0; --i) {
+        const float a_i = lane_bcast(al, i), b_i = lane_bcast(be, i), m_i = lane_bcast(mu, i);
+        const float dir = sD1[i * ldg + j] + sD2[(i + 1) * ldg + j];
+        const float G = (i >= j) ? dir + (i == 63 ? dgc : 0.f) + cg : 0.f;
+        const float R = (i >= j) ? (i == 63 ? drc : 0.f) + b_i * G + cr : 0.f;
+        sGa[i * ldg + j] = G;
+        sRa[i * ldg + j] = R;
+        cg = a_i * G;
+        cr = m_i * R;
+    }
 }
 
 // ---- T = (I + A)^{-1}, A strictly lower triangular 64x64 fp32 in LDS (row-major, stride lda, zeros on

@@ -25,6 +25,7 @@
 // An accumulator lane then holds 4 consecutive dk of one token: dq, dk leave as 8-byte stores and
 // the row dots against q, k need two shuffles.  (fp32 storage does not fit the staging buffer in
 // LDS: it reads the shared operands straight from HBM/L2 with the same code.)
+#include "mdn_coef.h"
 #include "mdn_device.h"
 #include "mdn_kernels.h"
 
@@ -70,21 +71,25 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     constexpr int NREG0 = (NV_V + NV_K) > 2 * NV_B ? (NV_V + NV_K) : 2 * NV_B;
     constexpr int NREG = NREG0 > NV_S ? NREG0 : NV_S;
 
-    __shared__ float sG[64 * LDG];     // Gamma; recycled as the per-entry products of dmu
-    __shared__ float sDG1[64 * LDG];   // direct dGamma from Bm; recycled as the products of dalpha
-    __shared__ float sDG2[65 * LDG];   // direct dGamma^- (row i here belongs to Gamma row i-1); recycled for dbeta
-    __shared__ __align__(16) T sW1e[64 * LDW]; // W1 . eta_j         [i][j]
-    __shared__ __align__(16) T sW2e[64 * LDW]; // W2 . eta_j         [i][j]
-    __shared__ __align__(16) T sW1T[64 * LDW]; // scale W1^T         [j][i]
-    __shared__ __align__(16) T sW2T[64 * LDW]; // (W2 . alpha_i)^T   [j][i]
+    __shared__ float sG[64 * LDG];     // Gamma
+    __shared__ float sRho[64 * LDG];   // Rho
+    __shared__ float sDG1[64 * LDG];   // direct dGamma from Bm
+    __shared__ float sDG2[65 * LDG];   // direct dGamma^- (row i here belongs to Gamma row i-1)
+    __shared__ __align__(16) T sW[4 * 64 * LDW];
+    T *sW1e = sW;                 // W1 . eta_j         [i][j]
+    T *sW2e = sW + 64 * LDW;      // W2 . eta_j         [i][j]
+    T *sW1T = sW + 2 * 64 * LDW;  // scale W1^T         [j][i]
+    T *sW2T = sW + 3 * 64 * LDW;  // (W2 . alpha_i)^T   [j][i]
+    // after the W products: accumulated adjoints of Gamma and Rho
+    float *sGa = reinterpret_cast<float *>(sW), *sRa = sGa + 64 * LDG;
+    static_assert(sizeof(T) * 4 * 64 * LDW >= sizeof(float) * 2 * 64 * LDG, "adjoint matrices do not fit the W space");
     __shared__ __align__(16) T sB[SB_ELEMS];   // staging buffer of the shared operands
-    __shared__ float s_al[64], s_be[64], s_mu[64], s_et[64], s_a[64], s_b[64], s_m[64];
+    __shared__ float s_al[64], s_et[64], s_a[64], s_b[64];
     // row dots come in two halves (one per dk half): [hf][token]
     __shared__ float s_da[2][64], s_db[2][64], s_dam[2][64], s_dbm[2][64], s_dgc[2][64], s_drc[2][64], s_dalk[2][64], s_detk[2][64];
     __shared__ float s_gC[64], s_rC[64];
     __shared__ float s_ga[64], s_gb[64], s_gm[64];
     __shared__ float s_red[8][3];
-    __shared__ float sRho[64 * LDG];   // Rho, rebuilt for the reverse scan
 
     const int tid = threadIdx.x, lane = lane_id(), w = wave_id(), r = lane & 15, kg = lane >> 4;
     const int wt = w & 3, hf = w >> 2;
@@ -152,13 +157,9 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
         issue_natural(P, vtg, rsv, cDV{}, cNV_V{});
         issue_natural(P + NV_V, kgl, rsk, cDK{}, cNV_K{});
     }
-    if (tid < 64) {
-        const size_t g = tok0 + (size_t)tid * d.H;
-        s_al[tid] = a.alpha[g];
-        s_be[tid] = a.beta[g];
-        s_mu[tid] = a.mu[g];
-        s_et[tid] = a.eta ? a.eta[g] : 1.f;
-    }
+    // gates of token `lane` (used by wave 0 for the coefficient scans)
+    const size_t gl = tok0 + (size_t)lane * d.H;
+    const float g_al = a.alpha[gl], g_be = a.beta[gl], g_mu = a.mu[gl], g_et = a.eta ? a.eta[gl] : 1.f;
     for (int c = tid; c < LDG; c += GT) sDG2[64 * LDG + c] = 0.f;
     Frag fdO[KSV], fdR[KSV], fq[KSK], fk[KSK]; // B fragments: row = token i
 #pragma unroll
@@ -187,23 +188,22 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     }
     __syncthreads();
 
-    // ---------------- phase 0: forward coefficient scan (Gamma, a, b, m): wave 0, lane j = column j
+    // ---------------- phase 0: forward coefficients: vectors by wave scans, matrices by a column scan
+    float pa = 0.f, pm = 0.f, pb = 0.f; // a_lane, m_lane, b_lane (wave 0)
     if (w == 0) {
-        const int j = lane;
-        float pa = 1.f, pm = 1.f, pb = 0.f, g = 0.f, rho = 0.f;
-#pragma unroll 8
-        for (int ii = 0; ii < 64; ++ii) {
-            const float al = s_al[ii], be = s_be[ii], mu = s_mu[ii];
-            pa *= al;
-            pm *= mu;
-            pb = al * pb + be * pm;
-            if (ii == j) { s_a[j] = pa; s_b[j] = pb; s_m[j] = pm; }
-            rho = (ii == j) ? 1.f : rho * mu;
-            g = al * g + be * rho;
-            sG[ii * LDG + j] = g;
-        }
-        s_gC[j] = g;   // Gamma_{C,j}
-        s_rC[j] = rho; // Rho_{C,j}
+        pa = scan_prod(g_al);
+        pm = scan_prod(g_mu);
+        float c = g_al;
+        pb = g_be * pm;
+        scan_affine_fwd(c, pb);
+        s_al[lane] = g_al;
+        s_et[lane] = g_et;
+        s_a[lane] = pa;
+        s_b[lane] = pb;
+        float gC, rC;
+        coef_column_scan<true>(g_al, g_be, g_mu, sG, sRho, LDG, gC, rC);
+        s_gC[lane] = gC; // Gamma_{C,j}
+        s_rC[lane] = rC; // Rho_{C,j}
     }
     __syncthreads();
 
@@ -404,44 +404,22 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     if (lane == 0) { s_red[w][0] = p1; s_red[w][1] = p2; s_red[w][2] = p3; }
     __syncthreads();
 
-    // ---------------- phase 4: reverse of the coefficient scans (wave 0)
-    if (w == 0) {
-        const int j = lane;
-        {
-            float rho = 0.f;
-#pragma unroll 8
-            for (int ii = 0; ii < 64; ++ii) {
-                rho = (ii == j) ? 1.f : rho * s_mu[ii];
-                sRho[ii * LDG + j] = rho;
-            }
-        }
-        // column j of the accumulated adjoints G^ (of Gamma) and R^ (of Rho), rows 63 .. j
-        float carryG = 0.f, carryR = 0.f;
-#pragma unroll 4
-        for (int ii = 63; ii >= 0; --ii) {
-            if (ii >= j) {
-                const float G = sDG1[ii * LDG + j] + sDG2[(ii + 1) * LDG + j] + (ii == 63 ? s_dgc[0][j] + s_dgc[1][j] : 0.f) + carryG;
-                const float R = (ii == 63 ? s_drc[0][j] + s_drc[1][j] : 0.f) + s_be[ii] * G + carryR;
-                const float gprev = (ii > j) ? sG[(ii - 1) * LDG + j] : 0.f;
-                const float rprev = (ii > j) ? sRho[(ii - 1) * LDG + j] : 0.f;
-                sDG1[ii * LDG + j] = G * gprev;                     // -> dalpha_i
-                sDG2[(ii + 1) * LDG + j] = G * sRho[ii * LDG + j];  // -> dbeta_i
-                sG[ii * LDG + j] = R * rprev;                       // -> dmu_i
-                carryG = s_al[ii] * G;
-                carryR = s_mu[ii] * R;
-            }
-        }
-    }
+    // ---------------- phase 4: reverse of the coefficient scans
+    if (w == 0)
+        coef_column_scan_reverse(g_al, g_be, g_mu, sDG1, sDG2, s_dgc[0][lane] + s_dgc[1][lane],
+                                 s_drc[0][lane] + s_drc[1][lane], sGa, sRa, LDG);
     __syncthreads();
     {
-        // row sums of the per-entry products: 8 threads per row
+        // dalpha_i += sum_{j<i} G_ij Gamma_{i-1,j};  dbeta_i += sum_{j<=i} G_ij Rho_ij;
+        // dmu_i += sum_{j<i} R_ij Rho_{i-1,j}: 8 threads per row
         const int row = tid >> 3, part = tid & 7;
         float ga = 0.f, gb = 0.f, gm = 0.f;
         for (int j = part; j <= row; j += 8) {
-            gb += sDG2[(row + 1) * LDG + j];
+            const float G = sGa[row * LDG + j], R = sRa[row * LDG + j];
+            gb += G * sRho[row * LDG + j];
             if (j < row) {
-                ga += sDG1[row * LDG + j];
-                gm += sG[row * LDG + j];
+                ga += G * sG[(row - 1) * LDG + j];
+                gm += R * sRho[(row - 1) * LDG + j];
             }
         }
         ga += __shfl_xor(ga, 1); ga += __shfl_xor(ga, 2); ga += __shfl_xor(ga, 4);
@@ -451,8 +429,10 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     }
     __syncthreads();
     if (w == 0) {
-        // vectors: b_i = alpha_i b_{i-1} + beta_i m_i, a_i = alpha_i a_{i-1}, m_i = mu_i m_{i-1};
-        // a^-_i = a_{i-1}, b^-_i = b_{i-1}.  Every lane runs the same 64 steps, lane i keeps step i.
+        // vectors (lane i = token i): reverse of b_i = alpha_i b_{i-1} + beta_i m_i, a_i = alpha_i a_{i-1},
+        // m_i = mu_i m_{i-1}, with a^-_i = a_{i-1}, b^-_i = b_{i-1}:
+        //   db_i = Db_i + alpha_{i+1} db_{i+1},  da_i = Da_i + alpha_{i+1} da_{i+1},
+        //   dm_i = Dm_i + beta_i db_i + mu_{i+1} dm_{i+1}
         float dS_S = 0.f, dS_M = 0.f, dM_M = 0.f;
 #pragma unroll
         for (int ww = 0; ww < 8; ++ww) {
@@ -460,29 +440,23 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
             dS_M += s_red[ww][1];
             dM_M += s_red[ww][2];
         }
-        float cb = 0.f, ca = 0.f, cm = 0.f; // carried adjoints arriving from step i+1
-        float my_al = 0.f, my_be = 0.f, my_mu = 0.f;
-#pragma unroll 8
-        for (int ii = 63; ii >= 0; --ii) {
-            const float al = s_al[ii], be = s_be[ii], mu = s_mu[ii];
-            const float aprev = (ii > 0) ? s_a[ii - 1] : 1.f, bprev = (ii > 0) ? s_b[ii - 1] : 0.f;
-            const float mprev = (ii > 0) ? s_m[ii - 1] : 1.f;
-            const float db = s_db[0][ii] + s_db[1][ii] + (ii < 63 ? s_dbm[0][ii + 1] + s_dbm[1][ii + 1] : -dS_M) + cb;
-            const float da = s_da[0][ii] + s_da[1][ii] + (ii < 63 ? s_dam[0][ii + 1] + s_dam[1][ii + 1] : dS_S) + ca;
-            const float dm = (ii == 63 ? dM_M : 0.f) + be * db + cm;
-            const float g_al = s_ga[ii] + db * bprev + da * aprev;
-            const float g_be = s_gb[ii] + db * s_m[ii];
-            const float g_mu = s_gm[ii] + dm * mprev;
-            if (ii == lane) { my_al = g_al; my_be = g_be; my_mu = g_mu; }
-            cb = al * db;
-            ca = al * da;
-            cm = mu * dm;
-        }
-        const size_t g = tok0 + (size_t)lane * d.H;
-        a.dalpha[g] = my_al + s_dalk[0][lane] + s_dalk[1][lane];
-        a.dbeta[g] = my_be;
-        a.dmu[g] = my_mu;
-        if (a.deta) a.deta[g] = s_detk[0][lane] + s_detk[1][lane];
+        const int li = lane;
+        const float al_next = __shfl_down(g_al, 1), mu_next = __shfl_down(g_mu, 1);
+        const float dbm_next = (li < 63) ? s_dbm[0][li + 1] + s_dbm[1][li + 1] : -dS_M;
+        const float dam_next = (li < 63) ? s_dam[0][li + 1] + s_dam[1][li + 1] : dS_S;
+        float cb = (li < 63) ? al_next : 0.f, db = s_db[0][li] + s_db[1][li] + dbm_next;
+        scan_affine_rev(cb, db);
+        float ca = (li < 63) ? al_next : 0.f, da = s_da[0][li] + s_da[1][li] + dam_next;
+        scan_affine_rev(ca, da);
+        float cm = (li < 63) ? mu_next : 0.f, dm = (li == 63 ? dM_M : 0.f) + g_be * db;
+        scan_affine_rev(cm, dm);
+        const float aprev = __shfl_up(pa, 1), bprev = __shfl_up(pb, 1), mprev = __shfl_up(pm, 1);
+        const float a_prev = (li > 0) ? aprev : 1.f, b_prev = (li > 0) ? bprev : 0.f, m_prev = (li > 0) ? mprev : 1.f;
+        const size_t g = tok0 + (size_t)li * d.H;
+        a.dalpha[g] = s_ga[li] + db * b_prev + da * a_prev + s_dalk[0][li] + s_dalk[1][li];
+        a.dbeta[g] = s_gb[li] + db * pm;
+        a.dmu[g] = s_gm[li] + dm * m_prev;
+        if (a.deta) a.deta[g] = s_detk[0][li] + s_detk[1][li];
     }
 }
 

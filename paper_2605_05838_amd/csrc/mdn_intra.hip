@@ -115,8 +115,7 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
         s_a[lane] = pa;
         s_b[lane] = pb;
         float gC, rC;
-        coef_column_scan<false>(a.alpha + tok0, a.beta + tok0, a.mu + tok0, (size_t)d.H, sG, LDG, nullptr, nullptr, 0,
-                                gC, rC);
+        coef_column_scan<false>(al, be, mu, sG, nullptr, LDG, gC, rC);
         coef[COEF_A * 64 + lane] = pa;
         coef[COEF_B * 64 + lane] = pb;
         coef[COEF_GC * 64 + lane] = gC * et;
