@@ -43,8 +43,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=3, help="measurement configuration 0..4 (default: 1.3B fwd+bwd)")
     ap.add_argument("--forward-only", action="store_true")
-    ap.add_argument("--save-states", action="store_true",
-                    help="forward keeps the chunk-start states (skips their reconstruction in the backward)")
+    ap.add_argument("--recompute", action="store_true",
+                    help="forward keeps only the correction values: the backward reconstructs the chunk-start "
+                         "states and recomputes its chunk-local operands (default: the forward keeps both)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket kernels with HIP events")
     args = ap.parse_args()
@@ -68,17 +69,18 @@ def main():
 
     fout, bout = {}, {}
     fws = bws = None
+    keep = do_bwd and not args.recompute
 
     def step():
         nonlocal fout, bout, fws, bws
         f = binding.mdn_chunk_fwd(t["q"], t["k"], t["v"], t["beta"], t["alpha"], t["mu"], eta=t["eta"], S0=t["S0"],
-                                  M0=t["M0"], scale=w.scale, save_vt=do_bwd, save_states=do_bwd and args.save_states,
+                                  M0=t["M0"], scale=w.scale, save_vt=do_bwd, save_states=keep, save_operands=keep,
                                   workspace=fws, out=fout)
         fws, fout = f["workspace"], f
         if do_bwd:
             g = binding.mdn_chunk_bwd(t["q"], t["k"], t["v"], t["beta"], t["alpha"], t["mu"], f["vt"], t["dO"],
-                                      eta=t["eta"], S0=t["S0"], M0=t["M0"], states=f["states"], scale=w.scale,
-                                      workspace=bws, out=bout)
+                                      eta=t["eta"], S0=t["S0"], M0=t["M0"], states=f["states"],
+                                      operands=f["operands"], scale=w.scale, workspace=bws, out=bout)
             bws, bout = g["workspace"], g
 
     for _ in range(args.warmup):
@@ -143,7 +145,7 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "T": w.T, "H": w.H, "dk": w.dk, "dv": w.dv, "C": w.C,
-                   "pass": "fwd+bwd" if do_bwd else "fwd", "states_saved_by_forward": bool(args.save_states)},
+                   "pass": "fwd+bwd" if do_bwd else "fwd", "forward_keeps_states_and_operands": bool(keep)},
         "path_tflops": round(path_tflops, 2), "path_frac_of_mfma_peak": round(path_tflops / peak, 5),
         "gpu_event_ms_per_step": round(ev0.elapsed_time(ev1) / args.steps, 4),
         "roofline": roofline, "kernels": kernels, "cpu_baseline": cpu,

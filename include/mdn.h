@@ -69,6 +69,11 @@ int mdn_workspace_bytes(const mdn_shape *shape, int which, size_t *bytes_out);
  * [B, H, T/C, 2, dk, dv] in the storage dtype. */
 int mdn_saved_states_bytes(const mdn_shape *shape, size_t *bytes_out);
 
+/* Bytes of the optional `operands_saved` buffer: the chunk-local operands of the reverse pass
+ * (transposed WY-style factors, masked products and triangular inverse, Sec. 3.1 "Chunkwise
+ * Algorithm") that a training forward can keep so that the backward does not recompute them. */
+int mdn_saved_operands_bytes(const mdn_shape *shape, size_t *bytes_out);
+
 /*
  * Chunkwise forward (Sec. 3.1 "Chunkwise Algorithm"; Appendix C, D).
  *   in : q, k [B,T,H,dk], v [B,T,H,dv] (storage dtype); beta, alpha, mu [B,T,H] fp32;
@@ -78,13 +83,15 @@ int mdn_saved_states_bytes(const mdn_shape *shape, size_t *bytes_out);
  *        vt_saved [B,T,H,dv] (storage dtype) or NULL: the correction values V~ that
  *        mdn_chunk_bwd needs (Sec. 3.1 "Practical Considerations");
  *        states_saved (see mdn_saved_states_bytes) or NULL: chunk-start states; when given to
- *        mdn_chunk_bwd it skips their reconstruction from V~.
+ *        mdn_chunk_bwd it skips their reconstruction from V~;
+ *        operands_saved (see mdn_saved_operands_bytes) or NULL: chunk-local operands of the
+ *        reverse pass; when given to mdn_chunk_bwd it skips their recomputation.
  *   workspace: at least mdn_workspace_bytes(MDN_WS_FWD); contents are scratch.
  */
 int mdn_chunk_fwd(const mdn_shape *shape, const void *q, const void *k, const void *v, const float *beta,
                   const float *alpha, const float *mu, const float *eta, const float *S0, const float *M0,
                   void *o, float *S_final, float *M_final, void *vt_saved, void *states_saved,
-                  void *workspace, size_t workspace_bytes, void *stream);
+                  void *operands_saved, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Chunkwise backward: adjoint of mdn_chunk_fwd for the scalar
@@ -92,7 +99,7 @@ int mdn_chunk_fwd(const mdn_shape *shape, const void *q, const void *k, const vo
  * The forward keeps V~ only (Sec. 3.1 "Practical Considerations"); the chunk-start states
  * are reconstructed from it unless states_saved is given.
  *   in : the forward inputs (same pointers/values as in the forward call), vt_saved (required),
- *        states_saved or NULL, dO [B,T,H,dv] (storage dtype),
+ *        states_saved or NULL, operands_saved or NULL, dO [B,T,H,dv] (storage dtype),
  *        dS_final, dM_final [B,H,dk,dv] fp32 or NULL (= 0).
  *   out: dq, dk [B,T,H,dk], dv [B,T,H,dv] (storage dtype); dbeta, dalpha, dmu [B,T,H] fp32;
  *        deta [B,T,H] fp32 or NULL; dS0, dM0 [B,H,dk,dv] fp32 or NULL.
@@ -101,8 +108,8 @@ int mdn_chunk_fwd(const mdn_shape *shape, const void *q, const void *k, const vo
  */
 int mdn_chunk_bwd(const mdn_shape *shape, const void *q, const void *k, const void *v, const float *beta,
                   const float *alpha, const float *mu, const float *eta, const float *S0, const float *M0,
-                  const void *vt_saved, const void *states_saved, const void *dO, const float *dS_final,
-                  const float *dM_final, void *dq, void *dk, void *dv, float *dbeta, float *dalpha,
+                  const void *vt_saved, const void *states_saved, const void *operands_saved, const void *dO,
+                  const float *dS_final, const float *dM_final, void *dq, void *dk, void *dv, float *dbeta, float *dalpha,
                   float *dmu, float *deta, float *dS0, float *dM0, void *workspace, size_t workspace_bytes,
                   void *stream);
 
@@ -127,7 +134,8 @@ int mdn_recurrent_step(const mdn_shape *shape, const void *q, const void *k, con
  * then releases the events.  Not thread-safe; meant for one benchmarking thread.
  */
 enum {
-    MDN_KERNEL_INTRA_FWD = 0, /* chunk-local coefficients, masked products, triangular solve, U/Y/Z */
+    MDN_KERNEL_INTRA_FWD = 0, /* chunk-local coefficients, masked products, triangular solve, U/Y/Z
+                                 (and the reverse pass's operands when operands_saved is given) */
     MDN_KERNEL_SCAN_FWD = 1,  /* sequential inter-chunk propagation of S and M, outputs */
     MDN_KERNEL_INTRA_BWD = 2, /* same as 0 in the operand layouts of the reverse pass */
     MDN_KERNEL_REBUILD = 3,   /* chunk-start states reconstructed from V~ */

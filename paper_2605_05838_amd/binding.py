@@ -17,7 +17,8 @@ LIB_PATH = os.path.join(_HERE, "libmdn_hip.so")
 MDN_DTYPE_BF16, MDN_DTYPE_F32 = 0, 1
 MDN_WS_FWD, MDN_WS_BWD = 0, 1
 
-EXPORTS = ("mdn_version", "mdn_strerror", "mdn_workspace_bytes", "mdn_saved_states_bytes", "mdn_chunk_fwd",
+EXPORTS = ("mdn_version", "mdn_strerror", "mdn_workspace_bytes", "mdn_saved_states_bytes",
+           "mdn_saved_operands_bytes", "mdn_chunk_fwd",
            "mdn_chunk_bwd", "mdn_recurrent_step", "mdn_profile_begin", "mdn_profile_end")
 
 KERNEL_NAMES = ("intra_fwd", "scan_fwd", "intra_bwd", "rebuild", "scan_bwd", "grad", "recurrent")
@@ -51,10 +52,12 @@ def load_library():
     lib.mdn_workspace_bytes.argtypes = [sp, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t)]
     lib.mdn_saved_states_bytes.restype = ctypes.c_int
     lib.mdn_saved_states_bytes.argtypes = [sp, ctypes.POINTER(ctypes.c_size_t)]
+    lib.mdn_saved_operands_bytes.restype = ctypes.c_int
+    lib.mdn_saved_operands_bytes.argtypes = [sp, ctypes.POINTER(ctypes.c_size_t)]
     lib.mdn_chunk_fwd.restype = ctypes.c_int
-    lib.mdn_chunk_fwd.argtypes = [sp] + [vp] * 3 + [fp] * 6 + [vp, fp, fp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.mdn_chunk_fwd.argtypes = [sp] + [vp] * 3 + [fp] * 6 + [vp, fp, fp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.mdn_chunk_bwd.restype = ctypes.c_int
-    lib.mdn_chunk_bwd.argtypes = [sp] + [vp] * 3 + [fp] * 6 + [vp] * 3 + [fp] * 2 + [vp] * 3 + [fp] * 6 + \
+    lib.mdn_chunk_bwd.argtypes = [sp] + [vp] * 3 + [fp] * 6 + [vp] * 4 + [fp] * 2 + [vp] * 3 + [fp] * 6 + \
         [vp, ctypes.c_size_t, vp]
     lib.mdn_recurrent_step.restype = ctypes.c_int
     lib.mdn_recurrent_step.argtypes = [sp] + [vp] * 3 + [fp] * 4 + [fp, fp, vp, vp]
@@ -115,6 +118,12 @@ def saved_states_bytes(shape: MdnShape) -> int:
     return n.value
 
 
+def saved_operands_bytes(shape: MdnShape) -> int:
+    n = ctypes.c_size_t(0)
+    _check(load_library().mdn_saved_operands_bytes(ctypes.byref(shape), ctypes.byref(n)), "mdn_saved_operands_bytes")
+    return n.value
+
+
 def _workspace(shape, which, workspace, device):
     need = workspace_bytes(shape, which)
     if workspace is None:
@@ -123,8 +132,8 @@ def _workspace(shape, which, workspace, device):
 
 
 def mdn_chunk_fwd(q, k, v, beta, alpha, mu, eta=None, S0=None, M0=None, scale=None, save_vt=False,
-                  save_states=False, output_final_state=True, workspace=None, out=None):
-    """Chunkwise forward.  Returns a dict: o, S, M (final states or None), vt, states (or None)."""
+                  save_states=False, save_operands=False, output_final_state=True, workspace=None, out=None):
+    """Chunkwise forward.  Returns a dict: o, S, M (final states or None), vt, states, operands (or None)."""
     lib = load_library()
     shape = make_shape(q, v, scale)
     for t in (k, v):
@@ -137,7 +146,11 @@ def mdn_chunk_fwd(q, k, v, beta, alpha, mu, eta=None, S0=None, M0=None, scale=No
     o = out.get("o")
     if o is None:
         o = torch.empty((B, T, H, dv), dtype=q.dtype, device=dev)
-    S = M = vt = states = None
+    S = M = vt = states = operands = None
+    if save_operands:
+        operands = out.get("operands")
+        if operands is None:
+            operands = torch.empty(saved_operands_bytes(shape), dtype=torch.uint8, device=dev)
     if output_final_state:
         S = out.get("S") if out.get("S") is not None else torch.empty((B, H, dk, dv), dtype=torch.float32, device=dev)
         M = out.get("M") if out.get("M") is not None else torch.empty((B, H, dk, dv), dtype=torch.float32, device=dev)
@@ -150,13 +163,13 @@ def mdn_chunk_fwd(q, k, v, beta, alpha, mu, eta=None, S0=None, M0=None, scale=No
     workspace, wbytes = _workspace(shape, MDN_WS_FWD, workspace, dev)
     rc = lib.mdn_chunk_fwd(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _f32(beta, "beta"), _f32(alpha, "alpha"),
                            _f32(mu, "mu"), _f32(eta, "eta"), _f32(S0, "S0"), _f32(M0, "M0"), _ptr(o), _ptr(S),
-                           _ptr(M), _ptr(vt), _ptr(states), _ptr(workspace), wbytes, _stream())
+                           _ptr(M), _ptr(vt), _ptr(states), _ptr(operands), _ptr(workspace), wbytes, _stream())
     _check(rc, "mdn_chunk_fwd")
-    return {"o": o, "S": S, "M": M, "vt": vt, "states": states, "workspace": workspace}
+    return {"o": o, "S": S, "M": M, "vt": vt, "states": states, "operands": operands, "workspace": workspace}
 
 
-def mdn_chunk_bwd(q, k, v, beta, alpha, mu, vt, dO, eta=None, S0=None, M0=None, states=None, dS_final=None,
-                  dM_final=None, scale=None, want_deta=False, want_dstates=True, workspace=None, out=None):
+def mdn_chunk_bwd(q, k, v, beta, alpha, mu, vt, dO, eta=None, S0=None, M0=None, states=None, operands=None,
+                  dS_final=None, dM_final=None, scale=None, want_deta=False, want_dstates=True, workspace=None, out=None):
     """Chunkwise backward.  Returns a dict: dq, dk, dv, dbeta, dalpha, dmu, deta, dS0, dM0."""
     lib = load_library()
     shape = make_shape(q, v, scale)
@@ -181,7 +194,7 @@ def mdn_chunk_bwd(q, k, v, beta, alpha, mu, vt, dO, eta=None, S0=None, M0=None, 
     workspace, wbytes = _workspace(shape, MDN_WS_BWD, workspace, dev)
     rc = lib.mdn_chunk_bwd(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _f32(beta, "beta"), _f32(alpha, "alpha"),
                            _f32(mu, "mu"), _f32(eta, "eta"), _f32(S0, "S0"), _f32(M0, "M0"), _ptr(vt), _ptr(states),
-                           _ptr(dO), _f32(dS_final, "dS_final"), _f32(dM_final, "dM_final"), _ptr(dq), _ptr(dk_t),
+                           _ptr(operands), _ptr(dO), _f32(dS_final, "dS_final"), _f32(dM_final, "dM_final"), _ptr(dq), _ptr(dk_t),
                            _ptr(dv_t), _f32(dbeta, "dbeta"), _f32(dalpha, "dalpha"), _f32(dmu, "dmu"),
                            _f32(deta, "deta"), _f32(dS0, "dS0"), _f32(dM0, "dM0"), _ptr(workspace), wbytes, _stream())
     _check(rc, "mdn_chunk_bwd")

@@ -41,7 +41,6 @@ struct Carver {
 };
 
 struct FwdWs { float *coef; void *KT, *U, *nY, *Z, *Bm; size_t total; };
-struct BwdWs { float *coef; void *KT, *QT, *nYT, *ZT, *BmT, *TmT, *dstates, *states; size_t total; };
 
 FwdWs carve_fwd(const Dims &d, void *ws) {
     const size_t es = d.dtype == MDN_DTYPE_F32 ? 4 : 2, nb = (size_t)d.BH * d.N;
@@ -57,10 +56,14 @@ FwdWs carve_fwd(const Dims &d, void *ws) {
     return w;
 }
 
-BwdWs carve_bwd(const Dims &d, void *ws) {
+// Operands of the reverse pass (what intra mode 1 / 2 writes); lives in the backward workspace or in
+// the buffer a training forward keeps for the backward.
+struct RevOps { float *coef; void *KT, *QT, *nYT, *ZT, *BmT, *TmT; size_t total; };
+
+RevOps carve_rev(const Dims &d, void *p) {
     const size_t es = d.dtype == MDN_DTYPE_F32 ? 4 : 2, nb = (size_t)d.BH * d.N;
-    Carver c(ws);
-    BwdWs w;
+    Carver c(p);
+    RevOps w;
     w.coef = static_cast<float *>(c.take(nb * (size_t)(6 * 64 * sizeof(float))));
     w.KT = c.take(nb * d.dk * 64 * es);
     w.QT = c.take(nb * d.dk * 64 * es);
@@ -68,6 +71,18 @@ BwdWs carve_bwd(const Dims &d, void *ws) {
     w.ZT = c.take(nb * d.dk * 64 * es);
     w.BmT = c.take(nb * 4096 * es);
     w.TmT = c.take(nb * 4096 * es);
+    w.total = c.off;
+    return w;
+}
+
+struct BwdWs { RevOps ops; void *dstates, *states; size_t total; };
+
+BwdWs carve_bwd(const Dims &d, void *ws) {
+    const size_t es = d.dtype == MDN_DTYPE_F32 ? 4 : 2, nb = (size_t)d.BH * d.N;
+    BwdWs w;
+    w.ops = carve_rev(d, ws);
+    Carver c(ws);
+    c.off = w.ops.total;
     w.dstates = c.take(nb * 2 * d.dk * d.dv * es);
     w.states = c.take(nb * 2 * d.dk * d.dv * es);
     w.total = c.off;
@@ -156,15 +171,25 @@ int mdn_saved_states_bytes(const mdn_shape *shape, size_t *bytes_out) {
     return MDN_OK;
 }
 
+int mdn_saved_operands_bytes(const mdn_shape *shape, size_t *bytes_out) {
+    Dims d;
+    if (!bytes_out) return MDN_ERR_NULL;
+    int rc = check_shape(shape, true, &d);
+    if (rc) return rc;
+    *bytes_out = carve_rev(d, nullptr).total;
+    return MDN_OK;
+}
+
 int mdn_chunk_fwd(const mdn_shape *shape, const void *q, const void *k, const void *v, const float *beta,
                   const float *alpha, const float *mu, const float *eta, const float *S0, const float *M0,
                   void *o, float *S_final, float *M_final, void *vt_saved, void *states_saved,
-                  void *workspace, size_t workspace_bytes, void *stream) {
+                  void *operands_saved, void *workspace, size_t workspace_bytes, void *stream) {
     Dims d;
     int rc = check_shape(shape, true, &d);
     if (rc) return rc;
     if (!q || !k || !v || !beta || !alpha || !mu || !o || !workspace) return MDN_ERR_NULL;
-    const void *ptrs[] = {q, k, v, beta, alpha, mu, eta, S0, M0, o, S_final, M_final, vt_saved, states_saved, workspace};
+    const void *ptrs[] = {q, k, v, beta, alpha, mu, eta, S0, M0, o, S_final, M_final, vt_saved, states_saved,
+                          operands_saved, workspace};
     for (const void *p : ptrs)
         if (p && misaligned(p)) return MDN_ERR_ALIGN;
     FwdWs w = carve_fwd(d, workspace);
@@ -174,11 +199,16 @@ int mdn_chunk_fwd(const mdn_shape *shape, const void *q, const void *k, const vo
     IntraArgs ia = {};
     ia.q = q; ia.k = k; ia.v = v; ia.alpha = alpha; ia.beta = beta; ia.mu = mu; ia.eta = eta;
     ia.coef = w.coef; ia.KT = w.KT; ia.U = w.U; ia.nY = w.nY; ia.Z = w.Z; ia.Bm = w.Bm;
-    rc = timed(MDN_KERNEL_INTRA_FWD, s, [&] { return launch_intra(d, false, ia, s); });
+    if (operands_saved) {
+        // training forward: one precompute pass writes the reverse pass's operands as well
+        const RevOps ro = carve_rev(d, operands_saved);
+        ia.coef = ro.coef; ia.KT = ro.KT; ia.QT = ro.QT; ia.nYT = ro.nYT; ia.ZT = ro.ZT; ia.BmT = ro.BmT; ia.TmT = ro.TmT;
+    }
+    rc = timed(MDN_KERNEL_INTRA_FWD, s, [&] { return launch_intra(d, operands_saved ? 2 : 0, ia, s); });
     if (rc) return rc;
 
     ScanFwdArgs sa = {};
-    sa.q = q; sa.coef = w.coef; sa.KT = w.KT; sa.U = w.U; sa.nY = w.nY; sa.Z = w.Z; sa.Bm = w.Bm;
+    sa.q = q; sa.coef = ia.coef; sa.KT = ia.KT; sa.U = w.U; sa.nY = w.nY; sa.Z = w.Z; sa.Bm = w.Bm;
     sa.S0 = S0; sa.M0 = M0; sa.o = o; sa.vt_saved = vt_saved; sa.states_saved = states_saved;
     sa.S_final = S_final; sa.M_final = M_final;
     return timed(MDN_KERNEL_SCAN_FWD, s, [&] { return launch_scan_fwd(d, sa, s); });
@@ -186,7 +216,8 @@ int mdn_chunk_fwd(const mdn_shape *shape, const void *q, const void *k, const vo
 
 int mdn_chunk_bwd(const mdn_shape *shape, const void *q, const void *k, const void *v, const float *beta,
                   const float *alpha, const float *mu, const float *eta, const float *S0, const float *M0,
-                  const void *vt_saved, const void *states_saved, const void *dO, const float *dS_final,
+                  const void *vt_saved, const void *states_saved, const void *operands_saved, const void *dO,
+                  const float *dS_final,
                   const float *dM_final, void *dq, void *dk, void *dv, float *dbeta, float *dalpha,
                   float *dmu, float *deta, float *dS0, float *dM0, void *workspace, size_t workspace_bytes,
                   void *stream) {
@@ -196,7 +227,7 @@ int mdn_chunk_bwd(const mdn_shape *shape, const void *q, const void *k, const vo
     if (!q || !k || !v || !beta || !alpha || !mu || !vt_saved || !dO || !dq || !dk || !dv || !dbeta || !dalpha ||
         !dmu || !workspace)
         return MDN_ERR_NULL;
-    const void *ptrs[] = {q, k, v, beta, alpha, mu, eta, S0, M0, vt_saved, states_saved, dO, dS_final, dM_final,
+    const void *ptrs[] = {q, k, v, beta, alpha, mu, eta, S0, M0, vt_saved, states_saved, operands_saved, dO, dS_final, dM_final,
                           dq, dk, dv, dbeta, dalpha, dmu, deta, dS0, dM0, workspace};
     for (const void *p : ptrs)
         if (p && misaligned(p)) return MDN_ERR_ALIGN;
@@ -204,33 +235,38 @@ int mdn_chunk_bwd(const mdn_shape *shape, const void *q, const void *k, const vo
     if (workspace_bytes < w.total) return MDN_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
 
-    // chunk-local operands in the layouts of the reverse pass
-    IntraArgs ia = {};
-    ia.q = q; ia.k = k; ia.v = v; ia.alpha = alpha; ia.beta = beta; ia.mu = mu; ia.eta = eta;
-    ia.coef = w.coef; ia.KT = w.KT; ia.QT = w.QT; ia.nYT = w.nYT; ia.ZT = w.ZT; ia.BmT = w.BmT; ia.TmT = w.TmT;
-    rc = timed(MDN_KERNEL_INTRA_BWD, s, [&] { return launch_intra(d, true, ia, s); });
-    if (rc) return rc;
+    // chunk-local operands in the layouts of the reverse pass: kept by the forward, or recomputed
+    RevOps ro = w.ops;
+    if (operands_saved) {
+        ro = carve_rev(d, const_cast<void *>(operands_saved));
+    } else {
+        IntraArgs ia = {};
+        ia.q = q; ia.k = k; ia.v = v; ia.alpha = alpha; ia.beta = beta; ia.mu = mu; ia.eta = eta;
+        ia.coef = ro.coef; ia.KT = ro.KT; ia.QT = ro.QT; ia.nYT = ro.nYT; ia.ZT = ro.ZT; ia.BmT = ro.BmT; ia.TmT = ro.TmT;
+        rc = timed(MDN_KERNEL_INTRA_BWD, s, [&] { return launch_intra(d, 1, ia, s); });
+        if (rc) return rc;
+    }
 
     // chunk-start states: given by the forward, or reconstructed from V~
     const void *states = states_saved;
     if (!states) {
         RebuildArgs ra = {};
-        ra.coef = w.coef; ra.KT = w.KT; ra.vt_saved = vt_saved; ra.S0 = S0; ra.M0 = M0; ra.states = w.states;
+        ra.coef = ro.coef; ra.KT = ro.KT; ra.vt_saved = vt_saved; ra.S0 = S0; ra.M0 = M0; ra.states = w.states;
         rc = timed(MDN_KERNEL_REBUILD, s, [&] { return launch_rebuild(d, ra, s); });
         if (rc) return rc;
         states = w.states;
     }
 
     ScanBwdArgs sb = {};
-    sb.k = k; sb.dO = dO; sb.coef = w.coef; sb.QT = w.QT; sb.nYT = w.nYT; sb.ZT = w.ZT; sb.BmT = w.BmT;
-    sb.TmT = w.TmT; sb.dS_final = dS_final; sb.dM_final = dM_final; sb.dv = dv; sb.dstates = w.dstates;
+    sb.k = k; sb.dO = dO; sb.coef = ro.coef; sb.QT = ro.QT; sb.nYT = ro.nYT; sb.ZT = ro.ZT; sb.BmT = ro.BmT;
+    sb.TmT = ro.TmT; sb.dS_final = dS_final; sb.dM_final = dM_final; sb.dv = dv; sb.dstates = w.dstates;
     sb.dS0 = dS0; sb.dM0 = dM0;
     rc = timed(MDN_KERNEL_SCAN_BWD, s, [&] { return launch_scan_bwd(d, sb, s); });
     if (rc) return rc;
 
     GradArgs ga = {};
     ga.q = q; ga.k = k; ga.alpha = alpha; ga.beta = beta; ga.mu = mu; ga.eta = eta;
-    ga.vt_saved = vt_saved; ga.dO = dO; ga.dv = dv; ga.KT = w.KT; ga.QT = w.QT;
+    ga.vt_saved = vt_saved; ga.dO = dO; ga.dv = dv; ga.KT = ro.KT; ga.QT = ro.QT;
     ga.states = states; ga.dstates = w.dstates;
     ga.dq = dq; ga.dk = dk; ga.dalpha = dalpha; ga.dbeta = dbeta; ga.dmu = dmu; ga.deta = deta;
     return timed(MDN_KERNEL_GRAD, s, [&] { return launch_grad(d, ga, s); });

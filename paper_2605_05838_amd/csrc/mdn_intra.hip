@@ -12,7 +12,8 @@
 //   WY-style factors  U = T V,  Y = T diag(a^-) P = (T diag(a)) K,  Z = T diag(b^-) P = (T diag(b^- alpha)) K
 //
 // One workgroup (4 waves) per (chunk, batch*head).  Forward mode writes U, -Y, Z, Bm and K^T;
-// backward mode writes the transposed operands the reverse scan needs (-Y^T, Z^T, Bm^T, T^T, K^T, Q^T).
+// backward mode writes the transposed operands the reverse scan needs (-Y^T, Z^T, Bm^T, T^T, K^T, Q^T);
+// a training forward can write both sets at once, so that the backward need not recompute them.
 // Everything is written in the blocked layouts of mdn_device.h (kblk / vblk), in which the serial
 // scans' fragment loads are contiguous.
 #include "mdn_coef.h"
@@ -37,13 +38,16 @@ __device__ __forceinline__ void store_tile_64cols(T *dst, const T *src, int ld, 
     }
 }
 
-template <typename T, int DK, int DV, bool BWD>
+// MODE 0: forward operands; 1: operands of the reverse pass; 2: both (training forward that keeps the
+// reverse pass's operands instead of recomputing them)
+template <typename T, int DK, int DV, int MODE>
 __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
+    constexpr bool FWD = MODE != 1, BWD = MODE != 0;
     typedef Op<T> O;
     constexpr int E = O::EPL;
     constexpr int LDN = DK + O::PAD; // natural tiles
     constexpr int LDT = 64 + O::PAD; // transposed tiles and the operand copy of T
-    constexpr int DX = BWD ? DK : DV;
+    constexpr int DX = FWD ? DV : DK;
     constexpr int REG_NAT = 2 * 64 * LDN, REG_TR = (DK + DX) * LDT;
     constexpr int REGION = REG_NAT > REG_TR ? REG_NAT : REG_TR;
     constexpr int NVK = 64 * DK / E / kThreads, NVX = 64 * DX / E / kThreads; // 16-byte vectors per thread
@@ -98,8 +102,8 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
 #pragma unroll
     for (int u = 0; u < NVX; ++u) {
         const int c = tid + u * kThreads, row = c % 64, cc = c / 64;
-        rxt[u] = BWD ? *reinterpret_cast<const Vec16<T> *>(qg + row * rsk + cc * E)
-                     : *reinterpret_cast<const Vec16<T> *>(vg + row * rsv + cc * E);
+        rxt[u] = FWD ? *reinterpret_cast<const Vec16<T> *>(vg + row * rsv + cc * E)
+                     : *reinterpret_cast<const Vec16<T> *>(qg + row * rsk + cc * E);
     }
 
     // ---- gate coefficients: wave 0.  Vectors by wave scans (lane i = token i), matrices by a column scan.
@@ -148,6 +152,7 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
             }
         if (BWD) {
             // qk[nt][x] = q_i . k_j, i = i0 + kq*4 + x, j = nt*16 + r  ->  Bm^T row j, k = i
+            zero_acc(qk);
             mma_rows<T, 4, DK>(qk, sQ + i0 * LDN, LDN, sK, LDN);
             T *out = static_cast<T *>(a.BmT) + blk * 4096;
 #pragma unroll
@@ -161,8 +166,10 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
                 }
                 store4(out + kblk<T>(64, j, i0 + kq * 4), v);
             }
-        } else {
+        }
+        if (FWD) {
             // qk[nt][x] = k_j . q_i, j = i0 + kq*4 + x, i = nt*16 + r  ->  Bm row i, k = j
+            zero_acc(qk);
             mma_rows<T, 4, DK>(qk, sK + i0 * LDN, LDN, sQ, LDN);
             T *out = static_cast<T *>(a.Bm) + blk * 4096;
 #pragma unroll
@@ -199,8 +206,8 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
 
     // raw transposed copies for the scans
     store_tile_64cols<T>(static_cast<T *>(a.KT) + blk * (DK * 64), sKT, LDT, DK, tid);
+    if (MODE == 1) store_tile_64cols<T>(static_cast<T *>(a.QT) + blk * (DK * 64), sXT, LDT, DK, tid);
     if (BWD) {
-        store_tile_64cols<T>(static_cast<T *>(a.QT) + blk * (DK * 64), sXT, LDT, DK, tid);
         T *tt = static_cast<T *>(a.TmT) + blk * 4096; // T^T: row j, k = i
         constexpr int E = O::EPL;
         for (int c = tid; c < 64 * (64 / E); c += kThreads) {
@@ -215,7 +222,7 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
     // ---- WY-style factors.  pass 0: U = T V (forward only); pass 1: Y; pass 2: Z.
     //      Each product is formed in the orientation whose accumulator lanes hold 4 consecutive
     //      entries along the index that is contiguous in the consumer's layout.
-    for (int pass = BWD ? 1 : 0; pass < 3; ++pass) {
+    for (int pass = FWD ? 0 : 1; pass < 3; ++pass) {
         if (tid < 64) {
             const float bprev = (tid > 0) ? s_b[tid - 1] : 0.f;
             s_cs[tid] = (pass == 0) ? 1.f : (pass == 1) ? s_a[tid] : bprev * s_al[tid];
@@ -227,7 +234,7 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
         }
         __syncthreads();
         const float sgn = pass == 1 ? -1.f : 1.f;
-        if (!BWD) {
+        if (FWD) {
             if (pass == 0) {
                 // U^T[dv][i] = sum_j V^T[dv][j] T[i][j]  ->  vblk [dv/16][token][16]
 #pragma unroll
@@ -253,7 +260,8 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
                     for (int nt = 0; nt < 4; ++nt) store4(out + kblk<T>(64, nt * 16 + r, m0 + kq * 4), sgn * y[nt]);
                 }
             }
-        } else {
+        }
+        if (BWD && pass > 0) {
             // Y[i][dk] = sum_j (T diag(cs))[i][j] K^T[dk][j]  ->  Y^T in kblk: row dk, k = i
             f32x4 y[DK / 16];
             zero_acc(y);
@@ -264,24 +272,43 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
         }
         __syncthreads();
     }
+    if (MODE == 2) {
+        // Q^T for the reverse pass, through the tile space the V^T tile no longer needs
+        static_assert(MODE != 2 || DX >= DK, "Q^T does not fit the V^T tile");
+        Vec16<T> rq[NVK];
+#pragma unroll
+        for (int u = 0; u < NVK; ++u) {
+            const int c = tid + u * kThreads, row = c % 64, cc = c / 64;
+            rq[u] = *reinterpret_cast<const Vec16<T> *>(qg + row * rsk + cc * E);
+        }
+#pragma unroll
+        for (int u = 0; u < NVK; ++u) {
+            const int c = tid + u * kThreads, row = c % 64, cc = c / 64;
+#pragma unroll
+            for (int e = 0; e < E; ++e) sXT[(cc * E + e) * LDT + row] = rq[u].e[e];
+        }
+        __syncthreads();
+        store_tile_64cols<T>(static_cast<T *>(a.QT) + blk * (DK * 64), sXT, LDT, DK, tid);
+    }
 }
 
 template <typename T, int DK, int DV>
-hipError_t launch_intra_t(const Dims &d, bool bwd, const IntraArgs &a, hipStream_t s) {
+hipError_t launch_intra_t(const Dims &d, int mode, const IntraArgs &a, hipStream_t s) {
     dim3 grid(d.N, d.BH), block(kThreads);
-    if (bwd) hipLaunchKernelGGL((intra_kernel<T, DK, DV, true>), grid, block, 0, s, d, a);
-    else hipLaunchKernelGGL((intra_kernel<T, DK, DV, false>), grid, block, 0, s, d, a);
+    if (mode == 0) hipLaunchKernelGGL((intra_kernel<T, DK, DV, 0>), grid, block, 0, s, d, a);
+    else if (mode == 1) hipLaunchKernelGGL((intra_kernel<T, DK, DV, 1>), grid, block, 0, s, d, a);
+    else hipLaunchKernelGGL((intra_kernel<T, DK, DV, 2>), grid, block, 0, s, d, a);
     return hipGetLastError();
 }
 
 } // namespace
 
-hipError_t launch_intra(const Dims &d, bool bwd, const IntraArgs &a, hipStream_t s) {
+hipError_t launch_intra(const Dims &d, int mode, const IntraArgs &a, hipStream_t s) {
     const bool f32 = d.dtype == 1;
     if (d.dk == 64 && d.dv == 64)
-        return f32 ? launch_intra_t<float, 64, 64>(d, bwd, a, s) : launch_intra_t<bf16_t, 64, 64>(d, bwd, a, s);
+        return f32 ? launch_intra_t<float, 64, 64>(d, mode, a, s) : launch_intra_t<bf16_t, 64, 64>(d, mode, a, s);
     if (d.dk == 128 && d.dv == 128)
-        return f32 ? launch_intra_t<float, 128, 128>(d, bwd, a, s) : launch_intra_t<bf16_t, 128, 128>(d, bwd, a, s);
+        return f32 ? launch_intra_t<float, 128, 128>(d, mode, a, s) : launch_intra_t<bf16_t, 128, 128>(d, mode, a, s);
     return hipErrorInvalidValue;
 }
 

@@ -81,7 +81,8 @@ struct RecurrentArgs {
     void *o;
 };
 
-hipError_t launch_intra(const Dims &d, bool bwd, const IntraArgs &a, hipStream_t s);
+// mode 0: forward operands, 1: reverse-pass operands, 2: both
+hipError_t launch_intra(const Dims &d, int mode, const IntraArgs &a, hipStream_t s);
 hipError_t launch_scan_fwd(const Dims &d, const ScanFwdArgs &a, hipStream_t s);
 hipError_t launch_rebuild(const Dims &d, const RebuildArgs &a, hipStream_t s);
 hipError_t launch_scan_bwd(const Dims &d, const ScanBwdArgs &a, hipStream_t s);

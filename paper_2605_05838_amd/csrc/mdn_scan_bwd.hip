@@ -17,6 +17,8 @@
 #include "mdn_device.h"
 #include "mdn_kernels.h"
 
+#include <stdlib.h>
+
 namespace mdn {
 
 namespace {
@@ -231,7 +233,9 @@ hipError_t launch_t(const Dims &d, const ScanBwdArgs &a, hipStream_t s) {
 // 32 dv columns per workgroup unless that leaves most of the 256 CUs without a workgroup
 // (fp32 storage at d = 128 always takes 16: the prefetched fragments of 32 columns do not fit the registers)
 template <typename T, int DK, int DV> hipError_t pick_dvb(const Dims &d, const ScanBwdArgs &a, hipStream_t s) {
-    if (d.BH * (DV / 32) < 192 || (sizeof(T) == 4 && DK == 128)) return launch_t<T, DK, DV, 16>(d, a, s);
+    static const char *force = getenv("MDN_DVB"); // tuning override: 16 or 32
+    const bool f16 = force && force[0] == '1', f32c = force && force[0] == '3';
+    if (!f32c && (f16 || d.BH * (DV / 32) < 192 || (sizeof(T) == 4 && DK == 128))) return launch_t<T, DK, DV, 16>(d, a, s);
     return launch_t<T, DK, DV, 32>(d, a, s);
 }
 

@@ -50,6 +50,7 @@ def test_workspace_query_validates_shapes():
     assert lib.mdn_workspace_bytes(None, 0, ctypes.byref(n)) == -1
     assert lib.mdn_saved_states_bytes(ctypes.byref(shape()), ctypes.byref(n)) == 0
     assert n.value == 2 * 3 * 2 * 2 * 128 * 128 * 2
+    assert lib.mdn_saved_operands_bytes(ctypes.byref(shape()), ctypes.byref(n)) == 0 and n.value > 0
     # fp32 storage doubles every stored intermediate except the fp32 coefficient block
     assert binding.workspace_bytes(shape(dtype=1), 0) > 1.9 * fwd - 4 * 6 * 64 * 2 * 3 * 2
 
@@ -58,14 +59,15 @@ def test_entry_points_reject_null_and_misaligned_pointers_before_touching_a_devi
     lib = binding.load_library()
     s = shape()
     null = [None] * 17
-    assert lib.mdn_chunk_fwd(ctypes.byref(s), *null[:14], None, 0, None) == -1
+    assert lib.mdn_chunk_fwd(ctypes.byref(s), *null[:15], None, 0, None) == -1
     assert lib.mdn_recurrent_step(ctypes.byref(s), *[None] * 10, None) == -1
     good = ctypes.c_void_p(4096)
     bad = ctypes.c_void_p(4098)
-    args = [good, good, good, good, good, good, None, None, None, bad, None, None, None, None, good, 1 << 40, None]
+    args = [good, good, good, good, good, good, None, None, None, bad, None, None, None, None, None, good, 1 << 40,
+            None]
     assert lib.mdn_chunk_fwd(ctypes.byref(s), *args) == -5
     args[9] = good
-    args[15] = 16
+    args[16] = 16
     assert lib.mdn_chunk_fwd(ctypes.byref(s), *args) == -4
 
 

@@ -13,24 +13,25 @@ TOL = {"f32": 1e-4, "bf16": 2e-2}
 GRADS = ("dq", "dk", "dv", "dalpha", "dbeta", "dmu", "deta", "dS0", "dM0")
 
 
-def run_fwd_bwd(w, t, dS_final=None, dM_final=None, save_states=False):
+def run_fwd_bwd(w, t, dS_final=None, dM_final=None, save_states=False, save_operands=False):
     f = binding.mdn_chunk_fwd(t["q"], t["k"], t["v"], t["beta"], t["alpha"], t["mu"], eta=t["eta"], S0=t["S0"],
-                              M0=t["M0"], scale=w.scale, save_vt=True, save_states=save_states)
+                              M0=t["M0"], scale=w.scale, save_vt=True, save_states=save_states,
+                              save_operands=save_operands)
     g = binding.mdn_chunk_bwd(t["q"], t["k"], t["v"], t["beta"], t["alpha"], t["mu"], f["vt"], t["dO"], eta=t["eta"],
-                              S0=t["S0"], M0=t["M0"], states=f["states"], dS_final=dS_final, dM_final=dM_final,
-                              scale=w.scale, want_deta=True)
+                              S0=t["S0"], M0=t["M0"], states=f["states"], operands=f["operands"], dS_final=dS_final,
+                              dM_final=dM_final, scale=w.scale, want_deta=True)
     torch.cuda.synchronize()
     return f, g
 
 
-def check_bwd(w, pairs=None, final_adjoints=False, save_states=False):
+def check_bwd(w, pairs=None, final_adjoints=False, save_states=False, save_operands=False):
     t = to_dev(w)
     dSf = dMf = None
     if final_adjoints:
         gen = torch.Generator(device="cpu").manual_seed(99)
         dSf = torch.randn((w.B, w.H, w.dk, w.dv), generator=gen).cuda()
         dMf = torch.randn((w.B, w.H, w.dk, w.dv), generator=gen).cuda()
-    f, g = run_fwd_bwd(w, t, dSf, dMf, save_states)
+    f, g = run_fwd_bwd(w, t, dSf, dMf, save_states, save_operands)
     if pairs is None:
         pairs = [(b, h) for b in range(w.B) for h in range(w.H)]
     a = select_pairs(w, pairs)
@@ -69,6 +70,19 @@ def test_backward_with_states_saved_by_the_forward_equals_reconstruction():
     for name in GRADS:
         assert torch.equal(g1[name], g2[name]), name      # the rebuilt states are bit-identical
     check_bwd(w, save_states=True)
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64), ("bf16", 64), ("f32", 128)])
+def test_backward_with_operands_kept_by_the_forward_equals_recomputation(dtype, d):
+    w = synth.custom(B=1, T=192, H=2, dk=d, dv=d, dtype=dtype, seed=35, backward=True, s0_std=0.1, with_eta=True)
+    t = to_dev(w)
+    f1, g1 = run_fwd_bwd(w, t)
+    f2, g2 = run_fwd_bwd(w, t, save_states=True, save_operands=True)
+    for name in ("o", "S", "M", "vt"):
+        assert torch.equal(f1[name], f2[name]), name
+    for name in GRADS:
+        assert torch.equal(g1[name], g2[name]), name      # same operands, same arithmetic: bit-identical
+    check_bwd(w, save_states=True, save_operands=True)
 
 
 def test_backward_mu_zero_and_beta_zero_f32():
