@@ -41,7 +41,7 @@ template <typename T, int DK, int MV> struct ChunkOps {
     float aC, bC, mC;
 };
 
-template <typename T, int DK, int DV, int DVB, bool REBUILD>
+template <typename T, int DK, int DV, int DVB, bool REBUILD, bool NO_STAGE1 = false>
 __device__ __forceinline__ void fetch_chunk(ChunkOps<T, DK, DVB / 16> &c, const Dims &d, const ScanFwdArgs &a,
                                             int bh, int b, int h, int n, int dv0) {
     typedef Op<T> O;
@@ -71,8 +71,10 @@ __device__ __forceinline__ void fetch_chunk(ChunkOps<T, DK, DVB / 16> &c, const 
         const T *Qg = static_cast<const T *>(a.q) + tok * DK + kg * O::EPL;
 #pragma unroll
         for (int s = 0; s < CO::KS; ++s) {
-            c.y[s] = O::load(Yg + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL));
-            c.z[s] = O::load(Zg + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL));
+            if (!NO_STAGE1) {
+                c.y[s] = O::load(Yg + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL));
+                c.z[s] = O::load(Zg + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL));
+            }
             c.q[s] = O::load(Qg + s * O::KSTEP);
         }
         const T *Bg = static_cast<const T *>(a.Bm) + blk * 4096;
@@ -257,10 +259,198 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
     }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// bf16 forward scan with loader waves.  Issuing a chunk's fragment loads costs the issuing wave about as
+// long as the chunk's MFMA work (the CU's vector-memory path moves roughly 30 bytes per clock), and a wave
+// cannot compute while it is stuck issuing.  So the workgroup gets 4 extra waves that do nothing but
+// feed: loader wave c copies the -Y and Z fragments of compute wave c from HBM straight into LDS
+// (global_load_lds, one 16-byte slot per lane: slot = lane, so the compute lane later reads back
+// exactly its own fragment, conflict-free), TWO chunks ahead through a ring of three buffers, never
+// draining its queue (it waits with vmcnt(NF) only for the older of its two bursts).  The compute waves
+// keep fetching the rest (Q, K^T, Bm rows, U, coefficients) into registers one chunk ahead.
+// Same arithmetic, same order, as scan_fwd_kernel: the results are bit-identical.
+template <int DK, int DV, int DVB>
+__global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a) {
+    typedef bf16_t T;
+    typedef Op<T> O;
+    typedef ChunkOps<T, DK, DVB / 16> CO;
+    constexpr int MV = DVB / 16, ND = DK / 64, G = DV / DVB, KS = CO::KS, NF = 2 * KS, NBUF = 3;
+    constexpr int LDST = 2 * DK + O::PAD, LDV = 64 + O::PAD;
+    __shared__ __align__(16) T sSt[DVB * LDST];
+    __shared__ __align__(16) T sV0[DVB * LDV];
+    __shared__ __align__(16) T sVg[DVB * LDV];
+    __shared__ __align__(16) T sVr[DVB * LDV];
+    __shared__ __align__(16) T sF[NBUF][4][NF][64 * O::EPL]; // [buffer][compute wave][fragment][lane slot]
+
+    int bh, blkv;
+    xcd_map(blockIdx.x, G, bh, blkv);
+    if (bh >= d.BH) return;
+    const int b = bh / d.H, h = bh % d.H, dv0 = blkv * DVB;
+    const int lane = lane_id(), wv = wave_id(), r = lane & 15, kg = lane >> 4;
+
+    if (wv >= 4) {
+        // ---------------- loader waves
+        const int cw = wv - 4, i = cw * 16 + r;
+        auto issue = [&](int n, int buf) {
+            const size_t blk = (size_t)bh * d.N + n;
+            const T *Yg = static_cast<const T *>(a.nY) + blk * (64 * DK);
+            const T *Zg = static_cast<const T *>(a.Z) + blk * (64 * DK);
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                __builtin_amdgcn_global_load_lds(Yg + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL),
+                                                 (__attribute__((address_space(3))) void *)&sF[buf][cw][s][0], 16, 0, 0);
+                __builtin_amdgcn_global_load_lds(Zg + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL),
+                                                 (__attribute__((address_space(3))) void *)&sF[buf][cw][KS + s][0], 16, 0, 0);
+            }
+        };
+        // two chunks ahead: while chunk n computes, chunk n+1 is complete or landing and chunk n+2 is issued
+        issue(0, 0);
+        issue(d.N > 1 ? 1 : 0, 1);
+        __builtin_amdgcn_s_waitcnt(0x0F70 | NF); // vmcnt(NF): chunk 0 landed, chunk 1 may still be in flight
+        __builtin_amdgcn_s_barrier();
+        for (int n = 0; n < d.N; ++n) {
+            issue((n + 2 < d.N) ? n + 2 : d.N - 1, (n + 2) % NBUF);
+            __builtin_amdgcn_s_barrier();            // barrier 1 of the chunk
+            __builtin_amdgcn_s_waitcnt(0x0F70 | NF); // vmcnt(NF): chunk n+1 landed
+            __builtin_amdgcn_s_barrier();            // barrier 2
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70); // drain
+        return;
+    }
+
+    // ---------------- compute waves
+    const int w = wv, i = w * 16 + r;
+    CO cur;
+    fetch_chunk<T, DK, DV, DVB, false, true>(cur, d, a, bh, b, h, 0, dv0);
+
+    f32x4 accS[MV][ND], accM[MV][ND];
+#pragma unroll
+    for (int mv = 0; mv < MV; ++mv)
+#pragma unroll
+        for (int nd = 0; nd < ND; ++nd) {
+            const size_t g = ((size_t)bh * DK + (w * ND + nd) * 16 + r) * DV + dv0 + mv * 16 + kg * 4;
+            accS[mv][nd] = a.S0 ? *reinterpret_cast<const f32x4 *>(a.S0 + g) : f32x4{0.f, 0.f, 0.f, 0.f};
+            accM[mv][nd] = a.M0 ? *reinterpret_cast<const f32x4 *>(a.M0 + g) : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+    publish_state<T, DK, MV>(sSt, LDST, accS, accM);
+    __syncthreads();
+
+    for (int n = 0; n < d.N; ++n) {
+        const size_t blk = (size_t)bh * d.N + n;
+        const size_t tok = ((size_t)b * d.T + (size_t)n * 64 + i) * d.H + h;
+        CO nxt;
+        fetch_chunk<T, DK, DV, DVB, false, true>(nxt, d, a, bh, b, h, (n + 1 < d.N) ? n + 1 : n, dv0);
+
+        if (a.states_saved) {
+            T *st = static_cast<T *>(a.states_saved) + blk * (2 * DK * DV);
+#pragma unroll
+            for (int mv = 0; mv < MV; ++mv)
+#pragma unroll
+                for (int nd = 0; nd < ND; ++nd) {
+                    const size_t off = vblk(DK, (w * ND + nd) * 16 + r, dv0 + mv * 16 + kg * 4);
+                    store4(st + off, accS[mv][nd]);
+                    store4(st + DK * DV + off, accM[mv][nd]);
+                }
+        }
+
+        // stage 1
+        f32x4 accO[MV], vt[MV], accV[MV], accOS[MV], accOM[MV];
+#pragma unroll
+        for (int mv = 0; mv < MV; ++mv) accV[mv] = cur.u[mv];
+        zero_acc(accOS);
+        zero_acc(accOM);
+        const T *sp = sSt + r * LDST + kg * O::EPL;
+        const T *fp = &sF[n % NBUF][w][0][lane * O::EPL];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const typename O::Frag fy = O::load(fp + s * (64 * O::EPL));
+            const typename O::Frag fz = O::load(fp + (KS + s) * (64 * O::EPL));
+            const typename O::Frag fq = cur.q[s];
+#pragma unroll
+            for (int mv = 0; mv < MV; ++mv) {
+                const typename O::Frag fs = O::load(sp + mv * 16 * LDST + s * O::KSTEP);
+                const typename O::Frag fm = O::load(sp + mv * 16 * LDST + DK + s * O::KSTEP);
+                accV[mv] = O::mma(fs, fy, accV[mv]);
+                accOS[mv] = O::mma(fs, fq, accOS[mv]);
+                accV[mv] = O::mma(fm, fz, accV[mv]);
+                accOM[mv] = O::mma(fm, fq, accOM[mv]);
+            }
+        }
+#pragma unroll
+        for (int mv = 0; mv < MV; ++mv) {
+            accO[mv] = cur.sa * accOS[mv] - cur.sb * accOM[mv];
+#pragma unroll
+            for (int x = 0; x < 4; ++x) vt[mv][x] = rounded<T>(accV[mv][x]);
+        }
+        if (a.vt_saved) {
+            T *vs = static_cast<T *>(a.vt_saved) + tok * DV + dv0 + kg * 4;
+#pragma unroll
+            for (int mv = 0; mv < MV; ++mv) store4(vs + mv * 16, vt[mv]);
+        }
+#pragma unroll
+        for (int mv = 0; mv < MV; ++mv)
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                const int dv = mv * 16 + kg * 4 + x;
+                sV0[dv * LDV + i] = from_f32<T>(vt[mv][x]);
+                sVg[dv * LDV + i] = from_f32<T>(cur.gc * vt[mv][x]);
+                sVr[dv * LDV + i] = from_f32<T>(-cur.rc * vt[mv][x]);
+            }
+        __syncthreads();
+
+        // stage 2
+        const T *v0p = sV0 + r * LDV + kg * O::EPL, *vgp = sVg + r * LDV + kg * O::EPL,
+                *vrp = sVr + r * LDV + kg * O::EPL;
+#pragma unroll
+        for (int mv = 0; mv < MV; ++mv)
+#pragma unroll
+            for (int nd = 0; nd < ND; ++nd) {
+                accS[mv][nd] = cur.aC * accS[mv][nd] - cur.bC * accM[mv][nd];
+                accM[mv][nd] = cur.mC * accM[mv][nd];
+            }
+#pragma unroll
+        for (int s = 0; s < CO::KS2; ++s)
+#pragma unroll
+            for (int mv = 0; mv < MV; ++mv) {
+                const typename O::Frag fg = O::load(vgp + mv * 16 * LDV + s * O::KSTEP);
+                const typename O::Frag fr = O::load(vrp + mv * 16 * LDV + s * O::KSTEP);
+#pragma unroll
+                for (int nd = 0; nd < ND; ++nd) {
+                    accS[mv][nd] = O::mma(fg, cur.kt[nd][s], accS[mv][nd]);
+                    accM[mv][nd] = O::mma(fr, cur.kt[nd][s], accM[mv][nd]);
+                }
+                const typename O::Frag f0 = O::load(v0p + mv * 16 * LDV + s * O::KSTEP);
+                accO[mv] = O::mma(f0, cur.bm[s], accO[mv]);
+            }
+        publish_state<T, DK, MV>(sSt, LDST, accS, accM);
+        T *og = static_cast<T *>(a.o) + tok * DV + dv0 + kg * 4;
+#pragma unroll
+        for (int mv = 0; mv < MV; ++mv) store4(og + mv * 16, accO[mv]);
+        __syncthreads();
+        cur = nxt;
+    }
+#pragma unroll
+    for (int mv = 0; mv < MV; ++mv)
+#pragma unroll
+        for (int nd = 0; nd < ND; ++nd) {
+            const size_t g = ((size_t)bh * DK + (w * ND + nd) * 16 + r) * DV + dv0 + mv * 16 + kg * 4;
+            if (a.S_final) *reinterpret_cast<f32x4 *>(a.S_final + g) = accS[mv][nd];
+            if (a.M_final) *reinterpret_cast<f32x4 *>(a.M_final + g) = accM[mv][nd];
+        }
+}
+
 template <typename T, int DK, int DV, int DVB, bool REBUILD>
 hipError_t launch_scan_t(const Dims &d, const ScanFwdArgs &a, hipStream_t s) {
     constexpr int G = DV / DVB;
     dim3 grid(((d.BH + 7) / 8) * 8 * G), block(kThreads);
+    if constexpr (sizeof(T) == 2 && !REBUILD) {
+        static const char *nows = getenv("MDN_NO_LOADER_WAVES"); // tuning switch
+        if (!nows) {
+            hipLaunchKernelGGL((scan_fwd_ws_kernel<DK, DV, DVB>), grid, dim3(512), 0, s, d, a);
+            return hipGetLastError();
+        }
+    }
     hipLaunchKernelGGL((scan_fwd_kernel<T, DK, DV, DVB, REBUILD>), grid, block, 0, s, d, a);
     return hipGetLastError();
 }
