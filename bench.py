@@ -36,6 +36,37 @@ def flops_per_tokhd(C, dk, dv):
     }
 
 
+def bytes_per_tokhd(C, dk, dv, es, keep):
+    """Bytes per token per head that each kernel must move once in this decomposition (es = bytes of a
+    stored element; gates and coefficients are fp32).  `keep`: the training forward also writes the
+    reverse pass's operands and the chunk-start states."""
+    coef = 6 * 4
+    fwd_ops = (dk + dv + 2 * dk + C) * es + coef          # K^T, U, -Y, Z, Bm, coefficient block
+    rev_ops = (4 * dk + 2 * C) * es + coef                # K^T, Q^T, -Y^T, Z^T, Bm^T, T^T, coefficient block
+    states = 2 * dk * dv * es // C                        # S, M of one chunk, per token
+    return {
+        "intra_fwd": (2 * dk + dv) * es + 16 + (fwd_ops + rev_ops - dk * es - coef if keep else fwd_ops),
+        "scan_fwd": fwd_ops + dk * es + 2 * dv * es + (states if keep else 0),   # + q; V~ and o out
+        "intra_bwd": 2 * dk * es + 16 + rev_ops,
+        "rebuild": dk * es + dv * es + coef + states,
+        "scan_bwd": rev_ops - dk * es + dk * es + dv * es + dv * es + states,    # ops w/o K^T, + k, dO; dv, dstates out
+        "grad": 2 * dk * es + 3 * dv * es + 2 * dk * es + 2 * states + 16 + 2 * dk * es + 12,
+    }
+
+
+def read_traffic(path):
+    """Measured HBM bytes per launch {kernel: fetch + write}, from the `traffic` lines of a profiles/ summary."""
+    out = {}
+    try:
+        for line in open(path):
+            p = line.split()
+            if len(p) == 4 and p[0] == "traffic":
+                out[p[1]] = int(p[2]) + int(p[3])
+    except OSError:
+        pass
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -48,6 +79,9 @@ def main():
                          "states and recomputes its chunk-local operands (default: the forward keeps both)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket kernels with HIP events")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="after the timed region, also run one plain device copy of this many MiB (the known-size "
+                         "kernel that the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled by)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the path has no multi-GPU part); use --gpus 1",
@@ -98,6 +132,12 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     kern = {} if args.no_kernel_events else binding.profile_end()
+    if args.calibration_copy_mib:
+        src = torch.empty(args.calibration_copy_mib << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
     ms_per_step = wall * 1e3 / args.steps
     tokens_per_s = w.tokens * args.steps / wall
 
@@ -112,11 +152,20 @@ def main():
             kernels[name] = {"avg_ms": round(avg, 4), "launches": cnt,
                              "gflop_per_launch": round(fl[name] * tokhd / 1e9, 3),
                              "tflops": round(fl[name] * tokhd / (avg * 1e-3) / 1e12, 2)}
-    roofline = None
+    roofline = roofline_hbm = None
     if kernels:
         dom = max(kernels, key=lambda k: kernels[k]["avg_ms"])
+        # measured HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled): only known for the
+        # default run of config 3, from the committed counter summary
+        traffic = None
+        if args.config == 3 and keep:
+            traffic = read_traffic(os.path.join(ROOT, "profiles", "step_c3_hbm_traffic.md")).get(dom)
         roofline = {"kernel": dom, "bound": "mfma", "achieved": kernels[dom]["tflops"], "peak": peak,
-                    "unit": "TFLOP/s", "frac": round(kernels[dom]["tflops"] / peak, 5), "traffic": None}
+                    "unit": "TFLOP/s", "frac": round(kernels[dom]["tflops"] / peak, 5), "traffic": traffic}
+        nbytes = bytes_per_tokhd(w.C, w.dk, w.dv, 2 if w.dtype == "bf16" else 4, keep)[dom] * tokhd
+        gbs = nbytes / (kernels[dom]["avg_ms"] * 1e-3) / 1e9
+        roofline_hbm = {"kernel": dom, "bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                        "frac": round(gbs / PEAK_HBM_GBS, 5), "traffic": traffic}
     total_flops = sum(fl[k] for k in (("intra_fwd", "scan_fwd") + (("intra_bwd", "rebuild", "scan_bwd", "grad")
                                                                    if do_bwd else ()))) * tokhd
     path_tflops = total_flops / (ms_per_step * 1e-3) / 1e12
@@ -148,7 +197,7 @@ def main():
                    "pass": "fwd+bwd" if do_bwd else "fwd", "forward_keeps_states_and_operands": bool(keep)},
         "path_tflops": round(path_tflops, 2), "path_frac_of_mfma_peak": round(path_tflops / peak, 5),
         "gpu_event_ms_per_step": round(ev0.elapsed_time(ev1) / args.steps, 4),
-        "roofline": roofline, "kernels": kernels, "cpu_baseline": cpu,
+        "roofline": roofline, "roofline_hbm": roofline_hbm, "kernels": kernels, "cpu_baseline": cpu,
     }
     print(json.dumps(line))
 
