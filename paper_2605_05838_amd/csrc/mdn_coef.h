@@ -77,22 +77,36 @@ __device__ __forceinline__ void coef_column_scan(float al, float be, float mu, f
 // ---- reverse of the column scans (adjoint): lane j owns column j.  With D_ij the direct adjoint of
 //      Gamma_ij (sD1[i][j] + sD2[i+1][j], plus dgc_j in row 63) and drc_j the direct adjoint of Rho_63,j:
 //        G_ij = D_ij + alpha_{i+1} G_{i+1,j}            R_ij = [i = 63] drc_j + beta_i G_ij + mu_{i+1} R_{i+1,j}
-//      for i = 63 .. j.  Writes sGa[i][j] = G_ij, sRa[i][j] = R_ij (entries with i < j are not written).
+//      for i = 63 .. j.  Writes sGa[i][j] = G_ij, sRa[i][j] = R_ij (zero for i < j).
 __device__ __forceinline__ void coef_column_scan_reverse(float al, float be, float mu, const float *sD1,
                                                          const float *sD2, float dgc, float drc, float *sGa,
                                                          float *sRa, int ldg) {
     const int j = lane_id();
     float cg = 0.f, cr = 0.f; // alpha_{i+1} G_{i+1,j}, mu_{i+1} R_{i+1,j}
+    // 16 rows at a time: all direct adjoints of the block are read before its dependent chain starts
+    // (every entry of sD1 / sD2 is defined, zero above the diagonal), so no LDS wait sits on the chain
 #pragma unroll
-    for (int i = 63; i >= 0; --i) {
-        const float a_i = lane_bcast(al, i), b_i = lane_bcast(be, i), m_i = lane_bcast(mu, i);
-        const float dir = sD1[i * ldg + j] + sD2[(i + 1) * ldg + j];
-        const float G = (i >= j) ? dir + (i == 63 ? dgc : 0.f) + cg : 0.f;
-        const float R = (i >= j) ? (i == 63 ? drc : 0.f) + b_i * G + cr : 0.f;
-        sGa[i * ldg + j] = G;
-        sRa[i * ldg + j] = R;
-        cg = a_i * G;
-        cr = m_i * R;
+    for (int i0 = 48; i0 >= 0; i0 -= 16) {
+        float dir[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) dir[u] = sD1[(i0 + u) * ldg + j] + sD2[(i0 + u + 1) * ldg + j];
+#pragma unroll
+        for (int u = 15; u >= 0; --u) {
+            const int i = i0 + u;
+            const float a_i = lane_bcast(al, i), b_i = lane_bcast(be, i), m_i = lane_bcast(mu, i);
+            float G = dir[u] + cg, R = cr;
+            if (i == 63) {
+                G += dgc;
+                R += drc;
+            }
+            R += b_i * G;
+            G = (i >= j) ? G : 0.f;
+            R = (i >= j) ? R : 0.f;
+            sGa[i * ldg + j] = G;
+            sRa[i * ldg + j] = R;
+            cg = a_i * G;
+            cr = m_i * R;
+        }
     }
 }
 

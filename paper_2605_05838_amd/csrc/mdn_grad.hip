@@ -17,14 +17,22 @@
 //   a_i = alpha_i a_{i-1}, m_i = mu_i m_{i-1}, Rho_ij = mu_i Rho_{i-1,j},
 //   b_i = alpha_i b_{i-1} + beta_i m_i, Gamma_ij = alpha_i Gamma_{i-1,j} + beta_i Rho_ij.
 //
-// One workgroup (8 waves) per (chunk, batch*head).  A wave owns 16 tokens and half of the dk (or j)
-// tiles of every product, and every product is formed transposed, tokens as the MFMA column index: the operands all waves share
-// (V~, K, K^T, Q^T, S, M, dS', dM') are the A operands and go through one LDS staging buffer,
-// tile after tile, each fetched from HBM with coalesced 16-byte loads while the previous tile is
-// being consumed; the wave's own rows of dO, dR, V~, q, k are B fragments held in registers.
-// An accumulator lane then holds 4 consecutive dk of one token: dq, dk leave as 8-byte stores and
-// the row dots against q, k need two shuffles.  (fp32 storage does not fit the staging buffer in
-// LDS: it reads the shared operands straight from HBM/L2 with the same code.)
+// One workgroup (8 waves) per (chunk, batch*head).  Every product is formed transposed (dk or j as the
+// MFMA row index, tokens as the column index), so an accumulator lane holds 4 consecutive dk of one
+// token: dq, dk leave as 8-byte stores and the row dots against q, k need two shuffles.
+//   * 64x64 products (phase A): wave = (token tile, half of the j tiles); A operands V~, K from LDS.
+//   * everything with a dk row index (phases B-F): wave = (dk tile, token group).  Its A operands are
+//     the wave's own 16 rows of K^T, Q^T, S, M, dS', dM': nobody else needs them, so they go from HBM
+//     straight into fragment registers, all in flight long before their use (no LDS copy, no barrier
+//     between the four state products).  The B operands are token rows that every wave needs: W1, W2
+//     (built in phase A) and the natural-layout tiles of dO, dR, V~ in LDS.
+//   * the token tiles V~, k, dO, dR go HBM -> LDS without passing through registers (global_load_lds,
+//     16 bytes per lane into consecutive LDS slots).  Rows are stored unpadded; to keep the fragment
+//     reads (16 rows x one 16-byte piece) off each other's banks, piece c of row i sits at position
+//     c ^ (i mod 16): the permutation is applied on the global side, where each lane is free to fetch
+//     any address.
+// (fp32 storage does not fit the token tiles in LDS: it reads them from HBM/L2 with the same code, and
+// keeps only two state tiles in registers at a time.)
 #include "mdn_coef.h"
 #include "mdn_device.h"
 #include "mdn_kernels.h"
@@ -36,7 +44,10 @@ namespace mdn {
 namespace {
 
 constexpr int LDG = 65; // row stride of the fp32 64x64 coefficient matrices in LDS
-constexpr int GT = 512;  // threads per workgroup: 8 waves = 4 token tiles x 2 halves of the dk (or j) tiles
+constexpr int GT = 512; // threads per workgroup: 8 waves
+
+// row-dot partial sums, one [dk tiles][64] block each
+enum { P_DA = 0, P_DB, P_DAM, P_DBM, P_DGC, P_DRC, P_DALK, P_DETK, P_COUNT };
 
 // sum over the 4 lanes (kg = 0..3) that hold the same token column r
 __device__ __forceinline__ float reduce_kg(float v) {
@@ -45,31 +56,45 @@ __device__ __forceinline__ float reduce_kg(float v) {
     return v;
 }
 
-// sum over dk of t^T[dk][i] * X[i][dk] for this lane's token; t tile mt holds dk = mt*16 + kg*4 + x
-template <int NK> __device__ __forceinline__ float coldot(const f32x4 (&t)[NK], const f32x4 (&xv)[NK]) {
-    float s = 0.f;
-#pragma unroll
-    for (int mt = 0; mt < NK; ++mt)
-#pragma unroll
-        for (int x = 0; x < 4; ++x) s += t[mt][x] * xv[mt][x];
-    return reduce_kg(s);
+// sum over the 16 dk of one accumulator tile of t^T[dk][i] * X[i][dk] for this lane's token
+__device__ __forceinline__ float coldot(f32x4 t, f32x4 xv) {
+    return reduce_kg(t[0] * xv[0] + t[1] * xv[1] + t[2] * xv[2] + t[3] * xv[3]);
 }
+
+// one natural-layout [64][D] token tile, HBM -> LDS without registers: the 16-byte slot (row, position p)
+// receives piece p ^ (row & XM) of that row.  Issued by 4 waves (lw = 0..3), NDMA instructions of 64
+// consecutive slots each.
+template <typename T, int D>
+__device__ __forceinline__ void dma_token_tile(T *ldst, const T *src, size_t rs, int lw, int lane) {
+    constexpr int E = Op<T>::EPL, CPR = D / E, XM = (CPR < 16 ? CPR : 16) - 1, NDMA = CPR / 4;
+#pragma unroll
+    for (int u = 0; u < NDMA; ++u) {
+        const int blk64 = u * 4 + lw, sl = blk64 * 64 + lane, row = sl / CPR, pc = (sl % CPR) ^ (row & XM);
+        __builtin_amdgcn_global_load_lds(src + (size_t)row * rs + pc * E,
+                                         (__attribute__((address_space(3))) void *)(ldst + blk64 * 64 * E), 16, 0, 0);
+    }
+}
+
+// keeps the compiler from moving instructions across this point (used to stop the fragment loads of
+// later contraction steps from piling up in registers)
+__device__ __forceinline__ void sched_fence() { __builtin_amdgcn_sched_barrier(0); }
 
 template <typename T, int DK, int DV, bool STAGED>
 __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     typedef Op<T> O;
     typedef typename O::Frag Frag;
     constexpr int E = O::EPL;
-    constexpr int LDW = 64 + O::PAD, LDNV = DV + O::PAD, LDNK = DK + O::PAD;
-    constexpr int NK = DK / 16, KSV = DV / O::KSTEP, KSK = DK / O::KSTEP, KS2 = 64 / O::KSTEP;
-    constexpr int NAT_ELEMS = 64 * LDNV + 64 * LDNK, BLK_ELEMS = 2 * DK * 64, ST_ELEMS = DK * DV;
-    constexpr int SB_ELEMS0 = NAT_ELEMS > BLK_ELEMS ? NAT_ELEMS : BLK_ELEMS;
-    constexpr int SB_ELEMS = STAGED ? (SB_ELEMS0 > ST_ELEMS ? SB_ELEMS0 : ST_ELEMS) : 8;
-    // 16-byte vectors per thread of each staged tile
-    constexpr int NV_V = 64 * DV / E / GT, NV_K = 64 * DK / E / GT, NV_B = DK * 64 / E / GT, NV_S = DK * DV / E / GT;
-    constexpr int NH = NK / 2; // dk tiles per wave
-    constexpr int NREG0 = (NV_V + NV_K) > 2 * NV_B ? (NV_V + NV_K) : 2 * NV_B;
-    constexpr int NREG = NREG0 > NV_S ? NREG0 : NV_S;
+    constexpr int LDW = 64 + O::PAD;
+    static_assert(DK == DV, "token tiles share one row length");
+    constexpr int D = DK, CPR = D / E;                 // 16-byte pieces per token row
+    constexpr int XM = (CPR < 16 ? CPR : 16) - 1;      // piece c of row i is stored at c ^ (i & XM)
+    constexpr int CPS = O::KSTEP / E;                  // pieces per contraction step
+    constexpr int KSV = DV / O::KSTEP, KSK = DK / O::KSTEP, KS2 = 64 / O::KSTEP;
+    constexpr int NKW = DK / 16;  // dk tiles = waves along dk
+    constexpr int TG = 8 / NKW;   // token groups
+    constexpr int TT = 4 / TG;    // token tiles per wave
+    constexpr bool DEEP = STAGED; // all four state tiles in registers at once
+    static_assert(NKW * TG == 8 && TT * TG == 4, "8 waves = dk tiles x token groups");
 
     __shared__ float sG[64 * LDG];     // Gamma
     __shared__ float sRho[64 * LDG];   // Rho
@@ -80,20 +105,27 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     T *sW2e = sW + 64 * LDW;      // W2 . eta_j         [i][j]
     T *sW1T = sW + 2 * 64 * LDW;  // scale W1^T         [j][i]
     T *sW2T = sW + 3 * 64 * LDW;  // (W2 . alpha_i)^T   [j][i]
-    // after the W products: accumulated adjoints of Gamma and Rho
+    // after the W products the space holds the row-dot partial sums, then the accumulated adjoints of Gamma, Rho
+    float *spart = reinterpret_cast<float *>(sW);
     float *sGa = reinterpret_cast<float *>(sW), *sRa = sGa + 64 * LDG;
     static_assert(sizeof(T) * 4 * 64 * LDW >= sizeof(float) * 2 * 64 * LDG, "adjoint matrices do not fit the W space");
-    __shared__ __align__(16) T sB[SB_ELEMS];   // staging buffer of the shared operands
+    static_assert(sizeof(T) * 4 * 64 * LDW >= sizeof(float) * P_COUNT * NKW * 64, "partial sums do not fit the W space");
+    // token tiles [64][D] (pieces permuted, see above): V~, dO, dR; k sits in the W space until the W matrices are written
+    __shared__ __align__(16) T sVt[STAGED ? 64 * D : 8];
+    __shared__ __align__(16) T sDO[STAGED ? 64 * D : 8];
+    __shared__ __align__(16) T sDR[STAGED ? 64 * D : 8];
+    T *sK = sW;
+    static_assert(4 * LDW >= D, "k tile does not fit the W space");
     __shared__ float s_al[64], s_et[64], s_a[64], s_b[64];
-    // row dots come in two halves (one per dk half): [hf][token]
-    __shared__ float s_da[2][64], s_db[2][64], s_dam[2][64], s_dbm[2][64], s_dgc[2][64], s_drc[2][64], s_dalk[2][64], s_detk[2][64];
     __shared__ float s_gC[64], s_rC[64];
     __shared__ float s_ga[64], s_gb[64], s_gm[64];
     __shared__ float s_red[8][3];
 
-    const int tid = threadIdx.x, lane = lane_id(), w = wave_id(), r = lane & 15, kg = lane >> 4;
-    const int wt = w & 3, hf = w >> 2;
-    const int i = wt * 16 + r; // this lane's token (MFMA column)
+    const int tid = threadIdx.x, lane = lane_id(), r = lane & 15, kg = lane >> 4;
+    const int w = __builtin_amdgcn_readfirstlane(wave_id()); // wave-uniform by construction: lets branches on it be scalar
+    const int wt = w & 3, hf = w >> 2;    // phase A: token tile, half of the j tiles
+    const int kt = w % NKW, tg = w / NKW; // phases B-F: dk tile, token group
+    const int i = wt * 16 + r;            // this lane's token (MFMA column) in phase A
     const int n = blockIdx.x, bh = blockIdx.y, b = bh / d.H, h = bh % d.H;
     const size_t tok0 = ((size_t)b * d.T + (size_t)n * 64) * d.H + h;
     const size_t blk = (size_t)bh * d.N + n;
@@ -108,87 +140,45 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     const T *Sg = static_cast<const T *>(a.states) + blk * (2 * DK * DV), *Mg = Sg + DK * DV;
     const T *dSg = static_cast<const T *>(a.dstates) + blk * (2 * DK * DV), *dMg = dSg + DK * DV;
 
-    // ---- cooperative tile movement: HBM -> registers (issue), registers -> LDS (commit)
-    Vec16<T> P[NREG], Q[NREG];
-    auto issue_natural = [&](Vec16<T> *dst, const T *src, size_t rs, auto D_, auto NV_) {
-        // [64][D] rows of the chunk; D/E vectors per row
-        constexpr int cpr = decltype(D_)::value / E;
-#pragma unroll
-        for (int u = 0; u < decltype(NV_)::value; ++u) {
-            const int c = tid + u * GT, row = c / cpr, cc = c % cpr;
-            dst[u] = *reinterpret_cast<const Vec16<T> *>(src + row * rs + cc * E);
-        }
+    // fragment of row `row`, contraction step st of a token tile (in LDS, or in global memory with row stride ld)
+    auto tfrag = [&](const T *tile, int ld, int row, int st) -> Frag {
+        if (STAGED) return O::load(tile + row * D + (((st * CPS + kg) ^ (row & XM)) * E));
+        return O::load(tile + (size_t)row * ld + st * O::KSTEP + kg * E);
     };
-    auto commit_natural = [&](const Vec16<T> *src, T *dstl, int ld, auto D_, auto NV_) {
-        constexpr int cpr = decltype(D_)::value / E;
+    // this wave's 16 rows (dk tile kt) of a [dk][dv] state tile as A fragments
+    auto load_state = [&](Frag(&f)[KSV], const T *tile) {
 #pragma unroll
-        for (int u = 0; u < decltype(NV_)::value; ++u) {
-            const int c = tid + u * GT, row = c / cpr, cc = c % cpr;
-            *reinterpret_cast<Vec16<T> *>(dstl + row * ld + cc * E) = src[u];
-        }
+        for (int s = 0; s < KSV; ++s) f[s] = O::load(tile + vblk(DK, kt * 16 + r, s * O::KSTEP + kg * E));
     };
-    auto issue_linear = [&](Vec16<T> *dst, const T *src, auto NV_) {
-#pragma unroll
-        for (int u = 0; u < decltype(NV_)::value; ++u)
-            dst[u] = *reinterpret_cast<const Vec16<T> *>(src + (size_t)(tid + u * GT) * E);
-    };
-    auto commit_linear = [&](const Vec16<T> *src, T *dstl, auto NV_) {
-#pragma unroll
-        for (int u = 0; u < decltype(NV_)::value; ++u)
-            *reinterpret_cast<Vec16<T> *>(dstl + (size_t)(tid + u * GT) * E) = src[u];
-    };
-    typedef std::integral_constant<int, DV> cDV;
-    typedef std::integral_constant<int, DK> cDK;
-    typedef std::integral_constant<int, NV_V> cNV_V;
-    typedef std::integral_constant<int, NV_K> cNV_K;
-    typedef std::integral_constant<int, NV_B> cNV_B;
-    typedef std::integral_constant<int, NV_S> cNV_S;
-    auto dot_regs = [&](const Vec16<T> *x, const Vec16<T> *y) {
+    auto dot_frags = [&](const Frag(&x)[KSV], const Frag(&y)[KSV]) {
         float s = 0.f;
 #pragma unroll
-        for (int u = 0; u < NV_S; ++u)
+        for (int u = 0; u < KSV; ++u)
 #pragma unroll
-            for (int e = 0; e < E; ++e) s += to_f32(x[u].e[e]) * to_f32(y[u].e[e]);
+            for (int e = 0; e < E; ++e) s += to_f32(x[u][e]) * to_f32(y[u][e]);
         return s;
     };
 
-    // ---------------- prologue: first tiles in flight, gates, this wave's own rows
-    if (STAGED) {
-        issue_natural(P, vtg, rsv, cDV{}, cNV_V{});
-        issue_natural(P + NV_V, kgl, rsk, cDK{}, cNV_K{});
-    }
-    // gates of token `lane` (used by wave 0 for the coefficient scans)
+    // ---------------- prologue: gates first, then everything this workgroup will read, in order of use
     const size_t gl = tok0 + (size_t)lane * d.H;
     const float g_al = a.alpha[gl], g_be = a.beta[gl], g_mu = a.mu[gl], g_et = a.eta ? a.eta[gl] : 1.f;
     for (int c = tid; c < LDG; c += GT) sDG2[64 * LDG + c] = 0.f;
-    Frag fdO[KSV], fdR[KSV], fq[KSK], fk[KSK]; // B fragments: row = token i
+    Frag fq[KSK]; // phase A B fragments of q (no LDS copy): row = token i
 #pragma unroll
-    for (int s = 0; s < KSV; ++s) {
-        fdO[s] = O::load(dog + (size_t)i * rsv + s * O::KSTEP + kg * E);
-        fdR[s] = O::load(drg + (size_t)i * rsv + s * O::KSTEP + kg * E);
-    }
+    for (int s = 0; s < KSK; ++s) fq[s] = O::load(qg + (size_t)i * rsk + s * O::KSTEP + kg * E);
+    Frag aK[KS2], aQ[KS2]; // this wave's rows of K^T, Q^T
 #pragma unroll
-    for (int s = 0; s < KSK; ++s) {
-        fq[s] = O::load(qg + (size_t)i * rsk + s * O::KSTEP + kg * E);
-        fk[s] = O::load(kgl + (size_t)i * rsk + s * O::KSTEP + kg * E);
+    for (int s = 0; s < KS2; ++s) {
+        aK[s] = O::load(KTg + kblk<T>(DK, kt * 16 + r, s * O::KSTEP + kg * E));
+        aQ[s] = O::load(QTg + kblk<T>(DK, kt * 16 + r, s * O::KSTEP + kg * E));
     }
-    // k_i and q_i in accumulator layout: element x of tile mt is dk = mt*16 + kg*4 + x
-    f32x4 kv[NH];
-#pragma unroll
-    for (int mt = 0; mt < NH; ++mt) kv[mt] = load4(kgl + (size_t)i * rsk + (hf * NH + mt) * 16 + kg * 4);
-
-    const T *tVt = STAGED ? sB : vtg;
-    const T *tK = STAGED ? sB + 64 * LDNV : kgl;
-    const int ldVt = STAGED ? LDNV : (int)rsv, ldK = STAGED ? LDNK : (int)rsk;
-    if (STAGED) {
-        commit_natural(P, sB, LDNV, cDV{}, cNV_V{});
-        commit_natural(P + NV_V, sB + 64 * LDNV, LDNK, cDK{}, cNV_K{});
-        issue_linear(P, KTg, cNV_B{});
-        issue_linear(P + NV_B, QTg, cNV_B{});
-    }
-    __syncthreads();
+    Frag fS[KSV], fM[KSV], fdS[KSV], fdM[KSV];
+    load_state(fS, Sg);
 
     // ---------------- phase 0: forward coefficients: vectors by wave scans, matrices by a column scan
+    //                  (wave 0, needs only the gates).  Meanwhile waves 4-7 start the token tiles on
+    //                  their way to LDS; wave 0 itself must have no such transfer pending on its path
+    //                  (also not in the compiler's view of it), or its first LDS instruction would wait for it.
     float pa = 0.f, pm = 0.f, pb = 0.f; // a_lane, m_lane, b_lane (wave 0)
     if (w == 0) {
         pa = scan_prod(g_al);
@@ -205,40 +195,62 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
         s_gC[lane] = gC; // Gamma_{C,j}
         s_rC[lane] = rC; // Rho_{C,j}
     }
-    __syncthreads();
+    if (STAGED && w >= 4) {
+        dma_token_tile<T, D>(sVt, vtg, rsv, w - 4, lane);
+        dma_token_tile<T, D>(sK, kgl, rsk, w - 4, lane);
+        dma_token_tile<T, D>(sDO, dog, rsv, w - 4, lane);
+        dma_token_tile<T, D>(sDR, drg, rsv, w - 4, lane);
+    }
+    const T *tVt = STAGED ? sVt : vtg, *tK = STAGED ? sK : kgl, *tDR = STAGED ? sDR : drg, *tDO = STAGED ? sDO : dog;
+    const int ldV = (int)rsv, ldK = (int)rsk; // row strides of the global tiles (fp32 path)
+    __syncthreads(); // token tiles landed, coefficients ready
 
     // ---------------- phase A: the four 64x64 products (transposed: rows j, column i) and the
     //                  masked matrices built from them
+    f32x4 accB[2], accA[2], accQK[2], accKK[2];
+    {
+        Frag fdO[KSV], fdR[KSV], fk[KSK];
+#pragma unroll
+        for (int s = 0; s < KSV; ++s) {
+            fdO[s] = tfrag(tDO, ldV, i, s);
+            fdR[s] = tfrag(tDR, ldV, i, s);
+        }
+#pragma unroll
+        for (int s = 0; s < KSK; ++s) fk[s] = tfrag(tK, ldK, i, s);
+#pragma unroll
+        for (int mh = 0; mh < 2; ++mh) {
+            const int j0 = (hf * 2 + mh) * 16 + r;
+            accB[mh] = accA[mh] = accQK[mh] = accKK[mh] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < KSV; ++s) {
+                const Frag fv = tfrag(tVt, ldV, j0, s);
+                accB[mh] = O::mma(fv, fdO[s], accB[mh]);
+                accA[mh] = O::mma(fv, fdR[s], accA[mh]);
+            }
+#pragma unroll
+            for (int s = 0; s < KSK; ++s) {
+                const Frag fkk = tfrag(tK, ldK, j0, s);
+                accQK[mh] = O::mma(fkk, fq[s], accQK[mh]);
+                accKK[mh] = O::mma(fkk, fk[s], accKK[mh]);
+            }
+        }
+    }
+    if (STAGED) __syncthreads(); // everybody is done with the k tile: the W matrices take its place
     {
         const float al_i = s_al[i];
 #pragma unroll
         for (int mh = 0; mh < 2; ++mh) {
             const int mt = hf * 2 + mh;
-            f32x4 accB = {0.f, 0.f, 0.f, 0.f}, accA = accB, accQK = accB, accKK = accB;
-            const T *vp = tVt + (size_t)(mt * 16 + r) * ldVt + kg * E;
-            const T *kp = tK + (size_t)(mt * 16 + r) * ldK + kg * E;
-#pragma unroll
-            for (int s = 0; s < KSV; ++s) {
-                const Frag fv = O::load(vp + s * O::KSTEP);
-                accB = O::mma(fv, fdO[s], accB);
-                accA = O::mma(fv, fdR[s], accA);
-            }
-#pragma unroll
-            for (int s = 0; s < KSK; ++s) {
-                const Frag fkk = O::load(kp + s * O::KSTEP);
-                accQK = O::mma(fkk, fq[s], accQK);
-                accKK = O::mma(fkk, fk[s], accKK);
-            }
             f32x4 w1e, w2e;
 #pragma unroll
             for (int x = 0; x < 4; ++x) {
                 const int j = mt * 16 + kg * 4 + x;
                 const float gam = sG[i * LDG + j], gprev = (i > 0) ? sG[(i - 1) * LDG + j] : 0.f;
                 const float et = s_et[j];
-                const float dBm = (j <= i) ? accB[x] : 0.f;
-                const float dA = (j < i) ? -accA[x] : 0.f;
-                sDG1[i * LDG + j] = dBm * (d.scale * et * accQK[x]);
-                sDG2[i * LDG + j] = dA * (al_i * et * accKK[x]);
+                const float dBm = (j <= i) ? accB[mh][x] : 0.f;
+                const float dA = (j < i) ? -accA[mh][x] : 0.f;
+                sDG1[i * LDG + j] = dBm * (d.scale * et * accQK[mh][x]);
+                sDG2[i * LDG + j] = dA * (al_i * et * accKK[mh][x]);
                 const float w1 = dBm * gam, w2 = dA * gprev;
                 w1e[x] = w1 * et;
                 w2e[x] = w2 * et;
@@ -250,142 +262,122 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
         }
     }
     __syncthreads();
+    if (DEEP) {
+        load_state(fM, Mg);
+        load_state(fdS, dSg); // dM' follows once S is no longer needed
+    }
+    // k and q of this wave's tokens in accumulator layout: element x is dk = kt*16 + kg*4 + x
+    f32x4 kv[TT], qv[TT];
+#pragma unroll
+    for (int t = 0; t < TT; ++t) {
+        const int it = (tg * TT + t) * 16 + r;
+        kv[t] = load4(kgl + (size_t)it * rsk + kt * 16 + kg * 4);
+        qv[t] = load4(qg + (size_t)it * rsk + kt * 16 + kg * 4);
+    }
 
     // ---------------- phase B: the token-contractions W1 K~, W2 K~, W1^T Q~, W2^T P
-    const T *tKT = STAGED ? sB : KTg, *tQT = STAGED ? sB + DK * 64 : QTg;
-    if (STAGED) {
-        commit_linear(P, sB, cNV_B{});
-        commit_linear(P + NV_B, sB + DK * 64, cNV_B{});
-        issue_linear(Q, Sg, cNV_S{});
-        __syncthreads();
-    }
-    f32x4 accQ[NH], accP[NH], accK[NH]; // dQ~^T, dP^T, dK~^T: [dk tile of this half][token i]
+    f32x4 accQ[TT], accP[TT], accK[TT]; // dQ~^T, dP^T, dK~^T: [dk tile kt][token tile t of this group]
     zero_acc(accQ);
     zero_acc(accP);
     zero_acc(accK);
 #pragma unroll
-    for (int s = 0; s < KS2; ++s) {
-        const Frag b1e = O::load(sW1e + i * LDW + s * O::KSTEP + kg * E);
-        const Frag b2e = O::load(sW2e + i * LDW + s * O::KSTEP + kg * E);
-        const Frag b1t = O::load(sW1T + i * LDW + s * O::KSTEP + kg * E);
-        const Frag b2t = O::load(sW2T + i * LDW + s * O::KSTEP + kg * E);
+    for (int s = 0; s < KS2; ++s)
 #pragma unroll
-        for (int mt = 0; mt < NH; ++mt) {
-            const Frag aK = O::load(tKT + kblk<T>(DK, (hf * NH + mt) * 16 + r, s * O::KSTEP + kg * E));
-            const Frag aQ = O::load(tQT + kblk<T>(DK, (hf * NH + mt) * 16 + r, s * O::KSTEP + kg * E));
-            accQ[mt] = O::mma(aK, b1e, accQ[mt]);
-            accP[mt] = O::mma(aK, b2e, accP[mt]);
-            accK[mt] = O::mma(aQ, b1t, accK[mt]);
-            accK[mt] = O::mma(aK, b2t, accK[mt]);
+        for (int t = 0; t < TT; ++t) {
+            const int wo = ((tg * TT + t) * 16 + r) * LDW + s * O::KSTEP + kg * E;
+            accQ[t] = O::mma(aK[s], O::load(sW1e + wo), accQ[t]);
+            accP[t] = O::mma(aK[s], O::load(sW2e + wo), accP[t]);
+            accK[t] = O::mma(aQ[s], O::load(sW1T + wo), accK[t]);
+            accK[t] = O::mma(aK[s], O::load(sW2T + wo), accK[t]);
         }
-    }
+    __syncthreads(); // the W space is free for the partial sums
 
-    // ---------------- phases C-F: products with the four state matrices, one staged tile each
-    // two products X^T[dk][i] = sum_dv St[dk][dv] f[i][dv] sharing the A fragments of one state tile
-    auto state_products = [&](const T *tile, const Frag (&f1)[KSV], const Frag (&f2)[KSV], f32x4 (&t1)[NH],
-                              f32x4 (&t2)[NH], bool second) {
+    // ---------------- phases C-F: products with the four state matrices.  X^T[dk][i] = sum_dv St[dk][dv] f[i][dv]
+    auto state_product = [&](const Frag(&fs)[KSV], const T *tile, f32x4(&t1)[TT]) {
         zero_acc(t1);
-        zero_acc(t2);
 #pragma unroll
-        for (int s = 0; s < KSV; ++s)
+        for (int s = 0; s < KSV; ++s) {
 #pragma unroll
-            for (int mt = 0; mt < NH; ++mt) {
-                const Frag as = O::load(tile + vblk(DK, (hf * NH + mt) * 16 + r, s * O::KSTEP + kg * E));
-                t1[mt] = O::mma(as, f1[s], t1[mt]);
-                if (second) t2[mt] = O::mma(as, f2[s], t2[mt]);
-            }
+            for (int t = 0; t < TT; ++t)
+                t1[t] = O::mma(fs[s], tfrag(tile, ldV, (tg * TT + t) * 16 + r, s), t1[t]);
+            sched_fence();
+        }
     };
+    auto part = [&](int q, int it) -> float & { return spart[(q * NKW + kt) * 64 + it]; };
     float p1 = 0.f, p2 = 0.f, p3 = 0.f; // partial <dS',S>, <dS',M>, <dM',M>
-    f32x4 t1[NH], t2[NH];
-    const float a_i = s_a[i], b_i = s_b[i], am_i = (i > 0) ? s_a[i - 1] : 1.f, bm_i = (i > 0) ? s_b[i - 1] : 0.f;
-    const float al_i = s_al[i], et_i = s_et[i];
+    f32x4 t1[TT];
 
     // C: S
-    if (STAGED) {
-        __syncthreads(); // phase B done with the staging buffer
-        commit_linear(Q, sB, cNV_S{});
-        issue_linear(P, dSg, cNV_S{});
-        __syncthreads();
+    if (!DEEP) load_state(fdS, dSg);
+    state_product(fS, tDO, t1);
+#pragma unroll
+    for (int t = 0; t < TT; ++t) {
+        const int it = (tg * TT + t) * 16 + r;
+        const float da = d.scale * coldot(t1[t], qv[t]);
+        if (kg == 0) part(P_DA, it) = da;
+        accQ[t] += s_a[it] * t1[t];
     }
-    state_products(STAGED ? sB : Sg, fdO, fdR, t1, t2, true);
-    {
-        f32x4 qv[NH];
+    state_product(fS, tDR, t1);
 #pragma unroll
-        for (int mt = 0; mt < NH; ++mt) qv[mt] = load4(qg + (size_t)i * rsk + (hf * NH + mt) * 16 + kg * 4);
-        const float da = d.scale * coldot<NH>(t1, qv);
-        const float dam = -al_i * coldot<NH>(t2, kv);
-        if (kg == 0) { s_da[hf][i] = da; s_dam[hf][i] = dam; }
-#pragma unroll
-        for (int mt = 0; mt < NH; ++mt) {
-            accQ[mt] += a_i * t1[mt];
-            accP[mt] -= am_i * t2[mt];
-        }
+    for (int t = 0; t < TT; ++t) {
+        const int it = (tg * TT + t) * 16 + r;
+        const float dam = -s_al[it] * coldot(t1[t], kv[t]);
+        if (kg == 0) part(P_DAM, it) = dam;
+        accP[t] -= ((it > 0) ? s_a[it - 1] : 1.f) * t1[t];
     }
     // E: dS'
-    Frag fVt[KSV];
+    if (!DEEP) load_state(fM, Mg);
+    state_product(fdS, tVt, t1);
 #pragma unroll
-    for (int s = 0; s < KSV; ++s) fVt[s] = O::load(vtg + (size_t)i * rsv + s * O::KSTEP + kg * E);
-    if (STAGED) {
-        __syncthreads();
-        p1 = dot_regs(P, Q);
-        commit_linear(P, sB, cNV_S{});
-        issue_linear(Q, Mg, cNV_S{});
-        __syncthreads();
+    for (int t = 0; t < TT; ++t) {
+        const int it = (tg * TT + t) * 16 + r;
+        const float dgc = s_et[it] * coldot(t1[t], kv[t]);
+        if (kg == 0) part(P_DGC, it) = dgc;
+        accK[t] += s_gC[it] * t1[t];
     }
-    state_products(STAGED ? sB : dSg, fVt, fVt, t1, t2, false);
-    const float gC_i = s_gC[i], rC_i = s_rC[i];
-    {
-        const float dgc = et_i * coldot<NH>(t1, kv);
-        if (kg == 0) s_dgc[hf][i] = dgc;
-#pragma unroll
-        for (int mt = 0; mt < NH; ++mt) accK[mt] += gC_i * t1[mt];
-    }
+    if (DEEP && tg == 0) p1 = dot_frags(fdS, fS);
     // D: M
-    if (STAGED) {
-        __syncthreads();
-        p2 = dot_regs(P, Q);
-        commit_linear(Q, sB, cNV_S{});
-        issue_linear(P, dMg, cNV_S{});
-        __syncthreads();
+    load_state(fdM, dMg);
+    state_product(fM, tDO, t1);
+#pragma unroll
+    for (int t = 0; t < TT; ++t) {
+        const int it = (tg * TT + t) * 16 + r;
+        const float db = -d.scale * coldot(t1[t], qv[t]);
+        if (kg == 0) part(P_DB, it) = db;
+        accQ[t] -= s_b[it] * t1[t];
+        store4(static_cast<T *>(a.dq) + (tok0 + (size_t)it * d.H) * DK + kt * 16 + kg * 4, d.scale * accQ[t]);
     }
-    state_products(STAGED ? sB : Mg, fdO, fdR, t1, t2, true);
-    {
-        f32x4 qv[NH];
+    state_product(fM, tDR, t1);
 #pragma unroll
-        for (int mt = 0; mt < NH; ++mt) qv[mt] = load4(qg + (size_t)i * rsk + (hf * NH + mt) * 16 + kg * 4);
-        const float db = -d.scale * coldot<NH>(t1, qv);
-        const float dbm = al_i * coldot<NH>(t2, kv);
-        if (kg == 0) { s_db[hf][i] = db; s_dbm[hf][i] = dbm; }
-#pragma unroll
-        for (int mt = 0; mt < NH; ++mt) {
-            accQ[mt] -= b_i * t1[mt];
-            accP[mt] += bm_i * t2[mt];
+    for (int t = 0; t < TT; ++t) {
+        const int it = (tg * TT + t) * 16 + r;
+        const float dbm = s_al[it] * coldot(t1[t], kv[t]);
+        accP[t] += ((it > 0) ? s_b[it - 1] : 0.f) * t1[t];
+        const float dalk = coldot(accP[t], kv[t]);
+        if (kg == 0) {
+            part(P_DBM, it) = dbm;
+            part(P_DALK, it) = dalk;
         }
-        T *dqg = static_cast<T *>(a.dq) + (tok0 + (size_t)i * d.H) * DK + hf * NH * 16 + kg * 4;
-#pragma unroll
-        for (int mt = 0; mt < NH; ++mt) store4(dqg + mt * 16, d.scale * accQ[mt]);
-        const float dalk = coldot<NH>(accP, kv);
-        if (kg == 0) s_dalk[hf][i] = dalk;
     }
+    if (DEEP && tg == 0) p2 = dot_frags(fdS, fM);
     // F: dM'
-    if (STAGED) {
-        __syncthreads();
-        p3 = dot_regs(P, Q);
-        commit_linear(P, sB, cNV_S{});
-        __syncthreads();
-    }
-    state_products(STAGED ? sB : dMg, fVt, fVt, t1, t2, false);
-    {
-        const float drc = -et_i * coldot<NH>(t1, kv);
+    state_product(fdM, tVt, t1);
 #pragma unroll
-        for (int mt = 0; mt < NH; ++mt) accK[mt] -= rC_i * t1[mt];
-        const float detk = coldot<NH>(accK, kv);
-        if (kg == 0) { s_drc[hf][i] = drc; s_detk[hf][i] = detk; }
-        T *dkg = static_cast<T *>(a.dk) + (tok0 + (size_t)i * d.H) * DK + hf * NH * 16 + kg * 4;
-#pragma unroll
-        for (int mt = 0; mt < NH; ++mt) store4(dkg + mt * 16, et_i * accK[mt] + al_i * accP[mt]);
+    for (int t = 0; t < TT; ++t) {
+        const int it = (tg * TT + t) * 16 + r;
+        const float et_i = s_et[it];
+        const float drc = -et_i * coldot(t1[t], kv[t]);
+        accK[t] -= s_rC[it] * t1[t];
+        const float detk = coldot(accK[t], kv[t]);
+        if (kg == 0) {
+            part(P_DRC, it) = drc;
+            part(P_DETK, it) = detk;
+        }
+        store4(static_cast<T *>(a.dk) + (tok0 + (size_t)it * d.H) * DK + kt * 16 + kg * 4,
+               et_i * accK[t] + s_al[it] * accP[t]);
     }
-    if (!STAGED) {
+    if (DEEP && tg == 0) p3 = dot_frags(fdM, fM);
+    if (!DEEP) {
         // <dS',S>, <dS',M>, <dM',M> straight from memory
         for (int c = tid * E; c < DK * DV; c += GT * E) {
 #pragma unroll
@@ -405,27 +397,37 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     __syncthreads();
 
     // ---------------- phase 4: reverse of the coefficient scans
-    if (w == 0)
-        coef_column_scan_reverse(g_al, g_be, g_mu, sDG1, sDG2, s_dgc[0][lane] + s_dgc[1][lane],
-                                 s_drc[0][lane] + s_drc[1][lane], sGa, sRa, LDG);
+    float tot[P_COUNT]; // wave 0: totals over the dk tiles of the row dots of token `lane`
+    if (w == 0) {
+#pragma unroll
+        for (int q = 0; q < P_COUNT; ++q) {
+            float s = 0.f;
+#pragma unroll
+            for (int k2 = 0; k2 < NKW; ++k2) s += spart[(q * NKW + k2) * 64 + lane];
+            tot[q] = s;
+        }
+        // (the partial sums share their space with sGa: all of them are in registers by now)
+        coef_column_scan_reverse(g_al, g_be, g_mu, sDG1, sDG2, tot[P_DGC], tot[P_DRC], sGa, sRa, LDG);
+    }
     __syncthreads();
     {
         // dalpha_i += sum_{j<i} G_ij Gamma_{i-1,j};  dbeta_i += sum_{j<=i} G_ij Rho_ij;
-        // dmu_i += sum_{j<i} R_ij Rho_{i-1,j}: 8 threads per row
-        const int row = tid >> 3, part = tid & 7;
+        // dmu_i += sum_{j<i} R_ij Rho_{i-1,j}: 8 threads per row; G, R, Gamma, Rho are zero above the diagonal
+        const int row = tid >> 3, pt = tid & 7, rowm = row > 0 ? row - 1 : 0;
         float ga = 0.f, gb = 0.f, gm = 0.f;
-        for (int j = part; j <= row; j += 8) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int j = pt + 8 * u;
             const float G = sGa[row * LDG + j], R = sRa[row * LDG + j];
-            gb += G * sRho[row * LDG + j];
-            if (j < row) {
-                ga += G * sG[(row - 1) * LDG + j];
-                gm += R * sRho[(row - 1) * LDG + j];
-            }
+            const float rho = sRho[row * LDG + j], gp = sG[rowm * LDG + j], rp = sRho[rowm * LDG + j];
+            gb += G * rho;
+            ga += (j < row) ? G * gp : 0.f;
+            gm += (j < row) ? R * rp : 0.f;
         }
         ga += __shfl_xor(ga, 1); ga += __shfl_xor(ga, 2); ga += __shfl_xor(ga, 4);
         gb += __shfl_xor(gb, 1); gb += __shfl_xor(gb, 2); gb += __shfl_xor(gb, 4);
         gm += __shfl_xor(gm, 1); gm += __shfl_xor(gm, 2); gm += __shfl_xor(gm, 4);
-        if (part == 0) { s_ga[row] = ga; s_gb[row] = gb; s_gm[row] = gm; }
+        if (pt == 0) { s_ga[row] = ga; s_gb[row] = gb; s_gm[row] = gm; }
     }
     __syncthreads();
     if (w == 0) {
@@ -442,21 +444,22 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
         }
         const int li = lane;
         const float al_next = __shfl_down(g_al, 1), mu_next = __shfl_down(g_mu, 1);
-        const float dbm_next = (li < 63) ? s_dbm[0][li + 1] + s_dbm[1][li + 1] : -dS_M;
-        const float dam_next = (li < 63) ? s_dam[0][li + 1] + s_dam[1][li + 1] : dS_S;
-        float cb = (li < 63) ? al_next : 0.f, db = s_db[0][li] + s_db[1][li] + dbm_next;
+        const float dbm_dn = __shfl_down(tot[P_DBM], 1), dam_dn = __shfl_down(tot[P_DAM], 1);
+        const float dbm_next = (li < 63) ? dbm_dn : -dS_M;
+        const float dam_next = (li < 63) ? dam_dn : dS_S;
+        float cb = (li < 63) ? al_next : 0.f, db = tot[P_DB] + dbm_next;
         scan_affine_rev(cb, db);
-        float ca = (li < 63) ? al_next : 0.f, da = s_da[0][li] + s_da[1][li] + dam_next;
+        float ca = (li < 63) ? al_next : 0.f, da = tot[P_DA] + dam_next;
         scan_affine_rev(ca, da);
         float cm = (li < 63) ? mu_next : 0.f, dm = (li == 63 ? dM_M : 0.f) + g_be * db;
         scan_affine_rev(cm, dm);
         const float aprev = __shfl_up(pa, 1), bprev = __shfl_up(pb, 1), mprev = __shfl_up(pm, 1);
         const float a_prev = (li > 0) ? aprev : 1.f, b_prev = (li > 0) ? bprev : 0.f, m_prev = (li > 0) ? mprev : 1.f;
         const size_t g = tok0 + (size_t)li * d.H;
-        a.dalpha[g] = s_ga[li] + db * b_prev + da * a_prev + s_dalk[0][li] + s_dalk[1][li];
+        a.dalpha[g] = s_ga[li] + db * b_prev + da * a_prev + tot[P_DALK];
         a.dbeta[g] = s_gb[li] + db * pm;
         a.dmu[g] = s_gm[li] + dm * m_prev;
-        if (a.deta) a.deta[g] = s_detk[0][li] + s_detk[1][li];
+        if (a.deta) a.deta[g] = tot[P_DETK];
     }
 }
 
