@@ -100,11 +100,28 @@ __device__ __forceinline__ f32x4 load4(const bf16_t *p) {
     return f32x4{(float)v[0], (float)v[1], (float)v[2], (float)v[3]};
 }
 __device__ __forceinline__ f32x4 load4(const float *p) { return *reinterpret_cast<const f32x4 *>(p); }
+// the same four elements kept in storage form (so that the conversion can sit at the use, not at the load)
+template <typename T> struct Raw4;
+template <> struct Raw4<bf16_t> { typedef bf16x4 type; };
+template <> struct Raw4<float> { typedef f32x4 type; };
+__device__ __forceinline__ bf16x4 load4_raw(const bf16_t *p) { return *reinterpret_cast<const bf16x4 *>(p); }
+__device__ __forceinline__ f32x4 load4_raw(const float *p) { return *reinterpret_cast<const f32x4 *>(p); }
+__device__ __forceinline__ f32x4 widen4(bf16x4 v) { return f32x4{(float)v[0], (float)v[1], (float)v[2], (float)v[3]}; }
+__device__ __forceinline__ f32x4 widen4(f32x4 v) { return v; }
 
 // 16 bytes of storage elements
 template <typename T> struct Vec16 {
     T e[Op<T>::EPL];
 };
+
+// base + 32-bit element offset, formed as a 32-bit BYTE offset: a wave-uniform base plus a per-lane
+// 32-bit offset is one address register (the hardware adds the scalar base) instead of a 64-bit pair
+template <typename T> __device__ __forceinline__ const T *at32(const T *base, unsigned elem_off) {
+    return reinterpret_cast<const T *>(reinterpret_cast<const char *>(base) + elem_off * (unsigned)sizeof(T));
+}
+template <typename T> __device__ __forceinline__ T *at32(T *base, unsigned elem_off) {
+    return reinterpret_cast<T *>(reinterpret_cast<char *>(base) + elem_off * (unsigned)sizeof(T));
+}
 
 // Blocked layouts of the chunk-local tensors that the library itself produces and consumes.
 // kblk: a [R][K] MFMA operand (fragment = row, KSTEP consecutive k) is stored as [K/KSTEP][R][KSTEP],

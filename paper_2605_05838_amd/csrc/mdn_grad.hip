@@ -45,6 +45,10 @@ namespace {
 
 constexpr int LDG = 65; // row stride of the fp32 64x64 coefficient matrices in LDS
 constexpr int GT = 512; // threads per workgroup: 8 waves
+#ifndef MDN_GRAD_STAGGER
+#define MDN_GRAD_STAGGER 0
+#endif
+constexpr int STAGGER = MDN_GRAD_STAGGER;
 
 // row-dot partial sums, one [dk tiles][64] block each
 enum { P_DA = 0, P_DB, P_DAM, P_DBM, P_DGC, P_DRC, P_DALK, P_DETK, P_COUNT };
@@ -65,12 +69,12 @@ __device__ __forceinline__ float coldot(f32x4 t, f32x4 xv) {
 // receives piece p ^ (row & XM) of that row.  Issued by 4 waves (lw = 0..3), NDMA instructions of 64
 // consecutive slots each.
 template <typename T, int D>
-__device__ __forceinline__ void dma_token_tile(T *ldst, const T *src, size_t rs, int lw, int lane) {
+__device__ __forceinline__ void dma_token_tile(T *ldst, const T *src, unsigned rs, int lw, int lane) {
     constexpr int E = Op<T>::EPL, CPR = D / E, XM = (CPR < 16 ? CPR : 16) - 1, NDMA = CPR / 4;
 #pragma unroll
     for (int u = 0; u < NDMA; ++u) {
         const int blk64 = u * 4 + lw, sl = blk64 * 64 + lane, row = sl / CPR, pc = (sl % CPR) ^ (row & XM);
-        __builtin_amdgcn_global_load_lds(src + (size_t)row * rs + pc * E,
+        __builtin_amdgcn_global_load_lds(at32(src, row * rs + pc * E),
                                          (__attribute__((address_space(3))) void *)(ldst + blk64 * 64 * E), 16, 0, 0);
     }
 }
@@ -129,7 +133,9 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     const int n = blockIdx.x, bh = blockIdx.y, b = bh / d.H, h = bh % d.H;
     const size_t tok0 = ((size_t)b * d.T + (size_t)n * 64) * d.H + h;
     const size_t blk = (size_t)bh * d.N + n;
-    const size_t rsk = (size_t)d.H * DK, rsv = (size_t)d.H * DV;
+    // per-lane offsets inside the chunk stay 32-bit (a uniform 64-bit base plus a 32-bit lane offset is
+    // one address register instead of two)
+    const unsigned rsk = (unsigned)d.H * DK, rsv = (unsigned)d.H * DV;
     const T *qg = static_cast<const T *>(a.q) + tok0 * DK;
     const T *kgl = static_cast<const T *>(a.k) + tok0 * DK;
     const T *vtg = static_cast<const T *>(a.vt_saved) + tok0 * DV;
@@ -143,12 +149,12 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     // fragment of row `row`, contraction step st of a token tile (in LDS, or in global memory with row stride ld)
     auto tfrag = [&](const T *tile, int ld, int row, int st) -> Frag {
         if (STAGED) return O::load(tile + row * D + (((st * CPS + kg) ^ (row & XM)) * E));
-        return O::load(tile + (size_t)row * ld + st * O::KSTEP + kg * E);
+        return O::load(at32(tile, row * ld + st * O::KSTEP + kg * E));
     };
     // this wave's 16 rows (dk tile kt) of a [dk][dv] state tile as A fragments
     auto load_state = [&](Frag(&f)[KSV], const T *tile) {
 #pragma unroll
-        for (int s = 0; s < KSV; ++s) f[s] = O::load(tile + vblk(DK, kt * 16 + r, s * O::KSTEP + kg * E));
+        for (int s = 0; s < KSV; ++s) f[s] = O::load(at32(tile, (unsigned)vblk(DK, kt * 16 + r, s * O::KSTEP + kg * E)));
     };
     auto dot_frags = [&](const Frag(&x)[KSV], const Frag(&y)[KSV]) {
         float s = 0.f;
@@ -160,17 +166,25 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     };
 
     // ---------------- prologue: gates first, then everything this workgroup will read, in order of use
-    const size_t gl = tok0 + (size_t)lane * d.H;
-    const float g_al = a.alpha[gl], g_be = a.beta[gl], g_mu = a.mu[gl], g_et = a.eta ? a.eta[gl] : 1.f;
+    if (STAGGER > 0) {
+        // first round of workgroups: every other one starts late, so that the memory-heavy start of one
+        // workgroup falls into the memory-idle end of its neighbours for the rest of the launch
+        const int lin = blockIdx.y * gridDim.x + blockIdx.x;
+        if (lin < 256 && (lin & 1))
+            for (int z = 0; z < STAGGER; ++z) __builtin_amdgcn_s_sleep(127);
+    }
+    const unsigned gl = (unsigned)(lane * d.H);
+    const float g_al = *at32(a.alpha + tok0, gl), g_be = *at32(a.beta + tok0, gl), g_mu = *at32(a.mu + tok0, gl);
+    const float g_et = a.eta ? *at32(a.eta + tok0, gl) : 1.f;
     for (int c = tid; c < LDG; c += GT) sDG2[64 * LDG + c] = 0.f;
     Frag fq[KSK]; // phase A B fragments of q (no LDS copy): row = token i
 #pragma unroll
-    for (int s = 0; s < KSK; ++s) fq[s] = O::load(qg + (size_t)i * rsk + s * O::KSTEP + kg * E);
+    for (int s = 0; s < KSK; ++s) fq[s] = O::load(at32(qg, i * rsk + s * O::KSTEP + kg * E));
     Frag aK[KS2], aQ[KS2]; // this wave's rows of K^T, Q^T
 #pragma unroll
     for (int s = 0; s < KS2; ++s) {
-        aK[s] = O::load(KTg + kblk<T>(DK, kt * 16 + r, s * O::KSTEP + kg * E));
-        aQ[s] = O::load(QTg + kblk<T>(DK, kt * 16 + r, s * O::KSTEP + kg * E));
+        aK[s] = O::load(at32(KTg, (unsigned)kblk<T>(DK, kt * 16 + r, s * O::KSTEP + kg * E)));
+        aQ[s] = O::load(at32(QTg, (unsigned)kblk<T>(DK, kt * 16 + r, s * O::KSTEP + kg * E)));
     }
     Frag fS[KSV], fM[KSV], fdS[KSV], fdM[KSV];
     load_state(fS, Sg);
@@ -262,19 +276,21 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
         }
     }
     __syncthreads();
-    if (DEEP) {
-        load_state(fM, Mg);
-        load_state(fdS, dSg); // dM' follows once S is no longer needed
-    }
     // k and q of this wave's tokens in accumulator layout: element x is dk = kt*16 + kg*4 + x
-    f32x4 kv[TT], qv[TT];
+    //  (kept in storage form: widening them here would make the wave wait for every load issued so far)
+    typename Raw4<T>::type kv[TT], qv[TT];
 #pragma unroll
     for (int t = 0; t < TT; ++t) {
         const int it = (tg * TT + t) * 16 + r;
-        kv[t] = load4(kgl + (size_t)it * rsk + kt * 16 + kg * 4);
-        qv[t] = load4(qg + (size_t)it * rsk + kt * 16 + kg * 4);
+        kv[t] = load4_raw(at32(kgl, it * rsk + kt * 16 + kg * 4));
+        qv[t] = load4_raw(at32(qg, it * rsk + kt * 16 + kg * 4));
     }
-
+    sched_fence(); // q, k rows are needed first: keep them ahead of the state tiles in the return order
+    if (DEEP) {
+        load_state(fdS, dSg);
+        load_state(fM, Mg); // dM' follows once S is no longer needed
+    }
+    sched_fence(); // these loads leave now, not after the products below
     // ---------------- phase B: the token-contractions W1 K~, W2 K~, W1^T Q~, W2^T P
     f32x4 accQ[TT], accP[TT], accK[TT]; // dQ~^T, dP^T, dK~^T: [dk tile kt][token tile t of this group]
     zero_acc(accQ);
@@ -293,102 +309,83 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     __syncthreads(); // the W space is free for the partial sums
 
     // ---------------- phases C-F: products with the four state matrices.  X^T[dk][i] = sum_dv St[dk][dv] f[i][dv]
-    auto state_product = [&](const Frag(&fs)[KSV], const T *tile, f32x4(&t1)[TT]) {
+    // two products sharing their B fragments (LDS reads are what bounds these phases):
+    //   t1^T[dk][i] = sum_dv Fa[dk][dv] X[i][dv],  t2^T likewise with Fb
+    auto state_product2 = [&](const Frag(&fa)[KSV], const Frag(&fb)[KSV], const T *tile, f32x4(&t1)[TT], f32x4(&t2)[TT]) {
         zero_acc(t1);
+        zero_acc(t2);
 #pragma unroll
         for (int s = 0; s < KSV; ++s) {
 #pragma unroll
-            for (int t = 0; t < TT; ++t)
-                t1[t] = O::mma(fs[s], tfrag(tile, ldV, (tg * TT + t) * 16 + r, s), t1[t]);
+            for (int t = 0; t < TT; ++t) {
+                const Frag x = tfrag(tile, ldV, (tg * TT + t) * 16 + r, s);
+                t1[t] = O::mma(fa[s], x, t1[t]);
+                t2[t] = O::mma(fb[s], x, t2[t]);
+            }
             sched_fence();
         }
     };
     auto part = [&](int q, int it) -> float & { return spart[(q * NKW + kt) * 64 + it]; };
     float p1 = 0.f, p2 = 0.f, p3 = 0.f; // partial <dS',S>, <dS',M>, <dM',M>
-    f32x4 t1[TT];
+    f32x4 t1[TT], t2[TT];
 
-    // C: S
-    if (!DEEP) load_state(fdS, dSg);
-    state_product(fS, tDO, t1);
-#pragma unroll
-    for (int t = 0; t < TT; ++t) {
-        const int it = (tg * TT + t) * 16 + r;
-        const float da = d.scale * coldot(t1[t], qv[t]);
-        if (kg == 0) part(P_DA, it) = da;
-        accQ[t] += s_a[it] * t1[t];
-    }
-    state_product(fS, tDR, t1);
-#pragma unroll
-    for (int t = 0; t < TT; ++t) {
-        const int it = (tg * TT + t) * 16 + r;
-        const float dam = -s_al[it] * coldot(t1[t], kv[t]);
-        if (kg == 0) part(P_DAM, it) = dam;
-        accP[t] -= ((it > 0) ? s_a[it - 1] : 1.f) * t1[t];
-    }
-    // E: dS'
+    // C: S and M against dO
     if (!DEEP) load_state(fM, Mg);
-    state_product(fdS, tVt, t1);
+    state_product2(fS, fM, tDO, t1, t2);
 #pragma unroll
     for (int t = 0; t < TT; ++t) {
         const int it = (tg * TT + t) * 16 + r;
-        const float dgc = s_et[it] * coldot(t1[t], kv[t]);
-        if (kg == 0) part(P_DGC, it) = dgc;
-        accK[t] += s_gC[it] * t1[t];
-    }
-    if (DEEP && tg == 0) p1 = dot_frags(fdS, fS);
-    // D: M
-    load_state(fdM, dMg);
-    state_product(fM, tDO, t1);
-#pragma unroll
-    for (int t = 0; t < TT; ++t) {
-        const int it = (tg * TT + t) * 16 + r;
-        const float db = -d.scale * coldot(t1[t], qv[t]);
-        if (kg == 0) part(P_DB, it) = db;
-        accQ[t] -= s_b[it] * t1[t];
-        store4(static_cast<T *>(a.dq) + (tok0 + (size_t)it * d.H) * DK + kt * 16 + kg * 4, d.scale * accQ[t]);
-    }
-    state_product(fM, tDR, t1);
-#pragma unroll
-    for (int t = 0; t < TT; ++t) {
-        const int it = (tg * TT + t) * 16 + r;
-        const float dbm = s_al[it] * coldot(t1[t], kv[t]);
-        accP[t] += ((it > 0) ? s_b[it - 1] : 0.f) * t1[t];
-        const float dalk = coldot(accP[t], kv[t]);
+        const f32x4 qw = widen4(qv[t]);
+        const float da = d.scale * coldot(t1[t], qw);
+        const float db = -d.scale * coldot(t2[t], qw);
         if (kg == 0) {
+            part(P_DA, it) = da;
+            part(P_DB, it) = db;
+        }
+        accQ[t] += s_a[it] * t1[t] - s_b[it] * t2[t];
+        store4(at32(static_cast<T *>(a.dq) + tok0 * DK, it * rsk + kt * 16 + kg * 4), d.scale * accQ[t]);
+    }
+    // D: S and M against dR
+    load_state(fdM, dMg);
+    if (!DEEP) load_state(fdS, dSg);
+    state_product2(fS, fM, tDR, t1, t2);
+#pragma unroll
+    for (int t = 0; t < TT; ++t) {
+        const int it = (tg * TT + t) * 16 + r;
+        const f32x4 kw = widen4(kv[t]);
+        const float al_i = s_al[it];
+        const float dam = -al_i * coldot(t1[t], kw);
+        const float dbm = al_i * coldot(t2[t], kw);
+        accP[t] += ((it > 0) ? s_b[it - 1] : 0.f) * t2[t] - ((it > 0) ? s_a[it - 1] : 1.f) * t1[t];
+        const float dalk = coldot(accP[t], kw);
+        if (kg == 0) {
+            part(P_DAM, it) = dam;
             part(P_DBM, it) = dbm;
             part(P_DALK, it) = dalk;
         }
     }
-    if (DEEP && tg == 0) p2 = dot_frags(fdS, fM);
-    // F: dM'
-    state_product(fdM, tVt, t1);
+    if (tg == 0) {
+        p1 = dot_frags(fdS, fS);
+        p2 = dot_frags(fdS, fM);
+        p3 = dot_frags(fdM, fM);
+    }
+    // E: dS' and dM' against V~
+    state_product2(fdS, fdM, tVt, t1, t2);
 #pragma unroll
     for (int t = 0; t < TT; ++t) {
         const int it = (tg * TT + t) * 16 + r;
+        const f32x4 kw = widen4(kv[t]);
         const float et_i = s_et[it];
-        const float drc = -et_i * coldot(t1[t], kv[t]);
-        accK[t] -= s_rC[it] * t1[t];
-        const float detk = coldot(accK[t], kv[t]);
+        const float dgc = et_i * coldot(t1[t], kw);
+        const float drc = -et_i * coldot(t2[t], kw);
+        accK[t] += s_gC[it] * t1[t] - s_rC[it] * t2[t];
+        const float detk = coldot(accK[t], kw);
         if (kg == 0) {
+            part(P_DGC, it) = dgc;
             part(P_DRC, it) = drc;
             part(P_DETK, it) = detk;
         }
-        store4(static_cast<T *>(a.dk) + (tok0 + (size_t)it * d.H) * DK + kt * 16 + kg * 4,
-               et_i * accK[t] + s_al[it] * accP[t]);
-    }
-    if (DEEP && tg == 0) p3 = dot_frags(fdM, fM);
-    if (!DEEP) {
-        // <dS',S>, <dS',M>, <dM',M> straight from memory
-        for (int c = tid * E; c < DK * DV; c += GT * E) {
-#pragma unroll
-            for (int e = 0; e < E; ++e) {
-                const float s = to_f32(Sg[c + e]), m = to_f32(Mg[c + e]);
-                const float ds = to_f32(dSg[c + e]), dm = to_f32(dMg[c + e]);
-                p1 += ds * s;
-                p2 += ds * m;
-                p3 += dm * m;
-            }
-        }
+        store4(at32(static_cast<T *>(a.dk) + tok0 * DK, it * rsk + kt * 16 + kg * 4), et_i * accK[t] + s_al[it] * accP[t]);
     }
     p1 = reduce64(p1);
     p2 = reduce64(p2);
@@ -455,11 +452,11 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
         scan_affine_rev(cm, dm);
         const float aprev = __shfl_up(pa, 1), bprev = __shfl_up(pb, 1), mprev = __shfl_up(pm, 1);
         const float a_prev = (li > 0) ? aprev : 1.f, b_prev = (li > 0) ? bprev : 0.f, m_prev = (li > 0) ? mprev : 1.f;
-        const size_t g = tok0 + (size_t)li * d.H;
-        a.dalpha[g] = s_ga[li] + db * b_prev + da * a_prev + tot[P_DALK];
-        a.dbeta[g] = s_gb[li] + db * pm;
-        a.dmu[g] = s_gm[li] + dm * m_prev;
-        if (a.deta) a.deta[g] = tot[P_DETK];
+        const unsigned g = (unsigned)(li * d.H);
+        *at32(a.dalpha + tok0, g) = s_ga[li] + db * b_prev + da * a_prev + tot[P_DALK];
+        *at32(a.dbeta + tok0, g) = s_gb[li] + db * pm;
+        *at32(a.dmu + tok0, g) = s_gm[li] + dm * m_prev;
+        if (a.deta) *at32(a.deta + tok0, g) = tot[P_DETK];
     }
 }
 
