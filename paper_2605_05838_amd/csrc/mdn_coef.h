@@ -74,6 +74,65 @@ __device__ __forceinline__ void coef_column_scan(float al, float be, float mu, f
     rC = rho;
 }
 
+// ---- the same column scans split over 4 waves: wave w (0..3) produces rows 16w .. 16w+15 of Gamma
+//      (and Rho) for all 64 columns, lane j = column j, every wave holding the gates of token `lane`.
+//      The state (g, rho) of column j moves from row i-1 to row i by the triangular map
+//        T_i = [alpha_i, beta_i mu_i; 0, mu_i],   starting from (beta_j, 1) in row j.
+//      A wave gets the state its columns have in row 16w-1 without walking there: products of the T_i
+//      inside each 16-row segment by a segmented suffix scan over the lanes, then at most two whole
+//      segment maps on top.  After that, 16 dependent steps instead of 64.
+//      gC, rC (row 63) are returned by wave 3 only.
+template <bool WANT_RHO>
+__device__ __forceinline__ void coef_column_scan_blocked(float al, float be, float mu, float *sG, float *sRho, int ldg,
+                                                         int w, float &gC, float &rC) {
+    const int j = lane_id(), jl = j & 15;
+    // inclusive suffix products inside the 16-lane segment: (A, B, M)_j = T_end o ... o T_j
+    float A = al, B = be * mu, M = mu;
+#pragma unroll
+    for (int dlt = 1; dlt < 16; dlt <<= 1) {
+        const float A2 = __shfl_down(A, dlt, 16), B2 = __shfl_down(B, dlt, 16), M2 = __shfl_down(M, dlt, 16);
+        if (jl + dlt < 16) { // (A2, B2, M2) o (A, B, M): this lane's map first, the later rows' after it
+            B = A2 * B + B2 * M;
+            A = A2 * A;
+            M = M2 * M;
+        }
+    }
+    // exclusive: product of T_{j+1} .. T_end (identity for the last lane of a segment)
+    const float Ax = __shfl_down(A, 1, 16), Bx = __shfl_down(B, 1, 16), Mx = __shfl_down(M, 1, 16);
+    // state of column j in the last row of its own segment
+    float g = (jl < 15) ? Ax * be + Bx : be, rho = (jl < 15) ? Mx : 1.f;
+    // on through whole segments up to row 16w - 1 (columns of segment J < I pass through segment I)
+#pragma unroll
+    for (int I = 1; I < 3; ++I) {
+        const float As = lane_bcast(A, 16 * I), Bs = lane_bcast(B, 16 * I), Ms = lane_bcast(M, 16 * I);
+        if (I < w && j < 16 * I) {
+            g = As * g + Bs * rho;
+            rho = Ms * rho;
+        }
+    }
+    if (j >= 16 * w) { // columns that start inside (or below) this wave's rows
+        g = 0.f;
+        rho = 0.f;
+    }
+    // lane_bcast needs a compile-time lane: one unrolled copy of the 16 steps per segment
+#pragma unroll
+    for (int seg = 0; seg < 4; ++seg) {
+        if (seg == w) {
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int i = seg * 16 + u;
+                const float a_i = lane_bcast(al, i), b_i = lane_bcast(be, i), m_i = lane_bcast(mu, i);
+                rho = (i == j) ? 1.f : rho * m_i;
+                g = a_i * g + b_i * rho;
+                sG[i * ldg + j] = g;
+                if (WANT_RHO) sRho[i * ldg + j] = rho;
+            }
+        }
+    }
+    gC = g;
+    rC = rho;
+}
+
 // ---- reverse of the column scans (adjoint): lane j owns column j.  With D_ij the direct adjoint of
 //      Gamma_ij (sD1[i][j] + sD2[i+1][j], plus dgc_j in row 63) and drc_j the direct adjoint of Rho_63,j:
 //        G_ij = D_ij + alpha_{i+1} G_{i+1,j}            R_ij = [i = 63] drc_j + beta_i G_ij + mu_{i+1} R_{i+1,j}
@@ -107,6 +166,94 @@ __device__ __forceinline__ void coef_column_scan_reverse(float al, float be, flo
             cg = a_i * G;
             cr = m_i * R;
         }
+    }
+}
+
+// ---- the reverse column scans split over 4 waves: wave w (0..3) owns rows 16w .. 16w+15, lane j = column j.
+//      Part 1 walks the wave's rows upwards with nothing coming in from the rows below (16 dependent
+//      steps), and also walks the three coefficients with which an incoming pair (Gin, Rin) = (G, R) of the
+//      row below the segment would enter each row:
+//        G_ij = Gloc_ij + gc_i Gin_j          R_ij = Rloc_ij + ec_i Gin_j + mc_i Rin_j
+//        gc_i = alpha_{i+1} gc_{i+1},  mc_i = mu_{i+1} mc_{i+1},  ec_i = beta_i gc_i + mu_{i+1} ec_{i+1}
+//      It leaves the segment's top row (local values, zero above the diagonal) and that row's three
+//      coefficients in LDS.  After a workgroup barrier, part 2 chains the top rows of the segments below to
+//      get what comes in, and completes and stores the wave's rows.
+struct RevScanRows {
+    float G[16], R[16], gc[16], ec[16], mc[16];
+};
+// sTop: [4][2][64] floats (top rows: G, R), sTopC: [4][3] floats (top-row coefficients)
+__device__ __forceinline__ void coef_scan_reverse_part1(float al, float be, float mu, const float *sD1, const float *sD2,
+                                                        float dgc, float drc, int ldg, int w, RevScanRows &rr, float *sTop,
+                                                        float *sTopC) {
+    const int j = lane_id();
+#pragma unroll
+    for (int seg = 0; seg < 4; ++seg) {
+        if (seg == w) {
+            const int i0 = seg * 16;
+            float dir[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) dir[u] = sD1[(i0 + u) * ldg + j] + sD2[(i0 + u + 1) * ldg + j];
+            float cg = 0.f, cr = 0.f;           // alpha_{i+1} Gloc_{i+1,j}, mu_{i+1} Rloc_{i+1,j}
+            float gc = 1.f, ec = 0.f, mc = 1.f; // coefficients of the row below the current one
+#pragma unroll
+            for (int u = 15; u >= 0; --u) {
+                const int i = i0 + u;
+                // gates of row i+1 (nothing below row 63: whatever stands here is multiplied by a zero incoming pair)
+                const float a_n = (i < 63) ? lane_bcast(al, (i + 1) & 63) : 0.f, m_n = (i < 63) ? lane_bcast(mu, (i + 1) & 63) : 0.f;
+                const float b_i = lane_bcast(be, i);
+                float G = dir[u] + cg, R = cr;
+                if (i == 63) {
+                    G += dgc;
+                    R += drc;
+                }
+                R += b_i * G;
+                rr.G[u] = G;
+                rr.R[u] = R;
+                gc = a_n * gc;
+                ec = b_i * gc + m_n * ec;
+                mc = m_n * mc;
+                rr.gc[u] = gc;
+                rr.ec[u] = ec;
+                rr.mc[u] = mc;
+                if (u > 0) {
+                    cg = lane_bcast(al, i) * G;
+                    cr = lane_bcast(mu, i) * R;
+                }
+            }
+            sTop[(seg * 2 + 0) * 64 + j] = (j <= i0) ? rr.G[0] : 0.f;
+            sTop[(seg * 2 + 1) * 64 + j] = (j <= i0) ? rr.R[0] : 0.f;
+            if (j == 0) {
+                sTopC[seg * 3 + 0] = rr.gc[0];
+                sTopC[seg * 3 + 1] = rr.ec[0];
+                sTopC[seg * 3 + 2] = rr.mc[0];
+            }
+        }
+    }
+}
+
+// Writes sGa[i][j] = G_ij, sRa[i][j] = R_ij for the wave's 16 rows (zero for i < j).
+__device__ __forceinline__ void coef_scan_reverse_part2(int ldg, int w, const RevScanRows &rr, const float *sTop,
+                                                        const float *sTopC, float *sGa, float *sRa) {
+    const int j = lane_id();
+    float Gin = 0.f, Rin = 0.f; // G, R of the row just below this wave's segment
+#pragma unroll
+    for (int seg = 3; seg >= 1; --seg) {
+        if (seg > w) {
+            const float gct = sTopC[seg * 3 + 0], ect = sTopC[seg * 3 + 1], mct = sTopC[seg * 3 + 2];
+            const bool act = j <= seg * 16;
+            const float Gt = sTop[(seg * 2 + 0) * 64 + j] + (act ? gct * Gin : 0.f);
+            const float Rt = sTop[(seg * 2 + 1) * 64 + j] + (act ? ect * Gin + mct * Rin : 0.f);
+            Gin = Gt;
+            Rin = Rt;
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+        const int i = w * 16 + u;
+        const float G = rr.G[u] + rr.gc[u] * Gin;
+        const float R = rr.R[u] + rr.ec[u] * Gin + rr.mc[u] * Rin;
+        sGa[i * ldg + j] = (i >= j) ? G : 0.f;
+        sRa[i * ldg + j] = (i >= j) ? R : 0.f;
     }
 }
 

@@ -43,7 +43,7 @@ namespace mdn {
 
 namespace {
 
-constexpr int LDG = 65; // row stride of the fp32 64x64 coefficient matrices in LDS
+constexpr int LDG = 68; // row stride of the fp32 64x64 coefficient matrices in LDS (rows 16-byte aligned)
 constexpr int GT = 512; // threads per workgroup: 8 waves
 #ifndef MDN_GRAD_STAGGER
 #define MDN_GRAD_STAGGER 0
@@ -66,14 +66,14 @@ __device__ __forceinline__ float coldot(f32x4 t, f32x4 xv) {
 }
 
 // one natural-layout [64][D] token tile, HBM -> LDS without registers: the 16-byte slot (row, position p)
-// receives piece p ^ (row & XM) of that row.  Issued by 4 waves (lw = 0..3), NDMA instructions of 64
+// receives piece p ^ (row & XM) of that row.  Issued by 2 waves (lw = 0, 1), NDMA instructions of 64
 // consecutive slots each.
 template <typename T, int D>
 __device__ __forceinline__ void dma_token_tile(T *ldst, const T *src, unsigned rs, int lw, int lane) {
-    constexpr int E = Op<T>::EPL, CPR = D / E, XM = (CPR < 16 ? CPR : 16) - 1, NDMA = CPR / 4;
+    constexpr int E = Op<T>::EPL, CPR = D / E, XM = (CPR < 16 ? CPR : 16) - 1, NDMA = CPR / 2;
 #pragma unroll
     for (int u = 0; u < NDMA; ++u) {
-        const int blk64 = u * 4 + lw, sl = blk64 * 64 + lane, row = sl / CPR, pc = (sl % CPR) ^ (row & XM);
+        const int blk64 = u * 2 + lw, sl = blk64 * 64 + lane, row = sl / CPR, pc = (sl % CPR) ^ (row & XM);
         __builtin_amdgcn_global_load_lds(at32(src, row * rs + pc * E),
                                          (__attribute__((address_space(3))) void *)(ldst + blk64 * 64 * E), 16, 0, 0);
     }
@@ -100,8 +100,8 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     constexpr bool DEEP = STAGED; // all four state tiles in registers at once
     static_assert(NKW * TG == 8 && TT * TG == 4, "8 waves = dk tiles x token groups");
 
-    __shared__ float sG[64 * LDG];     // Gamma
-    __shared__ float sRho[64 * LDG];   // Rho
+    __shared__ __align__(16) float sG[64 * LDG];     // Gamma
+    __shared__ __align__(16) float sRho[64 * LDG];   // Rho
     __shared__ float sDG1[64 * LDG];   // direct dGamma from Bm
     __shared__ float sDG2[65 * LDG];   // direct dGamma^- (row i here belongs to Gamma row i-1)
     __shared__ __align__(16) T sW[4 * 64 * LDW];
@@ -112,7 +112,8 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     // after the W products the space holds the row-dot partial sums, then the accumulated adjoints of Gamma, Rho
     float *spart = reinterpret_cast<float *>(sW);
     float *sGa = reinterpret_cast<float *>(sW), *sRa = sGa + 64 * LDG;
-    static_assert(sizeof(T) * 4 * 64 * LDW >= sizeof(float) * 2 * 64 * LDG, "adjoint matrices do not fit the W space");
+    float *sTop = sRa + 64 * LDG; // [4][2][64]: top rows of the four row segments of the reverse scan
+    static_assert(sizeof(T) * 4 * 64 * LDW >= sizeof(float) * (2 * 64 * LDG + 512), "adjoint matrices do not fit the W space");
     static_assert(sizeof(T) * 4 * 64 * LDW >= sizeof(float) * P_COUNT * NKW * 64, "partial sums do not fit the W space");
     // token tiles [64][D] (pieces permuted, see above): V~, dO, dR; k sits in the W space until the W matrices are written
     __shared__ __align__(16) T sVt[STAGED ? 64 * D : 8];
@@ -121,6 +122,7 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     T *sK = sW;
     static_assert(4 * LDW >= D, "k tile does not fit the W space");
     __shared__ float s_al[64], s_et[64], s_a[64], s_b[64];
+    __shared__ float sTopC[12];
     __shared__ float s_gC[64], s_rC[64];
     __shared__ float s_ga[64], s_gb[64], s_gm[64];
     __shared__ float s_red[8][3];
@@ -189,12 +191,20 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     Frag fS[KSV], fM[KSV], fdS[KSV], fdM[KSV];
     load_state(fS, Sg);
 
-    // ---------------- phase 0: forward coefficients: vectors by wave scans, matrices by a column scan
-    //                  (wave 0, needs only the gates).  Meanwhile waves 4-7 start the token tiles on
-    //                  their way to LDS; wave 0 itself must have no such transfer pending on its path
-    //                  (also not in the compiler's view of it), or its first LDS instruction would wait for it.
-    float pa = 0.f, pm = 0.f, pb = 0.f; // a_lane, m_lane, b_lane (wave 0)
-    if (w == 0) {
+    // ---------------- phase 0: forward coefficients (needs only the gates): waves 0-3 the matrices Gamma, Rho
+    //                  (16 rows each), wave 4 the vectors by wave scans.  Meanwhile waves 6, 7 start the
+    //                  token tiles on their way to LDS; a wave with such a transfer pending would wait for
+    //                  it at its next LDS instruction, so that block comes last in program order.
+    float pa = 0.f, pm = 0.f, pb = 0.f; // a_lane, m_lane, b_lane (wave 4)
+    if (w < 4) {
+        float gC, rC;
+        coef_column_scan_blocked<true>(g_al, g_be, g_mu, sG, sRho, LDG, w, gC, rC);
+        if (w == 3) {
+            s_gC[lane] = gC; // Gamma_{C,j}
+            s_rC[lane] = rC; // Rho_{C,j}
+        }
+    }
+    if (w == 4) {
         pa = scan_prod(g_al);
         pm = scan_prod(g_mu);
         float c = g_al;
@@ -204,16 +214,12 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
         s_et[lane] = g_et;
         s_a[lane] = pa;
         s_b[lane] = pb;
-        float gC, rC;
-        coef_column_scan<true>(g_al, g_be, g_mu, sG, sRho, LDG, gC, rC);
-        s_gC[lane] = gC; // Gamma_{C,j}
-        s_rC[lane] = rC; // Rho_{C,j}
     }
-    if (STAGED && w >= 4) {
-        dma_token_tile<T, D>(sVt, vtg, rsv, w - 4, lane);
-        dma_token_tile<T, D>(sK, kgl, rsk, w - 4, lane);
-        dma_token_tile<T, D>(sDO, dog, rsv, w - 4, lane);
-        dma_token_tile<T, D>(sDR, drg, rsv, w - 4, lane);
+    if (STAGED && w >= 6) {
+        dma_token_tile<T, D>(sVt, vtg, rsv, w - 6, lane);
+        dma_token_tile<T, D>(sK, kgl, rsk, w - 6, lane);
+        dma_token_tile<T, D>(sDO, dog, rsv, w - 6, lane);
+        dma_token_tile<T, D>(sDR, drg, rsv, w - 6, lane);
     }
     const T *tVt = STAGED ? sVt : vtg, *tK = STAGED ? sK : kgl, *tDR = STAGED ? sDR : drg, *tDO = STAGED ? sDO : dog;
     const int ldV = (int)rsv, ldK = (int)rsk; // row strides of the global tiles (fp32 path)
@@ -393,41 +399,25 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     if (lane == 0) { s_red[w][0] = p1; s_red[w][1] = p2; s_red[w][2] = p3; }
     __syncthreads();
 
-    // ---------------- phase 4: reverse of the coefficient scans
-    float tot[P_COUNT]; // wave 0: totals over the dk tiles of the row dots of token `lane`
-    if (w == 0) {
+    // ---------------- phase 4: reverse of the coefficient scans.  Waves 0-3: the matrices (16 rows each, two
+    //                  parts around a barrier); wave 4 (which holds a, b, m): the vectors.
+    auto total = [&](int q) { // sum over the dk tiles of one row dot of token `lane`
+        float s = 0.f;
 #pragma unroll
-        for (int q = 0; q < P_COUNT; ++q) {
-            float s = 0.f;
-#pragma unroll
-            for (int k2 = 0; k2 < NKW; ++k2) s += spart[(q * NKW + k2) * 64 + lane];
-            tot[q] = s;
+        for (int k2 = 0; k2 < NKW; ++k2) s += spart[(q * NKW + k2) * 64 + lane];
+        return s;
+    };
+    RevScanRows rr;
+    float db = 0.f, da = 0.f, dm = 0.f, dalk = 0.f, detk = 0.f;
+    if (w < 4) {
+        float dgc = 0.f, drc = 0.f;
+        if (w == 3) {
+            dgc = total(P_DGC);
+            drc = total(P_DRC);
         }
-        // (the partial sums share their space with sGa: all of them are in registers by now)
-        coef_column_scan_reverse(g_al, g_be, g_mu, sDG1, sDG2, tot[P_DGC], tot[P_DRC], sGa, sRa, LDG);
+        coef_scan_reverse_part1(g_al, g_be, g_mu, sDG1, sDG2, dgc, drc, LDG, w, rr, sTop, sTopC);
     }
-    __syncthreads();
-    {
-        // dalpha_i += sum_{j<i} G_ij Gamma_{i-1,j};  dbeta_i += sum_{j<=i} G_ij Rho_ij;
-        // dmu_i += sum_{j<i} R_ij Rho_{i-1,j}: 8 threads per row; G, R, Gamma, Rho are zero above the diagonal
-        const int row = tid >> 3, pt = tid & 7, rowm = row > 0 ? row - 1 : 0;
-        float ga = 0.f, gb = 0.f, gm = 0.f;
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int j = pt + 8 * u;
-            const float G = sGa[row * LDG + j], R = sRa[row * LDG + j];
-            const float rho = sRho[row * LDG + j], gp = sG[rowm * LDG + j], rp = sRho[rowm * LDG + j];
-            gb += G * rho;
-            ga += (j < row) ? G * gp : 0.f;
-            gm += (j < row) ? R * rp : 0.f;
-        }
-        ga += __shfl_xor(ga, 1); ga += __shfl_xor(ga, 2); ga += __shfl_xor(ga, 4);
-        gb += __shfl_xor(gb, 1); gb += __shfl_xor(gb, 2); gb += __shfl_xor(gb, 4);
-        gm += __shfl_xor(gm, 1); gm += __shfl_xor(gm, 2); gm += __shfl_xor(gm, 4);
-        if (pt == 0) { s_ga[row] = ga; s_gb[row] = gb; s_gm[row] = gm; }
-    }
-    __syncthreads();
-    if (w == 0) {
+    if (w == 4) {
         // vectors (lane i = token i): reverse of b_i = alpha_i b_{i-1} + beta_i m_i, a_i = alpha_i a_{i-1},
         // m_i = mu_i m_{i-1}, with a^-_i = a_{i-1}, b^-_i = b_{i-1}:
         //   db_i = Db_i + alpha_{i+1} db_{i+1},  da_i = Da_i + alpha_{i+1} da_{i+1},
@@ -439,24 +429,63 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
             dS_M += s_red[ww][1];
             dM_M += s_red[ww][2];
         }
+        const float t_da = total(P_DA), t_db = total(P_DB), t_dam = total(P_DAM), t_dbm = total(P_DBM);
+        dalk = total(P_DALK);
+        detk = total(P_DETK);
         const int li = lane;
         const float al_next = __shfl_down(g_al, 1), mu_next = __shfl_down(g_mu, 1);
-        const float dbm_dn = __shfl_down(tot[P_DBM], 1), dam_dn = __shfl_down(tot[P_DAM], 1);
+        const float dbm_dn = __shfl_down(t_dbm, 1), dam_dn = __shfl_down(t_dam, 1);
         const float dbm_next = (li < 63) ? dbm_dn : -dS_M;
         const float dam_next = (li < 63) ? dam_dn : dS_S;
-        float cb = (li < 63) ? al_next : 0.f, db = tot[P_DB] + dbm_next;
+        float cb = (li < 63) ? al_next : 0.f;
+        db = t_db + dbm_next;
         scan_affine_rev(cb, db);
-        float ca = (li < 63) ? al_next : 0.f, da = tot[P_DA] + dam_next;
+        float ca = (li < 63) ? al_next : 0.f;
+        da = t_da + dam_next;
         scan_affine_rev(ca, da);
-        float cm = (li < 63) ? mu_next : 0.f, dm = (li == 63 ? dM_M : 0.f) + g_be * db;
+        float cm = (li < 63) ? mu_next : 0.f;
+        dm = (li == 63 ? dM_M : 0.f) + g_be * db;
         scan_affine_rev(cm, dm);
+    }
+    __syncthreads(); // segment top rows exchanged; every partial sum has been read (their space is reused now)
+    if (w < 4) coef_scan_reverse_part2(LDG, w, rr, sTop, sTopC, sGa, sRa);
+    __syncthreads();
+    {
+        // dalpha_i += sum_{j<i} G_ij Gamma_{i-1,j};  dbeta_i += sum_{j<=i} G_ij Rho_ij;
+        // dmu_i += sum_{j<i} R_ij Rho_{i-1,j}: 8 threads per row, 8 consecutive columns each;
+        // G, R, Gamma, Rho are zero above the diagonal
+        const int row = tid >> 3, pt = tid & 7, rowm = row > 0 ? row - 1 : 0;
+        float ga = 0.f, gb = 0.f, gm = 0.f;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int j = pt * 8 + u * 4;
+            const f32x4 G = *reinterpret_cast<const f32x4 *>(&sGa[row * LDG + j]);
+            const f32x4 R = *reinterpret_cast<const f32x4 *>(&sRa[row * LDG + j]);
+            const f32x4 rho = *reinterpret_cast<const f32x4 *>(&sRho[row * LDG + j]);
+            const f32x4 gp = *reinterpret_cast<const f32x4 *>(&sG[rowm * LDG + j]);
+            const f32x4 rp = *reinterpret_cast<const f32x4 *>(&sRho[rowm * LDG + j]);
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                gb += G[x] * rho[x];
+                ga += (j + x < row) ? G[x] * gp[x] : 0.f;
+                gm += (j + x < row) ? R[x] * rp[x] : 0.f;
+            }
+        }
+        ga += __shfl_xor(ga, 1); ga += __shfl_xor(ga, 2); ga += __shfl_xor(ga, 4);
+        gb += __shfl_xor(gb, 1); gb += __shfl_xor(gb, 2); gb += __shfl_xor(gb, 4);
+        gm += __shfl_xor(gm, 1); gm += __shfl_xor(gm, 2); gm += __shfl_xor(gm, 4);
+        if (pt == 0) { s_ga[row] = ga; s_gb[row] = gb; s_gm[row] = gm; }
+    }
+    __syncthreads();
+    if (w == 4) {
+        const int li = lane;
         const float aprev = __shfl_up(pa, 1), bprev = __shfl_up(pb, 1), mprev = __shfl_up(pm, 1);
         const float a_prev = (li > 0) ? aprev : 1.f, b_prev = (li > 0) ? bprev : 0.f, m_prev = (li > 0) ? mprev : 1.f;
         const unsigned g = (unsigned)(li * d.H);
-        *at32(a.dalpha + tok0, g) = s_ga[li] + db * b_prev + da * a_prev + tot[P_DALK];
+        *at32(a.dalpha + tok0, g) = s_ga[li] + db * b_prev + da * a_prev + dalk;
         *at32(a.dbeta + tok0, g) = s_gb[li] + db * pm;
         *at32(a.dmu + tok0, g) = s_gm[li] + dm * m_prev;
-        if (a.deta) *at32(a.deta + tok0, g) = tot[P_DETK];
+        if (a.deta) *at32(a.deta + tok0, g) = detk;
     }
 }
 
