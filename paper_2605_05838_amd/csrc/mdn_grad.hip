@@ -182,19 +182,9 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     Frag fq[KSK]; // phase A B fragments of q (no LDS copy): row = token i
 #pragma unroll
     for (int s = 0; s < KSK; ++s) fq[s] = O::load(at32(qg, i * rsk + s * O::KSTEP + kg * E));
-    Frag aK[KS2], aQ[KS2]; // this wave's rows of K^T, Q^T
-#pragma unroll
-    for (int s = 0; s < KS2; ++s) {
-        aK[s] = O::load(at32(KTg, (unsigned)kblk<T>(DK, kt * 16 + r, s * O::KSTEP + kg * E)));
-        aQ[s] = O::load(at32(QTg, (unsigned)kblk<T>(DK, kt * 16 + r, s * O::KSTEP + kg * E)));
-    }
-    Frag fS[KSV], fM[KSV], fdS[KSV], fdM[KSV];
-    load_state(fS, Sg);
 
     // ---------------- phase 0: forward coefficients (needs only the gates): waves 0-3 the matrices Gamma, Rho
-    //                  (16 rows each), wave 4 the vectors by wave scans.  Meanwhile waves 6, 7 start the
-    //                  token tiles on their way to LDS; a wave with such a transfer pending would wait for
-    //                  it at its next LDS instruction, so that block comes last in program order.
+    //                  (16 rows each), wave 4 the vectors by wave scans
     float pa = 0.f, pm = 0.f, pb = 0.f; // a_lane, m_lane, b_lane (wave 4)
     if (w < 4) {
         float gC, rC;
@@ -215,6 +205,8 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
         s_a[lane] = pa;
         s_b[lane] = pb;
     }
+    // waves 6, 7 start the token tiles on their way to LDS.  (Last in program order before the barrier: a wave
+    // that has such a transfer pending, also only in the compiler's view of it, waits at its next LDS instruction.)
     if (STAGED && w >= 6) {
         dma_token_tile<T, D>(sVt, vtg, rsv, w - 6, lane);
         dma_token_tile<T, D>(sK, kgl, rsk, w - 6, lane);
@@ -223,7 +215,17 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     }
     const T *tVt = STAGED ? sVt : vtg, *tK = STAGED ? sK : kgl, *tDR = STAGED ? sDR : drg, *tDO = STAGED ? sDO : dog;
     const int ldV = (int)rsv, ldK = (int)rsk; // row strides of the global tiles (fp32 path)
-    __syncthreads(); // token tiles landed, coefficients ready
+    __syncthreads(); // token tiles and q fragments landed, coefficients ready
+    // what the later phases read goes on its way now, in order of use
+    Frag aK[KS2], aQ[KS2]; // this wave's rows of K^T, Q^T
+#pragma unroll
+    for (int s = 0; s < KS2; ++s) {
+        aK[s] = O::load(at32(KTg, (unsigned)kblk<T>(DK, kt * 16 + r, s * O::KSTEP + kg * E)));
+        aQ[s] = O::load(at32(QTg, (unsigned)kblk<T>(DK, kt * 16 + r, s * O::KSTEP + kg * E)));
+    }
+    Frag fS[KSV], fM[KSV], fdS[KSV], fdM[KSV];
+    load_state(fS, Sg);
+    sched_fence();
 
     // ---------------- phase A: the four 64x64 products (transposed: rows j, column i) and the
     //                  masked matrices built from them
