@@ -30,8 +30,10 @@ template <typename T, int DK, int MV> struct RevOps {
     typename O::Frag bmT[KS2];         // stage 1: Bm^T row i0 + r
     typename O::Frag tT[KS2];          // stage 2: T^T row i0 + r
     typename O::Frag qT[ND][KS2], yT[ND][KS2], zT[ND][KS2]; // stage 2: rows (dk) of this wave's state columns
-    f32x4 dO[MV];                      // dO[token i0 + r][4 consecutive dv]
-    float sa, sb, gc, rc;
+    // (kept exactly as loaded: arithmetic on a freshly loaded value would make the wave wait for it, and for
+    //  every load issued before it, at fetch time instead of one chunk later)
+    typename Raw4<T>::type dO[MV];     // dO[token i0 + r][4 consecutive dv], storage form
+    float sa, sb, gc, rc;              // a_i, b_i, Gamma_C eta, Rho_C eta
     float aC, bC, mC;
 };
 
@@ -44,8 +46,8 @@ __device__ __forceinline__ void fetch_chunk(RevOps<T, DK, DVB / 16> &c, const Di
     const size_t blk = (size_t)bh * d.N + n;
     const size_t tok = ((size_t)b * d.T + (size_t)n * 64 + i) * d.H + h;
     const float *coef = a.coef + blk * (kCoefRows * 64);
-    c.sa = d.scale * coef[COEF_A * 64 + i];
-    c.sb = d.scale * coef[COEF_B * 64 + i];
+    c.sa = coef[COEF_A * 64 + i];
+    c.sb = coef[COEF_B * 64 + i];
     c.gc = coef[COEF_GC * 64 + i];
     c.rc = coef[COEF_RC * 64 + i];
     c.aC = coef[COEF_SCALAR * 64 + 0];
@@ -71,7 +73,7 @@ __device__ __forceinline__ void fetch_chunk(RevOps<T, DK, DVB / 16> &c, const Di
         }
     const T *og = static_cast<const T *>(a.dO) + tok * DV + dv0 + kg * 4;
 #pragma unroll
-    for (int mv = 0; mv < DVB / 16; ++mv) c.dO[mv] = load4(og + mv * 16);
+    for (int mv = 0; mv < DVB / 16; ++mv) c.dO[mv] = load4_raw(og + mv * 16);
 }
 
 template <typename T, int DK, int DV, int DVB>
@@ -92,9 +94,6 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
     const int b = bh / d.H, h = bh % d.H, dv0 = blkv * DVB;
     const int lane = lane_id(), w = wave_id(), r = lane & 15, kg = lane >> 4, i = w * 16 + r;
 
-    CO cur;
-    fetch_chunk<T, DK, DV, DVB>(cur, d, a, bh, b, h, d.N - 1, dv0);
-
     // element x of tile (mv, nd): dS[dk = (w*ND + nd)*16 + r][dv = mv*16 + kg*4 + x]
     f32x4 accS[MV][ND], accM[MV][ND];
 #pragma unroll
@@ -106,9 +105,9 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
             accM[mv][nd] = a.dM_final ? *reinterpret_cast<const f32x4 *>(a.dM_final + g) : f32x4{0.f, 0.f, 0.f, 0.f};
         }
 
-    for (int n = d.N - 1; n >= 0; --n) {
+    // one chunk: the operands of chunk n are in `cur`; those of chunk n-1 go on their way into `nxt`
+    auto step = [&](int n, const CO &cur, CO &nxt) {
         const size_t blk = (size_t)bh * d.N + n;
-        CO nxt;
         fetch_chunk<T, DK, DV, DVB>(nxt, d, a, bh, b, h, n > 0 ? n - 1 : 0, dv0);
 
         // adjoints of this chunk's END states: operand copy to LDS, storage copy to HBM
@@ -132,15 +131,18 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
         }
         // dO^T slice of this chunk in three scalings
 #pragma unroll
-        for (int mv = 0; mv < MV; ++mv)
+        for (int mv = 0; mv < MV; ++mv) {
+            const f32x4 dOw = widen4(cur.dO[mv]);
+            const float sa = d.scale * cur.sa, sb = d.scale * cur.sb;
 #pragma unroll
             for (int x = 0; x < 4; ++x) {
                 const int dv = mv * 16 + kg * 4 + x;
-                const float v = cur.dO[mv][x];
+                const float v = dOw[x];
                 sO0[dv * LDV + i] = from_f32<T>(v);
-                sOa[dv * LDV + i] = from_f32<T>(cur.sa * v);
-                sOb[dv * LDV + i] = from_f32<T>(-cur.sb * v);
+                sOa[dv * LDV + i] = from_f32<T>(sa * v);
+                sOb[dv * LDV + i] = from_f32<T>(-sb * v);
             }
+        }
         __syncthreads();
 
         // ---------------- stage 1: dV~^T for token j = i
@@ -209,7 +211,18 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
             for (int mv = 0; mv < MV; ++mv) store4(dvg + mv * 16, dR[mv]);
         }
         __syncthreads();
-        cur = nxt;
+    };
+    // two operand sets used alternately: handing one set over to the other by assignment would touch
+    // every register of the set that was just requested, i.e. wait for all of its loads
+    {
+        CO opsA, opsB;
+        fetch_chunk<T, DK, DV, DVB>(opsA, d, a, bh, b, h, d.N - 1, dv0);
+        int n = d.N - 1;
+        for (; n >= 1; n -= 2) {
+            step(n, opsA, opsB);
+            step(n - 1, opsB, opsA);
+        }
+        if (n == 0) step(0, opsA, opsB);
     }
 
 #pragma unroll

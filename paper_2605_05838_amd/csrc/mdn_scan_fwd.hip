@@ -36,8 +36,10 @@ template <typename T, int DK, int MV> struct ChunkOps {
     typename O::Frag y[KS], z[KS], q[KS]; // stage 1: rows (token i0 + r) of -Y, Z, Q
     typename O::Frag bm[KS2];             // stage 2: Bm row i0 + r
     typename O::Frag kt[ND][KS2];         // stage 2: K^T rows (dk) of this wave's state columns
-    f32x4 u[MV];                          // U[token i0 + r][4 consecutive dv] (V~ in reconstruction)
-    float sa, sb, gc, rc;                 // scale a_i, scale b_i, Gamma_C eta, Rho_C eta for token i0 + r
+    // (everything below is kept exactly as loaded: arithmetic on a freshly loaded value would make the wave wait
+    //  for it, and for every load issued before it, at fetch time instead of one chunk later)
+    typename Raw4<T>::type u[MV];         // U[token i0 + r][4 consecutive dv] (V~ in reconstruction), storage form
+    float sa, sb, gc, rc;                 // a_i, b_i, Gamma_C eta, Rho_C eta for token i0 + r
     float aC, bC, mC;
 };
 
@@ -53,8 +55,8 @@ __device__ __forceinline__ void fetch_chunk(ChunkOps<T, DK, DVB / 16> &c, const 
     c.gc = coef[COEF_GC * 64 + i];
     c.rc = coef[COEF_RC * 64 + i];
     if (!REBUILD) {
-        c.sa = d.scale * coef[COEF_A * 64 + i];
-        c.sb = d.scale * coef[COEF_B * 64 + i];
+        c.sa = coef[COEF_A * 64 + i];
+        c.sb = coef[COEF_B * 64 + i];
     }
     c.aC = coef[COEF_SCALAR * 64 + 0];
     c.bC = coef[COEF_SCALAR * 64 + 1];
@@ -82,12 +84,12 @@ __device__ __forceinline__ void fetch_chunk(ChunkOps<T, DK, DVB / 16> &c, const 
         for (int s = 0; s < CO::KS2; ++s) c.bm[s] = O::load(Bg + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL));
         const T *Ug = static_cast<const T *>(a.U) + blk * (64 * DV);
 #pragma unroll
-        for (int mv = 0; mv < DVB / 16; ++mv) c.u[mv] = load4(Ug + vblk(64, i, dv0 + mv * 16 + kg * 4));
+        for (int mv = 0; mv < DVB / 16; ++mv) c.u[mv] = load4_raw(Ug + vblk(64, i, dv0 + mv * 16 + kg * 4));
     } else {
         // reconstruction reads the saved V~ where the forward reads U
         const T *vs = static_cast<const T *>(a.vt_saved) + tok * DV + dv0 + kg * 4;
 #pragma unroll
-        for (int mv = 0; mv < DVB / 16; ++mv) c.u[mv] = load4(vs + mv * 16);
+        for (int mv = 0; mv < DVB / 16; ++mv) c.u[mv] = load4_raw(vs + mv * 16);
     }
 }
 
@@ -168,7 +170,7 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
         if (!REBUILD) {
             f32x4 accV[MV], accOS[MV], accOM[MV];
 #pragma unroll
-            for (int mv = 0; mv < MV; ++mv) accV[mv] = cur.u[mv];
+            for (int mv = 0; mv < MV; ++mv) accV[mv] = widen4(cur.u[mv]);
             zero_acc(accOS);
             zero_acc(accOM);
             const T *sp = sSt + r * LDST + kg * O::EPL;
@@ -186,7 +188,7 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
             }
 #pragma unroll
             for (int mv = 0; mv < MV; ++mv) {
-                accO[mv] = cur.sa * accOS[mv] - cur.sb * accOM[mv];
+                accO[mv] = d.scale * (cur.sa * accOS[mv] - cur.sb * accOM[mv]);
 #pragma unroll
                 for (int x = 0; x < 4; ++x) vt[mv][x] = rounded<T>(accV[mv][x]);
             }
@@ -197,7 +199,7 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
             }
         } else {
 #pragma unroll
-            for (int mv = 0; mv < MV; ++mv) vt[mv] = cur.u[mv];
+            for (int mv = 0; mv < MV; ++mv) vt[mv] = widen4(cur.u[mv]);
         }
         // V~^T to LDS in the three scalings of stage 2
 #pragma unroll
@@ -357,7 +359,7 @@ __global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a)
         // stage 1
         f32x4 accO[MV], vt[MV], accV[MV], accOS[MV], accOM[MV];
 #pragma unroll
-        for (int mv = 0; mv < MV; ++mv) accV[mv] = cur.u[mv];
+        for (int mv = 0; mv < MV; ++mv) accV[mv] = widen4(cur.u[mv]);
         zero_acc(accOS);
         zero_acc(accOM);
         const T *sp = sSt + r * LDST + kg * O::EPL;
@@ -379,7 +381,7 @@ __global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a)
         }
 #pragma unroll
         for (int mv = 0; mv < MV; ++mv) {
-            accO[mv] = cur.sa * accOS[mv] - cur.sb * accOM[mv];
+            accO[mv] = d.scale * (cur.sa * accOS[mv] - cur.sb * accOM[mv]);
 #pragma unroll
             for (int x = 0; x < 4; ++x) vt[mv][x] = rounded<T>(accV[mv][x]);
         }
