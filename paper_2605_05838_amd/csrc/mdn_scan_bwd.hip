@@ -37,43 +37,68 @@ template <typename T, int DK, int MV> struct RevOps {
     float aC, bC, mC;
 };
 
-template <typename T, int DK, int DV, int DVB>
-__device__ __forceinline__ void fetch_chunk(RevOps<T, DK, DVB / 16> &c, const Dims &d, const ScanBwdArgs &a, int bh,
-                                            int b, int h, int n, int dv0) {
+// The operands of one chunk are requested in NPART portions spread over the work on the previous chunk: a
+// wave that issues them all at once sits at the issue until the memory pipeline has taken them (the time
+// to move a chunk's operands into the CU), with its matrix work waiting behind.
+constexpr int NPART = 6;
+template <typename T, int DK, int DV, int DVB, int P>
+__device__ __forceinline__ void fetch_part(RevOps<T, DK, DVB / 16> &c, const Dims &d, const ScanBwdArgs &a, int bh, int b,
+                                           int h, int n, int dv0) {
     typedef Op<T> O;
     typedef RevOps<T, DK, DVB / 16> CO;
     const int lane = lane_id(), w = wave_id(), r = lane & 15, kg = lane >> 4, i = w * 16 + r;
     const size_t blk = (size_t)bh * d.N + n;
     const size_t tok = ((size_t)b * d.T + (size_t)n * 64 + i) * d.H + h;
-    const float *coef = a.coef + blk * (kCoefRows * 64);
-    c.sa = coef[COEF_A * 64 + i];
-    c.sb = coef[COEF_B * 64 + i];
-    c.gc = coef[COEF_GC * 64 + i];
-    c.rc = coef[COEF_RC * 64 + i];
-    c.aC = coef[COEF_SCALAR * 64 + 0];
-    c.bC = coef[COEF_SCALAR * 64 + 1];
-    c.mC = coef[COEF_SCALAR * 64 + 2];
-    const T *kp = static_cast<const T *>(a.k) + tok * DK + kg * O::EPL;
+    if (P == 0) {
+        const float *coef = a.coef + blk * (kCoefRows * 64);
+        c.sa = coef[COEF_A * 64 + i];
+        c.sb = coef[COEF_B * 64 + i];
+        c.gc = coef[COEF_GC * 64 + i];
+        c.rc = coef[COEF_RC * 64 + i];
+        c.aC = coef[COEF_SCALAR * 64 + 0];
+        c.bC = coef[COEF_SCALAR * 64 + 1];
+        c.mC = coef[COEF_SCALAR * 64 + 2];
+        const T *og = static_cast<const T *>(a.dO) + tok * DV + dv0 + kg * 4;
 #pragma unroll
-    for (int s = 0; s < CO::KS; ++s) c.k[s] = O::load(kp + s * O::KSTEP);
-    const T *bp = static_cast<const T *>(a.BmT) + blk * 4096, *tp = static_cast<const T *>(a.TmT) + blk * 4096;
-#pragma unroll
-    for (int s = 0; s < CO::KS2; ++s) {
-        c.bmT[s] = O::load(bp + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL));
-        c.tT[s] = O::load(tp + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL));
+        for (int mv = 0; mv < DVB / 16; ++mv) c.dO[mv] = load4_raw(og + mv * 16);
     }
+    if (P == 1) {
+        const T *kp = static_cast<const T *>(a.k) + tok * DK + kg * O::EPL;
 #pragma unroll
-    for (int nd = 0; nd < CO::ND; ++nd)
+        for (int s = 0; s < CO::KS; ++s) c.k[s] = O::load(kp + s * O::KSTEP);
+    }
+    if (P == 2) {
+        const T *bp = static_cast<const T *>(a.BmT) + blk * 4096, *tp = static_cast<const T *>(a.TmT) + blk * 4096;
 #pragma unroll
         for (int s = 0; s < CO::KS2; ++s) {
-            const size_t off = blk * (DK * 64) + kblk<T>(DK, (w * CO::ND + nd) * 16 + r, s * O::KSTEP + kg * O::EPL);
-            c.qT[nd][s] = O::load(static_cast<const T *>(a.QT) + off);
-            c.yT[nd][s] = O::load(static_cast<const T *>(a.nYT) + off);
-            c.zT[nd][s] = O::load(static_cast<const T *>(a.ZT) + off);
+            c.bmT[s] = O::load(bp + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL));
+            c.tT[s] = O::load(tp + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL));
         }
-    const T *og = static_cast<const T *>(a.dO) + tok * DV + dv0 + kg * 4;
+    }
+    if (P >= 3) {
+        const T *src = static_cast<const T *>(P == 3 ? a.QT : P == 4 ? a.nYT : a.ZT) + blk * (DK * 64);
 #pragma unroll
-    for (int mv = 0; mv < DVB / 16; ++mv) c.dO[mv] = load4_raw(og + mv * 16);
+        for (int nd = 0; nd < CO::ND; ++nd)
+#pragma unroll
+            for (int s = 0; s < CO::KS2; ++s) {
+                const typename O::Frag f = O::load(src + kblk<T>(DK, (w * CO::ND + nd) * 16 + r, s * O::KSTEP + kg * O::EPL));
+                if (P == 3) c.qT[nd][s] = f;
+                if (P == 4) c.yT[nd][s] = f;
+                if (P == 5) c.zT[nd][s] = f;
+            }
+    }
+    __builtin_amdgcn_sched_barrier(0); // the portion leaves here, not where the scheduler would gather the loads
+}
+
+template <typename T, int DK, int DV, int DVB>
+__device__ __forceinline__ void fetch_chunk(RevOps<T, DK, DVB / 16> &c, const Dims &d, const ScanBwdArgs &a, int bh,
+                                            int b, int h, int n, int dv0) {
+    fetch_part<T, DK, DV, DVB, 0>(c, d, a, bh, b, h, n, dv0);
+    fetch_part<T, DK, DV, DVB, 1>(c, d, a, bh, b, h, n, dv0);
+    fetch_part<T, DK, DV, DVB, 2>(c, d, a, bh, b, h, n, dv0);
+    fetch_part<T, DK, DV, DVB, 3>(c, d, a, bh, b, h, n, dv0);
+    fetch_part<T, DK, DV, DVB, 4>(c, d, a, bh, b, h, n, dv0);
+    fetch_part<T, DK, DV, DVB, 5>(c, d, a, bh, b, h, n, dv0);
 }
 
 template <typename T, int DK, int DV, int DVB>
@@ -108,7 +133,8 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
     // one chunk: the operands of chunk n are in `cur`; those of chunk n-1 go on their way into `nxt`
     auto step = [&](int n, const CO &cur, CO &nxt) {
         const size_t blk = (size_t)bh * d.N + n;
-        fetch_chunk<T, DK, DV, DVB>(nxt, d, a, bh, b, h, n > 0 ? n - 1 : 0, dv0);
+        const int nn = n > 0 ? n - 1 : 0;
+        fetch_part<T, DK, DV, DVB, 0>(nxt, d, a, bh, b, h, nn, dv0);
 
         // adjoints of this chunk's END states: operand copy to LDS, storage copy to HBM
         {
@@ -129,6 +155,7 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
                     }
                 }
         }
+        fetch_part<T, DK, DV, DVB, 1>(nxt, d, a, bh, b, h, nn, dv0);
         // dO^T slice of this chunk in three scalings
 #pragma unroll
         for (int mv = 0; mv < MV; ++mv) {
@@ -157,6 +184,7 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
 #pragma unroll
                 for (int mv = 0; mv < MV; ++mv)
                     accD[mv] = O::mma(O::load(op + mv * 16 * LDV + s * O::KSTEP), cur.bmT[s], accD[mv]);
+            fetch_part<T, DK, DV, DVB, 2>(nxt, d, a, bh, b, h, nn, dv0);
             const T *sp = sD + r * LDST + kg * O::EPL;
 #pragma unroll
             for (int s = 0; s < CO::KS; ++s)
@@ -165,6 +193,7 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
                     x1[mv] = O::mma(O::load(sp + mv * 16 * LDST + s * O::KSTEP), cur.k[s], x1[mv]);
                     x2[mv] = O::mma(O::load(sp + mv * 16 * LDST + DK + s * O::KSTEP), cur.k[s], x2[mv]);
                 }
+            fetch_part<T, DK, DV, DVB, 3>(nxt, d, a, bh, b, h, nn, dv0);
 #pragma unroll
             for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
@@ -189,8 +218,10 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
                 }
             const T *oap = sOa + r * LDV + kg * O::EPL, *obp = sOb + r * LDV + kg * O::EPL,
                     *dvp = sDV + r * LDV + kg * O::EPL;
+            fetch_part<T, DK, DV, DVB, 4>(nxt, d, a, bh, b, h, nn, dv0);
 #pragma unroll
-            for (int s = 0; s < CO::KS2; ++s)
+            for (int s = 0; s < CO::KS2; ++s) {
+                if (s == CO::KS2 / 2) fetch_part<T, DK, DV, DVB, 5>(nxt, d, a, bh, b, h, nn, dv0);
 #pragma unroll
                 for (int mv = 0; mv < MV; ++mv) {
                     const typename O::Frag fa = O::load(oap + mv * 16 * LDV + s * O::KSTEP);
@@ -205,6 +236,7 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
                         accM[mv][nd] = O::mma(fd, cur.zT[nd][s], accM[mv][nd]);
                     }
                 }
+            }
             const size_t tok = ((size_t)b * d.T + (size_t)n * 64 + i) * d.H + h;
             T *dvg = static_cast<T *>(a.dv) + tok * DV + dv0 + kg * 4;
 #pragma unroll
