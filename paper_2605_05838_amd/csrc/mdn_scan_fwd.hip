@@ -43,54 +43,77 @@ template <typename T, int DK, int MV> struct ChunkOps {
     float aC, bC, mC;
 };
 
-template <typename T, int DK, int DV, int DVB, bool REBUILD, bool NO_STAGE1 = false>
-__device__ __forceinline__ void fetch_chunk(ChunkOps<T, DK, DVB / 16> &c, const Dims &d, const ScanFwdArgs &a,
-                                            int bh, int b, int h, int n, int dv0) {
+// The operands of one chunk are requested in portions (P = 0..4) spread over the work on the previous
+// chunk: a wave that issues them all at once sits at the issue until the memory pipeline has taken them
+// (the time to move a chunk's operands into the CU), with its matrix work waiting behind.
+template <typename T, int DK, int DV, int DVB, bool REBUILD, bool NO_STAGE1, int P>
+__device__ __forceinline__ void fetch_part(ChunkOps<T, DK, DVB / 16> &c, const Dims &d, const ScanFwdArgs &a, int bh,
+                                           int b, int h, int n, int dv0) {
     typedef Op<T> O;
     typedef ChunkOps<T, DK, DVB / 16> CO;
-    const int lane = lane_id(), w = wave_id(), r = lane & 15, kg = lane >> 4, i = w * 16 + r;
+    const int lane = lane_id(), w = wave_id() & 3, r = lane & 15, kg = lane >> 4, i = w * 16 + r;
     const size_t blk = (size_t)bh * d.N + n;
     const size_t tok = ((size_t)b * d.T + (size_t)n * 64 + i) * d.H + h;
-    const float *coef = a.coef + blk * (kCoefRows * 64);
-    c.gc = coef[COEF_GC * 64 + i];
-    c.rc = coef[COEF_RC * 64 + i];
-    if (!REBUILD) {
-        c.sa = coef[COEF_A * 64 + i];
-        c.sb = coef[COEF_B * 64 + i];
+    if (P == 0) {
+        const float *coef = a.coef + blk * (kCoefRows * 64);
+        c.gc = coef[COEF_GC * 64 + i];
+        c.rc = coef[COEF_RC * 64 + i];
+        if (!REBUILD) {
+            c.sa = coef[COEF_A * 64 + i];
+            c.sb = coef[COEF_B * 64 + i];
+        }
+        c.aC = coef[COEF_SCALAR * 64 + 0];
+        c.bC = coef[COEF_SCALAR * 64 + 1];
+        c.mC = coef[COEF_SCALAR * 64 + 2];
+        if (!REBUILD) {
+            const T *Ug = static_cast<const T *>(a.U) + blk * (64 * DV);
+#pragma unroll
+            for (int mv = 0; mv < DVB / 16; ++mv) c.u[mv] = load4_raw(Ug + vblk(64, i, dv0 + mv * 16 + kg * 4));
+        } else {
+            // reconstruction reads the saved V~ where the forward reads U
+            const T *vs = static_cast<const T *>(a.vt_saved) + tok * DV + dv0 + kg * 4;
+#pragma unroll
+            for (int mv = 0; mv < DVB / 16; ++mv) c.u[mv] = load4_raw(vs + mv * 16);
+        }
     }
-    c.aC = coef[COEF_SCALAR * 64 + 0];
-    c.bC = coef[COEF_SCALAR * 64 + 1];
-    c.mC = coef[COEF_SCALAR * 64 + 2];
-    const T *KTg = static_cast<const T *>(a.KT) + blk * (DK * 64);
-#pragma unroll
-    for (int nd = 0; nd < CO::ND; ++nd)
-#pragma unroll
-        for (int s = 0; s < CO::KS2; ++s)
-            c.kt[nd][s] = O::load(KTg + kblk<T>(DK, (w * CO::ND + nd) * 16 + r, s * O::KSTEP + kg * O::EPL));
-    if (!REBUILD) {
-        const T *Yg = static_cast<const T *>(a.nY) + blk * (64 * DK);
-        const T *Zg = static_cast<const T *>(a.Z) + blk * (64 * DK);
+    if (P == 1 && !REBUILD) {
         const T *Qg = static_cast<const T *>(a.q) + tok * DK + kg * O::EPL;
 #pragma unroll
-        for (int s = 0; s < CO::KS; ++s) {
-            if (!NO_STAGE1) {
-                c.y[s] = O::load(Yg + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL));
-                c.z[s] = O::load(Zg + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL));
-            }
-            c.q[s] = O::load(Qg + s * O::KSTEP);
-        }
+        for (int s = 0; s < CO::KS; ++s) c.q[s] = O::load(Qg + s * O::KSTEP);
+    }
+    if (P == 2) {
+        const T *KTg = static_cast<const T *>(a.KT) + blk * (DK * 64);
+#pragma unroll
+        for (int nd = 0; nd < CO::ND; ++nd)
+#pragma unroll
+            for (int s = 0; s < CO::KS2; ++s)
+                c.kt[nd][s] = O::load(KTg + kblk<T>(DK, (w * CO::ND + nd) * 16 + r, s * O::KSTEP + kg * O::EPL));
+    }
+    if (P == 3 && !REBUILD) {
         const T *Bg = static_cast<const T *>(a.Bm) + blk * 4096;
 #pragma unroll
         for (int s = 0; s < CO::KS2; ++s) c.bm[s] = O::load(Bg + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL));
-        const T *Ug = static_cast<const T *>(a.U) + blk * (64 * DV);
-#pragma unroll
-        for (int mv = 0; mv < DVB / 16; ++mv) c.u[mv] = load4_raw(Ug + vblk(64, i, dv0 + mv * 16 + kg * 4));
-    } else {
-        // reconstruction reads the saved V~ where the forward reads U
-        const T *vs = static_cast<const T *>(a.vt_saved) + tok * DV + dv0 + kg * 4;
-#pragma unroll
-        for (int mv = 0; mv < DVB / 16; ++mv) c.u[mv] = load4_raw(vs + mv * 16);
     }
+    if (P == 4 && !REBUILD && !NO_STAGE1) {
+        const T *Yg = static_cast<const T *>(a.nY) + blk * (64 * DK);
+        const T *Zg = static_cast<const T *>(a.Z) + blk * (64 * DK);
+#pragma unroll
+        for (int s = 0; s < CO::KS; ++s) {
+            c.y[s] = O::load(Yg + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL));
+            c.z[s] = O::load(Zg + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL));
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0); // the portion leaves here, not where the scheduler would gather the loads
+}
+
+template <typename T, int DK, int DV, int DVB, bool REBUILD, bool NO_STAGE1 = false>
+__device__ __forceinline__ void fetch_chunk(ChunkOps<T, DK, DVB / 16> &c, const Dims &d, const ScanFwdArgs &a,
+                                            int bh, int b, int h, int n, int dv0) {
+    fetch_part<T, DK, DV, DVB, REBUILD, NO_STAGE1, 0>(c, d, a, bh, b, h, n, dv0);
+    fetch_part<T, DK, DV, DVB, REBUILD, NO_STAGE1, 4>(c, d, a, bh, b, h, n, dv0);
+    fetch_part<T, DK, DV, DVB, REBUILD, NO_STAGE1, 1>(c, d, a, bh, b, h, n, dv0);
+    fetch_part<T, DK, DV, DVB, REBUILD, NO_STAGE1, 3>(c, d, a, bh, b, h, n, dv0);
+    fetch_part<T, DK, DV, DVB, REBUILD, NO_STAGE1, 2>(c, d, a, bh, b, h, n, dv0);
 }
 
 // accumulator element x of tile (mv, nd) of wave w is S[dk = (w*ND + nd)*16 + r][dv = mv*16 + kg*4 + x]
@@ -130,9 +153,6 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
     const int b = bh / d.H, h = bh % d.H, dv0 = blkv * DVB;
     const int lane = lane_id(), w = wave_id(), r = lane & 15, kg = lane >> 4, i = w * 16 + r;
 
-    CO cur;
-    fetch_chunk<T, DK, DV, DVB, REBUILD>(cur, d, a, bh, b, h, 0, dv0);
-
     f32x4 accS[MV][ND], accM[MV][ND];
 #pragma unroll
     for (int mv = 0; mv < MV; ++mv)
@@ -145,13 +165,12 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
     if (!REBUILD) publish_state<T, DK, MV>(sSt, LDST, accS, accM);
     __syncthreads();
 
-    for (int n = 0; n < d.N; ++n) {
+    // one chunk: its operands are in `cur`; those of the next chunk go on their way into `nxt`, portion by portion
+    auto step = [&](int n, const CO &cur, CO &nxt) {
         const size_t blk = (size_t)bh * d.N + n;
         const size_t tok = ((size_t)b * d.T + (size_t)n * 64 + i) * d.H + h;
-
-        // next chunk's operands: in flight while this chunk computes
-        CO nxt;
-        fetch_chunk<T, DK, DV, DVB, REBUILD>(nxt, d, a, bh, b, h, (n + 1 < d.N) ? n + 1 : n, dv0);
+        const int nn = (n + 1 < d.N) ? n + 1 : n;
+        fetch_part<T, DK, DV, DVB, REBUILD, false, 0>(nxt, d, a, bh, b, h, nn, dv0);
 
         if (a.states_saved) {
             T *st = static_cast<T *>(a.states_saved) + blk * (2 * DK * DV);
@@ -165,6 +184,7 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
                 }
         }
 
+        fetch_part<T, DK, DV, DVB, REBUILD, false, 4>(nxt, d, a, bh, b, h, nn, dv0);
         // ---------------- stage 1: V~^T and the inter-chunk read-outs for token i
         f32x4 accO[MV], vt[MV]; // vt = V~ rounded to the storage type
         if (!REBUILD) {
@@ -186,6 +206,7 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
                     accOM[mv] = O::mma(fm, cur.q[s], accOM[mv]);
                 }
             }
+            fetch_part<T, DK, DV, DVB, REBUILD, false, 1>(nxt, d, a, bh, b, h, nn, dv0);
 #pragma unroll
             for (int mv = 0; mv < MV; ++mv) {
                 accO[mv] = d.scale * (cur.sa * accOS[mv] - cur.sb * accOM[mv]);
@@ -216,6 +237,7 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
         // ---------------- stage 2: intra-chunk output and the state update
         const T *v0p = sV0 + r * LDV + kg * O::EPL, *vgp = sVg + r * LDV + kg * O::EPL,
                 *vrp = sVr + r * LDV + kg * O::EPL;
+        fetch_part<T, DK, DV, DVB, REBUILD, false, 2>(nxt, d, a, bh, b, h, nn, dv0);
 #pragma unroll
         for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
@@ -239,6 +261,7 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
                     accO[mv] = O::mma(f0, cur.bm[s], accO[mv]);
                 }
             }
+        fetch_part<T, DK, DV, DVB, REBUILD, false, 3>(nxt, d, a, bh, b, h, nn, dv0);
         if (!REBUILD) {
             publish_state<T, DK, MV>(sSt, LDST, accS, accM);
             T *og = static_cast<T *>(a.o) + tok * DV + dv0 + kg * 4;
@@ -246,7 +269,18 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
             for (int mv = 0; mv < MV; ++mv) store4(og + mv * 16, accO[mv]);
         }
         __syncthreads();
-        cur = nxt;
+    };
+    // two operand sets used alternately: handing one set over to the other by assignment would touch every
+    // register of the set that was just requested, i.e. wait for all of its loads
+    {
+        CO opsA, opsB;
+        fetch_chunk<T, DK, DV, DVB, REBUILD>(opsA, d, a, bh, b, h, 0, dv0);
+        int n = 0;
+        for (; n + 1 < d.N; n += 2) {
+            step(n, opsA, opsB);
+            step(n + 1, opsB, opsA);
+        }
+        if (n < d.N) step(n, opsA, opsB);
     }
 
     if (!REBUILD) {
@@ -323,9 +357,6 @@ __global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a)
 
     // ---------------- compute waves
     const int w = wv, i = w * 16 + r;
-    CO cur;
-    fetch_chunk<T, DK, DV, DVB, false, true>(cur, d, a, bh, b, h, 0, dv0);
-
     f32x4 accS[MV][ND], accM[MV][ND];
 #pragma unroll
     for (int mv = 0; mv < MV; ++mv)
@@ -338,11 +369,11 @@ __global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a)
     publish_state<T, DK, MV>(sSt, LDST, accS, accM);
     __syncthreads();
 
-    for (int n = 0; n < d.N; ++n) {
+    auto step = [&](int n, const CO &cur, CO &nxt) {
         const size_t blk = (size_t)bh * d.N + n;
         const size_t tok = ((size_t)b * d.T + (size_t)n * 64 + i) * d.H + h;
-        CO nxt;
-        fetch_chunk<T, DK, DV, DVB, false, true>(nxt, d, a, bh, b, h, (n + 1 < d.N) ? n + 1 : n, dv0);
+        const int nn = (n + 1 < d.N) ? n + 1 : n;
+        fetch_part<T, DK, DV, DVB, false, true, 0>(nxt, d, a, bh, b, h, nn, dv0);
 
         if (a.states_saved) {
             T *st = static_cast<T *>(a.states_saved) + blk * (2 * DK * DV);
@@ -356,6 +387,7 @@ __global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a)
                 }
         }
 
+        fetch_part<T, DK, DV, DVB, false, true, 1>(nxt, d, a, bh, b, h, nn, dv0);
         // stage 1
         f32x4 accO[MV], vt[MV], accV[MV], accOS[MV], accOM[MV];
 #pragma unroll
@@ -404,6 +436,7 @@ __global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a)
         // stage 2
         const T *v0p = sV0 + r * LDV + kg * O::EPL, *vgp = sVg + r * LDV + kg * O::EPL,
                 *vrp = sVr + r * LDV + kg * O::EPL;
+        fetch_part<T, DK, DV, DVB, false, true, 2>(nxt, d, a, bh, b, h, nn, dv0);
 #pragma unroll
         for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
@@ -425,12 +458,22 @@ __global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a)
                 const typename O::Frag f0 = O::load(v0p + mv * 16 * LDV + s * O::KSTEP);
                 accO[mv] = O::mma(f0, cur.bm[s], accO[mv]);
             }
+        fetch_part<T, DK, DV, DVB, false, true, 3>(nxt, d, a, bh, b, h, nn, dv0);
         publish_state<T, DK, MV>(sSt, LDST, accS, accM);
         T *og = static_cast<T *>(a.o) + tok * DV + dv0 + kg * 4;
 #pragma unroll
         for (int mv = 0; mv < MV; ++mv) store4(og + mv * 16, accO[mv]);
         __syncthreads();
-        cur = nxt;
+    };
+    {
+        CO opsA, opsB; // used alternately (no set is ever copied into the other)
+        fetch_chunk<T, DK, DV, DVB, false, true>(opsA, d, a, bh, b, h, 0, dv0);
+        int n = 0;
+        for (; n + 1 < d.N; n += 2) {
+            step(n, opsA, opsB);
+            step(n + 1, opsB, opsA);
+        }
+        if (n < d.N) step(n, opsA, opsB);
     }
 #pragma unroll
     for (int mv = 0; mv < MV; ++mv)
