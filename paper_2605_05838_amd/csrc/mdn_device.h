@@ -16,6 +16,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace mdn {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -66,6 +68,10 @@ template <typename T> __device__ __forceinline__ T from_f32(float x) { return (T
 template <typename T> __device__ __forceinline__ float rounded(float x) { return to_f32(from_f32<T>(x)); }
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+// value held by lane `src` (a compile-time constant) as a wave-uniform scalar
+__device__ __forceinline__ float lane_value(float v, int src) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), src));
+}
 __device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
 
 // acc[nt] += A(16 x K) * B(K x 16*NT)
@@ -134,6 +140,14 @@ template <typename T> __device__ __forceinline__ size_t kblk(int R, int row, int
 }
 __device__ __forceinline__ size_t vblk(int R, int row, int dv) {
     return ((size_t)(dv >> 4) * R + row) * 16 + (dv & 15);
+}
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>)
+template <int N, int I = 0, typename F> __device__ __forceinline__ void static_for(F &&f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<N, I + 1>(f);
+    }
 }
 
 template <int NT> __device__ __forceinline__ void zero_acc(f32x4 (&acc)[NT]) {

@@ -34,7 +34,7 @@ template <typename T, int DK, int MV> struct RevOps {
     //  every load issued before it, at fetch time instead of one chunk later)
     typename Raw4<T>::type dO[MV];     // dO[token i0 + r][4 consecutive dv], storage form
     float sa, sb, gc, rc;              // a_i, b_i, Gamma_C eta, Rho_C eta
-    float aC, bC, mC;
+    float sc;                          // lane & 3 = 0, 1, 2: a_C, b_C, m_C
 };
 
 // The operands of one chunk are requested in NPART portions spread over the work on the previous chunk: a
@@ -55,9 +55,9 @@ __device__ __forceinline__ void fetch_part(RevOps<T, DK, DVB / 16> &c, const Dim
         c.sb = coef[COEF_B * 64 + i];
         c.gc = coef[COEF_GC * 64 + i];
         c.rc = coef[COEF_RC * 64 + i];
-        c.aC = coef[COEF_SCALAR * 64 + 0];
-        c.bC = coef[COEF_SCALAR * 64 + 1];
-        c.mC = coef[COEF_SCALAR * 64 + 2];
+        // the three chunk scalars through the vector path as well: a scalar load would share its wait counter
+        // with the LDS reads and make the first of those wait for memory
+        c.sc = coef[COEF_SCALAR * 64 + (lane & 3)];
         const T *og = static_cast<const T *>(a.dO) + tok * DV + dv0 + kg * 4;
 #pragma unroll
         for (int mv = 0; mv < DVB / 16; ++mv) c.dO[mv] = load4_raw(og + mv * 16);
@@ -208,13 +208,14 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
         {
             f32x4 dR[MV];
             zero_acc(dR);
+            const float aC = lane_value(cur.sc, 0), bC = lane_value(cur.sc, 1), mC = lane_value(cur.sc, 2);
 #pragma unroll
             for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
                 for (int nd = 0; nd < ND; ++nd) {
                     const f32x4 s = accS[mv][nd], m = accM[mv][nd];
-                    accS[mv][nd] = cur.aC * s;
-                    accM[mv][nd] = cur.mC * m - cur.bC * s;
+                    accS[mv][nd] = aC * s;
+                    accM[mv][nd] = mC * m - bC * s;
                 }
             const T *oap = sOa + r * LDV + kg * O::EPL, *obp = sOb + r * LDV + kg * O::EPL,
                     *dvp = sDV + r * LDV + kg * O::EPL;

@@ -40,7 +40,7 @@ template <typename T, int DK, int MV> struct ChunkOps {
     //  for it, and for every load issued before it, at fetch time instead of one chunk later)
     typename Raw4<T>::type u[MV];         // U[token i0 + r][4 consecutive dv] (V~ in reconstruction), storage form
     float sa, sb, gc, rc;                 // a_i, b_i, Gamma_C eta, Rho_C eta for token i0 + r
-    float aC, bC, mC;
+    float sc;                          // lane & 3 = 0, 1, 2: a_C, b_C, m_C
 };
 
 // The operands of one chunk are requested in portions (P = 0..4) spread over the work on the previous
@@ -62,9 +62,9 @@ __device__ __forceinline__ void fetch_part(ChunkOps<T, DK, DVB / 16> &c, const D
             c.sa = coef[COEF_A * 64 + i];
             c.sb = coef[COEF_B * 64 + i];
         }
-        c.aC = coef[COEF_SCALAR * 64 + 0];
-        c.bC = coef[COEF_SCALAR * 64 + 1];
-        c.mC = coef[COEF_SCALAR * 64 + 2];
+        // the three chunk scalars through the vector path as well: a scalar load would share its wait counter
+        // with the LDS reads and make the first of those wait for memory
+        c.sc = coef[COEF_SCALAR * 64 + (lane & 3)];
         if (!REBUILD) {
             const T *Ug = static_cast<const T *>(a.U) + blk * (64 * DV);
 #pragma unroll
@@ -238,12 +238,13 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
         const T *v0p = sV0 + r * LDV + kg * O::EPL, *vgp = sVg + r * LDV + kg * O::EPL,
                 *vrp = sVr + r * LDV + kg * O::EPL;
         fetch_part<T, DK, DV, DVB, REBUILD, false, 2>(nxt, d, a, bh, b, h, nn, dv0);
+        const float aC = lane_value(cur.sc, 0), bC = lane_value(cur.sc, 1), mC = lane_value(cur.sc, 2);
 #pragma unroll
         for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
             for (int nd = 0; nd < ND; ++nd) {
-                accS[mv][nd] = cur.aC * accS[mv][nd] - cur.bC * accM[mv][nd];
-                accM[mv][nd] = cur.mC * accM[mv][nd];
+                accS[mv][nd] = aC * accS[mv][nd] - bC * accM[mv][nd];
+                accM[mv][nd] = mC * accM[mv][nd];
             }
 #pragma unroll
         for (int s = 0; s < CO::KS2; ++s)
@@ -375,18 +376,18 @@ __global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a)
         const int nn = (n + 1 < d.N) ? n + 1 : n;
         fetch_part<T, DK, DV, DVB, false, true, 0>(nxt, d, a, bh, b, h, nn, dv0);
 
-        if (a.states_saved) {
-            T *st = static_cast<T *>(a.states_saved) + blk * (2 * DK * DV);
-#pragma unroll
-            for (int mv = 0; mv < MV; ++mv)
-#pragma unroll
-                for (int nd = 0; nd < ND; ++nd) {
-                    const size_t off = vblk(DK, (w * ND + nd) * 16 + r, dv0 + mv * 16 + kg * 4);
-                    store4(st + off, accS[mv][nd]);
-                    store4(st + DK * DV + off, accM[mv][nd]);
-                }
-        }
-
+        // the chunk-start states leave in portions too, between the steps of stage 1 (all workgroups walk the
+        // chunks in step: whatever a workgroup writes in one burst, all of them write at that moment)
+        constexpr int NST = 2 * MV * ND;
+        T *st = static_cast<T *>(a.states_saved) + blk * (2 * DK * DV);
+        auto store_state = [&](auto IDX) {
+            constexpr int idx = decltype(IDX)::value, t = idx >> 1, mv = t / ND, nd = t % ND;
+            const size_t off = vblk(DK, (w * ND + nd) * 16 + r, dv0 + mv * 16 + kg * 4);
+            if (idx & 1)
+                store4(st + DK * DV + off, accM[mv][nd]);
+            else
+                store4(st + off, accS[mv][nd]);
+        };
         fetch_part<T, DK, DV, DVB, false, true, 1>(nxt, d, a, bh, b, h, nn, dv0);
         // stage 1
         f32x4 accO[MV], vt[MV], accV[MV], accOS[MV], accOM[MV];
@@ -409,6 +410,12 @@ __global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a)
                 accOS[mv] = O::mma(fs, fq, accOS[mv]);
                 accV[mv] = O::mma(fm, fz, accV[mv]);
                 accOM[mv] = O::mma(fm, fq, accOM[mv]);
+            }
+            if (a.states_saved) {
+                static_for<NST>([&](auto IDX) {
+                    if (decltype(IDX)::value * KS / NST == s) store_state(IDX);
+                });
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
 #pragma unroll
@@ -437,12 +444,13 @@ __global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a)
         const T *v0p = sV0 + r * LDV + kg * O::EPL, *vgp = sVg + r * LDV + kg * O::EPL,
                 *vrp = sVr + r * LDV + kg * O::EPL;
         fetch_part<T, DK, DV, DVB, false, true, 2>(nxt, d, a, bh, b, h, nn, dv0);
+        const float aC = lane_value(cur.sc, 0), bC = lane_value(cur.sc, 1), mC = lane_value(cur.sc, 2);
 #pragma unroll
         for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
             for (int nd = 0; nd < ND; ++nd) {
-                accS[mv][nd] = cur.aC * accS[mv][nd] - cur.bC * accM[mv][nd];
-                accM[mv][nd] = cur.mC * accM[mv][nd];
+                accS[mv][nd] = aC * accS[mv][nd] - bC * accM[mv][nd];
+                accM[mv][nd] = mC * accM[mv][nd];
             }
 #pragma unroll
         for (int s = 0; s < CO::KS2; ++s)
