@@ -27,12 +27,14 @@ namespace {
 constexpr int LDA = 68; // row stride (floats) of the fp32 A / T matrix in LDS
 constexpr int LDG = 65; // row stride (floats) of Gamma in LDS
 
-// LDS [R][ld] (first 64 columns) -> global, kblk layout of an [R][64] operand
+// LDS [R][ld] (first 64 columns) -> global, kblk layout of an [R][64] operand.  Consecutive lanes write
+// consecutive 16-byte pieces of the destination (the pieces of one row's contraction step, then the next
+// row's): every store instruction covers whole cache lines.
 template <typename T>
 __device__ __forceinline__ void store_tile_64cols(T *dst, const T *src, int ld, int rows, int tid) {
-    constexpr int E = Op<T>::EPL, CPR = 64 / E;
+    constexpr int E = Op<T>::EPL, PPS = Op<T>::KSTEP / E, CPR = 64 / E; // pieces per contraction step, per row
     for (int c = tid; c < rows * CPR; c += kThreads) {
-        const int row = c % rows, cc = c / rows;
+        const int p = c % PPS, row = (c / PPS) % rows, ks = c / (PPS * rows), cc = ks * PPS + p;
         *reinterpret_cast<Vec16<T> *>(dst + kblk<T>(rows, row, cc * E)) =
             *reinterpret_cast<const Vec16<T> *>(src + row * ld + cc * E);
     }
@@ -106,29 +108,34 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
                      : *reinterpret_cast<const Vec16<T> *>(qg + row * rsk + cc * E);
     }
 
-    // ---- gate coefficients: wave 0.  Vectors by wave scans (lane i = token i), matrices by a column scan.
-    if (w == 0) {
+    // ---- gate coefficients.  Matrix Gamma: every wave 16 rows (column scans started from segment maps);
+    //      vectors: wave 0, by wave scans (lane i = token i).
+    {
         const size_t g = tok0 + (size_t)lane * d.H;
         const float al = a.alpha[g], be = a.beta[g], mu = a.mu[g], et = a.eta ? a.eta[g] : 1.f;
-        const float pa = scan_prod(al), pm = scan_prod(mu);
-        float c = al, pb = be * pm;
-        scan_affine_fwd(c, pb); // b_i = alpha_i b_{i-1} + beta_i m_i
-        s_al[lane] = al;
-        s_be[lane] = be;
-        s_et[lane] = et;
-        s_a[lane] = pa;
-        s_b[lane] = pb;
+        if (w == 0) {
+            const float pa = scan_prod(al), pm = scan_prod(mu);
+            float c = al, pb = be * pm;
+            scan_affine_fwd(c, pb); // b_i = alpha_i b_{i-1} + beta_i m_i
+            s_al[lane] = al;
+            s_be[lane] = be;
+            s_et[lane] = et;
+            s_a[lane] = pa;
+            s_b[lane] = pb;
+            coef[COEF_A * 64 + lane] = pa;
+            coef[COEF_B * 64 + lane] = pb;
+            coef[COEF_ETA * 64 + lane] = et;
+            if (lane == 63) {
+                coef[COEF_SCALAR * 64 + 0] = pa;
+                coef[COEF_SCALAR * 64 + 1] = pb;
+                coef[COEF_SCALAR * 64 + 2] = pm;
+            }
+        }
         float gC, rC;
-        coef_column_scan<false>(al, be, mu, sG, nullptr, LDG, gC, rC);
-        coef[COEF_A * 64 + lane] = pa;
-        coef[COEF_B * 64 + lane] = pb;
-        coef[COEF_GC * 64 + lane] = gC * et;
-        coef[COEF_RC * 64 + lane] = rC * et;
-        coef[COEF_ETA * 64 + lane] = et;
-        if (lane == 63) {
-            coef[COEF_SCALAR * 64 + 0] = pa;
-            coef[COEF_SCALAR * 64 + 1] = pb;
-            coef[COEF_SCALAR * 64 + 2] = pm;
+        coef_column_scan_blocked<false>(al, be, mu, sG, nullptr, LDG, w, gC, rC);
+        if (w == 3) {
+            coef[COEF_GC * 64 + lane] = gC * et;
+            coef[COEF_RC * 64 + lane] = rC * et;
         }
     }
     __syncthreads();
@@ -210,8 +217,9 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
     if (BWD) {
         T *tt = static_cast<T *>(a.TmT) + blk * 4096; // T^T: row j, k = i
         constexpr int E = O::EPL;
+        constexpr int PPS = O::KSTEP / E; // 16-byte pieces per contraction step: consecutive lanes, consecutive pieces
         for (int c = tid; c < 64 * (64 / E); c += kThreads) {
-            const int jj = c & 63, cc = c >> 6;
+            const int pp = c % PPS, jj = (c / PPS) & 63, cc = (c / (PPS * 64)) * PPS + pp;
             Vec16<T> v;
 #pragma unroll
             for (int e = 0; e < E; ++e) v.e[e] = from_f32<T>(sA[(cc * E + e) * LDA + jj]);
