@@ -67,6 +67,45 @@ def read_traffic(path):
     return out
 
 
+def decode_bench(args, torch, binding, synth):
+    """One decode token per sequence through mdn_recurrent_step: HBM-bound on reading and writing S and M (fp32)."""
+    from gpu_util import to_dev
+    B, H, dk = args.decode, 16, 128
+    w = synth.custom(B=B, T=64, H=H, dk=dk, dv=dk, dtype="bf16", seed=7)
+    t = to_dev(w)
+    tok = {k: t[k][:, :1].contiguous() for k in ("q", "k", "v", "beta", "alpha", "mu")}
+    S = torch.zeros((B, H, dk, dk), dtype=torch.float32, device="cuda")
+    M = torch.zeros_like(S)
+    o = None
+
+    def step():
+        nonlocal o
+        o = binding.mdn_recurrent_step(tok["q"], tok["k"], tok["v"], tok["beta"], tok["alpha"], tok["mu"], S, M,
+                                       scale=w.scale, out=o)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    binding.profile_begin()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms, cnt = binding.profile_end()["recurrent"]
+    avg = ms / max(cnt, 1)
+    nbytes = 4 * B * H * dk * dk * 4  # S and M, read and written once, fp32
+    gbs = nbytes / (avg * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "MDN recurrent step (decode) tokens/sec", "value": round(B * args.steps / wall, 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall * 1e3 / args.steps, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"decode_B{B}_H{H}_d{dk}", "B": B, "T": 1, "H": H, "dk": dk, "dv": dk},
+        "roofline": {"kernel": "recurrent", "bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS,
+                     "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 5), "traffic": None},
+        "kernels": {"recurrent": {"avg_ms": round(avg, 4), "launches": cnt}}, "cpu_baseline": None}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -79,6 +118,9 @@ def main():
                          "states and recomputes its chunk-local operands (default: the forward keeps both)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket kernels with HIP events")
+    ap.add_argument("--decode", type=int, default=0, metavar="BATCH",
+                    help="instead of the training step, time mdn_recurrent_step: one token for BATCH sequences x 16 heads "
+                         "x 128x128 states (the decode regime of the recurrent form); prints its own JSON line")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="after the timed region, also run one plain device copy of this many MiB (the known-size "
                          "kernel that the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled by)")
@@ -97,6 +139,8 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
+    if args.decode:
+        return decode_bench(args, torch, binding, synth)
     w = synth.config(args.config)
     do_bwd = w.backward and not args.forward_only
     t = to_dev(w)

@@ -3,7 +3,10 @@
 //     e = v - S^T (alpha k);  M = mu M - eta k e^T;  S = alpha S - beta M;  o = scale S^T q
 // HBM-bound on reading and writing the two fp32 states once per call; plain fp32 FMA, no MFMA
 // (a GEMV and a rank-1 update per token).  Grid = batch*head x dv/32; a workgroup owns 32 state
-// columns, thread (slice, col) holds dk/8 rows of S and M for its column in registers.
+// columns; thread (slice, column group) holds dk/32 rows x 4 consecutive columns of S and M in
+// registers, so every state access is a 16-byte vector and every wave-level access covers whole
+// 128-byte lines.  The two reductions over dk go over the 8 slices of a wave by shuffles, then over
+// the 4 waves through LDS.
 #include "mdn_device.h"
 #include "mdn_kernels.h"
 
@@ -11,58 +14,71 @@ namespace mdn {
 
 namespace {
 
-constexpr int RCOLS = 32, RSLICES = kThreads / RCOLS;
+constexpr int RCOLS = 32, RCG = RCOLS / 4, RSLICES = kThreads / RCG; // 8 column groups x 32 slices
+
+// sum over the 8 slices of a wave (lane = slice_in_wave * 8 + column group)
+__device__ __forceinline__ f32x4 reduce_slices(f32x4 v) {
+#pragma unroll
+    for (int m = 8; m < 64; m <<= 1)
+#pragma unroll
+        for (int x = 0; x < 4; ++x) v[x] += __shfl_xor(v[x], m);
+    return v;
+}
 
 template <typename T, int DK, int DV>
 __global__ __launch_bounds__(kThreads) void recurrent_kernel(Dims d, RecurrentArgs a) {
     constexpr int ROWS = DK / RSLICES;
-    __shared__ float redE[RSLICES][RCOLS], redO[RSLICES][RCOLS];
+    static_assert(ROWS >= 1, "dk too small for the slice count");
+    __shared__ __align__(16) float redE[4][RCOLS], redO[4][RCOLS];
     const int bh = blockIdx.x, b = bh / d.H, h = bh % d.H;
-    const int col = threadIdx.x % RCOLS, sl = threadIdx.x / RCOLS;
-    const int j = blockIdx.y * RCOLS + col, r0 = sl * ROWS;
-    float S[ROWS], M[ROWS];
+    const int cg = threadIdx.x % RCG, sl = threadIdx.x / RCG, w = wave_id();
+    const int j = blockIdx.y * RCOLS + cg * 4, r0 = sl * ROWS;
+    f32x4 S[ROWS], M[ROWS];
     float *Sg = a.S + ((size_t)bh * DK + r0) * DV + j, *Mg = a.M + ((size_t)bh * DK + r0) * DV + j;
 #pragma unroll
     for (int i = 0; i < ROWS; ++i) {
-        S[i] = Sg[(size_t)i * DV];
-        M[i] = Mg[(size_t)i * DV];
+        S[i] = *reinterpret_cast<const f32x4 *>(Sg + (size_t)i * DV);
+        M[i] = *reinterpret_cast<const f32x4 *>(Mg + (size_t)i * DV);
     }
     for (int t = 0; t < d.T; ++t) {
         const size_t g = ((size_t)b * d.T + t) * d.H + h;
         const T *kt = static_cast<const T *>(a.k) + g * DK + r0;
         const T *qt = static_cast<const T *>(a.q) + g * DK + r0;
         const float al = a.alpha[g], be = a.beta[g], mu = a.mu[g], et = a.eta ? a.eta[g] : 1.f;
-        float kk[ROWS], part = 0.f;
+        float kk[ROWS];
+        f32x4 part = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int i = 0; i < ROWS; ++i) {
             kk[i] = to_f32(kt[i]);
-            part += al * kk[i] * S[i];
+            part += (al * kk[i]) * S[i];
         }
-        redE[sl][col] = part;
+        part = reduce_slices(part);
+        if ((threadIdx.x & 63) < RCG) *reinterpret_cast<f32x4 *>(&redE[w][cg * 4]) = part;
         __syncthreads();
-        float e = to_f32(static_cast<const T *>(a.v)[g * DV + j]);
+        f32x4 e = load4(static_cast<const T *>(a.v) + g * DV + j);
 #pragma unroll
-        for (int s = 0; s < RSLICES; ++s) e -= redE[s][col];
-        float po = 0.f;
+        for (int ww = 0; ww < 4; ++ww) e -= *reinterpret_cast<const f32x4 *>(&redE[ww][cg * 4]);
+        f32x4 po = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int i = 0; i < ROWS; ++i) {
-            M[i] = mu * M[i] - et * kk[i] * e;
+            M[i] = mu * M[i] - (et * kk[i]) * e;
             S[i] = al * S[i] - be * M[i];
             po += to_f32(qt[i]) * S[i];
         }
-        redO[sl][col] = po;
+        po = reduce_slices(po);
+        if ((threadIdx.x & 63) < RCG) *reinterpret_cast<f32x4 *>(&redO[w][cg * 4]) = po;
         __syncthreads();
         if (sl == 0) {
-            float o = 0.f;
+            f32x4 o = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int s = 0; s < RSLICES; ++s) o += redO[s][col];
-            static_cast<T *>(a.o)[g * DV + j] = from_f32<T>(d.scale * o);
+            for (int ww = 0; ww < 4; ++ww) o += *reinterpret_cast<const f32x4 *>(&redO[ww][cg * 4]);
+            store4(static_cast<T *>(a.o) + g * DV + j, d.scale * o);
         }
     }
 #pragma unroll
     for (int i = 0; i < ROWS; ++i) {
-        Sg[(size_t)i * DV] = S[i];
-        Mg[(size_t)i * DV] = M[i];
+        *reinterpret_cast<f32x4 *>(Sg + (size_t)i * DV) = S[i];
+        *reinterpret_cast<f32x4 *>(Mg + (size_t)i * DV) = M[i];
     }
 }
 
