@@ -48,7 +48,7 @@ __device__ __forceinline__ void scan_affine_rev(float &c, float &d) {
     }
 }
 
-// value held by lane `src` (compile-time constant after unrolling) as a wave-uniform scalar
+// value held by lane `src` (wave-uniform: a constant or a scalar) as a wave-uniform scalar
 __device__ __forceinline__ float lane_bcast(float v, int src) {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), src));
 }
@@ -114,20 +114,15 @@ __device__ __forceinline__ void coef_column_scan_blocked(float al, float be, flo
         g = 0.f;
         rho = 0.f;
     }
-    // lane_bcast needs a compile-time lane: one unrolled copy of the 16 steps per segment
+    // (w is wave-uniform: the lane selects below are scalar operands)
 #pragma unroll
-    for (int seg = 0; seg < 4; ++seg) {
-        if (seg == w) {
-#pragma unroll
-            for (int u = 0; u < 16; ++u) {
-                const int i = seg * 16 + u;
-                const float a_i = lane_bcast(al, i), b_i = lane_bcast(be, i), m_i = lane_bcast(mu, i);
-                rho = (i == j) ? 1.f : rho * m_i;
-                g = a_i * g + b_i * rho;
-                sG[i * ldg + j] = g;
-                if (WANT_RHO) sRho[i * ldg + j] = rho;
-            }
-        }
+    for (int u = 0; u < 16; ++u) {
+        const int i = w * 16 + u;
+        const float a_i = lane_bcast(al, i), b_i = lane_bcast(be, i), m_i = lane_bcast(mu, i);
+        rho = (i == j) ? 1.f : rho * m_i;
+        g = a_i * g + b_i * rho;
+        sG[i * ldg + j] = g;
+        if (WANT_RHO) sRho[i * ldg + j] = rho;
     }
     gC = g;
     rC = rho;
@@ -185,49 +180,43 @@ struct RevScanRows {
 __device__ __forceinline__ void coef_scan_reverse_part1(float al, float be, float mu, const float *sD1, const float *sD2,
                                                         float dgc, float drc, int ldg, int w, RevScanRows &rr, float *sTop,
                                                         float *sTopC) {
-    const int j = lane_id();
+    const int j = lane_id(), i0 = w * 16; // (w is wave-uniform: the lane selects below are scalar operands)
+    float dir[16];
 #pragma unroll
-    for (int seg = 0; seg < 4; ++seg) {
-        if (seg == w) {
-            const int i0 = seg * 16;
-            float dir[16];
+    for (int u = 0; u < 16; ++u) dir[u] = sD1[(i0 + u) * ldg + j] + sD2[(i0 + u + 1) * ldg + j];
+    float cg = 0.f, cr = 0.f;           // alpha_{i+1} Gloc_{i+1,j}, mu_{i+1} Rloc_{i+1,j}
+    float gc = 1.f, ec = 0.f, mc = 1.f; // coefficients of the row below the current one
 #pragma unroll
-            for (int u = 0; u < 16; ++u) dir[u] = sD1[(i0 + u) * ldg + j] + sD2[(i0 + u + 1) * ldg + j];
-            float cg = 0.f, cr = 0.f;           // alpha_{i+1} Gloc_{i+1,j}, mu_{i+1} Rloc_{i+1,j}
-            float gc = 1.f, ec = 0.f, mc = 1.f; // coefficients of the row below the current one
-#pragma unroll
-            for (int u = 15; u >= 0; --u) {
-                const int i = i0 + u;
-                // gates of row i+1 (nothing below row 63: whatever stands here is multiplied by a zero incoming pair)
-                const float a_n = (i < 63) ? lane_bcast(al, (i + 1) & 63) : 0.f, m_n = (i < 63) ? lane_bcast(mu, (i + 1) & 63) : 0.f;
-                const float b_i = lane_bcast(be, i);
-                float G = dir[u] + cg, R = cr;
-                if (i == 63) {
-                    G += dgc;
-                    R += drc;
-                }
-                R += b_i * G;
-                rr.G[u] = G;
-                rr.R[u] = R;
-                gc = a_n * gc;
-                ec = b_i * gc + m_n * ec;
-                mc = m_n * mc;
-                rr.gc[u] = gc;
-                rr.ec[u] = ec;
-                rr.mc[u] = mc;
-                if (u > 0) {
-                    cg = lane_bcast(al, i) * G;
-                    cr = lane_bcast(mu, i) * R;
-                }
-            }
-            sTop[(seg * 2 + 0) * 64 + j] = (j <= i0) ? rr.G[0] : 0.f;
-            sTop[(seg * 2 + 1) * 64 + j] = (j <= i0) ? rr.R[0] : 0.f;
-            if (j == 0) {
-                sTopC[seg * 3 + 0] = rr.gc[0];
-                sTopC[seg * 3 + 1] = rr.ec[0];
-                sTopC[seg * 3 + 2] = rr.mc[0];
-            }
+    for (int u = 15; u >= 0; --u) {
+        const int i = i0 + u;
+        // gates of row i+1 (nothing below row 63: whatever stands here is multiplied by a zero incoming pair)
+        const float a_n = (i < 63) ? lane_bcast(al, (i + 1) & 63) : 0.f, m_n = (i < 63) ? lane_bcast(mu, (i + 1) & 63) : 0.f;
+        const float b_i = lane_bcast(be, i);
+        float G = dir[u] + cg, R = cr;
+        if (i == 63) {
+            G += dgc;
+            R += drc;
         }
+        R += b_i * G;
+        rr.G[u] = G;
+        rr.R[u] = R;
+        gc = a_n * gc;
+        ec = b_i * gc + m_n * ec;
+        mc = m_n * mc;
+        rr.gc[u] = gc;
+        rr.ec[u] = ec;
+        rr.mc[u] = mc;
+        if (u > 0) {
+            cg = lane_bcast(al, i) * G;
+            cr = lane_bcast(mu, i) * R;
+        }
+    }
+    sTop[(w * 2 + 0) * 64 + j] = (j <= i0) ? rr.G[0] : 0.f;
+    sTop[(w * 2 + 1) * 64 + j] = (j <= i0) ? rr.R[0] : 0.f;
+    if (j == 0) {
+        sTopC[w * 3 + 0] = rr.gc[0];
+        sTopC[w * 3 + 1] = rr.ec[0];
+        sTopC[w * 3 + 2] = rr.mc[0];
     }
 }
 
