@@ -24,7 +24,12 @@
  *     and fp32 states) or MDN_DTYPE_F32 (fp32 MFMA throughout).
  *   - All pointers must be 16-byte aligned.  dk, dv in {64, 128}; C = 64; T % C == 0.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
- *     enqueued asynchronously on it; no call synchronises.
+ *     ordered after what the stream already holds and is complete when the stream reaches the
+ *     end of the call; no call synchronises.  When the serial scans would leave at least half
+ *     of the GPU idle (few batch*head pairs, many chunks) mdn_chunk_fwd / mdn_chunk_bwd split
+ *     the sequence into segments and run the chunk-parallel kernel of one segment beside the
+ *     scan of its neighbour on a second stream that the library creates once per device
+ *     (default priority) and joins back into `stream` with events; see mdn_set_segments().
  *   - Return value: MDN_OK (0) or a negative MDN_ERR_* code; nothing is launched when an
  *     error is returned from validation.  NaN/Inf in the inputs propagate, they are not detected.
  */
@@ -146,6 +151,14 @@ enum {
 };
 int mdn_profile_begin(void);
 int mdn_profile_end(float *ms, int *launches, int n);
+
+/*
+ * Number of segments mdn_chunk_fwd / mdn_chunk_bwd split the sequence into: k >= 1 forces k
+ * (1 = never split; capped at N/4 and at 16), 0 restores the automatic choice.  A tuning and
+ * test knob: results do not depend on it (states cross a segment boundary in fp32, exactly as
+ * they are carried inside a scan).  Returns the previous setting.
+ */
+int mdn_set_segments(int k);
 
 /* Static, human-readable text for a return code. */
 const char *mdn_strerror(int code);

@@ -19,7 +19,7 @@ MDN_WS_FWD, MDN_WS_BWD = 0, 1
 
 EXPORTS = ("mdn_version", "mdn_strerror", "mdn_workspace_bytes", "mdn_saved_states_bytes",
            "mdn_saved_operands_bytes", "mdn_chunk_fwd",
-           "mdn_chunk_bwd", "mdn_recurrent_step", "mdn_profile_begin", "mdn_profile_end")
+           "mdn_chunk_bwd", "mdn_recurrent_step", "mdn_profile_begin", "mdn_profile_end", "mdn_set_segments")
 
 KERNEL_NAMES = ("intra_fwd", "scan_fwd", "intra_bwd", "rebuild", "scan_bwd", "grad", "recurrent")
 
@@ -64,6 +64,8 @@ def load_library():
     lib.mdn_profile_begin.restype = ctypes.c_int
     lib.mdn_profile_end.restype = ctypes.c_int
     lib.mdn_profile_end.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int), ctypes.c_int]
+    lib.mdn_set_segments.restype = ctypes.c_int
+    lib.mdn_set_segments.argtypes = [ctypes.c_int]
     _lib = lib
     return lib
 
@@ -213,6 +215,11 @@ def mdn_recurrent_step(q, k, v, beta, alpha, mu, S, M, eta=None, scale=None, out
                                 _ptr(o), _stream())
     _check(rc, "mdn_recurrent_step")
     return o
+
+
+def set_segments(k):
+    """Force the number of sequence segments of mdn_chunk_fwd / mdn_chunk_bwd (0 = automatic); returns the old value."""
+    return int(load_library().mdn_set_segments(int(k)))
 
 
 def profile_begin():

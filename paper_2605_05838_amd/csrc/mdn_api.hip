@@ -22,6 +22,7 @@ int check_shape(const mdn_shape *s, bool chunked, Dims *d) {
     if (chunked && (s->C != 64 || s->T % 64 != 0)) return MDN_ERR_SHAPE;
     if ((long long)s->B * s->H > (1 << 24) || (long long)s->B * s->T * s->H > (1LL << 31) - 1) return MDN_ERR_SHAPE;
     d->B = s->B; d->T = s->T; d->H = s->H; d->N = s->T / 64; d->BH = s->B * s->H;
+    d->n0 = 0; d->n1 = d->N;
     d->dk = s->dk; d->dv = s->dv; d->dtype = s->dtype; d->scale = s->scale;
     return MDN_OK;
 }
@@ -40,7 +41,7 @@ struct Carver {
     }
 };
 
-struct FwdWs { float *coef; void *KT, *U, *nY, *Z, *Bm; size_t total; };
+struct FwdWs { float *coef; void *KT, *U, *nY, *Z, *Bm; float *carryS, *carryM; size_t total; };
 
 FwdWs carve_fwd(const Dims &d, void *ws) {
     const size_t es = d.dtype == MDN_DTYPE_F32 ? 4 : 2, nb = (size_t)d.BH * d.N;
@@ -52,6 +53,9 @@ FwdWs carve_fwd(const Dims &d, void *ws) {
     w.nY = c.take(nb * 64 * d.dk * es);
     w.Z = c.take(nb * 64 * d.dk * es);
     w.Bm = c.take(nb * 4096 * es);
+    // states handed from one segment of the sequence to the next when the call is split (see segments())
+    w.carryS = static_cast<float *>(c.take((size_t)d.BH * d.dk * d.dv * sizeof(float)));
+    w.carryM = static_cast<float *>(c.take((size_t)d.BH * d.dk * d.dv * sizeof(float)));
     w.total = c.off;
     return w;
 }
@@ -75,7 +79,7 @@ RevOps carve_rev(const Dims &d, void *p) {
     return w;
 }
 
-struct BwdWs { RevOps ops; void *dstates, *states; size_t total; };
+struct BwdWs { RevOps ops; void *dstates, *states; float *carryS, *carryM; size_t total; };
 
 BwdWs carve_bwd(const Dims &d, void *ws) {
     const size_t es = d.dtype == MDN_DTYPE_F32 ? 4 : 2, nb = (size_t)d.BH * d.N;
@@ -85,6 +89,8 @@ BwdWs carve_bwd(const Dims &d, void *ws) {
     c.off = w.ops.total;
     w.dstates = c.take(nb * 2 * d.dk * d.dv * es);
     w.states = c.take(nb * 2 * d.dk * d.dv * es);
+    w.carryS = static_cast<float *>(c.take((size_t)d.BH * d.dk * d.dv * sizeof(float)));
+    w.carryM = static_cast<float *>(c.take((size_t)d.BH * d.dk * d.dv * sizeof(float)));
     w.total = c.off;
     return w;
 }
@@ -107,11 +113,76 @@ template <typename F> int timed(int id, hipStream_t s, F &&launch) {
     return rc;
 }
 
+// ---- splitting a call into segments of the sequence.  When the serial scans occupy at most half of the CUs
+// (few (batch, head) pairs, long sequences), the chunk-parallel kernel of segment i+1 (forward) or of segment
+// i (backward) runs beside the scan of the neighbouring segment, on a second stream of the library's own:
+// the scan's workgroups leave the other CUs to it.  States cross a segment boundary through two small fp32
+// buffers in the workspace.
+int num_cus() {
+    static const int n = [] {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
+            v = 256;
+        return v;
+    }();
+    return n;
+}
+
+int g_segments = 0; // 0: automatic
+
+int segments(const Dims &d) {
+    int k;
+    if (g_segments > 0) {
+        k = g_segments;
+    } else {
+        // workgroups of a scan launch: one per (batch*head rounded up to 8, block of 32 or 16 dv columns)
+        const bool dvb16 = d.BH * (d.dv / 32) < 192 || (d.dtype == MDN_DTYPE_F32 && d.dk == 128);
+        const int scan_wgs = (d.BH + 7) / 8 * 8 * (d.dv / (dvb16 ? 16 : 32));
+        k = (2 * scan_wgs <= num_cus() && d.N >= 32) ? 8 : 1;
+    }
+    if (k > d.N / 4) k = d.N / 4;
+    return k < 1 ? 1 : (k > 16 ? 16 : k);
+}
+
+struct Side {
+    hipStream_t stream = nullptr;
+    std::vector<hipEvent_t> ev;
+};
+
+// the library's second stream and n events on the current device (created once, default priority)
+Side *side(int n) {
+    static std::vector<Side> per_device(64);
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= (int)per_device.size()) return nullptr;
+    Side &x = per_device[dev];
+    if (!x.stream && hipStreamCreateWithFlags(&x.stream, hipStreamNonBlocking) != hipSuccess) return nullptr;
+    while ((int)x.ev.size() < n) {
+        hipEvent_t e;
+        if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return nullptr;
+        x.ev.push_back(e);
+    }
+    return &x;
+}
+
+Dims segment(const Dims &d, int i, int k) {
+    Dims r = d;
+    r.n0 = (int)((long long)d.N * i / k);
+    r.n1 = (int)((long long)d.N * (i + 1) / k);
+    return r;
+}
+
 } // namespace
 
 extern "C" {
 
 int mdn_version(void) { return 100; }
+
+int mdn_set_segments(int k) {
+    const int prev = g_segments;
+    g_segments = k < 0 ? 0 : k;
+    return prev;
+}
 
 int mdn_profile_begin(void) {
     g_profiling = true;
@@ -204,14 +275,36 @@ int mdn_chunk_fwd(const mdn_shape *shape, const void *q, const void *k, const vo
         const RevOps ro = carve_rev(d, operands_saved);
         ia.coef = ro.coef; ia.KT = ro.KT; ia.QT = ro.QT; ia.nYT = ro.nYT; ia.ZT = ro.ZT; ia.BmT = ro.BmT; ia.TmT = ro.TmT;
     }
-    rc = timed(MDN_KERNEL_INTRA_FWD, s, [&] { return launch_intra(d, operands_saved ? 2 : 0, ia, s); });
-    if (rc) return rc;
-
     ScanFwdArgs sa = {};
     sa.q = q; sa.coef = ia.coef; sa.KT = ia.KT; sa.U = w.U; sa.nY = w.nY; sa.Z = w.Z; sa.Bm = w.Bm;
     sa.S0 = S0; sa.M0 = M0; sa.o = o; sa.vt_saved = vt_saved; sa.states_saved = states_saved;
     sa.S_final = S_final; sa.M_final = M_final;
-    return timed(MDN_KERNEL_SCAN_FWD, s, [&] { return launch_scan_fwd(d, sa, s); });
+    const int mode = operands_saved ? 2 : 0;
+    const int nseg = segments(d);
+    if (nseg == 1) {
+        rc = timed(MDN_KERNEL_INTRA_FWD, s, [&] { return launch_intra(d, mode, ia, s); });
+        if (rc) return rc;
+        return timed(MDN_KERNEL_SCAN_FWD, s, [&] { return launch_scan_fwd(d, sa, s); });
+    }
+    // segments: precompute of segment i+1 on the second stream beside the scan of segment i on the caller's
+    Side *sd = side(nseg + 1);
+    if (!sd) return MDN_ERR_LAUNCH;
+    if (hipEventRecord(sd->ev[nseg], s) != hipSuccess || hipStreamWaitEvent(sd->stream, sd->ev[nseg], 0) != hipSuccess)
+        return MDN_ERR_LAUNCH; // whatever the caller's stream holds so far comes first
+    for (int i = 0; i < nseg; ++i) {
+        const Dims di = segment(d, i, nseg);
+        rc = timed(MDN_KERNEL_INTRA_FWD, sd->stream, [&] { return launch_intra(di, mode, ia, sd->stream); });
+        if (rc) return rc;
+        if (hipEventRecord(sd->ev[i], sd->stream) != hipSuccess || hipStreamWaitEvent(s, sd->ev[i], 0) != hipSuccess)
+            return MDN_ERR_LAUNCH;
+        sa.S0 = i == 0 ? S0 : w.carryS;
+        sa.M0 = i == 0 ? M0 : w.carryM;
+        sa.S_final = i == nseg - 1 ? S_final : w.carryS;
+        sa.M_final = i == nseg - 1 ? M_final : w.carryM;
+        rc = timed(MDN_KERNEL_SCAN_FWD, s, [&] { return launch_scan_fwd(di, sa, s); });
+        if (rc) return rc;
+    }
+    return MDN_OK;
 }
 
 int mdn_chunk_bwd(const mdn_shape *shape, const void *q, const void *k, const void *v, const float *beta,
@@ -261,15 +354,37 @@ int mdn_chunk_bwd(const mdn_shape *shape, const void *q, const void *k, const vo
     sb.k = k; sb.dO = dO; sb.coef = ro.coef; sb.QT = ro.QT; sb.nYT = ro.nYT; sb.ZT = ro.ZT; sb.BmT = ro.BmT;
     sb.TmT = ro.TmT; sb.dS_final = dS_final; sb.dM_final = dM_final; sb.dv = dv; sb.dstates = w.dstates;
     sb.dS0 = dS0; sb.dM0 = dM0;
-    rc = timed(MDN_KERNEL_SCAN_BWD, s, [&] { return launch_scan_bwd(d, sb, s); });
-    if (rc) return rc;
-
     GradArgs ga = {};
     ga.q = q; ga.k = k; ga.alpha = alpha; ga.beta = beta; ga.mu = mu; ga.eta = eta;
     ga.vt_saved = vt_saved; ga.dO = dO; ga.dv = dv; ga.KT = ro.KT; ga.QT = ro.QT;
     ga.states = states; ga.dstates = w.dstates;
     ga.dq = dq; ga.dk = dk; ga.dalpha = dalpha; ga.dbeta = dbeta; ga.dmu = dmu; ga.deta = deta;
-    return timed(MDN_KERNEL_GRAD, s, [&] { return launch_grad(d, ga, s); });
+    const int nseg = segments(d);
+    if (nseg == 1) {
+        rc = timed(MDN_KERNEL_SCAN_BWD, s, [&] { return launch_scan_bwd(d, sb, s); });
+        if (rc) return rc;
+        return timed(MDN_KERNEL_GRAD, s, [&] { return launch_grad(d, ga, s); });
+    }
+    // segments, last first: the gradient kernel of segment i on the second stream beside the reverse scan
+    // of segment i-1 on the caller's; the caller's stream then waits for the last gradient launch
+    Side *sd = side(nseg + 1);
+    if (!sd) return MDN_ERR_LAUNCH;
+    for (int i = nseg - 1; i >= 0; --i) {
+        const Dims di = segment(d, i, nseg);
+        sb.dS_final = i == nseg - 1 ? dS_final : w.carryS;
+        sb.dM_final = i == nseg - 1 ? dM_final : w.carryM;
+        sb.dS0 = i == 0 ? dS0 : w.carryS;
+        sb.dM0 = i == 0 ? dM0 : w.carryM;
+        rc = timed(MDN_KERNEL_SCAN_BWD, s, [&] { return launch_scan_bwd(di, sb, s); });
+        if (rc) return rc;
+        if (hipEventRecord(sd->ev[i], s) != hipSuccess || hipStreamWaitEvent(sd->stream, sd->ev[i], 0) != hipSuccess)
+            return MDN_ERR_LAUNCH;
+        rc = timed(MDN_KERNEL_GRAD, sd->stream, [&] { return launch_grad(di, ga, sd->stream); });
+        if (rc) return rc;
+    }
+    if (hipEventRecord(sd->ev[nseg], sd->stream) != hipSuccess || hipStreamWaitEvent(s, sd->ev[nseg], 0) != hipSuccess)
+        return MDN_ERR_LAUNCH;
+    return MDN_OK;
 }
 
 int mdn_recurrent_step(const mdn_shape *shape, const void *q, const void *k, const void *v, const float *beta,

@@ -132,7 +132,7 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     const int wt = w & 3, hf = w >> 2;    // phase A: token tile, half of the j tiles
     const int kt = w % NKW, tg = w / NKW; // phases B-F: dk tile, token group
     const int i = wt * 16 + r;            // this lane's token (MFMA column) in phase A
-    const int n = blockIdx.x, bh = blockIdx.y, b = bh / d.H, h = bh % d.H;
+    const int n = d.n0 + blockIdx.x, bh = blockIdx.y, b = bh / d.H, h = bh % d.H;
     const size_t tok0 = ((size_t)b * d.T + (size_t)n * 64) * d.H + h;
     const size_t blk = (size_t)bh * d.N + n;
     // per-lane offsets inside the chunk stay 32-bit (a uniform 64-bit base plus a 32-bit lane offset is
@@ -493,7 +493,7 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
 
 template <typename T, int DK, int DV, bool STAGED>
 hipError_t launch_t(const Dims &d, const GradArgs &a, hipStream_t s) {
-    dim3 grid(d.N, d.BH), block(GT);
+    dim3 grid(d.n1 - d.n0, d.BH), block(GT);
     hipLaunchKernelGGL((grad_kernel<T, DK, DV, STAGED>), grid, block, 0, s, d, a);
     return hipGetLastError();
 }

@@ -67,7 +67,7 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
     T *sKT = sR, *sXT = sR + DK * LDT;    // phase B (aliases phase A)
 
     const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
-    const int n = blockIdx.x, bh = blockIdx.y;
+    const int n = d.n0 + blockIdx.x, bh = blockIdx.y;
     const int b = bh / d.H, h = bh % d.H;
     const size_t tok0 = ((size_t)b * d.T + (size_t)n * 64) * d.H + h;
     const size_t blk = (size_t)bh * d.N + n; // chunk-block index into the workspace tensors
@@ -302,7 +302,7 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
 
 template <typename T, int DK, int DV>
 hipError_t launch_intra_t(const Dims &d, int mode, const IntraArgs &a, hipStream_t s) {
-    dim3 grid(d.N, d.BH), block(kThreads);
+    dim3 grid(d.n1 - d.n0, d.BH), block(kThreads);
     if (mode == 0) hipLaunchKernelGGL((intra_kernel<T, DK, DV, 0>), grid, block, 0, s, d, a);
     else if (mode == 1) hipLaunchKernelGGL((intra_kernel<T, DK, DV, 1>), grid, block, 0, s, d, a);
     else hipLaunchKernelGGL((intra_kernel<T, DK, DV, 2>), grid, block, 0, s, d, a);

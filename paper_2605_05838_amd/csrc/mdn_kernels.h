@@ -8,6 +8,7 @@ namespace mdn {
 
 struct Dims {
     int B, T, H, N, BH; // N = T / 64 chunks, BH = B * H
+    int n0, n1;         // chunks [n0, n1) handled by this launch (0, N unless the call is split into segments)
     int dk, dv;
     int dtype; // MDN_DTYPE_*
     float scale;

@@ -133,7 +133,7 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
     // one chunk: the operands of chunk n are in `cur`; those of chunk n-1 go on their way into `nxt`
     auto step = [&](int n, const CO &cur, CO &nxt) {
         const size_t blk = (size_t)bh * d.N + n;
-        const int nn = n > 0 ? n - 1 : 0;
+        const int nn = n > d.n0 ? n - 1 : d.n0;
         fetch_part<T, DK, DV, DVB, 0>(nxt, d, a, bh, b, h, nn, dv0);
 
         // adjoints of this chunk's END states: operand copy to LDS, storage copy to HBM
@@ -249,13 +249,13 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
     // every register of the set that was just requested, i.e. wait for all of its loads
     {
         CO opsA, opsB;
-        fetch_chunk<T, DK, DV, DVB>(opsA, d, a, bh, b, h, d.N - 1, dv0);
-        int n = d.N - 1;
-        for (; n >= 1; n -= 2) {
+        fetch_chunk<T, DK, DV, DVB>(opsA, d, a, bh, b, h, d.n1 - 1, dv0);
+        int n = d.n1 - 1;
+        for (; n >= d.n0 + 1; n -= 2) {
             step(n, opsA, opsB);
             step(n - 1, opsB, opsA);
         }
-        if (n == 0) step(0, opsA, opsB);
+        if (n == d.n0) step(n, opsA, opsB);
     }
 
 #pragma unroll

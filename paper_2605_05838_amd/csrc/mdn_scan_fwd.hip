@@ -169,7 +169,7 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
     auto step = [&](int n, const CO &cur, CO &nxt) {
         const size_t blk = (size_t)bh * d.N + n;
         const size_t tok = ((size_t)b * d.T + (size_t)n * 64 + i) * d.H + h;
-        const int nn = (n + 1 < d.N) ? n + 1 : n;
+        const int nn = (n + 1 < d.n1) ? n + 1 : n;
         fetch_part<T, DK, DV, DVB, REBUILD, false, 0>(nxt, d, a, bh, b, h, nn, dv0);
 
         if (a.states_saved) {
@@ -275,13 +275,13 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
     // register of the set that was just requested, i.e. wait for all of its loads
     {
         CO opsA, opsB;
-        fetch_chunk<T, DK, DV, DVB, REBUILD>(opsA, d, a, bh, b, h, 0, dv0);
-        int n = 0;
-        for (; n + 1 < d.N; n += 2) {
+        fetch_chunk<T, DK, DV, DVB, REBUILD>(opsA, d, a, bh, b, h, d.n0, dv0);
+        int n = d.n0;
+        for (; n + 1 < d.n1; n += 2) {
             step(n, opsA, opsB);
             step(n + 1, opsB, opsA);
         }
-        if (n < d.N) step(n, opsA, opsB);
+        if (n < d.n1) step(n, opsA, opsB);
     }
 
     if (!REBUILD) {
@@ -342,12 +342,12 @@ __global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a)
             }
         };
         // two chunks ahead: while chunk n computes, chunk n+1 is complete or landing and chunk n+2 is issued
-        issue(0, 0);
-        issue(d.N > 1 ? 1 : 0, 1);
+        issue(d.n0, d.n0 % NBUF);
+        issue(d.n0 + 1 < d.n1 ? d.n0 + 1 : d.n0, (d.n0 + 1) % NBUF);
         __builtin_amdgcn_s_waitcnt(0x0F70 | NF); // vmcnt(NF): chunk 0 landed, chunk 1 may still be in flight
         __builtin_amdgcn_s_barrier();
-        for (int n = 0; n < d.N; ++n) {
-            issue((n + 2 < d.N) ? n + 2 : d.N - 1, (n + 2) % NBUF);
+        for (int n = d.n0; n < d.n1; ++n) {
+            issue((n + 2 < d.n1) ? n + 2 : d.n1 - 1, (n + 2) % NBUF);
             __builtin_amdgcn_s_barrier();            // barrier 1 of the chunk
             __builtin_amdgcn_s_waitcnt(0x0F70 | NF); // vmcnt(NF): chunk n+1 landed
             __builtin_amdgcn_s_barrier();            // barrier 2
@@ -373,7 +373,7 @@ __global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a)
     auto step = [&](int n, const CO &cur, CO &nxt) {
         const size_t blk = (size_t)bh * d.N + n;
         const size_t tok = ((size_t)b * d.T + (size_t)n * 64 + i) * d.H + h;
-        const int nn = (n + 1 < d.N) ? n + 1 : n;
+        const int nn = (n + 1 < d.n1) ? n + 1 : n;
         fetch_part<T, DK, DV, DVB, false, true, 0>(nxt, d, a, bh, b, h, nn, dv0);
 
         // the chunk-start states leave in portions too, between the steps of stage 1 (all workgroups walk the
@@ -475,13 +475,13 @@ __global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a)
     };
     {
         CO opsA, opsB; // used alternately (no set is ever copied into the other)
-        fetch_chunk<T, DK, DV, DVB, false, true>(opsA, d, a, bh, b, h, 0, dv0);
-        int n = 0;
-        for (; n + 1 < d.N; n += 2) {
+        fetch_chunk<T, DK, DV, DVB, false, true>(opsA, d, a, bh, b, h, d.n0, dv0);
+        int n = d.n0;
+        for (; n + 1 < d.n1; n += 2) {
             step(n, opsA, opsB);
             step(n + 1, opsB, opsA);
         }
-        if (n < d.N) step(n, opsA, opsB);
+        if (n < d.n1) step(n, opsA, opsB);
     }
 #pragma unroll
     for (int mv = 0; mv < MV; ++mv)

@@ -90,3 +90,36 @@ def test_backward_mu_zero_and_beta_zero_f32():
     w.arrays["mu"][:, ::3] = 0.0
     w.arrays["beta"][:, 7] = 0.0
     check_bwd(w, final_adjoints=True)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype,d,T,nseg", [("bf16", 128, 1280, 4), ("f32", 64, 832, 3), ("bf16", 64, 1024, 16)])
+def test_split_into_segments_on_two_streams_equals_the_unsplit_call(dtype, d, T, nseg):
+    """Splitting the sequence into segments (chunk-parallel kernels beside the scans, states carried across the
+    boundaries in fp32) must not change a single bit of any output, forward or backward."""
+    import torch
+    w = synth.custom(B=1, T=T, H=2, dk=d, dv=d, dtype=dtype, seed=36, backward=True, s0_std=0.1, with_eta=True)
+    t = to_dev(w)
+    dSf = torch.randn_like(t["S0"]) * 0.1
+    dMf = torch.randn_like(t["S0"]) * 0.1
+
+    def run():
+        f = binding.mdn_chunk_fwd(t["q"], t["k"], t["v"], t["beta"], t["alpha"], t["mu"], eta=t["eta"], S0=t["S0"],
+                                  M0=t["M0"], scale=w.scale, save_vt=True, save_states=True, save_operands=True)
+        g = binding.mdn_chunk_bwd(t["q"], t["k"], t["v"], t["beta"], t["alpha"], t["mu"], f["vt"], t["dO"], eta=t["eta"],
+                                  S0=t["S0"], M0=t["M0"], states=f["states"], operands=f["operands"], dS_final=dSf,
+                                  dM_final=dMf, scale=w.scale, want_deta=True, want_dstates=True)
+        torch.cuda.synchronize()
+        return f, g
+
+    old = binding.set_segments(1)
+    try:
+        f1, g1 = run()
+        binding.set_segments(nseg)
+        f2, g2 = run()
+    finally:
+        binding.set_segments(old)
+    for name in ("o", "S", "M", "vt", "states"):
+        assert torch.equal(f1[name], f2[name]), name
+    for name in ("dq", "dk", "dv", "dalpha", "dbeta", "dmu", "deta", "dS0", "dM0"):
+        assert torch.equal(g1[name], g2[name]), name
