@@ -62,7 +62,7 @@ FwdWs carve_fwd(const Dims &d, void *ws) {
 
 // Operands of the reverse pass (what intra mode 1 / 2 writes); lives in the backward workspace or in
 // the buffer a training forward keeps for the backward.
-struct RevOps { float *coef; void *KT, *QT, *nYT, *ZT, *BmT, *TmT; size_t total; };
+struct RevOps { float *coef; void *KT, *QT, *BmT, *TmT; size_t total; };
 
 RevOps carve_rev(const Dims &d, void *p) {
     const size_t es = d.dtype == MDN_DTYPE_F32 ? 4 : 2, nb = (size_t)d.BH * d.N;
@@ -71,8 +71,6 @@ RevOps carve_rev(const Dims &d, void *p) {
     w.coef = static_cast<float *>(c.take(nb * (size_t)(6 * 64 * sizeof(float))));
     w.KT = c.take(nb * d.dk * 64 * es);
     w.QT = c.take(nb * d.dk * 64 * es);
-    w.nYT = c.take(nb * d.dk * 64 * es);
-    w.ZT = c.take(nb * d.dk * 64 * es);
     w.BmT = c.take(nb * 4096 * es);
     w.TmT = c.take(nb * 4096 * es);
     w.total = c.off;
@@ -273,7 +271,7 @@ int mdn_chunk_fwd(const mdn_shape *shape, const void *q, const void *k, const vo
     if (operands_saved) {
         // training forward: one precompute pass writes the reverse pass's operands as well
         const RevOps ro = carve_rev(d, operands_saved);
-        ia.coef = ro.coef; ia.KT = ro.KT; ia.QT = ro.QT; ia.nYT = ro.nYT; ia.ZT = ro.ZT; ia.BmT = ro.BmT; ia.TmT = ro.TmT;
+        ia.coef = ro.coef; ia.KT = ro.KT; ia.QT = ro.QT; ia.BmT = ro.BmT; ia.TmT = ro.TmT;
     }
     ScanFwdArgs sa = {};
     sa.q = q; sa.coef = ia.coef; sa.KT = ia.KT; sa.U = w.U; sa.nY = w.nY; sa.Z = w.Z; sa.Bm = w.Bm;
@@ -335,7 +333,7 @@ int mdn_chunk_bwd(const mdn_shape *shape, const void *q, const void *k, const vo
     } else {
         IntraArgs ia = {};
         ia.q = q; ia.k = k; ia.v = v; ia.alpha = alpha; ia.beta = beta; ia.mu = mu; ia.eta = eta;
-        ia.coef = ro.coef; ia.KT = ro.KT; ia.QT = ro.QT; ia.nYT = ro.nYT; ia.ZT = ro.ZT; ia.BmT = ro.BmT; ia.TmT = ro.TmT;
+        ia.coef = ro.coef; ia.KT = ro.KT; ia.QT = ro.QT; ia.BmT = ro.BmT; ia.TmT = ro.TmT;
         rc = timed(MDN_KERNEL_INTRA_BWD, s, [&] { return launch_intra(d, 1, ia, s); });
         if (rc) return rc;
     }
@@ -351,7 +349,7 @@ int mdn_chunk_bwd(const mdn_shape *shape, const void *q, const void *k, const vo
     }
 
     ScanBwdArgs sb = {};
-    sb.k = k; sb.dO = dO; sb.coef = ro.coef; sb.QT = ro.QT; sb.nYT = ro.nYT; sb.ZT = ro.ZT; sb.BmT = ro.BmT;
+    sb.k = k; sb.dO = dO; sb.coef = ro.coef; sb.QT = ro.QT; sb.KT = ro.KT; sb.BmT = ro.BmT;
     sb.TmT = ro.TmT; sb.dS_final = dS_final; sb.dM_final = dM_final; sb.dv = dv; sb.dstates = w.dstates;
     sb.dS0 = dS0; sb.dM0 = dM0;
     GradArgs ga = {};

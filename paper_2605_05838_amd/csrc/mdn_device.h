@@ -30,8 +30,9 @@ constexpr int kThreads = 256; // 4 waves per workgroup
 constexpr int kCoefRows = 6;  // per-chunk coefficient block: [kCoefRows][64] floats
 
 // rows of the coefficient block
-enum { COEF_A = 0, COEF_B = 1, COEF_GC = 2, COEF_RC = 3, COEF_SCALAR = 4, COEF_ETA = 5 };
-// COEF_SCALAR row: [0] = a_C, [1] = b_C, [2] = m_C
+enum { COEF_A = 0, COEF_B = 1, COEF_GC = 2, COEF_RC = 3, COEF_SCALAR = 4, COEF_PB = 5 };
+// COEF_SCALAR row: [0] = a_C, [1] = b_C, [2] = m_C;  COEF_PB row: alpha_i b_{i-1} (the scaling of Z; that of Y,
+// alpha_i a_{i-1}, is a_i itself)
 
 template <typename T> struct Op;
 

@@ -12,7 +12,7 @@
 //   WY-style factors  U = T V,  Y = T diag(a^-) P = (T diag(a)) K,  Z = T diag(b^-) P = (T diag(b^- alpha)) K
 //
 // One workgroup (4 waves) per (chunk, batch*head).  Forward mode writes U, -Y, Z, Bm and K^T;
-// backward mode writes the transposed operands the reverse scan needs (-Y^T, Z^T, Bm^T, T^T, K^T, Q^T);
+// backward mode writes the transposed operands the reverse scan needs (Bm^T, T^T, K^T, Q^T);
 // a training forward can write both sets at once, so that the backward need not recompute them.
 // Everything is written in the blocked layouts of mdn_device.h (kblk / vblk), in which the serial
 // scans' fragment loads are contiguous.
@@ -124,7 +124,7 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
             s_b[lane] = pb;
             coef[COEF_A * 64 + lane] = pa;
             coef[COEF_B * 64 + lane] = pb;
-            coef[COEF_ETA * 64 + lane] = et;
+            coef[COEF_PB * 64 + lane] = al * __shfl_up(pb, 1) * (lane > 0 ? 1.f : 0.f); // alpha_i b_{i-1}, b_{-1} = 0
             if (lane == 63) {
                 coef[COEF_SCALAR * 64 + 0] = pa;
                 coef[COEF_SCALAR * 64 + 1] = pb;
@@ -230,7 +230,7 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
     // ---- WY-style factors.  pass 0: U = T V (forward only); pass 1: Y; pass 2: Z.
     //      Each product is formed in the orientation whose accumulator lanes hold 4 consecutive
     //      entries along the index that is contiguous in the consumer's layout.
-    for (int pass = FWD ? 0 : 1; pass < 3; ++pass) {
+    for (int pass = 0; FWD && pass < 3; ++pass) {
         if (tid < 64) {
             const float bprev = (tid > 0) ? s_b[tid - 1] : 0.f;
             s_cs[tid] = (pass == 0) ? 1.f : (pass == 1) ? s_a[tid] : bprev * s_al[tid];
@@ -268,15 +268,6 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
                     for (int nt = 0; nt < 4; ++nt) store4(out + kblk<T>(64, nt * 16 + r, m0 + kq * 4), sgn * y[nt]);
                 }
             }
-        }
-        if (BWD && pass > 0) {
-            // Y[i][dk] = sum_j (T diag(cs))[i][j] K^T[dk][j]  ->  Y^T in kblk: row dk, k = i
-            f32x4 y[DK / 16];
-            zero_acc(y);
-            mma_rows<T, DK / 16, 64>(y, sTop + i0 * LDT, LDT, sKT, LDT);
-            T *out = static_cast<T *>(pass == 1 ? a.nYT : a.ZT) + blk * (DK * 64);
-#pragma unroll
-            for (int nt = 0; nt < DK / 16; ++nt) store4(out + kblk<T>(DK, nt * 16 + r, i0 + kq * 4), sgn * y[nt]);
         }
         __syncthreads();
     }

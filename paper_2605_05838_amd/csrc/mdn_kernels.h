@@ -29,7 +29,6 @@ struct IntraArgs {
     void *Bm;                               // kblk [64][64]   (Q~ K~^T) .* Gamma
     // backward mode
     void *QT;                               // kblk [dk][64]   raw q, transposed
-    void *nYT, *ZT;                         // kblk [dk][64]   transposes of -Y, Z
     void *BmT;                              // kblk [64][64]   Bm transposed
     void *TmT;                              // kblk [64][64]   T transposed
 };
@@ -58,7 +57,7 @@ struct ScanBwdArgs {
     const void *k;                          // [B,T,H,dk]
     const void *dO;                         // [B,T,H,dv]
     const float *coef;
-    const void *QT, *nYT, *ZT, *BmT, *TmT;
+    const void *QT, *KT, *BmT, *TmT;
     const float *dS_final, *dM_final;       // or null
     void *dv;                               // [B,T,H,dv]  dV = T^T dV~
     void *dstates;                          // [BH][N][2] x vblk [dk][dv]: adjoints of the chunk-END states

@@ -5,15 +5,19 @@
 //     dV~ = Bm^T dO + (Gamma_C eta . K) dS' - (Rho_C eta . K) dM'
 //     dS  = a_C dS' + (a . Q~)^T dO - Y^T dV~
 //     dM  = m_C dM' - b_C dS' - (b . Q~)^T dO + Z^T dV~
+// With Y = T diag(a^-) P, Z = T diag(b^-) P, P = alpha K (Sec. 3.1) and dV = T^T dV~ (needed anyway):
+//     Y^T dV~ = K^T (a . dV)        (alpha_i a_{i-1} = a_i)
+//     Z^T dV~ = K^T (pb . dV)       (pb_i = alpha_i b_{i-1})
+// so the transposes of Y and Z are never stored or read: the raw K^T tile and two per-token scalings do.
 // Same decomposition as the forward scan: one workgroup per (batch*head, DVB dv-columns); every
 // product is formed transposed (dv = MFMA row index) so that an accumulator lane holds 4 consecutive
 // dv of one token or one dk row; dS'^T, dM'^T in fp32 accumulators (wave w owns dk columns
 // [w*dk/4, (w+1)*dk/4)), a storage-type copy [dv][dk | dk] in LDS as A operand; the per-token
 // scalings along the contraction index folded into the LDS copies of dO^T, so that the B operands
-// are raw rows of Q^T, -Y^T, Z^T, Bm^T and K; all of a chunk's fragments, its dO tile and
+// are raw rows of Q^T, K^T, Bm^T, T^T and K; all of a chunk's fragments, its dO tile and
 // coefficients are fetched into registers one chunk ahead.
-// It also forms dV = T^T dV~ from the LDS copy of dV~ (not on the chain) and writes the chunk-end
-// adjoint states for the chunk-parallel gradient kernel.
+// dV = T^T dV~ is formed from the LDS copy of dV~, written out, and fed back (scaled) into the state update.
+// The chunk-end adjoint states are written for the chunk-parallel gradient kernel.
 #include "mdn_device.h"
 #include "mdn_kernels.h"
 
@@ -29,18 +33,18 @@ template <typename T, int DK, int MV> struct RevOps {
     typename O::Frag k[KS];            // stage 1: K row (token i0 + r)
     typename O::Frag bmT[KS2];         // stage 1: Bm^T row i0 + r
     typename O::Frag tT[KS2];          // stage 2: T^T row i0 + r
-    typename O::Frag qT[ND][KS2], yT[ND][KS2], zT[ND][KS2]; // stage 2: rows (dk) of this wave's state columns
+    typename O::Frag qT[ND][KS2], kT[ND][KS2]; // stage 3: rows (dk) of Q^T, K^T for this wave's state columns
     // (kept exactly as loaded: arithmetic on a freshly loaded value would make the wave wait for it, and for
     //  every load issued before it, at fetch time instead of one chunk later)
     typename Raw4<T>::type dO[MV];     // dO[token i0 + r][4 consecutive dv], storage form
-    float sa, sb, gc, rc;              // a_i, b_i, Gamma_C eta, Rho_C eta
+    float sa, sb, gc, rc, pb;          // a_i, b_i, Gamma_C eta, Rho_C eta, alpha_i b_{i-1}
     float sc;                          // lane & 3 = 0, 1, 2: a_C, b_C, m_C
 };
 
 // The operands of one chunk are requested in NPART portions spread over the work on the previous chunk: a
 // wave that issues them all at once sits at the issue until the memory pipeline has taken them (the time
 // to move a chunk's operands into the CU), with its matrix work waiting behind.
-constexpr int NPART = 6;
+constexpr int NPART = 5;
 template <typename T, int DK, int DV, int DVB, int P>
 __device__ __forceinline__ void fetch_part(RevOps<T, DK, DVB / 16> &c, const Dims &d, const ScanBwdArgs &a, int bh, int b,
                                            int h, int n, int dv0) {
@@ -55,6 +59,7 @@ __device__ __forceinline__ void fetch_part(RevOps<T, DK, DVB / 16> &c, const Dim
         c.sb = coef[COEF_B * 64 + i];
         c.gc = coef[COEF_GC * 64 + i];
         c.rc = coef[COEF_RC * 64 + i];
+        c.pb = coef[COEF_PB * 64 + i];
         // the three chunk scalars through the vector path as well: a scalar load would share its wait counter
         // with the LDS reads and make the first of those wait for memory
         c.sc = coef[COEF_SCALAR * 64 + (lane & 3)];
@@ -75,16 +80,15 @@ __device__ __forceinline__ void fetch_part(RevOps<T, DK, DVB / 16> &c, const Dim
             c.tT[s] = O::load(tp + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL));
         }
     }
-    if (P >= 3) {
-        const T *src = static_cast<const T *>(P == 3 ? a.QT : P == 4 ? a.nYT : a.ZT) + blk * (DK * 64);
+    if (P == 3 || P == 4) {
+        const T *src = static_cast<const T *>(P == 3 ? a.QT : a.KT) + blk * (DK * 64);
 #pragma unroll
         for (int nd = 0; nd < CO::ND; ++nd)
 #pragma unroll
             for (int s = 0; s < CO::KS2; ++s) {
                 const typename O::Frag f = O::load(src + kblk<T>(DK, (w * CO::ND + nd) * 16 + r, s * O::KSTEP + kg * O::EPL));
                 if (P == 3) c.qT[nd][s] = f;
-                if (P == 4) c.yT[nd][s] = f;
-                if (P == 5) c.zT[nd][s] = f;
+                if (P == 4) c.kT[nd][s] = f;
             }
     }
     __builtin_amdgcn_sched_barrier(0); // the portion leaves here, not where the scheduler would gather the loads
@@ -98,7 +102,6 @@ __device__ __forceinline__ void fetch_chunk(RevOps<T, DK, DVB / 16> &c, const Di
     fetch_part<T, DK, DV, DVB, 2>(c, d, a, bh, b, h, n, dv0);
     fetch_part<T, DK, DV, DVB, 3>(c, d, a, bh, b, h, n, dv0);
     fetch_part<T, DK, DV, DVB, 4>(c, d, a, bh, b, h, n, dv0);
-    fetch_part<T, DK, DV, DVB, 5>(c, d, a, bh, b, h, n, dv0);
 }
 
 template <typename T, int DK, int DV, int DVB>
@@ -112,6 +115,8 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
     __shared__ __align__(16) T sOa[DVB * LDV];  // (scale a . dO)^T
     __shared__ __align__(16) T sOb[DVB * LDV];  // (-scale b . dO)^T
     __shared__ __align__(16) T sDV[DVB * LDV];  // dV~^T
+    __shared__ __align__(16) T sRa[DVB * LDV];  // (-a . dV)^T
+    __shared__ __align__(16) T sRb[DVB * LDV];  // (pb . dV)^T
 
     int bh, blkv;
     xcd_map(blockIdx.x, G, bh, blkv);
@@ -204,10 +209,36 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
         }
         __syncthreads();
 
-        // ---------------- stage 2: dV = T^T dV~ (off the chain) and the adjoints of the chunk-START states
+        // ---------------- stage 2: dV = T^T dV~ for token j = i: out to HBM, and back to LDS in the two scalings
+        //                  with which it enters the state adjoints
         {
             f32x4 dR[MV];
             zero_acc(dR);
+            const T *dvp = sDV + r * LDV + kg * O::EPL;
+#pragma unroll
+            for (int s = 0; s < CO::KS2; ++s)
+#pragma unroll
+                for (int mv = 0; mv < MV; ++mv)
+                    dR[mv] = O::mma(O::load(dvp + mv * 16 * LDV + s * O::KSTEP), cur.tT[s], dR[mv]);
+            fetch_part<T, DK, DV, DVB, 4>(nxt, d, a, bh, b, h, nn, dv0);
+            const size_t tok = ((size_t)b * d.T + (size_t)n * 64 + i) * d.H + h;
+            T *dvg = static_cast<T *>(a.dv) + tok * DV + dv0 + kg * 4;
+#pragma unroll
+            for (int mv = 0; mv < MV; ++mv) {
+                store4(dvg + mv * 16, dR[mv]);
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    const int dv = mv * 16 + kg * 4 + x;
+                    const float v = dR[mv][x];
+                    sRa[dv * LDV + i] = from_f32<T>(-cur.sa * v);
+                    sRb[dv * LDV + i] = from_f32<T>(cur.pb * v);
+                }
+            }
+        }
+        __syncthreads();
+
+        // ---------------- stage 3: the adjoints of the chunk-START states
+        {
             const float aC = lane_value(cur.sc, 0), bC = lane_value(cur.sc, 1), mC = lane_value(cur.sc, 2);
 #pragma unroll
             for (int mv = 0; mv < MV; ++mv)
@@ -217,31 +248,24 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
                     accS[mv][nd] = aC * s;
                     accM[mv][nd] = mC * m - bC * s;
                 }
-            const T *oap = sOa + r * LDV + kg * O::EPL, *obp = sOb + r * LDV + kg * O::EPL,
-                    *dvp = sDV + r * LDV + kg * O::EPL;
-            fetch_part<T, DK, DV, DVB, 4>(nxt, d, a, bh, b, h, nn, dv0);
+            const T *oap = sOa + r * LDV + kg * O::EPL, *obp = sOb + r * LDV + kg * O::EPL;
+            const T *rap = sRa + r * LDV + kg * O::EPL, *rbp = sRb + r * LDV + kg * O::EPL;
 #pragma unroll
-            for (int s = 0; s < CO::KS2; ++s) {
-                if (s == CO::KS2 / 2) fetch_part<T, DK, DV, DVB, 5>(nxt, d, a, bh, b, h, nn, dv0);
+            for (int s = 0; s < CO::KS2; ++s)
 #pragma unroll
                 for (int mv = 0; mv < MV; ++mv) {
                     const typename O::Frag fa = O::load(oap + mv * 16 * LDV + s * O::KSTEP);
                     const typename O::Frag fb = O::load(obp + mv * 16 * LDV + s * O::KSTEP);
-                    const typename O::Frag fd = O::load(dvp + mv * 16 * LDV + s * O::KSTEP);
-                    dR[mv] = O::mma(fd, cur.tT[s], dR[mv]);
+                    const typename O::Frag fra = O::load(rap + mv * 16 * LDV + s * O::KSTEP);
+                    const typename O::Frag frb = O::load(rbp + mv * 16 * LDV + s * O::KSTEP);
 #pragma unroll
                     for (int nd = 0; nd < ND; ++nd) {
                         accS[mv][nd] = O::mma(fa, cur.qT[nd][s], accS[mv][nd]);
-                        accS[mv][nd] = O::mma(fd, cur.yT[nd][s], accS[mv][nd]);
+                        accS[mv][nd] = O::mma(fra, cur.kT[nd][s], accS[mv][nd]);
                         accM[mv][nd] = O::mma(fb, cur.qT[nd][s], accM[mv][nd]);
-                        accM[mv][nd] = O::mma(fd, cur.zT[nd][s], accM[mv][nd]);
+                        accM[mv][nd] = O::mma(frb, cur.kT[nd][s], accM[mv][nd]);
                     }
                 }
-            }
-            const size_t tok = ((size_t)b * d.T + (size_t)n * 64 + i) * d.H + h;
-            T *dvg = static_cast<T *>(a.dv) + tok * DV + dv0 + kg * 4;
-#pragma unroll
-            for (int mv = 0; mv < MV; ++mv) store4(dvg + mv * 16, dR[mv]);
         }
         __syncthreads();
     };
