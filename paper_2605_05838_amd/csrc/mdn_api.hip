@@ -41,7 +41,7 @@ struct Carver {
     }
 };
 
-struct FwdWs { float *coef; void *KT, *U, *nY, *Z, *Bm; float *carryS, *carryM; size_t total; };
+struct FwdWs { float *coef; void *KT, *Tm, *Bm; float *carryS, *carryM; size_t total; };
 
 FwdWs carve_fwd(const Dims &d, void *ws) {
     const size_t es = d.dtype == MDN_DTYPE_F32 ? 4 : 2, nb = (size_t)d.BH * d.N;
@@ -49,9 +49,7 @@ FwdWs carve_fwd(const Dims &d, void *ws) {
     FwdWs w;
     w.coef = static_cast<float *>(c.take(nb * (size_t)(6 * 64 * sizeof(float))));
     w.KT = c.take(nb * d.dk * 64 * es);
-    w.U = c.take(nb * 64 * d.dv * es);
-    w.nY = c.take(nb * 64 * d.dk * es);
-    w.Z = c.take(nb * 64 * d.dk * es);
+    w.Tm = c.take(nb * 4096 * es);
     w.Bm = c.take(nb * 4096 * es);
     // states handed from one segment of the sequence to the next when the call is split (see segments())
     w.carryS = static_cast<float *>(c.take((size_t)d.BH * d.dk * d.dv * sizeof(float)));
@@ -266,15 +264,15 @@ int mdn_chunk_fwd(const mdn_shape *shape, const void *q, const void *k, const vo
     hipStream_t s = static_cast<hipStream_t>(stream);
 
     IntraArgs ia = {};
-    ia.q = q; ia.k = k; ia.v = v; ia.alpha = alpha; ia.beta = beta; ia.mu = mu; ia.eta = eta;
-    ia.coef = w.coef; ia.KT = w.KT; ia.U = w.U; ia.nY = w.nY; ia.Z = w.Z; ia.Bm = w.Bm;
+    ia.q = q; ia.k = k; ia.alpha = alpha; ia.beta = beta; ia.mu = mu; ia.eta = eta;
+    ia.coef = w.coef; ia.KT = w.KT; ia.Tm = w.Tm; ia.Bm = w.Bm;
     if (operands_saved) {
         // training forward: one precompute pass writes the reverse pass's operands as well
         const RevOps ro = carve_rev(d, operands_saved);
         ia.coef = ro.coef; ia.KT = ro.KT; ia.QT = ro.QT; ia.BmT = ro.BmT; ia.TmT = ro.TmT;
     }
     ScanFwdArgs sa = {};
-    sa.q = q; sa.coef = ia.coef; sa.KT = ia.KT; sa.U = w.U; sa.nY = w.nY; sa.Z = w.Z; sa.Bm = w.Bm;
+    sa.q = q; sa.k = k; sa.v = v; sa.coef = ia.coef; sa.KT = ia.KT; sa.Tm = w.Tm; sa.Bm = w.Bm;
     sa.S0 = S0; sa.M0 = M0; sa.o = o; sa.vt_saved = vt_saved; sa.states_saved = states_saved;
     sa.S_final = S_final; sa.M_final = M_final;
     const int mode = operands_saved ? 2 : 0;
@@ -332,7 +330,7 @@ int mdn_chunk_bwd(const mdn_shape *shape, const void *q, const void *k, const vo
         ro = carve_rev(d, const_cast<void *>(operands_saved));
     } else {
         IntraArgs ia = {};
-        ia.q = q; ia.k = k; ia.v = v; ia.alpha = alpha; ia.beta = beta; ia.mu = mu; ia.eta = eta;
+        ia.q = q; ia.k = k; ia.alpha = alpha; ia.beta = beta; ia.mu = mu; ia.eta = eta;
         ia.coef = ro.coef; ia.KT = ro.KT; ia.QT = ro.QT; ia.BmT = ro.BmT; ia.TmT = ro.TmT;
         rc = timed(MDN_KERNEL_INTRA_BWD, s, [&] { return launch_intra(d, 1, ia, s); });
         if (rc) return rc;

@@ -9,13 +9,17 @@
 //       A  = (P K~^T) .* Gamma^-   (strictly lower; Gamma^-_ij = Gamma_{i-1,j}),  P = alpha k, K~ = eta k
 //       Bm = (Q~ K~^T) .* Gamma    (lower incl. diagonal),                         Q~ = scale q
 //   triangular solve  T = (I + A)^{-1}
-//   WY-style factors  U = T V,  Y = T diag(a^-) P = (T diag(a)) K,  Z = T diag(b^-) P = (T diag(b^- alpha)) K
 //
-// One workgroup (4 waves) per (chunk, batch*head).  Forward mode writes U, -Y, Z, Bm and K^T;
-// backward mode writes the transposed operands the reverse scan needs (Bm^T, T^T, K^T, Q^T);
-// a training forward can write both sets at once, so that the backward need not recompute them.
-// Everything is written in the blocked layouts of mdn_device.h (kblk / vblk), in which the serial
-// scans' fragment loads are contiguous.
+// The WY-style factors U = T V, Y = T diag(a^-) P, Z = T diag(b^-) P of Sec. 3.1 are NOT formed: the scans
+// apply T themselves,  V~ = T (V - a.(K S) + pb.(K M))  with  alpha_i a_{i-1} = a_i,  pb_i = alpha_i b_{i-1}
+// (the same expression with T pulled out; Appendix C, Eq. "apx.v.before" solved for V~), and the reverse scan
+// uses Y^T dV~ = K^T (a . T^T dV~).  That trades three 64 x d products and their 1.3 KB per token of HBM
+// round trips for one 64 x 64 x dv product inside the scan.
+//
+// One workgroup (4 waves) per (chunk, batch*head).  Forward mode writes T, Bm and K^T; backward mode writes
+// the transposed operands the reverse scan needs (Bm^T, T^T, K^T, Q^T); a training forward writes both sets
+// at once, so that the backward need not recompute them.  Everything is written in the blocked layout of
+// mdn_device.h (kblk), in which the serial scans' fragment loads are contiguous.
 #include "mdn_coef.h"
 #include "mdn_device.h"
 #include "mdn_kernels.h"
@@ -49,10 +53,10 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
     constexpr int E = O::EPL;
     constexpr int LDN = DK + O::PAD; // natural tiles
     constexpr int LDT = 64 + O::PAD; // transposed tiles and the operand copy of T
-    constexpr int DX = FWD ? DV : DK;
+    constexpr int DX = BWD ? DK : 0; // second transposed tile: Q^T (reverse-pass operands only)
     constexpr int REG_NAT = 2 * 64 * LDN, REG_TR = (DK + DX) * LDT;
     constexpr int REGION = REG_NAT > REG_TR ? REG_NAT : REG_TR;
-    constexpr int NVK = 64 * DK / E / kThreads, NVX = 64 * DX / E / kThreads; // 16-byte vectors per thread
+    constexpr int NVK = 64 * DK / E / kThreads, NVX = BWD ? NVK : 1; // 16-byte vectors per thread
 
     __shared__ __align__(16) T sR[REGION];
     // Gamma (row stride LDG); later scratch of the block inverse; later the operand copy of T
@@ -61,7 +65,7 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
     float *sTT = sG;
     T *sTop = reinterpret_cast<T *>(sG);
     static_assert(sizeof(T) * 64 * LDT <= sizeof(float) * 64 * LDA, "operand copy of T does not fit");
-    __shared__ float s_al[64], s_be[64], s_et[64], s_a[64], s_b[64], s_cs[64];
+    __shared__ float s_al[64], s_be[64], s_et[64], s_a[64], s_b[64];
 
     T *sK = sR, *sQ = sR + 64 * LDN;      // phase A
     T *sKT = sR, *sXT = sR + DK * LDT;    // phase B (aliases phase A)
@@ -73,8 +77,7 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
     const size_t blk = (size_t)bh * d.N + n; // chunk-block index into the workspace tensors
     const T *qg = static_cast<const T *>(a.q) + tok0 * DK;
     const T *kg_ = static_cast<const T *>(a.k) + tok0 * DK;
-    const T *vg = static_cast<const T *>(a.v) + tok0 * DV;
-    const size_t rsk = (size_t)d.H * DK, rsv = (size_t)d.H * DV;
+    const size_t rsk = (size_t)d.H * DK;
     float *coef = a.coef + blk * (kCoefRows * 64);
 
     // ---- K, Q tiles: all loads in flight at once, then to LDS
@@ -101,11 +104,12 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
         const int c = tid + u * kThreads, row = c % 64, cc = c / 64;
         rkt[u] = *reinterpret_cast<const Vec16<T> *>(kg_ + row * rsk + cc * E);
     }
+    if (BWD) {
 #pragma unroll
-    for (int u = 0; u < NVX; ++u) {
-        const int c = tid + u * kThreads, row = c % 64, cc = c / 64;
-        rxt[u] = FWD ? *reinterpret_cast<const Vec16<T> *>(vg + row * rsv + cc * E)
-                     : *reinterpret_cast<const Vec16<T> *>(qg + row * rsk + cc * E);
+        for (int u = 0; u < NVX; ++u) {
+            const int c = tid + u * kThreads, row = c % 64, cc = c / 64;
+            rxt[u] = *reinterpret_cast<const Vec16<T> *>(qg + row * rsk + cc * E);
+        }
     }
 
     // ---- gate coefficients.  Matrix Gamma: every wave 16 rows (column scans started from segment maps);
@@ -201,11 +205,13 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
 #pragma unroll
         for (int e = 0; e < E; ++e) sKT[(cc * E + e) * LDT + row] = rkt[u].e[e];
     }
+    if (BWD) {
 #pragma unroll
-    for (int u = 0; u < NVX; ++u) {
-        const int c = tid + u * kThreads, row = c % 64, cc = c / 64;
+        for (int u = 0; u < NVX; ++u) {
+            const int c = tid + u * kThreads, row = c % 64, cc = c / 64;
 #pragma unroll
-        for (int e = 0; e < E; ++e) sXT[(cc * E + e) * LDT + row] = rxt[u].e[e];
+            for (int e = 0; e < E; ++e) sXT[(cc * E + e) * LDT + row] = rxt[u].e[e];
+        }
     }
     // ---- T = (I + A)^{-1} by 16x16 blocks, wave w = block row w
     tri_inverse_blocked(sA, sTT, LDA, w);
@@ -213,7 +219,7 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
 
     // raw transposed copies for the scans
     store_tile_64cols<T>(static_cast<T *>(a.KT) + blk * (DK * 64), sKT, LDT, DK, tid);
-    if (MODE == 1) store_tile_64cols<T>(static_cast<T *>(a.QT) + blk * (DK * 64), sXT, LDT, DK, tid);
+    if (BWD) store_tile_64cols<T>(static_cast<T *>(a.QT) + blk * (DK * 64), sXT, LDT, DK, tid);
     if (BWD) {
         T *tt = static_cast<T *>(a.TmT) + blk * 4096; // T^T: row j, k = i
         constexpr int E = O::EPL;
@@ -227,67 +233,16 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
         }
     }
 
-    // ---- WY-style factors.  pass 0: U = T V (forward only); pass 1: Y; pass 2: Z.
-    //      Each product is formed in the orientation whose accumulator lanes hold 4 consecutive
-    //      entries along the index that is contiguous in the consumer's layout.
-    for (int pass = 0; FWD && pass < 3; ++pass) {
-        if (tid < 64) {
-            const float bprev = (tid > 0) ? s_b[tid - 1] : 0.f;
-            s_cs[tid] = (pass == 0) ? 1.f : (pass == 1) ? s_a[tid] : bprev * s_al[tid];
+    if (FWD) {
+        T *tm = static_cast<T *>(a.Tm) + blk * 4096; // T: row i, k = j
+        constexpr int PPS = O::KSTEP / E;
+        for (int c = tid; c < 64 * (64 / E); c += kThreads) {
+            const int pp = c % PPS, ii = (c / PPS) & 63, cc = (c / (PPS * 64)) * PPS + pp;
+            Vec16<T> v;
+#pragma unroll
+            for (int e = 0; e < E; ++e) v.e[e] = from_f32<T>(sA[ii * LDA + cc * E + e]);
+            *reinterpret_cast<Vec16<T> *>(tm + kblk<T>(64, ii, cc * E)) = v;
         }
-        __syncthreads();
-        for (int c = tid; c < 4096; c += kThreads) {
-            const int ii = c >> 6, jj = c & 63;
-            sTop[ii * LDT + jj] = from_f32<T>(sA[ii * LDA + jj] * s_cs[jj]);
-        }
-        __syncthreads();
-        const float sgn = pass == 1 ? -1.f : 1.f;
-        if (FWD) {
-            if (pass == 0) {
-                // U^T[dv][i] = sum_j V^T[dv][j] T[i][j]  ->  vblk [dv/16][token][16]
-#pragma unroll
-                for (int mt = 0; mt < DV / 64; ++mt) {
-                    const int m0 = (w * (DV / 64) + mt) * 16;
-                    f32x4 u[4];
-                    zero_acc(u);
-                    mma_rows<T, 4, 64>(u, sXT + m0 * LDT, LDT, sTop, LDT);
-                    T *out = static_cast<T *>(a.U) + blk * (64 * DV);
-#pragma unroll
-                    for (int nt = 0; nt < 4; ++nt) store4(out + vblk(64, nt * 16 + r, m0 + kq * 4), u[nt]);
-                }
-            } else {
-                // Y^T[dk][i] = sum_j K^T[dk][j] (T diag(cs))[i][j]  ->  kblk: row i, k = dk
-#pragma unroll
-                for (int mt = 0; mt < DK / 64; ++mt) {
-                    const int m0 = (w * (DK / 64) + mt) * 16;
-                    f32x4 y[4];
-                    zero_acc(y);
-                    mma_rows<T, 4, 64>(y, sKT + m0 * LDT, LDT, sTop, LDT);
-                    T *out = static_cast<T *>(pass == 1 ? a.nY : a.Z) + blk * (64 * DK);
-#pragma unroll
-                    for (int nt = 0; nt < 4; ++nt) store4(out + kblk<T>(64, nt * 16 + r, m0 + kq * 4), sgn * y[nt]);
-                }
-            }
-        }
-        __syncthreads();
-    }
-    if (MODE == 2) {
-        // Q^T for the reverse pass, through the tile space the V^T tile no longer needs
-        static_assert(MODE != 2 || DX >= DK, "Q^T does not fit the V^T tile");
-        Vec16<T> rq[NVK];
-#pragma unroll
-        for (int u = 0; u < NVK; ++u) {
-            const int c = tid + u * kThreads, row = c % 64, cc = c / 64;
-            rq[u] = *reinterpret_cast<const Vec16<T> *>(qg + row * rsk + cc * E);
-        }
-#pragma unroll
-        for (int u = 0; u < NVK; ++u) {
-            const int c = tid + u * kThreads, row = c % 64, cc = c / 64;
-#pragma unroll
-            for (int e = 0; e < E; ++e) sXT[(cc * E + e) * LDT + row] = rq[u].e[e];
-        }
-        __syncthreads();
-        store_tile_64cols<T>(static_cast<T *>(a.QT) + blk * (DK * 64), sXT, LDT, DK, tid);
     }
 }
 

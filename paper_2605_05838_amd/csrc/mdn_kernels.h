@@ -18,14 +18,12 @@ struct Dims {
 // [BH][N][tile], in the storage dtype unless noted; inside a tile, an MFMA operand [rows][k] is in
 // the kblk layout and a [rows][dv] tensor in the vblk layout of mdn_device.h.
 struct IntraArgs {
-    const void *q, *k, *v;                  // [B,T,H,D]
+    const void *q, *k;                      // [B,T,H,dk]
     const float *alpha, *beta, *mu, *eta;   // [B,T,H]; eta may be null
     float *coef;                            // [BH][N][6][64] fp32
     void *KT;                               // kblk [dk][64]   raw k, transposed
     // forward mode
-    void *U;                                // vblk [64][dv]   T V
-    void *nY;                               // kblk [64][dk]  -T diag(a^-) P
-    void *Z;                                // kblk [64][dk]   T diag(b^-) P
+    void *Tm;                               // kblk [64][64]   T = (I + A)^-1: row i, contraction index j
     void *Bm;                               // kblk [64][64]   (Q~ K~^T) .* Gamma
     // backward mode
     void *QT;                               // kblk [dk][64]   raw q, transposed
@@ -34,9 +32,10 @@ struct IntraArgs {
 };
 
 struct ScanFwdArgs {
-    const void *q;                          // [B,T,H,dk]
+    const void *q, *k;                      // [B,T,H,dk]
+    const void *v;                          // [B,T,H,dv]
     const float *coef;
-    const void *KT, *U, *nY, *Z, *Bm;
+    const void *KT, *Tm, *Bm;
     const float *S0, *M0;                   // [B,H,dk,dv] or null
     void *o;                                // [B,T,H,dv]
     void *vt_saved;                         // [B,T,H,dv] or null

@@ -33,13 +33,14 @@ namespace {
 template <typename T, int DK, int MV> struct ChunkOps {
     typedef Op<T> O;
     static constexpr int KS = DK / O::KSTEP, KS2 = 64 / O::KSTEP, ND = DK / 64;
-    typename O::Frag y[KS], z[KS], q[KS]; // stage 1: rows (token i0 + r) of -Y, Z, Q
+    typename O::Frag kr[KS], q[KS];       // stage 1: rows (token i0 + r) of K, Q
+    typename O::Frag tm[KS2];             // stage 1: row i0 + r of T = (I + A)^-1
     typename O::Frag bm[KS2];             // stage 2: Bm row i0 + r
     typename O::Frag kt[ND][KS2];         // stage 2: K^T rows (dk) of this wave's state columns
     // (everything below is kept exactly as loaded: arithmetic on a freshly loaded value would make the wave wait
     //  for it, and for every load issued before it, at fetch time instead of one chunk later)
-    typename Raw4<T>::type u[MV];         // U[token i0 + r][4 consecutive dv] (V~ in reconstruction), storage form
-    float sa, sb, gc, rc;                 // a_i, b_i, Gamma_C eta, Rho_C eta for token i0 + r
+    typename Raw4<T>::type u[MV];         // V[token i0 + r][4 consecutive dv] (V~ in reconstruction), storage form
+    float sa, sb, gc, rc, pb;             // a_i, b_i, Gamma_C eta, Rho_C eta, alpha_i b_{i-1} for token i0 + r
     float sc;                          // lane & 3 = 0, 1, 2: a_C, b_C, m_C
 };
 
@@ -61,20 +62,15 @@ __device__ __forceinline__ void fetch_part(ChunkOps<T, DK, DVB / 16> &c, const D
         if (!REBUILD) {
             c.sa = coef[COEF_A * 64 + i];
             c.sb = coef[COEF_B * 64 + i];
+            c.pb = coef[COEF_PB * 64 + i];
         }
         // the three chunk scalars through the vector path as well: a scalar load would share its wait counter
         // with the LDS reads and make the first of those wait for memory
         c.sc = coef[COEF_SCALAR * 64 + (lane & 3)];
-        if (!REBUILD) {
-            const T *Ug = static_cast<const T *>(a.U) + blk * (64 * DV);
+        // the forward reads V, the reconstruction the saved V~
+        const T *vs = static_cast<const T *>(REBUILD ? a.vt_saved : a.v) + tok * DV + dv0 + kg * 4;
 #pragma unroll
-            for (int mv = 0; mv < DVB / 16; ++mv) c.u[mv] = load4_raw(Ug + vblk(64, i, dv0 + mv * 16 + kg * 4));
-        } else {
-            // reconstruction reads the saved V~ where the forward reads U
-            const T *vs = static_cast<const T *>(a.vt_saved) + tok * DV + dv0 + kg * 4;
-#pragma unroll
-            for (int mv = 0; mv < DVB / 16; ++mv) c.u[mv] = load4_raw(vs + mv * 16);
-        }
+        for (int mv = 0; mv < DVB / 16; ++mv) c.u[mv] = load4_raw(vs + mv * 16);
     }
     if (P == 1 && !REBUILD) {
         const T *Qg = static_cast<const T *>(a.q) + tok * DK + kg * O::EPL;
@@ -90,18 +86,17 @@ __device__ __forceinline__ void fetch_part(ChunkOps<T, DK, DVB / 16> &c, const D
                 c.kt[nd][s] = O::load(KTg + kblk<T>(DK, (w * CO::ND + nd) * 16 + r, s * O::KSTEP + kg * O::EPL));
     }
     if (P == 3 && !REBUILD) {
-        const T *Bg = static_cast<const T *>(a.Bm) + blk * 4096;
+        const T *Bg = static_cast<const T *>(a.Bm) + blk * 4096, *Tg = static_cast<const T *>(a.Tm) + blk * 4096;
 #pragma unroll
-        for (int s = 0; s < CO::KS2; ++s) c.bm[s] = O::load(Bg + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL));
+        for (int s = 0; s < CO::KS2; ++s) {
+            c.tm[s] = O::load(Tg + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL));
+            c.bm[s] = O::load(Bg + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL));
+        }
     }
     if (P == 4 && !REBUILD && !NO_STAGE1) {
-        const T *Yg = static_cast<const T *>(a.nY) + blk * (64 * DK);
-        const T *Zg = static_cast<const T *>(a.Z) + blk * (64 * DK);
+        const T *Kg = static_cast<const T *>(a.k) + tok * DK + kg * O::EPL;
 #pragma unroll
-        for (int s = 0; s < CO::KS; ++s) {
-            c.y[s] = O::load(Yg + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL));
-            c.z[s] = O::load(Zg + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL));
-        }
+        for (int s = 0; s < CO::KS; ++s) c.kr[s] = O::load(Kg + s * O::KSTEP);
     }
     __builtin_amdgcn_sched_barrier(0); // the portion leaves here, not where the scheduler would gather the loads
 }
@@ -143,6 +138,7 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
     constexpr int LDST = 2 * DK + O::PAD; // state copy: [DVB][S(dk) | M(dk)]
     constexpr int LDV = 64 + O::PAD;      // V~ copies: [DVB][64 tokens]
     __shared__ __align__(16) T sSt[DVB * LDST];
+    __shared__ __align__(16) T sRt[REBUILD ? 8 : DVB * LDV]; // R^T = (V - a.(K S) + pb.(K M))^T, all 64 tokens
     __shared__ __align__(16) T sV0[DVB * LDV];
     __shared__ __align__(16) T sVg[DVB * LDV];
     __shared__ __align__(16) T sVr[DVB * LDV];
@@ -185,12 +181,13 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
         }
 
         fetch_part<T, DK, DV, DVB, REBUILD, false, 4>(nxt, d, a, bh, b, h, nn, dv0);
-        // ---------------- stage 1: V~^T and the inter-chunk read-outs for token i
+        // ---------------- stage 1: R^T = (V - a.(K S) + pb.(K M))^T and the inter-chunk read-outs for token i,
+        //                  then V~^T = R^T T^T over all 64 tokens
         f32x4 accO[MV], vt[MV]; // vt = V~ rounded to the storage type
         if (!REBUILD) {
-            f32x4 accV[MV], accOS[MV], accOM[MV];
-#pragma unroll
-            for (int mv = 0; mv < MV; ++mv) accV[mv] = widen4(cur.u[mv]);
+            f32x4 x1[MV], x2[MV], accOS[MV], accOM[MV];
+            zero_acc(x1);
+            zero_acc(x2);
             zero_acc(accOS);
             zero_acc(accOM);
             const T *sp = sSt + r * LDST + kg * O::EPL;
@@ -200,9 +197,9 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
                 for (int mv = 0; mv < MV; ++mv) {
                     const typename O::Frag fs = O::load(sp + mv * 16 * LDST + s * O::KSTEP);
                     const typename O::Frag fm = O::load(sp + mv * 16 * LDST + DK + s * O::KSTEP);
-                    accV[mv] = O::mma(fs, cur.y[s], accV[mv]);
+                    x1[mv] = O::mma(fs, cur.kr[s], x1[mv]);
                     accOS[mv] = O::mma(fs, cur.q[s], accOS[mv]);
-                    accV[mv] = O::mma(fm, cur.z[s], accV[mv]);
+                    x2[mv] = O::mma(fm, cur.kr[s], x2[mv]);
                     accOM[mv] = O::mma(fm, cur.q[s], accOM[mv]);
                 }
             }
@@ -210,9 +207,23 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
 #pragma unroll
             for (int mv = 0; mv < MV; ++mv) {
                 accO[mv] = d.scale * (cur.sa * accOS[mv] - cur.sb * accOM[mv]);
+                const f32x4 rr = widen4(cur.u[mv]) - cur.sa * x1[mv] + cur.pb * x2[mv];
+#pragma unroll
+                for (int x = 0; x < 4; ++x) sRt[(mv * 16 + kg * 4 + x) * LDV + i] = from_f32<T>(rr[x]);
+            }
+            __syncthreads();
+            f32x4 accV[MV];
+            zero_acc(accV);
+            const T *rp = sRt + r * LDV + kg * O::EPL;
+#pragma unroll
+            for (int s = 0; s < CO::KS2; ++s)
+#pragma unroll
+                for (int mv = 0; mv < MV; ++mv)
+                    accV[mv] = O::mma(O::load(rp + mv * 16 * LDV + s * O::KSTEP), cur.tm[s], accV[mv]);
+#pragma unroll
+            for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
                 for (int x = 0; x < 4; ++x) vt[mv][x] = rounded<T>(accV[mv][x]);
-            }
             if (a.vt_saved) {
                 T *vs = static_cast<T *>(a.vt_saved) + tok * DV + dv0 + kg * 4;
 #pragma unroll
@@ -301,23 +312,24 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
 // bf16 forward scan with loader waves.  Issuing a chunk's fragment loads costs the issuing wave about as
 // long as the chunk's MFMA work (the CU's vector-memory path moves roughly 30 bytes per clock), and a wave
 // cannot compute while it is stuck issuing.  So the workgroup gets 4 extra waves that do nothing but
-// feed: loader wave c copies the -Y and Z fragments of compute wave c from HBM straight into LDS
+// feed: loader wave c copies the K-row fragments of compute wave c from HBM straight into LDS
 // (global_load_lds, one 16-byte slot per lane: slot = lane, so the compute lane later reads back
 // exactly its own fragment, conflict-free), TWO chunks ahead through a ring of three buffers, never
 // draining its queue (it waits with vmcnt(NF) only for the older of its two bursts).  The compute waves
-// keep fetching the rest (Q, K^T, Bm rows, U, coefficients) into registers one chunk ahead.
+// keep fetching the rest (Q, K^T, T and Bm rows, V, coefficients) into registers one chunk ahead.
 // Same arithmetic, same order, as scan_fwd_kernel: the results are bit-identical.
 template <int DK, int DV, int DVB>
 __global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a) {
     typedef bf16_t T;
     typedef Op<T> O;
     typedef ChunkOps<T, DK, DVB / 16> CO;
-    constexpr int MV = DVB / 16, ND = DK / 64, G = DV / DVB, KS = CO::KS, NF = 2 * KS, NBUF = 3;
+    constexpr int MV = DVB / 16, ND = DK / 64, G = DV / DVB, KS = CO::KS, NF = KS, NBUF = 3;
     constexpr int LDST = 2 * DK + O::PAD, LDV = 64 + O::PAD;
     __shared__ __align__(16) T sSt[DVB * LDST];
     __shared__ __align__(16) T sV0[DVB * LDV];
     __shared__ __align__(16) T sVg[DVB * LDV];
     __shared__ __align__(16) T sVr[DVB * LDV];
+    __shared__ __align__(16) T sRt[DVB * LDV];               // R^T = (V - a.(K S) + pb.(K M))^T, all 64 tokens
     __shared__ __align__(16) T sF[NBUF][4][NF][64 * O::EPL]; // [buffer][compute wave][fragment][lane slot]
 
     int bh, blkv;
@@ -330,16 +342,12 @@ __global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a)
         // ---------------- loader waves
         const int cw = wv - 4, i = cw * 16 + r;
         auto issue = [&](int n, int buf) {
-            const size_t blk = (size_t)bh * d.N + n;
-            const T *Yg = static_cast<const T *>(a.nY) + blk * (64 * DK);
-            const T *Zg = static_cast<const T *>(a.Z) + blk * (64 * DK);
+            const size_t tok = ((size_t)b * d.T + (size_t)n * 64 + i) * d.H + h;
+            const T *Kg = static_cast<const T *>(a.k) + tok * DK + kg * O::EPL;
 #pragma unroll
-            for (int s = 0; s < KS; ++s) {
-                __builtin_amdgcn_global_load_lds(Yg + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL),
+            for (int s = 0; s < KS; ++s)
+                __builtin_amdgcn_global_load_lds(Kg + s * O::KSTEP,
                                                  (__attribute__((address_space(3))) void *)&sF[buf][cw][s][0], 16, 0, 0);
-                __builtin_amdgcn_global_load_lds(Zg + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL),
-                                                 (__attribute__((address_space(3))) void *)&sF[buf][cw][KS + s][0], 16, 0, 0);
-            }
         };
         // two chunks ahead: while chunk n computes, chunk n+1 is complete or landing and chunk n+2 is issued
         issue(d.n0, d.n0 % NBUF);
@@ -349,8 +357,9 @@ __global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a)
         for (int n = d.n0; n < d.n1; ++n) {
             issue((n + 2 < d.n1) ? n + 2 : d.n1 - 1, (n + 2) % NBUF);
             __builtin_amdgcn_s_barrier();            // barrier 1 of the chunk
-            __builtin_amdgcn_s_waitcnt(0x0F70 | NF); // vmcnt(NF): chunk n+1 landed
             __builtin_amdgcn_s_barrier();            // barrier 2
+            __builtin_amdgcn_s_waitcnt(0x0F70 | NF); // vmcnt(NF): chunk n+1 landed
+            __builtin_amdgcn_s_barrier();            // barrier 3
         }
         __builtin_amdgcn_s_waitcnt(0x0F70); // drain
         return;
@@ -389,26 +398,25 @@ __global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a)
                 store4(st + off, accS[mv][nd]);
         };
         fetch_part<T, DK, DV, DVB, false, true, 1>(nxt, d, a, bh, b, h, nn, dv0);
-        // stage 1
-        f32x4 accO[MV], vt[MV], accV[MV], accOS[MV], accOM[MV];
-#pragma unroll
-        for (int mv = 0; mv < MV; ++mv) accV[mv] = widen4(cur.u[mv]);
+        // stage 1: R^T and the read-outs for token i, then V~^T = R^T T^T over all 64 tokens
+        f32x4 accO[MV], vt[MV], x1[MV], x2[MV], accOS[MV], accOM[MV];
+        zero_acc(x1);
+        zero_acc(x2);
         zero_acc(accOS);
         zero_acc(accOM);
         const T *sp = sSt + r * LDST + kg * O::EPL;
         const T *fp = &sF[n % NBUF][w][0][lane * O::EPL];
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            const typename O::Frag fy = O::load(fp + s * (64 * O::EPL));
-            const typename O::Frag fz = O::load(fp + (KS + s) * (64 * O::EPL));
+            const typename O::Frag fk = O::load(fp + s * (64 * O::EPL));
             const typename O::Frag fq = cur.q[s];
 #pragma unroll
             for (int mv = 0; mv < MV; ++mv) {
                 const typename O::Frag fs = O::load(sp + mv * 16 * LDST + s * O::KSTEP);
                 const typename O::Frag fm = O::load(sp + mv * 16 * LDST + DK + s * O::KSTEP);
-                accV[mv] = O::mma(fs, fy, accV[mv]);
+                x1[mv] = O::mma(fs, fk, x1[mv]);
                 accOS[mv] = O::mma(fs, fq, accOS[mv]);
-                accV[mv] = O::mma(fm, fz, accV[mv]);
+                x2[mv] = O::mma(fm, fk, x2[mv]);
                 accOM[mv] = O::mma(fm, fq, accOM[mv]);
             }
             if (a.states_saved) {
@@ -421,8 +429,24 @@ __global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a)
 #pragma unroll
         for (int mv = 0; mv < MV; ++mv) {
             accO[mv] = d.scale * (cur.sa * accOS[mv] - cur.sb * accOM[mv]);
+            const f32x4 rr = widen4(cur.u[mv]) - cur.sa * x1[mv] + cur.pb * x2[mv];
 #pragma unroll
-            for (int x = 0; x < 4; ++x) vt[mv][x] = rounded<T>(accV[mv][x]);
+            for (int x = 0; x < 4; ++x) sRt[(mv * 16 + kg * 4 + x) * LDV + i] = from_f32<T>(rr[x]);
+        }
+        __syncthreads(); // barrier 1 of the chunk (the loader waves count it too)
+        {
+            f32x4 accV[MV];
+            zero_acc(accV);
+            const T *rp = sRt + r * LDV + kg * O::EPL;
+#pragma unroll
+            for (int s = 0; s < CO::KS2; ++s)
+#pragma unroll
+                for (int mv = 0; mv < MV; ++mv)
+                    accV[mv] = O::mma(O::load(rp + mv * 16 * LDV + s * O::KSTEP), cur.tm[s], accV[mv]);
+#pragma unroll
+            for (int mv = 0; mv < MV; ++mv)
+#pragma unroll
+                for (int x = 0; x < 4; ++x) vt[mv][x] = rounded<T>(accV[mv][x]);
         }
         if (a.vt_saved) {
             T *vs = static_cast<T *>(a.vt_saved) + tok * DV + dv0 + kg * 4;
