@@ -41,15 +41,16 @@ def bytes_per_tokhd(C, dk, dv, es, keep):
     stored element; gates and coefficients are fp32).  `keep`: the training forward also writes the
     reverse pass's operands and the chunk-start states."""
     coef = 6 * 4
-    fwd_ops = (dk + dv + 2 * dk + C) * es + coef          # K^T, U, -Y, Z, Bm, coefficient block
-    rev_ops = (4 * dk + 2 * C) * es + coef                # K^T, Q^T, -Y^T, Z^T, Bm^T, T^T, coefficient block
+    fwd_ops = (dk + 2 * C) * es + coef                    # K^T, T, Bm, coefficient block
+    rev_ops = (2 * dk + 2 * C) * es + coef                # K^T, Q^T, Bm^T, T^T, coefficient block
     states = 2 * dk * dv * es // C                        # S, M of one chunk, per token
+    qk = 2 * dk * es
     return {
-        "intra_fwd": (2 * dk + dv) * es + 16 + (fwd_ops + rev_ops - dk * es - coef if keep else fwd_ops),
-        "scan_fwd": fwd_ops + dk * es + 2 * dv * es + (states if keep else 0),   # + q; V~ and o out
-        "intra_bwd": 2 * dk * es + 16 + rev_ops,
+        "intra_fwd": qk + 16 + (fwd_ops + rev_ops - dk * es - coef if keep else fwd_ops),
+        "scan_fwd": fwd_ops + qk + dv * es + 2 * dv * es + (states if keep else 0),   # + q, k, v; V~ and o out
+        "intra_bwd": qk + 16 + rev_ops,
         "rebuild": dk * es + dv * es + coef + states,
-        "scan_bwd": rev_ops - dk * es + dk * es + dv * es + dv * es + states,    # ops w/o K^T, + k, dO; dv, dstates out
+        "scan_bwd": rev_ops + dk * es + dv * es + dv * es + states,                   # + k, dO; dv, dstates out
         "grad": 2 * dk * es + 3 * dv * es + 2 * dk * es + 2 * states + 16 + 2 * dk * es + 12,
     }
 
