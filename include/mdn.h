@@ -75,7 +75,7 @@ int mdn_workspace_bytes(const mdn_shape *shape, int which, size_t *bytes_out);
 int mdn_saved_states_bytes(const mdn_shape *shape, size_t *bytes_out);
 
 /* Bytes of the optional `operands_saved` buffer: the chunk-local operands of the reverse pass
- * (transposed WY-style factors, masked products and triangular inverse, Sec. 3.1 "Chunkwise
+ * (transposed key and query tiles, masked products and triangular inverse, Sec. 3.1 "Chunkwise
  * Algorithm") that a training forward can keep so that the backward does not recompute them. */
 int mdn_saved_operands_bytes(const mdn_shape *shape, size_t *bytes_out);
 

@@ -1,6 +1,8 @@
 // Sequential inter-chunk propagation of the state S and the momentum M (forward), Sec. 3.1
 // "Chunkwise Algorithm":
-//     V~  = U - Y S + Z M
+//     V~  = U - Y S + Z M                      with U = T V, Y = T diag(a^-) P, Z = T diag(b^-) P, P = alpha K
+//         = T (V - a . (K S) + pb . (K M))     alpha_i a_{i-1} = a_i, pb_i = alpha_i b_{i-1}  (T pulled out:
+//                                              U, Y, Z are never formed, the scan applies T itself)
 //     O   = diag(a) Q~ S - diag(b) Q~ M + Bm V~
 //     S'  = a_C S - b_C M + (diag(Gamma_C) K~)^T V~
 //     M'  = m_C M - (diag(Rho_C) K~)^T V~
@@ -10,16 +12,18 @@
 //
 // Inside a workgroup (4 waves) every product is formed TRANSPOSED, with the dv index as the MFMA
 // row index: an accumulator lane then holds 4 consecutive dv of one token (or of one dk row), which
-// is 8 contiguous bytes of V~, O, U and of the saved states in HBM.
+// is 8 contiguous bytes of V, V~, O and of the saved states in HBM.
 //   S^T, M^T live in fp32 accumulators (wave w owns dk columns [w*dk/4, (w+1)*dk/4)); a storage-type
-//   copy sits in LDS as [dv][dk | dk] and is the A operand of the dk-contractions of stage 1
-//   (wave w owns tokens 16w..16w+15): V~^T and the two inter-chunk read-outs.  V~^T goes to LDS as
-//   [dv][token] in three scalings (raw, Gamma_C eta, -Rho_C eta): the A operand of the token-contractions
-//   of stage 2 (intra-chunk output, state update).  Scalings along a contraction index are folded
-//   into those copies, so the B operands are raw rows of -Y, Z, Q, Bm, K^T straight from HBM.
-// Two barriers per chunk.  Nothing a chunk reads from HBM depends on the state, so all of a chunk's
-// fragments, its U tile and its coefficients are fetched into registers one whole chunk ahead; the
-// serial chain then only waits on LDS and MFMA latency.
+//   copy sits in LDS as [dv][dk | dk] and is the A operand of the dk-contractions of stage 1a
+//   (wave w owns tokens 16w..16w+15): (K S)^T, (K M)^T and the two inter-chunk read-outs.
+//   R^T = (V - a.(K S) + pb.(K M))^T goes to LDS as [dv][token]; stage 1b contracts it over ALL tokens with
+//   the wave's rows of T: V~^T, which goes to LDS as [dv][token] in three scalings (raw, Gamma_C eta,
+//   -Rho_C eta): the A operand of the token-contractions of stage 2 (intra-chunk output, state update).
+//   Scalings along a contraction index are folded into those copies, so the B operands are raw rows of
+//   K, Q, T, Bm, K^T straight from HBM.
+// Three barriers per chunk.  Nothing a chunk reads from HBM depends on the state, so all of a chunk's
+// fragments, its V tile and its coefficients are requested one whole chunk ahead; the serial chain then
+// only waits on LDS and MFMA latency.
 #include "mdn_device.h"
 #include "mdn_kernels.h"
 
