@@ -67,15 +67,21 @@ __device__ __forceinline__ float coldot(f32x4 t, f32x4 xv) {
 
 // one natural-layout [64][D] token tile, HBM -> LDS without registers: the 16-byte slot (row, position p)
 // receives piece p ^ (row & XM) of that row.  Issued by 2 waves (lw = 0, 1), NDMA instructions of 64
-// consecutive slots each.
+// consecutive slots each (m0 = LDS address of the 64 slots; lane l fills slot l).
+// Written as inline assembly on purpose: the compiler then does not know of the transfer, and so neither makes
+// the issuing wave (nor, through its path-insensitive bookkeeping, any other wave) drain its whole load queue
+// at the next LDS instruction.  Waiting for the transfer is the caller's job (s_waitcnt vmcnt(0) by the
+// issuing waves before the barrier that publishes the tile); the compiler's own waits for loads it knows of
+// can only become longer through the extra entries in the queue, never shorter (loads return in order).
 template <typename T, int D>
 __device__ __forceinline__ void dma_token_tile(T *ldst, const T *src, unsigned rs, int lw, int lane) {
     constexpr int E = Op<T>::EPL, CPR = D / E, XM = (CPR < 16 ? CPR : 16) - 1, NDMA = CPR / 2;
 #pragma unroll
     for (int u = 0; u < NDMA; ++u) {
         const int blk64 = u * 2 + lw, sl = blk64 * 64 + lane, row = sl / CPR, pc = (sl % CPR) ^ (row & XM);
-        __builtin_amdgcn_global_load_lds(at32(src, row * rs + pc * E),
-                                         (__attribute__((address_space(3))) void *)(ldst + blk64 * 64 * E), 16, 0, 0);
+        const T *g = at32(src, row * rs + pc * E);
+        const unsigned l = (unsigned)(size_t)((__attribute__((address_space(3))) T *)(ldst + blk64 * 64 * E));
+        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(l) : "memory", "m0");
     }
 }
 
@@ -212,6 +218,7 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
         dma_token_tile<T, D>(sK, kgl, rsk, w - 6, lane);
         dma_token_tile<T, D>(sDO, dog, rsv, w - 6, lane);
         dma_token_tile<T, D>(sDR, drg, rsv, w - 6, lane);
+        __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): the tiles have landed before the barrier publishes them
     }
     const T *tVt = STAGED ? sVt : vtg, *tK = STAGED ? sK : kgl, *tDR = STAGED ? sDR : drg, *tDO = STAGED ? sDO : dog;
     const int ldV = (int)rsv, ldK = (int)rsk; // row strides of the global tiles (fp32 path)
