@@ -9,11 +9,11 @@
 
 namespace mdn {
 
-// ---- scans across the 64 lanes of a wave (Kogge-Stone); lane i holds element i
+// ---- scans across the 64 lanes of a wave (Kogge-Stone); lane i holds element i.  (The lane index is a
+//      parameter so that a caller with a long-running loop can pass its own, loop-variant copy.)
 
 // inclusive prefix product
-__device__ __forceinline__ float scan_prod(float v) {
-    const int lane = lane_id();
+__device__ __forceinline__ float scan_prod(float v, int lane = lane_id()) {
 #pragma unroll
     for (int dlt = 1; dlt < 64; dlt <<= 1) {
         const float o = __shfl_up(v, dlt);
@@ -23,8 +23,7 @@ __device__ __forceinline__ float scan_prod(float v) {
 }
 
 // x_i = c_i x_{i-1} + d_i with x_{-1} = 0: on return d holds x_i (c holds prod_{l<=i} c_l)
-__device__ __forceinline__ void scan_affine_fwd(float &c, float &d) {
-    const int lane = lane_id();
+__device__ __forceinline__ void scan_affine_fwd(float &c, float &d, int lane = lane_id()) {
 #pragma unroll
     for (int dlt = 1; dlt < 64; dlt <<= 1) {
         const float oc = __shfl_up(c, dlt), od = __shfl_up(d, dlt);
@@ -36,8 +35,7 @@ __device__ __forceinline__ void scan_affine_fwd(float &c, float &d) {
 }
 
 // x_i = c_i x_{i+1} + d_i with x_64 = 0: on return d holds x_i
-__device__ __forceinline__ void scan_affine_rev(float &c, float &d) {
-    const int lane = lane_id();
+__device__ __forceinline__ void scan_affine_rev(float &c, float &d, int lane = lane_id()) {
 #pragma unroll
     for (int dlt = 1; dlt < 64; dlt <<= 1) {
         const float oc = __shfl_down(c, dlt), od = __shfl_down(d, dlt);
@@ -84,8 +82,8 @@ __device__ __forceinline__ void coef_column_scan(float al, float be, float mu, f
 //      gC, rC (row 63) are returned by wave 3 only.
 template <bool WANT_RHO>
 __device__ __forceinline__ void coef_column_scan_blocked(float al, float be, float mu, float *sG, float *sRho, int ldg,
-                                                         int w, float &gC, float &rC) {
-    const int j = lane_id(), jl = j & 15;
+                                                         int w, float &gC, float &rC, int j = lane_id()) {
+    const int jl = j & 15;
     // inclusive suffix products inside the 16-lane segment: (A, B, M)_j = T_end o ... o T_j
     float A = al, B = be * mu, M = mu;
 #pragma unroll
@@ -170,17 +168,18 @@ __device__ __forceinline__ void coef_column_scan_reverse(float al, float be, flo
 //      row below the segment would enter each row:
 //        G_ij = Gloc_ij + gc_i Gin_j          R_ij = Rloc_ij + ec_i Gin_j + mc_i Rin_j
 //        gc_i = alpha_{i+1} gc_{i+1},  mc_i = mu_{i+1} mc_{i+1},  ec_i = beta_i gc_i + mu_{i+1} ec_{i+1}
-//      It leaves the segment's top row (local values, zero above the diagonal) and that row's three
+//      It leaves the segment's top row (local values, zero above the diagonal) and every row's three
 //      coefficients in LDS.  After a workgroup barrier, part 2 chains the top rows of the segments below to
 //      get what comes in, and completes and stores the wave's rows.
 struct RevScanRows {
-    float G[16], R[16], gc[16], ec[16], mc[16];
+    float G[16], R[16];
 };
-// sTop: [4][2][64] floats (top rows: G, R), sTopC: [4][3] floats (top-row coefficients)
+// sTop: [4][2][64] floats (top rows: G, R); sRowC: [3][64] floats (gc, ec, mc of every row: they are the
+// same for all columns, so one copy in LDS instead of 48 registers in every lane)
 __device__ __forceinline__ void coef_scan_reverse_part1(float al, float be, float mu, const float *sD1, const float *sD2,
                                                         float dgc, float drc, int ldg, int w, RevScanRows &rr, float *sTop,
-                                                        float *sTopC) {
-    const int j = lane_id(), i0 = w * 16; // (w is wave-uniform: the lane selects below are scalar operands)
+                                                        float *sRowC, int j = lane_id()) {
+    const int i0 = w * 16; // (w is wave-uniform: the lane selects below are scalar operands)
     float dir[16];
 #pragma unroll
     for (int u = 0; u < 16; ++u) dir[u] = sD1[(i0 + u) * ldg + j] + sD2[(i0 + u + 1) * ldg + j];
@@ -203,9 +202,11 @@ __device__ __forceinline__ void coef_scan_reverse_part1(float al, float be, floa
         gc = a_n * gc;
         ec = b_i * gc + m_n * ec;
         mc = m_n * mc;
-        rr.gc[u] = gc;
-        rr.ec[u] = ec;
-        rr.mc[u] = mc;
+        if (j == 0) {
+            sRowC[i] = gc;
+            sRowC[64 + i] = ec;
+            sRowC[128 + i] = mc;
+        }
         if (u > 0) {
             cg = lane_bcast(al, i) * G;
             cr = lane_bcast(mu, i) * R;
@@ -213,22 +214,16 @@ __device__ __forceinline__ void coef_scan_reverse_part1(float al, float be, floa
     }
     sTop[(w * 2 + 0) * 64 + j] = (j <= i0) ? rr.G[0] : 0.f;
     sTop[(w * 2 + 1) * 64 + j] = (j <= i0) ? rr.R[0] : 0.f;
-    if (j == 0) {
-        sTopC[w * 3 + 0] = rr.gc[0];
-        sTopC[w * 3 + 1] = rr.ec[0];
-        sTopC[w * 3 + 2] = rr.mc[0];
-    }
 }
 
 // Writes sGa[i][j] = G_ij, sRa[i][j] = R_ij for the wave's 16 rows (zero for i < j).
 __device__ __forceinline__ void coef_scan_reverse_part2(int ldg, int w, const RevScanRows &rr, const float *sTop,
-                                                        const float *sTopC, float *sGa, float *sRa) {
-    const int j = lane_id();
+                                                        const float *sRowC, float *sGa, float *sRa, int j = lane_id()) {
     float Gin = 0.f, Rin = 0.f; // G, R of the row just below this wave's segment
 #pragma unroll
     for (int seg = 3; seg >= 1; --seg) {
         if (seg > w) {
-            const float gct = sTopC[seg * 3 + 0], ect = sTopC[seg * 3 + 1], mct = sTopC[seg * 3 + 2];
+            const float gct = sRowC[seg * 16], ect = sRowC[64 + seg * 16], mct = sRowC[128 + seg * 16];
             const bool act = j <= seg * 16;
             const float Gt = sTop[(seg * 2 + 0) * 64 + j] + (act ? gct * Gin : 0.f);
             const float Rt = sTop[(seg * 2 + 1) * 64 + j] + (act ? ect * Gin + mct * Rin : 0.f);
@@ -239,8 +234,8 @@ __device__ __forceinline__ void coef_scan_reverse_part2(int ldg, int w, const Re
 #pragma unroll
     for (int u = 0; u < 16; ++u) {
         const int i = w * 16 + u;
-        const float G = rr.G[u] + rr.gc[u] * Gin;
-        const float R = rr.R[u] + rr.ec[u] * Gin + rr.mc[u] * Rin;
+        const float G = rr.G[u] + sRowC[i] * Gin;
+        const float R = rr.R[u] + sRowC[64 + i] * Gin + sRowC[128 + i] * Rin;
         sGa[i * ldg + j] = (i >= j) ? G : 0.f;
         sRa[i * ldg + j] = (i >= j) ? R : 0.f;
     }

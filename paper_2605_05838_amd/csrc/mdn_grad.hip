@@ -45,10 +45,6 @@ namespace {
 
 constexpr int LDG = 68; // row stride of the fp32 64x64 coefficient matrices in LDS (rows 16-byte aligned)
 constexpr int GT = 512; // threads per workgroup: 8 waves
-#ifndef MDN_GRAD_STAGGER
-#define MDN_GRAD_STAGGER 0
-#endif
-constexpr int STAGGER = MDN_GRAD_STAGGER;
 
 // row-dot partial sums, one [dk tiles][64] block each
 enum { P_DA = 0, P_DB, P_DAM, P_DBM, P_DGC, P_DRC, P_DALK, P_DETK, P_COUNT };
@@ -128,31 +124,64 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     T *sK = sW;
     static_assert(4 * LDW >= D, "k tile does not fit the W space");
     __shared__ float s_al[64], s_et[64], s_a[64], s_b[64];
-    __shared__ float sTopC[12];
+    __shared__ float sRowC[3 * 64]; // reverse scan: the three per-row coefficients
     __shared__ float s_gC[64], s_rC[64];
     __shared__ float s_ga[64], s_gb[64], s_gm[64];
     __shared__ float s_red[8][3];
 
-    const int tid = threadIdx.x, lane = lane_id(), r = lane & 15, kg = lane >> 4;
-    const int w = __builtin_amdgcn_readfirstlane(wave_id()); // wave-uniform by construction: lets branches on it be scalar
-    const int wt = w & 3, hf = w >> 2;    // phase A: token tile, half of the j tiles
-    const int kt = w % NKW, tg = w / NKW; // phases B-F: dk tile, token group
-    const int i = wt * 16 + r;            // this lane's token (MFMA column) in phase A
-    const int n = d.n0 + blockIdx.x, bh = blockIdx.y, b = bh / d.H, h = bh % d.H;
-    const size_t tok0 = ((size_t)b * d.T + (size_t)n * 64) * d.H + h;
-    const size_t blk = (size_t)bh * d.N + n;
+    // Wave and lane indices, re-derived at the start of every chunk from values the compiler cannot see
+    // through: otherwise every address and every wave-uniform offset this kernel ever forms is hoisted out of
+    // the chunk loop and kept in a register for its whole duration (hundreds of them, vector and scalar).
+    int w;              // wave-uniform by construction (a scalar register): branches on it are scalar
+    int wt, hf, kt, tg; // phase A: token tile, half of the j tiles; phases B-F: dk tile, token group
+    int tid, lane, r, kg, i; // i: this lane's token (MFMA column) in phase A
+    unsigned gl;
+    auto refresh_ids = [&]() {
+        int ws = __builtin_amdgcn_readfirstlane(wave_id());
+        asm volatile("" : "+s"(ws));
+        w = ws;
+        wt = w & 3;
+        hf = w >> 2;
+        kt = w % NKW;
+        tg = w / NKW;
+        int t = threadIdx.x;
+        asm volatile("" : "+v"(t));
+        tid = t;
+        lane = t & 63;
+        r = lane & 15;
+        kg = lane >> 4;
+        i = wt * 16 + r;
+        gl = (unsigned)(lane * d.H);
+    };
+    refresh_ids();
     // per-lane offsets inside the chunk stay 32-bit (a uniform 64-bit base plus a 32-bit lane offset is
     // one address register instead of two)
     const unsigned rsk = (unsigned)d.H * DK, rsv = (unsigned)d.H * DV;
-    const T *qg = static_cast<const T *>(a.q) + tok0 * DK;
-    const T *kgl = static_cast<const T *>(a.k) + tok0 * DK;
-    const T *vtg = static_cast<const T *>(a.vt_saved) + tok0 * DV;
-    const T *dog = static_cast<const T *>(a.dO) + tok0 * DV;
-    const T *drg = static_cast<const T *>(a.dv) + tok0 * DV; // dR = T^T dV~ (= dV), from the reverse scan
-    const T *KTg = static_cast<const T *>(a.KT) + blk * (DK * 64);
-    const T *QTg = static_cast<const T *>(a.QT) + blk * (DK * 64);
-    const T *Sg = static_cast<const T *>(a.states) + blk * (2 * DK * DV), *Mg = Sg + DK * DV;
-    const T *dSg = static_cast<const T *>(a.dstates) + blk * (2 * DK * DV), *dMg = dSg + DK * DV;
+
+    // The workgroup walks the chunks c, c + gridDim.x, ... of this launch (c counts the chunks [n0, n1) of all
+    // (batch, head) pairs, chunk index fastest).
+    const int nper = d.n1 - d.n0, nchunks = nper * d.BH;
+    int chunk = blockIdx.x;
+    if (chunk >= nchunks) return;
+    size_t tok0, blk;
+    const T *qg, *kgl, *vtg, *dog, *drg, *KTg, *QTg, *Sg, *Mg, *dSg, *dMg;
+    auto set_chunk = [&](int c) {
+        const int n = d.n0 + c % nper, bh = c / nper, b = bh / d.H, h = bh % d.H;
+        tok0 = ((size_t)b * d.T + (size_t)n * 64) * d.H + h;
+        blk = (size_t)bh * d.N + n;
+        qg = static_cast<const T *>(a.q) + tok0 * DK;
+        kgl = static_cast<const T *>(a.k) + tok0 * DK;
+        vtg = static_cast<const T *>(a.vt_saved) + tok0 * DV;
+        dog = static_cast<const T *>(a.dO) + tok0 * DV;
+        drg = static_cast<const T *>(a.dv) + tok0 * DV; // dR = T^T dV~ (= dV), from the reverse scan
+        KTg = static_cast<const T *>(a.KT) + blk * (DK * 64);
+        QTg = static_cast<const T *>(a.QT) + blk * (DK * 64);
+        Sg = static_cast<const T *>(a.states) + blk * (2 * DK * DV);
+        Mg = Sg + DK * DV;
+        dSg = static_cast<const T *>(a.dstates) + blk * (2 * DK * DV);
+        dMg = dSg + DK * DV;
+    };
+    set_chunk(chunk);
 
     // fragment of row `row`, contraction step st of a token tile (in LDS, or in global memory with row stride ld)
     auto tfrag = [&](const T *tile, int ld, int row, int st) -> Frag {
@@ -173,56 +202,70 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
         return s;
     };
 
-    // ---------------- prologue: gates first, then everything this workgroup will read, in order of use
-    if (STAGGER > 0) {
-        // first round of workgroups: every other one starts late, so that the memory-heavy start of one
-        // workgroup falls into the memory-idle end of its neighbours for the rest of the launch
-        const int lin = blockIdx.y * gridDim.x + blockIdx.x;
-        if (lin < 256 && (lin & 1))
-            for (int z = 0; z < STAGGER; ++z) __builtin_amdgcn_s_sleep(127);
-    }
-    const unsigned gl = (unsigned)(lane * d.H);
-    const float g_al = *at32(a.alpha + tok0, gl), g_be = *at32(a.beta + tok0, gl), g_mu = *at32(a.mu + tok0, gl);
-    const float g_et = a.eta ? *at32(a.eta + tok0, gl) : 1.f;
-    for (int c = tid; c < LDG; c += GT) sDG2[64 * LDG + c] = 0.f;
+    // ---- what a chunk needs first is requested as early as possible: its gates, its token tiles (straight into
+    //      LDS, waves 6 and 7) and its q fragments.  For every chunk but the workgroup's first that is during
+    //      the coefficient phase of the chunk before, which has no memory traffic of its own.
+    float n_al = 0.f, n_be = 0.f, n_mu = 0.f, n_et = 1.f; // gates of token `lane` of the chunk being requested
     Frag fq[KSK]; // phase A B fragments of q (no LDS copy): row = token i
-#pragma unroll
-    for (int s = 0; s < KSK; ++s) fq[s] = O::load(at32(qg, i * rsk + s * O::KSTEP + kg * E));
-
-    // ---------------- phase 0: forward coefficients (needs only the gates): waves 0-3 the matrices Gamma, Rho
-    //                  (16 rows each), wave 4 the vectors by wave scans
-    float pa = 0.f, pm = 0.f, pb = 0.f; // a_lane, m_lane, b_lane (wave 4)
-    if (w < 4) {
-        float gC, rC;
-        coef_column_scan_blocked<true>(g_al, g_be, g_mu, sG, sRho, LDG, w, gC, rC);
-        if (w == 3) {
-            s_gC[lane] = gC; // Gamma_{C,j}
-            s_rC[lane] = rC; // Rho_{C,j}
+    auto request_gates = [&]() {
+        if (w < 6) { // waves 6, 7 never use them, and must not wait for anything behind their tile transfers
+            n_al = *at32(a.alpha + tok0, gl);
+            n_be = *at32(a.beta + tok0, gl);
+            n_mu = *at32(a.mu + tok0, gl);
+            n_et = a.eta ? *at32(a.eta + tok0, gl) : 1.f;
         }
-    }
-    if (w == 4) {
-        pa = scan_prod(g_al);
-        pm = scan_prod(g_mu);
-        float c = g_al;
-        pb = g_be * pm;
-        scan_affine_fwd(c, pb);
-        s_al[lane] = g_al;
-        s_et[lane] = g_et;
-        s_a[lane] = pa;
-        s_b[lane] = pb;
-    }
-    // waves 6, 7 start the token tiles on their way to LDS.  (Last in program order before the barrier: a wave
-    // that has such a transfer pending, also only in the compiler's view of it, waits at its next LDS instruction.)
+    };
+    auto request_q = [&]() {
+#pragma unroll
+        for (int s = 0; s < KSK; ++s) fq[s] = O::load(at32(qg, i * rsk + s * O::KSTEP + kg * E));
+    };
+    // ---- phase 0: forward coefficients of the chunk whose gates are in n_*: waves 0-3 the matrices Gamma, Rho
+    //      (16 rows each), wave 4 the vectors by wave scans
+    float g_al = 0.f, g_be = 0.f, g_mu = 0.f, g_et = 1.f; // gates of token `lane` of the current chunk
+    float pa = 0.f, pm = 0.f, pb = 0.f;                   // a_lane, m_lane, b_lane of the current chunk (wave 4)
+    auto phase0 = [&]() {
+        g_al = n_al;
+        g_be = n_be;
+        g_mu = n_mu;
+        g_et = n_et;
+        if (w < 4) {
+            float gC, rC;
+            coef_column_scan_blocked<true>(g_al, g_be, g_mu, sG, sRho, LDG, w, gC, rC, lane);
+            if (w == 3) {
+                s_gC[lane] = gC; // Gamma_{C,j}
+                s_rC[lane] = rC; // Rho_{C,j}
+            }
+        }
+        if (w == 4) {
+            pa = scan_prod(g_al, lane);
+            pm = scan_prod(g_mu, lane);
+            float c = g_al;
+            pb = g_be * pm;
+            scan_affine_fwd(c, pb, lane);
+            s_al[lane] = g_al;
+            s_et[lane] = g_et;
+            s_a[lane] = pa;
+            s_b[lane] = pb;
+        }
+    };
+
+    for (int c = tid; c < LDG; c += GT) sDG2[64 * LDG + c] = 0.f;
+    request_gates();
     if (STAGED && w >= 6) {
         dma_token_tile<T, D>(sVt, vtg, rsv, w - 6, lane);
         dma_token_tile<T, D>(sK, kgl, rsk, w - 6, lane);
         dma_token_tile<T, D>(sDO, dog, rsv, w - 6, lane);
         dma_token_tile<T, D>(sDR, drg, rsv, w - 6, lane);
-        __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): the tiles have landed before the barrier publishes them
     }
-    const T *tVt = STAGED ? sVt : vtg, *tK = STAGED ? sK : kgl, *tDR = STAGED ? sDR : drg, *tDO = STAGED ? sDO : dog;
+    request_q();
+    phase0();
+
     const int ldV = (int)rsv, ldK = (int)rsk; // row strides of the global tiles (fp32 path)
-    __syncthreads(); // token tiles and q fragments landed, coefficients ready
+    for (;;) {
+    refresh_ids();
+    const T *tVt = STAGED ? sVt : vtg, *tK = STAGED ? sK : kgl, *tDR = STAGED ? sDR : drg, *tDO = STAGED ? sDO : dog;
+    if (STAGED && w >= 6) __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): this chunk's tiles have landed
+    __syncthreads(); // token tiles in LDS, coefficients ready
     // what the later phases read goes on its way now, in order of use
     Frag aK[KS2], aQ[KS2]; // this wave's rows of K^T, Q^T
 #pragma unroll
@@ -416,6 +459,20 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
         for (int k2 = 0; k2 < NKW; ++k2) s += spart[(q * NKW + k2) * 64 + lane];
         return s;
     };
+    // the workgroup's next chunk: gates and three of the four token tiles go on their way now
+    // (the LDS space of V~, dO, dR is free; that of k holds this phase's matrices until the row sums are done)
+    const size_t tok0_cur = tok0;
+    const int next = chunk + (int)gridDim.x;
+    const bool has_next = STAGED && next < nchunks; // (the unstaged kernel is launched with one workgroup per chunk)
+    if (has_next) {
+        set_chunk(next);
+        request_gates();
+        if (STAGED && w >= 6) {
+            dma_token_tile<T, D>(sVt, vtg, rsv, w - 6, lane);
+            dma_token_tile<T, D>(sDO, dog, rsv, w - 6, lane);
+            dma_token_tile<T, D>(sDR, drg, rsv, w - 6, lane);
+        }
+    }
     RevScanRows rr;
     float db = 0.f, da = 0.f, dm = 0.f, dalk = 0.f, detk = 0.f;
     if (w < 4) {
@@ -424,7 +481,7 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
             dgc = total(P_DGC);
             drc = total(P_DRC);
         }
-        coef_scan_reverse_part1(g_al, g_be, g_mu, sDG1, sDG2, dgc, drc, LDG, w, rr, sTop, sTopC);
+        coef_scan_reverse_part1(g_al, g_be, g_mu, sDG1, sDG2, dgc, drc, LDG, w, rr, sTop, sRowC, lane);
     }
     if (w == 4) {
         // vectors (lane i = token i): reverse of b_i = alpha_i b_{i-1} + beta_i m_i, a_i = alpha_i a_{i-1},
@@ -448,16 +505,16 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
         const float dam_next = (li < 63) ? dam_dn : dS_S;
         float cb = (li < 63) ? al_next : 0.f;
         db = t_db + dbm_next;
-        scan_affine_rev(cb, db);
+        scan_affine_rev(cb, db, lane);
         float ca = (li < 63) ? al_next : 0.f;
         da = t_da + dam_next;
-        scan_affine_rev(ca, da);
+        scan_affine_rev(ca, da, lane);
         float cm = (li < 63) ? mu_next : 0.f;
         dm = (li == 63 ? dM_M : 0.f) + g_be * db;
-        scan_affine_rev(cm, dm);
+        scan_affine_rev(cm, dm, lane);
     }
     __syncthreads(); // segment top rows exchanged; every partial sum has been read (their space is reused now)
-    if (w < 4) coef_scan_reverse_part2(LDG, w, rr, sTop, sTopC, sGa, sRa);
+    if (w < 4) coef_scan_reverse_part2(LDG, w, rr, sTop, sRowC, sGa, sRa, lane);
     __syncthreads();
     {
         // dalpha_i += sum_{j<i} G_ij Gamma_{i-1,j};  dbeta_i += sum_{j<=i} G_ij Rho_ij;
@@ -491,16 +548,35 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
         const float aprev = __shfl_up(pa, 1), bprev = __shfl_up(pb, 1), mprev = __shfl_up(pm, 1);
         const float a_prev = (li > 0) ? aprev : 1.f, b_prev = (li > 0) ? bprev : 0.f, m_prev = (li > 0) ? mprev : 1.f;
         const unsigned g = (unsigned)(li * d.H);
-        *at32(a.dalpha + tok0, g) = s_ga[li] + db * b_prev + da * a_prev + dalk;
-        *at32(a.dbeta + tok0, g) = s_gb[li] + db * pm;
-        *at32(a.dmu + tok0, g) = s_gm[li] + dm * m_prev;
-        if (a.deta) *at32(a.deta + tok0, g) = detk;
+        *at32(a.dalpha + tok0_cur, g) = s_ga[li] + db * b_prev + da * a_prev + dalk;
+        *at32(a.dbeta + tok0_cur, g) = s_gb[li] + db * pm;
+        *at32(a.dmu + tok0_cur, g) = s_gm[li] + dm * m_prev;
+        if (a.deta) *at32(a.deta + tok0_cur, g) = detk;
     }
+    if (!has_next) break;
+    chunk = next;
+    if (STAGED && w >= 6) dma_token_tile<T, D>(sK, kgl, rsk, w - 6, lane); // the row sums are done with its space
+    request_q(); // (not earlier: 16 registers that this phase has no room for)
+    phase0(); // Gamma, Rho are free again after the row sums; the next chunk's gates arrived long ago
+    } // chunks of this workgroup
+}
+
+inline int num_cus() {
+    static const int n = [] {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
+            v = 256;
+        return v;
+    }();
+    return n;
 }
 
 template <typename T, int DK, int DV, bool STAGED>
 hipError_t launch_t(const Dims &d, const GradArgs &a, hipStream_t s) {
-    dim3 grid(d.n1 - d.n0, d.BH), block(GT);
+    // staged (bf16): one workgroup per CU, each walking its share of the chunks; otherwise one per chunk
+    const int nchunks = (d.n1 - d.n0) * d.BH;
+    dim3 grid(STAGED && nchunks > num_cus() ? num_cus() : nchunks), block(GT);
     hipLaunchKernelGGL((grad_kernel<T, DK, DV, STAGED>), grid, block, 0, s, d, a);
     return hipGetLastError();
 }
