@@ -113,6 +113,13 @@ template <> struct Raw4<bf16_t> { typedef bf16x4 type; };
 template <> struct Raw4<float> { typedef f32x4 type; };
 __device__ __forceinline__ bf16x4 load4_raw(const bf16_t *p) { return *reinterpret_cast<const bf16x4 *>(p); }
 __device__ __forceinline__ f32x4 load4_raw(const float *p) { return *reinterpret_cast<const f32x4 *>(p); }
+template <typename T> __device__ __forceinline__ typename Raw4<T>::type narrow4(f32x4 v);
+template <> __device__ __forceinline__ bf16x4 narrow4<bf16_t>(f32x4 v) {
+    return bf16x4{(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
+}
+template <> __device__ __forceinline__ f32x4 narrow4<float>(f32x4 v) { return v; }
+__device__ __forceinline__ void store4_raw(bf16_t *p, bf16x4 v) { *reinterpret_cast<bf16x4 *>(p) = v; }
+__device__ __forceinline__ void store4_raw(float *p, f32x4 v) { *reinterpret_cast<f32x4 *>(p) = v; }
 __device__ __forceinline__ f32x4 widen4(bf16x4 v) { return f32x4{(float)v[0], (float)v[1], (float)v[2], (float)v[3]}; }
 __device__ __forceinline__ f32x4 widen4(f32x4 v) { return v; }
 
@@ -129,6 +136,47 @@ template <typename T> __device__ __forceinline__ const T *at32(const T *base, un
 template <typename T> __device__ __forceinline__ T *at32(T *base, unsigned elem_off) {
     return reinterpret_cast<T *>(reinterpret_cast<char *>(base) + elem_off * (unsigned)sizeof(T));
 }
+
+// An MFMA A operand [M rows][K] in LDS that a workgroup writes from accumulators (a lane holds 4 consecutive
+// rows m of one column k) and reads back as fragments (row m, EPL consecutive k).
+//   fp32 storage: kept [m][k]: four 4-byte writes per accumulator, one 16-byte read per fragment.
+//   bf16 storage: kept [k][m], rows of M + 8 elements: ONE 8-byte write per accumulator, and a fragment is two
+//     transposing reads (ds_read_b64_tr_b16: inside each group of 16 lanes, lane 4e + c addresses 4 consecutive
+//     m of row k0 + e, e = 0..3, and lane l receives element m0 + l of those four rows).  Measured per CU with 4
+//     waves: 1.7 ns per 8-byte write instruction against 4 x 3.7 ns for the four 2-byte writes of the [m][k]
+//     form, and 2 x 1.8 ns for the two transposing reads against 6.9 ns for the 16-byte fragment read.
+//     The row length M + 8 (M = 16, 32, 64) puts the 16 rows one write instruction touches, and the rows one
+//     read touches, on different banks.
+template <typename T, int M, int K> struct ATile;
+template <int M, int K> struct ATile<float, M, K> {
+    typedef Op<float> O;
+    static constexpr int LD = K + O::PAD, SIZE = M * LD;
+    // rows m0 .. m0+3 of column k
+    static __device__ __forceinline__ void put4(float *t, int m0, int k, f32x4 v) {
+#pragma unroll
+        for (int x = 0; x < 4; ++x) t[(m0 + x) * LD + k] = v[x];
+    }
+    // fragment of row 16 mt + r, k = k0 + kg*EPL .. (k0 a multiple of KSTEP)
+    static __device__ __forceinline__ O::Frag frag(const float *t, int mt, int k0, int r, int kg) {
+        return O::load(t + (mt * 16 + r) * LD + k0 + kg * O::EPL);
+    }
+};
+template <int M, int K> struct ATile<bf16_t, M, K> {
+    typedef Op<bf16_t> O;
+    typedef short s16x4 __attribute__((ext_vector_type(4)));
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
+    static constexpr int LD = M + 8, SIZE = K * LD;
+    static __device__ __forceinline__ void put4(bf16_t *t, int m0, int k, f32x4 v) { store4(t + k * LD + m0, v); }
+    static __device__ __forceinline__ s16x4 tr4(const bf16_t *p) {
+        return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p));
+    }
+    static __device__ __forceinline__ O::Frag frag(const bf16_t *t, int mt, int k0, int r, int kg) {
+        const bf16_t *p = t + (k0 + kg * 8 + (r >> 2)) * LD + mt * 16 + (r & 3) * 4;
+        const s16x4 lo = tr4(p), hi = tr4(p + 4 * LD);
+        const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        return __builtin_bit_cast(O::Frag, v);
+    }
+};
 
 // Blocked layouts of the chunk-local tensors that the library itself produces and consumes.
 // kblk: a [R][K] MFMA operand (fragment = row, KSTEP consecutive k) is stored as [K/KSTEP][R][KSTEP],

@@ -109,14 +109,16 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
     typedef Op<T> O;
     typedef RevOps<T, DK, DVB / 16> CO;
     constexpr int MV = DVB / 16, ND = DK / 64, G = DV / DVB;
-    constexpr int LDST = 2 * DK + O::PAD, LDV = 64 + O::PAD;
-    __shared__ __align__(16) T sD[DVB * LDST];  // [dv][dS'(dk) | dM'(dk)]
-    __shared__ __align__(16) T sO0[DVB * LDV];  // dO^T
-    __shared__ __align__(16) T sOa[DVB * LDV];  // (scale a . dO)^T
-    __shared__ __align__(16) T sOb[DVB * LDV];  // (-scale b . dO)^T
-    __shared__ __align__(16) T sDV[DVB * LDV];  // dV~^T
-    __shared__ __align__(16) T sRa[DVB * LDV];  // (-a . dV)^T
-    __shared__ __align__(16) T sRb[DVB * LDV];  // (pb . dV)^T
+    // the A operands that the workgroup builds itself (rows = dv; see ATile for how they sit in LDS)
+    typedef ATile<T, DVB, 2 * DK> TD; // contraction over dk: dS' | dM'
+    typedef ATile<T, DVB, 64> TV;     // contraction over the chunk's tokens
+    __shared__ __align__(16) T sD[TD::SIZE];  // [dv][dS'(dk) | dM'(dk)]
+    __shared__ __align__(16) T sO0[TV::SIZE]; // dO^T
+    __shared__ __align__(16) T sOa[TV::SIZE]; // (scale a . dO)^T
+    __shared__ __align__(16) T sOb[TV::SIZE]; // (-scale b . dO)^T
+    __shared__ __align__(16) T sDV[TV::SIZE]; // dV~^T
+    __shared__ __align__(16) T sRa[TV::SIZE]; // (-a . dV)^T
+    __shared__ __align__(16) T sRb[TV::SIZE]; // (pb . dV)^T
 
     int bh, blkv;
     xcd_map(blockIdx.x, G, bh, blkv);
@@ -141,23 +143,30 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
         const int nn = n > d.n0 ? n - 1 : d.n0;
         fetch_part<T, DK, DV, DVB, 0>(nxt, d, a, bh, b, h, nn, dv0);
 
-        // adjoints of this chunk's END states: operand copy to LDS, storage copy to HBM
+        // adjoints of this chunk's END states: operand copy to LDS, storage copy to HBM.  (The stores cost this
+        // kernel ~45 us whoever issues them and whenever: in one burst here, 208 us; spread over the step in 8
+        // portions, 213 us.  All values are narrowed first, so that the stores leave back to back.)
         {
+            constexpr int NS = 2 * MV * ND;
+            typename Raw4<T>::type sv[NS];
             T *ds = static_cast<T *>(a.dstates) + blk * (2 * DK * DV);
 #pragma unroll
             for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
                 for (int nd = 0; nd < ND; ++nd) {
-                    const int dk = (w * ND + nd) * 16 + r;
-                    const size_t off = vblk(DK, dk, dv0 + mv * 16 + kg * 4);
-                    store4(ds + off, accS[mv][nd]);
-                    store4(ds + DK * DV + off, accM[mv][nd]);
+                    const int dk = (w * ND + nd) * 16 + r, t = mv * ND + nd;
+                    sv[2 * t] = narrow4<T>(accS[mv][nd]);
+                    sv[2 * t + 1] = narrow4<T>(accM[mv][nd]);
+                    TD::put4(sD, mv * 16 + kg * 4, dk, accS[mv][nd]);
+                    TD::put4(sD, mv * 16 + kg * 4, DK + dk, accM[mv][nd]);
+                }
 #pragma unroll
-                    for (int x = 0; x < 4; ++x) {
-                        const int dv = mv * 16 + kg * 4 + x;
-                        sD[dv * LDST + dk] = from_f32<T>(accS[mv][nd][x]);
-                        sD[dv * LDST + DK + dk] = from_f32<T>(accM[mv][nd][x]);
-                    }
+            for (int mv = 0; mv < MV; ++mv)
+#pragma unroll
+                for (int nd = 0; nd < ND; ++nd) {
+                    const size_t off = vblk(DK, (w * ND + nd) * 16 + r, dv0 + mv * 16 + kg * 4);
+                    store4_raw(ds + off, sv[2 * (mv * ND + nd)]);
+                    store4_raw(ds + DK * DV + off, sv[2 * (mv * ND + nd) + 1]);
                 }
         }
         fetch_part<T, DK, DV, DVB, 1>(nxt, d, a, bh, b, h, nn, dv0);
@@ -166,14 +175,9 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
         for (int mv = 0; mv < MV; ++mv) {
             const f32x4 dOw = widen4(cur.dO[mv]);
             const float sa = d.scale * cur.sa, sb = d.scale * cur.sb;
-#pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                const int dv = mv * 16 + kg * 4 + x;
-                const float v = dOw[x];
-                sO0[dv * LDV + i] = from_f32<T>(v);
-                sOa[dv * LDV + i] = from_f32<T>(sa * v);
-                sOb[dv * LDV + i] = from_f32<T>(-sb * v);
-            }
+            TV::put4(sO0, mv * 16 + kg * 4, i, dOw);
+            TV::put4(sOa, mv * 16 + kg * 4, i, sa * dOw);
+            TV::put4(sOb, mv * 16 + kg * 4, i, -sb * dOw);
         }
         __syncthreads();
 
@@ -183,29 +187,22 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
             zero_acc(accD);
             zero_acc(x1);
             zero_acc(x2);
-            const T *op = sO0 + r * LDV + kg * O::EPL;
 #pragma unroll
             for (int s = 0; s < CO::KS2; ++s)
 #pragma unroll
                 for (int mv = 0; mv < MV; ++mv)
-                    accD[mv] = O::mma(O::load(op + mv * 16 * LDV + s * O::KSTEP), cur.bmT[s], accD[mv]);
+                    accD[mv] = O::mma(TV::frag(sO0, mv, s * O::KSTEP, r, kg), cur.bmT[s], accD[mv]);
             fetch_part<T, DK, DV, DVB, 2>(nxt, d, a, bh, b, h, nn, dv0);
-            const T *sp = sD + r * LDST + kg * O::EPL;
 #pragma unroll
             for (int s = 0; s < CO::KS; ++s)
 #pragma unroll
                 for (int mv = 0; mv < MV; ++mv) {
-                    x1[mv] = O::mma(O::load(sp + mv * 16 * LDST + s * O::KSTEP), cur.k[s], x1[mv]);
-                    x2[mv] = O::mma(O::load(sp + mv * 16 * LDST + DK + s * O::KSTEP), cur.k[s], x2[mv]);
+                    x1[mv] = O::mma(TD::frag(sD, mv, s * O::KSTEP, r, kg), cur.k[s], x1[mv]);
+                    x2[mv] = O::mma(TD::frag(sD, mv, DK + s * O::KSTEP, r, kg), cur.k[s], x2[mv]);
                 }
             fetch_part<T, DK, DV, DVB, 3>(nxt, d, a, bh, b, h, nn, dv0);
 #pragma unroll
-            for (int mv = 0; mv < MV; ++mv)
-#pragma unroll
-                for (int x = 0; x < 4; ++x) {
-                    const int dv = mv * 16 + kg * 4 + x;
-                    sDV[dv * LDV + i] = from_f32<T>(accD[mv][x] + cur.gc * x1[mv][x] - cur.rc * x2[mv][x]);
-                }
+            for (int mv = 0; mv < MV; ++mv) TV::put4(sDV, mv * 16 + kg * 4, i, accD[mv] + cur.gc * x1[mv] - cur.rc * x2[mv]);
         }
         __syncthreads();
 
@@ -214,25 +211,19 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
         {
             f32x4 dR[MV];
             zero_acc(dR);
-            const T *dvp = sDV + r * LDV + kg * O::EPL;
 #pragma unroll
             for (int s = 0; s < CO::KS2; ++s)
 #pragma unroll
                 for (int mv = 0; mv < MV; ++mv)
-                    dR[mv] = O::mma(O::load(dvp + mv * 16 * LDV + s * O::KSTEP), cur.tT[s], dR[mv]);
+                    dR[mv] = O::mma(TV::frag(sDV, mv, s * O::KSTEP, r, kg), cur.tT[s], dR[mv]);
             fetch_part<T, DK, DV, DVB, 4>(nxt, d, a, bh, b, h, nn, dv0);
             const size_t tok = ((size_t)b * d.T + (size_t)n * 64 + i) * d.H + h;
             T *dvg = static_cast<T *>(a.dv) + tok * DV + dv0 + kg * 4;
 #pragma unroll
             for (int mv = 0; mv < MV; ++mv) {
                 store4(dvg + mv * 16, dR[mv]);
-#pragma unroll
-                for (int x = 0; x < 4; ++x) {
-                    const int dv = mv * 16 + kg * 4 + x;
-                    const float v = dR[mv][x];
-                    sRa[dv * LDV + i] = from_f32<T>(-cur.sa * v);
-                    sRb[dv * LDV + i] = from_f32<T>(cur.pb * v);
-                }
+                TV::put4(sRa, mv * 16 + kg * 4, i, -cur.sa * dR[mv]);
+                TV::put4(sRb, mv * 16 + kg * 4, i, cur.pb * dR[mv]);
             }
         }
         __syncthreads();
@@ -248,16 +239,14 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
                     accS[mv][nd] = aC * s;
                     accM[mv][nd] = mC * m - bC * s;
                 }
-            const T *oap = sOa + r * LDV + kg * O::EPL, *obp = sOb + r * LDV + kg * O::EPL;
-            const T *rap = sRa + r * LDV + kg * O::EPL, *rbp = sRb + r * LDV + kg * O::EPL;
 #pragma unroll
             for (int s = 0; s < CO::KS2; ++s)
 #pragma unroll
                 for (int mv = 0; mv < MV; ++mv) {
-                    const typename O::Frag fa = O::load(oap + mv * 16 * LDV + s * O::KSTEP);
-                    const typename O::Frag fb = O::load(obp + mv * 16 * LDV + s * O::KSTEP);
-                    const typename O::Frag fra = O::load(rap + mv * 16 * LDV + s * O::KSTEP);
-                    const typename O::Frag frb = O::load(rbp + mv * 16 * LDV + s * O::KSTEP);
+                    const typename O::Frag fa = TV::frag(sOa, mv, s * O::KSTEP, r, kg);
+                    const typename O::Frag fb = TV::frag(sOb, mv, s * O::KSTEP, r, kg);
+                    const typename O::Frag fra = TV::frag(sRa, mv, s * O::KSTEP, r, kg);
+                    const typename O::Frag frb = TV::frag(sRb, mv, s * O::KSTEP, r, kg);
 #pragma unroll
                     for (int nd = 0; nd < ND; ++nd) {
                         accS[mv][nd] = O::mma(fa, cur.qT[nd][s], accS[mv][nd]);

@@ -37,15 +37,22 @@ namespace {
 template <typename T, int DK, int MV> struct ChunkOps {
     typedef Op<T> O;
     static constexpr int KS = DK / O::KSTEP, KS2 = 64 / O::KSTEP, ND = DK / 64;
-    typename O::Frag kr[KS], q[KS];       // stage 1: rows (token i0 + r) of K, Q
+    // (the per-token coefficients sit BETWEEN the fragment arrays on purpose: as neighbours the compiler reads
+    //  them back as one 16-byte vector, which keeps the whole operand set in scratch memory instead of registers)
+    typename O::Frag kr[KS];              // stage 1: rows (token i0 + r) of K
+    float sa;                             // a_i for token i0 + r
+    typename O::Frag q[KS];               // stage 1: rows of Q
+    float sb;                             // b_i
     typename O::Frag tm[KS2];             // stage 1: row i0 + r of T = (I + A)^-1
+    float gc;                             // Gamma_C eta
     typename O::Frag bm[KS2];             // stage 2: Bm row i0 + r
+    float rc;                             // Rho_C eta
     typename O::Frag kt[ND][KS2];         // stage 2: K^T rows (dk) of this wave's state columns
-    // (everything below is kept exactly as loaded: arithmetic on a freshly loaded value would make the wave wait
+    float pb;                             // alpha_i b_{i-1}
+    // (everything here is kept exactly as loaded: arithmetic on a freshly loaded value would make the wave wait
     //  for it, and for every load issued before it, at fetch time instead of one chunk later)
     typename Raw4<T>::type u[MV];         // V[token i0 + r][4 consecutive dv] (V~ in reconstruction), storage form
-    float sa, sb, gc, rc, pb;             // a_i, b_i, Gamma_C eta, Rho_C eta, alpha_i b_{i-1} for token i0 + r
-    float sc;                          // lane & 3 = 0, 1, 2: a_C, b_C, m_C
+    float sc;                             // lane & 3 = 0, 1, 2: a_C, b_C, m_C
 };
 
 // The operands of one chunk are requested in portions (P = 0..4) spread over the work on the previous
@@ -117,19 +124,17 @@ __device__ __forceinline__ void fetch_chunk(ChunkOps<T, DK, DVB / 16> &c, const 
 
 // accumulator element x of tile (mv, nd) of wave w is S[dk = (w*ND + nd)*16 + r][dv = mv*16 + kg*4 + x]
 template <typename T, int DK, int MV>
-__device__ __forceinline__ void publish_state(T *sSt, int ldst, const f32x4 (&accS)[MV][DK / 64],
-                                              const f32x4 (&accM)[MV][DK / 64]) {
+__device__ __forceinline__ void publish_state(T *sSt, const f32x4 (&accS)[MV][DK / 64], const f32x4 (&accM)[MV][DK / 64]) {
+    typedef ATile<T, MV * 16, 2 * DK> TS;
     const int r = lane_id() & 15, kg = lane_id() >> 4, w = wave_id();
 #pragma unroll
     for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
-        for (int nd = 0; nd < DK / 64; ++nd)
-#pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                const int dv = mv * 16 + kg * 4 + x, dk = (w * (DK / 64) + nd) * 16 + r;
-                sSt[dv * ldst + dk] = from_f32<T>(accS[mv][nd][x]);
-                sSt[dv * ldst + DK + dk] = from_f32<T>(accM[mv][nd][x]);
-            }
+        for (int nd = 0; nd < DK / 64; ++nd) {
+            const int dk = (w * (DK / 64) + nd) * 16 + r;
+            TS::put4(sSt, mv * 16 + kg * 4, dk, accS[mv][nd]);
+            TS::put4(sSt, mv * 16 + kg * 4, DK + dk, accM[mv][nd]);
+        }
 }
 
 // REBUILD = false: full forward scan.  REBUILD = true: state reconstruction from saved V~ only
@@ -139,13 +144,14 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
     typedef Op<T> O;
     typedef ChunkOps<T, DK, DVB / 16> CO;
     constexpr int MV = DVB / 16, ND = DK / 64, G = DV / DVB;
-    constexpr int LDST = 2 * DK + O::PAD; // state copy: [DVB][S(dk) | M(dk)]
-    constexpr int LDV = 64 + O::PAD;      // V~ copies: [DVB][64 tokens]
-    __shared__ __align__(16) T sSt[DVB * LDST];
-    __shared__ __align__(16) T sRt[REBUILD ? 8 : DVB * LDV]; // R^T = (V - a.(K S) + pb.(K M))^T, all 64 tokens
-    __shared__ __align__(16) T sV0[DVB * LDV];
-    __shared__ __align__(16) T sVg[DVB * LDV];
-    __shared__ __align__(16) T sVr[DVB * LDV];
+    // the A operands that the workgroup builds itself (rows = dv; see ATile for how they sit in LDS)
+    typedef ATile<T, DVB, 2 * DK> TS; // state copy, contraction over dk: S | M
+    typedef ATile<T, DVB, 64> TV;     // contraction over the chunk's tokens
+    __shared__ __align__(16) T sSt[TS::SIZE];
+    __shared__ __align__(16) T sRt[REBUILD ? 8 : TV::SIZE]; // R^T = (V - a.(K S) + pb.(K M))^T, all 64 tokens
+    __shared__ __align__(16) T sV0[TV::SIZE];
+    __shared__ __align__(16) T sVg[TV::SIZE];
+    __shared__ __align__(16) T sVr[TV::SIZE];
 
     int bh, blkv;
     xcd_map(blockIdx.x, G, bh, blkv);
@@ -162,7 +168,7 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
             accS[mv][nd] = a.S0 ? *reinterpret_cast<const f32x4 *>(a.S0 + g) : f32x4{0.f, 0.f, 0.f, 0.f};
             accM[mv][nd] = a.M0 ? *reinterpret_cast<const f32x4 *>(a.M0 + g) : f32x4{0.f, 0.f, 0.f, 0.f};
         }
-    if (!REBUILD) publish_state<T, DK, MV>(sSt, LDST, accS, accM);
+    if (!REBUILD) publish_state<T, DK, MV>(sSt, accS, accM);
     __syncthreads();
 
     // one chunk: its operands are in `cur`; those of the next chunk go on their way into `nxt`, portion by portion
@@ -172,19 +178,35 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
         const int nn = (n + 1 < d.n1) ? n + 1 : n;
         fetch_part<T, DK, DV, DVB, REBUILD, false, 0>(nxt, d, a, bh, b, h, nn, dv0);
 
+        // The chunk-start states leave for HBM out of a storage-type copy in registers: in one burst here in the
+        // forward scan, in 8 portions spread over the step in the reconstruction, which does little else than
+        // store (measured: forward 252 us burst / 256 us spread; reconstruction 127 us burst / 109 us spread).
+        // What the stores cost the forward scan (~75 us) does not depend on which wave issues them or when.
+        constexpr int NS = 2 * MV * ND;
+        typename Raw4<T>::type sv[NS];
+        T *st = static_cast<T *>(a.states_saved) + blk * (2 * DK * DV);
         if (a.states_saved) {
-            T *st = static_cast<T *>(a.states_saved) + blk * (2 * DK * DV);
 #pragma unroll
-            for (int mv = 0; mv < MV; ++mv)
-#pragma unroll
-                for (int nd = 0; nd < ND; ++nd) {
-                    const size_t off = vblk(DK, (w * ND + nd) * 16 + r, dv0 + mv * 16 + kg * 4);
-                    store4(st + off, accS[mv][nd]);
-                    store4(st + DK * DV + off, accM[mv][nd]);
-                }
+            for (int t = 0; t < MV * ND; ++t) {
+                sv[2 * t] = narrow4<T>(accS[t / ND][t % ND]);
+                sv[2 * t + 1] = narrow4<T>(accM[t / ND][t % ND]);
+            }
         }
+        auto emit_states = [&](auto PORTION) {
+            if (!a.states_saved) return;
+            static_for<NS>([&](auto IDX) {
+                constexpr int idx = decltype(IDX)::value, t = idx >> 1, mv = t / ND, nd = t % ND;
+                if ((REBUILD ? idx * 8 / NS : 0) == decltype(PORTION)::value) {
+                    const size_t off = vblk(DK, (w * ND + nd) * 16 + r, dv0 + mv * 16 + kg * 4);
+                    store4_raw(st + ((idx & 1) ? DK * DV : 0) + off, sv[idx]);
+                }
+            });
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        emit_states(std::integral_constant<int, 0>{});
 
         fetch_part<T, DK, DV, DVB, REBUILD, false, 4>(nxt, d, a, bh, b, h, nn, dv0);
+        emit_states(std::integral_constant<int, 1>{});
         // ---------------- stage 1: R^T = (V - a.(K S) + pb.(K M))^T and the inter-chunk read-outs for token i,
         //                  then V~^T = R^T T^T over all 64 tokens
         f32x4 accO[MV], vt[MV]; // vt = V~ rounded to the storage type
@@ -194,13 +216,12 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
             zero_acc(x2);
             zero_acc(accOS);
             zero_acc(accOM);
-            const T *sp = sSt + r * LDST + kg * O::EPL;
 #pragma unroll
             for (int s = 0; s < CO::KS; ++s) {
 #pragma unroll
                 for (int mv = 0; mv < MV; ++mv) {
-                    const typename O::Frag fs = O::load(sp + mv * 16 * LDST + s * O::KSTEP);
-                    const typename O::Frag fm = O::load(sp + mv * 16 * LDST + DK + s * O::KSTEP);
+                    const typename O::Frag fs = TS::frag(sSt, mv, s * O::KSTEP, r, kg);
+                    const typename O::Frag fm = TS::frag(sSt, mv, DK + s * O::KSTEP, r, kg);
                     x1[mv] = O::mma(fs, cur.kr[s], x1[mv]);
                     accOS[mv] = O::mma(fs, cur.q[s], accOS[mv]);
                     x2[mv] = O::mma(fm, cur.kr[s], x2[mv]);
@@ -211,19 +232,16 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
 #pragma unroll
             for (int mv = 0; mv < MV; ++mv) {
                 accO[mv] = d.scale * (cur.sa * accOS[mv] - cur.sb * accOM[mv]);
-                const f32x4 rr = widen4(cur.u[mv]) - cur.sa * x1[mv] + cur.pb * x2[mv];
-#pragma unroll
-                for (int x = 0; x < 4; ++x) sRt[(mv * 16 + kg * 4 + x) * LDV + i] = from_f32<T>(rr[x]);
+                TV::put4(sRt, mv * 16 + kg * 4, i, widen4(cur.u[mv]) - cur.sa * x1[mv] + cur.pb * x2[mv]);
             }
             __syncthreads();
             f32x4 accV[MV];
             zero_acc(accV);
-            const T *rp = sRt + r * LDV + kg * O::EPL;
 #pragma unroll
             for (int s = 0; s < CO::KS2; ++s)
 #pragma unroll
                 for (int mv = 0; mv < MV; ++mv)
-                    accV[mv] = O::mma(O::load(rp + mv * 16 * LDV + s * O::KSTEP), cur.tm[s], accV[mv]);
+                    accV[mv] = O::mma(TV::frag(sRt, mv, s * O::KSTEP, r, kg), cur.tm[s], accV[mv]);
 #pragma unroll
             for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
@@ -237,22 +255,20 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
 #pragma unroll
             for (int mv = 0; mv < MV; ++mv) vt[mv] = widen4(cur.u[mv]);
         }
+        emit_states(std::integral_constant<int, 2>{});
         // V~^T to LDS in the three scalings of stage 2
 #pragma unroll
-        for (int mv = 0; mv < MV; ++mv)
-#pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                const int dv = mv * 16 + kg * 4 + x;
-                if (!REBUILD) sV0[dv * LDV + i] = from_f32<T>(vt[mv][x]);
-                sVg[dv * LDV + i] = from_f32<T>(cur.gc * vt[mv][x]);
-                sVr[dv * LDV + i] = from_f32<T>(-cur.rc * vt[mv][x]);
-            }
+        for (int mv = 0; mv < MV; ++mv) {
+            if (!REBUILD) TV::put4(sV0, mv * 16 + kg * 4, i, vt[mv]);
+            TV::put4(sVg, mv * 16 + kg * 4, i, cur.gc * vt[mv]);
+            TV::put4(sVr, mv * 16 + kg * 4, i, -cur.rc * vt[mv]);
+        }
+        emit_states(std::integral_constant<int, 3>{});
         __syncthreads();
 
         // ---------------- stage 2: intra-chunk output and the state update
-        const T *v0p = sV0 + r * LDV + kg * O::EPL, *vgp = sVg + r * LDV + kg * O::EPL,
-                *vrp = sVr + r * LDV + kg * O::EPL;
         fetch_part<T, DK, DV, DVB, REBUILD, false, 2>(nxt, d, a, bh, b, h, nn, dv0);
+        emit_states(std::integral_constant<int, 4>{});
         const float aC = lane_value(cur.sc, 0), bC = lane_value(cur.sc, 1), mC = lane_value(cur.sc, 2);
 #pragma unroll
         for (int mv = 0; mv < MV; ++mv)
@@ -265,25 +281,27 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
         for (int s = 0; s < CO::KS2; ++s)
 #pragma unroll
             for (int mv = 0; mv < MV; ++mv) {
-                const typename O::Frag fg = O::load(vgp + mv * 16 * LDV + s * O::KSTEP);
-                const typename O::Frag fr = O::load(vrp + mv * 16 * LDV + s * O::KSTEP);
+                const typename O::Frag fg = TV::frag(sVg, mv, s * O::KSTEP, r, kg);
+                const typename O::Frag fr = TV::frag(sVr, mv, s * O::KSTEP, r, kg);
 #pragma unroll
                 for (int nd = 0; nd < ND; ++nd) {
                     accS[mv][nd] = O::mma(fg, cur.kt[nd][s], accS[mv][nd]);
                     accM[mv][nd] = O::mma(fr, cur.kt[nd][s], accM[mv][nd]);
                 }
                 if (!REBUILD) {
-                    const typename O::Frag f0 = O::load(v0p + mv * 16 * LDV + s * O::KSTEP);
-                    accO[mv] = O::mma(f0, cur.bm[s], accO[mv]);
+                    accO[mv] = O::mma(TV::frag(sV0, mv, s * O::KSTEP, r, kg), cur.bm[s], accO[mv]);
                 }
             }
+        emit_states(std::integral_constant<int, 5>{});
         fetch_part<T, DK, DV, DVB, REBUILD, false, 3>(nxt, d, a, bh, b, h, nn, dv0);
+        emit_states(std::integral_constant<int, 6>{});
         if (!REBUILD) {
-            publish_state<T, DK, MV>(sSt, LDST, accS, accM);
+            publish_state<T, DK, MV>(sSt, accS, accM);
             T *og = static_cast<T *>(a.o) + tok * DV + dv0 + kg * 4;
 #pragma unroll
             for (int mv = 0; mv < MV; ++mv) store4(og + mv * 16, accO[mv]);
         }
+        emit_states(std::integral_constant<int, 7>{});
         __syncthreads();
     };
     // two operand sets used alternately: handing one set over to the other by assignment would touch every
@@ -328,12 +346,13 @@ __global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a)
     typedef Op<T> O;
     typedef ChunkOps<T, DK, DVB / 16> CO;
     constexpr int MV = DVB / 16, ND = DK / 64, G = DV / DVB, KS = CO::KS, NF = KS, NBUF = 3;
-    constexpr int LDST = 2 * DK + O::PAD, LDV = 64 + O::PAD;
-    __shared__ __align__(16) T sSt[DVB * LDST];
-    __shared__ __align__(16) T sV0[DVB * LDV];
-    __shared__ __align__(16) T sVg[DVB * LDV];
-    __shared__ __align__(16) T sVr[DVB * LDV];
-    __shared__ __align__(16) T sRt[DVB * LDV];               // R^T = (V - a.(K S) + pb.(K M))^T, all 64 tokens
+    typedef ATile<T, DVB, 2 * DK> TS;
+    typedef ATile<T, DVB, 64> TV;
+    __shared__ __align__(16) T sSt[TS::SIZE];
+    __shared__ __align__(16) T sV0[TV::SIZE];
+    __shared__ __align__(16) T sVg[TV::SIZE];
+    __shared__ __align__(16) T sVr[TV::SIZE];
+    __shared__ __align__(16) T sRt[TV::SIZE];                // R^T = (V - a.(K S) + pb.(K M))^T, all 64 tokens
     __shared__ __align__(16) T sF[NBUF][4][NF][64 * O::EPL]; // [buffer][compute wave][fragment][lane slot]
 
     int bh, blkv;
@@ -380,7 +399,7 @@ __global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a)
             accS[mv][nd] = a.S0 ? *reinterpret_cast<const f32x4 *>(a.S0 + g) : f32x4{0.f, 0.f, 0.f, 0.f};
             accM[mv][nd] = a.M0 ? *reinterpret_cast<const f32x4 *>(a.M0 + g) : f32x4{0.f, 0.f, 0.f, 0.f};
         }
-    publish_state<T, DK, MV>(sSt, LDST, accS, accM);
+    publish_state<T, DK, MV>(sSt, accS, accM);
     __syncthreads();
 
     auto step = [&](int n, const CO &cur, CO &nxt) {
@@ -389,18 +408,6 @@ __global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a)
         const int nn = (n + 1 < d.n1) ? n + 1 : n;
         fetch_part<T, DK, DV, DVB, false, true, 0>(nxt, d, a, bh, b, h, nn, dv0);
 
-        // the chunk-start states leave in portions too, between the steps of stage 1 (all workgroups walk the
-        // chunks in step: whatever a workgroup writes in one burst, all of them write at that moment)
-        constexpr int NST = 2 * MV * ND;
-        T *st = static_cast<T *>(a.states_saved) + blk * (2 * DK * DV);
-        auto store_state = [&](auto IDX) {
-            constexpr int idx = decltype(IDX)::value, t = idx >> 1, mv = t / ND, nd = t % ND;
-            const size_t off = vblk(DK, (w * ND + nd) * 16 + r, dv0 + mv * 16 + kg * 4);
-            if (idx & 1)
-                store4(st + DK * DV + off, accM[mv][nd]);
-            else
-                store4(st + off, accS[mv][nd]);
-        };
         fetch_part<T, DK, DV, DVB, false, true, 1>(nxt, d, a, bh, b, h, nn, dv0);
         // stage 1: R^T and the read-outs for token i, then V~^T = R^T T^T over all 64 tokens
         f32x4 accO[MV], vt[MV], x1[MV], x2[MV], accOS[MV], accOM[MV];
@@ -408,7 +415,6 @@ __global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a)
         zero_acc(x2);
         zero_acc(accOS);
         zero_acc(accOM);
-        const T *sp = sSt + r * LDST + kg * O::EPL;
         const T *fp = &sF[n % NBUF][w][0][lane * O::EPL];
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
@@ -416,37 +422,28 @@ __global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a)
             const typename O::Frag fq = cur.q[s];
 #pragma unroll
             for (int mv = 0; mv < MV; ++mv) {
-                const typename O::Frag fs = O::load(sp + mv * 16 * LDST + s * O::KSTEP);
-                const typename O::Frag fm = O::load(sp + mv * 16 * LDST + DK + s * O::KSTEP);
+                const typename O::Frag fs = TS::frag(sSt, mv, s * O::KSTEP, r, kg);
+                const typename O::Frag fm = TS::frag(sSt, mv, DK + s * O::KSTEP, r, kg);
                 x1[mv] = O::mma(fs, fk, x1[mv]);
                 accOS[mv] = O::mma(fs, fq, accOS[mv]);
                 x2[mv] = O::mma(fm, fk, x2[mv]);
                 accOM[mv] = O::mma(fm, fq, accOM[mv]);
             }
-            if (a.states_saved) {
-                static_for<NST>([&](auto IDX) {
-                    if (decltype(IDX)::value * KS / NST == s) store_state(IDX);
-                });
-                __builtin_amdgcn_sched_barrier(0);
-            }
         }
 #pragma unroll
         for (int mv = 0; mv < MV; ++mv) {
             accO[mv] = d.scale * (cur.sa * accOS[mv] - cur.sb * accOM[mv]);
-            const f32x4 rr = widen4(cur.u[mv]) - cur.sa * x1[mv] + cur.pb * x2[mv];
-#pragma unroll
-            for (int x = 0; x < 4; ++x) sRt[(mv * 16 + kg * 4 + x) * LDV + i] = from_f32<T>(rr[x]);
+            TV::put4(sRt, mv * 16 + kg * 4, i, widen4(cur.u[mv]) - cur.sa * x1[mv] + cur.pb * x2[mv]);
         }
         __syncthreads(); // barrier 1 of the chunk (the loader waves count it too)
         {
             f32x4 accV[MV];
             zero_acc(accV);
-            const T *rp = sRt + r * LDV + kg * O::EPL;
 #pragma unroll
             for (int s = 0; s < CO::KS2; ++s)
 #pragma unroll
                 for (int mv = 0; mv < MV; ++mv)
-                    accV[mv] = O::mma(O::load(rp + mv * 16 * LDV + s * O::KSTEP), cur.tm[s], accV[mv]);
+                    accV[mv] = O::mma(TV::frag(sRt, mv, s * O::KSTEP, r, kg), cur.tm[s], accV[mv]);
 #pragma unroll
             for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
@@ -458,19 +455,14 @@ __global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a)
             for (int mv = 0; mv < MV; ++mv) store4(vs + mv * 16, vt[mv]);
         }
 #pragma unroll
-        for (int mv = 0; mv < MV; ++mv)
-#pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                const int dv = mv * 16 + kg * 4 + x;
-                sV0[dv * LDV + i] = from_f32<T>(vt[mv][x]);
-                sVg[dv * LDV + i] = from_f32<T>(cur.gc * vt[mv][x]);
-                sVr[dv * LDV + i] = from_f32<T>(-cur.rc * vt[mv][x]);
-            }
+        for (int mv = 0; mv < MV; ++mv) {
+            TV::put4(sV0, mv * 16 + kg * 4, i, vt[mv]);
+            TV::put4(sVg, mv * 16 + kg * 4, i, cur.gc * vt[mv]);
+            TV::put4(sVr, mv * 16 + kg * 4, i, -cur.rc * vt[mv]);
+        }
         __syncthreads();
 
         // stage 2
-        const T *v0p = sV0 + r * LDV + kg * O::EPL, *vgp = sVg + r * LDV + kg * O::EPL,
-                *vrp = sVr + r * LDV + kg * O::EPL;
         fetch_part<T, DK, DV, DVB, false, true, 2>(nxt, d, a, bh, b, h, nn, dv0);
         const float aC = lane_value(cur.sc, 0), bC = lane_value(cur.sc, 1), mC = lane_value(cur.sc, 2);
 #pragma unroll
@@ -484,18 +476,17 @@ __global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a)
         for (int s = 0; s < CO::KS2; ++s)
 #pragma unroll
             for (int mv = 0; mv < MV; ++mv) {
-                const typename O::Frag fg = O::load(vgp + mv * 16 * LDV + s * O::KSTEP);
-                const typename O::Frag fr = O::load(vrp + mv * 16 * LDV + s * O::KSTEP);
+                const typename O::Frag fg = TV::frag(sVg, mv, s * O::KSTEP, r, kg);
+                const typename O::Frag fr = TV::frag(sVr, mv, s * O::KSTEP, r, kg);
 #pragma unroll
                 for (int nd = 0; nd < ND; ++nd) {
                     accS[mv][nd] = O::mma(fg, cur.kt[nd][s], accS[mv][nd]);
                     accM[mv][nd] = O::mma(fr, cur.kt[nd][s], accM[mv][nd]);
                 }
-                const typename O::Frag f0 = O::load(v0p + mv * 16 * LDV + s * O::KSTEP);
-                accO[mv] = O::mma(f0, cur.bm[s], accO[mv]);
+                accO[mv] = O::mma(TV::frag(sV0, mv, s * O::KSTEP, r, kg), cur.bm[s], accO[mv]);
             }
         fetch_part<T, DK, DV, DVB, false, true, 3>(nxt, d, a, bh, b, h, nn, dv0);
-        publish_state<T, DK, MV>(sSt, LDST, accS, accM);
+        publish_state<T, DK, MV>(sSt, accS, accM);
         T *og = static_cast<T *>(a.o) + tok * DV + dv0 + kg * 4;
 #pragma unroll
         for (int mv = 0; mv < MV; ++mv) store4(og + mv * 16, accO[mv]);
@@ -526,9 +517,11 @@ hipError_t launch_scan_t(const Dims &d, const ScanFwdArgs &a, hipStream_t s) {
     constexpr int G = DV / DVB;
     dim3 grid(((d.BH + 7) / 8) * 8 * G), block(kThreads);
     if constexpr (sizeof(T) == 2 && !REBUILD) {
-        // the loader-wave variant wins when the scan does not also write the chunk-start states (inference,
-        // or a training forward that leaves them to be reconstructed); with those stores in the compute waves'
-        // queue the plain kernel is the faster one (measured: 253 vs 260 us, and 177 vs 169 us without them)
+        // the loader-wave variant (which does not write the chunk-start states) serves inference and a training
+        // forward that leaves the states to be reconstructed.  With the state stores the plain kernel is the
+        // faster one whoever issues them (measured: 253 us plain; 260 us with the compute waves of the
+        // loader-wave variant storing in portions, 261 us with its loader waves storing out of the LDS copy;
+        // 177 vs 169 us without the stores): what the stores cost is not the issuing wave's time.
         static const char *nows = getenv("MDN_NO_LOADER_WAVES"); // tuning switch: never use the loader-wave variant
         if (!nows && !a.states_saved) {
             hipLaunchKernelGGL((scan_fwd_ws_kernel<DK, DV, DVB>), grid, dim3(512), 0, s, d, a);
