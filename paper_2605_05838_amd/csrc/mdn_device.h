@@ -161,20 +161,23 @@ template <int M, int K> struct ATile<float, M, K> {
         return O::load(t + (mt * 16 + r) * LD + k0 + kg * O::EPL);
     }
 };
-template <int M, int K> struct ATile<bf16_t, M, K> {
-    typedef Op<bf16_t> O;
+// fragment (row or column 16*.. + r of the operand, k = k0 + kg*8 .. +7) of a bf16 matrix kept [k][n] with row
+// length ld in LDS, n0 = first of the 16 n: two transposing reads (rows k0 + kg*8 + 0..3 and + 4..7)
+__device__ __forceinline__ bf16x8 tr_frag(const bf16_t *t, int ld, int k0, int n0, int r, int kg) {
     typedef short s16x4 __attribute__((ext_vector_type(4)));
     typedef short s16x8 __attribute__((ext_vector_type(8)));
+    const bf16_t *p = t + (k0 + kg * 8 + (r >> 2)) * ld + n0 + (r & 3) * 4;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p + 4 * ld));
+    const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+}
+template <int M, int K> struct ATile<bf16_t, M, K> {
+    typedef Op<bf16_t> O;
     static constexpr int LD = M + 8, SIZE = K * LD;
     static __device__ __forceinline__ void put4(bf16_t *t, int m0, int k, f32x4 v) { store4(t + k * LD + m0, v); }
-    static __device__ __forceinline__ s16x4 tr4(const bf16_t *p) {
-        return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p));
-    }
     static __device__ __forceinline__ O::Frag frag(const bf16_t *t, int mt, int k0, int r, int kg) {
-        const bf16_t *p = t + (k0 + kg * 8 + (r >> 2)) * LD + mt * 16 + (r & 3) * 4;
-        const s16x4 lo = tr4(p), hi = tr4(p + 4 * LD);
-        const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        return __builtin_bit_cast(O::Frag, v);
+        return tr_frag(t, LD, k0, mt * 16, r, kg);
     }
 };
 

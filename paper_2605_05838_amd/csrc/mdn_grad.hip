@@ -100,17 +100,18 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     constexpr int TG = 8 / NKW;   // token groups
     constexpr int TT = 4 / TG;    // token tiles per wave
     constexpr bool DEEP = STAGED; // all four state tiles in registers at once
+    constexpr bool WTR = sizeof(T) == 2; // 16-bit storage: transposing LDS reads instead of transposed LDS writes
     static_assert(NKW * TG == 8 && TT * TG == 4, "8 waves = dk tiles x token groups");
 
     __shared__ __align__(16) float sG[64 * LDG];     // Gamma
     __shared__ __align__(16) float sRho[64 * LDG];   // Rho
-    __shared__ float sDG1[64 * LDG];   // direct dGamma from Bm
-    __shared__ float sDG2[65 * LDG];   // direct dGamma^- (row i here belongs to Gamma row i-1)
+    __shared__ __align__(16) float sDG1[64 * LDG];   // direct dGamma from Bm
+    __shared__ __align__(16) float sDG2[65 * LDG];   // direct dGamma^- (row i here belongs to Gamma row i-1)
     __shared__ __align__(16) T sW[4 * 64 * LDW];
     T *sW1e = sW;                 // W1 . eta_j         [i][j]
     T *sW2e = sW + 64 * LDW;      // W2 . eta_j         [i][j]
-    T *sW1T = sW + 2 * 64 * LDW;  // scale W1^T         [j][i]
-    T *sW2T = sW + 3 * 64 * LDW;  // (W2 . alpha_i)^T   [j][i]
+    T *sW1T = sW + 2 * 64 * LDW;  // scale W1: [i][j] in 16-bit storage (read transposed), else its transpose [j][i]
+    T *sW2T = sW + 3 * 64 * LDW;  // W2 . alpha_i: likewise
     // after the W products the space holds the row-dot partial sums, then the accumulated adjoints of Gamma, Rho
     float *spart = reinterpret_cast<float *>(sW);
     float *sGa = reinterpret_cast<float *>(sW), *sRa = sGa + 64 * LDG;
@@ -123,7 +124,7 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     __shared__ __align__(16) T sDR[STAGED ? 64 * D : 8];
     T *sK = sW;
     static_assert(4 * LDW >= D, "k tile does not fit the W space");
-    __shared__ float s_al[64], s_et[64], s_a[64], s_b[64];
+    __shared__ __align__(16) float s_al[64], s_et[64], s_a[64], s_b[64];
     __shared__ float sRowC[3 * 64]; // reverse scan: the three per-row coefficients
     __shared__ float s_gC[64], s_rC[64];
     __shared__ float s_ga[64], s_gb[64], s_gm[64];
@@ -309,28 +310,43 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     }
     if (STAGED) __syncthreads(); // everybody is done with the k tile: the W matrices take its place
     {
+        // this lane: token i (row of the masked matrices), columns j0 .. j0+3 of tile mt; everything a row needs
+        // is 16 contiguous bytes, read and written as such
         const float al_i = s_al[i];
 #pragma unroll
         for (int mh = 0; mh < 2; ++mh) {
-            const int mt = hf * 2 + mh;
-            f32x4 w1e, w2e;
+            const int mt = hf * 2 + mh, j0 = mt * 16 + kg * 4;
+            const f32x4 gam = *reinterpret_cast<const f32x4 *>(&sG[i * LDG + j0]);
+            const f32x4 gprev = (i > 0) ? *reinterpret_cast<const f32x4 *>(&sG[(i - 1) * LDG + j0]) : f32x4{0.f, 0.f, 0.f, 0.f};
+            const f32x4 et = *reinterpret_cast<const f32x4 *>(&s_et[j0]);
+            f32x4 w1e, w2e, w1s, w2a, dg1, dg2;
 #pragma unroll
             for (int x = 0; x < 4; ++x) {
-                const int j = mt * 16 + kg * 4 + x;
-                const float gam = sG[i * LDG + j], gprev = (i > 0) ? sG[(i - 1) * LDG + j] : 0.f;
-                const float et = s_et[j];
+                const int j = j0 + x;
                 const float dBm = (j <= i) ? accB[mh][x] : 0.f;
                 const float dA = (j < i) ? -accA[mh][x] : 0.f;
-                sDG1[i * LDG + j] = dBm * (d.scale * et * accQK[mh][x]);
-                sDG2[i * LDG + j] = dA * (al_i * et * accKK[mh][x]);
-                const float w1 = dBm * gam, w2 = dA * gprev;
-                w1e[x] = w1 * et;
-                w2e[x] = w2 * et;
-                sW1T[j * LDW + i] = from_f32<T>(w1 * d.scale);
-                sW2T[j * LDW + i] = from_f32<T>(w2 * al_i);
+                dg1[x] = dBm * (d.scale * et[x] * accQK[mh][x]);
+                dg2[x] = dA * (al_i * et[x] * accKK[mh][x]);
+                const float w1 = dBm * gam[x], w2 = dA * gprev[x];
+                w1e[x] = w1 * et[x];
+                w2e[x] = w2 * et[x];
+                w1s[x] = w1 * d.scale;
+                w2a[x] = w2 * al_i;
             }
-            store4(sW1e + i * LDW + mt * 16 + kg * 4, w1e);
-            store4(sW2e + i * LDW + mt * 16 + kg * 4, w2e);
+            *reinterpret_cast<f32x4 *>(&sDG1[i * LDG + j0]) = dg1;
+            *reinterpret_cast<f32x4 *>(&sDG2[i * LDG + j0]) = dg2;
+            store4(sW1e + i * LDW + j0, w1e);
+            store4(sW2e + i * LDW + j0, w2e);
+            if (WTR) { // kept [i][j] like the others; the products that contract over i read them transposed
+                store4(sW1T + i * LDW + j0, w1s);
+                store4(sW2T + i * LDW + j0, w2a);
+            } else {
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    sW1T[(j0 + x) * LDW + i] = from_f32<T>(w1s[x]);
+                    sW2T[(j0 + x) * LDW + i] = from_f32<T>(w2a[x]);
+                }
+            }
         }
     }
     __syncthreads();
@@ -350,6 +366,13 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     }
     sched_fence(); // these loads leave now, not after the products below
     // ---------------- phase B: the token-contractions W1 K~, W2 K~, W1^T Q~, W2^T P
+    // B fragment (column j = j0 + r, contraction over i, step s) of W1^T / W2^T
+    auto wt_frag = [&](const T *m, int j0, int s) -> Frag {
+        if constexpr (WTR)
+            return tr_frag(m, LDW, s * O::KSTEP, j0, r, kg);
+        else
+            return O::load(m + (j0 + r) * LDW + s * O::KSTEP + kg * E);
+    };
     f32x4 accQ[TT], accP[TT], accK[TT]; // dQ~^T, dP^T, dK~^T: [dk tile kt][token tile t of this group]
     zero_acc(accQ);
     zero_acc(accP);
@@ -361,8 +384,8 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
             const int wo = ((tg * TT + t) * 16 + r) * LDW + s * O::KSTEP + kg * E;
             accQ[t] = O::mma(aK[s], O::load(sW1e + wo), accQ[t]);
             accP[t] = O::mma(aK[s], O::load(sW2e + wo), accP[t]);
-            accK[t] = O::mma(aQ[s], O::load(sW1T + wo), accK[t]);
-            accK[t] = O::mma(aK[s], O::load(sW2T + wo), accK[t]);
+            accK[t] = O::mma(aQ[s], wt_frag(sW1T, (tg * TT + t) * 16, s), accK[t]);
+            accK[t] = O::mma(aK[s], wt_frag(sW2T, (tg * TT + t) * 16, s), accK[t]);
         }
     __syncthreads(); // the W space is free for the partial sums
 
