@@ -107,6 +107,66 @@ def decode_bench(args, torch, binding, synth):
         "kernels": {"recurrent": {"avg_ms": round(avg, 4), "launches": cnt}}, "cpu_baseline": None}))
 
 
+def handoff_bench(args, torch, binding, synth):
+    """Prefill -> decode hand-off: mdn_chunk_fwd over T_ctx tokens (inference mode: nothing kept for a backward)
+    leaves S, M; mdn_recurrent_step then decodes from them, one token per call and in blocks of 8 tokens per call.
+    The decode cost does not depend on T_ctx (Fig. 4, left: the state has a fixed size), the prefill cost is linear."""
+    from gpu_util import to_dev
+    B, H, dk = args.handoff, 16, 128
+    rows = []
+    for T_ctx in (1024, 4096, 16384):
+        w = synth.custom(B=B, T=T_ctx, H=H, dk=dk, dv=dk, dtype="bf16", seed=11)
+        t = to_dev(w)
+        names = ("q", "k", "v", "beta", "alpha", "mu")
+        tok1 = {k: t[k][:, :1].contiguous() for k in names}   # the decode tokens: synthetic, like the prompt's
+        tok8 = {k: t[k][:, :8].contiguous() for k in names}
+        out = None
+
+        def prefill():
+            nonlocal out
+            out = binding.mdn_chunk_fwd(*(t[k] for k in names), scale=w.scale, out=out, workspace=out and out["workspace"])
+
+        def timed(fn, n):
+            for _ in range(max(args.warmup // 2, 1)):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(n):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) * 1e3 / n
+
+        ms_prefill = timed(prefill, max(args.steps // 4, 2))
+        S, M = out["S"].clone(), out["M"].clone()
+        o1 = o8 = None
+
+        def dec1():
+            nonlocal o1
+            o1 = binding.mdn_recurrent_step(*(tok1[k] for k in names), S, M, scale=w.scale, out=o1)
+
+        def dec8():
+            nonlocal o8
+            o8 = binding.mdn_recurrent_step(*(tok8[k] for k in names), S, M, scale=w.scale, out=o8)
+
+        ms1 = timed(dec1, args.steps * 4)
+        ms8 = timed(dec8, args.steps * 2)
+        rows.append({"T_ctx": T_ctx, "prefill_ms": round(ms_prefill, 4),
+                     "prefill_tokens_per_s": round(B * T_ctx / (ms_prefill * 1e-3), 1),
+                     "decode_ms_per_token": round(ms1, 4), "decode_block8_ms_per_token": round(ms8 / 8, 4)})
+        del t, out, S, M
+        torch.cuda.empty_cache()
+    nbytes = 4 * B * H * dk * dk * 4
+    gbs = nbytes / (rows[-1]["decode_ms_per_token"] * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "MDN decode latency after prefill hand-off", "value": rows[-1]["decode_ms_per_token"], "unit": "ms/token",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": rows[-1]["decode_ms_per_token"],
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"handoff_B{B}_H{H}_d{dk}", "B": B, "H": H, "dk": dk, "dv": dk},
+        "roofline": {"kernel": "recurrent", "bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS,
+                     "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 5), "traffic": None},
+        "by_context": rows, "cpu_baseline": None}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -122,6 +182,10 @@ def main():
     ap.add_argument("--decode", type=int, default=0, metavar="BATCH",
                     help="instead of the training step, time mdn_recurrent_step: one token for BATCH sequences x 16 heads "
                          "x 128x128 states (the decode regime of the recurrent form); prints its own JSON line")
+    ap.add_argument("--handoff", type=int, default=0, metavar="BATCH",
+                    help="instead of the training step: prefill BATCH sequences x 16 heads x d128 of 1024 / 4096 / 16384 "
+                         "tokens with mdn_chunk_fwd, then decode from the states it leaves (mdn_recurrent_step, one token "
+                         "and 8 tokens per call); prints its own JSON line with the decode latency per context length")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="after the timed region, also run one plain device copy of this many MiB (the known-size "
                          "kernel that the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled by)")
@@ -142,6 +206,8 @@ def main():
     torch.cuda.set_device(0)
     if args.decode:
         return decode_bench(args, torch, binding, synth)
+    if args.handoff:
+        return handoff_bench(args, torch, binding, synth)
     w = synth.config(args.config)
     do_bwd = w.backward and not args.forward_only
     t = to_dev(w)

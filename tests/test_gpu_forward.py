@@ -86,3 +86,30 @@ def test_recurrent_step_matches_oracle_and_chunk_forward(dtype):
     tol = 1e-5 if dtype == "f32" else 2e-2      # fp32 FMA recurrence; bf16 only rounds o
     assert rel_err(host(o), ref["o"]) <= tol
     assert rel_err(host(S), ref["S"]) <= 1e-5 and rel_err(host(M), ref["M"]) <= 1e-5
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_prefill_states_hand_off_to_the_recurrent_step(dtype):
+    """Prefill with the chunkwise forward, decode from the states it leaves (a block of 8 tokens in one call,
+    then a single token): outputs and states equal the oracle's over the whole sequence (Fig. 1: both forms
+    compute the same recurrence, so a sequence may switch from one to the other at a chunk boundary)."""
+    Tp, Td = 192, 9
+    w = synth.custom(B=2, T=Tp + Td, H=3, dk=128, dv=128, dtype=dtype, seed=31, with_eta=True, s0_std=0.1)
+    t = to_dev(w)
+    names = ("q", "k", "v", "beta", "alpha", "mu")
+    cut = lambda a, b: {k: t[k][:, a:b].contiguous() for k in names + ("eta",)}
+    p = cut(0, Tp)
+    f = binding.mdn_chunk_fwd(*(p[k] for k in names), eta=p["eta"], S0=t["S0"], scale=w.scale)
+    S, M = f["S"], f["M"]
+    outs = [f["o"]]
+    for a, b in ((Tp, Tp + 8), (Tp + 8, Tp + Td)):
+        c = cut(a, b)
+        outs.append(binding.mdn_recurrent_step(*(c[k] for k in names), S, M, eta=c["eta"], scale=w.scale))
+    torch.cuda.synchronize()
+    o = torch.cat(outs, 1)
+    arrays = {k: (None if v is None else v.astype(np.float64)) for k, v in w.arrays.items()}
+    ref = oracle_fwd(arrays, w.scale)
+    tol = 1e-4 if dtype == "f32" else 2e-2
+    assert rel_err(host(o)[:, Tp:], ref["o"][:, Tp:]) <= tol
+    assert rel_err(host(o), ref["o"]) <= tol
+    assert rel_err(host(S), ref["S"]) <= tol and rel_err(host(M), ref["M"]) <= tol
