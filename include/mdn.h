@@ -22,7 +22,10 @@
  *   - shape.dtype selects the storage type of q, k, v, o, dO, dq, dk, dv and of every
  *     intermediate the library stores: MDN_DTYPE_BF16 (bf16 MFMA operands, fp32 accumulation
  *     and fp32 states) or MDN_DTYPE_F32 (fp32 MFMA throughout).
- *   - All pointers must be 16-byte aligned.  dk, dv in {64, 128}; C = 64; T % C == 0.
+ *   - All pointers must be 16-byte aligned.  dk, dv in {64, 128}; C = 64; any T >= 1: when T is not a
+ *     multiple of C the last chunk is partial (Algorithm 1 pads it; here the padding tokens are exact
+ *     identity steps, k = v = q = 0, alpha = mu = 1, beta = 0, on copies inside the workspace, so outputs,
+ *     final states and gradients are those of the T tokens given).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
  *     ordered after what the stream already holds and is complete when the stream reaches the
  *     end of the call; no call synchronises.  When the serial scans would leave at least half
@@ -48,7 +51,7 @@ enum { MDN_DTYPE_BF16 = 0, MDN_DTYPE_F32 = 1 };
 enum {
     MDN_OK = 0,
     MDN_ERR_NULL = -1,      /* a required pointer is NULL */
-    MDN_ERR_SHAPE = -2,     /* unsupported B/T/H/dk/dv/C (T % C != 0, dk or dv not in {64,128}, C != 64, ...) */
+    MDN_ERR_SHAPE = -2,     /* unsupported B/T/H/dk/dv/C (dk or dv not in {64,128}, C != 64, sizes < 1, ...) */
     MDN_ERR_DTYPE = -3,     /* dtype is neither MDN_DTYPE_BF16 nor MDN_DTYPE_F32 */
     MDN_ERR_WORKSPACE = -4, /* workspace_bytes smaller than mdn_workspace_bytes() reports */
     MDN_ERR_ALIGN = -5,     /* a pointer is not 16-byte aligned */
@@ -70,8 +73,9 @@ typedef struct mdn_shape {
  * (MDN_WS_BWD) needs for this shape.  Host-only; touches no device. */
 int mdn_workspace_bytes(const mdn_shape *shape, int which, size_t *bytes_out);
 
-/* Bytes of the optional `states_saved` buffer: the states S, M at the start of every chunk,
- * [B, H, T/C, 2, dk, dv] in the storage dtype. */
+/* Bytes of the optional `states_saved` buffer: the states S, M at the start of every chunk in the storage
+ * dtype, 2 dk dv elements per (batch, head, chunk), ceil(T/C) chunks.  Only mdn_chunk_bwd reads it (the blocks
+ * of the full chunks come first, [B, H, T/C, 2, dk, dv], then one block per (batch, head) for a partial chunk). */
 int mdn_saved_states_bytes(const mdn_shape *shape, size_t *bytes_out);
 
 /* Bytes of the optional `operands_saved` buffer: the chunk-local operands of the reverse pass

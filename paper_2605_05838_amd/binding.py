@@ -161,7 +161,7 @@ def mdn_chunk_fwd(q, k, v, beta, alpha, mu, eta=None, S0=None, M0=None, scale=No
     if save_states:
         states = out.get("states")
         if states is None:
-            states = torch.empty((B, H, T // 64, 2, dk, dv), dtype=q.dtype, device=dev)
+            states = torch.empty((B, H, -(-T // 64), 2, dk, dv), dtype=q.dtype, device=dev)  # opaque to the caller
     workspace, wbytes = _workspace(shape, MDN_WS_FWD, workspace, dev)
     rc = lib.mdn_chunk_fwd(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _f32(beta, "beta"), _f32(alpha, "alpha"),
                            _f32(mu, "mu"), _f32(eta, "eta"), _f32(S0, "S0"), _f32(M0, "M0"), _ptr(o), _ptr(S),

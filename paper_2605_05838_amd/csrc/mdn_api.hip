@@ -19,9 +19,9 @@ int check_shape(const mdn_shape *s, bool chunked, Dims *d) {
     if (s->dtype != MDN_DTYPE_BF16 && s->dtype != MDN_DTYPE_F32) return MDN_ERR_DTYPE;
     if (s->B < 1 || s->T < 1 || s->H < 1) return MDN_ERR_SHAPE;
     if (!((s->dk == 64 && s->dv == 64) || (s->dk == 128 && s->dv == 128))) return MDN_ERR_SHAPE;
-    if (chunked && (s->C != 64 || s->T % 64 != 0)) return MDN_ERR_SHAPE;
+    if (chunked && s->C != 64) return MDN_ERR_SHAPE;
     if ((long long)s->B * s->H > (1 << 24) || (long long)s->B * s->T * s->H > (1LL << 31) - 1) return MDN_ERR_SHAPE;
-    d->B = s->B; d->T = s->T; d->H = s->H; d->N = s->T / 64; d->BH = s->B * s->H;
+    d->B = s->B; d->T = s->T; d->H = s->H; d->N = s->T / 64; d->BH = s->B * s->H; // N: the FULL chunks
     d->n0 = 0; d->n1 = d->N;
     d->dk = s->dk; d->dv = s->dv; d->dtype = s->dtype; d->scale = s->scale;
     return MDN_OK;
@@ -90,6 +90,74 @@ BwdWs carve_bwd(const Dims &d, void *ws) {
     w.total = c.off;
     return w;
 }
+
+// ---- a sequence length that is not a multiple of 64: the full chunks run on the caller's tensors (d.N counts
+// them, d.T stays the row stride between sequences), the partial last chunk on padded copies (see mdn_tail.hip)
+Dims tail_dims(const Dims &d) {
+    Dims t = d;
+    t.T = 64; t.N = 1; t.n0 = 0; t.n1 = 1;
+    return t;
+}
+
+size_t elem_size(const Dims &d) { return d.dtype == MDN_DTYPE_F32 ? 4 : 2; }
+size_t saved_states_part(const Dims &d) { return (size_t)d.BH * d.N * 2 * d.dk * d.dv * elem_size(d); }
+
+// padded [B,64,H,*] copies of the partial chunk's tensors, and the states handed between the two parts
+struct TailBufs {
+    void *q, *k, *v, *o, *vt, *dO, *dq, *dk, *dv;
+    float *beta, *alpha, *mu, *eta, *dbeta, *dalpha, *dmu, *deta;
+    float *S_mid, *M_mid, *dS_mid, *dM_mid;
+    size_t total;
+};
+
+TailBufs carve_tail(const Dims &d, bool backward, void *p) {
+    const size_t es = elem_size(d), rows = (size_t)d.B * 64 * d.H, st = (size_t)d.BH * d.dk * d.dv * sizeof(float);
+    Carver c(p);
+    TailBufs t = {};
+    t.q = c.take(rows * d.dk * es);
+    t.k = c.take(rows * d.dk * es);
+    t.v = c.take(rows * d.dv * es);
+    t.vt = c.take(rows * d.dv * es);
+    t.beta = static_cast<float *>(c.take(rows * 4));
+    t.alpha = static_cast<float *>(c.take(rows * 4));
+    t.mu = static_cast<float *>(c.take(rows * 4));
+    t.eta = static_cast<float *>(c.take(rows * 4));
+    t.S_mid = static_cast<float *>(c.take(st));
+    t.M_mid = static_cast<float *>(c.take(st));
+    if (!backward) {
+        t.o = c.take(rows * d.dv * es);
+    } else {
+        t.dO = c.take(rows * d.dv * es);
+        t.dq = c.take(rows * d.dk * es);
+        t.dk = c.take(rows * d.dk * es);
+        t.dv = c.take(rows * d.dv * es);
+        t.dbeta = static_cast<float *>(c.take(rows * 4));
+        t.dalpha = static_cast<float *>(c.take(rows * 4));
+        t.dmu = static_cast<float *>(c.take(rows * 4));
+        t.deta = static_cast<float *>(c.take(rows * 4));
+        t.dS_mid = static_cast<float *>(c.take(st));
+        t.dM_mid = static_cast<float *>(c.take(st));
+    }
+    t.total = c.off;
+    return t;
+}
+
+void *offset(void *p, size_t bytes) { return p ? static_cast<char *>(p) + bytes : nullptr; }
+const void *offset(const void *p, size_t bytes) { return p ? static_cast<const char *>(p) + bytes : nullptr; }
+
+struct TailList {
+    TailCopy c;
+    TailList(const Dims &d, int r) {
+        c = {};
+        c.B = d.B; c.T = d.T; c.H = d.H; c.t0 = d.N * 64; c.r = r;
+    }
+    void add(const void *full, void *padded, size_t row_bytes, float pad = 0.f) {
+        if (!full || !padded) return;
+        TailTensor &t = c.t[c.n++];
+        t.full = full; t.padded = padded; t.row_bytes = (int)row_bytes;
+        memcpy(&t.pad_word, &pad, 4); // (0.f and 1.f are also right for the 16-bit rows: only 0 is used there)
+    }
+};
 
 int launch_status(hipError_t e) { return e == hipSuccess ? MDN_OK : MDN_ERR_LAUNCH; }
 
@@ -168,6 +236,149 @@ Dims segment(const Dims &d, int i, int k) {
     return r;
 }
 
+// ---- the forward over the chunks [0, d.N) of the tensors in `c`
+struct FwdCall {
+    const void *q, *k, *v;
+    const float *beta, *alpha, *mu, *eta, *S0, *M0;
+    void *o;
+    float *S_final, *M_final;
+    void *vt_saved, *states_saved, *operands_saved;
+};
+
+int run_fwd(const Dims &d, const FwdCall &c, const FwdWs &w, hipStream_t s) {
+    int rc;
+    IntraArgs ia = {};
+    ia.q = c.q; ia.k = c.k; ia.alpha = c.alpha; ia.beta = c.beta; ia.mu = c.mu; ia.eta = c.eta;
+    ia.coef = w.coef; ia.KT = w.KT; ia.Tm = w.Tm; ia.Bm = w.Bm;
+    if (c.operands_saved) {
+        // training forward: one precompute pass writes the reverse pass's operands as well
+        const RevOps ro = carve_rev(d, c.operands_saved);
+        ia.coef = ro.coef; ia.KT = ro.KT; ia.QT = ro.QT; ia.BmT = ro.BmT; ia.TmT = ro.TmT;
+    }
+    ScanFwdArgs sa = {};
+    sa.q = c.q; sa.k = c.k; sa.v = c.v; sa.coef = ia.coef; sa.KT = ia.KT; sa.Tm = w.Tm; sa.Bm = w.Bm;
+    sa.S0 = c.S0; sa.M0 = c.M0; sa.o = c.o; sa.vt_saved = c.vt_saved; sa.states_saved = c.states_saved;
+    sa.S_final = c.S_final; sa.M_final = c.M_final;
+    const int mode = c.operands_saved ? 2 : 0;
+    const int nseg = segments(d);
+    if (nseg == 1) {
+        rc = timed(MDN_KERNEL_INTRA_FWD, s, [&] { return launch_intra(d, mode, ia, s); });
+        if (rc) return rc;
+        return timed(MDN_KERNEL_SCAN_FWD, s, [&] { return launch_scan_fwd(d, sa, s); });
+    }
+    // segments: precompute of segment i+1 on the second stream beside the scan of segment i on the caller's
+    Side *sd = side(nseg + 1);
+    if (!sd) return MDN_ERR_LAUNCH;
+    if (hipEventRecord(sd->ev[nseg], s) != hipSuccess || hipStreamWaitEvent(sd->stream, sd->ev[nseg], 0) != hipSuccess)
+        return MDN_ERR_LAUNCH; // whatever the caller's stream holds so far comes first
+    for (int i = 0; i < nseg; ++i) {
+        const Dims di = segment(d, i, nseg);
+        rc = timed(MDN_KERNEL_INTRA_FWD, sd->stream, [&] { return launch_intra(di, mode, ia, sd->stream); });
+        if (rc) return rc;
+        if (hipEventRecord(sd->ev[i], sd->stream) != hipSuccess || hipStreamWaitEvent(s, sd->ev[i], 0) != hipSuccess)
+            return MDN_ERR_LAUNCH;
+        sa.S0 = i == 0 ? c.S0 : w.carryS;
+        sa.M0 = i == 0 ? c.M0 : w.carryM;
+        sa.S_final = i == nseg - 1 ? c.S_final : w.carryS;
+        sa.M_final = i == nseg - 1 ? c.M_final : w.carryM;
+        rc = timed(MDN_KERNEL_SCAN_FWD, s, [&] { return launch_scan_fwd(di, sa, s); });
+        if (rc) return rc;
+    }
+    return MDN_OK;
+}
+
+// ---- the backward over the chunks [0, d.N) of the tensors in `c`, in two steps: what does not depend on the
+// adjoints coming in from the right (the reverse pass's operands, the chunk-start states), then the rest
+struct BwdCall {
+    const void *q, *k, *v;
+    const float *beta, *alpha, *mu, *eta, *S0, *M0;
+    const void *vt_saved, *states_saved, *operands_saved, *dO;
+    const float *dS_final, *dM_final;
+    void *dq, *dk, *dv;
+    float *dbeta, *dalpha, *dmu, *deta, *dS0, *dM0;
+};
+struct Prepared {
+    RevOps ro;
+    const void *states;
+};
+
+// S_after, M_after (or null): the states after the last chunk, which the reconstruction can hand on
+int bwd_prepare(const Dims &d, const BwdCall &c, const BwdWs &w, float *S_after, float *M_after, hipStream_t s,
+                Prepared *out) {
+    int rc;
+    // chunk-local operands in the layouts of the reverse pass: kept by the forward, or recomputed
+    out->ro = w.ops;
+    if (c.operands_saved) {
+        out->ro = carve_rev(d, const_cast<void *>(c.operands_saved));
+    } else {
+        IntraArgs ia = {};
+        ia.q = c.q; ia.k = c.k; ia.alpha = c.alpha; ia.beta = c.beta; ia.mu = c.mu; ia.eta = c.eta;
+        ia.coef = out->ro.coef; ia.KT = out->ro.KT; ia.QT = out->ro.QT; ia.BmT = out->ro.BmT; ia.TmT = out->ro.TmT;
+        rc = timed(MDN_KERNEL_INTRA_BWD, s, [&] { return launch_intra(d, 1, ia, s); });
+        if (rc) return rc;
+    }
+    // chunk-start states: given by the forward, or reconstructed from V~
+    out->states = c.states_saved;
+    if (!out->states) {
+        RebuildArgs ra = {};
+        ra.coef = out->ro.coef; ra.KT = out->ro.KT; ra.vt_saved = c.vt_saved; ra.S0 = c.S0; ra.M0 = c.M0;
+        ra.states = w.states; ra.S_final = S_after; ra.M_final = M_after;
+        rc = timed(MDN_KERNEL_REBUILD, s, [&] { return launch_rebuild(d, ra, s); });
+        if (rc) return rc;
+        out->states = w.states;
+    }
+    return MDN_OK;
+}
+
+int bwd_run(const Dims &d, const BwdCall &c, const BwdWs &w, const Prepared &p, hipStream_t s) {
+    int rc;
+    const RevOps &ro = p.ro;
+    ScanBwdArgs sb = {};
+    sb.k = c.k; sb.dO = c.dO; sb.coef = ro.coef; sb.QT = ro.QT; sb.KT = ro.KT; sb.BmT = ro.BmT;
+    sb.TmT = ro.TmT; sb.dS_final = c.dS_final; sb.dM_final = c.dM_final; sb.dv = c.dv; sb.dstates = w.dstates;
+    sb.dS0 = c.dS0; sb.dM0 = c.dM0;
+    GradArgs ga = {};
+    ga.q = c.q; ga.k = c.k; ga.alpha = c.alpha; ga.beta = c.beta; ga.mu = c.mu; ga.eta = c.eta;
+    ga.vt_saved = c.vt_saved; ga.dO = c.dO; ga.dv = c.dv; ga.KT = ro.KT; ga.QT = ro.QT;
+    ga.states = p.states; ga.dstates = w.dstates;
+    ga.dq = c.dq; ga.dk = c.dk; ga.dalpha = c.dalpha; ga.dbeta = c.dbeta; ga.dmu = c.dmu; ga.deta = c.deta;
+    const int nseg = segments(d);
+    if (nseg == 1) {
+        rc = timed(MDN_KERNEL_SCAN_BWD, s, [&] { return launch_scan_bwd(d, sb, s); });
+        if (rc) return rc;
+        return timed(MDN_KERNEL_GRAD, s, [&] { return launch_grad(d, ga, s); });
+    }
+    // segments, last first: the gradient kernel of segment i on the second stream beside the reverse scan
+    // of segment i-1 on the caller's; the caller's stream then waits for the last gradient launch
+    Side *sd = side(nseg + 1);
+    if (!sd) return MDN_ERR_LAUNCH;
+    for (int i = nseg - 1; i >= 0; --i) {
+        const Dims di = segment(d, i, nseg);
+        sb.dS_final = i == nseg - 1 ? c.dS_final : w.carryS;
+        sb.dM_final = i == nseg - 1 ? c.dM_final : w.carryM;
+        sb.dS0 = i == 0 ? c.dS0 : w.carryS;
+        sb.dM0 = i == 0 ? c.dM0 : w.carryM;
+        rc = timed(MDN_KERNEL_SCAN_BWD, s, [&] { return launch_scan_bwd(di, sb, s); });
+        if (rc) return rc;
+        if (hipEventRecord(sd->ev[i], s) != hipSuccess || hipStreamWaitEvent(sd->stream, sd->ev[i], 0) != hipSuccess)
+            return MDN_ERR_LAUNCH;
+        rc = timed(MDN_KERNEL_GRAD, sd->stream, [&] { return launch_grad(di, ga, sd->stream); });
+        if (rc) return rc;
+    }
+    if (hipEventRecord(sd->ev[nseg], sd->stream) != hipSuccess || hipStreamWaitEvent(s, sd->ev[nseg], 0) != hipSuccess)
+        return MDN_ERR_LAUNCH;
+    return MDN_OK;
+}
+
+size_t fwd_ws_total(const Dims &d, int r) {
+    if (r == 0) return carve_fwd(d, nullptr).total;
+    return carve_fwd(d, nullptr).total + carve_fwd(tail_dims(d), nullptr).total + carve_tail(d, false, nullptr).total;
+}
+size_t bwd_ws_total(const Dims &d, int r) {
+    if (r == 0) return carve_bwd(d, nullptr).total;
+    return carve_bwd(d, nullptr).total + carve_bwd(tail_dims(d), nullptr).total + carve_tail(d, true, nullptr).total;
+}
+
 } // namespace
 
 extern "C" {
@@ -207,7 +418,7 @@ const char *mdn_strerror(int code) {
     switch (code) {
     case MDN_OK: return "ok";
     case MDN_ERR_NULL: return "a required pointer is NULL";
-    case MDN_ERR_SHAPE: return "unsupported shape (need dk = dv in {64,128}, C = 64, T % 64 == 0, sizes >= 1)";
+    case MDN_ERR_SHAPE: return "unsupported shape (need dk = dv in {64,128}, C = 64, sizes >= 1)";
     case MDN_ERR_DTYPE: return "unsupported dtype";
     case MDN_ERR_WORKSPACE: return "workspace too small";
     case MDN_ERR_ALIGN: return "pointer not 16-byte aligned";
@@ -222,8 +433,8 @@ int mdn_workspace_bytes(const mdn_shape *shape, int which, size_t *bytes_out) {
     if (!bytes_out) return MDN_ERR_NULL;
     int rc = check_shape(shape, true, &d);
     if (rc) return rc;
-    if (which == MDN_WS_FWD) *bytes_out = carve_fwd(d, nullptr).total;
-    else if (which == MDN_WS_BWD) *bytes_out = carve_bwd(d, nullptr).total;
+    if (which == MDN_WS_FWD) *bytes_out = fwd_ws_total(d, shape->T % 64);
+    else if (which == MDN_WS_BWD) *bytes_out = bwd_ws_total(d, shape->T % 64);
     else return MDN_ERR_SHAPE;
     return MDN_OK;
 }
@@ -233,8 +444,8 @@ int mdn_saved_states_bytes(const mdn_shape *shape, size_t *bytes_out) {
     if (!bytes_out) return MDN_ERR_NULL;
     int rc = check_shape(shape, true, &d);
     if (rc) return rc;
-    const size_t es = d.dtype == MDN_DTYPE_F32 ? 4 : 2;
-    *bytes_out = (size_t)d.BH * d.N * 2 * d.dk * d.dv * es;
+    // the full chunks' blocks first, then (T % 64 != 0) one block per (batch, head) for the partial chunk
+    *bytes_out = saved_states_part(d) + (shape->T % 64 ? saved_states_part(tail_dims(d)) : 0);
     return MDN_OK;
 }
 
@@ -243,7 +454,7 @@ int mdn_saved_operands_bytes(const mdn_shape *shape, size_t *bytes_out) {
     if (!bytes_out) return MDN_ERR_NULL;
     int rc = check_shape(shape, true, &d);
     if (rc) return rc;
-    *bytes_out = carve_rev(d, nullptr).total;
+    *bytes_out = carve_rev(d, nullptr).total + (shape->T % 64 ? carve_rev(tail_dims(d), nullptr).total : 0);
     return MDN_OK;
 }
 
@@ -259,48 +470,44 @@ int mdn_chunk_fwd(const mdn_shape *shape, const void *q, const void *k, const vo
                           operands_saved, workspace};
     for (const void *p : ptrs)
         if (p && misaligned(p)) return MDN_ERR_ALIGN;
-    FwdWs w = carve_fwd(d, workspace);
-    if (workspace_bytes < w.total) return MDN_ERR_WORKSPACE;
+    const int r = shape->T % 64;
+    if (workspace_bytes < fwd_ws_total(d, r)) return MDN_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    FwdCall c = {q, k, v, beta, alpha, mu, eta, S0, M0, o, S_final, M_final, vt_saved, states_saved, operands_saved};
+    const FwdWs w = carve_fwd(d, workspace);
+    if (r == 0) return run_fwd(d, c, w, s);
 
-    IntraArgs ia = {};
-    ia.q = q; ia.k = k; ia.alpha = alpha; ia.beta = beta; ia.mu = mu; ia.eta = eta;
-    ia.coef = w.coef; ia.KT = w.KT; ia.Tm = w.Tm; ia.Bm = w.Bm;
-    if (operands_saved) {
-        // training forward: one precompute pass writes the reverse pass's operands as well
-        const RevOps ro = carve_rev(d, operands_saved);
-        ia.coef = ro.coef; ia.KT = ro.KT; ia.QT = ro.QT; ia.BmT = ro.BmT; ia.TmT = ro.TmT;
-    }
-    ScanFwdArgs sa = {};
-    sa.q = q; sa.k = k; sa.v = v; sa.coef = ia.coef; sa.KT = ia.KT; sa.Tm = w.Tm; sa.Bm = w.Bm;
-    sa.S0 = S0; sa.M0 = M0; sa.o = o; sa.vt_saved = vt_saved; sa.states_saved = states_saved;
-    sa.S_final = S_final; sa.M_final = M_final;
-    const int mode = operands_saved ? 2 : 0;
-    const int nseg = segments(d);
-    if (nseg == 1) {
-        rc = timed(MDN_KERNEL_INTRA_FWD, s, [&] { return launch_intra(d, mode, ia, s); });
-        if (rc) return rc;
-        return timed(MDN_KERNEL_SCAN_FWD, s, [&] { return launch_scan_fwd(d, sa, s); });
-    }
-    // segments: precompute of segment i+1 on the second stream beside the scan of segment i on the caller's
-    Side *sd = side(nseg + 1);
-    if (!sd) return MDN_ERR_LAUNCH;
-    if (hipEventRecord(sd->ev[nseg], s) != hipSuccess || hipStreamWaitEvent(sd->stream, sd->ev[nseg], 0) != hipSuccess)
-        return MDN_ERR_LAUNCH; // whatever the caller's stream holds so far comes first
-    for (int i = 0; i < nseg; ++i) {
-        const Dims di = segment(d, i, nseg);
-        rc = timed(MDN_KERNEL_INTRA_FWD, sd->stream, [&] { return launch_intra(di, mode, ia, sd->stream); });
-        if (rc) return rc;
-        if (hipEventRecord(sd->ev[i], sd->stream) != hipSuccess || hipStreamWaitEvent(s, sd->ev[i], 0) != hipSuccess)
-            return MDN_ERR_LAUNCH;
-        sa.S0 = i == 0 ? S0 : w.carryS;
-        sa.M0 = i == 0 ? M0 : w.carryM;
-        sa.S_final = i == nseg - 1 ? S_final : w.carryS;
-        sa.M_final = i == nseg - 1 ? M_final : w.carryM;
-        rc = timed(MDN_KERNEL_SCAN_FWD, s, [&] { return launch_scan_fwd(di, sa, s); });
+    // full chunks on the caller's tensors, then the partial chunk on padded copies
+    const Dims dt = tail_dims(d);
+    const FwdWs wt = carve_fwd(dt, offset(workspace, w.total));
+    const TailBufs tb = carve_tail(d, false, offset(workspace, w.total + wt.total));
+    const size_t es = elem_size(d);
+    if (d.N > 0) {
+        c.S_final = tb.S_mid;
+        c.M_final = tb.M_mid;
+        rc = run_fwd(d, c, w, s);
         if (rc) return rc;
     }
-    return MDN_OK;
+    TailList in(d, r);
+    in.add(q, tb.q, d.dk * es);
+    in.add(k, tb.k, d.dk * es);
+    in.add(v, tb.v, d.dv * es);
+    in.add(beta, tb.beta, 4, 0.f);
+    in.add(alpha, tb.alpha, 4, 1.f);
+    in.add(mu, tb.mu, 4, 1.f);
+    in.add(eta, tb.eta, 4, 1.f);
+    rc = launch_status(launch_tail_copy(in.c, true, s));
+    if (rc) return rc;
+    FwdCall ct = {tb.q, tb.k, tb.v, tb.beta, tb.alpha, tb.mu, eta ? tb.eta : nullptr,
+                  d.N > 0 ? tb.S_mid : S0, d.N > 0 ? tb.M_mid : M0, tb.o, S_final, M_final,
+                  vt_saved ? tb.vt : nullptr, offset(states_saved, saved_states_part(d)),
+                  offset(operands_saved, carve_rev(d, nullptr).total)};
+    rc = run_fwd(dt, ct, wt, s);
+    if (rc) return rc;
+    TailList out(d, r);
+    out.add(o, tb.o, d.dv * es);
+    out.add(vt_saved, tb.vt, d.dv * es);
+    return launch_status(launch_tail_copy(out.c, false, s));
 }
 
 int mdn_chunk_bwd(const mdn_shape *shape, const void *q, const void *k, const void *v, const float *beta,
@@ -320,67 +527,67 @@ int mdn_chunk_bwd(const mdn_shape *shape, const void *q, const void *k, const vo
                           dq, dk, dv, dbeta, dalpha, dmu, deta, dS0, dM0, workspace};
     for (const void *p : ptrs)
         if (p && misaligned(p)) return MDN_ERR_ALIGN;
-    BwdWs w = carve_bwd(d, workspace);
-    if (workspace_bytes < w.total) return MDN_ERR_WORKSPACE;
+    const int r = shape->T % 64;
+    if (workspace_bytes < bwd_ws_total(d, r)) return MDN_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
-
-    // chunk-local operands in the layouts of the reverse pass: kept by the forward, or recomputed
-    RevOps ro = w.ops;
-    if (operands_saved) {
-        ro = carve_rev(d, const_cast<void *>(operands_saved));
-    } else {
-        IntraArgs ia = {};
-        ia.q = q; ia.k = k; ia.alpha = alpha; ia.beta = beta; ia.mu = mu; ia.eta = eta;
-        ia.coef = ro.coef; ia.KT = ro.KT; ia.QT = ro.QT; ia.BmT = ro.BmT; ia.TmT = ro.TmT;
-        rc = timed(MDN_KERNEL_INTRA_BWD, s, [&] { return launch_intra(d, 1, ia, s); });
-        if (rc) return rc;
+    BwdCall c = {q, k, v, beta, alpha, mu, eta, S0, M0, vt_saved, states_saved, operands_saved, dO, dS_final, dM_final,
+                 dq, dk, dv, dbeta, dalpha, dmu, deta, dS0, dM0};
+    const BwdWs w = carve_bwd(d, workspace);
+    Prepared pm;
+    if (r == 0) {
+        rc = bwd_prepare(d, c, w, nullptr, nullptr, s, &pm);
+        return rc ? rc : bwd_run(d, c, w, pm, s);
     }
 
-    // chunk-start states: given by the forward, or reconstructed from V~
-    const void *states = states_saved;
-    if (!states) {
-        RebuildArgs ra = {};
-        ra.coef = ro.coef; ra.KT = ro.KT; ra.vt_saved = vt_saved; ra.S0 = S0; ra.M0 = M0; ra.states = w.states;
-        rc = timed(MDN_KERNEL_REBUILD, s, [&] { return launch_rebuild(d, ra, s); });
-        if (rc) return rc;
-        states = w.states;
-    }
-
-    ScanBwdArgs sb = {};
-    sb.k = k; sb.dO = dO; sb.coef = ro.coef; sb.QT = ro.QT; sb.KT = ro.KT; sb.BmT = ro.BmT;
-    sb.TmT = ro.TmT; sb.dS_final = dS_final; sb.dM_final = dM_final; sb.dv = dv; sb.dstates = w.dstates;
-    sb.dS0 = dS0; sb.dM0 = dM0;
-    GradArgs ga = {};
-    ga.q = q; ga.k = k; ga.alpha = alpha; ga.beta = beta; ga.mu = mu; ga.eta = eta;
-    ga.vt_saved = vt_saved; ga.dO = dO; ga.dv = dv; ga.KT = ro.KT; ga.QT = ro.QT;
-    ga.states = states; ga.dstates = w.dstates;
-    ga.dq = dq; ga.dk = dk; ga.dalpha = dalpha; ga.dbeta = dbeta; ga.dmu = dmu; ga.deta = deta;
-    const int nseg = segments(d);
-    if (nseg == 1) {
-        rc = timed(MDN_KERNEL_SCAN_BWD, s, [&] { return launch_scan_bwd(d, sb, s); });
-        if (rc) return rc;
-        return timed(MDN_KERNEL_GRAD, s, [&] { return launch_grad(d, ga, s); });
-    }
-    // segments, last first: the gradient kernel of segment i on the second stream beside the reverse scan
-    // of segment i-1 on the caller's; the caller's stream then waits for the last gradient launch
-    Side *sd = side(nseg + 1);
-    if (!sd) return MDN_ERR_LAUNCH;
-    for (int i = nseg - 1; i >= 0; --i) {
-        const Dims di = segment(d, i, nseg);
-        sb.dS_final = i == nseg - 1 ? dS_final : w.carryS;
-        sb.dM_final = i == nseg - 1 ? dM_final : w.carryM;
-        sb.dS0 = i == 0 ? dS0 : w.carryS;
-        sb.dM0 = i == 0 ? dM0 : w.carryM;
-        rc = timed(MDN_KERNEL_SCAN_BWD, s, [&] { return launch_scan_bwd(di, sb, s); });
-        if (rc) return rc;
-        if (hipEventRecord(sd->ev[i], s) != hipSuccess || hipStreamWaitEvent(sd->stream, sd->ev[i], 0) != hipSuccess)
-            return MDN_ERR_LAUNCH;
-        rc = timed(MDN_KERNEL_GRAD, sd->stream, [&] { return launch_grad(di, ga, sd->stream); });
+    // the partial chunk comes last in the sequence, so first in the reverse pass; what it needs from the full
+    // chunks (the states they leave) is ready after their preparation step
+    const Dims dt = tail_dims(d);
+    const BwdWs wt = carve_bwd(dt, offset(workspace, w.total));
+    const TailBufs tb = carve_tail(d, true, offset(workspace, w.total + wt.total));
+    const size_t es = elem_size(d);
+    if (d.N > 0) {
+        rc = bwd_prepare(d, c, w, tb.S_mid, tb.M_mid, s, &pm);
         if (rc) return rc;
     }
-    if (hipEventRecord(sd->ev[nseg], sd->stream) != hipSuccess || hipStreamWaitEvent(s, sd->ev[nseg], 0) != hipSuccess)
-        return MDN_ERR_LAUNCH;
-    return MDN_OK;
+    TailList in(d, r);
+    in.add(q, tb.q, d.dk * es);
+    in.add(k, tb.k, d.dk * es);
+    in.add(v, tb.v, d.dv * es);
+    in.add(vt_saved, tb.vt, d.dv * es);
+    in.add(dO, tb.dO, d.dv * es);
+    in.add(beta, tb.beta, 4, 0.f);
+    in.add(alpha, tb.alpha, 4, 1.f);
+    in.add(mu, tb.mu, 4, 1.f);
+    in.add(eta, tb.eta, 4, 1.f);
+    rc = launch_status(launch_tail_copy(in.c, true, s));
+    if (rc) return rc;
+    // (with states kept by the forward the partial chunk's start states are in their own part of that buffer;
+    //  otherwise they are reconstructed from what the full chunks leave)
+    BwdCall ct = {tb.q, tb.k, tb.v, tb.beta, tb.alpha, tb.mu, eta ? tb.eta : nullptr,
+                  d.N > 0 ? tb.S_mid : S0, d.N > 0 ? tb.M_mid : M0, tb.vt,
+                  offset(states_saved, saved_states_part(d)), offset(operands_saved, carve_rev(d, nullptr).total), tb.dO,
+                  dS_final, dM_final, tb.dq, tb.dk, tb.dv, tb.dbeta, tb.dalpha, tb.dmu, deta ? tb.deta : nullptr,
+                  d.N > 0 ? tb.dS_mid : dS0, d.N > 0 ? tb.dM_mid : dM0};
+    Prepared pt;
+    rc = bwd_prepare(dt, ct, wt, nullptr, nullptr, s, &pt);
+    if (rc) return rc;
+    rc = bwd_run(dt, ct, wt, pt, s);
+    if (rc) return rc;
+    if (d.N > 0) {
+        c.dS_final = tb.dS_mid;
+        c.dM_final = tb.dM_mid;
+        rc = bwd_run(d, c, w, pm, s);
+        if (rc) return rc;
+    }
+    TailList out(d, r);
+    out.add(dq, tb.dq, d.dk * es);
+    out.add(dk, tb.dk, d.dk * es);
+    out.add(dv, tb.dv, d.dv * es);
+    out.add(dbeta, tb.dbeta, 4);
+    out.add(dalpha, tb.dalpha, 4);
+    out.add(dmu, tb.dmu, 4);
+    out.add(deta, tb.deta, 4);
+    return launch_status(launch_tail_copy(out.c, false, s));
 }
 
 int mdn_recurrent_step(const mdn_shape *shape, const void *q, const void *k, const void *v, const float *beta,

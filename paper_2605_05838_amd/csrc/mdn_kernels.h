@@ -50,6 +50,7 @@ struct RebuildArgs {
     const void *vt_saved;                   // [B,T,H,dv]
     const float *S0, *M0;
     void *states;                           // [BH][N][2] x vblk [dk][dv]
+    float *S_final, *M_final;               // states after the last chunk, or null
 };
 
 struct ScanBwdArgs {
@@ -87,5 +88,19 @@ hipError_t launch_rebuild(const Dims &d, const RebuildArgs &a, hipStream_t s);
 hipError_t launch_scan_bwd(const Dims &d, const ScanBwdArgs &a, hipStream_t s);
 hipError_t launch_grad(const Dims &d, const GradArgs &a, hipStream_t s);
 hipError_t launch_recurrent(const Dims &d, const RecurrentArgs &a, hipStream_t s);
+
+// Rows of a partial last chunk: tokens t0 .. t0+r-1 of every sequence of a [B,T,H,row] tensor <-> rows 0 .. r-1 of
+// a padded [B,64,H,row] copy (gather fills the rows from r on with pad_word).
+struct TailTensor {
+    const void *full; // the caller's tensor (written by scatter)
+    void *padded;     // the padded copy (written by gather)
+    int row_bytes;    // a multiple of 4
+    uint32_t pad_word;
+};
+struct TailCopy {
+    int B, T, H, t0, r, n; // n tensors
+    TailTensor t[12];
+};
+hipError_t launch_tail_copy(const TailCopy &c, bool gather, hipStream_t s);
 
 } // namespace mdn

@@ -317,16 +317,14 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
         if (n < d.n1) step(n, opsA, opsB);
     }
 
-    if (!REBUILD) {
 #pragma unroll
-        for (int mv = 0; mv < MV; ++mv)
+    for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
-            for (int nd = 0; nd < ND; ++nd) {
-                const size_t g = ((size_t)bh * DK + (w * ND + nd) * 16 + r) * DV + dv0 + mv * 16 + kg * 4;
-                if (a.S_final) *reinterpret_cast<f32x4 *>(a.S_final + g) = accS[mv][nd];
-                if (a.M_final) *reinterpret_cast<f32x4 *>(a.M_final + g) = accM[mv][nd];
-            }
-    }
+        for (int nd = 0; nd < ND; ++nd) {
+            const size_t g = ((size_t)bh * DK + (w * ND + nd) * 16 + r) * DV + dv0 + mv * 16 + kg * 4;
+            if (a.S_final) *reinterpret_cast<f32x4 *>(a.S_final + g) = accS[mv][nd];
+            if (a.M_final) *reinterpret_cast<f32x4 *>(a.M_final + g) = accM[mv][nd];
+        }
 }
 
 
@@ -563,6 +561,8 @@ hipError_t launch_rebuild(const Dims &d, const RebuildArgs &r, hipStream_t s) {
     a.S0 = r.S0;
     a.M0 = r.M0;
     a.states_saved = r.states;
+    a.S_final = r.S_final;
+    a.M_final = r.M_final;
     return dispatch_scan<true>(d, a, s);
 }
 

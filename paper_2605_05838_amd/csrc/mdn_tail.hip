@@ -1,0 +1,52 @@
+// A sequence whose length is not a multiple of the chunk size (Algorithm 1 pads such a sequence): the
+// full chunks run on the caller's tensors as they are; the last, partial chunk runs on a padded copy of its
+// tokens.  A padding token has k = v = q = 0, alpha = mu = 1, beta = 0: by Eq. Mt.recurrent / St.recurrent it
+// changes neither S nor M, so the states after the padded chunk are the exact final states, and with dO = 0 on
+// the padding rows the reverse pass is exact as well.  These two kernels move the partial chunk's rows into
+// and out of the padded [B, 64, H, *] copies.
+#include "mdn_device.h"
+#include "mdn_kernels.h"
+
+namespace mdn {
+
+namespace {
+
+// one row = row_bytes (a multiple of 4) of tensor t; blockIdx.y = tensor, blockIdx.x = (b, i, h) row
+__global__ __launch_bounds__(64) void tail_gather_kernel(TailCopy c) {
+    const TailTensor t = c.t[blockIdx.y];
+    const int row = blockIdx.x, h = row % c.H, i = (row / c.H) % 64, b = row / (c.H * 64);
+    const int words = t.row_bytes / 4;
+    uint32_t *dst = reinterpret_cast<uint32_t *>(static_cast<char *>(t.padded) + (size_t)row * t.row_bytes);
+    if (i < c.r) {
+        const size_t srow = ((size_t)b * c.T + (size_t)c.t0 + i) * c.H + h;
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(static_cast<const char *>(t.full) + srow * t.row_bytes);
+        for (int x = threadIdx.x; x < words; x += 64) dst[x] = src[x];
+    } else {
+        for (int x = threadIdx.x; x < words; x += 64) dst[x] = t.pad_word;
+    }
+}
+
+__global__ __launch_bounds__(64) void tail_scatter_kernel(TailCopy c) {
+    const TailTensor t = c.t[blockIdx.y];
+    const int row = blockIdx.x, h = row % c.H, i = (row / c.H) % 64, b = row / (c.H * 64);
+    if (i >= c.r) return;
+    const int words = t.row_bytes / 4;
+    const uint32_t *src = reinterpret_cast<const uint32_t *>(static_cast<const char *>(t.padded) + (size_t)row * t.row_bytes);
+    const size_t drow = ((size_t)b * c.T + (size_t)c.t0 + i) * c.H + h;
+    uint32_t *dst = reinterpret_cast<uint32_t *>(static_cast<char *>(const_cast<void *>(t.full)) + drow * t.row_bytes);
+    for (int x = threadIdx.x; x < words; x += 64) dst[x] = src[x];
+}
+
+} // namespace
+
+hipError_t launch_tail_copy(const TailCopy &c, bool gather, hipStream_t s) {
+    if (c.n < 1) return hipSuccess;
+    dim3 grid(c.B * 64 * c.H, c.n), block(64);
+    if (gather)
+        hipLaunchKernelGGL(tail_gather_kernel, grid, block, 0, s, c);
+    else
+        hipLaunchKernelGGL(tail_scatter_kernel, grid, block, 0, s, c);
+    return hipGetLastError();
+}
+
+} // namespace mdn

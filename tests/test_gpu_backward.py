@@ -123,3 +123,16 @@ def test_split_into_segments_on_two_streams_equals_the_unsplit_call(dtype, d, T,
         assert torch.equal(f1[name], f2[name]), name
     for name in ("dq", "dk", "dv", "dalpha", "dbeta", "dmu", "deta", "dS0", "dM0"):
         assert torch.equal(g1[name], g2[name]), name
+
+
+@pytest.mark.parametrize("dtype,d,T,keep_states,keep_operands",
+                         [("f32", 64, 200, False, False), ("bf16", 128, 200, True, True), ("f32", 128, 40, False, False),
+                          ("bf16", 64, 135, True, False), ("f32", 64, 200, False, True)])
+def test_backward_of_a_sequence_length_that_is_not_a_multiple_of_the_chunk_size(dtype, d, T, keep_states, keep_operands):
+    """All gradients of the T tokens given, with adjoints of the final states coming in, whether the forward kept
+    its states / operands or the backward rebuilds them (the partial chunk goes first in the reverse pass and takes
+    its start states from what the full chunks leave)."""
+    w = synth.custom(B=2, T=T, H=2, dk=d, dv=d, dtype=dtype, seed=43, with_eta=True, s0_std=0.3, backward=True)
+    rng = np.random.default_rng(9)
+    w.arrays["M0"] = (rng.standard_normal((2, 2, d, d)) * 0.2).astype(np.float32)
+    check_bwd(w, final_adjoints=True, save_states=keep_states, save_operands=keep_operands)

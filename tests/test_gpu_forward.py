@@ -113,3 +113,14 @@ def test_prefill_states_hand_off_to_the_recurrent_step(dtype):
     assert rel_err(host(o)[:, Tp:], ref["o"][:, Tp:]) <= tol
     assert rel_err(host(o), ref["o"]) <= tol
     assert rel_err(host(S), ref["S"]) <= tol and rel_err(host(M), ref["M"]) <= tol
+
+
+@pytest.mark.parametrize("dtype,d,T", [("f32", 64, 200), ("bf16", 128, 200), ("f32", 128, 40), ("bf16", 64, 70),
+                                       ("f32", 64, 1)])
+def test_sequence_length_that_is_not_a_multiple_of_the_chunk_size(dtype, d, T):
+    """A partial last chunk (and a sequence shorter than one chunk) gives the outputs and final states of
+    exactly the T tokens given: the padding the library adds consists of identity steps of the recurrence."""
+    w = synth.custom(B=2, T=T, H=3, dk=d, dv=d, dtype=dtype, seed=41, with_eta=True, s0_std=0.3)
+    rng = np.random.default_rng(8)
+    w.arrays["M0"] = (rng.standard_normal((2, 3, d, d)) * 0.2).astype(np.float32)
+    check_fwd(w)
