@@ -97,18 +97,24 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
             *reinterpret_cast<Vec16<T> *>(sQ + row * LDN + cc * E) = rq[u];
         }
     }
-    // sources of the transposed tiles: in flight until the K, Q tiles are no longer needed
-    Vec16<T> rkt[NVK], rxt[NVX];
+    // 16-bit storage: the transposed tiles K^T, Q^T come straight out of the natural tiles in LDS through
+    // transposing reads (a fragment of such a read is one 16-byte piece of the blocked layout).  32-bit storage:
+    // the rows are loaded a second time in the order of the transposed tiles (in flight until the K, Q tiles are
+    // no longer needed) and transposed through LDS.
+    constexpr bool TRT = sizeof(T) == 2;
+    Vec16<T> rkt[TRT ? 1 : NVK], rxt[TRT ? 1 : NVX];
+    if constexpr (!TRT) {
 #pragma unroll
-    for (int u = 0; u < NVK; ++u) {
-        const int c = tid + u * kThreads, row = c % 64, cc = c / 64;
-        rkt[u] = *reinterpret_cast<const Vec16<T> *>(kg_ + row * rsk + cc * E);
-    }
-    if (BWD) {
-#pragma unroll
-        for (int u = 0; u < NVX; ++u) {
+        for (int u = 0; u < NVK; ++u) {
             const int c = tid + u * kThreads, row = c % 64, cc = c / 64;
-            rxt[u] = *reinterpret_cast<const Vec16<T> *>(qg + row * rsk + cc * E);
+            rkt[u] = *reinterpret_cast<const Vec16<T> *>(kg_ + row * rsk + cc * E);
+        }
+        if (BWD) {
+#pragma unroll
+            for (int u = 0; u < NVX; ++u) {
+                const int c = tid + u * kThreads, row = c % 64, cc = c / 64;
+                rxt[u] = *reinterpret_cast<const Vec16<T> *>(qg + row * rsk + cc * E);
+            }
         }
     }
 
@@ -198,19 +204,34 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
     }
     __syncthreads();
 
-    // ---- transposed tiles into the space of the K, Q tiles (dst[d][row] = src[row][d])
+    if constexpr (TRT) {
+        // ---- K^T, Q^T for the scans: (dk tile, 32-token step) blocks dealt over the waves; lane (r, kq) reads
+        //      (dk = 16 dt + r, tokens 32 ks + 8 kq ..) and owns exactly that 16-byte piece of the blocked layout,
+        //      so a wave stores 1 KB of consecutive bytes
+        T *KTo = static_cast<T *>(a.KT) + blk * (DK * 64);
+        T *QTo = BWD ? static_cast<T *>(a.QT) + blk * (DK * 64) : nullptr;
 #pragma unroll
-    for (int u = 0; u < NVK; ++u) {
-        const int c = tid + u * kThreads, row = c % 64, cc = c / 64;
+        for (int t = 0; t < (DK / 16) * 2 / 4; ++t) {
+            const int tt = w + 4 * t, dt = tt >> 1, ks = tt & 1;
+            const size_t o = kblk<T>(DK, dt * 16 + r, ks * 32 + kq * 8);
+            *reinterpret_cast<typename O::Frag *>(KTo + o) = tr_frag(sK, LDN, ks * 32, dt * 16, r, kq);
+            if (BWD) *reinterpret_cast<typename O::Frag *>(QTo + o) = tr_frag(sQ, LDN, ks * 32, dt * 16, r, kq);
+        }
+    } else {
+        // ---- transposed tiles into the space of the K, Q tiles (dst[d][row] = src[row][d])
 #pragma unroll
-        for (int e = 0; e < E; ++e) sKT[(cc * E + e) * LDT + row] = rkt[u].e[e];
-    }
-    if (BWD) {
-#pragma unroll
-        for (int u = 0; u < NVX; ++u) {
+        for (int u = 0; u < NVK; ++u) {
             const int c = tid + u * kThreads, row = c % 64, cc = c / 64;
 #pragma unroll
-            for (int e = 0; e < E; ++e) sXT[(cc * E + e) * LDT + row] = rxt[u].e[e];
+            for (int e = 0; e < E; ++e) sKT[(cc * E + e) * LDT + row] = rkt[u].e[e];
+        }
+        if (BWD) {
+#pragma unroll
+            for (int u = 0; u < NVX; ++u) {
+                const int c = tid + u * kThreads, row = c % 64, cc = c / 64;
+#pragma unroll
+                for (int e = 0; e < E; ++e) sXT[(cc * E + e) * LDT + row] = rxt[u].e[e];
+            }
         }
     }
     // ---- T = (I + A)^{-1} by 16x16 blocks, wave w = block row w
@@ -218,8 +239,10 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
     __syncthreads();
 
     // raw transposed copies for the scans
-    store_tile_64cols<T>(static_cast<T *>(a.KT) + blk * (DK * 64), sKT, LDT, DK, tid);
-    if (BWD) store_tile_64cols<T>(static_cast<T *>(a.QT) + blk * (DK * 64), sXT, LDT, DK, tid);
+    if constexpr (!TRT) {
+        store_tile_64cols<T>(static_cast<T *>(a.KT) + blk * (DK * 64), sKT, LDT, DK, tid);
+        if (BWD) store_tile_64cols<T>(static_cast<T *>(a.QT) + blk * (DK * 64), sXT, LDT, DK, tid);
+    }
     if (BWD) {
         T *tt = static_cast<T *>(a.TmT) + blk * 4096; // T^T: row j, k = i
         constexpr int E = O::EPL;
