@@ -80,21 +80,18 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
     const size_t rsk = (size_t)d.H * DK;
     float *coef = a.coef + blk * (kCoefRows * 64);
 
-    // ---- K, Q tiles: all loads in flight at once, then to LDS
+    // ---- the gates first, then the K, Q tiles: all loads in flight at once; the coefficient scans below need
+    //      only the gates and run while the tiles are on their way
+    const size_t gtok = tok0 + (size_t)lane * d.H;
+    const float g_al = a.alpha[gtok], g_be = a.beta[gtok], g_mu = a.mu[gtok], g_et = a.eta ? a.eta[gtok] : 1.f;
+    typename O::Frag rk[NVK], rq[NVK];
     {
-        Vec16<T> rk[NVK], rq[NVK];
         constexpr int CPR = DK / E;
 #pragma unroll
         for (int u = 0; u < NVK; ++u) {
             const int c = tid + u * kThreads, row = c / CPR, cc = c % CPR;
-            rk[u] = *reinterpret_cast<const Vec16<T> *>(kg_ + row * rsk + cc * E);
-            rq[u] = *reinterpret_cast<const Vec16<T> *>(qg + row * rsk + cc * E);
-        }
-#pragma unroll
-        for (int u = 0; u < NVK; ++u) {
-            const int c = tid + u * kThreads, row = c / CPR, cc = c % CPR;
-            *reinterpret_cast<Vec16<T> *>(sK + row * LDN + cc * E) = rk[u];
-            *reinterpret_cast<Vec16<T> *>(sQ + row * LDN + cc * E) = rq[u];
+            rk[u] = O::load(kg_ + row * rsk + cc * E);
+            rq[u] = O::load(qg + row * rsk + cc * E);
         }
     }
     // 16-bit storage: the transposed tiles K^T, Q^T come straight out of the natural tiles in LDS through
@@ -121,8 +118,7 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
     // ---- gate coefficients.  Matrix Gamma: every wave 16 rows (column scans started from segment maps);
     //      vectors: wave 0, by wave scans (lane i = token i).
     {
-        const size_t g = tok0 + (size_t)lane * d.H;
-        const float al = a.alpha[g], be = a.beta[g], mu = a.mu[g], et = a.eta ? a.eta[g] : 1.f;
+        const float al = g_al, be = g_be, mu = g_mu, et = g_et;
         if (w == 0) {
             const float pa = scan_prod(al), pm = scan_prod(mu);
             float c = al, pb = be * pm;
@@ -146,6 +142,15 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
         if (w == 3) {
             coef[COEF_GC * 64 + lane] = gC * et;
             coef[COEF_RC * 64 + lane] = rC * et;
+        }
+    }
+    {
+        constexpr int CPR = DK / E;
+#pragma unroll
+        for (int u = 0; u < NVK; ++u) {
+            const int c = tid + u * kThreads, row = c / CPR, cc = c % CPR;
+            *reinterpret_cast<typename O::Frag *>(sK + row * LDN + cc * E) = rk[u];
+            *reinterpret_cast<typename O::Frag *>(sQ + row * LDN + cc * E) = rq[u];
         }
     }
     __syncthreads();
