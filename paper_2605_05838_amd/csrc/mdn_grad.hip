@@ -122,8 +122,8 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     __shared__ __align__(16) T sVt[STAGED ? 64 * D : 8];
     __shared__ __align__(16) T sDO[STAGED ? 64 * D : 8];
     __shared__ __align__(16) T sDR[STAGED ? 64 * D : 8];
-    T *sK = sW;
-    static_assert(4 * LDW >= D, "k tile does not fit the W space");
+    T *sK = sW, *sQ = sW + 64 * D;
+    static_assert(4 * LDW >= 2 * D, "k and q tiles do not fit the W space");
     __shared__ __align__(16) float s_al[64], s_et[64], s_a[64], s_b[64];
     __shared__ float sRowC[3 * 64]; // reverse scan: the three per-row coefficients
     __shared__ float s_gC[64], s_rC[64];
@@ -207,7 +207,6 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     //      LDS, waves 6 and 7) and its q fragments.  For every chunk but the workgroup's first that is during
     //      the coefficient phase of the chunk before, which has no memory traffic of its own.
     float n_al = 0.f, n_be = 0.f, n_mu = 0.f, n_et = 1.f; // gates of token `lane` of the chunk being requested
-    Frag fq[KSK]; // phase A B fragments of q (no LDS copy): row = token i
     auto request_gates = [&]() {
         if (w < 6) { // waves 6, 7 never use them, and must not wait for anything behind their tile transfers
             n_al = *at32(a.alpha + tok0, gl);
@@ -215,10 +214,6 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
             n_mu = *at32(a.mu + tok0, gl);
             n_et = a.eta ? *at32(a.eta + tok0, gl) : 1.f;
         }
-    };
-    auto request_q = [&]() {
-#pragma unroll
-        for (int s = 0; s < KSK; ++s) fq[s] = O::load(at32(qg, i * rsk + s * O::KSTEP + kg * E));
     };
     // ---- phase 0: forward coefficients of the chunk whose gates are in n_*: waves 0-3 the matrices Gamma, Rho
     //      (16 rows each), wave 4 the vectors by wave scans
@@ -255,16 +250,16 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     if (STAGED && w >= 6) {
         dma_token_tile<T, D>(sVt, vtg, rsv, w - 6, lane);
         dma_token_tile<T, D>(sK, kgl, rsk, w - 6, lane);
+        dma_token_tile<T, D>(sQ, qg, rsk, w - 6, lane);
         dma_token_tile<T, D>(sDO, dog, rsv, w - 6, lane);
         dma_token_tile<T, D>(sDR, drg, rsv, w - 6, lane);
     }
-    request_q();
     phase0();
 
     const int ldV = (int)rsv, ldK = (int)rsk; // row strides of the global tiles (fp32 path)
     for (;;) {
     refresh_ids();
-    const T *tVt = STAGED ? sVt : vtg, *tK = STAGED ? sK : kgl, *tDR = STAGED ? sDR : drg, *tDO = STAGED ? sDO : dog;
+    const T *tVt = STAGED ? sVt : vtg, *tK = STAGED ? sK : kgl, *tQ = STAGED ? sQ : qg, *tDR = STAGED ? sDR : drg, *tDO = STAGED ? sDO : dog;
     if (STAGED && w >= 6) __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): this chunk's tiles have landed
     __syncthreads(); // token tiles in LDS, coefficients ready
     // what the later phases read goes on its way now, in order of use
@@ -282,14 +277,17 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     //                  masked matrices built from them
     f32x4 accB[2], accA[2], accQK[2], accKK[2];
     {
-        Frag fdO[KSV], fdR[KSV], fk[KSK];
+        Frag fdO[KSV], fdR[KSV], fk[KSK], fq[KSK];
 #pragma unroll
         for (int s = 0; s < KSV; ++s) {
             fdO[s] = tfrag(tDO, ldV, i, s);
             fdR[s] = tfrag(tDR, ldV, i, s);
         }
 #pragma unroll
-        for (int s = 0; s < KSK; ++s) fk[s] = tfrag(tK, ldK, i, s);
+        for (int s = 0; s < KSK; ++s) {
+            fk[s] = tfrag(tK, ldK, i, s);
+            fq[s] = tfrag(tQ, ldK, i, s);
+        }
 #pragma unroll
         for (int mh = 0; mh < 2; ++mh) {
             const int j0 = (hf * 2 + mh) * 16 + r;
@@ -308,7 +306,19 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
             }
         }
     }
-    if (STAGED) __syncthreads(); // everybody is done with the k tile: the W matrices take its place
+    // k and q of this wave's tokens in accumulator layout: element x is dk = kt*16 + kg*4 + x
+    //  (kept in storage form: widening them here would make the wave wait for every load issued so far)
+    typename Raw4<T>::type kv[TT], qv[TT];
+    if (STAGED) {
+#pragma unroll
+        for (int t = 0; t < TT; ++t) {
+            const int it = (tg * TT + t) * 16 + r, c = kt * (16 / E) + (kg * 4) / E; // 16-byte piece of the row
+            const int o = it * D + ((c ^ (it & XM)) * E) + (kg * 4) % E;
+            kv[t] = load4_raw(sK + o);
+            qv[t] = load4_raw(sQ + o);
+        }
+    }
+    if (STAGED) __syncthreads(); // everybody is done with the k and q tiles: the W matrices take their place
     {
         // this lane: token i (row of the masked matrices), columns j0 .. j0+3 of tile mt; everything a row needs
         // is 16 contiguous bytes, read and written as such
@@ -350,16 +360,15 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
         }
     }
     __syncthreads();
-    // k and q of this wave's tokens in accumulator layout: element x is dk = kt*16 + kg*4 + x
-    //  (kept in storage form: widening them here would make the wave wait for every load issued so far)
-    typename Raw4<T>::type kv[TT], qv[TT];
+    if (!STAGED) { // (staged: taken from the tiles in LDS before the W matrices replaced them)
 #pragma unroll
-    for (int t = 0; t < TT; ++t) {
-        const int it = (tg * TT + t) * 16 + r;
-        kv[t] = load4_raw(at32(kgl, it * rsk + kt * 16 + kg * 4));
-        qv[t] = load4_raw(at32(qg, it * rsk + kt * 16 + kg * 4));
+        for (int t = 0; t < TT; ++t) {
+            const int it = (tg * TT + t) * 16 + r;
+            kv[t] = load4_raw(at32(kgl, it * rsk + kt * 16 + kg * 4));
+            qv[t] = load4_raw(at32(qg, it * rsk + kt * 16 + kg * 4));
+        }
+        sched_fence(); // q, k rows are needed first: keep them ahead of the state tiles in the return order
     }
-    sched_fence(); // q, k rows are needed first: keep them ahead of the state tiles in the return order
     if (DEEP) {
         load_state(fdS, dSg);
         load_state(fM, Mg); // dM' follows once S is no longer needed
@@ -578,8 +587,10 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     }
     if (!has_next) break;
     chunk = next;
-    if (STAGED && w >= 6) dma_token_tile<T, D>(sK, kgl, rsk, w - 6, lane); // the row sums are done with its space
-    request_q(); // (not earlier: 16 registers that this phase has no room for)
+    if (STAGED && w >= 6) { // the row sums are done with the space of the k and q tiles
+        dma_token_tile<T, D>(sK, kgl, rsk, w - 6, lane);
+        dma_token_tile<T, D>(sQ, qg, rsk, w - 6, lane);
+    }
     phase0(); // Gamma, Rho are free again after the row sums; the next chunk's gates arrived long ago
     } // chunks of this workgroup
 }
