@@ -163,14 +163,19 @@ template <int M, int K> struct ATile<float, M, K> {
 };
 // fragment (row or column 16*.. + r of the operand, k = k0 + kg*8 .. +7) of a bf16 matrix kept [k][n] with row
 // length ld in LDS, n0 = first of the 16 n: two transposing reads (rows k0 + kg*8 + 0..3 and + 4..7)
-__device__ __forceinline__ bf16x8 tr_frag(const bf16_t *t, int ld, int k0, int n0, int r, int kg) {
+// (the two reads given as addresses: for layouts whose rows are permuted piecewise)
+__device__ __forceinline__ bf16x8 tr_pair(const bf16_t *p_lo, const bf16_t *p_hi) {
     typedef short s16x4 __attribute__((ext_vector_type(4)));
     typedef short s16x8 __attribute__((ext_vector_type(8)));
-    const bf16_t *p = t + (k0 + kg * 8 + (r >> 2)) * ld + n0 + (r & 3) * 4;
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p));
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p + 4 * ld));
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p_lo));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p_hi));
     const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, v);
+}
+__device__ __forceinline__ f32x4 tr_pair(const float *, const float *) { return f32x4{0.f, 0.f, 0.f, 0.f}; } // (never used)
+__device__ __forceinline__ bf16x8 tr_frag(const bf16_t *t, int ld, int k0, int n0, int r, int kg) {
+    const bf16_t *p = t + (k0 + kg * 8 + (r >> 2)) * ld + n0 + (r & 3) * 4;
+    return tr_pair(p, p + 4 * ld);
 }
 template <int M, int K> struct ATile<bf16_t, M, K> {
     typedef Op<bf16_t> O;

@@ -189,6 +189,17 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
         if (STAGED) return O::load(tile + row * D + (((st * CPS + kg) ^ (row & XM)) * E));
         return O::load(at32(tile, row * ld + st * O::KSTEP + kg * E));
     };
+    // A fragment (row dk = 16 kt + r, tokens 32 s + 8 kg ..) of the transpose of a token tile in LDS: two transposing
+    // reads; lane 4e + c of a 16-lane group addresses tokens 32 s + 8 kg (+ 4) + e, dk 16 kt + 4c .. 4c+3
+    auto tile_tr_frag = [&](const T *tile, int s) -> Frag {
+        if constexpr (STAGED) {
+            const int row = s * 32 + kg * 8 + (r >> 2), c = kt * (16 / E) + ((r & 3) * 4) / E, sub = ((r & 3) * 4) % E;
+            return tr_pair(tile + row * D + ((c ^ (row & XM)) * E) + sub,
+                           tile + (row + 4) * D + ((c ^ ((row + 4) & XM)) * E) + sub);
+        } else {
+            return Frag{};
+        }
+    };
     // this wave's 16 rows (dk tile kt) of a [dk][dv] state tile as A fragments
     auto load_state = [&](Frag(&f)[KSV], const T *tile) {
 #pragma unroll
@@ -263,11 +274,18 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     if (STAGED && w >= 6) __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): this chunk's tiles have landed
     __syncthreads(); // token tiles in LDS, coefficients ready
     // what the later phases read goes on its way now, in order of use
-    Frag aK[KS2], aQ[KS2]; // this wave's rows of K^T, Q^T
+    Frag aK[KS2], aQ[KS2]; // this wave's rows of K^T, Q^T (A fragments: row dk = 16 kt + r, contraction over tokens)
 #pragma unroll
     for (int s = 0; s < KS2; ++s) {
-        aK[s] = O::load(at32(KTg, (unsigned)kblk<T>(DK, kt * 16 + r, s * O::KSTEP + kg * E)));
-        aQ[s] = O::load(at32(QTg, (unsigned)kblk<T>(DK, kt * 16 + r, s * O::KSTEP + kg * E)));
+        if constexpr (STAGED) {
+            // out of the k, q tiles in LDS by transposing reads (the tiles give way to the W matrices after
+            // phase A, so now): no second trip to HBM for bytes the CU already holds
+            aK[s] = tile_tr_frag(sK, s);
+            aQ[s] = tile_tr_frag(sQ, s);
+        } else {
+            aK[s] = O::load(at32(KTg, (unsigned)kblk<T>(DK, kt * 16 + r, s * O::KSTEP + kg * E)));
+            aQ[s] = O::load(at32(QTg, (unsigned)kblk<T>(DK, kt * 16 + r, s * O::KSTEP + kg * E)));
+        }
     }
     Frag fS[KSV], fM[KSV], fdS[KSV], fdM[KSV];
     load_state(fS, Sg);
