@@ -51,7 +51,9 @@ def bytes_per_tokhd(C, dk, dv, es, keep):
         "intra_bwd": qk + 16 + rev_ops,
         "rebuild": dk * es + dv * es + coef + states,
         "scan_bwd": rev_ops + dk * es + dv * es + dv * es + states,                   # + k, dO; dv, dstates out
-        "grad": 2 * dk * es + 3 * dv * es + 2 * dk * es + 2 * states + 16 + 2 * dk * es + 12,
+        # q, k, V~, dO, dV and both state pairs in; dq, dk and the gate gradients out (with 16-bit storage K^T and Q^T
+        # come out of the k, q tiles on chip; the fp32 path still reads them: 2 dk es more)
+        "grad": 2 * dk * es + 3 * dv * es + 2 * states + 16 + 2 * dk * es + 12 + (2 * dk * es if es == 4 else 0),
     }
 
 
