@@ -164,32 +164,56 @@ __device__ __forceinline__ void coef_column_scan_reverse(float al, float be, flo
 
 // ---- the reverse column scans split over 4 waves: wave w (0..3) owns rows 16w .. 16w+15, lane j = column j.
 //      Part 1 walks the wave's rows upwards with nothing coming in from the rows below (16 dependent
-//      steps), and also walks the three coefficients with which an incoming pair (Gin, Rin) = (G, R) of the
-//      row below the segment would enter each row:
+//      steps).  With the three coefficients with which an incoming pair (Gin, Rin) = (G, R) of the row below
+//      the segment enters each row,
 //        G_ij = Gloc_ij + gc_i Gin_j          R_ij = Rloc_ij + ec_i Gin_j + mc_i Rin_j
 //        gc_i = alpha_{i+1} gc_{i+1},  mc_i = mu_{i+1} mc_{i+1},  ec_i = beta_i gc_i + mu_{i+1} ec_{i+1}
-//      It leaves the segment's top row (local values, zero above the diagonal) and every row's three
-//      coefficients in LDS.  After a workgroup barrier, part 2 chains the top rows of the segments below to
-//      get what comes in, and completes and stores the wave's rows.
+//      (gc = mc = 1, ec = 0 below the segment's last row; alpha_64 = mu_64 = 0: nothing comes in below row 63),
+//      part 2, after a workgroup barrier, chains the top rows of the segments below to get what comes in, and
+//      completes and stores the wave's rows.  The coefficients are the same for all columns: ONE wave forms
+//      them for all 64 rows at once (lane = row, suffix scans inside the 16-lane segments) beside part 1.
 struct RevScanRows {
     float G[16], R[16];
 };
-// sTop: [4][2][64] floats (top rows: G, R); sRowC: [3][64] floats (gc, ec, mc of every row: they are the
-// same for all columns, so one copy in LDS instead of 48 registers in every lane)
+// sRowC: [3][64] floats (gc, ec, mc of every row); called by one whole wave, lane = row
+__device__ __forceinline__ void coef_scan_reverse_rowcoefs(float al, float be, float mu, float *sRowC, int lane = lane_id()) {
+    const int jl = lane & 15;
+    const float an = __shfl_down(al, 1), mn = __shfl_down(mu, 1);
+    float gc = lane < 63 ? an : 0.f, mc = lane < 63 ? mn : 0.f; // alpha_{i+1}, mu_{i+1}
+    const float y = mc;
+#pragma unroll
+    for (int dlt = 1; dlt < 16; dlt <<= 1) { // inclusive suffix products inside the segment
+        const float og = __shfl_down(gc, dlt, 16), om = __shfl_down(mc, dlt, 16);
+        if (jl + dlt < 16) {
+            gc *= og;
+            mc *= om;
+        }
+    }
+    float c = y, ec = be * gc; // ec_i = y_i ec_{i+1} + beta_i gc_i
+#pragma unroll
+    for (int dlt = 1; dlt < 16; dlt <<= 1) {
+        const float oc = __shfl_down(c, dlt, 16), od = __shfl_down(ec, dlt, 16);
+        if (jl + dlt < 16) {
+            ec = c * od + ec;
+            c = c * oc;
+        }
+    }
+    sRowC[lane] = gc;
+    sRowC[64 + lane] = ec;
+    sRowC[128 + lane] = mc;
+}
+// sTop: [4][2][64] floats (top rows: G, R)
 __device__ __forceinline__ void coef_scan_reverse_part1(float al, float be, float mu, const float *sD1, const float *sD2,
                                                         float dgc, float drc, int ldg, int w, RevScanRows &rr, float *sTop,
-                                                        float *sRowC, int j = lane_id()) {
+                                                        int j = lane_id()) {
     const int i0 = w * 16; // (w is wave-uniform: the lane selects below are scalar operands)
     float dir[16];
 #pragma unroll
     for (int u = 0; u < 16; ++u) dir[u] = sD1[(i0 + u) * ldg + j] + sD2[(i0 + u + 1) * ldg + j];
-    float cg = 0.f, cr = 0.f;           // alpha_{i+1} Gloc_{i+1,j}, mu_{i+1} Rloc_{i+1,j}
-    float gc = 1.f, ec = 0.f, mc = 1.f; // coefficients of the row below the current one
+    float cg = 0.f, cr = 0.f; // alpha_{i+1} Gloc_{i+1,j}, mu_{i+1} Rloc_{i+1,j}
 #pragma unroll
     for (int u = 15; u >= 0; --u) {
         const int i = i0 + u;
-        // gates of row i+1 (nothing below row 63: whatever stands here is multiplied by a zero incoming pair)
-        const float a_n = (i < 63) ? lane_bcast(al, (i + 1) & 63) : 0.f, m_n = (i < 63) ? lane_bcast(mu, (i + 1) & 63) : 0.f;
         const float b_i = lane_bcast(be, i);
         float G = dir[u] + cg, R = cr;
         if (i == 63) {
@@ -199,14 +223,6 @@ __device__ __forceinline__ void coef_scan_reverse_part1(float al, float be, floa
         R += b_i * G;
         rr.G[u] = G;
         rr.R[u] = R;
-        gc = a_n * gc;
-        ec = b_i * gc + m_n * ec;
-        mc = m_n * mc;
-        if (j == 0) {
-            sRowC[i] = gc;
-            sRowC[64 + i] = ec;
-            sRowC[128 + i] = mc;
-        }
         if (u > 0) {
             cg = lane_bcast(al, i) * G;
             cr = lane_bcast(mu, i) * R;

@@ -531,8 +531,9 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
             dgc = total(P_DGC);
             drc = total(P_DRC);
         }
-        coef_scan_reverse_part1(g_al, g_be, g_mu, sDG1, sDG2, dgc, drc, LDG, w, rr, sTop, sRowC, lane);
+        coef_scan_reverse_part1(g_al, g_be, g_mu, sDG1, sDG2, dgc, drc, LDG, w, rr, sTop, lane);
     }
+    if (w == 5) coef_scan_reverse_rowcoefs(g_al, g_be, g_mu, sRowC, lane); // (a wave with nothing else to do here)
     if (w == 4) {
         // vectors (lane i = token i): reverse of b_i = alpha_i b_{i-1} + beta_i m_i, a_i = alpha_i a_{i-1},
         // m_i = mu_i m_{i-1}, with a^-_i = a_{i-1}, b^-_i = b_{i-1}:
