@@ -9,46 +9,92 @@
 
 namespace mdn {
 
-// ---- scans across the 64 lanes of a wave (Kogge-Stone); lane i holds element i.  (The lane index is a
-//      parameter so that a caller with a long-running loop can pass its own, loop-variant copy.)
-
-// inclusive prefix product
-__device__ __forceinline__ float scan_prod(float v, int lane = lane_id()) {
-#pragma unroll
-    for (int dlt = 1; dlt < 64; dlt <<= 1) {
-        const float o = __shfl_up(v, dlt);
-        if (lane >= dlt) v *= o;
-    }
-    return v;
+// ---- lane shifts inside the 16-lane rows of a wave, as data-parallel-primitive moves (a few clocks; a general
+//      cross-lane shuffle goes through the LDS pipeline and costs ~100 clocks on a dependent chain)
+// value of lane - N of the same row; `fill` in the N lowest lanes of each row
+template <int N> __device__ __forceinline__ float row_up(float v, float fill) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(fill), __float_as_int(v), 0x110 | N, 0xF, 0xF, false));
 }
-
-// x_i = c_i x_{i-1} + d_i with x_{-1} = 0: on return d holds x_i (c holds prod_{l<=i} c_l)
-__device__ __forceinline__ void scan_affine_fwd(float &c, float &d, int lane = lane_id()) {
-#pragma unroll
-    for (int dlt = 1; dlt < 64; dlt <<= 1) {
-        const float oc = __shfl_up(c, dlt), od = __shfl_up(d, dlt);
-        if (lane >= dlt) {
-            d = c * od + d;
-            c = c * oc;
-        }
-    }
-}
-
-// x_i = c_i x_{i+1} + d_i with x_64 = 0: on return d holds x_i
-__device__ __forceinline__ void scan_affine_rev(float &c, float &d, int lane = lane_id()) {
-#pragma unroll
-    for (int dlt = 1; dlt < 64; dlt <<= 1) {
-        const float oc = __shfl_down(c, dlt), od = __shfl_down(d, dlt);
-        if (lane + dlt < 64) {
-            d = c * od + d;
-            c = c * oc;
-        }
-    }
+// value of lane + N of the same row; `fill` in the N highest lanes of each row
+template <int N> __device__ __forceinline__ float row_down(float v, float fill) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(fill), __float_as_int(v), 0x100 | N, 0xF, 0xF, false));
 }
 
 // value held by lane `src` (wave-uniform: a constant or a scalar) as a wave-uniform scalar
 __device__ __forceinline__ float lane_bcast(float v, int src) {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), src));
+}
+
+// value of lane + 1 / lane - 1 across the whole wave (`fill` in lane 63 / lane 0): the row shift, with the three
+// lanes at the row boundaries patched by scalar broadcasts
+__device__ __forceinline__ float wave_down1(float v, float fill, int lane) {
+    float r = row_down<1>(v, fill);
+    const float b16 = lane_bcast(v, 16), b32 = lane_bcast(v, 32), b48 = lane_bcast(v, 48);
+    r = (lane == 15) ? b16 : r;
+    r = (lane == 31) ? b32 : r;
+    r = (lane == 47) ? b48 : r;
+    return r;
+}
+__device__ __forceinline__ float wave_up1(float v, float fill, int lane) {
+    float r = row_up<1>(v, fill);
+    const float b15 = lane_bcast(v, 15), b31 = lane_bcast(v, 31), b47 = lane_bcast(v, 47);
+    r = (lane == 16) ? b15 : r;
+    r = (lane == 32) ? b31 : r;
+    r = (lane == 48) ? b47 : r;
+    return r;
+}
+
+// ---- scans across the 64 lanes of a wave; lane i holds element i.  Inside each 16-lane row by four shift-and-
+//      combine steps (the fill value is the identity of the combination, so no lane needs a select), then the
+//      rows are chained through three scalar broadcasts.  (The lane index is a parameter so that a caller with
+//      a long-running loop can pass its own, loop-variant copy.)
+
+// inclusive prefix product
+__device__ __forceinline__ float scan_prod(float v, int lane = lane_id()) {
+    v *= row_up<1>(v, 1.f);
+    v *= row_up<2>(v, 1.f);
+    v *= row_up<4>(v, 1.f);
+    v *= row_up<8>(v, 1.f);
+#pragma unroll
+    for (int row = 1; row < 4; ++row) {
+        const float p = lane_bcast(v, 16 * row - 1); // product up to the end of the row before
+        if ((lane >> 4) == row) v *= p;
+    }
+    return v;
+}
+
+// x_i = c_i x_{i-1} + d_i with x_{-1} = 0: on return d holds x_i (c is used up)
+__device__ __forceinline__ void scan_affine_fwd(float &c, float &d, int lane = lane_id()) {
+#define MDN_STEP(N)                                                   \
+    {                                                                 \
+        const float oc = row_up<N>(c, 1.f), od = row_up<N>(d, 0.f);   \
+        d = c * od + d;                                               \
+        c = c * oc;                                                   \
+    }
+    MDN_STEP(1) MDN_STEP(2) MDN_STEP(4) MDN_STEP(8)
+#undef MDN_STEP
+#pragma unroll
+    for (int row = 1; row < 4; ++row) {
+        const float x = lane_bcast(d, 16 * row - 1); // x at the end of the row before
+        if ((lane >> 4) == row) d = c * x + d;
+    }
+}
+
+// x_i = c_i x_{i+1} + d_i with x_64 = 0: on return d holds x_i (c is used up)
+__device__ __forceinline__ void scan_affine_rev(float &c, float &d, int lane = lane_id()) {
+#define MDN_STEP(N)                                                       \
+    {                                                                     \
+        const float oc = row_down<N>(c, 1.f), od = row_down<N>(d, 0.f);   \
+        d = c * od + d;                                                   \
+        c = c * oc;                                                       \
+    }
+    MDN_STEP(1) MDN_STEP(2) MDN_STEP(4) MDN_STEP(8)
+#undef MDN_STEP
+#pragma unroll
+    for (int row = 2; row >= 0; --row) {
+        const float x = lane_bcast(d, 16 * (row + 1)); // x at the start of the row after
+        if ((lane >> 4) == row) d = c * x + d;
+    }
 }
 
 // ---- column scans of the 64x64 coefficient matrices; one wave, lane j owns column j and also HOLDS
@@ -85,18 +131,19 @@ __device__ __forceinline__ void coef_column_scan_blocked(float al, float be, flo
                                                          int w, float &gC, float &rC, int j = lane_id()) {
     const int jl = j & 15;
     // inclusive suffix products inside the 16-lane segment: (A, B, M)_j = T_end o ... o T_j
+    // ((A2, B2, M2) o (A, B, M): this lane's map first, the later rows' after it; the fill is the identity map)
     float A = al, B = be * mu, M = mu;
-#pragma unroll
-    for (int dlt = 1; dlt < 16; dlt <<= 1) {
-        const float A2 = __shfl_down(A, dlt, 16), B2 = __shfl_down(B, dlt, 16), M2 = __shfl_down(M, dlt, 16);
-        if (jl + dlt < 16) { // (A2, B2, M2) o (A, B, M): this lane's map first, the later rows' after it
-            B = A2 * B + B2 * M;
-            A = A2 * A;
-            M = M2 * M;
-        }
+#define MDN_STEP(N)                                                                                  \
+    {                                                                                                \
+        const float A2 = row_down<N>(A, 1.f), B2 = row_down<N>(B, 0.f), M2 = row_down<N>(M, 1.f);    \
+        B = A2 * B + B2 * M;                                                                         \
+        A = A2 * A;                                                                                  \
+        M = M2 * M;                                                                                  \
     }
+    MDN_STEP(1) MDN_STEP(2) MDN_STEP(4) MDN_STEP(8)
+#undef MDN_STEP
     // exclusive: product of T_{j+1} .. T_end (identity for the last lane of a segment)
-    const float Ax = __shfl_down(A, 1, 16), Bx = __shfl_down(B, 1, 16), Mx = __shfl_down(M, 1, 16);
+    const float Ax = row_down<1>(A, 1.f), Bx = row_down<1>(B, 0.f), Mx = row_down<1>(M, 1.f);
     // state of column j in the last row of its own segment
     float g = (jl < 15) ? Ax * be + Bx : be, rho = (jl < 15) ? Mx : 1.f;
     // on through whole segments up to row 16w - 1 (columns of segment J < I pass through segment I)
@@ -177,27 +224,25 @@ struct RevScanRows {
 };
 // sRowC: [3][64] floats (gc, ec, mc of every row); called by one whole wave, lane = row
 __device__ __forceinline__ void coef_scan_reverse_rowcoefs(float al, float be, float mu, float *sRowC, int lane = lane_id()) {
-    const int jl = lane & 15;
-    const float an = __shfl_down(al, 1), mn = __shfl_down(mu, 1);
-    float gc = lane < 63 ? an : 0.f, mc = lane < 63 ? mn : 0.f; // alpha_{i+1}, mu_{i+1}
+    float gc = wave_down1(al, 0.f, lane), mc = wave_down1(mu, 0.f, lane); // alpha_{i+1}, mu_{i+1}; nothing below row 63
     const float y = mc;
-#pragma unroll
-    for (int dlt = 1; dlt < 16; dlt <<= 1) { // inclusive suffix products inside the segment
-        const float og = __shfl_down(gc, dlt, 16), om = __shfl_down(mc, dlt, 16);
-        if (jl + dlt < 16) {
-            gc *= og;
-            mc *= om;
-        }
+    // inclusive suffix products inside the segment
+#define MDN_STEP(N)                   \
+    {                                 \
+        gc *= row_down<N>(gc, 1.f);   \
+        mc *= row_down<N>(mc, 1.f);   \
     }
+    MDN_STEP(1) MDN_STEP(2) MDN_STEP(4) MDN_STEP(8)
+#undef MDN_STEP
     float c = y, ec = be * gc; // ec_i = y_i ec_{i+1} + beta_i gc_i
-#pragma unroll
-    for (int dlt = 1; dlt < 16; dlt <<= 1) {
-        const float oc = __shfl_down(c, dlt, 16), od = __shfl_down(ec, dlt, 16);
-        if (jl + dlt < 16) {
-            ec = c * od + ec;
-            c = c * oc;
-        }
+#define MDN_STEP(N)                                                        \
+    {                                                                      \
+        const float oc = row_down<N>(c, 1.f), od = row_down<N>(ec, 0.f);   \
+        ec = c * od + ec;                                                  \
+        c = c * oc;                                                        \
     }
+    MDN_STEP(1) MDN_STEP(2) MDN_STEP(4) MDN_STEP(8)
+#undef MDN_STEP
     sRowC[lane] = gc;
     sRowC[64 + lane] = ec;
     sRowC[128 + lane] = mc;

@@ -550,8 +550,8 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
         dalk = total(P_DALK);
         detk = total(P_DETK);
         const int li = lane;
-        const float al_next = __shfl_down(g_al, 1), mu_next = __shfl_down(g_mu, 1);
-        const float dbm_dn = __shfl_down(t_dbm, 1), dam_dn = __shfl_down(t_dam, 1);
+        const float al_next = wave_down1(g_al, 0.f, lane), mu_next = wave_down1(g_mu, 0.f, lane);
+        const float dbm_dn = wave_down1(t_dbm, 0.f, lane), dam_dn = wave_down1(t_dam, 0.f, lane);
         const float dbm_next = (li < 63) ? dbm_dn : -dS_M;
         const float dam_next = (li < 63) ? dam_dn : dS_S;
         float cb = (li < 63) ? al_next : 0.f;
@@ -596,7 +596,7 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     __syncthreads();
     if (w == 4) {
         const int li = lane;
-        const float aprev = __shfl_up(pa, 1), bprev = __shfl_up(pb, 1), mprev = __shfl_up(pm, 1);
+        const float aprev = wave_up1(pa, 1.f, lane), bprev = wave_up1(pb, 0.f, lane), mprev = wave_up1(pm, 1.f, lane);
         const float a_prev = (li > 0) ? aprev : 1.f, b_prev = (li > 0) ? bprev : 0.f, m_prev = (li > 0) ? mprev : 1.f;
         const unsigned g = (unsigned)(li * d.H);
         *at32(a.dalpha + tok0_cur, g) = s_ga[li] + db * b_prev + da * a_prev + dalk;

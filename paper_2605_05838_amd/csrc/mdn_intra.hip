@@ -130,7 +130,7 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
             s_b[lane] = pb;
             coef[COEF_A * 64 + lane] = pa;
             coef[COEF_B * 64 + lane] = pb;
-            coef[COEF_PB * 64 + lane] = al * __shfl_up(pb, 1) * (lane > 0 ? 1.f : 0.f); // alpha_i b_{i-1}, b_{-1} = 0
+            coef[COEF_PB * 64 + lane] = al * wave_up1(pb, 0.f, lane); // alpha_i b_{i-1}, b_{-1} = 0
             if (lane == 63) {
                 coef[COEF_SCALAR * 64 + 0] = pa;
                 coef[COEF_SCALAR * 64 + 1] = pb;
