@@ -135,6 +135,31 @@ int mdn_recurrent_step(const mdn_shape *shape, const void *q, const void *k, con
                        void *stream);
 
 /*
+ * Stability-aware gate parameterisation (Sec. 3.3, "Stability Aware Gating Parameterization"): from the four
+ * per-head projections of every token to the linear-domain gates that mdn_chunk_fwd / mdn_recurrent_step take,
+ *     eta   = tanh(x_eta / tau) + 1,    theta = arctan(eta s),   alpha_max = cos^2 theta,   beta_max = sin^2 theta,
+ *     alpha = alpha_max exp(-a_alpha[h] softplus(x_alpha + b_alpha[h])),
+ *     mu    = exp(max(-a_mu[h] softplus(x_mu + b_mu[h]), mu_log_min)),        beta = sigmoid(x_beta) beta_max.
+ * All tensors [B,T,H] fp32 contiguous on the device; a_alpha, b_alpha, a_mu, b_mu are device vectors of H floats
+ * (the caller's; a_* > 0); s, tau > 0 and mu_log_min (the paper's default -1) are host scalars.
+ * mdn_gates_bwd is the adjoint for L = <alpha,dalpha> + <beta,dbeta> + <mu,dmu> + <eta,deta> (the four gradients
+ * that mdn_chunk_bwd returns): dx_* [B,T,H], and dparams = [4][H] floats (da_alpha, db_alpha, da_mu, db_mu;
+ * overwritten; summed with floating-point atomics, so the last bits depend on the order) or NULL.
+ * Errors: MDN_ERR_NULL, MDN_ERR_SHAPE (sizes < 1, H > 1024, tau <= 0), MDN_ERR_LAUNCH.  Nothing is allocated.
+ */
+typedef struct mdn_gate_params {
+    int32_t B, T, H;
+    const float *a_alpha, *b_alpha, *a_mu, *b_mu; /* device, [H] each */
+    float s, tau, mu_log_min;
+} mdn_gate_params;
+
+int mdn_gates_fwd(const mdn_gate_params *params, const float *x_alpha, const float *x_mu, const float *x_beta,
+                  const float *x_eta, float *alpha, float *beta, float *mu, float *eta, void *stream);
+int mdn_gates_bwd(const mdn_gate_params *params, const float *x_alpha, const float *x_mu, const float *x_beta,
+                  const float *x_eta, const float *dalpha, const float *dbeta, const float *dmu, const float *deta,
+                  float *dx_alpha, float *dx_mu, float *dx_beta, float *dx_eta, float *dparams, void *stream);
+
+/*
  * Optional per-kernel timing (used by the benchmark to attribute time to kernels).
  * Between mdn_profile_begin() and mdn_profile_end() every kernel the library launches is
  * bracketed by a pair of HIP events recorded on the launch stream.  mdn_profile_end()

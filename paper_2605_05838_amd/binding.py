@@ -19,7 +19,8 @@ MDN_WS_FWD, MDN_WS_BWD = 0, 1
 
 EXPORTS = ("mdn_version", "mdn_strerror", "mdn_workspace_bytes", "mdn_saved_states_bytes",
            "mdn_saved_operands_bytes", "mdn_chunk_fwd",
-           "mdn_chunk_bwd", "mdn_recurrent_step", "mdn_profile_begin", "mdn_profile_end", "mdn_set_segments")
+           "mdn_chunk_bwd", "mdn_recurrent_step", "mdn_profile_begin", "mdn_profile_end", "mdn_set_segments",
+           "mdn_gates_fwd", "mdn_gates_bwd")
 
 KERNEL_NAMES = ("intra_fwd", "scan_fwd", "intra_bwd", "rebuild", "scan_bwd", "grad", "recurrent")
 
@@ -27,6 +28,12 @@ KERNEL_NAMES = ("intra_fwd", "scan_fwd", "intra_bwd", "rebuild", "scan_bwd", "gr
 class MdnShape(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("T", ctypes.c_int32), ("H", ctypes.c_int32), ("dk", ctypes.c_int32),
                 ("dv", ctypes.c_int32), ("C", ctypes.c_int32), ("dtype", ctypes.c_int32), ("scale", ctypes.c_float)]
+
+
+class MdnGateParams(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("T", ctypes.c_int32), ("H", ctypes.c_int32), ("a_alpha", ctypes.c_void_p),
+                ("b_alpha", ctypes.c_void_p), ("a_mu", ctypes.c_void_p), ("b_mu", ctypes.c_void_p),
+                ("s", ctypes.c_float), ("tau", ctypes.c_float), ("mu_log_min", ctypes.c_float)]
 
 
 class MdnError(RuntimeError):
@@ -66,6 +73,11 @@ def load_library():
     lib.mdn_profile_end.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int), ctypes.c_int]
     lib.mdn_set_segments.restype = ctypes.c_int
     lib.mdn_set_segments.argtypes = [ctypes.c_int]
+    gp = ctypes.POINTER(MdnGateParams)
+    lib.mdn_gates_fwd.restype = ctypes.c_int
+    lib.mdn_gates_fwd.argtypes = [gp] + [fp] * 8 + [vp]
+    lib.mdn_gates_bwd.restype = ctypes.c_int
+    lib.mdn_gates_bwd.argtypes = [gp] + [fp] * 13 + [vp]
     _lib = lib
     return lib
 
@@ -233,3 +245,40 @@ def profile_end():
     cnt = (ctypes.c_int * n)()
     _check(load_library().mdn_profile_end(ms, cnt, n), "mdn_profile_end")
     return {KERNEL_NAMES[i]: (float(ms[i]), int(cnt[i])) for i in range(n)}
+
+
+def _gate_params(x, a_alpha, b_alpha, a_mu, b_mu, s, tau, mu_log_min):
+    B, T, H = x.shape
+    for name, t in (("a_alpha", a_alpha), ("b_alpha", b_alpha), ("a_mu", a_mu), ("b_mu", b_mu)):
+        if t.shape != (H,):
+            raise MdnError(f"{name} must have shape [H]")
+    return MdnGateParams(B, T, H, _f32(a_alpha, "a_alpha").value, _f32(b_alpha, "b_alpha").value,
+                         _f32(a_mu, "a_mu").value, _f32(b_mu, "b_mu").value, float(s), float(tau), float(mu_log_min))
+
+
+def mdn_gates_fwd(x_alpha, x_mu, x_beta, x_eta, a_alpha, b_alpha, a_mu, b_mu, s, tau, mu_log_min=-1.0):
+    """Gate parameterisation: projections [B,T,H] fp32 -> dict(alpha, beta, mu, eta), each [B,T,H] fp32."""
+    lib = load_library()
+    p = _gate_params(x_alpha, a_alpha, b_alpha, a_mu, b_mu, s, tau, mu_log_min)
+    out = {k: torch.empty_like(x_alpha) for k in ("alpha", "beta", "mu", "eta")}
+    rc = lib.mdn_gates_fwd(ctypes.byref(p), _f32(x_alpha, "x_alpha"), _f32(x_mu, "x_mu"), _f32(x_beta, "x_beta"),
+                           _f32(x_eta, "x_eta"), _ptr(out["alpha"]), _ptr(out["beta"]), _ptr(out["mu"]), _ptr(out["eta"]),
+                           _stream())
+    _check(rc, "mdn_gates_fwd")
+    return out
+
+
+def mdn_gates_bwd(x_alpha, x_mu, x_beta, x_eta, a_alpha, b_alpha, a_mu, b_mu, s, tau, dalpha, dbeta, dmu, deta,
+                  mu_log_min=-1.0, want_dparams=True):
+    """Adjoint of mdn_gates_fwd: dict(dx_alpha, dx_mu, dx_beta, dx_eta [B,T,H]; dparams [4,H] = da_alpha, db_alpha,
+    da_mu, db_mu, or None)."""
+    lib = load_library()
+    p = _gate_params(x_alpha, a_alpha, b_alpha, a_mu, b_mu, s, tau, mu_log_min)
+    out = {k: torch.empty_like(x_alpha) for k in ("dx_alpha", "dx_mu", "dx_beta", "dx_eta")}
+    out["dparams"] = torch.empty((4, x_alpha.shape[2]), dtype=torch.float32, device=x_alpha.device) if want_dparams else None
+    rc = lib.mdn_gates_bwd(ctypes.byref(p), _f32(x_alpha, "x_alpha"), _f32(x_mu, "x_mu"), _f32(x_beta, "x_beta"),
+                           _f32(x_eta, "x_eta"), _f32(dalpha, "dalpha"), _f32(dbeta, "dbeta"), _f32(dmu, "dmu"),
+                           _f32(deta, "deta"), _ptr(out["dx_alpha"]), _ptr(out["dx_mu"]), _ptr(out["dx_beta"]),
+                           _ptr(out["dx_eta"]), _ptr(out["dparams"]), _stream())
+    _check(rc, "mdn_gates_bwd")
+    return out
