@@ -136,3 +136,27 @@ def test_backward_of_a_sequence_length_that_is_not_a_multiple_of_the_chunk_size(
     rng = np.random.default_rng(9)
     w.arrays["M0"] = (rng.standard_normal((2, 2, d, d)) * 0.2).astype(np.float32)
     check_bwd(w, final_adjoints=True, save_states=keep_states, save_operands=keep_operands)
+
+
+@pytest.mark.parametrize("T,nseg", [(2048 + 37, 4), (1024 + 63, 2)])
+def test_partial_last_chunk_together_with_segments_on_two_streams(T, nseg):
+    """The full chunks split into segments on two streams, the partial chunk after them (before them in the reverse
+    pass): same results as the oracle, and as the unsplit call bit for bit."""
+    w = synth.custom(B=1, T=T, H=2, dk=64, dv=64, dtype="bf16", seed=47, with_eta=True, s0_std=0.2, backward=True)
+    t = to_dev(w)
+    prev = binding.set_segments(1)
+    try:
+        f1, g1 = run_fwd_bwd(w, t, save_states=True, save_operands=True)
+        binding.set_segments(nseg)
+        f2, g2 = run_fwd_bwd(w, t, save_states=True, save_operands=True)
+    finally:
+        binding.set_segments(prev)
+    for k in ("o", "S", "M", "vt"):
+        assert torch.equal(f1[k], f2[k]), k
+    for k in GRADS:
+        assert torch.equal(g1[k], g2[k]), k
+    a = {k: (None if v is None else v.astype(np.float64)) for k, v in w.arrays.items()}
+    ref = orc.backward(a["q"], a["k"], a["v"], a["alpha"], a["beta"], a["mu"], a["dO"], eta=a["eta"], S0=a["S0"],
+                       M0=a["M0"], scale=w.scale)
+    for name in GRADS:
+        assert rel_err(host(g2[name]), ref[name]) <= TOL["bf16"], name

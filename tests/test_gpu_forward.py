@@ -124,3 +124,9 @@ def test_sequence_length_that_is_not_a_multiple_of_the_chunk_size(dtype, d, T):
     rng = np.random.default_rng(8)
     w.arrays["M0"] = (rng.standard_normal((2, 3, d, d)) * 0.2).astype(np.float32)
     check_fwd(w)
+
+
+@pytest.mark.parametrize("T", [63, 65, 127, 129])
+def test_lengths_around_the_chunk_boundaries(T):
+    w = synth.custom(B=1, T=T, H=2, dk=64, dv=64, dtype="f32", seed=53, with_eta=True, s0_std=0.3)
+    check_fwd(w)
