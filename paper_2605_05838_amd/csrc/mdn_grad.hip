@@ -289,6 +289,7 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     }
     Frag fS[KSV], fM[KSV], fdS[KSV], fdM[KSV];
     load_state(fS, Sg);
+    if (DEEP) load_state(fM, Mg);
     sched_fence();
 
     // ---------------- phase A: the four 64x64 products (transposed: rows j, column i) and the
@@ -388,8 +389,7 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
         sched_fence(); // q, k rows are needed first: keep them ahead of the state tiles in the return order
     }
     if (DEEP) {
-        load_state(fdS, dSg);
-        load_state(fM, Mg); // dM' follows once S is no longer needed
+        load_state(fdS, dSg); // dM' follows once S is no longer needed
     }
     sched_fence(); // these loads leave now, not after the products below
     // ---------------- phase B: the token-contractions W1 K~, W2 K~, W1^T Q~, W2^T P
