@@ -160,6 +160,29 @@ int mdn_gates_bwd(const mdn_gate_params *params, const float *x_alpha, const flo
                   float *dx_alpha, float *dx_mu, float *dx_beta, float *dx_eta, float *dparams, void *stream);
 
 /*
+ * The elementwise operations around the delta rule in the MDN layer (Sec. 3.3, architecture paragraph) and their
+ * adjoints.  shape gives B, T, H, dk = dv in {64, 128} and the storage dtype of the [B,T,H,d] tensors (C and scale
+ * are not used); parameter vectors are device fp32; eps is the constant under the square roots.
+ *   front end, on the short-convolution outputs x_q, x_k [B,T,H,dk], x_v [B,T,H,dv], with d [H]:
+ *       q = L2Norm(SiLU(x_q) - d_h SiLU(x_k))   (output correction, applied before the normalisation),
+ *       k = L2Norm(SiLU(x_k)),   v = SiLU(x_v),   L2Norm(x) = x / sqrt(sum x^2 + eps);
+ *     mdn_frontend_bwd: dq, dk, dv -> dx_q, dx_k, dx_v and dd [H] (overwritten; NULL = not wanted).
+ *   back end, on the output o of the delta rule and the gate projection g, both [B,T,H,dv], with w [dv]:
+ *       y = sigmoid(g) * w * o / sqrt(mean(o^2) + eps)   (head-wise RMS norm, data-dependent output gate);
+ *     mdn_epilogue_bwd: dy -> d_o, dg and dw [dv] (overwritten; NULL = not wanted).
+ * Parameter gradients are summed with floating-point atomics (last bits depend on the order).  Nothing is allocated.
+ * Errors: MDN_ERR_NULL, MDN_ERR_SHAPE, MDN_ERR_DTYPE, MDN_ERR_LAUNCH.
+ */
+int mdn_frontend_fwd(const mdn_shape *shape, const void *x_q, const void *x_k, const void *x_v, const float *d, float eps,
+                     void *q, void *k, void *v, void *stream);
+int mdn_frontend_bwd(const mdn_shape *shape, const void *x_q, const void *x_k, const void *x_v, const float *d, float eps,
+                     const void *dq, const void *dk, const void *dv, void *dx_q, void *dx_k, void *dx_v, float *dd,
+                     void *stream);
+int mdn_epilogue_fwd(const mdn_shape *shape, const void *o, const void *g, const float *w, float eps, void *y, void *stream);
+int mdn_epilogue_bwd(const mdn_shape *shape, const void *o, const void *g, const float *w, float eps, const void *dy,
+                     void *d_o, void *dg, float *dw, void *stream);
+
+/*
  * Optional per-kernel timing (used by the benchmark to attribute time to kernels).
  * Between mdn_profile_begin() and mdn_profile_end() every kernel the library launches is
  * bracketed by a pair of HIP events recorded on the launch stream.  mdn_profile_end()

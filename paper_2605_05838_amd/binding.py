@@ -20,7 +20,8 @@ MDN_WS_FWD, MDN_WS_BWD = 0, 1
 EXPORTS = ("mdn_version", "mdn_strerror", "mdn_workspace_bytes", "mdn_saved_states_bytes",
            "mdn_saved_operands_bytes", "mdn_chunk_fwd",
            "mdn_chunk_bwd", "mdn_recurrent_step", "mdn_profile_begin", "mdn_profile_end", "mdn_set_segments",
-           "mdn_gates_fwd", "mdn_gates_bwd")
+           "mdn_gates_fwd", "mdn_gates_bwd", "mdn_frontend_fwd", "mdn_frontend_bwd", "mdn_epilogue_fwd",
+           "mdn_epilogue_bwd")
 
 KERNEL_NAMES = ("intra_fwd", "scan_fwd", "intra_bwd", "rebuild", "scan_bwd", "grad", "recurrent")
 
@@ -78,6 +79,15 @@ def load_library():
     lib.mdn_gates_fwd.argtypes = [gp] + [fp] * 8 + [vp]
     lib.mdn_gates_bwd.restype = ctypes.c_int
     lib.mdn_gates_bwd.argtypes = [gp] + [fp] * 13 + [vp]
+    cf = ctypes.c_float
+    lib.mdn_frontend_fwd.restype = ctypes.c_int
+    lib.mdn_frontend_fwd.argtypes = [sp, vp, vp, vp, fp, cf, vp, vp, vp, vp]
+    lib.mdn_frontend_bwd.restype = ctypes.c_int
+    lib.mdn_frontend_bwd.argtypes = [sp, vp, vp, vp, fp, cf] + [vp] * 6 + [fp, vp]
+    lib.mdn_epilogue_fwd.restype = ctypes.c_int
+    lib.mdn_epilogue_fwd.argtypes = [sp, vp, vp, fp, cf, vp, vp]
+    lib.mdn_epilogue_bwd.restype = ctypes.c_int
+    lib.mdn_epilogue_bwd.argtypes = [sp, vp, vp, fp, cf, vp, vp, vp, fp, vp]
     _lib = lib
     return lib
 
@@ -281,4 +291,45 @@ def mdn_gates_bwd(x_alpha, x_mu, x_beta, x_eta, a_alpha, b_alpha, a_mu, b_mu, s,
                            _f32(deta, "deta"), _ptr(out["dx_alpha"]), _ptr(out["dx_mu"]), _ptr(out["dx_beta"]),
                            _ptr(out["dx_eta"]), _ptr(out["dparams"]), _stream())
     _check(rc, "mdn_gates_bwd")
+    return out
+
+
+def mdn_frontend_fwd(x_q, x_k, x_v, d, eps=1e-6):
+    """SiLU, output correction and L2 norms on the short-convolution outputs -> dict(q, k, v)."""
+    shape = make_shape(x_q, x_v, 1.0)
+    out = {"q": torch.empty_like(x_q), "k": torch.empty_like(x_k), "v": torch.empty_like(x_v)}
+    rc = load_library().mdn_frontend_fwd(ctypes.byref(shape), _ptr(x_q), _ptr(x_k), _ptr(x_v), _f32(d, "d"), float(eps),
+                                         _ptr(out["q"]), _ptr(out["k"]), _ptr(out["v"]), _stream())
+    _check(rc, "mdn_frontend_fwd")
+    return out
+
+
+def mdn_frontend_bwd(x_q, x_k, x_v, d, dq, dk, dv, eps=1e-6, want_dd=True):
+    shape = make_shape(x_q, x_v, 1.0)
+    out = {"dx_q": torch.empty_like(x_q), "dx_k": torch.empty_like(x_k), "dx_v": torch.empty_like(x_v),
+           "dd": torch.empty_like(d) if want_dd else None}
+    rc = load_library().mdn_frontend_bwd(ctypes.byref(shape), _ptr(x_q), _ptr(x_k), _ptr(x_v), _f32(d, "d"), float(eps),
+                                         _ptr(dq), _ptr(dk), _ptr(dv), _ptr(out["dx_q"]), _ptr(out["dx_k"]),
+                                         _ptr(out["dx_v"]), _ptr(out["dd"]), _stream())
+    _check(rc, "mdn_frontend_bwd")
+    return out
+
+
+def mdn_epilogue_fwd(o, g, w, eps=1e-6):
+    """Head-wise RMS norm with weight w [dv] times sigmoid(g) -> y."""
+    B, T, H, dv = o.shape
+    shape = MdnShape(B, T, H, dv, dv, 64, _dtype_code(o), 1.0)
+    y = torch.empty_like(o)
+    rc = load_library().mdn_epilogue_fwd(ctypes.byref(shape), _ptr(o), _ptr(g), _f32(w, "w"), float(eps), _ptr(y), _stream())
+    _check(rc, "mdn_epilogue_fwd")
+    return y
+
+
+def mdn_epilogue_bwd(o, g, w, dy, eps=1e-6, want_dw=True):
+    B, T, H, dv = o.shape
+    shape = MdnShape(B, T, H, dv, dv, 64, _dtype_code(o), 1.0)
+    out = {"do": torch.empty_like(o), "dg": torch.empty_like(g), "dw": torch.empty_like(w) if want_dw else None}
+    rc = load_library().mdn_epilogue_bwd(ctypes.byref(shape), _ptr(o), _ptr(g), _f32(w, "w"), float(eps), _ptr(dy),
+                                         _ptr(out["do"]), _ptr(out["dg"]), _ptr(out["dw"]), _stream())
+    _check(rc, "mdn_epilogue_bwd")
     return out
