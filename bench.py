@@ -27,9 +27,9 @@ def flops_per_tokhd(C, dk, dv):
     exploited), following the step list of the chunkwise algorithm."""
     tri = 2.0 * C * C / 3.0
     return {
-        "intra_fwd": 8 * C * dk + 2 * C * dv + tri,      # masked products, solve, U/Y/Z
+        "intra_fwd": 8 * C * dk + 2 * C * dv + tri,      # masked products, solve, T V / T diag(a^-) P / T diag(b^-) P of the paper's step list
         "scan_fwd": 12 * dk * dv + 2 * C * dv,           # V~, inter read-out, S'/M' update, intra output
-        "intra_bwd": 8 * C * dk + tri,                   # recomputed products, solve, Y/Z
+        "intra_bwd": 8 * C * dk + tri,                   # recomputed products, solve, the two P products
         "rebuild": 4 * dk * dv,                          # S'/M' update lines only
         "scan_bwd": 12 * dk * dv + 2 * C * dv,           # dV~, dS, dM
         "grad": 8 * C * dk + 6 * C * dv + 12 * dk * dv,  # chunk-parallel gradients

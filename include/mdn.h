@@ -191,7 +191,7 @@ int mdn_epilogue_bwd(const mdn_shape *shape, const void *o, const void *g, const
  * then releases the events.  Not thread-safe; meant for one benchmarking thread.
  */
 enum {
-    MDN_KERNEL_INTRA_FWD = 0, /* chunk-local coefficients, masked products, triangular solve, U/Y/Z
+    MDN_KERNEL_INTRA_FWD = 0, /* chunk-local coefficients, masked products, triangular solve
                                  (and the reverse pass's operands when operands_saved is given) */
     MDN_KERNEL_SCAN_FWD = 1,  /* sequential inter-chunk propagation of S and M, outputs */
     MDN_KERNEL_INTRA_BWD = 2, /* same as 0 in the operand layouts of the reverse pass */

@@ -17,22 +17,25 @@
 //   a_i = alpha_i a_{i-1}, m_i = mu_i m_{i-1}, Rho_ij = mu_i Rho_{i-1,j},
 //   b_i = alpha_i b_{i-1} + beta_i m_i, Gamma_ij = alpha_i Gamma_{i-1,j} + beta_i Rho_ij.
 //
-// One workgroup (8 waves) per (chunk, batch*head).  Every product is formed transposed (dk or j as the
-// MFMA row index, tokens as the column index), so an accumulator lane holds 4 consecutive dk of one
-// token: dq, dk leave as 8-byte stores and the row dots against q, k need two shuffles.
-//   * 64x64 products (phase A): wave = (token tile, half of the j tiles); A operands V~, K from LDS.
+// 16-bit storage ("staged"): one workgroup (8 waves) per CU walks its share of the (chunk, batch*head) pairs and
+// requests the next chunk's gates and token tiles during the coefficient phases of the current one; 32-bit storage:
+// one workgroup per chunk.  Every product is formed transposed (dk or j as the MFMA row index, tokens as the column
+// index), so an accumulator lane holds 4 consecutive dk of one token: dq, dk leave as 8-byte stores and the row
+// dots against q, k need two shuffles.
+//   * 64x64 products (phase A): wave = (token tile, half of the j tiles); operands V~, k, q, dO, dR from LDS.
 //   * everything with a dk row index (phases B-F): wave = (dk tile, token group).  Its A operands are
-//     the wave's own 16 rows of K^T, Q^T, S, M, dS', dM': nobody else needs them, so they go from HBM
-//     straight into fragment registers, all in flight long before their use (no LDS copy, no barrier
-//     between the four state products).  The B operands are token rows that every wave needs: W1, W2
-//     (built in phase A) and the natural-layout tiles of dO, dR, V~ in LDS.
-//   * the token tiles V~, k, dO, dR go HBM -> LDS without passing through registers (global_load_lds,
+//     the wave's own 16 rows of S, M, dS', dM' (nobody else needs them, so they go from HBM straight into
+//     fragment registers, in flight long before their use: no LDS copy, no barrier between the state products)
+//     and of K^T, Q^T (transposing LDS reads of the k, q tiles, taken while those tiles are still there).  The B
+//     operands are token rows that every wave needs: W1, W2 (built in phase A) and the natural-layout tiles of
+//     dO, dR, V~ in LDS.
+//   * the token tiles V~, k, q, dO, dR go HBM -> LDS without passing through registers (global_load_lds,
 //     16 bytes per lane into consecutive LDS slots).  Rows are stored unpadded; to keep the fragment
 //     reads (16 rows x one 16-byte piece) off each other's banks, piece c of row i sits at position
 //     c ^ (i mod 16): the permutation is applied on the global side, where each lane is free to fetch
-//     any address.
-// (fp32 storage does not fit the token tiles in LDS: it reads them from HBM/L2 with the same code, and
-// keeps only two state tiles in registers at a time.)
+//     any address.  The kernel asks HBM for no byte twice.
+// (fp32 storage does not fit the token tiles in LDS: it reads them, and K^T, Q^T, from HBM/L2 with the same code,
+// and keeps only two state tiles in registers at a time.)
 #include "mdn_coef.h"
 #include "mdn_device.h"
 #include "mdn_kernels.h"

@@ -12,7 +12,7 @@
 // Same decomposition as the forward scan: one workgroup per (batch*head, DVB dv-columns); every
 // product is formed transposed (dv = MFMA row index) so that an accumulator lane holds 4 consecutive
 // dv of one token or one dk row; dS'^T, dM'^T in fp32 accumulators (wave w owns dk columns
-// [w*dk/4, (w+1)*dk/4)), a storage-type copy [dv][dk | dk] in LDS as A operand; the per-token
+// [w*dk/4, (w+1)*dk/4)), a storage-type copy in LDS (rows dv, contraction index dk | dk: see ATile) as A operand; the per-token
 // scalings along the contraction index folded into the LDS copies of dO^T, so that the B operands
 // are raw rows of Q^T, K^T, Bm^T, T^T and K; all of a chunk's fragments, its dO tile and
 // coefficients are fetched into registers one chunk ahead.

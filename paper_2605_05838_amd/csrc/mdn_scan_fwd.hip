@@ -14,10 +14,10 @@
 // row index: an accumulator lane then holds 4 consecutive dv of one token (or of one dk row), which
 // is 8 contiguous bytes of V, V~, O and of the saved states in HBM.
 //   S^T, M^T live in fp32 accumulators (wave w owns dk columns [w*dk/4, (w+1)*dk/4)); a storage-type
-//   copy sits in LDS as [dv][dk | dk] and is the A operand of the dk-contractions of stage 1a
+//   copy sits in LDS (rows dv, contraction index dk | dk: see ATile) and is the A operand of the dk-contractions of stage 1a
 //   (wave w owns tokens 16w..16w+15): (K S)^T, (K M)^T and the two inter-chunk read-outs.
-//   R^T = (V - a.(K S) + pb.(K M))^T goes to LDS as [dv][token]; stage 1b contracts it over ALL tokens with
-//   the wave's rows of T: V~^T, which goes to LDS as [dv][token] in three scalings (raw, Gamma_C eta,
+//   R^T = (V - a.(K S) + pb.(K M))^T goes to LDS (rows dv, contraction index token); stage 1b contracts it over ALL
+//   tokens with the wave's rows of T: V~^T, which goes to LDS the same way in three scalings (raw, Gamma_C eta,
 //   -Rho_C eta): the A operand of the token-contractions of stage 2 (intra-chunk output, state update).
 //   Scalings along a contraction index are folded into those copies, so the B operands are raw rows of
 //   K, Q, T, Bm, K^T straight from HBM.
