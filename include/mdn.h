@@ -123,6 +123,27 @@ int mdn_chunk_bwd(const mdn_shape *shape, const void *q, const void *k, const vo
                   void *stream);
 
 /*
+ * Packed variable-length batches (Algorithm 1 is per sequence; a training batch usually packs several): the
+ * sequences lie one after another along T of [1, T, H, *] tensors, sequence i being the tokens
+ * [cu_seqlens[i], cu_seqlens[i+1]); cu_seqlens is a HOST array of n_seq + 1 increasing offsets with cu_seqlens[0] = 0
+ * and cu_seqlens[n_seq] = shape.T; shape.B must be 1.  States are [n_seq, H, dk, dv].  Any lengths >= 1.
+ * Each sequence runs by itself through the same kernels as mdn_chunk_fwd / mdn_chunk_bwd, one after the other on the
+ * stream (exact, but a batch of many short sequences does not fill the GPU); the backward reconstructs the states
+ * and recomputes the operands (no states_saved / operands_saved here).  workspace: mdn_workspace_bytes_varlen.
+ * Errors as for the fixed-length calls; MDN_ERR_SHAPE also for inconsistent cu_seqlens.
+ */
+int mdn_workspace_bytes_varlen(const mdn_shape *shape, const int32_t *cu_seqlens, int32_t n_seq, int which, size_t *bytes_out);
+int mdn_chunk_fwd_varlen(const mdn_shape *shape, const int32_t *cu_seqlens, int32_t n_seq, const void *q, const void *k,
+                         const void *v, const float *beta, const float *alpha, const float *mu, const float *eta,
+                         const float *S0, const float *M0, void *o, float *S_final, float *M_final, void *vt_saved,
+                         void *workspace, size_t workspace_bytes, void *stream);
+int mdn_chunk_bwd_varlen(const mdn_shape *shape, const int32_t *cu_seqlens, int32_t n_seq, const void *q, const void *k,
+                         const void *v, const float *beta, const float *alpha, const float *mu, const float *eta,
+                         const float *S0, const float *M0, const void *vt_saved, const void *dO, const float *dS_final,
+                         const float *dM_final, void *dq, void *dk, void *dv, float *dbeta, float *dalpha, float *dmu,
+                         float *deta, float *dS0, float *dM0, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Recurrent (decoding) form, Eq. Mt.recurrent / St.recurrent, Appendix E recurrent form:
  * advances S, M in place over the shape.T tokens given (usually T = 1) and writes o.
  *   in : q, k, v, beta, alpha, mu, eta as for mdn_chunk_fwd (T tokens);

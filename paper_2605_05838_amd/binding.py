@@ -21,7 +21,7 @@ EXPORTS = ("mdn_version", "mdn_strerror", "mdn_workspace_bytes", "mdn_saved_stat
            "mdn_saved_operands_bytes", "mdn_chunk_fwd",
            "mdn_chunk_bwd", "mdn_recurrent_step", "mdn_profile_begin", "mdn_profile_end", "mdn_set_segments",
            "mdn_gates_fwd", "mdn_gates_bwd", "mdn_frontend_fwd", "mdn_frontend_bwd", "mdn_epilogue_fwd",
-           "mdn_epilogue_bwd")
+           "mdn_epilogue_bwd", "mdn_workspace_bytes_varlen", "mdn_chunk_fwd_varlen", "mdn_chunk_bwd_varlen")
 
 KERNEL_NAMES = ("intra_fwd", "scan_fwd", "intra_bwd", "rebuild", "scan_bwd", "grad", "recurrent")
 
@@ -80,6 +80,14 @@ def load_library():
     lib.mdn_gates_bwd.restype = ctypes.c_int
     lib.mdn_gates_bwd.argtypes = [gp] + [fp] * 13 + [vp]
     cf = ctypes.c_float
+    ip = ctypes.POINTER(ctypes.c_int32)
+    lib.mdn_workspace_bytes_varlen.restype = ctypes.c_int
+    lib.mdn_workspace_bytes_varlen.argtypes = [sp, ip, ctypes.c_int32, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t)]
+    lib.mdn_chunk_fwd_varlen.restype = ctypes.c_int
+    lib.mdn_chunk_fwd_varlen.argtypes = [sp, ip, ctypes.c_int32] + [vp] * 3 + [fp] * 6 + [vp, fp, fp, vp, vp, ctypes.c_size_t, vp]
+    lib.mdn_chunk_bwd_varlen.restype = ctypes.c_int
+    lib.mdn_chunk_bwd_varlen.argtypes = [sp, ip, ctypes.c_int32] + [vp] * 3 + [fp] * 6 + [vp, vp] + [fp] * 2 + [vp] * 3 + \
+        [fp] * 6 + [vp, ctypes.c_size_t, vp]
     lib.mdn_frontend_fwd.restype = ctypes.c_int
     lib.mdn_frontend_fwd.argtypes = [sp, vp, vp, vp, fp, cf, vp, vp, vp, vp]
     lib.mdn_frontend_bwd.restype = ctypes.c_int
@@ -331,5 +339,60 @@ def mdn_epilogue_bwd(o, g, w, dy, eps=1e-6, want_dw=True):
     out = {"do": torch.empty_like(o), "dg": torch.empty_like(g), "dw": torch.empty_like(w) if want_dw else None}
     rc = load_library().mdn_epilogue_bwd(ctypes.byref(shape), _ptr(o), _ptr(g), _f32(w, "w"), float(eps), _ptr(dy),
                                          _ptr(out["do"]), _ptr(out["dg"]), _ptr(out["dw"]), _stream())
-    _check(rc, "mdn_epilogue_bwd")
+    _check(rc, "mdn_epilogue_bwd", "mdn_workspace_bytes_varlen", "mdn_chunk_fwd_varlen", "mdn_chunk_bwd_varlen")
+    return out
+
+
+def _cu(cu_seqlens):
+    cu = [int(x) for x in cu_seqlens]
+    return (ctypes.c_int32 * len(cu))(*cu), len(cu) - 1
+
+
+def _varlen_workspace(shape, cu, n, which, device):
+    need = ctypes.c_size_t(0)
+    _check(load_library().mdn_workspace_bytes_varlen(ctypes.byref(shape), cu, n, which, ctypes.byref(need)),
+           "mdn_workspace_bytes_varlen")
+    return torch.empty(max(need.value, 16), dtype=torch.uint8, device=device), need.value
+
+
+def mdn_chunk_fwd_varlen(q, k, v, beta, alpha, mu, cu_seqlens, eta=None, S0=None, M0=None, scale=None, save_vt=False):
+    """Packed variable-length forward: q, k, v [1, T, H, d], gates [1, T, H], cu_seqlens a host sequence of n + 1
+    offsets; states [n, H, dk, dv].  Returns dict(o, S, M, vt)."""
+    shape = make_shape(q, v, scale)
+    cu, n = _cu(cu_seqlens)
+    _, T, H, dk = q.shape
+    dv = v.shape[-1]
+    o = torch.empty_like(v)
+    S = torch.empty((n, H, dk, dv), dtype=torch.float32, device=q.device)
+    M = torch.empty_like(S)
+    vt = torch.empty_like(v) if save_vt else None
+    ws, nb = _varlen_workspace(shape, cu, n, MDN_WS_FWD, q.device)
+    rc = load_library().mdn_chunk_fwd_varlen(ctypes.byref(shape), cu, n, _ptr(q), _ptr(k), _ptr(v), _f32(beta, "beta"),
+                                             _f32(alpha, "alpha"), _f32(mu, "mu"), _f32(eta, "eta"), _f32(S0, "S0"),
+                                             _f32(M0, "M0"), _ptr(o), _ptr(S), _ptr(M), _ptr(vt), _ptr(ws), nb, _stream())
+    _check(rc, "mdn_chunk_fwd_varlen")
+    return {"o": o, "S": S, "M": M, "vt": vt}
+
+
+def mdn_chunk_bwd_varlen(q, k, v, beta, alpha, mu, vt, dO, cu_seqlens, eta=None, S0=None, M0=None, dS_final=None,
+                         dM_final=None, scale=None, want_deta=False):
+    """Packed variable-length backward.  Returns dict(dq, dk, dv, dbeta, dalpha, dmu, deta, dS0, dM0)."""
+    shape = make_shape(q, v, scale)
+    cu, n = _cu(cu_seqlens)
+    _, T, H, dk = q.shape
+    dv_ = v.shape[-1]
+    out = {"dq": torch.empty_like(q), "dk": torch.empty_like(k), "dv": torch.empty_like(v)}
+    for name in ("dbeta", "dalpha", "dmu"):
+        out[name] = torch.empty_like(beta)
+    out["deta"] = torch.empty_like(beta) if want_deta else None
+    out["dS0"] = torch.empty((n, H, dk, dv_), dtype=torch.float32, device=q.device)
+    out["dM0"] = torch.empty_like(out["dS0"])
+    ws, nb = _varlen_workspace(shape, cu, n, MDN_WS_BWD, q.device)
+    rc = load_library().mdn_chunk_bwd_varlen(ctypes.byref(shape), cu, n, _ptr(q), _ptr(k), _ptr(v), _f32(beta, "beta"),
+                                             _f32(alpha, "alpha"), _f32(mu, "mu"), _f32(eta, "eta"), _f32(S0, "S0"),
+                                             _f32(M0, "M0"), _ptr(vt), _ptr(dO), _f32(dS_final, "dS_final"),
+                                             _f32(dM_final, "dM_final"), _ptr(out["dq"]), _ptr(out["dk"]), _ptr(out["dv"]),
+                                             _ptr(out["dbeta"]), _ptr(out["dalpha"]), _ptr(out["dmu"]), _ptr(out["deta"]),
+                                             _ptr(out["dS0"]), _ptr(out["dM0"]), _ptr(ws), nb, _stream())
+    _check(rc, "mdn_chunk_bwd_varlen")
     return out

@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 #include <string.h>
+#include <type_traits>
 #include <vector>
 
 using namespace mdn;
@@ -379,6 +380,134 @@ size_t bwd_ws_total(const Dims &d, int r) {
     return carve_bwd(d, nullptr).total + carve_bwd(tail_dims(d), nullptr).total + carve_tail(d, true, nullptr).total;
 }
 
+// The forward over a sequence of any length: d.N full chunks and r = T % 64 tokens of a partial one.
+int fwd_any(const Dims &d, int r, FwdCall c, void *workspace, hipStream_t s) {
+    int rc;
+    const FwdWs w = carve_fwd(d, workspace);
+    if (r == 0) return run_fwd(d, c, w, s);
+
+    // full chunks on the caller's tensors, then the partial chunk on padded copies
+    const Dims dt = tail_dims(d);
+    const FwdWs wt = carve_fwd(dt, offset(workspace, w.total));
+    const TailBufs tb = carve_tail(d, false, offset(workspace, w.total + wt.total));
+    const size_t es = elem_size(d);
+    float *S_final = c.S_final, *M_final = c.M_final;
+    void *o = c.o;
+    if (d.N > 0) {
+        c.S_final = tb.S_mid;
+        c.M_final = tb.M_mid;
+        rc = run_fwd(d, c, w, s);
+        if (rc) return rc;
+    }
+    TailList in(d, r);
+    in.add(c.q, tb.q, d.dk * es);
+    in.add(c.k, tb.k, d.dk * es);
+    in.add(c.v, tb.v, d.dv * es);
+    in.add(c.beta, tb.beta, 4, 0.f);
+    in.add(c.alpha, tb.alpha, 4, 1.f);
+    in.add(c.mu, tb.mu, 4, 1.f);
+    in.add(c.eta, tb.eta, 4, 1.f);
+    rc = launch_status(launch_tail_copy(in.c, true, s));
+    if (rc) return rc;
+    FwdCall ct = {tb.q, tb.k, tb.v, tb.beta, tb.alpha, tb.mu, c.eta ? tb.eta : nullptr,
+                  d.N > 0 ? tb.S_mid : c.S0, d.N > 0 ? tb.M_mid : c.M0, tb.o, S_final, M_final,
+                  c.vt_saved ? tb.vt : nullptr, offset(c.states_saved, saved_states_part(d)),
+                  offset(c.operands_saved, carve_rev(d, nullptr).total)};
+    rc = run_fwd(dt, ct, wt, s);
+    if (rc) return rc;
+    TailList out(d, r);
+    out.add(o, tb.o, d.dv * es);
+    out.add(c.vt_saved, tb.vt, d.dv * es);
+    return launch_status(launch_tail_copy(out.c, false, s));
+}
+
+// The backward over a sequence of any length (see fwd_any).
+int bwd_any(const Dims &d, int r, BwdCall c, void *workspace, hipStream_t s) {
+    int rc;
+    const BwdCall u = c; // the caller's pointers (c is redirected for the full chunks below)
+    const BwdWs w = carve_bwd(d, workspace);
+    Prepared pm;
+    if (r == 0) {
+        rc = bwd_prepare(d, c, w, nullptr, nullptr, s, &pm);
+        return rc ? rc : bwd_run(d, c, w, pm, s);
+    }
+
+    // the partial chunk comes last in the sequence, so first in the reverse pass; what it needs from the full
+    // chunks (the states they leave) is ready after their preparation step
+    const Dims dt = tail_dims(d);
+    const BwdWs wt = carve_bwd(dt, offset(workspace, w.total));
+    const TailBufs tb = carve_tail(d, true, offset(workspace, w.total + wt.total));
+    const size_t es = elem_size(d);
+    if (d.N > 0) {
+        rc = bwd_prepare(d, c, w, tb.S_mid, tb.M_mid, s, &pm);
+        if (rc) return rc;
+    }
+    TailList in(d, r);
+    in.add(u.q, tb.q, d.dk * es);
+    in.add(u.k, tb.k, d.dk * es);
+    in.add(u.v, tb.v, d.dv * es);
+    in.add(u.vt_saved, tb.vt, d.dv * es);
+    in.add(u.dO, tb.dO, d.dv * es);
+    in.add(u.beta, tb.beta, 4, 0.f);
+    in.add(u.alpha, tb.alpha, 4, 1.f);
+    in.add(u.mu, tb.mu, 4, 1.f);
+    in.add(u.eta, tb.eta, 4, 1.f);
+    rc = launch_status(launch_tail_copy(in.c, true, s));
+    if (rc) return rc;
+    // (with states kept by the forward the partial chunk's start states are in their own part of that buffer;
+    //  otherwise they are reconstructed from what the full chunks leave)
+    BwdCall ct = {tb.q, tb.k, tb.v, tb.beta, tb.alpha, tb.mu, u.eta ? tb.eta : nullptr,
+                  d.N > 0 ? tb.S_mid : u.S0, d.N > 0 ? tb.M_mid : u.M0, tb.vt,
+                  offset(u.states_saved, saved_states_part(d)), offset(u.operands_saved, carve_rev(d, nullptr).total), tb.dO,
+                  u.dS_final, u.dM_final, tb.dq, tb.dk, tb.dv, tb.dbeta, tb.dalpha, tb.dmu, u.deta ? tb.deta : nullptr,
+                  d.N > 0 ? tb.dS_mid : u.dS0, d.N > 0 ? tb.dM_mid : u.dM0};
+    Prepared pt;
+    rc = bwd_prepare(dt, ct, wt, nullptr, nullptr, s, &pt);
+    if (rc) return rc;
+    rc = bwd_run(dt, ct, wt, pt, s);
+    if (rc) return rc;
+    if (d.N > 0) {
+        c.dS_final = tb.dS_mid;
+        c.dM_final = tb.dM_mid;
+        rc = bwd_run(d, c, w, pm, s);
+        if (rc) return rc;
+    }
+    TailList out(d, r);
+    out.add(u.dq, tb.dq, d.dk * es);
+    out.add(u.dk, tb.dk, d.dk * es);
+    out.add(u.dv, tb.dv, d.dv * es);
+    out.add(u.dbeta, tb.dbeta, 4);
+    out.add(u.dalpha, tb.dalpha, 4);
+    out.add(u.dmu, tb.dmu, 4);
+    out.add(u.deta, tb.deta, 4);
+    return launch_status(launch_tail_copy(out.c, false, s));
+}
+
+// ---- packed variable-length batches: the sequences lie one after another along T of a [1, T, H, *] tensor;
+// sequence i is tokens [cu[i], cu[i+1]).  Each sequence runs as a batch of one through the any-length path
+// (stream order makes the shared workspace safe).
+int check_varlen(const mdn_shape *shape, const int32_t *cu, int32_t n_seq, Dims *d) {
+    const int rc = check_shape(shape, true, d);
+    if (rc) return rc;
+    if (!cu) return MDN_ERR_NULL;
+    if (shape->B != 1 || n_seq < 1 || cu[0] != 0 || cu[n_seq] != shape->T) return MDN_ERR_SHAPE;
+    for (int i = 0; i < n_seq; ++i)
+        if (cu[i + 1] <= cu[i]) return MDN_ERR_SHAPE;
+    return MDN_OK;
+}
+
+Dims seq_dims(const Dims &all, int len) {
+    Dims d = all;
+    d.B = 1; d.T = len; d.N = len / 64; d.BH = all.H; d.n0 = 0; d.n1 = d.N;
+    return d;
+}
+
+template <typename P> P *at_token(P *base, size_t token, size_t bytes_per_token) {
+    return base ? reinterpret_cast<P *>(reinterpret_cast<char *>(const_cast<typename std::remove_const<P>::type *>(base)) +
+                                        token * bytes_per_token)
+                : nullptr;
+}
+
 } // namespace
 
 extern "C" {
@@ -474,40 +603,7 @@ int mdn_chunk_fwd(const mdn_shape *shape, const void *q, const void *k, const vo
     if (workspace_bytes < fwd_ws_total(d, r)) return MDN_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     FwdCall c = {q, k, v, beta, alpha, mu, eta, S0, M0, o, S_final, M_final, vt_saved, states_saved, operands_saved};
-    const FwdWs w = carve_fwd(d, workspace);
-    if (r == 0) return run_fwd(d, c, w, s);
-
-    // full chunks on the caller's tensors, then the partial chunk on padded copies
-    const Dims dt = tail_dims(d);
-    const FwdWs wt = carve_fwd(dt, offset(workspace, w.total));
-    const TailBufs tb = carve_tail(d, false, offset(workspace, w.total + wt.total));
-    const size_t es = elem_size(d);
-    if (d.N > 0) {
-        c.S_final = tb.S_mid;
-        c.M_final = tb.M_mid;
-        rc = run_fwd(d, c, w, s);
-        if (rc) return rc;
-    }
-    TailList in(d, r);
-    in.add(q, tb.q, d.dk * es);
-    in.add(k, tb.k, d.dk * es);
-    in.add(v, tb.v, d.dv * es);
-    in.add(beta, tb.beta, 4, 0.f);
-    in.add(alpha, tb.alpha, 4, 1.f);
-    in.add(mu, tb.mu, 4, 1.f);
-    in.add(eta, tb.eta, 4, 1.f);
-    rc = launch_status(launch_tail_copy(in.c, true, s));
-    if (rc) return rc;
-    FwdCall ct = {tb.q, tb.k, tb.v, tb.beta, tb.alpha, tb.mu, eta ? tb.eta : nullptr,
-                  d.N > 0 ? tb.S_mid : S0, d.N > 0 ? tb.M_mid : M0, tb.o, S_final, M_final,
-                  vt_saved ? tb.vt : nullptr, offset(states_saved, saved_states_part(d)),
-                  offset(operands_saved, carve_rev(d, nullptr).total)};
-    rc = run_fwd(dt, ct, wt, s);
-    if (rc) return rc;
-    TailList out(d, r);
-    out.add(o, tb.o, d.dv * es);
-    out.add(vt_saved, tb.vt, d.dv * es);
-    return launch_status(launch_tail_copy(out.c, false, s));
+    return fwd_any(d, r, c, workspace, s);
 }
 
 int mdn_chunk_bwd(const mdn_shape *shape, const void *q, const void *k, const void *v, const float *beta,
@@ -532,62 +628,92 @@ int mdn_chunk_bwd(const mdn_shape *shape, const void *q, const void *k, const vo
     hipStream_t s = static_cast<hipStream_t>(stream);
     BwdCall c = {q, k, v, beta, alpha, mu, eta, S0, M0, vt_saved, states_saved, operands_saved, dO, dS_final, dM_final,
                  dq, dk, dv, dbeta, dalpha, dmu, deta, dS0, dM0};
-    const BwdWs w = carve_bwd(d, workspace);
-    Prepared pm;
-    if (r == 0) {
-        rc = bwd_prepare(d, c, w, nullptr, nullptr, s, &pm);
-        return rc ? rc : bwd_run(d, c, w, pm, s);
-    }
+    return bwd_any(d, r, c, workspace, s);
+}
 
-    // the partial chunk comes last in the sequence, so first in the reverse pass; what it needs from the full
-    // chunks (the states they leave) is ready after their preparation step
-    const Dims dt = tail_dims(d);
-    const BwdWs wt = carve_bwd(dt, offset(workspace, w.total));
-    const TailBufs tb = carve_tail(d, true, offset(workspace, w.total + wt.total));
-    const size_t es = elem_size(d);
-    if (d.N > 0) {
-        rc = bwd_prepare(d, c, w, tb.S_mid, tb.M_mid, s, &pm);
+int mdn_workspace_bytes_varlen(const mdn_shape *shape, const int32_t *cu_seqlens, int32_t n_seq, int which, size_t *bytes_out) {
+    Dims d;
+    if (!bytes_out) return MDN_ERR_NULL;
+    const int rc = check_varlen(shape, cu_seqlens, n_seq, &d);
+    if (rc) return rc;
+    if (which != MDN_WS_FWD && which != MDN_WS_BWD) return MDN_ERR_SHAPE;
+    size_t need = 0;
+    for (int i = 0; i < n_seq; ++i) {
+        const int len = cu_seqlens[i + 1] - cu_seqlens[i];
+        const Dims ds = seq_dims(d, len);
+        const size_t b = which == MDN_WS_FWD ? fwd_ws_total(ds, len % 64) : bwd_ws_total(ds, len % 64);
+        need = b > need ? b : need;
+    }
+    *bytes_out = need;
+    return MDN_OK;
+}
+
+int mdn_chunk_fwd_varlen(const mdn_shape *shape, const int32_t *cu_seqlens, int32_t n_seq, const void *q, const void *k,
+                         const void *v, const float *beta, const float *alpha, const float *mu, const float *eta,
+                         const float *S0, const float *M0, void *o, float *S_final, float *M_final, void *vt_saved,
+                         void *workspace, size_t workspace_bytes, void *stream) {
+    Dims d;
+    int rc = check_varlen(shape, cu_seqlens, n_seq, &d);
+    if (rc) return rc;
+    if (!q || !k || !v || !beta || !alpha || !mu || !o || !workspace) return MDN_ERR_NULL;
+    const void *ptrs[] = {q, k, v, beta, alpha, mu, eta, S0, M0, o, S_final, M_final, vt_saved, workspace};
+    for (const void *p : ptrs)
+        if (p && misaligned(p)) return MDN_ERR_ALIGN;
+    size_t need = 0;
+    rc = mdn_workspace_bytes_varlen(shape, cu_seqlens, n_seq, MDN_WS_FWD, &need);
+    if (rc) return rc;
+    if (workspace_bytes < need) return MDN_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t es = elem_size(d), rk = (size_t)d.H * d.dk * es, rv = (size_t)d.H * d.dv * es, rg = (size_t)d.H * 4;
+    const size_t st = (size_t)d.H * d.dk * d.dv * sizeof(float);
+    for (int i = 0; i < n_seq; ++i) {
+        const size_t t0 = (size_t)cu_seqlens[i];
+        const int len = cu_seqlens[i + 1] - cu_seqlens[i];
+        FwdCall c = {at_token(q, t0, rk), at_token(k, t0, rk), at_token(v, t0, rv), at_token(beta, t0, rg),
+                     at_token(alpha, t0, rg), at_token(mu, t0, rg), at_token(eta, t0, rg), at_token(S0, i, st),
+                     at_token(M0, i, st), at_token(o, t0, rv), at_token(S_final, i, st), at_token(M_final, i, st),
+                     at_token(vt_saved, t0, rv), nullptr, nullptr};
+        rc = fwd_any(seq_dims(d, len), len % 64, c, workspace, s);
         if (rc) return rc;
     }
-    TailList in(d, r);
-    in.add(q, tb.q, d.dk * es);
-    in.add(k, tb.k, d.dk * es);
-    in.add(v, tb.v, d.dv * es);
-    in.add(vt_saved, tb.vt, d.dv * es);
-    in.add(dO, tb.dO, d.dv * es);
-    in.add(beta, tb.beta, 4, 0.f);
-    in.add(alpha, tb.alpha, 4, 1.f);
-    in.add(mu, tb.mu, 4, 1.f);
-    in.add(eta, tb.eta, 4, 1.f);
-    rc = launch_status(launch_tail_copy(in.c, true, s));
+    return MDN_OK;
+}
+
+int mdn_chunk_bwd_varlen(const mdn_shape *shape, const int32_t *cu_seqlens, int32_t n_seq, const void *q, const void *k,
+                         const void *v, const float *beta, const float *alpha, const float *mu, const float *eta,
+                         const float *S0, const float *M0, const void *vt_saved, const void *dO, const float *dS_final,
+                         const float *dM_final, void *dq, void *dk, void *dv, float *dbeta, float *dalpha, float *dmu,
+                         float *deta, float *dS0, float *dM0, void *workspace, size_t workspace_bytes, void *stream) {
+    Dims d;
+    int rc = check_varlen(shape, cu_seqlens, n_seq, &d);
     if (rc) return rc;
-    // (with states kept by the forward the partial chunk's start states are in their own part of that buffer;
-    //  otherwise they are reconstructed from what the full chunks leave)
-    BwdCall ct = {tb.q, tb.k, tb.v, tb.beta, tb.alpha, tb.mu, eta ? tb.eta : nullptr,
-                  d.N > 0 ? tb.S_mid : S0, d.N > 0 ? tb.M_mid : M0, tb.vt,
-                  offset(states_saved, saved_states_part(d)), offset(operands_saved, carve_rev(d, nullptr).total), tb.dO,
-                  dS_final, dM_final, tb.dq, tb.dk, tb.dv, tb.dbeta, tb.dalpha, tb.dmu, deta ? tb.deta : nullptr,
-                  d.N > 0 ? tb.dS_mid : dS0, d.N > 0 ? tb.dM_mid : dM0};
-    Prepared pt;
-    rc = bwd_prepare(dt, ct, wt, nullptr, nullptr, s, &pt);
+    if (!q || !k || !v || !beta || !alpha || !mu || !vt_saved || !dO || !dq || !dk || !dv || !dbeta || !dalpha || !dmu ||
+        !workspace)
+        return MDN_ERR_NULL;
+    const void *ptrs[] = {q, k, v, beta, alpha, mu, eta, S0, M0, vt_saved, dO, dS_final, dM_final, dq, dk, dv, dbeta, dalpha,
+                          dmu, deta, dS0, dM0, workspace};
+    for (const void *p : ptrs)
+        if (p && misaligned(p)) return MDN_ERR_ALIGN;
+    size_t need = 0;
+    rc = mdn_workspace_bytes_varlen(shape, cu_seqlens, n_seq, MDN_WS_BWD, &need);
     if (rc) return rc;
-    rc = bwd_run(dt, ct, wt, pt, s);
-    if (rc) return rc;
-    if (d.N > 0) {
-        c.dS_final = tb.dS_mid;
-        c.dM_final = tb.dM_mid;
-        rc = bwd_run(d, c, w, pm, s);
+    if (workspace_bytes < need) return MDN_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t es = elem_size(d), rk = (size_t)d.H * d.dk * es, rv = (size_t)d.H * d.dv * es, rg = (size_t)d.H * 4;
+    const size_t st = (size_t)d.H * d.dk * d.dv * sizeof(float);
+    for (int i = 0; i < n_seq; ++i) {
+        const size_t t0 = (size_t)cu_seqlens[i];
+        const int len = cu_seqlens[i + 1] - cu_seqlens[i];
+        BwdCall c = {at_token(q, t0, rk), at_token(k, t0, rk), at_token(v, t0, rv), at_token(beta, t0, rg),
+                     at_token(alpha, t0, rg), at_token(mu, t0, rg), at_token(eta, t0, rg), at_token(S0, i, st),
+                     at_token(M0, i, st), at_token(vt_saved, t0, rv), nullptr, nullptr, at_token(dO, t0, rv),
+                     at_token(dS_final, i, st), at_token(dM_final, i, st), at_token(dq, t0, rk), at_token(dk, t0, rk),
+                     at_token(dv, t0, rv), at_token(dbeta, t0, rg), at_token(dalpha, t0, rg), at_token(dmu, t0, rg),
+                     at_token(deta, t0, rg), at_token(dS0, i, st), at_token(dM0, i, st)};
+        rc = bwd_any(seq_dims(d, len), len % 64, c, workspace, s);
         if (rc) return rc;
     }
-    TailList out(d, r);
-    out.add(dq, tb.dq, d.dk * es);
-    out.add(dk, tb.dk, d.dk * es);
-    out.add(dv, tb.dv, d.dv * es);
-    out.add(dbeta, tb.dbeta, 4);
-    out.add(dalpha, tb.dalpha, 4);
-    out.add(dmu, tb.dmu, 4);
-    out.add(deta, tb.deta, 4);
-    return launch_status(launch_tail_copy(out.c, false, s));
+    return MDN_OK;
 }
 
 int mdn_recurrent_step(const mdn_shape *shape, const void *q, const void *k, const void *v, const float *beta,

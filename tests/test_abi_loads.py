@@ -85,3 +85,18 @@ def test_cpu_tensors_are_refused():
     g = torch.zeros(1, 64, 1)
     with pytest.raises(binding.MdnError):
         binding.mdn_chunk_fwd(x, x, x, g, g, g)
+
+
+def test_varlen_workspace_query_validates_the_offsets():
+    lib = binding.load_library()
+    n = ctypes.c_size_t(0)
+    cu = lambda *v: (ctypes.c_int32 * len(v))(*v)
+    s1 = shape(B=1, T=300)
+    assert lib.mdn_workspace_bytes_varlen(ctypes.byref(s1), cu(0, 100, 300), 2, 0, ctypes.byref(n)) == 0 and n.value > 0
+    longest = n.value
+    assert lib.mdn_workspace_bytes_varlen(ctypes.byref(s1), cu(0, 150, 300), 2, 0, ctypes.byref(n)) == 0 and n.value < longest
+    assert lib.mdn_workspace_bytes_varlen(ctypes.byref(s1), cu(0, 100, 299), 2, 0, ctypes.byref(n)) == -2   # does not end at T
+    assert lib.mdn_workspace_bytes_varlen(ctypes.byref(s1), cu(0, 100, 100, 300), 3, 0, ctypes.byref(n)) == -2   # empty sequence
+    assert lib.mdn_workspace_bytes_varlen(ctypes.byref(s1), cu(1, 100, 300), 2, 0, ctypes.byref(n)) == -2   # does not start at 0
+    assert lib.mdn_workspace_bytes_varlen(ctypes.byref(shape(B=2, T=300)), cu(0, 100, 300), 2, 0, ctypes.byref(n)) == -2
+    assert lib.mdn_workspace_bytes_varlen(ctypes.byref(s1), None, 2, 0, ctypes.byref(n)) == -1
