@@ -339,7 +339,7 @@ def mdn_epilogue_bwd(o, g, w, dy, eps=1e-6, want_dw=True):
     out = {"do": torch.empty_like(o), "dg": torch.empty_like(g), "dw": torch.empty_like(w) if want_dw else None}
     rc = load_library().mdn_epilogue_bwd(ctypes.byref(shape), _ptr(o), _ptr(g), _f32(w, "w"), float(eps), _ptr(dy),
                                          _ptr(out["do"]), _ptr(out["dg"]), _ptr(out["dw"]), _stream())
-    _check(rc, "mdn_epilogue_bwd", "mdn_workspace_bytes_varlen", "mdn_chunk_fwd_varlen", "mdn_chunk_bwd_varlen")
+    _check(rc, "mdn_epilogue_bwd")
     return out
 
 

@@ -127,7 +127,8 @@ def test_split_into_segments_on_two_streams_equals_the_unsplit_call(dtype, d, T,
 
 @pytest.mark.parametrize("dtype,d,T,keep_states,keep_operands",
                          [("f32", 64, 200, False, False), ("bf16", 128, 200, True, True), ("f32", 128, 40, False, False),
-                          ("bf16", 64, 135, True, False), ("f32", 64, 200, False, True)])
+                          ("bf16", 64, 135, True, False), ("f32", 64, 200, False, True), ("bf16", 64, 40, True, True),
+                          ("f32", 64, 1, True, False)])
 def test_backward_of_a_sequence_length_that_is_not_a_multiple_of_the_chunk_size(dtype, d, T, keep_states, keep_operands):
     """All gradients of the T tokens given, with adjoints of the final states coming in, whether the forward kept
     its states / operands or the backward rebuilds them (the partial chunk goes first in the reverse pass and takes
