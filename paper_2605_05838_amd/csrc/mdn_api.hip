@@ -48,7 +48,7 @@ FwdWs carve_fwd(const Dims &d, void *ws) {
     const size_t es = d.dtype == MDN_DTYPE_F32 ? 4 : 2, nb = (size_t)d.BH * d.N;
     Carver c(ws);
     FwdWs w;
-    w.coef = static_cast<float *>(c.take(nb * (size_t)(6 * 64 * sizeof(float))));
+    w.coef = static_cast<float *>(c.take(nb * (size_t)(64 * kCoefBlockCols * sizeof(float))));
     w.KT = c.take(nb * d.dk * 64 * es);
     w.Tm = c.take(nb * 4096 * es);
     w.Bm = c.take(nb * 4096 * es);
@@ -67,7 +67,7 @@ RevOps carve_rev(const Dims &d, void *p) {
     const size_t es = d.dtype == MDN_DTYPE_F32 ? 4 : 2, nb = (size_t)d.BH * d.N;
     Carver c(p);
     RevOps w;
-    w.coef = static_cast<float *>(c.take(nb * (size_t)(6 * 64 * sizeof(float))));
+    w.coef = static_cast<float *>(c.take(nb * (size_t)(64 * kCoefBlockCols * sizeof(float))));
     w.KT = c.take(nb * d.dk * 64 * es);
     w.QT = c.take(nb * d.dk * 64 * es);
     w.BmT = c.take(nb * 4096 * es);
@@ -322,7 +322,7 @@ int bwd_prepare(const Dims &d, const BwdCall &c, const BwdWs &w, float *S_after,
     out->states = c.states_saved;
     if (!out->states) {
         RebuildArgs ra = {};
-        ra.coef = out->ro.coef; ra.KT = out->ro.KT; ra.vt_saved = c.vt_saved; ra.S0 = c.S0; ra.M0 = c.M0;
+        ra.coef = out->ro.coef; ra.k = c.k; ra.KT = out->ro.KT; ra.vt_saved = c.vt_saved; ra.S0 = c.S0; ra.M0 = c.M0;
         ra.states = w.states; ra.S_final = S_after; ra.M_final = M_after;
         rc = timed(MDN_KERNEL_REBUILD, s, [&] { return launch_rebuild(d, ra, s); });
         if (rc) return rc;

@@ -27,12 +27,13 @@ typedef __bf16 bf16_t;
 
 constexpr int kC = 64;        // chunk size
 constexpr int kThreads = 256; // 4 waves per workgroup
-constexpr int kCoefRows = 6;  // per-chunk coefficient block: [kCoefRows][64] floats
+constexpr int kCoefRows = 8;  // per-chunk coefficient block: [64 tokens][kCoefRows] floats (= kCoefBlockCols of mdn_kernels.h)
 
-// rows of the coefficient block
-enum { COEF_A = 0, COEF_B = 1, COEF_GC = 2, COEF_RC = 3, COEF_SCALAR = 4, COEF_PB = 5 };
-// COEF_SCALAR row: [0] = a_C, [1] = b_C, [2] = m_C;  COEF_PB row: alpha_i b_{i-1} (the scaling of Z; that of Y,
-// alpha_i a_{i-1}, is a_i itself)
+// the coefficients of token i of a chunk, as two 16-byte vectors {a_i, b_i, alpha_i b_{i-1}, a_C} and
+// {Gamma_C eta_i, Rho_C eta_i, b_C, m_C}: the chunk scalars a_C, b_C, m_C are repeated in every row, so that a
+// lane has everything about its token and its chunk after two loads (the scaling of Z is alpha_i b_{i-1}; that of
+// Y, alpha_i a_{i-1}, is a_i itself)
+enum { COEF_A = 0, COEF_B = 1, COEF_PB = 2, COEF_AC = 3, COEF_GC = 4, COEF_RC = 5, COEF_BC = 6, COEF_MC = 7 };
 
 template <typename T> struct Op;
 
@@ -123,6 +124,43 @@ __device__ __forceinline__ void store4_raw(float *p, f32x4 v) { *reinterpret_cas
 __device__ __forceinline__ f32x4 widen4(bf16x4 v) { return f32x4{(float)v[0], (float)v[1], (float)v[2], (float)v[3]}; }
 __device__ __forceinline__ f32x4 widen4(f32x4 v) { return v; }
 
+// A lane's MV accumulator vectors as MV*4 CONSECUTIVE storage elements at p (16-bit storage, MV = 2: one 16-byte
+// access instead of two of 8 bytes).  Which columns of a [.., dv] tensor a lane's accumulator rows stand for is
+// the kernel's choice when dv is a pure batch index of the computation; choosing them consecutive halves the
+// number of vector-memory instructions for everything that is exchanged in accumulator layout.
+template <int MV> __device__ __forceinline__ void load_cols_raw(const bf16_t *p, bf16x4 (&u)[MV]) {
+    if constexpr (MV == 2) {
+        const bf16x8 w = *reinterpret_cast<const bf16x8 *>(p);
+        u[0] = __builtin_shufflevector(w, w, 0, 1, 2, 3);
+        u[1] = __builtin_shufflevector(w, w, 4, 5, 6, 7);
+    } else {
+#pragma unroll
+        for (int mv = 0; mv < MV; ++mv) u[mv] = load4_raw(p + mv * 4);
+    }
+}
+template <int MV> __device__ __forceinline__ void load_cols_raw(const float *p, f32x4 (&u)[MV]) {
+#pragma unroll
+    for (int mv = 0; mv < MV; ++mv) u[mv] = load4_raw(p + mv * 4);
+}
+template <int MV> __device__ __forceinline__ void store_cols_raw(bf16_t *p, const bf16x4 (&u)[MV]) {
+    if constexpr (MV == 2) {
+        *reinterpret_cast<bf16x8 *>(p) = __builtin_shufflevector(u[0], u[1], 0, 1, 2, 3, 4, 5, 6, 7);
+    } else {
+#pragma unroll
+        for (int mv = 0; mv < MV; ++mv) store4_raw(p + mv * 4, u[mv]);
+    }
+}
+template <int MV> __device__ __forceinline__ void store_cols_raw(float *p, const f32x4 (&u)[MV]) {
+#pragma unroll
+    for (int mv = 0; mv < MV; ++mv) store4_raw(p + mv * 4, u[mv]);
+}
+template <typename T, int MV> __device__ __forceinline__ void store_cols(T *p, const f32x4 (&v)[MV]) {
+    typename Raw4<T>::type u[MV];
+#pragma unroll
+    for (int mv = 0; mv < MV; ++mv) u[mv] = narrow4<T>(v[mv]);
+    store_cols_raw<MV>(p, u);
+}
+
 // 16 bytes of storage elements
 template <typename T> struct Vec16 {
     T e[Op<T>::EPL];
@@ -185,6 +223,43 @@ template <int M, int K> struct ATile<bf16_t, M, K> {
         return tr_frag(t, LD, k0, mt * 16, r, kg);
     }
 };
+
+// one natural-layout [64][D] token tile, HBM -> LDS without registers: the 16-byte slot (row, position p)
+// receives piece p ^ (row & XM) of that row (XM = min(pieces per row, 16) - 1).  Issued by NW waves
+// (lw = 0 .. NW-1), each D / (EPL * NW) instructions of 64 consecutive slots (m0 = LDS address of the 64
+// slots; lane l fills slot l).
+// Written as inline assembly on purpose: the compiler then does not know of the transfer, and so neither makes
+// the issuing wave (nor, through its path-insensitive bookkeeping, any other wave) drain its whole load queue
+// at the next LDS instruction.  Waiting for the transfer is the caller's job (a vector-memory wait of the
+// issuing wave that covers it, before the barrier that publishes the tile); the compiler's own waits for loads
+// it knows of can only become longer through the extra entries in the queue, never shorter (loads return in
+// order).
+template <typename T, int D, int NW = 2>
+__device__ __forceinline__ void dma_token_tile(T *ldst, const T *src, unsigned rs, int lw, int lane) {
+    constexpr int E = Op<T>::EPL, CPR = D / E, XM = (CPR < 16 ? CPR : 16) - 1, NDMA = CPR / NW;
+#pragma unroll
+    for (int u = 0; u < NDMA; ++u) {
+        const int blk64 = u * NW + lw, sl = blk64 * 64 + lane, row = sl / CPR, pc = (sl % CPR) ^ (row & XM);
+        const T *g = at32(src, row * rs + pc * E);
+        const unsigned l = (unsigned)(size_t)((__attribute__((address_space(3))) T *)(ldst + blk64 * 64 * E));
+        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(l) : "memory", "m0");
+    }
+}
+// Fragments out of such a tile (bf16: the transposing read is a 16-bit instruction).
+//   row fragment: row `row`, elements 32 st + 8 kg .. + 7 (the tile as [row][k] operand)
+template <int D> __device__ __forceinline__ bf16x8 token_tile_row_frag(const bf16_t *tile, int row, int st, int kg) {
+    constexpr int CPR = D / 8, XM = (CPR < 16 ? CPR : 16) - 1;
+    return Op<bf16_t>::load(tile + row * D + (((st * 4 + kg) ^ (row & XM)) * 8));
+}
+//   column fragment: column 16 ct + r, rows 32 s + 8 kg .. + 7 (the transposed tile as [column][row] operand): two
+//   transposing reads; lane 4e + c of a 16-lane group addresses rows 32 s + 8 kg (+ 4) + e, columns 16 ct + 4c .. 4c+3
+template <int D> __device__ __forceinline__ bf16x8 token_tile_col_frag(const bf16_t *tile, int ct, int s, int r, int kg) {
+    constexpr int CPR = D / 8, XM = (CPR < 16 ? CPR : 16) - 1;
+    const int row = s * 32 + kg * 8 + (r >> 2), c = ct * 2 + ((r & 3) >> 1), sub = ((r & 3) * 4) & 7;
+    return tr_pair(tile + row * D + ((c ^ (row & XM)) * 8) + sub, tile + (row + 4) * D + ((c ^ ((row + 4) & XM)) * 8) + sub);
+}
+template <int D> __device__ __forceinline__ f32x4 token_tile_row_frag(const float *, int, int, int) { return f32x4{0.f, 0.f, 0.f, 0.f}; }
+template <int D> __device__ __forceinline__ f32x4 token_tile_col_frag(const float *, int, int, int, int) { return f32x4{0.f, 0.f, 0.f, 0.f}; }
 
 // Blocked layouts of the chunk-local tensors that the library itself produces and consumes.
 // kblk: a [R][K] MFMA operand (fragment = row, KSTEP consecutive k) is stored as [K/KSTEP][R][KSTEP],

@@ -64,26 +64,6 @@ __device__ __forceinline__ float coldot(f32x4 t, f32x4 xv) {
     return reduce_kg(t[0] * xv[0] + t[1] * xv[1] + t[2] * xv[2] + t[3] * xv[3]);
 }
 
-// one natural-layout [64][D] token tile, HBM -> LDS without registers: the 16-byte slot (row, position p)
-// receives piece p ^ (row & XM) of that row.  Issued by 2 waves (lw = 0, 1), NDMA instructions of 64
-// consecutive slots each (m0 = LDS address of the 64 slots; lane l fills slot l).
-// Written as inline assembly on purpose: the compiler then does not know of the transfer, and so neither makes
-// the issuing wave (nor, through its path-insensitive bookkeeping, any other wave) drain its whole load queue
-// at the next LDS instruction.  Waiting for the transfer is the caller's job (s_waitcnt vmcnt(0) by the
-// issuing waves before the barrier that publishes the tile); the compiler's own waits for loads it knows of
-// can only become longer through the extra entries in the queue, never shorter (loads return in order).
-template <typename T, int D>
-__device__ __forceinline__ void dma_token_tile(T *ldst, const T *src, unsigned rs, int lw, int lane) {
-    constexpr int E = Op<T>::EPL, CPR = D / E, XM = (CPR < 16 ? CPR : 16) - 1, NDMA = CPR / 2;
-#pragma unroll
-    for (int u = 0; u < NDMA; ++u) {
-        const int blk64 = u * 2 + lw, sl = blk64 * 64 + lane, row = sl / CPR, pc = (sl % CPR) ^ (row & XM);
-        const T *g = at32(src, row * rs + pc * E);
-        const unsigned l = (unsigned)(size_t)((__attribute__((address_space(3))) T *)(ldst + blk64 * 64 * E));
-        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(l) : "memory", "m0");
-    }
-}
-
 // keeps the compiler from moving instructions across this point (used to stop the fragment loads of
 // later contraction steps from piling up in registers)
 __device__ __forceinline__ void sched_fence() { __builtin_amdgcn_sched_barrier(0); }

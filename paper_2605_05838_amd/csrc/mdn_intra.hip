@@ -128,20 +128,17 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
             s_et[lane] = et;
             s_a[lane] = pa;
             s_b[lane] = pb;
-            coef[COEF_A * 64 + lane] = pa;
-            coef[COEF_B * 64 + lane] = pb;
-            coef[COEF_PB * 64 + lane] = al * wave_up1(pb, 0.f, lane); // alpha_i b_{i-1}, b_{-1} = 0
-            if (lane == 63) {
-                coef[COEF_SCALAR * 64 + 0] = pa;
-                coef[COEF_SCALAR * 64 + 1] = pb;
-                coef[COEF_SCALAR * 64 + 2] = pm;
-            }
+            // alpha_i b_{i-1} (b_{-1} = 0), and the chunk-end values a_C, b_C, m_C into every row
+            const f32x4 c0 = {pa, pb, al * wave_up1(pb, 0.f, lane), lane_value(pa, 63)};
+            *reinterpret_cast<f32x4 *>(coef + lane * kCoefRows + COEF_A) = c0;
+            coef[lane * kCoefRows + COEF_BC] = lane_value(pb, 63);
+            coef[lane * kCoefRows + COEF_MC] = lane_value(pm, 63);
         }
         float gC, rC;
         coef_column_scan_blocked<false>(al, be, mu, sG, nullptr, LDG, w, gC, rC);
         if (w == 3) {
-            coef[COEF_GC * 64 + lane] = gC * et;
-            coef[COEF_RC * 64 + lane] = rC * et;
+            coef[lane * kCoefRows + COEF_GC] = gC * et;
+            coef[lane * kCoefRows + COEF_RC] = rC * et;
         }
     }
     {

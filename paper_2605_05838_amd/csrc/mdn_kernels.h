@@ -17,10 +17,12 @@ struct Dims {
 // Chunk-parallel precompute ("intra") kernel arguments.  Workspace tensors are chunk-blocked,
 // [BH][N][tile], in the storage dtype unless noted; inside a tile, an MFMA operand [rows][k] is in
 // the kblk layout and a [rows][dv] tensor in the vblk layout of mdn_device.h.
+constexpr int kCoefBlockCols = 8; // floats per token in the coefficient block
+
 struct IntraArgs {
     const void *q, *k;                      // [B,T,H,dk]
     const float *alpha, *beta, *mu, *eta;   // [B,T,H]; eta may be null
-    float *coef;                            // [BH][N][6][64] fp32
+    float *coef;                            // [BH][N][64][kCoefBlockCols] fp32 (one row of coefficients per token)
     void *KT;                               // kblk [dk][64]   raw k, transposed
     // forward mode
     void *Tm;                               // kblk [64][64]   T = (I + A)^-1: row i, contraction index j
@@ -46,6 +48,7 @@ struct ScanFwdArgs {
 // State reconstruction from saved V~ (backward, when the forward did not keep the states).
 struct RebuildArgs {
     const float *coef;
+    const void *k;                          // [B,T,H,dk] (16-bit storage reads K^T out of the k rows)
     const void *KT;
     const void *vt_saved;                   // [B,T,H,dv]
     const float *S0, *M0;

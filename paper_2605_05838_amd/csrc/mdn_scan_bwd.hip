@@ -11,7 +11,8 @@
 // so the transposes of Y and Z are never stored or read: the raw K^T tile and two per-token scalings do.
 // Same decomposition as the forward scan: one workgroup per (batch*head, DVB dv-columns); every
 // product is formed transposed (dv = MFMA row index) so that an accumulator lane holds 4 consecutive
-// dv of one token or one dk row; dS'^T, dM'^T in fp32 accumulators (wave w owns dk columns
+// dv of one token or one dk row (row 4 kg + x of MFMA tile mv stands for column dv0 + kg*4*MV + 4 mv + x, so that a
+// lane's MV tiles are neighbours in HBM and go as one vector); dS'^T, dM'^T in fp32 accumulators (wave w owns dk columns
 // [w*dk/4, (w+1)*dk/4)), a storage-type copy in LDS (rows dv, contraction index dk | dk: see ATile) as A operand; the per-token
 // scalings along the contraction index folded into the LDS copies of dO^T, so that the B operands
 // are raw rows of Q^T, K^T, Bm^T, T^T and K; all of a chunk's fragments, its dO tile and
@@ -37,8 +38,7 @@ template <typename T, int DK, int MV> struct RevOps {
     // (kept exactly as loaded: arithmetic on a freshly loaded value would make the wave wait for it, and for
     //  every load issued before it, at fetch time instead of one chunk later)
     typename Raw4<T>::type dO[MV];     // dO[token i0 + r][4 consecutive dv], storage form
-    float sa, sb, gc, rc, pb;          // a_i, b_i, Gamma_C eta, Rho_C eta, alpha_i b_{i-1}
-    float sc;                          // lane & 3 = 0, 1, 2: a_C, b_C, m_C
+    f32x4 c0, c1;                      // the token's coefficient row (COEF_*)
 };
 
 // The operands of one chunk are requested in NPART portions spread over the work on the previous chunk: a
@@ -54,18 +54,12 @@ __device__ __forceinline__ void fetch_part(RevOps<T, DK, DVB / 16> &c, const Dim
     const size_t blk = (size_t)bh * d.N + n;
     const size_t tok = ((size_t)b * d.T + (size_t)n * 64 + i) * d.H + h;
     if (P == 0) {
-        const float *coef = a.coef + blk * (kCoefRows * 64);
-        c.sa = coef[COEF_A * 64 + i];
-        c.sb = coef[COEF_B * 64 + i];
-        c.gc = coef[COEF_GC * 64 + i];
-        c.rc = coef[COEF_RC * 64 + i];
-        c.pb = coef[COEF_PB * 64 + i];
-        // the three chunk scalars through the vector path as well: a scalar load would share its wait counter
-        // with the LDS reads and make the first of those wait for memory
-        c.sc = coef[COEF_SCALAR * 64 + (lane & 3)];
-        const T *og = static_cast<const T *>(a.dO) + tok * DV + dv0 + kg * 4;
-#pragma unroll
-        for (int mv = 0; mv < DVB / 16; ++mv) c.dO[mv] = load4_raw(og + mv * 16);
+        // (through the vector path on purpose: a scalar load would share its wait counter with the LDS reads and
+        //  make the first of those wait for memory)
+        const float *coef = a.coef + blk * (kCoefRows * 64) + i * kCoefRows;
+        c.c0 = *reinterpret_cast<const f32x4 *>(coef);
+        c.c1 = *reinterpret_cast<const f32x4 *>(coef + 4);
+        load_cols_raw<DVB / 16>(static_cast<const T *>(a.dO) + tok * DV + dv0 + kg * (DVB / 4), c.dO);
     }
     if (P == 1) {
         const T *kp = static_cast<const T *>(a.k) + tok * DK + kg * O::EPL;
@@ -132,7 +126,7 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
     for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
         for (int nd = 0; nd < ND; ++nd) {
-            const size_t g = ((size_t)bh * DK + (w * ND + nd) * 16 + r) * DV + dv0 + mv * 16 + kg * 4;
+            const size_t g = ((size_t)bh * DK + (w * ND + nd) * 16 + r) * DV + dv0 + kg * (4 * MV) + mv * 4;
             accS[mv][nd] = a.dS_final ? *reinterpret_cast<const f32x4 *>(a.dS_final + g) : f32x4{0.f, 0.f, 0.f, 0.f};
             accM[mv][nd] = a.dM_final ? *reinterpret_cast<const f32x4 *>(a.dM_final + g) : f32x4{0.f, 0.f, 0.f, 0.f};
         }
@@ -147,34 +141,31 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
         // kernel ~45 us whoever issues them and whenever: in one burst here, 208 us; spread over the step in 8
         // portions, 213 us.  All values are narrowed first, so that the stores leave back to back.)
         {
-            constexpr int NS = 2 * MV * ND;
-            typename Raw4<T>::type sv[NS];
+            typename Raw4<T>::type sv[2 * ND][MV];
             T *ds = static_cast<T *>(a.dstates) + blk * (2 * DK * DV);
 #pragma unroll
             for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
                 for (int nd = 0; nd < ND; ++nd) {
-                    const int dk = (w * ND + nd) * 16 + r, t = mv * ND + nd;
-                    sv[2 * t] = narrow4<T>(accS[mv][nd]);
-                    sv[2 * t + 1] = narrow4<T>(accM[mv][nd]);
+                    const int dk = (w * ND + nd) * 16 + r;
+                    sv[2 * nd][mv] = narrow4<T>(accS[mv][nd]);
+                    sv[2 * nd + 1][mv] = narrow4<T>(accM[mv][nd]);
                     TD::put4(sD, mv * 16 + kg * 4, dk, accS[mv][nd]);
                     TD::put4(sD, mv * 16 + kg * 4, DK + dk, accM[mv][nd]);
                 }
 #pragma unroll
-            for (int mv = 0; mv < MV; ++mv)
-#pragma unroll
-                for (int nd = 0; nd < ND; ++nd) {
-                    const size_t off = vblk(DK, (w * ND + nd) * 16 + r, dv0 + mv * 16 + kg * 4);
-                    store4_raw(ds + off, sv[2 * (mv * ND + nd)]);
-                    store4_raw(ds + DK * DV + off, sv[2 * (mv * ND + nd) + 1]);
-                }
+            for (int nd = 0; nd < ND; ++nd) {
+                const size_t off = vblk(DK, (w * ND + nd) * 16 + r, dv0 + kg * (4 * MV));
+                store_cols_raw<MV>(ds + off, sv[2 * nd]);
+                store_cols_raw<MV>(ds + DK * DV + off, sv[2 * nd + 1]);
+            }
         }
         fetch_part<T, DK, DV, DVB, 1>(nxt, d, a, bh, b, h, nn, dv0);
         // dO^T slice of this chunk in three scalings
 #pragma unroll
         for (int mv = 0; mv < MV; ++mv) {
             const f32x4 dOw = widen4(cur.dO[mv]);
-            const float sa = d.scale * cur.sa, sb = d.scale * cur.sb;
+            const float sa = d.scale * cur.c0[COEF_A], sb = d.scale * cur.c0[COEF_B];
             TV::put4(sO0, mv * 16 + kg * 4, i, dOw);
             TV::put4(sOa, mv * 16 + kg * 4, i, sa * dOw);
             TV::put4(sOb, mv * 16 + kg * 4, i, -sb * dOw);
@@ -202,7 +193,7 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
                 }
             fetch_part<T, DK, DV, DVB, 3>(nxt, d, a, bh, b, h, nn, dv0);
 #pragma unroll
-            for (int mv = 0; mv < MV; ++mv) TV::put4(sDV, mv * 16 + kg * 4, i, accD[mv] + cur.gc * x1[mv] - cur.rc * x2[mv]);
+            for (int mv = 0; mv < MV; ++mv) TV::put4(sDV, mv * 16 + kg * 4, i, accD[mv] + cur.c1[COEF_GC - 4] * x1[mv] - cur.c1[COEF_RC - 4] * x2[mv]);
         }
         __syncthreads();
 
@@ -218,19 +209,18 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
                     dR[mv] = O::mma(TV::frag(sDV, mv, s * O::KSTEP, r, kg), cur.tT[s], dR[mv]);
             fetch_part<T, DK, DV, DVB, 4>(nxt, d, a, bh, b, h, nn, dv0);
             const size_t tok = ((size_t)b * d.T + (size_t)n * 64 + i) * d.H + h;
-            T *dvg = static_cast<T *>(a.dv) + tok * DV + dv0 + kg * 4;
+            store_cols<T, MV>(static_cast<T *>(a.dv) + tok * DV + dv0 + kg * (4 * MV), dR);
 #pragma unroll
             for (int mv = 0; mv < MV; ++mv) {
-                store4(dvg + mv * 16, dR[mv]);
-                TV::put4(sRa, mv * 16 + kg * 4, i, -cur.sa * dR[mv]);
-                TV::put4(sRb, mv * 16 + kg * 4, i, cur.pb * dR[mv]);
+                TV::put4(sRa, mv * 16 + kg * 4, i, -cur.c0[COEF_A] * dR[mv]);
+                TV::put4(sRb, mv * 16 + kg * 4, i, cur.c0[COEF_PB] * dR[mv]);
             }
         }
         __syncthreads();
 
         // ---------------- stage 3: the adjoints of the chunk-START states
         {
-            const float aC = lane_value(cur.sc, 0), bC = lane_value(cur.sc, 1), mC = lane_value(cur.sc, 2);
+            const float aC = cur.c0[COEF_AC], bC = cur.c1[COEF_BC - 4], mC = cur.c1[COEF_MC - 4];
 #pragma unroll
             for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
@@ -275,7 +265,7 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
     for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
         for (int nd = 0; nd < ND; ++nd) {
-            const size_t g = ((size_t)bh * DK + (w * ND + nd) * 16 + r) * DV + dv0 + mv * 16 + kg * 4;
+            const size_t g = ((size_t)bh * DK + (w * ND + nd) * 16 + r) * DV + dv0 + kg * (4 * MV) + mv * 4;
             if (a.dS0) *reinterpret_cast<f32x4 *>(a.dS0 + g) = accS[mv][nd];
             if (a.dM0) *reinterpret_cast<f32x4 *>(a.dM0 + g) = accM[mv][nd];
         }

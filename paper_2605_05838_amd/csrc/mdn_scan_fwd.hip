@@ -12,7 +12,10 @@
 //
 // Inside a workgroup (4 waves) every product is formed TRANSPOSED, with the dv index as the MFMA
 // row index: an accumulator lane then holds 4 consecutive dv of one token (or of one dk row), which
-// is 8 contiguous bytes of V, V~, O and of the saved states in HBM.
+// is 8 contiguous bytes of V, V~, O and of the saved states in HBM.  Row m = 4 kg + x of MFMA tile mv stands
+// for column dv0 + kg*4*MV + 4 mv + x of the workgroup's DVB = 16 MV columns, so that the MV tiles of a lane
+// are neighbours in HBM and go as one vector (16-bit storage, MV = 2: 16 bytes); inside LDS the tiles keep
+// their own order (row mv*16 + m), which no one outside the workgroup sees.
 //   S^T, M^T live in fp32 accumulators (wave w owns dk columns [w*dk/4, (w+1)*dk/4)); a storage-type
 //   copy sits in LDS (rows dv, contraction index dk | dk: see ATile) and is the A operand of the dk-contractions of stage 1a
 //   (wave w owns tokens 16w..16w+15): (K S)^T, (K M)^T and the two inter-chunk read-outs.
@@ -33,32 +36,27 @@ namespace mdn {
 
 namespace {
 
+static_assert(kCoefRows == kCoefBlockCols, "device-side and host-side view of the coefficient block");
+
 // Operands of one chunk held by one lane.
 template <typename T, int DK, int MV> struct ChunkOps {
     typedef Op<T> O;
     static constexpr int KS = DK / O::KSTEP, KS2 = 64 / O::KSTEP, ND = DK / 64;
-    // (the per-token coefficients sit BETWEEN the fragment arrays on purpose: as neighbours the compiler reads
-    //  them back as one 16-byte vector, which keeps the whole operand set in scratch memory instead of registers)
-    typename O::Frag kr[KS];              // stage 1: rows (token i0 + r) of K
-    float sa;                             // a_i for token i0 + r
+    typename O::Frag kr[KS];              // stage 1: rows (token i0 + r) of K (32-bit storage)
     typename O::Frag q[KS];               // stage 1: rows of Q
-    float sb;                             // b_i
     typename O::Frag tm[KS2];             // stage 1: row i0 + r of T = (I + A)^-1
-    float gc;                             // Gamma_C eta
     typename O::Frag bm[KS2];             // stage 2: Bm row i0 + r
-    float rc;                             // Rho_C eta
-    typename O::Frag kt[ND][KS2];         // stage 2: K^T rows (dk) of this wave's state columns
-    float pb;                             // alpha_i b_{i-1}
+    typename O::Frag kt[ND][KS2];         // stage 2: K^T rows (dk) of this wave's state columns (32-bit storage)
     // (everything here is kept exactly as loaded: arithmetic on a freshly loaded value would make the wave wait
     //  for it, and for every load issued before it, at fetch time instead of one chunk later)
-    typename Raw4<T>::type u[MV];         // V[token i0 + r][4 consecutive dv] (V~ in reconstruction), storage form
-    float sc;                             // lane & 3 = 0, 1, 2: a_C, b_C, m_C
+    typename Raw4<T>::type u[MV];         // V[token i0 + r][4 MV consecutive dv] (V~ in reconstruction), storage form
+    f32x4 c0, c1;                         // the token's coefficient row (COEF_*)
 };
 
 // The operands of one chunk are requested in portions (P = 0..4) spread over the work on the previous
 // chunk: a wave that issues them all at once sits at the issue until the memory pipeline has taken them
 // (the time to move a chunk's operands into the CU), with its matrix work waiting behind.
-template <typename T, int DK, int DV, int DVB, bool REBUILD, bool NO_STAGE1, int P>
+template <typename T, int DK, int DV, int DVB, bool REBUILD, bool NO_STAGE1, int P, bool KTILE = false>
 __device__ __forceinline__ void fetch_part(ChunkOps<T, DK, DVB / 16> &c, const Dims &d, const ScanFwdArgs &a, int bh,
                                            int b, int h, int n, int dv0) {
     typedef Op<T> O;
@@ -67,28 +65,21 @@ __device__ __forceinline__ void fetch_part(ChunkOps<T, DK, DVB / 16> &c, const D
     const size_t blk = (size_t)bh * d.N + n;
     const size_t tok = ((size_t)b * d.T + (size_t)n * 64 + i) * d.H + h;
     if (P == 0) {
-        const float *coef = a.coef + blk * (kCoefRows * 64);
-        c.gc = coef[COEF_GC * 64 + i];
-        c.rc = coef[COEF_RC * 64 + i];
-        if (!REBUILD) {
-            c.sa = coef[COEF_A * 64 + i];
-            c.sb = coef[COEF_B * 64 + i];
-            c.pb = coef[COEF_PB * 64 + i];
-        }
-        // the three chunk scalars through the vector path as well: a scalar load would share its wait counter
-        // with the LDS reads and make the first of those wait for memory
-        c.sc = coef[COEF_SCALAR * 64 + (lane & 3)];
+        // (through the vector path on purpose: a scalar load would share its wait counter with the LDS reads and
+        //  make the first of those wait for memory)
+        const float *coef = a.coef + blk * (kCoefRows * 64) + i * kCoefRows;
+        c.c0 = *reinterpret_cast<const f32x4 *>(coef);
+        c.c1 = *reinterpret_cast<const f32x4 *>(coef + 4);
         // the forward reads V, the reconstruction the saved V~
-        const T *vs = static_cast<const T *>(REBUILD ? a.vt_saved : a.v) + tok * DV + dv0 + kg * 4;
-#pragma unroll
-        for (int mv = 0; mv < DVB / 16; ++mv) c.u[mv] = load4_raw(vs + mv * 16);
+        const T *vs = static_cast<const T *>(REBUILD ? a.vt_saved : a.v) + tok * DV + dv0 + kg * (DVB / 4);
+        load_cols_raw<DVB / 16>(vs, c.u);
     }
     if (P == 1 && !REBUILD) {
         const T *Qg = static_cast<const T *>(a.q) + tok * DK + kg * O::EPL;
 #pragma unroll
         for (int s = 0; s < CO::KS; ++s) c.q[s] = O::load(Qg + s * O::KSTEP);
     }
-    if (P == 2) {
+    if (P == 2 && !KTILE) {
         const T *KTg = static_cast<const T *>(a.KT) + blk * (DK * 64);
 #pragma unroll
         for (int nd = 0; nd < CO::ND; ++nd)
@@ -104,7 +95,7 @@ __device__ __forceinline__ void fetch_part(ChunkOps<T, DK, DVB / 16> &c, const D
             c.bm[s] = O::load(Bg + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL));
         }
     }
-    if (P == 4 && !REBUILD && !NO_STAGE1) {
+    if (P == 4 && !REBUILD && !NO_STAGE1 && !KTILE) {
         const T *Kg = static_cast<const T *>(a.k) + tok * DK + kg * O::EPL;
 #pragma unroll
         for (int s = 0; s < CO::KS; ++s) c.kr[s] = O::load(Kg + s * O::KSTEP);
@@ -112,14 +103,14 @@ __device__ __forceinline__ void fetch_part(ChunkOps<T, DK, DVB / 16> &c, const D
     __builtin_amdgcn_sched_barrier(0); // the portion leaves here, not where the scheduler would gather the loads
 }
 
-template <typename T, int DK, int DV, int DVB, bool REBUILD, bool NO_STAGE1 = false>
+template <typename T, int DK, int DV, int DVB, bool REBUILD, bool NO_STAGE1 = false, bool KTILE = false>
 __device__ __forceinline__ void fetch_chunk(ChunkOps<T, DK, DVB / 16> &c, const Dims &d, const ScanFwdArgs &a,
                                             int bh, int b, int h, int n, int dv0) {
-    fetch_part<T, DK, DV, DVB, REBUILD, NO_STAGE1, 0>(c, d, a, bh, b, h, n, dv0);
-    fetch_part<T, DK, DV, DVB, REBUILD, NO_STAGE1, 4>(c, d, a, bh, b, h, n, dv0);
-    fetch_part<T, DK, DV, DVB, REBUILD, NO_STAGE1, 1>(c, d, a, bh, b, h, n, dv0);
-    fetch_part<T, DK, DV, DVB, REBUILD, NO_STAGE1, 3>(c, d, a, bh, b, h, n, dv0);
-    fetch_part<T, DK, DV, DVB, REBUILD, NO_STAGE1, 2>(c, d, a, bh, b, h, n, dv0);
+    fetch_part<T, DK, DV, DVB, REBUILD, NO_STAGE1, 0, KTILE>(c, d, a, bh, b, h, n, dv0);
+    fetch_part<T, DK, DV, DVB, REBUILD, NO_STAGE1, 4, KTILE>(c, d, a, bh, b, h, n, dv0);
+    fetch_part<T, DK, DV, DVB, REBUILD, NO_STAGE1, 1, KTILE>(c, d, a, bh, b, h, n, dv0);
+    fetch_part<T, DK, DV, DVB, REBUILD, NO_STAGE1, 3, KTILE>(c, d, a, bh, b, h, n, dv0);
+    fetch_part<T, DK, DV, DVB, REBUILD, NO_STAGE1, 2, KTILE>(c, d, a, bh, b, h, n, dv0);
 }
 
 // accumulator element x of tile (mv, nd) of wave w is S[dk = (w*ND + nd)*16 + r][dv = mv*16 + kg*4 + x]
@@ -152,6 +143,10 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
     __shared__ __align__(16) T sV0[TV::SIZE];
     __shared__ __align__(16) T sVg[TV::SIZE];
     __shared__ __align__(16) T sVr[TV::SIZE];
+    // 16-bit storage: the chunk's k rows come into LDS once (three chunks in flight) and serve both as rows
+    // (stage 1) and, through transposing reads, as K^T (stage 2); fp32 reads the rows and the K^T tile from HBM
+    constexpr bool KTILE = sizeof(T) == 2 && !REBUILD;
+    __shared__ __align__(16) T sKr[KTILE ? 3 * 64 * DK : 8];
 
     int bh, blkv;
     xcd_map(blockIdx.x, G, bh, blkv);
@@ -159,53 +154,73 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
     const int b = bh / d.H, h = bh % d.H, dv0 = blkv * DVB;
     const int lane = lane_id(), w = wave_id(), r = lane & 15, kg = lane >> 4, i = w * 16 + r;
 
+    // k rows of chunk n into ring slot `slot`
+    auto request_k = [&](int n, int slot) {
+        if constexpr (KTILE) {
+            const T *kg0 = static_cast<const T *>(a.k) + (((size_t)b * d.T + (size_t)n * 64) * d.H + h) * DK;
+            dma_token_tile<T, DK, 4>(sKr + slot * (64 * DK), kg0, (unsigned)(d.H * DK), __builtin_amdgcn_readfirstlane(w), lane);
+        }
+    };
+    request_k(d.n0, 0);
+    request_k(d.n0 + 1 < d.n1 ? d.n0 + 1 : d.n0, 1);
+
     f32x4 accS[MV][ND], accM[MV][ND];
 #pragma unroll
     for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
         for (int nd = 0; nd < ND; ++nd) {
-            const size_t g = ((size_t)bh * DK + (w * ND + nd) * 16 + r) * DV + dv0 + mv * 16 + kg * 4;
+            const size_t g = ((size_t)bh * DK + (w * ND + nd) * 16 + r) * DV + dv0 + kg * (4 * MV) + mv * 4;
             accS[mv][nd] = a.S0 ? *reinterpret_cast<const f32x4 *>(a.S0 + g) : f32x4{0.f, 0.f, 0.f, 0.f};
             accM[mv][nd] = a.M0 ? *reinterpret_cast<const f32x4 *>(a.M0 + g) : f32x4{0.f, 0.f, 0.f, 0.f};
         }
     if (!REBUILD) publish_state<T, DK, MV>(sSt, accS, accM);
+    if (KTILE) __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): this wave's part of the first two k tiles has landed
     __syncthreads();
 
-    // one chunk: its operands are in `cur`; those of the next chunk go on their way into `nxt`, portion by portion
+    // one chunk: its operands are in `cur`; those of the next chunk go on their way into `nxt`, portion by portion.
+    // The k tile of chunk n+2 is requested first of all: every wave uses values it loads later in this step (the
+    // next chunk's V and q rows) during the next step, before that step's barriers, and loads return in order, so
+    // each wave's part of the tile has landed by then and the barriers publish it before chunk n+2 begins.
+    int slot = 0;
     auto step = [&](int n, const CO &cur, CO &nxt) {
         const size_t blk = (size_t)bh * d.N + n;
         const size_t tok = ((size_t)b * d.T + (size_t)n * 64 + i) * d.H + h;
         const int nn = (n + 1 < d.n1) ? n + 1 : n;
-        fetch_part<T, DK, DV, DVB, REBUILD, false, 0>(nxt, d, a, bh, b, h, nn, dv0);
+        const T *kc = sKr + slot * (64 * DK);
+        if (n + 2 < d.n1) request_k(n + 2, slot >= 1 ? slot - 1 : 2);
+        slot = slot == 2 ? 0 : slot + 1;
+        fetch_part<T, DK, DV, DVB, REBUILD, false, 0, KTILE>(nxt, d, a, bh, b, h, nn, dv0);
 
         // The chunk-start states leave for HBM out of a storage-type copy in registers: in one burst here in the
         // forward scan, in 8 portions spread over the step in the reconstruction, which does little else than
         // store (measured: forward 252 us burst / 256 us spread; reconstruction 127 us burst / 109 us spread).
         // What the stores cost the forward scan (~75 us) does not depend on which wave issues them or when.
-        constexpr int NS = 2 * MV * ND;
-        typename Raw4<T>::type sv[NS];
+        constexpr int NS = 2 * ND; // vector stores per lane: S and M, ND rows, MV * 4 consecutive columns each
+        typename Raw4<T>::type sv[NS][MV];
         T *st = static_cast<T *>(a.states_saved) + blk * (2 * DK * DV);
         if (a.states_saved) {
 #pragma unroll
-            for (int t = 0; t < MV * ND; ++t) {
-                sv[2 * t] = narrow4<T>(accS[t / ND][t % ND]);
-                sv[2 * t + 1] = narrow4<T>(accM[t / ND][t % ND]);
-            }
+            for (int nd = 0; nd < ND; ++nd)
+#pragma unroll
+                for (int mv = 0; mv < MV; ++mv) {
+                    sv[2 * nd][mv] = narrow4<T>(accS[mv][nd]);
+                    sv[2 * nd + 1][mv] = narrow4<T>(accM[mv][nd]);
+                }
         }
         auto emit_states = [&](auto PORTION) {
             if (!a.states_saved) return;
             static_for<NS>([&](auto IDX) {
-                constexpr int idx = decltype(IDX)::value, t = idx >> 1, mv = t / ND, nd = t % ND;
+                constexpr int idx = decltype(IDX)::value, nd = idx >> 1;
                 if ((REBUILD ? idx * 8 / NS : 0) == decltype(PORTION)::value) {
-                    const size_t off = vblk(DK, (w * ND + nd) * 16 + r, dv0 + mv * 16 + kg * 4);
-                    store4_raw(st + ((idx & 1) ? DK * DV : 0) + off, sv[idx]);
+                    const size_t off = vblk(DK, (w * ND + nd) * 16 + r, dv0 + kg * (4 * MV));
+                    store_cols_raw<MV>(st + ((idx & 1) ? DK * DV : 0) + off, sv[idx]);
                 }
             });
             __builtin_amdgcn_sched_barrier(0);
         };
         emit_states(std::integral_constant<int, 0>{});
 
-        fetch_part<T, DK, DV, DVB, REBUILD, false, 4>(nxt, d, a, bh, b, h, nn, dv0);
+        fetch_part<T, DK, DV, DVB, REBUILD, false, 4, KTILE>(nxt, d, a, bh, b, h, nn, dv0);
         emit_states(std::integral_constant<int, 1>{});
         // ---------------- stage 1: R^T = (V - a.(K S) + pb.(K M))^T and the inter-chunk read-outs for token i,
         //                  then V~^T = R^T T^T over all 64 tokens
@@ -222,17 +237,18 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
                 for (int mv = 0; mv < MV; ++mv) {
                     const typename O::Frag fs = TS::frag(sSt, mv, s * O::KSTEP, r, kg);
                     const typename O::Frag fm = TS::frag(sSt, mv, DK + s * O::KSTEP, r, kg);
-                    x1[mv] = O::mma(fs, cur.kr[s], x1[mv]);
+                    const typename O::Frag fk = KTILE ? token_tile_row_frag<DK>(kc, i, s, kg) : cur.kr[s];
+                    x1[mv] = O::mma(fs, fk, x1[mv]);
                     accOS[mv] = O::mma(fs, cur.q[s], accOS[mv]);
-                    x2[mv] = O::mma(fm, cur.kr[s], x2[mv]);
+                    x2[mv] = O::mma(fm, fk, x2[mv]);
                     accOM[mv] = O::mma(fm, cur.q[s], accOM[mv]);
                 }
             }
-            fetch_part<T, DK, DV, DVB, REBUILD, false, 1>(nxt, d, a, bh, b, h, nn, dv0);
+            fetch_part<T, DK, DV, DVB, REBUILD, false, 1, KTILE>(nxt, d, a, bh, b, h, nn, dv0);
 #pragma unroll
             for (int mv = 0; mv < MV; ++mv) {
-                accO[mv] = d.scale * (cur.sa * accOS[mv] - cur.sb * accOM[mv]);
-                TV::put4(sRt, mv * 16 + kg * 4, i, widen4(cur.u[mv]) - cur.sa * x1[mv] + cur.pb * x2[mv]);
+                accO[mv] = d.scale * (cur.c0[COEF_A] * accOS[mv] - cur.c0[COEF_B] * accOM[mv]);
+                TV::put4(sRt, mv * 16 + kg * 4, i, widen4(cur.u[mv]) - cur.c0[COEF_A] * x1[mv] + cur.c0[COEF_PB] * x2[mv]);
             }
             __syncthreads();
             f32x4 accV[MV];
@@ -247,9 +263,7 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
 #pragma unroll
                 for (int x = 0; x < 4; ++x) vt[mv][x] = rounded<T>(accV[mv][x]);
             if (a.vt_saved) {
-                T *vs = static_cast<T *>(a.vt_saved) + tok * DV + dv0 + kg * 4;
-#pragma unroll
-                for (int mv = 0; mv < MV; ++mv) store4(vs + mv * 16, vt[mv]);
+                store_cols<T, MV>(static_cast<T *>(a.vt_saved) + tok * DV + dv0 + kg * (4 * MV), vt);
             }
         } else {
 #pragma unroll
@@ -260,16 +274,16 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
 #pragma unroll
         for (int mv = 0; mv < MV; ++mv) {
             if (!REBUILD) TV::put4(sV0, mv * 16 + kg * 4, i, vt[mv]);
-            TV::put4(sVg, mv * 16 + kg * 4, i, cur.gc * vt[mv]);
-            TV::put4(sVr, mv * 16 + kg * 4, i, -cur.rc * vt[mv]);
+            TV::put4(sVg, mv * 16 + kg * 4, i, cur.c1[COEF_GC - 4] * vt[mv]);
+            TV::put4(sVr, mv * 16 + kg * 4, i, -cur.c1[COEF_RC - 4] * vt[mv]);
         }
         emit_states(std::integral_constant<int, 3>{});
         __syncthreads();
 
         // ---------------- stage 2: intra-chunk output and the state update
-        fetch_part<T, DK, DV, DVB, REBUILD, false, 2>(nxt, d, a, bh, b, h, nn, dv0);
+        fetch_part<T, DK, DV, DVB, REBUILD, false, 2, KTILE>(nxt, d, a, bh, b, h, nn, dv0);
         emit_states(std::integral_constant<int, 4>{});
-        const float aC = lane_value(cur.sc, 0), bC = lane_value(cur.sc, 1), mC = lane_value(cur.sc, 2);
+        const float aC = cur.c0[COEF_AC], bC = cur.c1[COEF_BC - 4], mC = cur.c1[COEF_MC - 4];
 #pragma unroll
         for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
@@ -285,21 +299,20 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
                 const typename O::Frag fr = TV::frag(sVr, mv, s * O::KSTEP, r, kg);
 #pragma unroll
                 for (int nd = 0; nd < ND; ++nd) {
-                    accS[mv][nd] = O::mma(fg, cur.kt[nd][s], accS[mv][nd]);
-                    accM[mv][nd] = O::mma(fr, cur.kt[nd][s], accM[mv][nd]);
+                    const typename O::Frag fkt = KTILE ? token_tile_col_frag<DK>(kc, w * ND + nd, s, r, kg) : cur.kt[nd][s];
+                    accS[mv][nd] = O::mma(fg, fkt, accS[mv][nd]);
+                    accM[mv][nd] = O::mma(fr, fkt, accM[mv][nd]);
                 }
                 if (!REBUILD) {
                     accO[mv] = O::mma(TV::frag(sV0, mv, s * O::KSTEP, r, kg), cur.bm[s], accO[mv]);
                 }
             }
         emit_states(std::integral_constant<int, 5>{});
-        fetch_part<T, DK, DV, DVB, REBUILD, false, 3>(nxt, d, a, bh, b, h, nn, dv0);
+        fetch_part<T, DK, DV, DVB, REBUILD, false, 3, KTILE>(nxt, d, a, bh, b, h, nn, dv0);
         emit_states(std::integral_constant<int, 6>{});
         if (!REBUILD) {
             publish_state<T, DK, MV>(sSt, accS, accM);
-            T *og = static_cast<T *>(a.o) + tok * DV + dv0 + kg * 4;
-#pragma unroll
-            for (int mv = 0; mv < MV; ++mv) store4(og + mv * 16, accO[mv]);
+            store_cols<T, MV>(static_cast<T *>(a.o) + tok * DV + dv0 + kg * (4 * MV), accO);
         }
         emit_states(std::integral_constant<int, 7>{});
         __syncthreads();
@@ -308,7 +321,7 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
     // register of the set that was just requested, i.e. wait for all of its loads
     {
         CO opsA, opsB;
-        fetch_chunk<T, DK, DV, DVB, REBUILD>(opsA, d, a, bh, b, h, d.n0, dv0);
+        fetch_chunk<T, DK, DV, DVB, REBUILD, false, KTILE>(opsA, d, a, bh, b, h, d.n0, dv0);
         int n = d.n0;
         for (; n + 1 < d.n1; n += 2) {
             step(n, opsA, opsB);
@@ -321,7 +334,7 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
     for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
         for (int nd = 0; nd < ND; ++nd) {
-            const size_t g = ((size_t)bh * DK + (w * ND + nd) * 16 + r) * DV + dv0 + mv * 16 + kg * 4;
+            const size_t g = ((size_t)bh * DK + (w * ND + nd) * 16 + r) * DV + dv0 + kg * (4 * MV) + mv * 4;
             if (a.S_final) *reinterpret_cast<f32x4 *>(a.S_final + g) = accS[mv][nd];
             if (a.M_final) *reinterpret_cast<f32x4 *>(a.M_final + g) = accM[mv][nd];
         }
@@ -393,7 +406,7 @@ __global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a)
     for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
         for (int nd = 0; nd < ND; ++nd) {
-            const size_t g = ((size_t)bh * DK + (w * ND + nd) * 16 + r) * DV + dv0 + mv * 16 + kg * 4;
+            const size_t g = ((size_t)bh * DK + (w * ND + nd) * 16 + r) * DV + dv0 + kg * (4 * MV) + mv * 4;
             accS[mv][nd] = a.S0 ? *reinterpret_cast<const f32x4 *>(a.S0 + g) : f32x4{0.f, 0.f, 0.f, 0.f};
             accM[mv][nd] = a.M0 ? *reinterpret_cast<const f32x4 *>(a.M0 + g) : f32x4{0.f, 0.f, 0.f, 0.f};
         }
@@ -430,8 +443,8 @@ __global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a)
         }
 #pragma unroll
         for (int mv = 0; mv < MV; ++mv) {
-            accO[mv] = d.scale * (cur.sa * accOS[mv] - cur.sb * accOM[mv]);
-            TV::put4(sRt, mv * 16 + kg * 4, i, widen4(cur.u[mv]) - cur.sa * x1[mv] + cur.pb * x2[mv]);
+            accO[mv] = d.scale * (cur.c0[COEF_A] * accOS[mv] - cur.c0[COEF_B] * accOM[mv]);
+            TV::put4(sRt, mv * 16 + kg * 4, i, widen4(cur.u[mv]) - cur.c0[COEF_A] * x1[mv] + cur.c0[COEF_PB] * x2[mv]);
         }
         __syncthreads(); // barrier 1 of the chunk (the loader waves count it too)
         {
@@ -448,21 +461,19 @@ __global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a)
                 for (int x = 0; x < 4; ++x) vt[mv][x] = rounded<T>(accV[mv][x]);
         }
         if (a.vt_saved) {
-            T *vs = static_cast<T *>(a.vt_saved) + tok * DV + dv0 + kg * 4;
-#pragma unroll
-            for (int mv = 0; mv < MV; ++mv) store4(vs + mv * 16, vt[mv]);
+            store_cols<T, MV>(static_cast<T *>(a.vt_saved) + tok * DV + dv0 + kg * (4 * MV), vt);
         }
 #pragma unroll
         for (int mv = 0; mv < MV; ++mv) {
             TV::put4(sV0, mv * 16 + kg * 4, i, vt[mv]);
-            TV::put4(sVg, mv * 16 + kg * 4, i, cur.gc * vt[mv]);
-            TV::put4(sVr, mv * 16 + kg * 4, i, -cur.rc * vt[mv]);
+            TV::put4(sVg, mv * 16 + kg * 4, i, cur.c1[COEF_GC - 4] * vt[mv]);
+            TV::put4(sVr, mv * 16 + kg * 4, i, -cur.c1[COEF_RC - 4] * vt[mv]);
         }
         __syncthreads();
 
         // stage 2
         fetch_part<T, DK, DV, DVB, false, true, 2>(nxt, d, a, bh, b, h, nn, dv0);
-        const float aC = lane_value(cur.sc, 0), bC = lane_value(cur.sc, 1), mC = lane_value(cur.sc, 2);
+        const float aC = cur.c0[COEF_AC], bC = cur.c1[COEF_BC - 4], mC = cur.c1[COEF_MC - 4];
 #pragma unroll
         for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
@@ -485,9 +496,7 @@ __global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a)
             }
         fetch_part<T, DK, DV, DVB, false, true, 3>(nxt, d, a, bh, b, h, nn, dv0);
         publish_state<T, DK, MV>(sSt, accS, accM);
-        T *og = static_cast<T *>(a.o) + tok * DV + dv0 + kg * 4;
-#pragma unroll
-        for (int mv = 0; mv < MV; ++mv) store4(og + mv * 16, accO[mv]);
+        store_cols<T, MV>(static_cast<T *>(a.o) + tok * DV + dv0 + kg * (4 * MV), accO);
         __syncthreads();
     };
     {
@@ -504,7 +513,7 @@ __global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a)
     for (int mv = 0; mv < MV; ++mv)
 #pragma unroll
         for (int nd = 0; nd < ND; ++nd) {
-            const size_t g = ((size_t)bh * DK + (w * ND + nd) * 16 + r) * DV + dv0 + mv * 16 + kg * 4;
+            const size_t g = ((size_t)bh * DK + (w * ND + nd) * 16 + r) * DV + dv0 + kg * (4 * MV) + mv * 4;
             if (a.S_final) *reinterpret_cast<f32x4 *>(a.S_final + g) = accS[mv][nd];
             if (a.M_final) *reinterpret_cast<f32x4 *>(a.M_final + g) = accM[mv][nd];
         }
@@ -542,6 +551,7 @@ hipError_t pick_dvb(const Dims &d, const ScanFwdArgs &a, hipStream_t s) {
 
 template <bool REBUILD> hipError_t dispatch_scan(const Dims &d, const ScanFwdArgs &a, hipStream_t s) {
     const bool f32 = d.dtype == 1;
+    if (!a.coef || !a.k || (f32 && !a.KT)) return hipErrorInvalidValue; // operands every variant reads
     if (d.dk == 64 && d.dv == 64)
         return f32 ? pick_dvb<float, 64, 64, REBUILD>(d, a, s) : pick_dvb<bf16_t, 64, 64, REBUILD>(d, a, s);
     if (d.dk == 128 && d.dv == 128)
@@ -556,6 +566,7 @@ hipError_t launch_scan_fwd(const Dims &d, const ScanFwdArgs &a, hipStream_t s) {
 hipError_t launch_rebuild(const Dims &d, const RebuildArgs &r, hipStream_t s) {
     ScanFwdArgs a = {};
     a.coef = r.coef;
+    a.k = r.k;
     a.KT = r.KT;
     a.vt_saved = const_cast<void *>(r.vt_saved);
     a.S0 = r.S0;

@@ -59,7 +59,7 @@ def test_workspace_query_validates_shapes():
     assert lib.mdn_saved_operands_bytes(ctypes.byref(shape()), ctypes.byref(n)) == 0 and n.value > 0
     # fp32 storage doubles every stored intermediate; the coefficient block and the two state buffers that
     # carry S, M between segments of a split call are fp32 in both modes
-    fixed = 4 * 6 * 64 * 2 * 3 * 2 + 2 * (3 * 2 * 128 * 128 * 4 + 256)
+    fixed = 4 * 8 * 64 * 2 * 3 * 2 + 2 * (3 * 2 * 128 * 128 * 4 + 256)
     assert binding.workspace_bytes(shape(dtype=1), 0) > 1.9 * (fwd - fixed)
 
 
