@@ -207,17 +207,20 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
     __syncthreads();
 
     if constexpr (TRT) {
-        // ---- K^T, Q^T for the scans: (dk tile, 32-token step) blocks dealt over the waves; lane (r, kq) reads
-        //      (dk = 16 dt + r, tokens 32 ks + 8 kq ..) and owns exactly that 16-byte piece of the blocked layout,
-        //      so a wave stores 1 KB of consecutive bytes
-        T *KTo = static_cast<T *>(a.KT) + blk * (DK * 64);
-        T *QTo = BWD ? static_cast<T *>(a.QT) + blk * (DK * 64) : nullptr;
+        // ---- K^T (and, on request, Q^T) in the blocked layout, for the one consumer that does not make them
+        //      itself out of the k rows (the loader-wave forward scan): (dk tile, 32-token step) blocks dealt over
+        //      the waves; lane (r, kq) reads (dk = 16 dt + r, tokens 32 ks + 8 kq ..) and owns exactly that
+        //      16-byte piece of the blocked layout, so a wave stores 1 KB of consecutive bytes
+        if (a.KT || (BWD && a.QT)) {
+            T *KTo = a.KT ? static_cast<T *>(a.KT) + blk * (DK * 64) : nullptr;
+            T *QTo = BWD && a.QT ? static_cast<T *>(a.QT) + blk * (DK * 64) : nullptr;
 #pragma unroll
-        for (int t = 0; t < (DK / 16) * 2 / 4; ++t) {
-            const int tt = w + 4 * t, dt = tt >> 1, ks = tt & 1;
-            const size_t o = kblk<T>(DK, dt * 16 + r, ks * 32 + kq * 8);
-            *reinterpret_cast<typename O::Frag *>(KTo + o) = tr_frag(sK, LDN, ks * 32, dt * 16, r, kq);
-            if (BWD) *reinterpret_cast<typename O::Frag *>(QTo + o) = tr_frag(sQ, LDN, ks * 32, dt * 16, r, kq);
+            for (int t = 0; t < (DK / 16) * 2 / 4; ++t) {
+                const int tt = w + 4 * t, dt = tt >> 1, ks = tt & 1;
+                const size_t o = kblk<T>(DK, dt * 16 + r, ks * 32 + kq * 8);
+                if (KTo) *reinterpret_cast<typename O::Frag *>(KTo + o) = tr_frag(sK, LDN, ks * 32, dt * 16, r, kq);
+                if (QTo) *reinterpret_cast<typename O::Frag *>(QTo + o) = tr_frag(sQ, LDN, ks * 32, dt * 16, r, kq);
+            }
         }
     } else {
         // ---- transposed tiles into the space of the K, Q tiles (dst[d][row] = src[row][d])

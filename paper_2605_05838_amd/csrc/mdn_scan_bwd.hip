@@ -292,6 +292,7 @@ template <typename T, int DK, int DV> hipError_t pick_dvb(const Dims &d, const S
 
 hipError_t launch_scan_bwd(const Dims &d, const ScanBwdArgs &a, hipStream_t s) {
     const bool f32 = d.dtype == 1;
+    if (!a.coef || !a.k || !a.dO || !a.BmT || !a.TmT || !a.QT || !a.KT) return hipErrorInvalidValue;
     if (d.dk == 64 && d.dv == 64) return f32 ? pick_dvb<float, 64, 64>(d, a, s) : pick_dvb<bf16_t, 64, 64>(d, a, s);
     if (d.dk == 128 && d.dv == 128)
         return f32 ? pick_dvb<float, 128, 128>(d, a, s) : pick_dvb<bf16_t, 128, 128>(d, a, s);

@@ -143,8 +143,11 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
     __shared__ __align__(16) T sV0[TV::SIZE];
     __shared__ __align__(16) T sVg[TV::SIZE];
     __shared__ __align__(16) T sVr[TV::SIZE];
-    // 16-bit storage: the chunk's k rows come into LDS once (three chunks in flight) and serve both as rows
-    // (stage 1) and, through transposing reads, as K^T (stage 2); fp32 reads the rows and the K^T tile from HBM
+    // 16-bit storage, full scan: the chunk's k rows come into LDS once (three chunks in flight) and serve both as
+    // rows (stage 1) and, through transposing reads, as K^T (stage 2): 231 us against 236 us with both read from
+    // HBM into registers.  (The reconstruction, which needs K^T alone, is faster with the K^T tile from HBM:
+    // 128 against 148 us; so is the reverse scan with K, K^T, Q^T from HBM: 203 against 224 us with k and q tiles
+    // in LDS, which is busy enough there.)  32-bit storage reads the rows and the K^T tile from HBM.
     constexpr bool KTILE = sizeof(T) == 2 && !REBUILD;
     __shared__ __align__(16) T sKr[KTILE ? 3 * 64 * DK : 8];
 
@@ -233,11 +236,11 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
             zero_acc(accOM);
 #pragma unroll
             for (int s = 0; s < CO::KS; ++s) {
+                const typename O::Frag fk = KTILE ? token_tile_row_frag<DK>(kc, i, s, kg) : cur.kr[s];
 #pragma unroll
                 for (int mv = 0; mv < MV; ++mv) {
                     const typename O::Frag fs = TS::frag(sSt, mv, s * O::KSTEP, r, kg);
                     const typename O::Frag fm = TS::frag(sSt, mv, DK + s * O::KSTEP, r, kg);
-                    const typename O::Frag fk = KTILE ? token_tile_row_frag<DK>(kc, i, s, kg) : cur.kr[s];
                     x1[mv] = O::mma(fs, fk, x1[mv]);
                     accOS[mv] = O::mma(fs, cur.q[s], accOS[mv]);
                     x2[mv] = O::mma(fm, fk, x2[mv]);
@@ -292,21 +295,24 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
                 accM[mv][nd] = mC * accM[mv][nd];
             }
 #pragma unroll
-        for (int s = 0; s < CO::KS2; ++s)
+        for (int s = 0; s < CO::KS2; ++s) {
+            typename O::Frag fkt[ND];
+#pragma unroll
+            for (int nd = 0; nd < ND; ++nd) fkt[nd] = KTILE ? token_tile_col_frag<DK>(kc, w * ND + nd, s, r, kg) : cur.kt[nd][s];
 #pragma unroll
             for (int mv = 0; mv < MV; ++mv) {
                 const typename O::Frag fg = TV::frag(sVg, mv, s * O::KSTEP, r, kg);
                 const typename O::Frag fr = TV::frag(sVr, mv, s * O::KSTEP, r, kg);
 #pragma unroll
                 for (int nd = 0; nd < ND; ++nd) {
-                    const typename O::Frag fkt = KTILE ? token_tile_col_frag<DK>(kc, w * ND + nd, s, r, kg) : cur.kt[nd][s];
-                    accS[mv][nd] = O::mma(fg, fkt, accS[mv][nd]);
-                    accM[mv][nd] = O::mma(fr, fkt, accM[mv][nd]);
+                    accS[mv][nd] = O::mma(fg, fkt[nd], accS[mv][nd]);
+                    accM[mv][nd] = O::mma(fr, fkt[nd], accM[mv][nd]);
                 }
                 if (!REBUILD) {
                     accO[mv] = O::mma(TV::frag(sV0, mv, s * O::KSTEP, r, kg), cur.bm[s], accO[mv]);
                 }
             }
+        }
         emit_states(std::integral_constant<int, 5>{});
         fetch_part<T, DK, DV, DVB, REBUILD, false, 3, KTILE>(nxt, d, a, bh, b, h, nn, dv0);
         emit_states(std::integral_constant<int, 6>{});
@@ -519,6 +525,11 @@ __global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a)
         }
 }
 
+bool use_loader_waves(const ScanFwdArgs &a) {
+    static const char *nows = getenv("MDN_NO_LOADER_WAVES"); // tuning switch: never use the loader-wave variant
+    return !nows && !a.states_saved;
+}
+
 template <typename T, int DK, int DV, int DVB, bool REBUILD>
 hipError_t launch_scan_t(const Dims &d, const ScanFwdArgs &a, hipStream_t s) {
     constexpr int G = DV / DVB;
@@ -529,8 +540,7 @@ hipError_t launch_scan_t(const Dims &d, const ScanFwdArgs &a, hipStream_t s) {
         // faster one whoever issues them (measured: 253 us plain; 260 us with the compute waves of the
         // loader-wave variant storing in portions, 261 us with its loader waves storing out of the LDS copy;
         // 177 vs 169 us without the stores): what the stores cost is not the issuing wave's time.
-        static const char *nows = getenv("MDN_NO_LOADER_WAVES"); // tuning switch: never use the loader-wave variant
-        if (!nows && !a.states_saved) {
+        if (use_loader_waves(a)) {
             hipLaunchKernelGGL((scan_fwd_ws_kernel<DK, DV, DVB>), grid, dim3(512), 0, s, d, a);
             return hipGetLastError();
         }
@@ -551,7 +561,7 @@ hipError_t pick_dvb(const Dims &d, const ScanFwdArgs &a, hipStream_t s) {
 
 template <bool REBUILD> hipError_t dispatch_scan(const Dims &d, const ScanFwdArgs &a, hipStream_t s) {
     const bool f32 = d.dtype == 1;
-    if (!a.coef || !a.k || (f32 && !a.KT)) return hipErrorInvalidValue; // operands every variant reads
+    if (!a.coef || !a.k || ((f32 || REBUILD || use_loader_waves(a)) && !a.KT)) return hipErrorInvalidValue;
     if (d.dk == 64 && d.dv == 64)
         return f32 ? pick_dvb<float, 64, 64, REBUILD>(d, a, s) : pick_dvb<bf16_t, 64, 64, REBUILD>(d, a, s);
     if (d.dk == 128 && d.dv == 128)
@@ -562,6 +572,8 @@ template <bool REBUILD> hipError_t dispatch_scan(const Dims &d, const ScanFwdArg
 } // namespace
 
 hipError_t launch_scan_fwd(const Dims &d, const ScanFwdArgs &a, hipStream_t s) { return dispatch_scan<false>(d, a, s); }
+
+bool scan_fwd_reads_KT(const Dims &d, const ScanFwdArgs &a) { return d.dtype == 1 || use_loader_waves(a); }
 
 hipError_t launch_rebuild(const Dims &d, const RebuildArgs &r, hipStream_t s) {
     ScanFwdArgs a = {};
