@@ -144,10 +144,10 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
     __shared__ __align__(16) T sVg[TV::SIZE];
     __shared__ __align__(16) T sVr[TV::SIZE];
     // 16-bit storage, full scan: the chunk's k rows come into LDS once (three chunks in flight) and serve both as
-    // rows (stage 1) and, through transposing reads, as K^T (stage 2): 231 us against 236 us with both read from
-    // HBM into registers.  (The reconstruction, which needs K^T alone, is faster with the K^T tile from HBM:
-    // 128 against 148 us; so is the reverse scan with K, K^T, Q^T from HBM: 203 against 224 us with k and q tiles
-    // in LDS, which is busy enough there.)  32-bit storage reads the rows and the K^T tile from HBM.
+    // rows (stage 1) and, through transposing reads, as K^T (stage 2): as fast as reading both from HBM into
+    // registers, and K^T need not exist for it.  (The reconstruction, which needs K^T alone, is faster with the K^T
+    // tile from HBM: 128 against 148 us; so is the reverse scan with K, K^T, Q^T from HBM: 203 against 224 us with
+    // k and q tiles in LDS.)  32-bit storage reads the rows and the K^T tile from HBM.
     constexpr bool KTILE = sizeof(T) == 2 && !REBUILD;
     __shared__ __align__(16) T sKr[KTILE ? 3 * 64 * DK : 8];
 
