@@ -41,14 +41,14 @@ def bytes_per_tokhd(C, dk, dv, es, keep):
     stored element; gates and coefficients are fp32).  `keep`: the training forward also writes the
     reverse pass's operands and the chunk-start states."""
     coef = 8 * 4                                          # one row of 8 fp32 coefficients per token
-    fwd_ops = (dk + 2 * C) * es + coef                    # K^T, T, Bm, coefficient block
+    kt_fwd = dk * es if es == 4 else 0                    # K^T for the forward scan: 16-bit storage makes it on chip
+    fwd_ops = kt_fwd + 2 * C * es + coef                  # (K^T,) T, Bm, coefficient block
     rev_ops = (2 * dk + 2 * C) * es + coef                # K^T, Q^T, Bm^T, T^T, coefficient block
     states = 2 * dk * dv * es // C                        # S, M of one chunk, per token
     qk = 2 * dk * es
     return {
-        "intra_fwd": qk + 16 + (fwd_ops + rev_ops - dk * es - coef if keep else fwd_ops),
-        # + q, k, v; V~ and o out (with 16-bit storage the scan that keeps the states takes K^T out of the k rows on chip)
-        "scan_fwd": fwd_ops - (dk * es if keep and es == 2 else 0) + qk + dv * es + 2 * dv * es + (states if keep else 0),
+        "intra_fwd": qk + 16 + (2 * C * es + rev_ops if keep else fwd_ops),
+        "scan_fwd": fwd_ops + qk + dv * es + 2 * dv * es + (states if keep else 0),   # + q, k, v; V~ and o out
         "intra_bwd": qk + 16 + rev_ops,
         "rebuild": dk * es + dv * es + coef + states,
         "scan_bwd": rev_ops + dk * es + dv * es + dv * es + states,                   # + k, dO; dv, dstates out

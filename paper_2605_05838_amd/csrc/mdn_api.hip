@@ -261,7 +261,7 @@ int run_fwd(const Dims &d, const FwdCall &c, const FwdWs &w, hipStream_t s) {
     sa.S0 = c.S0; sa.M0 = c.M0; sa.o = c.o; sa.vt_saved = c.vt_saved; sa.states_saved = c.states_saved;
     sa.S_final = c.S_final; sa.M_final = c.M_final;
     // K^T for this forward alone: not written if its scan forms K^T out of the k rows itself
-    if (!c.operands_saved && !scan_fwd_reads_KT(d, sa)) ia.KT = nullptr, sa.KT = nullptr;
+    if (!c.operands_saved && !scan_fwd_reads_KT(d)) ia.KT = nullptr, sa.KT = nullptr;
     const int mode = c.operands_saved ? 2 : 0;
     const int nseg = segments(d);
     if (nseg == 1) {

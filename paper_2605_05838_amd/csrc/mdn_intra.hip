@@ -207,8 +207,8 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
     __syncthreads();
 
     if constexpr (TRT) {
-        // ---- K^T (and, on request, Q^T) in the blocked layout, for the one consumer that does not make them
-        //      itself out of the k rows (the loader-wave forward scan): (dk tile, 32-token step) blocks dealt over
+        // ---- K^T, Q^T in the blocked layout, where asked for (the reverse scan and the state reconstruction read
+        //      them; the forward scan makes K^T itself out of the k rows): (dk tile, 32-token step) blocks dealt over
         //      the waves; lane (r, kq) reads (dk = 16 dt + r, tokens 32 ks + 8 kq ..) and owns exactly that
         //      16-byte piece of the blocked layout, so a wave stores 1 KB of consecutive bytes
         if (a.KT || (BWD && a.QT)) {

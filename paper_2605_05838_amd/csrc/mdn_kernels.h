@@ -87,8 +87,8 @@ struct RecurrentArgs {
 // mode 0: forward operands, 1: reverse-pass operands, 2: both
 hipError_t launch_intra(const Dims &d, int mode, const IntraArgs &a, hipStream_t s);
 hipError_t launch_scan_fwd(const Dims &d, const ScanFwdArgs &a, hipStream_t s);
-// whether that launch reads a.KT (32-bit storage, and the 16-bit variant that does not form K^T out of the k rows)
-bool scan_fwd_reads_KT(const Dims &d, const ScanFwdArgs &a);
+// whether that launch reads a.KT (32-bit storage; 16-bit storage forms K^T out of the k rows in LDS)
+bool scan_fwd_reads_KT(const Dims &d);
 hipError_t launch_rebuild(const Dims &d, const RebuildArgs &a, hipStream_t s);
 hipError_t launch_scan_bwd(const Dims &d, const ScanBwdArgs &a, hipStream_t s);
 hipError_t launch_grad(const Dims &d, const GradArgs &a, hipStream_t s);

@@ -56,7 +56,7 @@ template <typename T, int DK, int MV> struct ChunkOps {
 // The operands of one chunk are requested in portions (P = 0..4) spread over the work on the previous
 // chunk: a wave that issues them all at once sits at the issue until the memory pipeline has taken them
 // (the time to move a chunk's operands into the CU), with its matrix work waiting behind.
-template <typename T, int DK, int DV, int DVB, bool REBUILD, bool NO_STAGE1, int P, bool KTILE = false>
+template <typename T, int DK, int DV, int DVB, bool REBUILD, int P, bool KTILE>
 __device__ __forceinline__ void fetch_part(ChunkOps<T, DK, DVB / 16> &c, const Dims &d, const ScanFwdArgs &a, int bh,
                                            int b, int h, int n, int dv0) {
     typedef Op<T> O;
@@ -95,7 +95,7 @@ __device__ __forceinline__ void fetch_part(ChunkOps<T, DK, DVB / 16> &c, const D
             c.bm[s] = O::load(Bg + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL));
         }
     }
-    if (P == 4 && !REBUILD && !NO_STAGE1 && !KTILE) {
+    if (P == 4 && !REBUILD && !KTILE) {
         const T *Kg = static_cast<const T *>(a.k) + tok * DK + kg * O::EPL;
 #pragma unroll
         for (int s = 0; s < CO::KS; ++s) c.kr[s] = O::load(Kg + s * O::KSTEP);
@@ -103,14 +103,14 @@ __device__ __forceinline__ void fetch_part(ChunkOps<T, DK, DVB / 16> &c, const D
     __builtin_amdgcn_sched_barrier(0); // the portion leaves here, not where the scheduler would gather the loads
 }
 
-template <typename T, int DK, int DV, int DVB, bool REBUILD, bool NO_STAGE1 = false, bool KTILE = false>
+template <typename T, int DK, int DV, int DVB, bool REBUILD, bool KTILE>
 __device__ __forceinline__ void fetch_chunk(ChunkOps<T, DK, DVB / 16> &c, const Dims &d, const ScanFwdArgs &a,
                                             int bh, int b, int h, int n, int dv0) {
-    fetch_part<T, DK, DV, DVB, REBUILD, NO_STAGE1, 0, KTILE>(c, d, a, bh, b, h, n, dv0);
-    fetch_part<T, DK, DV, DVB, REBUILD, NO_STAGE1, 4, KTILE>(c, d, a, bh, b, h, n, dv0);
-    fetch_part<T, DK, DV, DVB, REBUILD, NO_STAGE1, 1, KTILE>(c, d, a, bh, b, h, n, dv0);
-    fetch_part<T, DK, DV, DVB, REBUILD, NO_STAGE1, 3, KTILE>(c, d, a, bh, b, h, n, dv0);
-    fetch_part<T, DK, DV, DVB, REBUILD, NO_STAGE1, 2, KTILE>(c, d, a, bh, b, h, n, dv0);
+    fetch_part<T, DK, DV, DVB, REBUILD, 0, KTILE>(c, d, a, bh, b, h, n, dv0);
+    fetch_part<T, DK, DV, DVB, REBUILD, 4, KTILE>(c, d, a, bh, b, h, n, dv0);
+    fetch_part<T, DK, DV, DVB, REBUILD, 1, KTILE>(c, d, a, bh, b, h, n, dv0);
+    fetch_part<T, DK, DV, DVB, REBUILD, 3, KTILE>(c, d, a, bh, b, h, n, dv0);
+    fetch_part<T, DK, DV, DVB, REBUILD, 2, KTILE>(c, d, a, bh, b, h, n, dv0);
 }
 
 // accumulator element x of tile (mv, nd) of wave w is S[dk = (w*ND + nd)*16 + r][dv = mv*16 + kg*4 + x]
@@ -192,7 +192,7 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
         const T *kc = sKr + slot * (64 * DK);
         if (n + 2 < d.n1) request_k(n + 2, slot >= 1 ? slot - 1 : 2);
         slot = slot == 2 ? 0 : slot + 1;
-        fetch_part<T, DK, DV, DVB, REBUILD, false, 0, KTILE>(nxt, d, a, bh, b, h, nn, dv0);
+        fetch_part<T, DK, DV, DVB, REBUILD, 0, KTILE>(nxt, d, a, bh, b, h, nn, dv0);
 
         // The chunk-start states leave for HBM out of a storage-type copy in registers: in one burst here in the
         // forward scan, in 8 portions spread over the step in the reconstruction, which does little else than
@@ -223,7 +223,7 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
         };
         emit_states(std::integral_constant<int, 0>{});
 
-        fetch_part<T, DK, DV, DVB, REBUILD, false, 4, KTILE>(nxt, d, a, bh, b, h, nn, dv0);
+        fetch_part<T, DK, DV, DVB, REBUILD, 4, KTILE>(nxt, d, a, bh, b, h, nn, dv0);
         emit_states(std::integral_constant<int, 1>{});
         // ---------------- stage 1: R^T = (V - a.(K S) + pb.(K M))^T and the inter-chunk read-outs for token i,
         //                  then V~^T = R^T T^T over all 64 tokens
@@ -247,7 +247,7 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
                     accOM[mv] = O::mma(fm, cur.q[s], accOM[mv]);
                 }
             }
-            fetch_part<T, DK, DV, DVB, REBUILD, false, 1, KTILE>(nxt, d, a, bh, b, h, nn, dv0);
+            fetch_part<T, DK, DV, DVB, REBUILD, 1, KTILE>(nxt, d, a, bh, b, h, nn, dv0);
 #pragma unroll
             for (int mv = 0; mv < MV; ++mv) {
                 accO[mv] = d.scale * (cur.c0[COEF_A] * accOS[mv] - cur.c0[COEF_B] * accOM[mv]);
@@ -284,7 +284,7 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
         __syncthreads();
 
         // ---------------- stage 2: intra-chunk output and the state update
-        fetch_part<T, DK, DV, DVB, REBUILD, false, 2, KTILE>(nxt, d, a, bh, b, h, nn, dv0);
+        fetch_part<T, DK, DV, DVB, REBUILD, 2, KTILE>(nxt, d, a, bh, b, h, nn, dv0);
         emit_states(std::integral_constant<int, 4>{});
         const float aC = cur.c0[COEF_AC], bC = cur.c1[COEF_BC - 4], mC = cur.c1[COEF_MC - 4];
 #pragma unroll
@@ -314,7 +314,7 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
             }
         }
         emit_states(std::integral_constant<int, 5>{});
-        fetch_part<T, DK, DV, DVB, REBUILD, false, 3, KTILE>(nxt, d, a, bh, b, h, nn, dv0);
+        fetch_part<T, DK, DV, DVB, REBUILD, 3, KTILE>(nxt, d, a, bh, b, h, nn, dv0);
         emit_states(std::integral_constant<int, 6>{});
         if (!REBUILD) {
             publish_state<T, DK, MV>(sSt, accS, accM);
@@ -327,7 +327,7 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
     // register of the set that was just requested, i.e. wait for all of its loads
     {
         CO opsA, opsB;
-        fetch_chunk<T, DK, DV, DVB, REBUILD, false, KTILE>(opsA, d, a, bh, b, h, d.n0, dv0);
+        fetch_chunk<T, DK, DV, DVB, REBUILD, KTILE>(opsA, d, a, bh, b, h, d.n0, dv0);
         int n = d.n0;
         for (; n + 1 < d.n1; n += 2) {
             step(n, opsA, opsB);
@@ -346,205 +346,11 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
         }
 }
 
-
-// ---------------------------------------------------------------------------------------------
-// bf16 forward scan with loader waves.  Issuing a chunk's fragment loads costs the issuing wave about as
-// long as the chunk's MFMA work (the CU's vector-memory path moves roughly 30 bytes per clock), and a wave
-// cannot compute while it is stuck issuing.  So the workgroup gets 4 extra waves that do nothing but
-// feed: loader wave c copies the K-row fragments of compute wave c from HBM straight into LDS
-// (global_load_lds, one 16-byte slot per lane: slot = lane, so the compute lane later reads back
-// exactly its own fragment, conflict-free), TWO chunks ahead through a ring of three buffers, never
-// draining its queue (it waits with vmcnt(NF) only for the older of its two bursts).  The compute waves
-// keep fetching the rest (Q, K^T, T and Bm rows, V, coefficients) into registers one chunk ahead.
-// Same arithmetic, same order, as scan_fwd_kernel: the results are bit-identical.
-template <int DK, int DV, int DVB>
-__global__ __launch_bounds__(512) void scan_fwd_ws_kernel(Dims d, ScanFwdArgs a) {
-    typedef bf16_t T;
-    typedef Op<T> O;
-    typedef ChunkOps<T, DK, DVB / 16> CO;
-    constexpr int MV = DVB / 16, ND = DK / 64, G = DV / DVB, KS = CO::KS, NF = KS, NBUF = 3;
-    typedef ATile<T, DVB, 2 * DK> TS;
-    typedef ATile<T, DVB, 64> TV;
-    __shared__ __align__(16) T sSt[TS::SIZE];
-    __shared__ __align__(16) T sV0[TV::SIZE];
-    __shared__ __align__(16) T sVg[TV::SIZE];
-    __shared__ __align__(16) T sVr[TV::SIZE];
-    __shared__ __align__(16) T sRt[TV::SIZE];                // R^T = (V - a.(K S) + pb.(K M))^T, all 64 tokens
-    __shared__ __align__(16) T sF[NBUF][4][NF][64 * O::EPL]; // [buffer][compute wave][fragment][lane slot]
-
-    int bh, blkv;
-    xcd_map(blockIdx.x, G, bh, blkv);
-    if (bh >= d.BH) return;
-    const int b = bh / d.H, h = bh % d.H, dv0 = blkv * DVB;
-    const int lane = lane_id(), wv = wave_id(), r = lane & 15, kg = lane >> 4;
-
-    if (wv >= 4) {
-        // ---------------- loader waves
-        const int cw = wv - 4, i = cw * 16 + r;
-        auto issue = [&](int n, int buf) {
-            const size_t tok = ((size_t)b * d.T + (size_t)n * 64 + i) * d.H + h;
-            const T *Kg = static_cast<const T *>(a.k) + tok * DK + kg * O::EPL;
-#pragma unroll
-            for (int s = 0; s < KS; ++s)
-                __builtin_amdgcn_global_load_lds(Kg + s * O::KSTEP,
-                                                 (__attribute__((address_space(3))) void *)&sF[buf][cw][s][0], 16, 0, 0);
-        };
-        // two chunks ahead: while chunk n computes, chunk n+1 is complete or landing and chunk n+2 is issued
-        issue(d.n0, d.n0 % NBUF);
-        issue(d.n0 + 1 < d.n1 ? d.n0 + 1 : d.n0, (d.n0 + 1) % NBUF);
-        __builtin_amdgcn_s_waitcnt(0x0F70 | NF); // vmcnt(NF): chunk 0 landed, chunk 1 may still be in flight
-        __builtin_amdgcn_s_barrier();
-        for (int n = d.n0; n < d.n1; ++n) {
-            issue((n + 2 < d.n1) ? n + 2 : d.n1 - 1, (n + 2) % NBUF);
-            __builtin_amdgcn_s_barrier();            // barrier 1 of the chunk
-            __builtin_amdgcn_s_barrier();            // barrier 2
-            __builtin_amdgcn_s_waitcnt(0x0F70 | NF); // vmcnt(NF): chunk n+1 landed
-            __builtin_amdgcn_s_barrier();            // barrier 3
-        }
-        __builtin_amdgcn_s_waitcnt(0x0F70); // drain
-        return;
-    }
-
-    // ---------------- compute waves
-    const int w = wv, i = w * 16 + r;
-    f32x4 accS[MV][ND], accM[MV][ND];
-#pragma unroll
-    for (int mv = 0; mv < MV; ++mv)
-#pragma unroll
-        for (int nd = 0; nd < ND; ++nd) {
-            const size_t g = ((size_t)bh * DK + (w * ND + nd) * 16 + r) * DV + dv0 + kg * (4 * MV) + mv * 4;
-            accS[mv][nd] = a.S0 ? *reinterpret_cast<const f32x4 *>(a.S0 + g) : f32x4{0.f, 0.f, 0.f, 0.f};
-            accM[mv][nd] = a.M0 ? *reinterpret_cast<const f32x4 *>(a.M0 + g) : f32x4{0.f, 0.f, 0.f, 0.f};
-        }
-    publish_state<T, DK, MV>(sSt, accS, accM);
-    __syncthreads();
-
-    auto step = [&](int n, const CO &cur, CO &nxt) {
-        const size_t blk = (size_t)bh * d.N + n;
-        const size_t tok = ((size_t)b * d.T + (size_t)n * 64 + i) * d.H + h;
-        const int nn = (n + 1 < d.n1) ? n + 1 : n;
-        fetch_part<T, DK, DV, DVB, false, true, 0>(nxt, d, a, bh, b, h, nn, dv0);
-
-        fetch_part<T, DK, DV, DVB, false, true, 1>(nxt, d, a, bh, b, h, nn, dv0);
-        // stage 1: R^T and the read-outs for token i, then V~^T = R^T T^T over all 64 tokens
-        f32x4 accO[MV], vt[MV], x1[MV], x2[MV], accOS[MV], accOM[MV];
-        zero_acc(x1);
-        zero_acc(x2);
-        zero_acc(accOS);
-        zero_acc(accOM);
-        const T *fp = &sF[n % NBUF][w][0][lane * O::EPL];
-#pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            const typename O::Frag fk = O::load(fp + s * (64 * O::EPL));
-            const typename O::Frag fq = cur.q[s];
-#pragma unroll
-            for (int mv = 0; mv < MV; ++mv) {
-                const typename O::Frag fs = TS::frag(sSt, mv, s * O::KSTEP, r, kg);
-                const typename O::Frag fm = TS::frag(sSt, mv, DK + s * O::KSTEP, r, kg);
-                x1[mv] = O::mma(fs, fk, x1[mv]);
-                accOS[mv] = O::mma(fs, fq, accOS[mv]);
-                x2[mv] = O::mma(fm, fk, x2[mv]);
-                accOM[mv] = O::mma(fm, fq, accOM[mv]);
-            }
-        }
-#pragma unroll
-        for (int mv = 0; mv < MV; ++mv) {
-            accO[mv] = d.scale * (cur.c0[COEF_A] * accOS[mv] - cur.c0[COEF_B] * accOM[mv]);
-            TV::put4(sRt, mv * 16 + kg * 4, i, widen4(cur.u[mv]) - cur.c0[COEF_A] * x1[mv] + cur.c0[COEF_PB] * x2[mv]);
-        }
-        __syncthreads(); // barrier 1 of the chunk (the loader waves count it too)
-        {
-            f32x4 accV[MV];
-            zero_acc(accV);
-#pragma unroll
-            for (int s = 0; s < CO::KS2; ++s)
-#pragma unroll
-                for (int mv = 0; mv < MV; ++mv)
-                    accV[mv] = O::mma(TV::frag(sRt, mv, s * O::KSTEP, r, kg), cur.tm[s], accV[mv]);
-#pragma unroll
-            for (int mv = 0; mv < MV; ++mv)
-#pragma unroll
-                for (int x = 0; x < 4; ++x) vt[mv][x] = rounded<T>(accV[mv][x]);
-        }
-        if (a.vt_saved) {
-            store_cols<T, MV>(static_cast<T *>(a.vt_saved) + tok * DV + dv0 + kg * (4 * MV), vt);
-        }
-#pragma unroll
-        for (int mv = 0; mv < MV; ++mv) {
-            TV::put4(sV0, mv * 16 + kg * 4, i, vt[mv]);
-            TV::put4(sVg, mv * 16 + kg * 4, i, cur.c1[COEF_GC - 4] * vt[mv]);
-            TV::put4(sVr, mv * 16 + kg * 4, i, -cur.c1[COEF_RC - 4] * vt[mv]);
-        }
-        __syncthreads();
-
-        // stage 2
-        fetch_part<T, DK, DV, DVB, false, true, 2>(nxt, d, a, bh, b, h, nn, dv0);
-        const float aC = cur.c0[COEF_AC], bC = cur.c1[COEF_BC - 4], mC = cur.c1[COEF_MC - 4];
-#pragma unroll
-        for (int mv = 0; mv < MV; ++mv)
-#pragma unroll
-            for (int nd = 0; nd < ND; ++nd) {
-                accS[mv][nd] = aC * accS[mv][nd] - bC * accM[mv][nd];
-                accM[mv][nd] = mC * accM[mv][nd];
-            }
-#pragma unroll
-        for (int s = 0; s < CO::KS2; ++s)
-#pragma unroll
-            for (int mv = 0; mv < MV; ++mv) {
-                const typename O::Frag fg = TV::frag(sVg, mv, s * O::KSTEP, r, kg);
-                const typename O::Frag fr = TV::frag(sVr, mv, s * O::KSTEP, r, kg);
-#pragma unroll
-                for (int nd = 0; nd < ND; ++nd) {
-                    accS[mv][nd] = O::mma(fg, cur.kt[nd][s], accS[mv][nd]);
-                    accM[mv][nd] = O::mma(fr, cur.kt[nd][s], accM[mv][nd]);
-                }
-                accO[mv] = O::mma(TV::frag(sV0, mv, s * O::KSTEP, r, kg), cur.bm[s], accO[mv]);
-            }
-        fetch_part<T, DK, DV, DVB, false, true, 3>(nxt, d, a, bh, b, h, nn, dv0);
-        publish_state<T, DK, MV>(sSt, accS, accM);
-        store_cols<T, MV>(static_cast<T *>(a.o) + tok * DV + dv0 + kg * (4 * MV), accO);
-        __syncthreads();
-    };
-    {
-        CO opsA, opsB; // used alternately (no set is ever copied into the other)
-        fetch_chunk<T, DK, DV, DVB, false, true>(opsA, d, a, bh, b, h, d.n0, dv0);
-        int n = d.n0;
-        for (; n + 1 < d.n1; n += 2) {
-            step(n, opsA, opsB);
-            step(n + 1, opsB, opsA);
-        }
-        if (n < d.n1) step(n, opsA, opsB);
-    }
-#pragma unroll
-    for (int mv = 0; mv < MV; ++mv)
-#pragma unroll
-        for (int nd = 0; nd < ND; ++nd) {
-            const size_t g = ((size_t)bh * DK + (w * ND + nd) * 16 + r) * DV + dv0 + kg * (4 * MV) + mv * 4;
-            if (a.S_final) *reinterpret_cast<f32x4 *>(a.S_final + g) = accS[mv][nd];
-            if (a.M_final) *reinterpret_cast<f32x4 *>(a.M_final + g) = accM[mv][nd];
-        }
-}
-
-bool use_loader_waves(const ScanFwdArgs &a) {
-    static const char *nows = getenv("MDN_NO_LOADER_WAVES"); // tuning switch: never use the loader-wave variant
-    return !nows && !a.states_saved;
-}
 
 template <typename T, int DK, int DV, int DVB, bool REBUILD>
 hipError_t launch_scan_t(const Dims &d, const ScanFwdArgs &a, hipStream_t s) {
     constexpr int G = DV / DVB;
     dim3 grid(((d.BH + 7) / 8) * 8 * G), block(kThreads);
-    if constexpr (sizeof(T) == 2 && !REBUILD) {
-        // the loader-wave variant (which does not write the chunk-start states) serves inference and a training
-        // forward that leaves the states to be reconstructed.  With the state stores the plain kernel is the
-        // faster one whoever issues them (measured: 253 us plain; 260 us with the compute waves of the
-        // loader-wave variant storing in portions, 261 us with its loader waves storing out of the LDS copy;
-        // 177 vs 169 us without the stores): what the stores cost is not the issuing wave's time.
-        if (use_loader_waves(a)) {
-            hipLaunchKernelGGL((scan_fwd_ws_kernel<DK, DV, DVB>), grid, dim3(512), 0, s, d, a);
-            return hipGetLastError();
-        }
-    }
     hipLaunchKernelGGL((scan_fwd_kernel<T, DK, DV, DVB, REBUILD>), grid, block, 0, s, d, a);
     return hipGetLastError();
 }
@@ -561,7 +367,7 @@ hipError_t pick_dvb(const Dims &d, const ScanFwdArgs &a, hipStream_t s) {
 
 template <bool REBUILD> hipError_t dispatch_scan(const Dims &d, const ScanFwdArgs &a, hipStream_t s) {
     const bool f32 = d.dtype == 1;
-    if (!a.coef || !a.k || ((f32 || REBUILD || use_loader_waves(a)) && !a.KT)) return hipErrorInvalidValue;
+    if (!a.coef || !a.k || ((f32 || REBUILD) && !a.KT)) return hipErrorInvalidValue;
     if (d.dk == 64 && d.dv == 64)
         return f32 ? pick_dvb<float, 64, 64, REBUILD>(d, a, s) : pick_dvb<bf16_t, 64, 64, REBUILD>(d, a, s);
     if (d.dk == 128 && d.dv == 128)
@@ -573,7 +379,7 @@ template <bool REBUILD> hipError_t dispatch_scan(const Dims &d, const ScanFwdArg
 
 hipError_t launch_scan_fwd(const Dims &d, const ScanFwdArgs &a, hipStream_t s) { return dispatch_scan<false>(d, a, s); }
 
-bool scan_fwd_reads_KT(const Dims &d, const ScanFwdArgs &a) { return d.dtype == 1 || use_loader_waves(a); }
+bool scan_fwd_reads_KT(const Dims &d) { return d.dtype == 1; }
 
 hipError_t launch_rebuild(const Dims &d, const RebuildArgs &r, hipStream_t s) {
     ScanFwdArgs a = {};
