@@ -188,13 +188,18 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
 #pragma unroll
         for (int s = 0; s < KSV; ++s) f[s] = O::load(at32(tile, (unsigned)vblk(DK, kt * 16 + r, s * O::KSTEP + kg * E)));
     };
+    // this lane's share of <X, Y> = sum over the wave's 16 rows and all dv of X[dk][dv] Y[dk][dv] for two state tiles
+    // held as fragments: the matrix unit forms X Y^T (16 x 16, contraction over dv; a fragment serves as A and as B
+    // operand alike) and the trace is picked off the accumulators, element (m, m) sitting in lane r = m, kg = m / 4.
+    // (Multiplying the 2 x 512 register elements out on the vector unit took ~100 instructions per product, a
+    // sixth of the kernel's longest phase.)
     auto dot_frags = [&](const Frag(&x)[KSV], const Frag(&y)[KSV]) {
-        float s = 0.f;
+        f32x4 dd = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int u = 0; u < KSV; ++u)
-#pragma unroll
-            for (int e = 0; e < E; ++e) s += to_f32(x[u][e]) * to_f32(y[u][e]);
-        return s;
+        for (int u = 0; u < KSV; ++u) dd = O::mma(x[u], y[u], dd);
+        const int c = r & 3;
+        const float v = c == 0 ? dd[0] : c == 1 ? dd[1] : c == 2 ? dd[2] : dd[3];
+        return (r >> 2) == kg ? v : 0.f;
     };
 
     // ---- what a chunk needs first is requested as early as possible: its gates, its token tiles (straight into
