@@ -342,22 +342,37 @@ __device__ __forceinline__ void mma_rows_kblk(f32x4 (&acc)[NT], const T *__restr
     }
 }
 
+// Cross-lane sums without the LDS crossbar (a shuffle compiles to ds_bpermute: an LDS instruction with LDS
+// latency).  Inside a row of 16 lanes: DPP quad permutes and row rotations.  Across rows: the row / half swaps
+// (v_permlane16_swap: odd rows of the first operand <-> even rows of the second; v_permlane32_swap: upper half of
+// the first <-> lower half of the second): with the same value in both operands the two results are the value of
+// the lane's own row (half) pair member and that of the other, in every lane.
+template <int CTRL> __device__ __forceinline__ float dpp_move(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+// v + (v of lane ^ 16), in every lane
+__device__ __forceinline__ float add_xor16(float v) {
+    typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+    const u32x2 p = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(p[0]) + __uint_as_float(p[1]);
+}
+// v + (v of lane ^ 32), in every lane
+__device__ __forceinline__ float add_xor32(float v) {
+    typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+    const u32x2 p = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(p[0]) + __uint_as_float(p[1]);
+}
 // sum over the 16 lanes that share kg (i.e. over the column index r of an accumulator row)
 __device__ __forceinline__ float reduce16(float v) {
-    v += __shfl_xor(v, 1);
-    v += __shfl_xor(v, 2);
-    v += __shfl_xor(v, 4);
-    v += __shfl_xor(v, 8);
+    v += dpp_move<0xB1>(v);  // quad_perm [1,0,3,2]
+    v += dpp_move<0x4E>(v);  // quad_perm [2,3,0,1]
+    v += dpp_move<0x124>(v); // row_ror 4
+    v += dpp_move<0x128>(v); // row_ror 8
     return v;
 }
 
 // sum over the whole wave
-__device__ __forceinline__ float reduce64(float v) {
-    v = reduce16(v);
-    v += __shfl_xor(v, 16);
-    v += __shfl_xor(v, 32);
-    return v;
-}
+__device__ __forceinline__ float reduce64(float v) { return add_xor32(add_xor16(reduce16(v))); }
 
 // Workgroup id -> (bh, sub) with all `nsub` workgroups of one bh on the same XCD (workgroups are
 // dealt round-robin to the 8 XCDs, each with its own L2).  Grid must be 8 * ceil(BH/8) * nsub.

@@ -53,11 +53,7 @@ constexpr int GT = 512; // threads per workgroup: 8 waves
 enum { P_DA = 0, P_DB, P_DAM, P_DBM, P_DGC, P_DRC, P_DALK, P_DETK, P_COUNT };
 
 // sum over the 4 lanes (kg = 0..3) that hold the same token column r
-__device__ __forceinline__ float reduce_kg(float v) {
-    v += __shfl_xor(v, 16);
-    v += __shfl_xor(v, 32);
-    return v;
-}
+__device__ __forceinline__ float reduce_kg(float v) { return add_xor32(add_xor16(v)); }
 
 // sum over the 16 dk of one accumulator tile of t^T[dk][i] * X[i][dk] for this lane's token
 __device__ __forceinline__ float coldot(f32x4 t, f32x4 xv) {
@@ -576,9 +572,17 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
                 gm += (j + x < row) ? R[x] * rp[x] : 0.f;
             }
         }
-        ga += __shfl_xor(ga, 1); ga += __shfl_xor(ga, 2); ga += __shfl_xor(ga, 4);
-        gb += __shfl_xor(gb, 1); gb += __shfl_xor(gb, 2); gb += __shfl_xor(gb, 4);
-        gm += __shfl_xor(gm, 1); gm += __shfl_xor(gm, 2); gm += __shfl_xor(gm, 4);
+        // sum over the 8 lanes of a token (quad exchanges, then the neighbouring quad by a row rotation each way:
+        // lanes 0-3 of an aligned group of 8 take the quad to their right, lanes 4-7 the one to their left)
+        auto sum8 = [&](float v) {
+            v += dpp_move<0xB1>(v);
+            v += dpp_move<0x4E>(v);
+            const float up = dpp_move<0x12C>(v), dn = dpp_move<0x124>(v); // row_ror 12 = lane + 4, row_ror 4 = lane - 4
+            return v + ((lane & 4) ? dn : up);
+        };
+        ga = sum8(ga);
+        gb = sum8(gb);
+        gm = sum8(gm);
         if (pt == 0) { s_ga[row] = ga; s_gb[row] = gb; s_gm[row] = gm; }
     }
     __syncthreads();

@@ -19,9 +19,10 @@ constexpr int RCOLS = 32, RCG = RCOLS / 4, RSLICES = kThreads / RCG; // 8 column
 // sum over the 8 slices of a wave (lane = slice_in_wave * 8 + column group)
 __device__ __forceinline__ f32x4 reduce_slices(f32x4 v) {
 #pragma unroll
-    for (int m = 8; m < 64; m <<= 1)
-#pragma unroll
-        for (int x = 0; x < 4; ++x) v[x] += __shfl_xor(v[x], m);
+    for (int x = 0; x < 4; ++x) {
+        v[x] += dpp_move<0x128>(v[x]); // lane ^ 8 (rotation by half a row)
+        v[x] = add_xor32(add_xor16(v[x]));
+    }
     return v;
 }
 
