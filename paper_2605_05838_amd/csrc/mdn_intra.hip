@@ -65,7 +65,7 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
     float *sTT = sG;
     T *sTop = reinterpret_cast<T *>(sG);
     static_assert(sizeof(T) * 64 * LDT <= sizeof(float) * 64 * LDA, "operand copy of T does not fit");
-    __shared__ float s_al[64], s_be[64], s_et[64], s_a[64], s_b[64];
+    __shared__ __align__(16) float s_al[64], s_be[64], s_et[64], s_a[64], s_b[64];
 
     T *sK = sR, *sQ = sR + 64 * LDN;      // phase A
     T *sKT = sR, *sXT = sR + DK * LDT;    // phase B (aliases phase A)
@@ -161,14 +161,22 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
         zero_acc(kk);
         zero_acc(qk);
         mma_rows<T, 4, DK>(kk, sK + i0 * LDN, LDN, sK, LDN);
+        // K K^T is symmetric: element x of tile nt is read as k_i . k_j with i = nt*16 + r (row of A) and
+        // j = i0 + kq*4 + x, so that a lane holds 4 consecutive j of one row: eta and the row of A are one 16-byte
+        // LDS access each
 #pragma unroll
-        for (int nt = 0; nt < 4; ++nt)
+        for (int nt = 0; nt < 4; ++nt) {
+            const int i = nt * 16 + r, j0 = i0 + kq * 4;
+            // (Gamma's rows have an odd stride, for the column accesses of the reverse-pass product below: its four
+            //  values are read one by one)
+            const float *gr = &sG[(i > 0 ? i - 1 : 0) * LDG + j0];
+            const f32x4 et = *reinterpret_cast<const f32x4 *>(&s_et[j0]);
+            const float al_i = s_al[i];
+            f32x4 v;
 #pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                const int i = i0 + kq * 4 + x, j = nt * 16 + r;
-                const float gprev = (i > 0) ? sG[(i - 1) * LDG + j] : 0.f;
-                sA[i * LDA + j] = (j < i) ? s_al[i] * s_et[j] * gprev * kk[nt][x] : 0.f;
-            }
+            for (int x = 0; x < 4; ++x) v[x] = (j0 + x < i) ? al_i * et[x] * gr[x] * kk[nt][x] : 0.f;
+            *reinterpret_cast<f32x4 *>(&sA[i * LDA + j0]) = v;
+        }
         if (BWD) {
             // qk[nt][x] = q_i . k_j, i = i0 + kq*4 + x, j = nt*16 + r  ->  Bm^T row j, k = i
             zero_acc(qk);
@@ -193,13 +201,12 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
             T *out = static_cast<T *>(a.Bm) + blk * 4096;
 #pragma unroll
             for (int nt = 0; nt < 4; ++nt) {
-                const int i = nt * 16 + r;
+                const int i = nt * 16 + r, j0 = i0 + kq * 4;
+                const float *gr = &sG[i * LDG + j0];
+                const f32x4 et = *reinterpret_cast<const f32x4 *>(&s_et[j0]);
                 f32x4 v;
 #pragma unroll
-                for (int x = 0; x < 4; ++x) {
-                    const int j = i0 + kq * 4 + x;
-                    v[x] = (j <= i) ? d.scale * s_et[j] * sG[i * LDG + j] * qk[nt][x] : 0.f;
-                }
+                for (int x = 0; x < 4; ++x) v[x] = (j0 + x <= i) ? d.scale * et[x] * gr[x] * qk[nt][x] : 0.f;
                 store4(out + kblk<T>(64, i, i0 + kq * 4), v);
             }
         }
