@@ -24,13 +24,13 @@ def run_fwd_bwd(w, t, dS_final=None, dM_final=None, save_states=False, save_oper
     return f, g
 
 
-def check_bwd(w, pairs=None, final_adjoints=False, save_states=False, save_operands=False):
+def check_bwd(w, pairs=None, final_adjoints=False, save_states=False, save_operands=False, adjoint_std=1.0):
     t = to_dev(w)
     dSf = dMf = None
     if final_adjoints:
         gen = torch.Generator(device="cpu").manual_seed(99)
-        dSf = torch.randn((w.B, w.H, w.dk, w.dv), generator=gen).cuda()
-        dMf = torch.randn((w.B, w.H, w.dk, w.dv), generator=gen).cuda()
+        dSf = (torch.randn((w.B, w.H, w.dk, w.dv), generator=gen) * adjoint_std).cuda()
+        dMf = (torch.randn((w.B, w.H, w.dk, w.dv), generator=gen) * adjoint_std).cuda()
     f, g = run_fwd_bwd(w, t, dSf, dMf, save_states, save_operands)
     if pairs is None:
         pairs = [(b, h) for b in range(w.B) for h in range(w.H)]
