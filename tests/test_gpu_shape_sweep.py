@@ -1,7 +1,7 @@
 """GPU parity over a seeded sweep of shapes and call options: odd batch and head counts (workgroup placement with
 B*H not a multiple of the 8 dies), lengths around the chunk boundaries, both storage types and head sizes, with and
-without kept states / operands, initial states and adjoints of the final states.  Every gradient (and through the
-backward's own forward call every forward output it consumes) is compared with the fp64 oracle."""
+without kept states / operands, initial states and adjoints of the final states.  The forward outputs
+(o, V~, final states) and every gradient are compared with the fp64 oracle."""
 import random
 
 import numpy as np
@@ -9,6 +9,7 @@ import pytest
 
 from paper_2605_05838_amd import synth
 from test_gpu_backward import check_bwd
+from test_gpu_forward import check_fwd
 
 pytestmark = pytest.mark.gpu
 
@@ -35,6 +36,7 @@ def test_seeded_shape_sweep(case, B, T, H, d, dtype, keep_states, keep_operands,
     w = synth.custom(**kw)
     if with_m0:
         w.arrays["M0"] = (np.random.default_rng(case).standard_normal((B, H, d, d)) * 0.2).astype(np.float32)
+    check_fwd(w)  # o, V~ and the final states of the inference-mode forward
     # Adjoints of the final states enter dalpha, dmu of the last tokens through <dS', S>, a sum of dk*dv products of
     # two tensors that 16-bit storage keeps rounded: with unit-variance adjoints on every state element its rounding
     # error alone (2^-8.5 |dS' . S|_F, about 0.03 here) reaches the 2e-2 bound on its own, so the 16-bit cases take
