@@ -170,6 +170,48 @@ def handoff_bench(args, torch, binding, synth):
         "by_context": rows, "cpu_baseline": None}))
 
 
+def varlen_bench(args, torch, binding, synth):
+    """Packed variable-length batches, forward + backward (the backward rebuilds states and operands): the batch as one
+    stream of tokens (no per-sequence states asked for) against the same batch run sequence by sequence."""
+    from gpu_util import to_dev
+    total, H, dk = args.varlen, 16, 128
+    rows = []
+    for nseq in (8, 64, 256):
+        L = total // nseq
+        w = synth.custom(B=1, T=nseq * L, H=H, dk=dk, dv=dk, dtype="bf16", seed=5, backward=True)
+        t = to_dev(w)
+        cu = [i * L for i in range(nseq + 1)]
+        names = ("q", "k", "v", "beta", "alpha", "mu")
+        row = {"sequences": nseq, "tokens_each": L}
+        for one_stream in (True, False):
+            def step():
+                f = binding.mdn_chunk_fwd_varlen(*(t[k] for k in names), cu, scale=w.scale, save_vt=True,
+                                                 want_states=not one_stream)
+                binding.mdn_chunk_bwd_varlen(*(t[k] for k in names), f["vt"], t["dO"], cu, scale=w.scale,
+                                             want_state_grads=not one_stream)
+            for _ in range(2):
+                step()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            n = max(args.steps // 5, 2)
+            for _ in range(n):
+                step()
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3 / n
+            key = "one_stream" if one_stream else "sequence_by_sequence"
+            row[key + "_ms"] = round(ms, 3)
+            row[key + "_tokens_per_s"] = round(nseq * L / (ms * 1e-3), 1)
+        rows.append(row)
+        del t
+        torch.cuda.empty_cache()
+    print(json.dumps({
+        "metric": "MDN packed variable-length batch fwd+bwd tokens/sec", "value": rows[1]["one_stream_tokens_per_s"],
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": rows[1]["one_stream_ms"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"varlen_{total}tokens_H{H}_d{dk}", "H": H, "dk": dk, "dv": dk}, "roofline": None,
+        "by_batch": rows, "cpu_baseline": None}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -189,6 +231,8 @@ def main():
                     help="instead of the training step: prefill BATCH sequences x 16 heads x d128 of 1024 / 4096 / 16384 "
                          "tokens with mdn_chunk_fwd, then decode from the states it leaves (mdn_recurrent_step, one token "
                          "and 8 tokens per call); prints its own JSON line with the decode latency per context length")
+    ap.add_argument("--varlen", type=int, default=0, metavar="TOKENS",
+                    help="packed variable-length batches of TOKENS tokens in 8, 64, 256 equal sequences (16 heads, d = 128)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="after the timed region, also run one plain device copy of this many MiB (the known-size "
                          "kernel that the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled by)")
@@ -209,6 +253,8 @@ def main():
     torch.cuda.set_device(0)
     if args.decode:
         return decode_bench(args, torch, binding, synth)
+    if args.varlen:
+        return varlen_bench(args, torch, binding, synth)
     if args.handoff:
         return handoff_bench(args, torch, binding, synth)
     w = synth.config(args.config)

@@ -127,9 +127,15 @@ int mdn_chunk_bwd(const mdn_shape *shape, const void *q, const void *k, const vo
  * sequences lie one after another along T of [1, T, H, *] tensors, sequence i being the tokens
  * [cu_seqlens[i], cu_seqlens[i+1]); cu_seqlens is a HOST array of n_seq + 1 increasing offsets with cu_seqlens[0] = 0
  * and cu_seqlens[n_seq] = shape.T; shape.B must be 1.  States are [n_seq, H, dk, dv].  Any lengths >= 1.
- * Each sequence runs by itself through the same kernels as mdn_chunk_fwd / mdn_chunk_bwd, one after the other on the
- * stream (exact, but a batch of many short sequences does not fill the GPU); the backward reconstructs the states
- * and recomputes the operands (no states_saved / operands_saved here).  workspace: mdn_workspace_bytes_varlen.
+ * A call that neither gives nor asks for per-sequence states (forward: S0, M0, S_final, M_final all NULL; backward:
+ * S0, M0, dS_final, dM_final, dS0, dM0 all NULL) runs the whole batch as ONE stream of shape.T tokens, with alpha and
+ * mu set to zero (in copies of its own) at the first token of every sequence but the first: by Eq. Mt.recurrent /
+ * St.recurrent such a token neither sees the states before it nor passes an adjoint back to them, which is what a
+ * sequence that starts from zero states computes; the gradients of those zeroed gates are zero.  One set of
+ * launches however many the sequences.  Any other call runs each sequence by itself through the same kernels as
+ * mdn_chunk_fwd / mdn_chunk_bwd, one after the other on the stream (exact, but a batch of many short sequences does
+ * not fill the GPU).  The backward reconstructs the states and recomputes the operands (no states_saved /
+ * operands_saved here).  workspace: mdn_workspace_bytes_varlen.
  * Errors as for the fixed-length calls; MDN_ERR_SHAPE also for inconsistent cu_seqlens.
  */
 int mdn_workspace_bytes_varlen(const mdn_shape *shape, const int32_t *cu_seqlens, int32_t n_seq, int which, size_t *bytes_out);

@@ -355,16 +355,18 @@ def _varlen_workspace(shape, cu, n, which, device):
     return torch.empty(max(need.value, 16), dtype=torch.uint8, device=device), need.value
 
 
-def mdn_chunk_fwd_varlen(q, k, v, beta, alpha, mu, cu_seqlens, eta=None, S0=None, M0=None, scale=None, save_vt=False):
+def mdn_chunk_fwd_varlen(q, k, v, beta, alpha, mu, cu_seqlens, eta=None, S0=None, M0=None, scale=None, save_vt=False,
+                         want_states=True):
     """Packed variable-length forward: q, k, v [1, T, H, d], gates [1, T, H], cu_seqlens a host sequence of n + 1
-    offsets; states [n, H, dk, dv].  Returns dict(o, S, M, vt)."""
+    offsets; states [n, H, dk, dv].  Returns dict(o, S, M, vt); S, M are None with want_states=False (without initial
+    states either, the library then runs the batch as one stream of tokens)."""
     shape = make_shape(q, v, scale)
     cu, n = _cu(cu_seqlens)
     _, T, H, dk = q.shape
     dv = v.shape[-1]
     o = torch.empty_like(v)
-    S = torch.empty((n, H, dk, dv), dtype=torch.float32, device=q.device)
-    M = torch.empty_like(S)
+    S = torch.empty((n, H, dk, dv), dtype=torch.float32, device=q.device) if want_states else None
+    M = torch.empty_like(S) if want_states else None
     vt = torch.empty_like(v) if save_vt else None
     ws, nb = _varlen_workspace(shape, cu, n, MDN_WS_FWD, q.device)
     rc = load_library().mdn_chunk_fwd_varlen(ctypes.byref(shape), cu, n, _ptr(q), _ptr(k), _ptr(v), _f32(beta, "beta"),
@@ -375,8 +377,10 @@ def mdn_chunk_fwd_varlen(q, k, v, beta, alpha, mu, cu_seqlens, eta=None, S0=None
 
 
 def mdn_chunk_bwd_varlen(q, k, v, beta, alpha, mu, vt, dO, cu_seqlens, eta=None, S0=None, M0=None, dS_final=None,
-                         dM_final=None, scale=None, want_deta=False):
-    """Packed variable-length backward.  Returns dict(dq, dk, dv, dbeta, dalpha, dmu, deta, dS0, dM0)."""
+                         dM_final=None, scale=None, want_deta=False, want_state_grads=True):
+    """Packed variable-length backward.  Returns dict(dq, dk, dv, dbeta, dalpha, dmu, deta, dS0, dM0); dS0, dM0 are
+    None with want_state_grads=False (with no initial states and no adjoints of the final states either, the
+    library then runs the batch as one stream of tokens)."""
     shape = make_shape(q, v, scale)
     cu, n = _cu(cu_seqlens)
     _, T, H, dk = q.shape
@@ -385,8 +389,8 @@ def mdn_chunk_bwd_varlen(q, k, v, beta, alpha, mu, vt, dO, cu_seqlens, eta=None,
     for name in ("dbeta", "dalpha", "dmu"):
         out[name] = torch.empty_like(beta)
     out["deta"] = torch.empty_like(beta) if want_deta else None
-    out["dS0"] = torch.empty((n, H, dk, dv_), dtype=torch.float32, device=q.device)
-    out["dM0"] = torch.empty_like(out["dS0"])
+    out["dS0"] = torch.empty((n, H, dk, dv_), dtype=torch.float32, device=q.device) if want_state_grads else None
+    out["dM0"] = torch.empty_like(out["dS0"]) if want_state_grads else None
     ws, nb = _varlen_workspace(shape, cu, n, MDN_WS_BWD, q.device)
     rc = load_library().mdn_chunk_bwd_varlen(ctypes.byref(shape), cu, n, _ptr(q), _ptr(k), _ptr(v), _f32(beta, "beta"),
                                              _f32(alpha, "alpha"), _f32(mu, "mu"), _f32(eta, "eta"), _f32(S0, "S0"),

@@ -504,6 +504,47 @@ Dims seq_dims(const Dims &all, int len) {
     return d;
 }
 
+// ---- the same batch as ONE stream of tokens.  By Eq. Mt.recurrent / St.recurrent a token with alpha = mu = 0
+// sees nothing of the states before it (e = v, M = -eta k e^T, S = -beta M: what a sequence that starts from zero
+// states computes at its first token, whose own alpha and mu multiply those zeros and do not matter), and passes no
+// adjoint back to them.  So with alpha and mu set to zero at the first token of every sequence but the first, the
+// whole batch is one sequence of shape->T tokens: one set of launches, however many and however short the sequences,
+// and no partial chunk but the last.  Open to calls that neither give nor ask for per-sequence states; the
+// gradients of the zeroed gates are zero (they multiply zero states) and are set so.
+struct PackedWs { float *alpha, *mu; void *rest; size_t total; };
+
+PackedWs carve_packed(const Dims &d, bool backward, void *ws) {
+    Carver c(ws);
+    PackedWs w;
+    w.alpha = static_cast<float *>(c.take((size_t)d.T * d.H * sizeof(float)));
+    w.mu = static_cast<float *>(c.take((size_t)d.T * d.H * sizeof(float)));
+    w.rest = ws ? static_cast<char *>(ws) + c.off : nullptr;
+    w.total = c.off + (backward ? bwd_ws_total(d, d.T % 64) : fwd_ws_total(d, d.T % 64));
+    return w;
+}
+
+// value at the first tokens of sequences 1 .. n_seq-1 of a (and b)
+int set_at_sequence_starts(const Dims &d, const int32_t *cu, int n_seq, float *a, float *b, float value, hipStream_t s) {
+    SeqStarts st;
+    st.H = d.H;
+    for (int i = 1; i < n_seq;) {
+        st.n = 0;
+        while (i < n_seq && st.n < kSeqStartsPerLaunch) st.t[st.n++] = cu[i++];
+        if (launch_set_at_tokens(a, b, value, st, s) != hipSuccess) return MDN_ERR_LAUNCH;
+    }
+    return MDN_OK;
+}
+
+// copies of alpha, mu with the sequence starts zeroed
+int packed_gates(const Dims &d, const int32_t *cu, int n_seq, const float *alpha, const float *mu, const PackedWs &w,
+                 hipStream_t s) {
+    const size_t bytes = (size_t)d.T * d.H * sizeof(float);
+    if (hipMemcpyAsync(w.alpha, alpha, bytes, hipMemcpyDeviceToDevice, s) != hipSuccess ||
+        hipMemcpyAsync(w.mu, mu, bytes, hipMemcpyDeviceToDevice, s) != hipSuccess)
+        return MDN_ERR_LAUNCH;
+    return set_at_sequence_starts(d, cu, n_seq, w.alpha, w.mu, 0.f, s);
+}
+
 template <typename P> P *at_token(P *base, size_t token, size_t bytes_per_token) {
     return base ? reinterpret_cast<P *>(reinterpret_cast<char *>(const_cast<typename std::remove_const<P>::type *>(base)) +
                                         token * bytes_per_token)
@@ -646,7 +687,9 @@ int mdn_workspace_bytes_varlen(const mdn_shape *shape, const int32_t *cu_seqlens
         const size_t b = which == MDN_WS_FWD ? fwd_ws_total(ds, len % 64) : bwd_ws_total(ds, len % 64);
         need = b > need ? b : need;
     }
-    *bytes_out = need;
+    // (either way of running the batch may be taken: see mdn_chunk_fwd_varlen)
+    const size_t packed = carve_packed(d, which == MDN_WS_BWD, nullptr).total;
+    *bytes_out = packed > need ? packed : need;
     return MDN_OK;
 }
 
@@ -666,6 +709,14 @@ int mdn_chunk_fwd_varlen(const mdn_shape *shape, const int32_t *cu_seqlens, int3
     if (rc) return rc;
     if (workspace_bytes < need) return MDN_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!S0 && !M0 && !S_final && !M_final) {
+        // no per-sequence states in or out: the batch as one stream of tokens
+        const PackedWs w = carve_packed(d, false, workspace);
+        rc = packed_gates(d, cu_seqlens, n_seq, alpha, mu, w, s);
+        if (rc) return rc;
+        FwdCall c = {q, k, v, beta, w.alpha, w.mu, eta, nullptr, nullptr, o, nullptr, nullptr, vt_saved, nullptr, nullptr};
+        return fwd_any(d, d.T % 64, c, w.rest, s);
+    }
     const size_t es = elem_size(d), rk = (size_t)d.H * d.dk * es, rv = (size_t)d.H * d.dv * es, rg = (size_t)d.H * 4;
     const size_t st = (size_t)d.H * d.dk * d.dv * sizeof(float);
     for (int i = 0; i < n_seq; ++i) {
@@ -701,6 +752,17 @@ int mdn_chunk_bwd_varlen(const mdn_shape *shape, const int32_t *cu_seqlens, int3
     if (rc) return rc;
     if (workspace_bytes < need) return MDN_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!S0 && !M0 && !dS_final && !dM_final && !dS0 && !dM0) {
+        // no per-sequence states or state adjoints in or out: the batch as one stream of tokens
+        const PackedWs w = carve_packed(d, true, workspace);
+        rc = packed_gates(d, cu_seqlens, n_seq, alpha, mu, w, s);
+        if (rc) return rc;
+        BwdCall c = {q, k, v, beta, w.alpha, w.mu, eta, nullptr, nullptr, vt_saved, nullptr, nullptr, dO, nullptr, nullptr,
+                     dq, dk, dv, dbeta, dalpha, dmu, deta, nullptr, nullptr};
+        rc = bwd_any(d, d.T % 64, c, w.rest, s);
+        if (rc) return rc;
+        return set_at_sequence_starts(d, cu_seqlens, n_seq, dalpha, dmu, 0.f, s);
+    }
     const size_t es = elem_size(d), rk = (size_t)d.H * d.dk * es, rv = (size_t)d.H * d.dv * es, rg = (size_t)d.H * 4;
     const size_t st = (size_t)d.H * d.dk * d.dv * sizeof(float);
     for (int i = 0; i < n_seq; ++i) {

@@ -108,4 +108,14 @@ struct TailCopy {
 };
 hipError_t launch_tail_copy(const TailCopy &c, bool gather, hipStream_t s);
 
+// Packed variable-length batches run as one stream of tokens whose state is cut at the first token of every
+// sequence but the first: x[t, h] = value for the listed tokens t of up to two [T, H] fp32 tensors (a, b; b may be
+// null).  The token list travels in the kernel arguments, kSeqStartsPerLaunch at a time.
+constexpr int kSeqStartsPerLaunch = 240;
+struct SeqStarts {
+    int n, H;
+    int t[kSeqStartsPerLaunch];
+};
+hipError_t launch_set_at_tokens(float *a, float *b, float value, const SeqStarts &st, hipStream_t s);
+
 } // namespace mdn

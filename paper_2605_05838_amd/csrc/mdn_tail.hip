@@ -37,7 +37,23 @@ __global__ __launch_bounds__(64) void tail_scatter_kernel(TailCopy c) {
     for (int x = threadIdx.x; x < words; x += 64) dst[x] = src[x];
 }
 
+// blockIdx.x = entry of the token list; threads over the heads
+__global__ __launch_bounds__(64) void set_at_tokens_kernel(float *a, float *b, float value, SeqStarts st) {
+    const size_t row = (size_t)st.t[blockIdx.x] * st.H;
+    for (int h = threadIdx.x; h < st.H; h += 64) {
+        a[row + h] = value;
+        if (b) b[row + h] = value;
+    }
+}
+
 } // namespace
+
+hipError_t launch_set_at_tokens(float *a, float *b, float value, const SeqStarts &st, hipStream_t s) {
+    if (st.n < 1) return hipSuccess;
+    if (!a || st.n > kSeqStartsPerLaunch || st.H < 1) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(set_at_tokens_kernel, dim3(st.n), dim3(64), 0, s, a, b, value, st);
+    return hipGetLastError();
+}
 
 hipError_t launch_tail_copy(const TailCopy &c, bool gather, hipStream_t s) {
     if (c.n < 1) return hipSuccess;

@@ -93,8 +93,13 @@ def test_varlen_workspace_query_validates_the_offsets():
     cu = lambda *v: (ctypes.c_int32 * len(v))(*v)
     s1 = shape(B=1, T=300)
     assert lib.mdn_workspace_bytes_varlen(ctypes.byref(s1), cu(0, 100, 300), 2, 0, ctypes.byref(n)) == 0 and n.value > 0
-    longest = n.value
-    assert lib.mdn_workspace_bytes_varlen(ctypes.byref(s1), cu(0, 150, 300), 2, 0, ctypes.byref(n)) == 0 and n.value < longest
+    # enough for either way of running the batch: sequence by sequence (the longest one decides), or as one stream
+    # of all T tokens with its own copies of alpha and mu
+    whole = ctypes.c_size_t(0)
+    assert lib.mdn_workspace_bytes(ctypes.byref(s1), 0, ctypes.byref(whole)) == 0
+    assert n.value >= whole.value + 2 * 300 * s1.H * 4
+    first = n.value
+    assert lib.mdn_workspace_bytes_varlen(ctypes.byref(s1), cu(0, 150, 300), 2, 0, ctypes.byref(n)) == 0 and n.value <= first
     assert lib.mdn_workspace_bytes_varlen(ctypes.byref(s1), cu(0, 100, 299), 2, 0, ctypes.byref(n)) == -2   # does not end at T
     assert lib.mdn_workspace_bytes_varlen(ctypes.byref(s1), cu(0, 100, 100, 300), 3, 0, ctypes.byref(n)) == -2   # empty sequence
     assert lib.mdn_workspace_bytes_varlen(ctypes.byref(s1), cu(1, 100, 300), 2, 0, ctypes.byref(n)) == -2   # does not start at 0

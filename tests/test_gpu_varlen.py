@@ -47,3 +47,38 @@ def test_packed_sequences_forward_and_backward(dtype, d, lens):
             assert rel_err(host(g[name])[:, sl], rb[name]) <= tol, (i, name)
         for name in ("dS0", "dM0"):
             assert rel_err(host(g[name])[i:i + 1], rb[name]) <= tol, (i, name)
+
+
+@pytest.mark.parametrize("dtype,d,lens", [("f32", 64, (70, 128, 5, 191, 1, 64)), ("bf16", 128, (256, 33, 200, 1, 63, 65)),
+                                          ("bf16", 64, (40,) * 9), ("f32", 128, (300,))])
+def test_packed_sequences_as_one_stream_of_tokens(dtype, d, lens):
+    """No per-sequence states in or out: the library runs the batch as one stream with alpha = mu = 0 at the sequence
+    starts.  Every sequence must come out as the oracle computes it by itself from zero states (sequence starts inside
+    chunks, on chunk boundaries, sequences of one token), and the caller's alpha, mu must be left as they were."""
+    T, H = sum(lens), 3
+    w = synth.custom(B=1, T=T, H=H, dk=d, dv=d, dtype=dtype, seed=72, with_eta=True, backward=True)
+    t = to_dev(w)
+    n = len(lens)
+    cu = np.concatenate([[0], np.cumsum(lens)]).tolist()
+    al0, mu0 = t["alpha"].clone(), t["mu"].clone()
+    f = binding.mdn_chunk_fwd_varlen(t["q"], t["k"], t["v"], t["beta"], t["alpha"], t["mu"], cu, eta=t["eta"],
+                                     scale=w.scale, save_vt=True, want_states=False)
+    g = binding.mdn_chunk_bwd_varlen(t["q"], t["k"], t["v"], t["beta"], t["alpha"], t["mu"], f["vt"], t["dO"], cu,
+                                     eta=t["eta"], scale=w.scale, want_deta=True, want_state_grads=False)
+    torch.cuda.synchronize()
+    assert f["S"] is None and g["dS0"] is None
+    assert torch.equal(al0, t["alpha"]) and torch.equal(mu0, t["mu"])
+    a = {k: (None if v is None else v.astype(np.float64)) for k, v in w.arrays.items()}
+    tol = TOL[dtype]
+    for i in range(n):
+        sl = slice(cu[i], cu[i + 1])
+        seq = {k: a[k][:, sl] for k in ("q", "k", "v", "alpha", "beta", "mu", "eta", "dO")}
+        rf = orc.forward(seq["q"], seq["k"], seq["v"], seq["alpha"], seq["beta"], seq["mu"], eta=seq["eta"], scale=w.scale)
+        assert rel_err(host(f["o"])[:, sl], rf["o"]) <= tol, (i, "o")
+        assert rel_err(host(f["vt"])[:, sl], rf["vt"]) <= tol, (i, "vt")
+        rb = orc.backward(seq["q"], seq["k"], seq["v"], seq["alpha"], seq["beta"], seq["mu"], seq["dO"], eta=seq["eta"],
+                          scale=w.scale)
+        for name in ("dq", "dk", "dv", "dalpha", "dbeta", "dmu", "deta"):
+            assert rel_err(host(g[name])[:, sl], rb[name]) <= tol, (i, name)
+        # the first token's alpha, mu multiply zero states: their gradients are exactly zero
+        assert float(host(g["dalpha"])[:, cu[i]].max()) == 0.0 and float(host(g["dmu"])[:, cu[i]].min()) == 0.0, i
