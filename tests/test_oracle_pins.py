@@ -209,6 +209,36 @@ def test_state_passing_equals_one_run():
     assert np.allclose(r2["S"], full["S"], atol=1e-12) and np.allclose(r2["M"], full["M"], atol=1e-12)
 
 
+def test_zero_alpha_and_mu_cut_the_state_forward_and_backward():
+    """Eq. Mt.recurrent / St.recurrent: a token with alpha = mu = 0 computes e = v, M = -eta k^T e, S = -beta M
+    whatever came before, and passes no adjoint back.  Two sequences packed into one, with alpha and mu zeroed at the
+    first token of the second, must therefore give each sequence's own outputs and gradients (the gradients of the two
+    zeroed gates aside, which for a sequence of its own are zero: they multiply zero states)."""
+    rng = np.random.default_rng(16)
+    c = rand_case(rng, B=1, T=23, H=2, dk=4, dv=5, states=False)
+    dO = rng.standard_normal(c["v"].shape)
+    cut = 9
+    packed = {k_: (None if v_ is None else v_.copy()) for k_, v_ in c.items()}
+    packed["alpha"][:, cut] = 0.0
+    packed["mu"][:, cut] = 0.0
+    fp = fwd(packed)
+    bp = orc.backward(packed["q"], packed["k"], packed["v"], packed["alpha"], packed["beta"], packed["mu"], dO,
+                      eta=packed["eta"])
+    for sl in (slice(0, cut), slice(cut, 23)):
+        seq = {k_: (v_[:, sl] if k_ not in ("S0", "M0") and v_ is not None else v_) for k_, v_ in c.items()}
+        f1 = fwd(seq)
+        b1 = orc.backward(seq["q"], seq["k"], seq["v"], seq["alpha"], seq["beta"], seq["mu"], dO[:, sl], eta=seq["eta"])
+        assert np.allclose(fp["o"][:, sl], f1["o"], atol=1e-12) and np.allclose(fp["vt"][:, sl], f1["vt"], atol=1e-12)
+        for name in ("dq", "dk", "dv", "dbeta", "deta"):
+            assert np.allclose(bp[name][:, sl], b1[name], atol=1e-11), name
+        for name in ("dalpha", "dmu"):
+            keep = slice(sl.start + 1, sl.stop)   # all but the sequence's first token
+            assert np.allclose(bp[name][:, keep], b1[name][:, 1:], atol=1e-11), name
+            assert np.all(b1[name][:, 0] == 0.0), name
+    assert np.allclose(fp["S"], fwd({k_: (v_[:, cut:] if k_ not in ("S0", "M0") and v_ is not None else v_)
+                                     for k_, v_ in c.items()})["S"], atol=1e-12)
+
+
 def test_batch_head_independence_and_layout():
     """Each (b, h) of a [B,T,H,*] call equals a B=H=1 call on its slice (pins the index arithmetic)."""
     rng = np.random.default_rng(8)
