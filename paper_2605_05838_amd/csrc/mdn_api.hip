@@ -171,11 +171,11 @@ template <typename F> int timed(int id, hipStream_t s, F &&launch) {
     if (!g_profiling) return launch_status(launch());
     TimedLaunch t{id, nullptr, nullptr};
     if (hipEventCreate(&t.start) != hipSuccess || hipEventCreate(&t.stop) != hipSuccess) return MDN_ERR_LAUNCH;
-    hipEventRecord(t.start, s);
+    const bool r0 = hipEventRecord(t.start, s) == hipSuccess;
     const int rc = launch_status(launch());
-    hipEventRecord(t.stop, s);
+    const bool r1 = hipEventRecord(t.stop, s) == hipSuccess;
     g_timed.push_back(t);
-    return rc;
+    return r0 && r1 ? rc : MDN_ERR_LAUNCH;
 }
 
 // ---- splitting a call into segments of the sequence.  When the serial scans occupy at most half of the CUs
@@ -579,8 +579,7 @@ int mdn_profile_end(float *ms, int *launches, int n) {
             if (ms) ms[t.id] += e;
             if (launches) launches[t.id] += 1;
         }
-        hipEventDestroy(t.start);
-        hipEventDestroy(t.stop);
+        if (hipEventDestroy(t.start) != hipSuccess || hipEventDestroy(t.stop) != hipSuccess) rc = MDN_ERR_LAUNCH;
     }
     g_timed.clear();
     return rc;

@@ -52,19 +52,17 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
     typedef Op<T> O;
     constexpr int E = O::EPL;
     constexpr int LDN = DK + O::PAD; // natural tiles
-    constexpr int LDT = 64 + O::PAD; // transposed tiles and the operand copy of T
+    constexpr int LDT = 64 + O::PAD; // transposed tiles (32-bit storage)
     constexpr int DX = BWD ? DK : 0; // second transposed tile: Q^T (reverse-pass operands only)
     constexpr int REG_NAT = 2 * 64 * LDN, REG_TR = (DK + DX) * LDT;
     constexpr int REGION = REG_NAT > REG_TR ? REG_NAT : REG_TR;
     constexpr int NVK = 64 * DK / E / kThreads, NVX = BWD ? NVK : 1; // 16-byte vectors per thread
 
     __shared__ __align__(16) T sR[REGION];
-    // Gamma (row stride LDG); later scratch of the block inverse; later the operand copy of T
+    // Gamma (row stride LDG); later scratch of the block inverse
     __shared__ __align__(16) float sG[64 * LDA];
     __shared__ __align__(16) float sA[64 * LDA];
     float *sTT = sG;
-    T *sTop = reinterpret_cast<T *>(sG);
-    static_assert(sizeof(T) * 64 * LDT <= sizeof(float) * 64 * LDA, "operand copy of T does not fit");
     __shared__ __align__(16) float s_al[64], s_be[64], s_et[64], s_a[64], s_b[64];
 
     T *sK = sR, *sQ = sR + 64 * LDN;      // phase A

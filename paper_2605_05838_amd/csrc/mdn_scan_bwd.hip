@@ -41,10 +41,9 @@ template <typename T, int DK, int MV> struct RevOps {
     f32x4 c0, c1;                      // the token's coefficient row (COEF_*)
 };
 
-// The operands of one chunk are requested in NPART portions spread over the work on the previous chunk: a
+// The operands of one chunk are requested in five portions (P = 0..4) spread over the work on the previous chunk: a
 // wave that issues them all at once sits at the issue until the memory pipeline has taken them (the time
 // to move a chunk's operands into the CU), with its matrix work waiting behind.
-constexpr int NPART = 5;
 template <typename T, int DK, int DV, int DVB, int P>
 __device__ __forceinline__ void fetch_part(RevOps<T, DK, DVB / 16> &c, const Dims &d, const ScanBwdArgs &a, int bh, int b,
                                            int h, int n, int dv0) {
