@@ -204,7 +204,7 @@ int segments(const Dims &d) {
         // workgroups of a scan launch: one per (batch*head rounded up to 8, block of 32 or 16 dv columns)
         const bool dvb16 = d.BH * (d.dv / 32) < 192 || (d.dtype == MDN_DTYPE_F32 && d.dk == 128);
         const int scan_wgs = (d.BH + 7) / 8 * 8 * (d.dv / (dvb16 ? 16 : 32));
-        k = (2 * scan_wgs <= num_cus() && d.N >= 32) ? 8 : 1;
+        k = (2 * scan_wgs <= num_cus() && d.N >= 32) ? 4 : 1;
     }
     if (k > d.N / 4) k = d.N / 4;
     return k < 1 ? 1 : (k > 16 ? 16 : k);
