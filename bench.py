@@ -201,8 +201,27 @@ def varlen_bench(args, torch, binding, synth):
             key = "one_stream" if one_stream else "sequence_by_sequence"
             row[key + "_ms"] = round(ms, 3)
             row[key + "_tokens_per_s"] = round(nseq * L / (ms * 1e-3), 1)
+        # prefill of the same batch as prompts: forward only, final states of every sequence wanted (zero initial
+        # states: the stream form plus one batch of last chunks; with initial states given: sequence by sequence)
+        zeros = torch.zeros((nseq, H, dk, dk), dtype=torch.float32, device="cuda")
+        for one_stream in (True, False):
+            def prefill():
+                binding.mdn_chunk_fwd_varlen(*(t[k] for k in names), cu, scale=w.scale,
+                                             S0=None if one_stream else zeros, M0=None if one_stream else zeros)
+            for _ in range(2):
+                prefill()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            n = max(args.steps // 5, 2)
+            for _ in range(n):
+                prefill()
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3 / n
+            key = "prefill_one_stream" if one_stream else "prefill_sequence_by_sequence"
+            row[key + "_ms"] = round(ms, 3)
+            row[key + "_tokens_per_s"] = round(nseq * L / (ms * 1e-3), 1)
         rows.append(row)
-        del t
+        del t, zeros
         torch.cuda.empty_cache()
     print(json.dumps({
         "metric": "MDN packed variable-length batch fwd+bwd tokens/sec", "value": rows[1]["one_stream_tokens_per_s"],

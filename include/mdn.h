@@ -132,7 +132,11 @@ int mdn_chunk_bwd(const mdn_shape *shape, const void *q, const void *k, const vo
  * mu set to zero (in copies of its own) at the first token of every sequence but the first: by Eq. Mt.recurrent /
  * St.recurrent such a token neither sees the states before it nor passes an adjoint back to them, which is what a
  * sequence that starts from zero states computes; the gradients of those zeroed gates are zero.  One set of
- * launches however many the sequences.  Any other call runs each sequence by itself through the same kernels as
+ * launches however many the sequences.  A forward with zero initial states that wants the final states (S0, M0 NULL,
+ * S_final and M_final given: prefill of a batch of prompts) runs the same stream, keeps its chunk-start states in the
+ * workspace and then runs, as one batch, the last chunk of every sequence once more from its start state up to the
+ * sequence's end (with 16-bit storage those start states carry the storage rounding).  Any other call runs each
+ * sequence by itself through the same kernels as
  * mdn_chunk_fwd / mdn_chunk_bwd, one after the other on the stream (exact, but a batch of many short sequences does
  * not fill the GPU).  The backward reconstructs the states and recomputes the operands (no states_saved /
  * operands_saved here).  workspace: mdn_workspace_bytes_varlen.

@@ -545,6 +545,88 @@ int packed_gates(const Dims &d, const int32_t *cu, int n_seq, const float *alpha
     return set_at_sequence_starts(d, cu, n_seq, w.alpha, w.mu, 0.f, s);
 }
 
+// ---- the stream form with per-sequence FINAL states (zero initial states): the stream keeps its chunk-start
+// states; the state after a sequence's last token is that of the chunk holding the token, run once more from its
+// start state over the tokens up to the sequence's end, the rest of the chunk padded with tokens that change no state
+// (as for a partial last chunk).  All sequences' last chunks form one batch of n_seq rows of 64 tokens.
+Dims rows_dims(const Dims &d, int n_seq) {
+    Dims t = tail_dims(d);
+    t.B = n_seq; t.BH = n_seq * d.H;
+    return t;
+}
+
+struct PackedFinalWs {
+    PackedWs g;       // gate copies
+    void *states;     // chunk-start states of the stream (full chunks, then the partial chunk's block)
+    void *k, *v, *o;  // padded rows [n_seq, 64, H, *]
+    float *beta, *alpha, *mu, *eta, *S0, *M0;
+    void *rest_stream, *rest_rows;
+    size_t total;
+};
+
+PackedFinalWs carve_packed_final(const Dims &d, int n_seq, void *ws) {
+    const size_t es = elem_size(d), rows = (size_t)n_seq * 64 * d.H, st = (size_t)n_seq * d.H * d.dk * d.dv * sizeof(float);
+    const Dims dr = rows_dims(d, n_seq);
+    Carver c(ws);
+    PackedFinalWs w = {};
+    w.g.alpha = static_cast<float *>(c.take((size_t)d.T * d.H * sizeof(float)));
+    w.g.mu = static_cast<float *>(c.take((size_t)d.T * d.H * sizeof(float)));
+    w.states = c.take(saved_states_part(d) + (d.T % 64 ? saved_states_part(tail_dims(d)) : 0));
+    w.k = c.take(rows * d.dk * es);
+    w.v = c.take(rows * d.dv * es);
+    w.o = c.take(rows * d.dv * es);
+    w.beta = static_cast<float *>(c.take(rows * 4));
+    w.alpha = static_cast<float *>(c.take(rows * 4));
+    w.mu = static_cast<float *>(c.take(rows * 4));
+    w.eta = static_cast<float *>(c.take(rows * 4));
+    w.S0 = static_cast<float *>(c.take(st));
+    w.M0 = static_cast<float *>(c.take(st));
+    w.rest_stream = c.take(fwd_ws_total(d, d.T % 64));
+    w.rest_rows = c.take(fwd_ws_total(dr, 0));
+    w.total = c.off;
+    return w;
+}
+
+int packed_final_states(const Dims &d, const int32_t *cu, int n_seq, const FwdCall &stream, const PackedFinalWs &w,
+                        float *S_final, float *M_final, hipStream_t s) {
+    const size_t es = elem_size(d), st = (size_t)d.H * d.dk * d.dv;
+    for (int i0 = 0; i0 < n_seq; i0 += kSeqRowsPerLaunch) {
+        const int n = n_seq - i0 < kSeqRowsPerLaunch ? n_seq - i0 : kSeqRowsPerLaunch;
+        const size_t rows0 = (size_t)i0 * 64 * d.H;
+        SeqRows g = {};
+        SeqChunks sc = {};
+        g.n = sc.n = n; g.H = sc.H = d.H;
+        sc.N = d.N; sc.dk = d.dk; sc.dv = d.dv; sc.dtype = d.dtype;
+        for (int e = 0; e < n; ++e) {
+            const int end = cu[i0 + e + 1], chunk = (end - 1) / 64;
+            sc.chunk[e] = chunk;
+            g.t0[e] = chunk * 64;
+            g.r[e] = end - chunk * 64;
+        }
+        auto add = [&](const void *full, void *padded, size_t row_bytes, float pad) {
+            if (!full) return;
+            TailTensor &t = g.t[g.ntens++];
+            t.full = full; t.padded = static_cast<char *>(padded) + rows0 * row_bytes; t.row_bytes = (int)row_bytes;
+            memcpy(&t.pad_word, &pad, 4);
+        };
+        add(stream.k, w.k, d.dk * es, 0.f);
+        add(stream.v, w.v, d.dv * es, 0.f);
+        add(stream.beta, w.beta, 4, 0.f);
+        add(stream.alpha, w.alpha, 4, 1.f);
+        add(stream.mu, w.mu, 4, 1.f);
+        add(stream.eta, w.eta, 4, 1.f);
+        if (launch_gather_seq_rows(g, s) != hipSuccess) return MDN_ERR_LAUNCH;
+        if (launch_states_to_f32(w.states, offset(w.states, saved_states_part(d)), sc, w.S0 + (size_t)i0 * st,
+                                 w.M0 + (size_t)i0 * st, s) != hipSuccess)
+            return MDN_ERR_LAUNCH;
+    }
+    // (the rows' outputs o are of no use: q is given the k rows, o a scratch tensor)
+    const Dims dr = rows_dims(d, n_seq);
+    FwdCall c = {w.k, w.k, w.v, w.beta, w.alpha, w.mu, stream.eta ? w.eta : nullptr, w.S0, w.M0, w.o, S_final, M_final,
+                 nullptr, nullptr, nullptr};
+    return run_fwd(dr, c, carve_fwd(dr, w.rest_rows), s);
+}
+
 template <typename P> P *at_token(P *base, size_t token, size_t bytes_per_token) {
     return base ? reinterpret_cast<P *>(reinterpret_cast<char *>(const_cast<typename std::remove_const<P>::type *>(base)) +
                                         token * bytes_per_token)
@@ -687,7 +769,11 @@ int mdn_workspace_bytes_varlen(const mdn_shape *shape, const int32_t *cu_seqlens
         need = b > need ? b : need;
     }
     // (either way of running the batch may be taken: see mdn_chunk_fwd_varlen)
-    const size_t packed = carve_packed(d, which == MDN_WS_BWD, nullptr).total;
+    size_t packed = carve_packed(d, which == MDN_WS_BWD, nullptr).total;
+    if (which == MDN_WS_FWD) {
+        const size_t pf = carve_packed_final(d, n_seq, nullptr).total;
+        packed = pf > packed ? pf : packed;
+    }
     *bytes_out = packed > need ? packed : need;
     return MDN_OK;
 }
@@ -715,6 +801,16 @@ int mdn_chunk_fwd_varlen(const mdn_shape *shape, const int32_t *cu_seqlens, int3
         if (rc) return rc;
         FwdCall c = {q, k, v, beta, w.alpha, w.mu, eta, nullptr, nullptr, o, nullptr, nullptr, vt_saved, nullptr, nullptr};
         return fwd_any(d, d.T % 64, c, w.rest, s);
+    }
+    if (!S0 && !M0 && S_final && M_final) {
+        // zero initial states, final states of every sequence wanted: the stream, then the sequences' last chunks
+        const PackedFinalWs w = carve_packed_final(d, n_seq, workspace);
+        rc = packed_gates(d, cu_seqlens, n_seq, alpha, mu, w.g, s);
+        if (rc) return rc;
+        FwdCall c = {q, k, v, beta, w.g.alpha, w.g.mu, eta, nullptr, nullptr, o, nullptr, nullptr, vt_saved, w.states, nullptr};
+        rc = fwd_any(d, d.T % 64, c, w.rest_stream, s);
+        if (rc) return rc;
+        return packed_final_states(d, cu_seqlens, n_seq, c, w, S_final, M_final, s);
     }
     const size_t es = elem_size(d), rk = (size_t)d.H * d.dk * es, rv = (size_t)d.H * d.dv * es, rg = (size_t)d.H * 4;
     const size_t st = (size_t)d.H * d.dk * d.dv * sizeof(float);

@@ -118,4 +118,24 @@ struct SeqStarts {
 };
 hipError_t launch_set_at_tokens(float *a, float *b, float value, const SeqStarts &st, hipStream_t s);
 
+// The last (possibly partial) chunk of each listed sequence of a token stream [T, H, *], as a batch of padded
+// 64-token rows [n, 64, H, *]: entry i takes tokens [t0[i], t0[i] + r[i]) (1 <= r <= 64) and pads like TailCopy.
+constexpr int kSeqRowsPerLaunch = 200;
+struct SeqRows {
+    int n, H, ntens;
+    int t0[kSeqRowsPerLaunch], r[kSeqRowsPerLaunch];
+    TailTensor t[8];
+};
+hipError_t launch_gather_seq_rows(const SeqRows &g, hipStream_t s);
+
+// Chunk-start states out of the saved-states buffer of a single-batch call (blocks [H][N][2] in the vblk layout and
+// the storage type, then one block pair per head for the partial chunk) as fp32 [n, H, dk, dv]: entry i takes chunk
+// chunk[i] (== N: the partial chunk's block).
+struct SeqChunks {
+    int n, H, N, dk, dv, dtype;
+    int chunk[kSeqRowsPerLaunch];
+};
+hipError_t launch_states_to_f32(const void *states_full, const void *states_tail, const SeqChunks &c, float *S, float *M,
+                                hipStream_t s);
+
 } // namespace mdn

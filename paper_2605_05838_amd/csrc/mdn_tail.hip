@@ -46,7 +46,64 @@ __global__ __launch_bounds__(64) void set_at_tokens_kernel(float *a, float *b, f
     }
 }
 
+// blockIdx.y = tensor, blockIdx.x = (entry, i, h) row of the padded batch
+__global__ __launch_bounds__(64) void gather_seq_rows_kernel(SeqRows g) {
+    const TailTensor t = g.t[blockIdx.y];
+    const int row = blockIdx.x, h = row % g.H, i = (row / g.H) % 64, e = row / (g.H * 64);
+    const int words = t.row_bytes / 4;
+    uint32_t *dst = reinterpret_cast<uint32_t *>(static_cast<char *>(t.padded) + (size_t)row * t.row_bytes);
+    if (i < g.r[e]) {
+        const size_t srow = ((size_t)g.t0[e] + i) * g.H + h;
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(static_cast<const char *>(t.full) + srow * t.row_bytes);
+        for (int x = threadIdx.x; x < words; x += 64) dst[x] = src[x];
+    } else {
+        for (int x = threadIdx.x; x < words; x += 64) dst[x] = t.pad_word;
+    }
+}
+
+// blockIdx.x = entry, blockIdx.y = head, blockIdx.z = 0: S, 1: M
+template <typename T> __global__ __launch_bounds__(256) void states_to_f32_kernel(const T *full, const T *tail, SeqChunks c,
+                                                                                  float *S, float *M) {
+    const int e = blockIdx.x, h = blockIdx.y, which = blockIdx.z, n = c.chunk[e];
+    const size_t blk = (size_t)c.dk * c.dv;
+    const T *src = n < c.N ? full + (((size_t)h * c.N + n) * 2 + which) * blk : tail + ((size_t)h * 2 + which) * blk;
+    float *dst = (which ? M : S) + ((size_t)e * c.H + h) * blk;
+    for (int x = threadIdx.x; x < c.dk * c.dv; x += 256) {
+        const int row = x / c.dv, col = x % c.dv;
+        dst[x] = to_f32(src[vblk(c.dk, row, col)]);
+    }
+}
+
 } // namespace
+
+hipError_t launch_gather_seq_rows(const SeqRows &g, hipStream_t s) {
+    if (g.n < 1 || g.ntens < 1) return hipSuccess;
+    if (g.n > kSeqRowsPerLaunch || g.ntens > 8 || g.H < 1) return hipErrorInvalidValue;
+    for (int e = 0; e < g.n; ++e)
+        if (g.t0[e] < 0 || g.r[e] < 1 || g.r[e] > 64) return hipErrorInvalidValue;
+    for (int k = 0; k < g.ntens; ++k)
+        if (!g.t[k].full || !g.t[k].padded || g.t[k].row_bytes < 4 || g.t[k].row_bytes % 4) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(gather_seq_rows_kernel, dim3(g.n * 64 * g.H, g.ntens), dim3(64), 0, s, g);
+    return hipGetLastError();
+}
+
+hipError_t launch_states_to_f32(const void *states_full, const void *states_tail, const SeqChunks &c, float *S, float *M,
+                                hipStream_t s) {
+    if (c.n < 1) return hipSuccess;
+    if (c.n > kSeqRowsPerLaunch || !S || !M || c.H < 1 || c.N < 0) return hipErrorInvalidValue;
+    for (int e = 0; e < c.n; ++e) {
+        if (c.chunk[e] < 0 || c.chunk[e] > c.N) return hipErrorInvalidValue;
+        if (c.chunk[e] < c.N ? !states_full : !states_tail) return hipErrorInvalidValue;
+    }
+    const dim3 grid(c.n, c.H, 2), block(256);
+    if (c.dtype == 1)
+        hipLaunchKernelGGL(states_to_f32_kernel<float>, grid, block, 0, s, static_cast<const float *>(states_full),
+                           static_cast<const float *>(states_tail), c, S, M);
+    else
+        hipLaunchKernelGGL(states_to_f32_kernel<bf16_t>, grid, block, 0, s, static_cast<const bf16_t *>(states_full),
+                           static_cast<const bf16_t *>(states_tail), c, S, M);
+    return hipGetLastError();
+}
 
 hipError_t launch_set_at_tokens(float *a, float *b, float value, const SeqStarts &st, hipStream_t s) {
     if (st.n < 1) return hipSuccess;

@@ -82,3 +82,29 @@ def test_packed_sequences_as_one_stream_of_tokens(dtype, d, lens):
             assert rel_err(host(g[name])[:, sl], rb[name]) <= tol, (i, name)
         # the first token's alpha, mu multiply zero states: their gradients are exactly zero
         assert float(host(g["dalpha"])[:, cu[i]].max()) == 0.0 and float(host(g["dmu"])[:, cu[i]].min()) == 0.0, i
+
+
+@pytest.mark.parametrize("dtype,d,lens", [("f32", 64, (70, 128, 5, 191, 1, 64, 3, 2)), ("bf16", 128, (256, 33, 200, 1, 63, 65)),
+                                          ("bf16", 64, (40,) * 9), ("f32", 128, (300,)), ("f32", 64, (7, 9))])
+def test_packed_prompts_with_final_states_of_every_sequence(dtype, d, lens):
+    """Zero initial states, final states wanted (prefill of a batch of prompts): the stream form, then one batch of the
+    sequences' last chunks run again from their start states.  o and every sequence's S, M against the oracle
+    (sequences that end inside a chunk, on a chunk boundary, several sequences inside one chunk, a total length below
+    one chunk)."""
+    T, H = sum(lens), 2
+    w = synth.custom(B=1, T=T, H=H, dk=d, dv=d, dtype=dtype, seed=73, with_eta=True)
+    t = to_dev(w)
+    n = len(lens)
+    cu = np.concatenate([[0], np.cumsum(lens)]).tolist()
+    f = binding.mdn_chunk_fwd_varlen(t["q"], t["k"], t["v"], t["beta"], t["alpha"], t["mu"], cu, eta=t["eta"],
+                                     scale=w.scale)
+    torch.cuda.synchronize()
+    a = {k: (None if v is None else v.astype(np.float64)) for k, v in w.arrays.items()}
+    tol = TOL[dtype]
+    for i in range(n):
+        sl = slice(cu[i], cu[i + 1])
+        seq = {k: a[k][:, sl] for k in ("q", "k", "v", "alpha", "beta", "mu", "eta")}
+        rf = orc.forward(seq["q"], seq["k"], seq["v"], seq["alpha"], seq["beta"], seq["mu"], eta=seq["eta"], scale=w.scale)
+        assert rel_err(host(f["o"])[:, sl], rf["o"]) <= tol, (i, "o")
+        assert rel_err(host(f["S"])[i:i + 1], rf["S"]) <= tol, (i, "S")
+        assert rel_err(host(f["M"])[i:i + 1], rf["M"]) <= tol, (i, "M")
