@@ -195,16 +195,23 @@ int num_cus() {
 }
 
 int g_segments = 0; // 0: automatic
+bool g_side_stream_taken = false; // two calls run beside each other on the two streams: no segments inside them
+
+// the serial scans of a call would occupy at most half of the CUs
+bool few_scan_workgroups(const Dims &d) {
+    // workgroups of a scan launch: one per (batch*head rounded up to 8, block of 32 or 16 dv columns)
+    const bool dvb16 = d.BH * (d.dv / 32) < 192 || (d.dtype == MDN_DTYPE_F32 && d.dk == 128);
+    const int scan_wgs = (d.BH + 7) / 8 * 8 * (d.dv / (dvb16 ? 16 : 32));
+    return 2 * scan_wgs <= num_cus();
+}
 
 int segments(const Dims &d) {
     int k;
+    if (g_side_stream_taken) return 1;
     if (g_segments > 0) {
         k = g_segments;
     } else {
-        // workgroups of a scan launch: one per (batch*head rounded up to 8, block of 32 or 16 dv columns)
-        const bool dvb16 = d.BH * (d.dv / 32) < 192 || (d.dtype == MDN_DTYPE_F32 && d.dk == 128);
-        const int scan_wgs = (d.BH + 7) / 8 * 8 * (d.dv / (dvb16 ? 16 : 32));
-        k = (2 * scan_wgs <= num_cus() && d.N >= 32) ? 4 : 1;
+        k = (few_scan_workgroups(d) && d.N >= 32) ? 4 : 1;
     }
     if (k > d.N / 4) k = d.N / 4;
     return k < 1 ? 1 : (k > 16 ? 16 : k);
@@ -511,16 +518,56 @@ Dims seq_dims(const Dims &all, int len) {
 // whole batch is one sequence of shape->T tokens: one set of launches, however many and however short the sequences,
 // and no partial chunk but the last.  Open to calls that neither give nor ask for per-sequence states; the
 // gradients of the zeroed gates are zero (they multiply zero states) and are set so.
-struct PackedWs { float *alpha, *mu; void *rest; size_t total; };
+// When the stream's scans would leave half of the CUs idle (few heads), it is cut in two at the sequence start nearest
+// to its middle and the halves run beside each other, one on the caller's stream and one on the library's second
+// stream: nothing passes between them, the state is cut there anyway.
+struct PackedWs { float *alpha, *mu; void *rest, *rest2; int cut; size_t total; };
 
-PackedWs carve_packed(const Dims &d, bool backward, void *ws) {
+// index m (0 < m < n_seq) of the sequence that starts the second half, or 0: no cut
+int packed_cut(const Dims &d, const int32_t *cu, int n_seq) {
+    if (n_seq < 2 || !few_scan_workgroups(d) || d.T < 2048) return 0;
+    int best = 1;
+    for (int i = 1; i < n_seq; ++i)
+        if (llabs(2LL * cu[i] - d.T) < llabs(2LL * cu[best] - d.T)) best = i;
+    // (a lopsided cut would only take the overlap of the chunk-parallel kernels with the scans away from the long half)
+    const int small = cu[best] < d.T - cu[best] ? cu[best] : d.T - cu[best];
+    return small >= d.T / 4 ? best : 0;
+}
+
+PackedWs carve_packed(const Dims &d, const int32_t *cu, int n_seq, bool backward, void *ws) {
     Carver c(ws);
-    PackedWs w;
+    PackedWs w = {};
     w.alpha = static_cast<float *>(c.take((size_t)d.T * d.H * sizeof(float)));
     w.mu = static_cast<float *>(c.take((size_t)d.T * d.H * sizeof(float)));
-    w.rest = ws ? static_cast<char *>(ws) + c.off : nullptr;
-    w.total = c.off + (backward ? bwd_ws_total(d, d.T % 64) : fwd_ws_total(d, d.T % 64));
+    w.cut = packed_cut(d, cu, n_seq);
+    auto need = [&](int len) {
+        const Dims p = seq_dims(d, len);
+        return backward ? bwd_ws_total(p, len % 64) : fwd_ws_total(p, len % 64);
+    };
+    if (w.cut) {
+        w.rest = c.take(need(cu[w.cut]));
+        w.rest2 = c.take(need(d.T - cu[w.cut]));
+    } else {
+        w.rest = c.take(need(d.T));
+    }
+    w.total = c.off;
     return w;
+}
+
+// the two halves beside each other: first(stream), second(stream) are the two calls
+template <typename F1, typename F2> int run_beside(hipStream_t s, F1 &&first, F2 &&second) {
+    constexpr int E0 = 30, E1 = 31; // (the events below these belong to the segments of a single call)
+    Side *sd = side(E1 + 1);
+    if (!sd) return MDN_ERR_LAUNCH;
+    if (hipEventRecord(sd->ev[E0], s) != hipSuccess || hipStreamWaitEvent(sd->stream, sd->ev[E0], 0) != hipSuccess)
+        return MDN_ERR_LAUNCH; // whatever the caller's stream holds so far comes first
+    g_side_stream_taken = true;
+    int rc = first(s);
+    if (!rc) rc = second(sd->stream);
+    g_side_stream_taken = false;
+    if (hipEventRecord(sd->ev[E1], sd->stream) != hipSuccess || hipStreamWaitEvent(s, sd->ev[E1], 0) != hipSuccess)
+        return MDN_ERR_LAUNCH;
+    return rc;
 }
 
 // value at the first tokens of sequences 1 .. n_seq-1 of a (and b)
@@ -769,7 +816,7 @@ int mdn_workspace_bytes_varlen(const mdn_shape *shape, const int32_t *cu_seqlens
         need = b > need ? b : need;
     }
     // (either way of running the batch may be taken: see mdn_chunk_fwd_varlen)
-    size_t packed = carve_packed(d, which == MDN_WS_BWD, nullptr).total;
+    size_t packed = carve_packed(d, cu_seqlens, n_seq, which == MDN_WS_BWD, nullptr).total;
     if (which == MDN_WS_FWD) {
         const size_t pf = carve_packed_final(d, n_seq, nullptr).total;
         packed = pf > packed ? pf : packed;
@@ -796,11 +843,20 @@ int mdn_chunk_fwd_varlen(const mdn_shape *shape, const int32_t *cu_seqlens, int3
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (!S0 && !M0 && !S_final && !M_final) {
         // no per-sequence states in or out: the batch as one stream of tokens
-        const PackedWs w = carve_packed(d, false, workspace);
+        const PackedWs w = carve_packed(d, cu_seqlens, n_seq, false, workspace);
         rc = packed_gates(d, cu_seqlens, n_seq, alpha, mu, w, s);
         if (rc) return rc;
-        FwdCall c = {q, k, v, beta, w.alpha, w.mu, eta, nullptr, nullptr, o, nullptr, nullptr, vt_saved, nullptr, nullptr};
-        return fwd_any(d, d.T % 64, c, w.rest, s);
+        const size_t es = elem_size(d), rk = (size_t)d.H * d.dk * es, rv = (size_t)d.H * d.dv * es, rg = (size_t)d.H * 4;
+        auto part = [&](size_t t0, int len, void *ws, hipStream_t st) {
+            FwdCall c = {at_token(q, t0, rk), at_token(k, t0, rk), at_token(v, t0, rv), at_token(beta, t0, rg),
+                         at_token(w.alpha, t0, rg), at_token(w.mu, t0, rg), at_token(eta, t0, rg), nullptr, nullptr,
+                         at_token(o, t0, rv), nullptr, nullptr, at_token(vt_saved, t0, rv), nullptr, nullptr};
+            return fwd_any(seq_dims(d, len), len % 64, c, ws, st);
+        };
+        if (!w.cut) return part(0, d.T, w.rest, s);
+        const int t1 = cu_seqlens[w.cut];
+        return run_beside(s, [&](hipStream_t st) { return part(0, t1, w.rest, st); },
+                          [&](hipStream_t st) { return part((size_t)t1, d.T - t1, w.rest2, st); });
     }
     if (!S0 && !M0 && S_final && M_final) {
         // zero initial states, final states of every sequence wanted: the stream, then the sequences' last chunks
@@ -849,12 +905,25 @@ int mdn_chunk_bwd_varlen(const mdn_shape *shape, const int32_t *cu_seqlens, int3
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (!S0 && !M0 && !dS_final && !dM_final && !dS0 && !dM0) {
         // no per-sequence states or state adjoints in or out: the batch as one stream of tokens
-        const PackedWs w = carve_packed(d, true, workspace);
+        const PackedWs w = carve_packed(d, cu_seqlens, n_seq, true, workspace);
         rc = packed_gates(d, cu_seqlens, n_seq, alpha, mu, w, s);
         if (rc) return rc;
-        BwdCall c = {q, k, v, beta, w.alpha, w.mu, eta, nullptr, nullptr, vt_saved, nullptr, nullptr, dO, nullptr, nullptr,
-                     dq, dk, dv, dbeta, dalpha, dmu, deta, nullptr, nullptr};
-        rc = bwd_any(d, d.T % 64, c, w.rest, s);
+        const size_t es = elem_size(d), rk = (size_t)d.H * d.dk * es, rv = (size_t)d.H * d.dv * es, rg = (size_t)d.H * 4;
+        auto part = [&](size_t t0, int len, void *ws, hipStream_t st) {
+            BwdCall c = {at_token(q, t0, rk), at_token(k, t0, rk), at_token(v, t0, rv), at_token(beta, t0, rg),
+                         at_token(w.alpha, t0, rg), at_token(w.mu, t0, rg), at_token(eta, t0, rg), nullptr, nullptr,
+                         at_token(vt_saved, t0, rv), nullptr, nullptr, at_token(dO, t0, rv), nullptr, nullptr,
+                         at_token(dq, t0, rk), at_token(dk, t0, rk), at_token(dv, t0, rv), at_token(dbeta, t0, rg),
+                         at_token(dalpha, t0, rg), at_token(dmu, t0, rg), at_token(deta, t0, rg), nullptr, nullptr};
+            return bwd_any(seq_dims(d, len), len % 64, c, ws, st);
+        };
+        if (!w.cut) {
+            rc = part(0, d.T, w.rest, s);
+        } else {
+            const int t1 = cu_seqlens[w.cut];
+            rc = run_beside(s, [&](hipStream_t st) { return part(0, t1, w.rest, st); },
+                            [&](hipStream_t st) { return part((size_t)t1, d.T - t1, w.rest2, st); });
+        }
         if (rc) return rc;
         return set_at_sequence_starts(d, cu_seqlens, n_seq, dalpha, dmu, 0.f, s);
     }

@@ -87,6 +87,11 @@ struct RecurrentArgs {
 // mode 0: forward operands, 1: reverse-pass operands, 2: both
 hipError_t launch_intra(const Dims &d, int mode, const IntraArgs &a, hipStream_t s);
 hipError_t launch_scan_fwd(const Dims &d, const ScanFwdArgs &a, hipStream_t s);
+// Dynamic LDS bytes that keep a second workgroup of `kernel` off a CU (0 if one workgroup fills more than half of the
+// 160 KB already).  For launches with fewer workgroups than CUs: the dispatcher otherwise puts two of them on one CU
+// and leaves other CUs empty, and two scan workgroups that share a CU take turns at everything.
+size_t lds_bytes_for_one_workgroup_per_cu(const void *kernel);
+
 // whether that launch reads a.KT (32-bit storage; 16-bit storage forms K^T out of the k rows in LDS)
 bool scan_fwd_reads_KT(const Dims &d);
 hipError_t launch_rebuild(const Dims &d, const RebuildArgs &a, hipStream_t s);

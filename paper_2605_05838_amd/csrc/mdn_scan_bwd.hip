@@ -274,7 +274,10 @@ template <typename T, int DK, int DV, int DVB>
 hipError_t launch_t(const Dims &d, const ScanBwdArgs &a, hipStream_t s) {
     constexpr int G = DV / DVB;
     dim3 grid(((d.BH + 7) / 8) * 8 * G), block(kThreads);
-    hipLaunchKernelGGL((scan_bwd_kernel<T, DK, DV, DVB>), grid, block, 0, s, d, a);
+    static const size_t spread =
+        lds_bytes_for_one_workgroup_per_cu(reinterpret_cast<const void *>(&scan_bwd_kernel<T, DK, DV, DVB>));
+    const size_t dyn = grid.x <= 256 ? spread : 0; // fewer workgroups than CUs: one per CU
+    hipLaunchKernelGGL((scan_bwd_kernel<T, DK, DV, DVB>), grid, block, dyn, s, d, a);
     return hipGetLastError();
 }
 

@@ -351,7 +351,10 @@ template <typename T, int DK, int DV, int DVB, bool REBUILD>
 hipError_t launch_scan_t(const Dims &d, const ScanFwdArgs &a, hipStream_t s) {
     constexpr int G = DV / DVB;
     dim3 grid(((d.BH + 7) / 8) * 8 * G), block(kThreads);
-    hipLaunchKernelGGL((scan_fwd_kernel<T, DK, DV, DVB, REBUILD>), grid, block, 0, s, d, a);
+    static const size_t spread = lds_bytes_for_one_workgroup_per_cu(
+        reinterpret_cast<const void *>(&scan_fwd_kernel<T, DK, DV, DVB, REBUILD>));
+    const size_t dyn = grid.x <= 256 ? spread : 0; // fewer workgroups than CUs: one per CU
+    hipLaunchKernelGGL((scan_fwd_kernel<T, DK, DV, DVB, REBUILD>), grid, block, dyn, s, d, a);
     return hipGetLastError();
 }
 
@@ -376,6 +379,13 @@ template <bool REBUILD> hipError_t dispatch_scan(const Dims &d, const ScanFwdArg
 }
 
 } // namespace
+
+size_t lds_bytes_for_one_workgroup_per_cu(const void *kernel) {
+    hipFuncAttributes fa;
+    if (hipFuncGetAttributes(&fa, kernel) != hipSuccess) return 0;
+    const size_t half = 80 * 1024, want = half + 1024; // two workgroups of more than 80 KB do not fit the 160 KB of a CU
+    return fa.sharedSizeBytes > half ? 0 : want - fa.sharedSizeBytes;
+}
 
 hipError_t launch_scan_fwd(const Dims &d, const ScanFwdArgs &a, hipStream_t s) { return dispatch_scan<false>(d, a, s); }
 

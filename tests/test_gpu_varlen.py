@@ -50,11 +50,13 @@ def test_packed_sequences_forward_and_backward(dtype, d, lens):
 
 
 @pytest.mark.parametrize("dtype,d,lens", [("f32", 64, (70, 128, 5, 191, 1, 64)), ("bf16", 128, (256, 33, 200, 1, 63, 65)),
-                                          ("bf16", 64, (40,) * 9), ("f32", 128, (300,))])
+                                          ("bf16", 64, (40,) * 9), ("f32", 128, (300,)),
+                                          ("f32", 64, (700, 333, 64, 1, 900, 250)), ("bf16", 128, (1030, 1100))])
 def test_packed_sequences_as_one_stream_of_tokens(dtype, d, lens):
     """No per-sequence states in or out: the library runs the batch as one stream with alpha = mu = 0 at the sequence
     starts.  Every sequence must come out as the oracle computes it by itself from zero states (sequence starts inside
-    chunks, on chunk boundaries, sequences of one token), and the caller's alpha, mu must be left as they were."""
+    chunks, on chunk boundaries, sequences of one token; the two longest batches are cut in two halves that run beside
+    each other on two streams), and the caller's alpha, mu must be left as they were."""
     T, H = sum(lens), 3
     w = synth.custom(B=1, T=T, H=H, dk=d, dv=d, dtype=dtype, seed=72, with_eta=True, backward=True)
     t = to_dev(w)
