@@ -602,23 +602,39 @@ Dims rows_dims(const Dims &d, int n_seq) {
     return t;
 }
 
+// one half of the stream (or all of it): sequences [seq0, seq1), tokens [t0, t0 + len)
+struct StreamPiece {
+    int seq0, seq1, t0, len;
+    void *states; // its chunk-start states (full chunks, then the partial chunk's block)
+    void *rest;   // its forward workspace
+};
+
 struct PackedFinalWs {
     PackedWs g;       // gate copies
-    void *states;     // chunk-start states of the stream (full chunks, then the partial chunk's block)
+    int npieces;
+    StreamPiece piece[2];
     void *k, *v, *o;  // padded rows [n_seq, 64, H, *]
     float *beta, *alpha, *mu, *eta, *S0, *M0;
-    void *rest_stream, *rest_rows;
+    void *rest_rows;
     size_t total;
 };
 
-PackedFinalWs carve_packed_final(const Dims &d, int n_seq, void *ws) {
+PackedFinalWs carve_packed_final(const Dims &d, const int32_t *cu, int n_seq, void *ws) {
     const size_t es = elem_size(d), rows = (size_t)n_seq * 64 * d.H, st = (size_t)n_seq * d.H * d.dk * d.dv * sizeof(float);
     const Dims dr = rows_dims(d, n_seq);
     Carver c(ws);
     PackedFinalWs w = {};
     w.g.alpha = static_cast<float *>(c.take((size_t)d.T * d.H * sizeof(float)));
     w.g.mu = static_cast<float *>(c.take((size_t)d.T * d.H * sizeof(float)));
-    w.states = c.take(saved_states_part(d) + (d.T % 64 ? saved_states_part(tail_dims(d)) : 0));
+    const int cut = packed_cut(d, cu, n_seq);
+    w.npieces = cut ? 2 : 1;
+    w.piece[0] = {0, cut ? cut : n_seq, 0, cut ? cu[cut] : d.T, nullptr, nullptr};
+    w.piece[1] = {cut, n_seq, cut ? cu[cut] : 0, cut ? d.T - cu[cut] : 0, nullptr, nullptr};
+    for (int p = 0; p < w.npieces; ++p) {
+        const Dims dp = seq_dims(d, w.piece[p].len);
+        w.piece[p].states = c.take(saved_states_part(dp) + (dp.T % 64 ? saved_states_part(tail_dims(dp)) : 0));
+        w.piece[p].rest = c.take(fwd_ws_total(dp, dp.T % 64));
+    }
     w.k = c.take(rows * d.dk * es);
     w.v = c.take(rows * d.dv * es);
     w.o = c.take(rows * d.dv * es);
@@ -628,7 +644,6 @@ PackedFinalWs carve_packed_final(const Dims &d, int n_seq, void *ws) {
     w.eta = static_cast<float *>(c.take(rows * 4));
     w.S0 = static_cast<float *>(c.take(st));
     w.M0 = static_cast<float *>(c.take(st));
-    w.rest_stream = c.take(fwd_ws_total(d, d.T % 64));
     w.rest_rows = c.take(fwd_ws_total(dr, 0));
     w.total = c.off;
     return w;
@@ -637,35 +652,39 @@ PackedFinalWs carve_packed_final(const Dims &d, int n_seq, void *ws) {
 int packed_final_states(const Dims &d, const int32_t *cu, int n_seq, const FwdCall &stream, const PackedFinalWs &w,
                         float *S_final, float *M_final, hipStream_t s) {
     const size_t es = elem_size(d), st = (size_t)d.H * d.dk * d.dv;
-    for (int i0 = 0; i0 < n_seq; i0 += kSeqRowsPerLaunch) {
-        const int n = n_seq - i0 < kSeqRowsPerLaunch ? n_seq - i0 : kSeqRowsPerLaunch;
-        const size_t rows0 = (size_t)i0 * 64 * d.H;
-        SeqRows g = {};
-        SeqChunks sc = {};
-        g.n = sc.n = n; g.H = sc.H = d.H;
-        sc.N = d.N; sc.dk = d.dk; sc.dv = d.dv; sc.dtype = d.dtype;
-        for (int e = 0; e < n; ++e) {
-            const int end = cu[i0 + e + 1], chunk = (end - 1) / 64;
-            sc.chunk[e] = chunk;
-            g.t0[e] = chunk * 64;
-            g.r[e] = end - chunk * 64;
+    for (int p = 0; p < w.npieces; ++p) {
+        const StreamPiece &pc = w.piece[p];
+        const Dims dp = seq_dims(d, pc.len); // (the piece's chunks count from its own first token)
+        for (int i0 = pc.seq0; i0 < pc.seq1; i0 += kSeqRowsPerLaunch) {
+            const int n = pc.seq1 - i0 < kSeqRowsPerLaunch ? pc.seq1 - i0 : kSeqRowsPerLaunch;
+            const size_t rows0 = (size_t)i0 * 64 * d.H;
+            SeqRows g = {};
+            SeqChunks sc = {};
+            g.n = sc.n = n; g.H = sc.H = d.H;
+            sc.N = dp.N; sc.dk = d.dk; sc.dv = d.dv; sc.dtype = d.dtype;
+            for (int e = 0; e < n; ++e) {
+                const int end = cu[i0 + e + 1] - pc.t0, chunk = (end - 1) / 64;
+                sc.chunk[e] = chunk;
+                g.t0[e] = pc.t0 + chunk * 64;
+                g.r[e] = end - chunk * 64;
+            }
+            auto add = [&](const void *full, void *padded, size_t row_bytes, float pad) {
+                if (!full) return;
+                TailTensor &t = g.t[g.ntens++];
+                t.full = full; t.padded = static_cast<char *>(padded) + rows0 * row_bytes; t.row_bytes = (int)row_bytes;
+                memcpy(&t.pad_word, &pad, 4);
+            };
+            add(stream.k, w.k, d.dk * es, 0.f);
+            add(stream.v, w.v, d.dv * es, 0.f);
+            add(stream.beta, w.beta, 4, 0.f);
+            add(stream.alpha, w.alpha, 4, 1.f);
+            add(stream.mu, w.mu, 4, 1.f);
+            add(stream.eta, w.eta, 4, 1.f);
+            if (launch_gather_seq_rows(g, s) != hipSuccess) return MDN_ERR_LAUNCH;
+            if (launch_states_to_f32(pc.states, offset(pc.states, saved_states_part(dp)), sc, w.S0 + (size_t)i0 * st,
+                                     w.M0 + (size_t)i0 * st, s) != hipSuccess)
+                return MDN_ERR_LAUNCH;
         }
-        auto add = [&](const void *full, void *padded, size_t row_bytes, float pad) {
-            if (!full) return;
-            TailTensor &t = g.t[g.ntens++];
-            t.full = full; t.padded = static_cast<char *>(padded) + rows0 * row_bytes; t.row_bytes = (int)row_bytes;
-            memcpy(&t.pad_word, &pad, 4);
-        };
-        add(stream.k, w.k, d.dk * es, 0.f);
-        add(stream.v, w.v, d.dv * es, 0.f);
-        add(stream.beta, w.beta, 4, 0.f);
-        add(stream.alpha, w.alpha, 4, 1.f);
-        add(stream.mu, w.mu, 4, 1.f);
-        add(stream.eta, w.eta, 4, 1.f);
-        if (launch_gather_seq_rows(g, s) != hipSuccess) return MDN_ERR_LAUNCH;
-        if (launch_states_to_f32(w.states, offset(w.states, saved_states_part(d)), sc, w.S0 + (size_t)i0 * st,
-                                 w.M0 + (size_t)i0 * st, s) != hipSuccess)
-            return MDN_ERR_LAUNCH;
     }
     // (the rows' outputs o are of no use: q is given the k rows, o a scratch tensor)
     const Dims dr = rows_dims(d, n_seq);
@@ -818,7 +837,7 @@ int mdn_workspace_bytes_varlen(const mdn_shape *shape, const int32_t *cu_seqlens
     // (either way of running the batch may be taken: see mdn_chunk_fwd_varlen)
     size_t packed = carve_packed(d, cu_seqlens, n_seq, which == MDN_WS_BWD, nullptr).total;
     if (which == MDN_WS_FWD) {
-        const size_t pf = carve_packed_final(d, n_seq, nullptr).total;
+        const size_t pf = carve_packed_final(d, cu_seqlens, n_seq, nullptr).total;
         packed = pf > packed ? pf : packed;
     }
     *bytes_out = packed > need ? packed : need;
@@ -860,13 +879,24 @@ int mdn_chunk_fwd_varlen(const mdn_shape *shape, const int32_t *cu_seqlens, int3
     }
     if (!S0 && !M0 && S_final && M_final) {
         // zero initial states, final states of every sequence wanted: the stream, then the sequences' last chunks
-        const PackedFinalWs w = carve_packed_final(d, n_seq, workspace);
+        const PackedFinalWs w = carve_packed_final(d, cu_seqlens, n_seq, workspace);
         rc = packed_gates(d, cu_seqlens, n_seq, alpha, mu, w.g, s);
         if (rc) return rc;
-        FwdCall c = {q, k, v, beta, w.g.alpha, w.g.mu, eta, nullptr, nullptr, o, nullptr, nullptr, vt_saved, w.states, nullptr};
-        rc = fwd_any(d, d.T % 64, c, w.rest_stream, s);
+        const size_t es = elem_size(d), rk = (size_t)d.H * d.dk * es, rv = (size_t)d.H * d.dv * es, rg = (size_t)d.H * 4;
+        auto part = [&](const StreamPiece &pc, hipStream_t st) {
+            const size_t t0 = (size_t)pc.t0;
+            FwdCall c = {at_token(q, t0, rk), at_token(k, t0, rk), at_token(v, t0, rv), at_token(beta, t0, rg),
+                         at_token(w.g.alpha, t0, rg), at_token(w.g.mu, t0, rg), at_token(eta, t0, rg), nullptr, nullptr,
+                         at_token(o, t0, rv), nullptr, nullptr, at_token(vt_saved, t0, rv), pc.states, nullptr};
+            return fwd_any(seq_dims(d, pc.len), pc.len % 64, c, pc.rest, st);
+        };
+        rc = w.npieces == 1 ? part(w.piece[0], s)
+                            : run_beside(s, [&](hipStream_t st) { return part(w.piece[0], st); },
+                                         [&](hipStream_t st) { return part(w.piece[1], st); });
         if (rc) return rc;
-        return packed_final_states(d, cu_seqlens, n_seq, c, w, S_final, M_final, s);
+        const FwdCall whole = {q, k, v, beta, w.g.alpha, w.g.mu, eta, nullptr, nullptr, o, nullptr, nullptr, vt_saved, nullptr,
+                               nullptr};
+        return packed_final_states(d, cu_seqlens, n_seq, whole, w, S_final, M_final, s);
     }
     const size_t es = elem_size(d), rk = (size_t)d.H * d.dk * es, rv = (size_t)d.H * d.dv * es, rg = (size_t)d.H * 4;
     const size_t st = (size_t)d.H * d.dk * d.dv * sizeof(float);

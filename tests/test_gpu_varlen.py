@@ -87,12 +87,13 @@ def test_packed_sequences_as_one_stream_of_tokens(dtype, d, lens):
 
 
 @pytest.mark.parametrize("dtype,d,lens", [("f32", 64, (70, 128, 5, 191, 1, 64, 3, 2)), ("bf16", 128, (256, 33, 200, 1, 63, 65)),
-                                          ("bf16", 64, (40,) * 9), ("f32", 128, (300,)), ("f32", 64, (7, 9))])
+                                          ("bf16", 64, (40,) * 9), ("f32", 128, (300,)), ("f32", 64, (7, 9)),
+                                          ("f32", 64, (700, 333, 64, 1, 900, 250)), ("bf16", 128, (1030, 1100))])
 def test_packed_prompts_with_final_states_of_every_sequence(dtype, d, lens):
     """Zero initial states, final states wanted (prefill of a batch of prompts): the stream form, then one batch of the
     sequences' last chunks run again from their start states.  o and every sequence's S, M against the oracle
     (sequences that end inside a chunk, on a chunk boundary, several sequences inside one chunk, a total length below
-    one chunk)."""
+    one chunk, batches long enough to be cut in two halves that run beside each other)."""
     T, H = sum(lens), 2
     w = synth.custom(B=1, T=T, H=H, dk=d, dv=d, dtype=dtype, seed=73, with_eta=True)
     t = to_dev(w)
