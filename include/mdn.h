@@ -59,7 +59,7 @@ enum {
     MDN_ERR_DEVICE = -7     /* the current device is not a gfx950 GPU */
 };
 
-enum { MDN_WS_FWD = 0, MDN_WS_BWD = 1 };
+enum { MDN_WS_FWD = 0, MDN_WS_BWD = 1, MDN_WS_BWD_STATE_ADJOINTS = 2 };
 
 typedef struct mdn_shape {
     int32_t B, T, H;  /* batch, sequence length, heads */
@@ -70,7 +70,8 @@ typedef struct mdn_shape {
 } mdn_shape;
 
 /* Bytes of scratch `workspace` that mdn_chunk_fwd (which = MDN_WS_FWD) or mdn_chunk_bwd
- * (MDN_WS_BWD) needs for this shape.  Host-only; touches no device. */
+ * (MDN_WS_BWD; MDN_WS_BWD_STATE_ADJOINTS for a call that passes dS_final or dM_final) needs for this shape.
+ * Host-only; touches no device. */
 int mdn_workspace_bytes(const mdn_shape *shape, int which, size_t *bytes_out);
 
 /* Bytes of the optional `states_saved` buffer: the states S, M at the start of every chunk in the storage
@@ -113,7 +114,11 @@ int mdn_chunk_fwd(const mdn_shape *shape, const void *q, const void *k, const vo
  *   out: dq, dk [B,T,H,dk], dv [B,T,H,dv] (storage dtype); dbeta, dalpha, dmu [B,T,H] fp32;
  *        deta [B,T,H] fp32 or NULL; dS0, dM0 [B,H,dk,dv] fp32 or NULL.
  *        Gradients are with respect to the linear gate values.
- *   workspace: at least mdn_workspace_bytes(MDN_WS_BWD).
+ *   workspace: at least mdn_workspace_bytes(MDN_WS_BWD); with dS_final or dM_final given,
+ *        mdn_workspace_bytes(MDN_WS_BWD_STATE_ADJOINTS).  Adjoints that enter from outside can be large against
+ *        everything dO puts into the states, so with 16-bit storage such a call carries the chunk states and their
+ *        adjoints between its kernels as bf16 pairs (value + rounding remainder) and reconstructs the states from
+ *        V~ even when states_saved is given (the forward's copy has no remainders).
  */
 int mdn_chunk_bwd(const mdn_shape *shape, const void *q, const void *k, const void *v, const float *beta,
                   const float *alpha, const float *mu, const float *eta, const float *S0, const float *M0,

@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmdn_hip.so")
 
 MDN_DTYPE_BF16, MDN_DTYPE_F32 = 0, 1
-MDN_WS_FWD, MDN_WS_BWD = 0, 1
+MDN_WS_FWD, MDN_WS_BWD, MDN_WS_BWD_STATE_ADJOINTS = 0, 1, 2
 
 EXPORTS = ("mdn_version", "mdn_strerror", "mdn_workspace_bytes", "mdn_saved_states_bytes",
            "mdn_saved_operands_bytes", "mdn_chunk_fwd",
@@ -223,7 +223,8 @@ def mdn_chunk_bwd(q, k, v, beta, alpha, mu, vt, dO, eta=None, S0=None, M0=None, 
     deta = get("deta", (B, T, H), torch.float32) if want_deta else None
     dS0 = get("dS0", (B, H, dk, dv_), torch.float32) if want_dstates else None
     dM0 = get("dM0", (B, H, dk, dv_), torch.float32) if want_dstates else None
-    workspace, wbytes = _workspace(shape, MDN_WS_BWD, workspace, dev)
+    which = MDN_WS_BWD if dS_final is None and dM_final is None else MDN_WS_BWD_STATE_ADJOINTS
+    workspace, wbytes = _workspace(shape, which, workspace, dev)
     rc = lib.mdn_chunk_bwd(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _f32(beta, "beta"), _f32(alpha, "alpha"),
                            _f32(mu, "mu"), _f32(eta, "eta"), _f32(S0, "S0"), _f32(M0, "M0"), _ptr(vt), _ptr(states),
                            _ptr(operands), _ptr(dO), _f32(dS_final, "dS_final"), _f32(dM_final, "dM_final"), _ptr(dq), _ptr(dk_t),

@@ -76,9 +76,11 @@ RevOps carve_rev(const Dims &d, void *p) {
     return w;
 }
 
-struct BwdWs { RevOps ops; void *dstates, *states; float *carryS, *carryM; size_t total; };
+struct BwdWs { RevOps ops; void *dstates, *states, *dstates_lo, *states_lo; float *carryS, *carryM; size_t total; };
 
-BwdWs carve_bwd(const Dims &d, void *ws) {
+// `precise`: room for the rounding remainders of the two state tensors as well (16-bit storage, calls that bring
+// adjoints of the final states in; see precise_call)
+BwdWs carve_bwd(const Dims &d, void *ws, bool precise) {
     const size_t es = d.dtype == MDN_DTYPE_F32 ? 4 : 2, nb = (size_t)d.BH * d.N;
     BwdWs w;
     w.ops = carve_rev(d, ws);
@@ -86,6 +88,8 @@ BwdWs carve_bwd(const Dims &d, void *ws) {
     c.off = w.ops.total;
     w.dstates = c.take(nb * 2 * d.dk * d.dv * es);
     w.states = c.take(nb * 2 * d.dk * d.dv * es);
+    w.dstates_lo = precise ? c.take(nb * 2 * d.dk * d.dv * es) : nullptr;
+    w.states_lo = precise ? c.take(nb * 2 * d.dk * d.dv * es) : nullptr;
     w.carryS = static_cast<float *>(c.take((size_t)d.BH * d.dk * d.dv * sizeof(float)));
     w.carryM = static_cast<float *>(c.take((size_t)d.BH * d.dk * d.dv * sizeof(float)));
     w.total = c.off;
@@ -312,9 +316,17 @@ struct Prepared {
     const void *states;
 };
 
+// Adjoints of the final states that come in from outside can be large against everything dO puts into the states;
+// the sums of dk dv products that they enter (the state traces, the products with V~) then carry the 16-bit storage
+// rounding of the chunk states and chunk adjoints at full weight.  Such a call keeps the rounding remainders of both
+// tensors as well (which also means it reconstructs the states rather than taking the forward's 16-bit copy).
+bool precise_call(const Dims &d, const BwdCall &c) {
+    return d.dtype == MDN_DTYPE_BF16 && (c.dS_final || c.dM_final);
+}
+
 // S_after, M_after (or null): the states after the last chunk, which the reconstruction can hand on
 int bwd_prepare(const Dims &d, const BwdCall &c, const BwdWs &w, float *S_after, float *M_after, hipStream_t s,
-                Prepared *out) {
+                Prepared *out, bool precise) {
     int rc;
     // chunk-local operands in the layouts of the reverse pass: kept by the forward, or recomputed
     out->ro = w.ops;
@@ -328,11 +340,11 @@ int bwd_prepare(const Dims &d, const BwdCall &c, const BwdWs &w, float *S_after,
         if (rc) return rc;
     }
     // chunk-start states: given by the forward, or reconstructed from V~
-    out->states = c.states_saved;
+    out->states = precise ? nullptr : c.states_saved;
     if (!out->states) {
         RebuildArgs ra = {};
         ra.coef = out->ro.coef; ra.k = c.k; ra.KT = out->ro.KT; ra.vt_saved = c.vt_saved; ra.S0 = c.S0; ra.M0 = c.M0;
-        ra.states = w.states; ra.S_final = S_after; ra.M_final = M_after;
+        ra.states = w.states; ra.states_lo = precise ? w.states_lo : nullptr; ra.S_final = S_after; ra.M_final = M_after;
         rc = timed(MDN_KERNEL_REBUILD, s, [&] { return launch_rebuild(d, ra, s); });
         if (rc) return rc;
         out->states = w.states;
@@ -340,17 +352,18 @@ int bwd_prepare(const Dims &d, const BwdCall &c, const BwdWs &w, float *S_after,
     return MDN_OK;
 }
 
-int bwd_run(const Dims &d, const BwdCall &c, const BwdWs &w, const Prepared &p, hipStream_t s) {
+int bwd_run(const Dims &d, const BwdCall &c, const BwdWs &w, const Prepared &p, hipStream_t s, bool precise) {
     int rc;
     const RevOps &ro = p.ro;
     ScanBwdArgs sb = {};
     sb.k = c.k; sb.dO = c.dO; sb.coef = ro.coef; sb.QT = ro.QT; sb.KT = ro.KT; sb.BmT = ro.BmT;
     sb.TmT = ro.TmT; sb.dS_final = c.dS_final; sb.dM_final = c.dM_final; sb.dv = c.dv; sb.dstates = w.dstates;
-    sb.dS0 = c.dS0; sb.dM0 = c.dM0;
+    sb.dS0 = c.dS0; sb.dM0 = c.dM0; sb.dstates_lo = precise ? w.dstates_lo : nullptr;
     GradArgs ga = {};
     ga.q = c.q; ga.k = c.k; ga.alpha = c.alpha; ga.beta = c.beta; ga.mu = c.mu; ga.eta = c.eta;
     ga.vt_saved = c.vt_saved; ga.dO = c.dO; ga.dv = c.dv; ga.KT = ro.KT; ga.QT = ro.QT;
     ga.states = p.states; ga.dstates = w.dstates;
+    ga.states_lo = precise ? w.states_lo : nullptr; ga.dstates_lo = precise ? w.dstates_lo : nullptr;
     ga.dq = c.dq; ga.dk = c.dk; ga.dalpha = c.dalpha; ga.dbeta = c.dbeta; ga.dmu = c.dmu; ga.deta = c.deta;
     const int nseg = segments(d);
     if (nseg == 1) {
@@ -384,9 +397,10 @@ size_t fwd_ws_total(const Dims &d, int r) {
     if (r == 0) return carve_fwd(d, nullptr).total;
     return carve_fwd(d, nullptr).total + carve_fwd(tail_dims(d), nullptr).total + carve_tail(d, false, nullptr).total;
 }
-size_t bwd_ws_total(const Dims &d, int r) {
-    if (r == 0) return carve_bwd(d, nullptr).total;
-    return carve_bwd(d, nullptr).total + carve_bwd(tail_dims(d), nullptr).total + carve_tail(d, true, nullptr).total;
+size_t bwd_ws_total(const Dims &d, int r, bool precise) {
+    if (r == 0) return carve_bwd(d, nullptr, precise).total;
+    return carve_bwd(d, nullptr, precise).total + carve_bwd(tail_dims(d), nullptr, precise).total +
+           carve_tail(d, true, nullptr).total;
 }
 
 // The forward over a sequence of any length: d.N full chunks and r = T % 64 tokens of a partial one.
@@ -434,21 +448,22 @@ int fwd_any(const Dims &d, int r, FwdCall c, void *workspace, hipStream_t s) {
 int bwd_any(const Dims &d, int r, BwdCall c, void *workspace, hipStream_t s) {
     int rc;
     const BwdCall u = c; // the caller's pointers (c is redirected for the full chunks below)
-    const BwdWs w = carve_bwd(d, workspace);
+    const bool precise = precise_call(d, u);
+    const BwdWs w = carve_bwd(d, workspace, precise);
     Prepared pm;
     if (r == 0) {
-        rc = bwd_prepare(d, c, w, nullptr, nullptr, s, &pm);
-        return rc ? rc : bwd_run(d, c, w, pm, s);
+        rc = bwd_prepare(d, c, w, nullptr, nullptr, s, &pm, precise);
+        return rc ? rc : bwd_run(d, c, w, pm, s, precise);
     }
 
     // the partial chunk comes last in the sequence, so first in the reverse pass; what it needs from the full
     // chunks (the states they leave) is ready after their preparation step
     const Dims dt = tail_dims(d);
-    const BwdWs wt = carve_bwd(dt, offset(workspace, w.total));
+    const BwdWs wt = carve_bwd(dt, offset(workspace, w.total), precise);
     const TailBufs tb = carve_tail(d, true, offset(workspace, w.total + wt.total));
     const size_t es = elem_size(d);
     if (d.N > 0) {
-        rc = bwd_prepare(d, c, w, tb.S_mid, tb.M_mid, s, &pm);
+        rc = bwd_prepare(d, c, w, tb.S_mid, tb.M_mid, s, &pm, precise);
         if (rc) return rc;
     }
     TailList in(d, r);
@@ -471,14 +486,14 @@ int bwd_any(const Dims &d, int r, BwdCall c, void *workspace, hipStream_t s) {
                   u.dS_final, u.dM_final, tb.dq, tb.dk, tb.dv, tb.dbeta, tb.dalpha, tb.dmu, u.deta ? tb.deta : nullptr,
                   d.N > 0 ? tb.dS_mid : u.dS0, d.N > 0 ? tb.dM_mid : u.dM0};
     Prepared pt;
-    rc = bwd_prepare(dt, ct, wt, nullptr, nullptr, s, &pt);
+    rc = bwd_prepare(dt, ct, wt, nullptr, nullptr, s, &pt, precise);
     if (rc) return rc;
-    rc = bwd_run(dt, ct, wt, pt, s);
+    rc = bwd_run(dt, ct, wt, pt, s, precise);
     if (rc) return rc;
     if (d.N > 0) {
         c.dS_final = tb.dS_mid;
         c.dM_final = tb.dM_mid;
-        rc = bwd_run(d, c, w, pm, s);
+        rc = bwd_run(d, c, w, pm, s, precise);
         if (rc) return rc;
     }
     TailList out(d, r);
@@ -542,7 +557,7 @@ PackedWs carve_packed(const Dims &d, const int32_t *cu, int n_seq, bool backward
     w.cut = packed_cut(d, cu, n_seq);
     auto need = [&](int len) {
         const Dims p = seq_dims(d, len);
-        return backward ? bwd_ws_total(p, len % 64) : fwd_ws_total(p, len % 64);
+        return backward ? bwd_ws_total(p, len % 64, false) : fwd_ws_total(p, len % 64);
     };
     if (w.cut) {
         w.rest = c.take(need(cu[w.cut]));
@@ -753,7 +768,8 @@ int mdn_workspace_bytes(const mdn_shape *shape, int which, size_t *bytes_out) {
     int rc = check_shape(shape, true, &d);
     if (rc) return rc;
     if (which == MDN_WS_FWD) *bytes_out = fwd_ws_total(d, shape->T % 64);
-    else if (which == MDN_WS_BWD) *bytes_out = bwd_ws_total(d, shape->T % 64);
+    else if (which == MDN_WS_BWD) *bytes_out = bwd_ws_total(d, shape->T % 64, false);
+    else if (which == MDN_WS_BWD_STATE_ADJOINTS) *bytes_out = bwd_ws_total(d, shape->T % 64, d.dtype == MDN_DTYPE_BF16);
     else return MDN_ERR_SHAPE;
     return MDN_OK;
 }
@@ -814,10 +830,10 @@ int mdn_chunk_bwd(const mdn_shape *shape, const void *q, const void *k, const vo
     for (const void *p : ptrs)
         if (p && misaligned(p)) return MDN_ERR_ALIGN;
     const int r = shape->T % 64;
-    if (workspace_bytes < bwd_ws_total(d, r)) return MDN_ERR_WORKSPACE;
-    hipStream_t s = static_cast<hipStream_t>(stream);
     BwdCall c = {q, k, v, beta, alpha, mu, eta, S0, M0, vt_saved, states_saved, operands_saved, dO, dS_final, dM_final,
                  dq, dk, dv, dbeta, dalpha, dmu, deta, dS0, dM0};
+    if (workspace_bytes < bwd_ws_total(d, r, precise_call(d, c))) return MDN_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
     return bwd_any(d, r, c, workspace, s);
 }
 
@@ -831,7 +847,8 @@ int mdn_workspace_bytes_varlen(const mdn_shape *shape, const int32_t *cu_seqlens
     for (int i = 0; i < n_seq; ++i) {
         const int len = cu_seqlens[i + 1] - cu_seqlens[i];
         const Dims ds = seq_dims(d, len);
-        const size_t b = which == MDN_WS_FWD ? fwd_ws_total(ds, len % 64) : bwd_ws_total(ds, len % 64);
+        // (a sequence run by itself may bring adjoints of its final states in)
+        const size_t b = which == MDN_WS_FWD ? fwd_ws_total(ds, len % 64) : bwd_ws_total(ds, len % 64, ds.dtype == MDN_DTYPE_BF16);
         need = b > need ? b : need;
     }
     // (either way of running the batch may be taken: see mdn_chunk_fwd_varlen)

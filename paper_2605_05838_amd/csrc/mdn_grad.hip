@@ -64,7 +64,9 @@ __device__ __forceinline__ float coldot(f32x4 t, f32x4 xv) {
 // later contraction steps from piling up in registers)
 __device__ __forceinline__ void sched_fence() { __builtin_amdgcn_sched_barrier(0); }
 
-template <typename T, int DK, int DV, bool STAGED>
+// LO: the rounding remainders of the four state tensors are given as well (GradArgs::states_lo, dstates_lo): the three
+// state traces and the products of dS', dM' with V~ then take hi + lo of their factors.
+template <typename T, int DK, int DV, bool STAGED, bool LO>
 __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     typedef Op<T> O;
     typedef typename O::Frag Frag;
@@ -144,7 +146,7 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     int chunk = blockIdx.x;
     if (chunk >= nchunks) return;
     size_t tok0, blk;
-    const T *qg, *kgl, *vtg, *dog, *drg, *KTg, *QTg, *Sg, *Mg, *dSg, *dMg;
+    const T *qg, *kgl, *vtg, *dog, *drg, *KTg, *QTg, *Sg, *Mg, *dSg, *dMg, *Slg = nullptr, *dSlg = nullptr;
     auto set_chunk = [&](int c) {
         const int n = d.n0 + c % nper, bh = c / nper, b = bh / d.H, h = bh % d.H;
         tok0 = ((size_t)b * d.T + (size_t)n * 64) * d.H + h;
@@ -160,6 +162,10 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
         Mg = Sg + DK * DV;
         dSg = static_cast<const T *>(a.dstates) + blk * (2 * DK * DV);
         dMg = dSg + DK * DV;
+        if constexpr (LO) {
+            Slg = static_cast<const T *>(a.states_lo) + blk * (2 * DK * DV);
+            dSlg = static_cast<const T *>(a.dstates_lo) + blk * (2 * DK * DV);
+        }
     };
     set_chunk(chunk);
 
@@ -403,9 +409,12 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     // ---------------- phases C-F: products with the four state matrices.  X^T[dk][i] = sum_dv St[dk][dv] f[i][dv]
     // two products sharing their B fragments (LDS reads are what bounds these phases):
     //   t1^T[dk][i] = sum_dv Fa[dk][dv] X[i][dv],  t2^T likewise with Fb
-    auto state_product2 = [&](const Frag(&fa)[KSV], const Frag(&fb)[KSV], const T *tile, f32x4(&t1)[TT], f32x4(&t2)[TT]) {
-        zero_acc(t1);
-        zero_acc(t2);
+    auto state_product2 = [&](const Frag(&fa)[KSV], const Frag(&fb)[KSV], const T *tile, f32x4(&t1)[TT], f32x4(&t2)[TT],
+                              bool add = false) {
+        if (!add) {
+            zero_acc(t1);
+            zero_acc(t2);
+        }
 #pragma unroll
         for (int s = 0; s < KSV; ++s) {
 #pragma unroll
@@ -463,6 +472,25 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     }
     // E: dS' and dM' against V~
     state_product2(fdS, fdM, tVt, t1, t2);
+    if constexpr (LO) {
+        // the remainders: (hi + lo)(hi + lo) without the lo lo term, one tile of remainders in registers at a time
+        Frag fx[KSV];
+        load_state(fx, Slg);
+        if (tg == 0) p1 += dot_frags(fdS, fx);
+        load_state(fx, Slg + DK * DV);
+        if (tg == 0) {
+            p2 += dot_frags(fdS, fx);
+            p3 += dot_frags(fdM, fx);
+        }
+        load_state(fdS, dSlg);
+        if (tg == 0) {
+            p1 += dot_frags(fdS, fS);
+            p2 += dot_frags(fdS, fM);
+        }
+        load_state(fdM, dSlg + DK * DV);
+        if (tg == 0) p3 += dot_frags(fdM, fM);
+        state_product2(fdS, fdM, tVt, t1, t2, true);
+    }
 #pragma unroll
     for (int t = 0; t < TT; ++t) {
         const int it = (tg * TT + t) * 16 + r;
@@ -617,12 +645,12 @@ inline int num_cus() {
     return n;
 }
 
-template <typename T, int DK, int DV, bool STAGED>
+template <typename T, int DK, int DV, bool STAGED, bool LO = false>
 hipError_t launch_t(const Dims &d, const GradArgs &a, hipStream_t s) {
     // staged (bf16): one workgroup per CU, each walking its share of the chunks; otherwise one per chunk
     const int nchunks = (d.n1 - d.n0) * d.BH;
     dim3 grid(STAGED && nchunks > num_cus() ? num_cus() : nchunks), block(GT);
-    hipLaunchKernelGGL((grad_kernel<T, DK, DV, STAGED>), grid, block, 0, s, d, a);
+    hipLaunchKernelGGL((grad_kernel<T, DK, DV, STAGED, LO>), grid, block, 0, s, d, a);
     return hipGetLastError();
 }
 
@@ -630,6 +658,12 @@ hipError_t launch_t(const Dims &d, const GradArgs &a, hipStream_t s) {
 
 hipError_t launch_grad(const Dims &d, const GradArgs &a, hipStream_t s) {
     const bool f32 = d.dtype == 1;
+    if (!a.states_lo != !a.dstates_lo || (f32 && a.states_lo)) return hipErrorInvalidValue;
+    if (a.states_lo) { // 16-bit storage with the rounding remainders of the state tensors
+        if (d.dk == 64 && d.dv == 64) return launch_t<bf16_t, 64, 64, true, true>(d, a, s);
+        if (d.dk == 128 && d.dv == 128) return launch_t<bf16_t, 128, 128, true, true>(d, a, s);
+        return hipErrorInvalidValue;
+    }
     if (d.dk == 64 && d.dv == 64)
         return f32 ? launch_t<float, 64, 64, false>(d, a, s) : launch_t<bf16_t, 64, 64, true>(d, a, s);
     if (d.dk == 128 && d.dv == 128)

@@ -42,6 +42,8 @@ struct ScanFwdArgs {
     void *o;                                // [B,T,H,dv]
     void *vt_saved;                         // [B,T,H,dv] or null
     void *states_saved;                     // [BH][N][2] x vblk [dk][dv], or null
+    void *states_lo;                        // same layout, or null: what the 16-bit rounding of states_saved dropped
+                                            // (reconstruction only; see GradArgs)
     float *S_final, *M_final;               // or null
 };
 
@@ -53,6 +55,7 @@ struct RebuildArgs {
     const void *vt_saved;                   // [B,T,H,dv]
     const float *S0, *M0;
     void *states;                           // [BH][N][2] x vblk [dk][dv]
+    void *states_lo;                        // or null: the rounding remainders of `states` (16-bit storage)
     float *S_final, *M_final;               // states after the last chunk, or null
 };
 
@@ -64,6 +67,7 @@ struct ScanBwdArgs {
     const float *dS_final, *dM_final;       // or null
     void *dv;                               // [B,T,H,dv]  dV = T^T dV~
     void *dstates;                          // [BH][N][2] x vblk [dk][dv]: adjoints of the chunk-END states
+    void *dstates_lo;                       // or null: the rounding remainders of `dstates` (16-bit storage)
     float *dS0, *dM0;                       // or null
 };
 
@@ -73,6 +77,11 @@ struct GradArgs {
     const void *vt_saved, *dO, *dv;         // [B,T,H,dv]; dv (= dR, from the reverse scan) is read
     const void *KT, *QT;
     const void *states, *dstates;           // [BH][N][2] x vblk [dk][dv]
+    // 16-bit storage, calls that bring adjoints of the final states in (both or neither): x - bf16(x) of the two
+    // tensors above, again in bf16.  Adjoints that enter from outside can be large against everything dO puts into
+    // the states; <dS', S>, <dS', M>, <dM', M> and the products of dS', dM' with V~ are then sums of dk dv terms
+    // whose storage rounding alone would reach the tolerance, so those sums take hi + lo of both factors.
+    const void *states_lo, *dstates_lo;
     void *dq, *dk;
     float *dalpha, *dbeta, *dmu, *deta;     // deta may be null
 };

@@ -158,6 +158,23 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
                 store_cols_raw<MV>(ds + off, sv[2 * nd]);
                 store_cols_raw<MV>(ds + DK * DV + off, sv[2 * nd + 1]);
             }
+            if constexpr (sizeof(T) == 2) {
+                if (a.dstates_lo) { // what the rounding above dropped, rounded again (see GradArgs)
+                    T *dl = static_cast<T *>(a.dstates_lo) + blk * (2 * DK * DV);
+#pragma unroll
+                    for (int nd = 0; nd < ND; ++nd) {
+                        typename Raw4<T>::type ls[MV], lm[MV];
+#pragma unroll
+                        for (int mv = 0; mv < MV; ++mv) {
+                            ls[mv] = narrow4<T>(accS[mv][nd] - widen4(sv[2 * nd][mv]));
+                            lm[mv] = narrow4<T>(accM[mv][nd] - widen4(sv[2 * nd + 1][mv]));
+                        }
+                        const size_t off = vblk(DK, (w * ND + nd) * 16 + r, dv0 + kg * (4 * MV));
+                        store_cols_raw<MV>(dl + off, ls);
+                        store_cols_raw<MV>(dl + DK * DV + off, lm);
+                    }
+                }
+            }
         }
         fetch_part<T, DK, DV, DVB, 1>(nxt, d, a, bh, b, h, nn, dv0);
         // dO^T slice of this chunk in three scalings

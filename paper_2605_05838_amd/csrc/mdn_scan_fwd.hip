@@ -210,6 +210,21 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
                     sv[2 * nd + 1][mv] = narrow4<T>(accM[mv][nd]);
                 }
         }
+        // what that rounding dropped, rounded again (reconstruction with 16-bit storage, on request)
+        constexpr bool LO = REBUILD && sizeof(T) == 2;
+        typename Raw4<T>::type sl[LO ? NS : 1][MV];
+        T *stl = static_cast<T *>(a.states_lo) + blk * (2 * DK * DV);
+        if constexpr (LO) {
+            if (a.states_lo) {
+#pragma unroll
+                for (int nd = 0; nd < ND; ++nd)
+#pragma unroll
+                    for (int mv = 0; mv < MV; ++mv) {
+                        sl[2 * nd][mv] = narrow4<T>(accS[mv][nd] - widen4(sv[2 * nd][mv]));
+                        sl[2 * nd + 1][mv] = narrow4<T>(accM[mv][nd] - widen4(sv[2 * nd + 1][mv]));
+                    }
+            }
+        }
         auto emit_states = [&](auto PORTION) {
             if (!a.states_saved) return;
             static_for<NS>([&](auto IDX) {
@@ -217,6 +232,9 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
                 if ((REBUILD ? idx * 8 / NS : 0) == decltype(PORTION)::value) {
                     const size_t off = vblk(DK, (w * ND + nd) * 16 + r, dv0 + kg * (4 * MV));
                     store_cols_raw<MV>(st + ((idx & 1) ? DK * DV : 0) + off, sv[idx]);
+                    if constexpr (LO) {
+                        if (a.states_lo) store_cols_raw<MV>(stl + ((idx & 1) ? DK * DV : 0) + off, sl[idx]);
+                    }
                 }
             });
             __builtin_amdgcn_sched_barrier(0);
@@ -400,6 +418,7 @@ hipError_t launch_rebuild(const Dims &d, const RebuildArgs &r, hipStream_t s) {
     a.S0 = r.S0;
     a.M0 = r.M0;
     a.states_saved = r.states;
+    a.states_lo = r.states_lo;
     a.S_final = r.S_final;
     a.M_final = r.M_final;
     return dispatch_scan<true>(d, a, s);

@@ -37,9 +37,4 @@ def test_seeded_shape_sweep(case, B, T, H, d, dtype, keep_states, keep_operands,
     if with_m0:
         w.arrays["M0"] = (np.random.default_rng(case).standard_normal((B, H, d, d)) * 0.2).astype(np.float32)
     check_fwd(w)  # o, V~ and the final states of the inference-mode forward
-    # Adjoints of the final states enter dalpha, dmu of the last tokens through <dS', S>, a sum of dk*dv products of
-    # two tensors that 16-bit storage keeps rounded: with unit-variance adjoints on every state element its rounding
-    # error alone (2^-8.5 |dS' . S|_F, about 0.03 here) reaches the 2e-2 bound on its own, so the 16-bit cases take
-    # adjoints of the size of the other gradient signals instead
-    check_bwd(w, final_adjoints=final_adjoints, save_states=keep_states, save_operands=keep_operands,
-              adjoint_std=1.0 if dtype == "f32" else 0.1)
+    check_bwd(w, final_adjoints=final_adjoints, save_states=keep_states, save_operands=keep_operands)
