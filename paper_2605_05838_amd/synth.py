@@ -138,3 +138,19 @@ def custom(**kw) -> Workload:
     kw.setdefault("backward", False)
     kw.setdefault("seed", 0)
     return generate(Workload(**kw))
+
+
+def to_device(w: Workload, device="cuda"):
+    """The workload's arrays as torch tensors on `device` (q, k, v, dO in the storage dtype: the values are
+    representable, so the conversion is exact; everything else fp32)."""
+    import torch
+    dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    t = {}
+    for name, arr in w.arrays.items():
+        if arr is None:
+            t[name] = None
+        elif name in ("q", "k", "v", "dO"):
+            t[name] = torch.from_numpy(arr).to(device=device, dtype=dt)
+        else:
+            t[name] = torch.from_numpy(arr).to(device)
+    return t

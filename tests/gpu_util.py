@@ -1,20 +1,13 @@
 """Helpers of the GPU parity tests: move a synthetic workload to the device, slice (b, h) pairs
-for the oracle, and the error metric (max |x - ref| / max |ref| per tensor)."""
+for the oracle, and the two error metrics per tensor: max |x - ref| / max |ref| (the bound the tolerances are
+stated for) and the RMS-relative error rms(x - ref) / rms(ref), which a few large entries cannot hide behind."""
 import numpy as np
-import torch
+
+from paper_2605_05838_amd import synth
 
 
 def to_dev(w, device="cuda"):
-    dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
-    t = {}
-    for name, arr in w.arrays.items():
-        if arr is None:
-            t[name] = None
-        elif name in ("q", "k", "v", "dO"):
-            t[name] = torch.from_numpy(arr).to(device=device, dtype=dt)   # exact: values are representable
-        else:
-            t[name] = torch.from_numpy(arr).to(device)
-    return t
+    return synth.to_device(w, device)
 
 
 def host(x):
@@ -48,3 +41,18 @@ def gather_pairs(x, pairs, is_state=False):
 def rel_err(x, ref):
     den = np.abs(ref).max()
     return float(np.abs(x - ref).max() / (den if den > 0 else 1.0))
+
+
+def rms_rel_err(x, ref):
+    den = np.sqrt(np.mean(np.square(ref)))
+    return float(np.sqrt(np.mean(np.square(x - ref))) / (den if den > 0 else 1.0))
+
+
+def worst_err(x, ref):
+    """The larger of the two metrics: what the tests bound."""
+    return max(rel_err(x, ref), rms_rel_err(x, ref))
+
+
+def fmt_errs(errs):
+    """{name: (max-normalised, rms-relative)} as a short string."""
+    return "{" + ", ".join(f"{k}: {a:.2e}/{b:.2e}" for k, (a, b) in errs.items()) + "}"

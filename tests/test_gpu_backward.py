@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 import torch
 
-from gpu_util import gather_pairs, host, rel_err, select_pairs, to_dev
+from gpu_util import fmt_errs, gather_pairs, host, rel_err, rms_rel_err, select_pairs, to_dev, worst_err
 from oracle import mdn_oracle as orc
 from paper_2605_05838_amd import binding, synth
 
@@ -41,10 +41,10 @@ def check_bwd(w, pairs=None, final_adjoints=False, save_states=False, save_opera
     errs = {}
     for name in GRADS:
         x = gather_pairs(host(g[name]), pairs, is_state=name in ("dS0", "dM0"))
-        errs[name] = rel_err(x, ref[name])
-    print(w.name, {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+        errs[name] = (rel_err(x, ref[name]), rms_rel_err(x, ref[name]))
+    print(w.name, "max-normalised/rms-relative", fmt_errs(errs), flush=True)
     for name, e in errs.items():
-        assert e <= TOL[w.dtype], (w.name, name, e)
+        assert max(e) <= TOL[w.dtype], (w.name, name, e)
     return errs
 
 
@@ -160,4 +160,4 @@ def test_partial_last_chunk_together_with_segments_on_two_streams(T, nseg):
     ref = orc.backward(a["q"], a["k"], a["v"], a["alpha"], a["beta"], a["mu"], a["dO"], eta=a["eta"], S0=a["S0"],
                        M0=a["M0"], scale=w.scale)
     for name in GRADS:
-        assert rel_err(host(g2[name]), ref[name]) <= TOL["bf16"], name
+        assert worst_err(host(g2[name]), ref[name]) <= TOL["bf16"], name

@@ -3,13 +3,13 @@ import numpy as np
 import pytest
 import torch
 
-from gpu_util import gather_pairs, host, rel_err, select_pairs, to_dev
+from gpu_util import fmt_errs, gather_pairs, host, rel_err, rms_rel_err, select_pairs, to_dev, worst_err
 from oracle import mdn_oracle as orc
 from paper_2605_05838_amd import binding, synth
 
 pytestmark = pytest.mark.gpu
 
-TOL = {"f32": 1e-4, "bf16": 2e-2}   # max |x - ref| / max |ref| per tensor
+TOL = {"f32": 1e-4, "bf16": 2e-2}   # per tensor, on max |x - ref| / max |ref| and on rms(x - ref) / rms(ref)
 
 
 def run_fwd(w, **kw):
@@ -25,20 +25,20 @@ def oracle_fwd(a, scale):
                        scale=scale)
 
 
-def check_fwd(w, pairs=None):
-    t, r = run_fwd(w)
+def check_fwd(w, pairs=None, **kw):
+    """Outputs, V~ and final states against the oracle, on all (batch, head) pairs unless `pairs` names some; kw goes
+    to the forward call (what it keeps for a backward)."""
+    t, r = run_fwd(w, **kw)
     if pairs is None:
         pairs = [(b, h) for b in range(w.B) for h in range(w.H)]
     ref = oracle_fwd(select_pairs(w, pairs), w.scale)
-    errs = {
-        "o": rel_err(gather_pairs(host(r["o"]), pairs), ref["o"]),
-        "vt": rel_err(gather_pairs(host(r["vt"]), pairs), ref["vt"]),
-        "S": rel_err(gather_pairs(host(r["S"]), pairs, True), ref["S"]),
-        "M": rel_err(gather_pairs(host(r["M"]), pairs, True), ref["M"]),
-    }
-    print(w.name, {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+    errs = {}
+    for name in ("o", "vt", "S", "M"):
+        x = gather_pairs(host(r[name]), pairs, name in ("S", "M"))
+        errs[name] = (rel_err(x, ref[name]), rms_rel_err(x, ref[name]))
+    print(w.name, "max-normalised/rms-relative", fmt_errs(errs), flush=True)
     for name, e in errs.items():
-        assert e <= TOL[w.dtype], (w.name, name, e)
+        assert max(e) <= TOL[w.dtype], (w.name, name, e)
     return errs
 
 
@@ -84,8 +84,8 @@ def test_recurrent_step_matches_oracle_and_chunk_forward(dtype):
     a = {k: (None if v is None else v.astype(np.float64)) for k, v in w.arrays.items()}
     ref = oracle_fwd(a, w.scale)
     tol = 1e-5 if dtype == "f32" else 2e-2      # fp32 FMA recurrence; bf16 only rounds o
-    assert rel_err(host(o), ref["o"]) <= tol
-    assert rel_err(host(S), ref["S"]) <= 1e-5 and rel_err(host(M), ref["M"]) <= 1e-5
+    assert worst_err(host(o), ref["o"]) <= tol
+    assert worst_err(host(S), ref["S"]) <= 1e-5 and worst_err(host(M), ref["M"]) <= 1e-5
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -110,9 +110,9 @@ def test_prefill_states_hand_off_to_the_recurrent_step(dtype):
     arrays = {k: (None if v is None else v.astype(np.float64)) for k, v in w.arrays.items()}
     ref = oracle_fwd(arrays, w.scale)
     tol = 1e-4 if dtype == "f32" else 2e-2
-    assert rel_err(host(o)[:, Tp:], ref["o"][:, Tp:]) <= tol
-    assert rel_err(host(o), ref["o"]) <= tol
-    assert rel_err(host(S), ref["S"]) <= tol and rel_err(host(M), ref["M"]) <= tol
+    assert worst_err(host(o)[:, Tp:], ref["o"][:, Tp:]) <= tol
+    assert worst_err(host(o), ref["o"]) <= tol
+    assert worst_err(host(S), ref["S"]) <= tol and worst_err(host(M), ref["M"]) <= tol
 
 
 @pytest.mark.parametrize("dtype,d,T", [("f32", 64, 200), ("bf16", 128, 200), ("f32", 128, 40), ("bf16", 64, 70),

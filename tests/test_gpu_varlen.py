@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 import torch
 
-from gpu_util import host, rel_err, to_dev
+from gpu_util import host, to_dev, worst_err
 from oracle import mdn_oracle as orc
 from paper_2605_05838_amd import binding, synth
 
@@ -38,15 +38,15 @@ def test_packed_sequences_forward_and_backward(dtype, d, lens):
         s0, m0 = S0[i:i + 1].astype(np.float64), M0[i:i + 1].astype(np.float64)
         rf = orc.forward(seq["q"], seq["k"], seq["v"], seq["alpha"], seq["beta"], seq["mu"], eta=seq["eta"], S0=s0, M0=m0,
                          scale=w.scale)
-        assert rel_err(host(f["o"])[:, sl], rf["o"]) <= tol, (i, "o")
-        assert rel_err(host(f["S"])[i:i + 1], rf["S"]) <= tol and rel_err(host(f["M"])[i:i + 1], rf["M"]) <= tol, (i, "S/M")
+        assert worst_err(host(f["o"])[:, sl], rf["o"]) <= tol, (i, "o")
+        assert worst_err(host(f["S"])[i:i + 1], rf["S"]) <= tol and worst_err(host(f["M"])[i:i + 1], rf["M"]) <= tol, (i, "S/M")
         rb = orc.backward(seq["q"], seq["k"], seq["v"], seq["alpha"], seq["beta"], seq["mu"], seq["dO"], eta=seq["eta"],
                           S0=s0, M0=m0, dS_T=dSf[i:i + 1].astype(np.float64), dM_T=dMf[i:i + 1].astype(np.float64),
                           scale=w.scale)
         for name in ("dq", "dk", "dv", "dalpha", "dbeta", "dmu", "deta"):
-            assert rel_err(host(g[name])[:, sl], rb[name]) <= tol, (i, name)
+            assert worst_err(host(g[name])[:, sl], rb[name]) <= tol, (i, name)
         for name in ("dS0", "dM0"):
-            assert rel_err(host(g[name])[i:i + 1], rb[name]) <= tol, (i, name)
+            assert worst_err(host(g[name])[i:i + 1], rb[name]) <= tol, (i, name)
 
 
 @pytest.mark.parametrize("dtype,d,lens", [("f32", 64, (70, 128, 5, 191, 1, 64)), ("bf16", 128, (256, 33, 200, 1, 63, 65)),
@@ -76,12 +76,12 @@ def test_packed_sequences_as_one_stream_of_tokens(dtype, d, lens):
         sl = slice(cu[i], cu[i + 1])
         seq = {k: a[k][:, sl] for k in ("q", "k", "v", "alpha", "beta", "mu", "eta", "dO")}
         rf = orc.forward(seq["q"], seq["k"], seq["v"], seq["alpha"], seq["beta"], seq["mu"], eta=seq["eta"], scale=w.scale)
-        assert rel_err(host(f["o"])[:, sl], rf["o"]) <= tol, (i, "o")
-        assert rel_err(host(f["vt"])[:, sl], rf["vt"]) <= tol, (i, "vt")
+        assert worst_err(host(f["o"])[:, sl], rf["o"]) <= tol, (i, "o")
+        assert worst_err(host(f["vt"])[:, sl], rf["vt"]) <= tol, (i, "vt")
         rb = orc.backward(seq["q"], seq["k"], seq["v"], seq["alpha"], seq["beta"], seq["mu"], seq["dO"], eta=seq["eta"],
                           scale=w.scale)
         for name in ("dq", "dk", "dv", "dalpha", "dbeta", "dmu", "deta"):
-            assert rel_err(host(g[name])[:, sl], rb[name]) <= tol, (i, name)
+            assert worst_err(host(g[name])[:, sl], rb[name]) <= tol, (i, name)
         # the first token's alpha, mu multiply zero states: their gradients are exactly zero
         assert float(host(g["dalpha"])[:, cu[i]].max()) == 0.0 and float(host(g["dmu"])[:, cu[i]].min()) == 0.0, i
 
@@ -108,6 +108,6 @@ def test_packed_prompts_with_final_states_of_every_sequence(dtype, d, lens):
         sl = slice(cu[i], cu[i + 1])
         seq = {k: a[k][:, sl] for k in ("q", "k", "v", "alpha", "beta", "mu", "eta")}
         rf = orc.forward(seq["q"], seq["k"], seq["v"], seq["alpha"], seq["beta"], seq["mu"], eta=seq["eta"], scale=w.scale)
-        assert rel_err(host(f["o"])[:, sl], rf["o"]) <= tol, (i, "o")
-        assert rel_err(host(f["S"])[i:i + 1], rf["S"]) <= tol, (i, "S")
-        assert rel_err(host(f["M"])[i:i + 1], rf["M"]) <= tol, (i, "M")
+        assert worst_err(host(f["o"])[:, sl], rf["o"]) <= tol, (i, "o")
+        assert worst_err(host(f["S"])[i:i + 1], rf["S"]) <= tol, (i, "S")
+        assert worst_err(host(f["M"])[i:i + 1], rf["M"]) <= tol, (i, "M")
