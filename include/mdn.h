@@ -13,9 +13,14 @@
  * mdn_recurrent_step evaluates it token by token (decoding, Appendix E recurrent form).
  *
  * Conventions shared by every entry point
- *   - Every pointer is a DEVICE pointer unless stated otherwise; the caller owns all buffers,
- *     the library allocates no device memory and keeps no state between calls (the optional
- *     per-kernel timing facility at the end of this header is the one exception).
+ *   - Every pointer is a DEVICE pointer unless stated otherwise; the caller owns all buffers and
+ *     the library allocates no device memory.  What it keeps between calls, all of it safe to use
+ *     from several host threads: the mdn_set_segments() setting (one atomic integer for the
+ *     process); the event list of the optional timing facility at the end of this header (behind a
+ *     mutex); and, once a call has been split over two streams, one extra stream and a few events
+ *     per device, shared by all calls on that device (a call that uses them holds the device's
+ *     mutex while it enqueues, so concurrent callers are serialised on that second stream, never
+ *     mixed up).
  *   - Token tensors are contiguous [B, T, H, D] (D = dk for q, k; dv for v, o), gates are
  *     contiguous [B, T, H] fp32 in the LINEAR domain (alpha, mu in [0,1], beta step size;
  *     mu = 0 is allowed), states are contiguous [B, H, dk, dv] fp32.
@@ -32,9 +37,11 @@
  *     of the GPU idle (few batch*head pairs, many chunks) mdn_chunk_fwd / mdn_chunk_bwd split
  *     the sequence into segments and run the chunk-parallel kernel of one segment beside the
  *     scan of its neighbour on a second stream that the library creates once per device
- *     (default priority) and joins back into `stream` with events; see mdn_set_segments().
+ *     (default priority) and joins back into `stream` with events, also when a launch fails on the
+ *     way; see mdn_set_segments().
  *   - Return value: MDN_OK (0) or a negative MDN_ERR_* code; nothing is launched when an
  *     error is returned from validation.  NaN/Inf in the inputs propagate, they are not detected.
+ *   - No environment variable or other hidden setting influences a call.
  */
 #ifndef MDN_H
 #define MDN_H
@@ -224,7 +231,8 @@ int mdn_epilogue_bwd(const mdn_shape *shape, const void *o, const void *g, const
  * bracketed by a pair of HIP events recorded on the launch stream.  mdn_profile_end()
  * synchronises those events and adds, per kernel id, the elapsed milliseconds into ms[id] and
  * the number of launches into launches[id] (HOST arrays of n entries; ids >= n are dropped),
- * then releases the events.  Not thread-safe; meant for one benchmarking thread.
+ * then releases the events.  The switch is process-wide (launches of every thread are recorded while it is
+ * on); meant for one benchmarking thread.
  */
 enum {
     MDN_KERNEL_INTRA_FWD = 0, /* chunk-local coefficients, masked products, triangular solve
@@ -244,7 +252,7 @@ int mdn_profile_end(float *ms, int *launches, int n);
  * Number of segments mdn_chunk_fwd / mdn_chunk_bwd split the sequence into: k >= 1 forces k
  * (1 = never split; capped at N/4 and at 16), 0 restores the automatic choice.  A tuning and
  * test knob: results do not depend on it (states cross a segment boundary in fp32, exactly as
- * they are carried inside a scan).  Returns the previous setting.
+ * they are carried inside a scan).  Returns the previous setting (an atomic exchange: process-wide).
  */
 int mdn_set_segments(int k);
 

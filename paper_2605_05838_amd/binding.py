@@ -115,6 +115,60 @@ def _ptr(t):
     return ctypes.c_void_p(t.data_ptr())
 
 
+def _expect(name, t, shape, dtype, like, optional=False):
+    """Shape, dtype, device and layout of one tensor against what the call's q implies.  The C ABI takes raw pointers
+    and trusts them: a tensor of the wrong size would be read or written out of bounds on the device, so every tensor
+    is checked here, before anything is launched."""
+    if t is None:
+        if optional:
+            return
+        raise MdnError(f"{name} is required")
+    if tuple(t.shape) != tuple(shape):
+        raise MdnError(f"{name}: expected shape {tuple(shape)}, got {tuple(t.shape)}")
+    if t.dtype != dtype:
+        raise MdnError(f"{name}: expected dtype {dtype}, got {t.dtype}")
+    if t.device != like.device:
+        raise MdnError(f"{name} is on {t.device}, q on {like.device}: all tensors of a call share one device")
+    if not t.is_contiguous():
+        raise MdnError(f"{name} must be contiguous")
+
+
+def _expect_bytes(name, t, nbytes, like, optional=True):
+    """An opaque buffer (workspace, kept states / operands): at least nbytes, on q's device, contiguous."""
+    if t is None:
+        if optional:
+            return
+        raise MdnError(f"{name} is required")
+    have = t.numel() * t.element_size()
+    if have < nbytes:
+        raise MdnError(f"{name}: {have} bytes, the call needs {nbytes}")
+    if t.device != like.device:
+        raise MdnError(f"{name} is on {t.device}, q on {like.device}: all tensors of a call share one device")
+    if not t.is_contiguous():
+        raise MdnError(f"{name} must be contiguous")
+
+
+def _check_inputs(q, k, v, beta, alpha, mu, eta, S0, M0, states_batch=None):
+    """The forward inputs that every chunkwise / recurrent call takes; returns (B, T, H, dk, dv)."""
+    if q.dim() != 4 or v.dim() != 4:
+        raise MdnError(f"q, v must be [B, T, H, d]; got {tuple(q.shape)}, {tuple(v.shape)}")
+    _dtype_code(q)
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    f32 = torch.float32
+    _expect("k", k, (B, T, H, dk), q.dtype, q)
+    _expect("v", v, (B, T, H, dv), q.dtype, q)
+    for name, g in (("beta", beta), ("alpha", alpha), ("mu", mu)):
+        _expect(name, g, (B, T, H), f32, q)
+    _expect("eta", eta, (B, T, H), f32, q, optional=True)
+    nb = B if states_batch is None else states_batch
+    _expect("S0", S0, (nb, H, dk, dv), f32, q, optional=True)
+    _expect("M0", M0, (nb, H, dk, dv), f32, q, optional=True)
+    if not q.is_contiguous():
+        raise MdnError("q must be contiguous")
+    return B, T, H, dk, dv
+
+
 def _f32(t, name):
     if t is not None and t.dtype != torch.float32:
         raise MdnError(f"{name} must be float32")
@@ -167,13 +221,9 @@ def mdn_chunk_fwd(q, k, v, beta, alpha, mu, eta=None, S0=None, M0=None, scale=No
                   save_states=False, save_operands=False, output_final_state=True, workspace=None, out=None):
     """Chunkwise forward.  Returns a dict: o, S, M (final states or None), vt, states, operands (or None)."""
     lib = load_library()
+    B, T, H, dk, dv = _check_inputs(q, k, v, beta, alpha, mu, eta, S0, M0)
     shape = make_shape(q, v, scale)
-    for t in (k, v):
-        if t.dtype != q.dtype:
-            raise MdnError("q, k, v must share one dtype")
     out = {} if out is None else out
-    B, T, H, dk = q.shape
-    dv = v.shape[-1]
     dev = q.device
     o = out.get("o")
     if o is None:
@@ -192,6 +242,16 @@ def mdn_chunk_fwd(q, k, v, beta, alpha, mu, eta=None, S0=None, M0=None, scale=No
         states = out.get("states")
         if states is None:
             states = torch.empty((B, H, -(-T // 64), 2, dk, dv), dtype=q.dtype, device=dev)  # opaque to the caller
+    f32 = torch.float32
+    _expect("out['o']", o, (B, T, H, dv), q.dtype, q)
+    _expect("out['S']", S, (B, H, dk, dv), f32, q, optional=True)
+    _expect("out['M']", M, (B, H, dk, dv), f32, q, optional=True)
+    _expect("out['vt']", vt, (B, T, H, dv), q.dtype, q, optional=True)
+    if states is not None:
+        _expect_bytes("out['states']", states, saved_states_bytes(shape), q)
+    if operands is not None:
+        _expect_bytes("out['operands']", operands, saved_operands_bytes(shape), q)
+    _expect_bytes("workspace", workspace, workspace_bytes(shape, MDN_WS_FWD), q)
     workspace, wbytes = _workspace(shape, MDN_WS_FWD, workspace, dev)
     rc = lib.mdn_chunk_fwd(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _f32(beta, "beta"), _f32(alpha, "alpha"),
                            _f32(mu, "mu"), _f32(eta, "eta"), _f32(S0, "S0"), _f32(M0, "M0"), _ptr(o), _ptr(S),
@@ -204,15 +264,25 @@ def mdn_chunk_bwd(q, k, v, beta, alpha, mu, vt, dO, eta=None, S0=None, M0=None, 
                   dS_final=None, dM_final=None, scale=None, want_deta=False, want_dstates=True, workspace=None, out=None):
     """Chunkwise backward.  Returns a dict: dq, dk, dv, dbeta, dalpha, dmu, deta, dS0, dM0."""
     lib = load_library()
+    B, T, H, dk, dv_ = _check_inputs(q, k, v, beta, alpha, mu, eta, S0, M0)
     shape = make_shape(q, v, scale)
     out = {} if out is None else out
-    B, T, H, dk = q.shape
-    dv_ = v.shape[-1]
     dev = q.device
+    _expect("vt", vt, (B, T, H, dv_), q.dtype, q)
+    _expect("dO", dO, (B, T, H, dv_), q.dtype, q)
+    _expect("dS_final", dS_final, (B, H, dk, dv_), torch.float32, q, optional=True)
+    _expect("dM_final", dM_final, (B, H, dk, dv_), torch.float32, q, optional=True)
+    if states is not None:
+        _expect_bytes("states", states, saved_states_bytes(shape), q)
+    if operands is not None:
+        _expect_bytes("operands", operands, saved_operands_bytes(shape), q)
 
     def get(name, shp, dt):
         t = out.get(name)
-        return t if t is not None else torch.empty(shp, dtype=dt, device=dev)
+        if t is None:
+            return torch.empty(shp, dtype=dt, device=dev)
+        _expect(f"out['{name}']", t, shp, dt, q)
+        return t
 
     dq = get("dq", (B, T, H, dk), q.dtype)
     dk_t = get("dk", (B, T, H, dk), q.dtype)
@@ -224,6 +294,7 @@ def mdn_chunk_bwd(q, k, v, beta, alpha, mu, vt, dO, eta=None, S0=None, M0=None, 
     dS0 = get("dS0", (B, H, dk, dv_), torch.float32) if want_dstates else None
     dM0 = get("dM0", (B, H, dk, dv_), torch.float32) if want_dstates else None
     which = MDN_WS_BWD if dS_final is None and dM_final is None else MDN_WS_BWD_STATE_ADJOINTS
+    _expect_bytes("workspace", workspace, workspace_bytes(shape, which), q)
     workspace, wbytes = _workspace(shape, which, workspace, dev)
     rc = lib.mdn_chunk_bwd(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _f32(beta, "beta"), _f32(alpha, "alpha"),
                            _f32(mu, "mu"), _f32(eta, "eta"), _f32(S0, "S0"), _f32(M0, "M0"), _ptr(vt), _ptr(states),
@@ -238,9 +309,12 @@ def mdn_chunk_bwd(q, k, v, beta, alpha, mu, vt, dO, eta=None, S0=None, M0=None, 
 def mdn_recurrent_step(q, k, v, beta, alpha, mu, S, M, eta=None, scale=None, out=None):
     """Recurrent form over the T tokens given; S, M [B,H,dk,dv] fp32 are updated in place.  Returns o."""
     lib = load_library()
+    B, T, H, dk, dv = _check_inputs(q, k, v, beta, alpha, mu, eta, S, M)
+    if S is None or M is None:
+        raise MdnError("S and M are required (they are advanced in place)")
     shape = make_shape(q, v, scale)
-    B, T, H, _ = q.shape
-    o = out if out is not None else torch.empty((B, T, H, v.shape[-1]), dtype=q.dtype, device=q.device)
+    o = out if out is not None else torch.empty((B, T, H, dv), dtype=q.dtype, device=q.device)
+    _expect("out", o, (B, T, H, dv), q.dtype, q)
     rc = lib.mdn_recurrent_step(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _f32(beta, "beta"),
                                 _f32(alpha, "alpha"), _f32(mu, "mu"), _f32(eta, "eta"), _f32(S, "S"), _f32(M, "M"),
                                 _ptr(o), _stream())
@@ -267,10 +341,11 @@ def profile_end():
 
 
 def _gate_params(x, a_alpha, b_alpha, a_mu, b_mu, s, tau, mu_log_min):
+    if x.dim() != 3:
+        raise MdnError(f"gate projections must be [B, T, H]; got {tuple(x.shape)}")
     B, T, H = x.shape
     for name, t in (("a_alpha", a_alpha), ("b_alpha", b_alpha), ("a_mu", a_mu), ("b_mu", b_mu)):
-        if t.shape != (H,):
-            raise MdnError(f"{name} must have shape [H]")
+        _expect(name, t, (H,), torch.float32, x)
     return MdnGateParams(B, T, H, _f32(a_alpha, "a_alpha").value, _f32(b_alpha, "b_alpha").value,
                          _f32(a_mu, "a_mu").value, _f32(b_mu, "b_mu").value, float(s), float(tau), float(mu_log_min))
 
@@ -278,6 +353,8 @@ def _gate_params(x, a_alpha, b_alpha, a_mu, b_mu, s, tau, mu_log_min):
 def mdn_gates_fwd(x_alpha, x_mu, x_beta, x_eta, a_alpha, b_alpha, a_mu, b_mu, s, tau, mu_log_min=-1.0):
     """Gate parameterisation: projections [B,T,H] fp32 -> dict(alpha, beta, mu, eta), each [B,T,H] fp32."""
     lib = load_library()
+    for name, t in (("x_alpha", x_alpha), ("x_mu", x_mu), ("x_beta", x_beta), ("x_eta", x_eta)):
+        _expect(name, t, x_alpha.shape, torch.float32, x_alpha)
     p = _gate_params(x_alpha, a_alpha, b_alpha, a_mu, b_mu, s, tau, mu_log_min)
     out = {k: torch.empty_like(x_alpha) for k in ("alpha", "beta", "mu", "eta")}
     rc = lib.mdn_gates_fwd(ctypes.byref(p), _f32(x_alpha, "x_alpha"), _f32(x_mu, "x_mu"), _f32(x_beta, "x_beta"),
@@ -292,6 +369,9 @@ def mdn_gates_bwd(x_alpha, x_mu, x_beta, x_eta, a_alpha, b_alpha, a_mu, b_mu, s,
     """Adjoint of mdn_gates_fwd: dict(dx_alpha, dx_mu, dx_beta, dx_eta [B,T,H]; dparams [4,H] = da_alpha, db_alpha,
     da_mu, db_mu, or None)."""
     lib = load_library()
+    for name, t in (("x_alpha", x_alpha), ("x_mu", x_mu), ("x_beta", x_beta), ("x_eta", x_eta), ("dalpha", dalpha),
+                    ("dbeta", dbeta), ("dmu", dmu), ("deta", deta)):
+        _expect(name, t, x_alpha.shape, torch.float32, x_alpha)
     p = _gate_params(x_alpha, a_alpha, b_alpha, a_mu, b_mu, s, tau, mu_log_min)
     out = {k: torch.empty_like(x_alpha) for k in ("dx_alpha", "dx_mu", "dx_beta", "dx_eta")}
     out["dparams"] = torch.empty((4, x_alpha.shape[2]), dtype=torch.float32, device=x_alpha.device) if want_dparams else None
@@ -303,8 +383,30 @@ def mdn_gates_bwd(x_alpha, x_mu, x_beta, x_eta, a_alpha, b_alpha, a_mu, b_mu, s,
     return out
 
 
+def _check_frontend(x_q, x_k, x_v, d):
+    if x_q.dim() != 4 or x_v.dim() != 4:
+        raise MdnError(f"x_q, x_v must be [B, T, H, d]; got {tuple(x_q.shape)}, {tuple(x_v.shape)}")
+    _dtype_code(x_q)
+    B, T, H, dk = x_q.shape
+    _expect("x_q", x_q, (B, T, H, dk), x_q.dtype, x_q)
+    _expect("x_k", x_k, (B, T, H, dk), x_q.dtype, x_q)
+    _expect("x_v", x_v, (B, T, H, x_v.shape[-1]), x_q.dtype, x_q)
+    _expect("d", d, (H,), torch.float32, x_q)
+
+
+def _check_epilogue(o, g, w, dy=None):
+    if o.dim() != 4:
+        raise MdnError(f"o must be [B, T, H, dv]; got {tuple(o.shape)}")
+    _dtype_code(o)
+    _expect("o", o, o.shape, o.dtype, o)
+    _expect("g", g, o.shape, o.dtype, o)
+    _expect("w", w, (o.shape[-1],), torch.float32, o)
+    _expect("dy", dy, o.shape, o.dtype, o, optional=True)
+
+
 def mdn_frontend_fwd(x_q, x_k, x_v, d, eps=1e-6):
     """SiLU, output correction and L2 norms on the short-convolution outputs -> dict(q, k, v)."""
+    _check_frontend(x_q, x_k, x_v, d)
     shape = make_shape(x_q, x_v, 1.0)
     out = {"q": torch.empty_like(x_q), "k": torch.empty_like(x_k), "v": torch.empty_like(x_v)}
     rc = load_library().mdn_frontend_fwd(ctypes.byref(shape), _ptr(x_q), _ptr(x_k), _ptr(x_v), _f32(d, "d"), float(eps),
@@ -314,6 +416,10 @@ def mdn_frontend_fwd(x_q, x_k, x_v, d, eps=1e-6):
 
 
 def mdn_frontend_bwd(x_q, x_k, x_v, d, dq, dk, dv, eps=1e-6, want_dd=True):
+    _check_frontend(x_q, x_k, x_v, d)
+    _expect("dq", dq, x_q.shape, x_q.dtype, x_q)
+    _expect("dk", dk, x_k.shape, x_q.dtype, x_q)
+    _expect("dv", dv, x_v.shape, x_q.dtype, x_q)
     shape = make_shape(x_q, x_v, 1.0)
     out = {"dx_q": torch.empty_like(x_q), "dx_k": torch.empty_like(x_k), "dx_v": torch.empty_like(x_v),
            "dd": torch.empty_like(d) if want_dd else None}
@@ -326,6 +432,7 @@ def mdn_frontend_bwd(x_q, x_k, x_v, d, dq, dk, dv, eps=1e-6, want_dd=True):
 
 def mdn_epilogue_fwd(o, g, w, eps=1e-6):
     """Head-wise RMS norm with weight w [dv] times sigmoid(g) -> y."""
+    _check_epilogue(o, g, w)
     B, T, H, dv = o.shape
     shape = MdnShape(B, T, H, dv, dv, 64, _dtype_code(o), 1.0)
     y = torch.empty_like(o)
@@ -335,6 +442,7 @@ def mdn_epilogue_fwd(o, g, w, eps=1e-6):
 
 
 def mdn_epilogue_bwd(o, g, w, dy, eps=1e-6, want_dw=True):
+    _check_epilogue(o, g, w, dy)
     B, T, H, dv = o.shape
     shape = MdnShape(B, T, H, dv, dv, 64, _dtype_code(o), 1.0)
     out = {"do": torch.empty_like(o), "dg": torch.empty_like(g), "dw": torch.empty_like(w) if want_dw else None}
@@ -344,8 +452,10 @@ def mdn_epilogue_bwd(o, g, w, dy, eps=1e-6, want_dw=True):
     return out
 
 
-def _cu(cu_seqlens):
+def _cu(cu_seqlens, T):
     cu = [int(x) for x in cu_seqlens]
+    if len(cu) < 2 or cu[0] != 0 or cu[-1] != T or any(b <= a for a, b in zip(cu, cu[1:])):
+        raise MdnError(f"cu_seqlens must rise from 0 to T = {T} without empty sequences; got {cu[:8]}{'...' if len(cu) > 8 else ''}")
     return (ctypes.c_int32 * len(cu))(*cu), len(cu) - 1
 
 
@@ -361,10 +471,11 @@ def mdn_chunk_fwd_varlen(q, k, v, beta, alpha, mu, cu_seqlens, eta=None, S0=None
     """Packed variable-length forward: q, k, v [1, T, H, d], gates [1, T, H], cu_seqlens a host sequence of n + 1
     offsets; states [n, H, dk, dv].  Returns dict(o, S, M, vt); S, M are None with want_states=False (without initial
     states either, the library then runs the batch as one stream of tokens)."""
+    if q.dim() != 4 or q.shape[0] != 1:
+        raise MdnError(f"packed batches are [1, T, H, d]; got q {tuple(q.shape)}")
+    cu, n = _cu(cu_seqlens, q.shape[1])
+    _, T, H, dk, dv = _check_inputs(q, k, v, beta, alpha, mu, eta, S0, M0, states_batch=n)
     shape = make_shape(q, v, scale)
-    cu, n = _cu(cu_seqlens)
-    _, T, H, dk = q.shape
-    dv = v.shape[-1]
     o = torch.empty_like(v)
     S = torch.empty((n, H, dk, dv), dtype=torch.float32, device=q.device) if want_states else None
     M = torch.empty_like(S) if want_states else None
@@ -382,10 +493,15 @@ def mdn_chunk_bwd_varlen(q, k, v, beta, alpha, mu, vt, dO, cu_seqlens, eta=None,
     """Packed variable-length backward.  Returns dict(dq, dk, dv, dbeta, dalpha, dmu, deta, dS0, dM0); dS0, dM0 are
     None with want_state_grads=False (with no initial states and no adjoints of the final states either, the
     library then runs the batch as one stream of tokens)."""
+    if q.dim() != 4 or q.shape[0] != 1:
+        raise MdnError(f"packed batches are [1, T, H, d]; got q {tuple(q.shape)}")
+    cu, n = _cu(cu_seqlens, q.shape[1])
+    _, T, H, dk, dv_ = _check_inputs(q, k, v, beta, alpha, mu, eta, S0, M0, states_batch=n)
+    _expect("vt", vt, (1, T, H, dv_), q.dtype, q)
+    _expect("dO", dO, (1, T, H, dv_), q.dtype, q)
+    _expect("dS_final", dS_final, (n, H, dk, dv_), torch.float32, q, optional=True)
+    _expect("dM_final", dM_final, (n, H, dk, dv_), torch.float32, q, optional=True)
     shape = make_shape(q, v, scale)
-    cu, n = _cu(cu_seqlens)
-    _, T, H, dk = q.shape
-    dv_ = v.shape[-1]
     out = {"dq": torch.empty_like(q), "dk": torch.empty_like(k), "dv": torch.empty_like(v)}
     for name in ("dbeta", "dalpha", "dmu"):
         out[name] = torch.empty_like(beta)

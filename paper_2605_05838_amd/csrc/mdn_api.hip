@@ -5,6 +5,8 @@
 
 #include <hip/hip_runtime.h>
 #include <string.h>
+#include <atomic>
+#include <mutex>
 #include <type_traits>
 #include <vector>
 
@@ -166,19 +168,24 @@ struct TailList {
 
 int launch_status(hipError_t e) { return e == hipSuccess ? MDN_OK : MDN_ERR_LAUNCH; }
 
-// ---- optional per-kernel timing: event pairs around every launch while enabled
+// ---- optional per-kernel timing: event pairs around every launch while enabled.  The list of pairs is shared by
+// all threads of the process and guarded by a mutex.
 struct TimedLaunch { int id; hipEvent_t start, stop; };
-bool g_profiling = false;
+std::atomic<bool> g_profiling{false};
+std::mutex g_timed_mutex;
 std::vector<TimedLaunch> g_timed;
 
 template <typename F> int timed(int id, hipStream_t s, F &&launch) {
-    if (!g_profiling) return launch_status(launch());
+    if (!g_profiling.load(std::memory_order_relaxed)) return launch_status(launch());
     TimedLaunch t{id, nullptr, nullptr};
     if (hipEventCreate(&t.start) != hipSuccess || hipEventCreate(&t.stop) != hipSuccess) return MDN_ERR_LAUNCH;
     const bool r0 = hipEventRecord(t.start, s) == hipSuccess;
     const int rc = launch_status(launch());
     const bool r1 = hipEventRecord(t.stop, s) == hipSuccess;
-    g_timed.push_back(t);
+    {
+        std::lock_guard<std::mutex> lock(g_timed_mutex);
+        g_timed.push_back(t);
+    }
     return r0 && r1 ? rc : MDN_ERR_LAUNCH;
 }
 
@@ -187,33 +194,19 @@ template <typename F> int timed(int id, hipStream_t s, F &&launch) {
 // i (backward) runs beside the scan of the neighbouring segment, on a second stream of the library's own:
 // the scan's workgroups leave the other CUs to it.  States cross a segment boundary through two small fp32
 // buffers in the workspace.
-int num_cus() {
-    static const int n = [] {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
-            v = 256;
-        return v;
-    }();
-    return n;
-}
-
-int g_segments = 0; // 0: automatic
-bool g_side_stream_taken = false; // two calls run beside each other on the two streams: no segments inside them
+std::atomic<int> g_segments{0}; // 0: automatic
+// this thread is inside a pair of calls that run beside each other on the two streams: no segments inside them
+thread_local bool t_side_stream_taken = false;
 
 // the serial scans of a call would occupy at most half of the CUs
-bool few_scan_workgroups(const Dims &d) {
-    // workgroups of a scan launch: one per (batch*head rounded up to 8, block of 32 or 16 dv columns)
-    const bool dvb16 = d.BH * (d.dv / 32) < 192 || (d.dtype == MDN_DTYPE_F32 && d.dk == 128);
-    const int scan_wgs = (d.BH + 7) / 8 * 8 * (d.dv / (dvb16 ? 16 : 32));
-    return 2 * scan_wgs <= num_cus();
-}
+bool few_scan_workgroups(const Dims &d) { return 2 * scan_workgroups(d) <= num_cus(); }
 
 int segments(const Dims &d) {
     int k;
-    if (g_side_stream_taken) return 1;
-    if (g_segments > 0) {
-        k = g_segments;
+    if (t_side_stream_taken) return 1;
+    const int forced = g_segments.load(std::memory_order_relaxed);
+    if (forced > 0) {
+        k = forced;
     } else {
         k = (few_scan_workgroups(d) && d.N >= 32) ? 4 : 1;
     }
@@ -221,17 +214,27 @@ int segments(const Dims &d) {
     return k < 1 ? 1 : (k > 16 ? 16 : k);
 }
 
+// The library's second stream and its events, one set per device, shared by every call on that device.  A call that
+// uses them holds the device's mutex while it ENQUEUES (the kernels themselves run after it has returned): an event
+// is recorded and waited for inside one such section, so calls from several host threads cannot interleave their
+// record / wait pairs; their work on the second stream is simply ordered one call after the other.
 struct Side {
     hipStream_t stream = nullptr;
     std::vector<hipEvent_t> ev;
+    std::recursive_mutex mutex; // (recursive: two calls beside each other take it, then each call inside may again)
 };
 
-// the library's second stream and n events on the current device (created once, default priority)
-Side *side(int n) {
-    static std::vector<Side> per_device(64);
+// the second stream and n events on the current device (created once, default priority); call with the lock held
+Side *side_device() {
+    static Side per_device[64];
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= (int)per_device.size()) return nullptr;
-    Side &x = per_device[dev];
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    return &per_device[dev];
+}
+Side *side(int n) {
+    Side *xp = side_device();
+    if (!xp) return nullptr;
+    Side &x = *xp;
     if (!x.stream && hipStreamCreateWithFlags(&x.stream, hipStreamNonBlocking) != hipSuccess) return nullptr;
     while ((int)x.ev.size() < n) {
         hipEvent_t e;
@@ -281,22 +284,28 @@ int run_fwd(const Dims &d, const FwdCall &c, const FwdWs &w, hipStream_t s) {
         return timed(MDN_KERNEL_SCAN_FWD, s, [&] { return launch_scan_fwd(d, sa, s); });
     }
     // segments: precompute of segment i+1 on the second stream beside the scan of segment i on the caller's
+    Side *sdev = side_device();
+    if (!sdev) return MDN_ERR_LAUNCH;
+    std::lock_guard<std::recursive_mutex> lock(sdev->mutex);
     Side *sd = side(nseg + 1);
     if (!sd) return MDN_ERR_LAUNCH;
     if (hipEventRecord(sd->ev[nseg], s) != hipSuccess || hipStreamWaitEvent(sd->stream, sd->ev[nseg], 0) != hipSuccess)
         return MDN_ERR_LAUNCH; // whatever the caller's stream holds so far comes first
+    // (from here on the second stream holds work of this call: whatever happens, the caller's stream waits for it
+    //  before the call returns, so that "complete when the stream reaches the end of the call" also holds for a
+    //  call that fails half-way)
     for (int i = 0; i < nseg; ++i) {
         const Dims di = segment(d, i, nseg);
         rc = timed(MDN_KERNEL_INTRA_FWD, sd->stream, [&] { return launch_intra(di, mode, ia, sd->stream); });
+        const bool joined = hipEventRecord(sd->ev[i], sd->stream) == hipSuccess && hipStreamWaitEvent(s, sd->ev[i], 0) == hipSuccess;
         if (rc) return rc;
-        if (hipEventRecord(sd->ev[i], sd->stream) != hipSuccess || hipStreamWaitEvent(s, sd->ev[i], 0) != hipSuccess)
-            return MDN_ERR_LAUNCH;
+        if (!joined) return MDN_ERR_LAUNCH;
         sa.S0 = i == 0 ? c.S0 : w.carryS;
         sa.M0 = i == 0 ? c.M0 : w.carryM;
         sa.S_final = i == nseg - 1 ? c.S_final : w.carryS;
         sa.M_final = i == nseg - 1 ? c.M_final : w.carryM;
         rc = timed(MDN_KERNEL_SCAN_FWD, s, [&] { return launch_scan_fwd(di, sa, s); });
-        if (rc) return rc;
+        if (rc) return rc; // (every launch on the second stream so far has been joined above)
     }
     return MDN_OK;
 }
@@ -373,24 +382,30 @@ int bwd_run(const Dims &d, const BwdCall &c, const BwdWs &w, const Prepared &p, 
     }
     // segments, last first: the gradient kernel of segment i on the second stream beside the reverse scan
     // of segment i-1 on the caller's; the caller's stream then waits for the last gradient launch
+    Side *sdev = side_device();
+    if (!sdev) return MDN_ERR_LAUNCH;
+    std::lock_guard<std::recursive_mutex> lock(sdev->mutex);
     Side *sd = side(nseg + 1);
     if (!sd) return MDN_ERR_LAUNCH;
-    for (int i = nseg - 1; i >= 0; --i) {
+    rc = MDN_OK;
+    for (int i = nseg - 1; i >= 0 && !rc; --i) {
         const Dims di = segment(d, i, nseg);
         sb.dS_final = i == nseg - 1 ? c.dS_final : w.carryS;
         sb.dM_final = i == nseg - 1 ? c.dM_final : w.carryM;
         sb.dS0 = i == 0 ? c.dS0 : w.carryS;
         sb.dM0 = i == 0 ? c.dM0 : w.carryM;
         rc = timed(MDN_KERNEL_SCAN_BWD, s, [&] { return launch_scan_bwd(di, sb, s); });
-        if (rc) return rc;
-        if (hipEventRecord(sd->ev[i], s) != hipSuccess || hipStreamWaitEvent(sd->stream, sd->ev[i], 0) != hipSuccess)
-            return MDN_ERR_LAUNCH;
+        if (rc) break;
+        if (hipEventRecord(sd->ev[i], s) != hipSuccess || hipStreamWaitEvent(sd->stream, sd->ev[i], 0) != hipSuccess) {
+            rc = MDN_ERR_LAUNCH;
+            break;
+        }
         rc = timed(MDN_KERNEL_GRAD, sd->stream, [&] { return launch_grad(di, ga, sd->stream); });
-        if (rc) return rc;
     }
+    // the caller's stream waits for whatever went to the second stream, also when a launch failed on the way
     if (hipEventRecord(sd->ev[nseg], sd->stream) != hipSuccess || hipStreamWaitEvent(s, sd->ev[nseg], 0) != hipSuccess)
         return MDN_ERR_LAUNCH;
-    return MDN_OK;
+    return rc;
 }
 
 size_t fwd_ws_total(const Dims &d, int r) {
@@ -572,14 +587,17 @@ PackedWs carve_packed(const Dims &d, const int32_t *cu, int n_seq, bool backward
 // the two halves beside each other: first(stream), second(stream) are the two calls
 template <typename F1, typename F2> int run_beside(hipStream_t s, F1 &&first, F2 &&second) {
     constexpr int E0 = 30, E1 = 31; // (the events below these belong to the segments of a single call)
+    Side *sdev = side_device();
+    if (!sdev) return MDN_ERR_LAUNCH;
+    std::lock_guard<std::recursive_mutex> lock(sdev->mutex);
     Side *sd = side(E1 + 1);
     if (!sd) return MDN_ERR_LAUNCH;
     if (hipEventRecord(sd->ev[E0], s) != hipSuccess || hipStreamWaitEvent(sd->stream, sd->ev[E0], 0) != hipSuccess)
         return MDN_ERR_LAUNCH; // whatever the caller's stream holds so far comes first
-    g_side_stream_taken = true;
+    t_side_stream_taken = true;
     int rc = first(s);
     if (!rc) rc = second(sd->stream);
-    g_side_stream_taken = false;
+    t_side_stream_taken = false;
     if (hipEventRecord(sd->ev[E1], sd->stream) != hipSuccess || hipStreamWaitEvent(s, sd->ev[E1], 0) != hipSuccess)
         return MDN_ERR_LAUNCH;
     return rc;
@@ -720,21 +738,22 @@ extern "C" {
 
 int mdn_version(void) { return 100; }
 
-int mdn_set_segments(int k) {
-    const int prev = g_segments;
-    g_segments = k < 0 ? 0 : k;
-    return prev;
-}
+int mdn_set_segments(int k) { return g_segments.exchange(k < 0 ? 0 : k); }
 
 int mdn_profile_begin(void) {
-    g_profiling = true;
+    g_profiling.store(true);
     return MDN_OK;
 }
 
 int mdn_profile_end(float *ms, int *launches, int n) {
-    g_profiling = false;
+    g_profiling.store(false);
     int rc = MDN_OK;
-    for (const TimedLaunch &t : g_timed) {
+    std::vector<TimedLaunch> taken;
+    {
+        std::lock_guard<std::mutex> lock(g_timed_mutex);
+        taken.swap(g_timed);
+    }
+    for (const TimedLaunch &t : taken) {
         float e = 0.f;
         if (hipEventSynchronize(t.stop) != hipSuccess || hipEventElapsedTime(&e, t.start, t.stop) != hipSuccess)
             rc = MDN_ERR_LAUNCH;
@@ -744,7 +763,6 @@ int mdn_profile_end(float *ms, int *launches, int n) {
         }
         if (hipEventDestroy(t.start) != hipSuccess || hipEventDestroy(t.stop) != hipSuccess) rc = MDN_ERR_LAUNCH;
     }
-    g_timed.clear();
     return rc;
 }
 

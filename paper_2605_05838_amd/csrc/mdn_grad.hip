@@ -634,17 +634,6 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     } // chunks of this workgroup
 }
 
-inline int num_cus() {
-    static const int n = [] {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
-            v = 256;
-        return v;
-    }();
-    return n;
-}
-
 template <typename T, int DK, int DV, bool STAGED, bool LO = false>
 hipError_t launch_t(const Dims &d, const GradArgs &a, hipStream_t s) {
     // staged (bf16): one workgroup per CU, each walking its share of the chunks; otherwise one per chunk

@@ -93,6 +93,14 @@ struct RecurrentArgs {
     void *o;
 };
 
+// compute units of the current device (256 if it cannot be asked)
+int num_cus();
+// dv columns per workgroup of the scans for this shape: 32, unless that leaves a quarter of the CUs or more without
+// a workgroup or (32-bit storage, d = 128) the prefetched fragments of 32 columns do not fit the registers: then 16
+int scan_dvb(const Dims &d);
+// workgroups of one scan launch: (batch*head rounded up to 8) x dv / scan_dvb
+int scan_workgroups(const Dims &d);
+
 // mode 0: forward operands, 1: reverse-pass operands, 2: both
 hipError_t launch_intra(const Dims &d, int mode, const IntraArgs &a, hipStream_t s);
 hipError_t launch_scan_fwd(const Dims &d, const ScanFwdArgs &a, hipStream_t s);

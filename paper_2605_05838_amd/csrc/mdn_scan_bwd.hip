@@ -293,17 +293,13 @@ hipError_t launch_t(const Dims &d, const ScanBwdArgs &a, hipStream_t s) {
     dim3 grid(((d.BH + 7) / 8) * 8 * G), block(kThreads);
     static const size_t spread =
         lds_bytes_for_one_workgroup_per_cu(reinterpret_cast<const void *>(&scan_bwd_kernel<T, DK, DV, DVB>));
-    const size_t dyn = grid.x <= 256 ? spread : 0; // fewer workgroups than CUs: one per CU
+    const size_t dyn = (int)grid.x <= num_cus() ? spread : 0; // no more workgroups than CUs: one per CU
     hipLaunchKernelGGL((scan_bwd_kernel<T, DK, DV, DVB>), grid, block, dyn, s, d, a);
     return hipGetLastError();
 }
 
-// 32 dv columns per workgroup unless that leaves most of the 256 CUs without a workgroup
-// (fp32 storage at d = 128 always takes 16: the prefetched fragments of 32 columns do not fit the registers)
 template <typename T, int DK, int DV> hipError_t pick_dvb(const Dims &d, const ScanBwdArgs &a, hipStream_t s) {
-    static const char *force = getenv("MDN_DVB"); // tuning override: 16 or 32
-    const bool f16 = force && force[0] == '1', f32c = force && force[0] == '3';
-    if (!f32c && (f16 || d.BH * (DV / 32) < 192 || (sizeof(T) == 4 && DK == 128))) return launch_t<T, DK, DV, 16>(d, a, s);
+    if (scan_dvb(d) == 16) return launch_t<T, DK, DV, 16>(d, a, s);
     return launch_t<T, DK, DV, 32>(d, a, s);
 }
 

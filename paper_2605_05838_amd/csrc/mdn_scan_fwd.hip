@@ -181,9 +181,9 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
     __syncthreads();
 
     // one chunk: its operands are in `cur`; those of the next chunk go on their way into `nxt`, portion by portion.
-    // The k tile of chunk n+2 is requested first of all: every wave uses values it loads later in this step (the
-    // next chunk's V and q rows) during the next step, before that step's barriers, and loads return in order, so
-    // each wave's part of the tile has landed by then and the barriers publish it before chunk n+2 begins.
+    // The k tile of chunk n+2 is requested first of all; each wave waits for its part of that transfer before the
+    // first barrier of the NEXT step (see the wait there), and that step's barriers publish the tile before chunk
+    // n+2 begins.
     int slot = 0;
     auto step = [&](int n, const CO &cur, CO &nxt) {
         const size_t blk = (size_t)bh * d.N + n;
@@ -270,6 +270,17 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
             for (int mv = 0; mv < MV; ++mv) {
                 accO[mv] = d.scale * (cur.c0[COEF_A] * accOS[mv] - cur.c0[COEF_B] * accOM[mv]);
                 TV::put4(sRt, mv * 16 + kg * 4, i, widen4(cur.u[mv]) - cur.c0[COEF_A] * x1[mv] + cur.c0[COEF_PB] * x2[mv]);
+            }
+            if constexpr (KTILE) {
+                // This wave's part of the k tile requested at the start of the PREVIOUS step has landed: at least
+                // AFTER vector-memory instructions were issued behind it (previous step: coefficients and V 3, q KS,
+                // T and Bm 4, o 1; this step: coefficients and V 3, q KS; more with the optional stores and the next
+                // tile's request), they complete in order, and no more than AFTER of them are younger than this
+                // step's own requests (the tile's D/32, 3, the 2 ND state stores, KS) -- so the wait never holds a
+                // wave for a load it has only just issued.
+                constexpr int AFTER = 11 + 2 * CO::KS;
+                static_assert(AFTER <= 63 && DK / 32 + 3 + 2 * ND + CO::KS <= AFTER, "vmcnt immediate");
+                __builtin_amdgcn_s_waitcnt(0x0F70 | (AFTER & 15) | ((AFTER >> 4) << 14));
             }
             __syncthreads();
             f32x4 accV[MV];
@@ -371,18 +382,14 @@ hipError_t launch_scan_t(const Dims &d, const ScanFwdArgs &a, hipStream_t s) {
     dim3 grid(((d.BH + 7) / 8) * 8 * G), block(kThreads);
     static const size_t spread = lds_bytes_for_one_workgroup_per_cu(
         reinterpret_cast<const void *>(&scan_fwd_kernel<T, DK, DV, DVB, REBUILD>));
-    const size_t dyn = grid.x <= 256 ? spread : 0; // fewer workgroups than CUs: one per CU
+    const size_t dyn = (int)grid.x <= num_cus() ? spread : 0; // no more workgroups than CUs: one per CU
     hipLaunchKernelGGL((scan_fwd_kernel<T, DK, DV, DVB, REBUILD>), grid, block, dyn, s, d, a);
     return hipGetLastError();
 }
 
-// 32 dv columns per workgroup unless that leaves most of the 256 CUs without a workgroup
-// (fp32 storage at d = 128 always takes 16: the prefetched fragments of 32 columns do not fit the registers)
 template <typename T, int DK, int DV, bool REBUILD>
 hipError_t pick_dvb(const Dims &d, const ScanFwdArgs &a, hipStream_t s) {
-    static const char *force = getenv("MDN_DVB"); // tuning override: 16 or 32
-    const bool f16 = force && force[0] == '1', f32c = force && force[0] == '3';
-    if (!f32c && (f16 || d.BH * (DV / 32) < 192 || (sizeof(T) == 4 && DK == 128))) return launch_scan_t<T, DK, DV, 16, REBUILD>(d, a, s);
+    if (scan_dvb(d) == 16) return launch_scan_t<T, DK, DV, 16, REBUILD>(d, a, s);
     return launch_scan_t<T, DK, DV, 32, REBUILD>(d, a, s);
 }
 
@@ -397,6 +404,24 @@ template <bool REBUILD> hipError_t dispatch_scan(const Dims &d, const ScanFwdArg
 }
 
 } // namespace
+
+int num_cus() {
+    static const int n = [] {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
+            v = 256;
+        return v;
+    }();
+    return n;
+}
+
+int scan_dvb(const Dims &d) {
+    const bool f32 = d.dtype == 1;
+    return (4 * d.BH * (d.dv / 32) < 3 * num_cus() || (f32 && d.dk == 128)) ? 16 : 32;
+}
+
+int scan_workgroups(const Dims &d) { return (d.BH + 7) / 8 * 8 * (d.dv / scan_dvb(d)); }
 
 size_t lds_bytes_for_one_workgroup_per_cu(const void *kernel) {
     hipFuncAttributes fa;

@@ -105,3 +105,117 @@ def test_varlen_workspace_query_validates_the_offsets():
     assert lib.mdn_workspace_bytes_varlen(ctypes.byref(s1), cu(1, 100, 300), 2, 0, ctypes.byref(n)) == -2   # does not start at 0
     assert lib.mdn_workspace_bytes_varlen(ctypes.byref(shape(B=2, T=300)), cu(0, 100, 300), 2, 0, ctypes.byref(n)) == -2
     assert lib.mdn_workspace_bytes_varlen(ctypes.byref(s1), None, 2, 0, ctypes.byref(n)) == -1
+
+
+def _cpu_inputs(B=1, T=64, H=2, d=64, dtype=None):
+    import torch
+    dtype = dtype or torch.float32
+    q = torch.zeros(B, T, H, d, dtype=dtype)
+    g = torch.zeros(B, T, H)
+    return dict(q=q, k=q.clone(), v=q.clone(), beta=g, alpha=g.clone(), mu=g.clone())
+
+
+@pytest.mark.parametrize("bad", ["k_shape", "v_dtype", "gate_shape", "gate_dtype", "S0_shape", "eta_shape", "out_o",
+                                 "workspace_small", "states_small"])
+def test_binding_refuses_tensors_that_do_not_fit_q_before_any_launch(bad):
+    """The C ABI trusts raw pointers, so the binding checks every tensor's shape, dtype and device against what q
+    implies; the checks run before a pointer is taken (they fire on CPU tensors, with no device in reach)."""
+    import torch
+    t = _cpu_inputs()
+    kw = {}
+    if bad == "k_shape":
+        t["k"] = torch.zeros(1, 64, 2, 32)
+    elif bad == "v_dtype":
+        t["v"] = t["v"].to(torch.bfloat16)
+    elif bad == "gate_shape":
+        t["alpha"] = torch.zeros(1, 63, 2)
+    elif bad == "gate_dtype":
+        t["mu"] = t["mu"].double()
+    elif bad == "S0_shape":
+        kw["S0"] = torch.zeros(1, 2, 64, 32)
+    elif bad == "eta_shape":
+        kw["eta"] = torch.zeros(1, 64)
+    elif bad == "out_o":
+        kw["out"] = {"o": torch.zeros(1, 32, 2, 64)}
+    elif bad == "workspace_small":
+        kw["workspace"] = torch.zeros(1024, dtype=torch.uint8)
+    elif bad == "states_small":
+        kw.update(save_states=True, out={"states": torch.zeros(16)})
+    with pytest.raises(binding.MdnError) as e:
+        binding.mdn_chunk_fwd(t["q"], t["k"], t["v"], t["beta"], t["alpha"], t["mu"], **kw)
+    assert "GPU" not in str(e.value), str(e.value)      # refused for what is wrong with it, not for being a CPU tensor
+
+
+def test_binding_checks_the_backward_and_the_other_entry_points_too():
+    import torch
+    t = _cpu_inputs()
+    names = ("q", "k", "v", "beta", "alpha", "mu")
+    vt = torch.zeros(1, 64, 2, 64)
+    with pytest.raises(binding.MdnError, match="dO"):
+        binding.mdn_chunk_bwd(*(t[k] for k in names), vt, torch.zeros(1, 64, 2, 32))
+    with pytest.raises(binding.MdnError, match="dS_final"):
+        binding.mdn_chunk_bwd(*(t[k] for k in names), vt, vt.clone(), dS_final=torch.zeros(1, 2, 64, 64, dtype=torch.float64))
+    with pytest.raises(binding.MdnError, match=r"out\['dq'\]"):
+        binding.mdn_chunk_bwd(*(t[k] for k in names), vt, vt.clone(), out={"dq": torch.zeros(1, 64, 2, 32)})
+    S = torch.zeros(1, 2, 64, 64)
+    with pytest.raises(binding.MdnError, match="M0"):     # the states of the recurrent step go through the same check
+        binding.mdn_recurrent_step(*(t[k] for k in names), S, torch.zeros(1, 2, 64, 32))
+    with pytest.raises(binding.MdnError, match="cu_seqlens"):
+        binding.mdn_chunk_fwd_varlen(*(t[k] for k in names), [0, 40, 63])
+    with pytest.raises(binding.MdnError, match="cu_seqlens"):
+        binding.mdn_chunk_fwd_varlen(*(t[k] for k in names), [0, 40, 40, 64])
+    with pytest.raises(binding.MdnError, match="S0"):     # per-sequence states: [n_seq, H, dk, dv]
+        binding.mdn_chunk_fwd_varlen(*(t[k] for k in names), [0, 40, 64], S0=torch.zeros(1, 2, 64, 64))
+    x = torch.zeros(1, 64, 2)
+    h = torch.zeros(2)
+    with pytest.raises(binding.MdnError, match="b_mu"):
+        binding.mdn_gates_fwd(x, x, x, x, h, h, h, torch.zeros(3), 1.0, 1.0)
+    with pytest.raises(binding.MdnError, match="x_beta"):
+        binding.mdn_gates_fwd(x, x, torch.zeros(1, 64, 3), x, h, h, h, h, 1.0, 1.0)
+    with pytest.raises(binding.MdnError, match="x_k"):
+        binding.mdn_frontend_fwd(t["q"], torch.zeros(1, 64, 2, 32), t["v"], h)
+    with pytest.raises(binding.MdnError, match="w"):
+        binding.mdn_epilogue_fwd(t["q"], t["q"], torch.zeros(32))
+
+
+def test_backward_workspace_for_calls_with_adjoints_of_the_final_states():
+    """Such a call keeps the rounding remainders of the chunk states and chunk adjoints (16-bit storage): two more
+    state-sized tensors; with 32-bit storage nothing changes."""
+    plain = binding.workspace_bytes(shape(), binding.MDN_WS_BWD)
+    more = binding.workspace_bytes(shape(), binding.MDN_WS_BWD_STATE_ADJOINTS)
+    states = 2 * 3 * 2 * 2 * 128 * 128 * 2
+    assert more == plain + 2 * states
+    f32 = shape(dtype=1)
+    assert binding.workspace_bytes(f32, binding.MDN_WS_BWD) == binding.workspace_bytes(f32, binding.MDN_WS_BWD_STATE_ADJOINTS)
+    lib = binding.load_library()
+    n = ctypes.c_size_t(0)
+    assert lib.mdn_workspace_bytes(ctypes.byref(shape()), 3, ctypes.byref(n)) == -2
+
+
+def test_host_side_entry_points_from_several_threads():
+    """mdn_set_segments is one atomic exchange for the process and the size queries touch no shared state: threads that
+    call them at the same time see consistent values (every value a call returns is one that some call has set)."""
+    import threading
+    lib = binding.load_library()
+    want = binding.workspace_bytes(shape(), binding.MDN_WS_BWD)
+    old = lib.mdn_set_segments(0)
+    seen, wrong = [set() for _ in range(8)], []
+
+    def work(i):
+        n = ctypes.c_size_t(0)
+        for it in range(3000):
+            seen[i].add(lib.mdn_set_segments(1 + (i + it) % 7))
+            if lib.mdn_workspace_bytes(ctypes.byref(shape()), 1, ctypes.byref(n)) != 0 or n.value != want:
+                wrong.append(n.value)
+            if lib.mdn_strerror(-4 - i % 3) is None:
+                wrong.append("strerror")
+
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(8)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    last = lib.mdn_set_segments(old)
+    assert not wrong
+    assert set().union(*seen) <= set(range(0, 8)) and 1 <= last <= 7
+    assert lib.mdn_set_segments(old) == old
