@@ -111,6 +111,25 @@ int mdn_chunk_fwd(const mdn_shape *shape, const void *q, const void *k, const vo
                   void *operands_saved, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * mdn_chunk_fwd for callers that cannot allocate device memory or create streams and events: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs, outputs, results (bit for bit) and
+ * errors as mdn_chunk_fwd without states_saved / operands_saved; what would be the workspace is a fixed array of
+ * MDN_NOALLOC_SCRATCH_BYTES inside the library's device image (each GPU the library runs on holds its own copy until
+ * the process ends).  The call allocates nothing, creates nothing and never uses a second stream (one launch sequence
+ * on `stream`, whatever the shape).
+ *   - A shape whose mdn_workspace_bytes(MDN_WS_FWD) exceeds MDN_NOALLOC_SCRATCH_BYTES is refused with
+ *     MDN_ERR_WORKSPACE before anything is launched (16-bit storage, d = 128: about 18 KB per chunk and
+ *     (batch, head) pair, i.e. up to B*H*T = 233 000 tokens-heads; 32-bit storage, d = 128: 66 KB per chunk).
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two host
+ *     threads) race on it and give wrong results; calls ordered on one stream are safe.  The array keeps the last
+ *     call's contents; nothing in it has to start from zero.
+ */
+#define MDN_NOALLOC_SCRATCH_BYTES (64u << 20)
+int mdn_chunk_fwd_noalloc(const mdn_shape *shape, const void *q, const void *k, const void *v, const float *beta,
+                          const float *alpha, const float *mu, const float *eta, const float *S0, const float *M0,
+                          void *o, float *S_final, float *M_final, void *vt_saved, void *stream);
+
+/*
  * Chunkwise backward: adjoint of mdn_chunk_fwd for the scalar
  *     L = <o, dO> + <S_final, dS_final> + <M_final, dM_final>.
  * The forward keeps V~ only (Sec. 3.1 "Practical Considerations"); the chunk-start states

@@ -18,7 +18,7 @@ MDN_DTYPE_BF16, MDN_DTYPE_F32 = 0, 1
 MDN_WS_FWD, MDN_WS_BWD, MDN_WS_BWD_STATE_ADJOINTS = 0, 1, 2
 
 EXPORTS = ("mdn_version", "mdn_strerror", "mdn_workspace_bytes", "mdn_saved_states_bytes",
-           "mdn_saved_operands_bytes", "mdn_chunk_fwd",
+           "mdn_saved_operands_bytes", "mdn_chunk_fwd", "mdn_chunk_fwd_noalloc",
            "mdn_chunk_bwd", "mdn_recurrent_step", "mdn_profile_begin", "mdn_profile_end", "mdn_set_segments",
            "mdn_gates_fwd", "mdn_gates_bwd", "mdn_frontend_fwd", "mdn_frontend_bwd", "mdn_epilogue_fwd",
            "mdn_epilogue_bwd", "mdn_workspace_bytes_varlen", "mdn_chunk_fwd_varlen", "mdn_chunk_bwd_varlen")
@@ -64,6 +64,8 @@ def load_library():
     lib.mdn_saved_operands_bytes.argtypes = [sp, ctypes.POINTER(ctypes.c_size_t)]
     lib.mdn_chunk_fwd.restype = ctypes.c_int
     lib.mdn_chunk_fwd.argtypes = [sp] + [vp] * 3 + [fp] * 6 + [vp, fp, fp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.mdn_chunk_fwd_noalloc.restype = ctypes.c_int
+    lib.mdn_chunk_fwd_noalloc.argtypes = [sp] + [vp] * 3 + [fp] * 6 + [vp, fp, fp, vp, vp]
     lib.mdn_chunk_bwd.restype = ctypes.c_int
     lib.mdn_chunk_bwd.argtypes = [sp] + [vp] * 3 + [fp] * 6 + [vp] * 4 + [fp] * 2 + [vp] * 3 + [fp] * 6 + \
         [vp, ctypes.c_size_t, vp]
@@ -258,6 +260,24 @@ def mdn_chunk_fwd(q, k, v, beta, alpha, mu, eta=None, S0=None, M0=None, scale=No
                            _ptr(M), _ptr(vt), _ptr(states), _ptr(operands), _ptr(workspace), wbytes, _stream())
     _check(rc, "mdn_chunk_fwd")
     return {"o": o, "S": S, "M": M, "vt": vt, "states": states, "operands": operands, "workspace": workspace}
+
+
+def mdn_chunk_fwd_noalloc(q, k, v, beta, alpha, mu, out, eta=None, S0=None, M0=None, scale=None):
+    """mdn_chunk_fwd through the entry point that allocates nothing: `out` holds the caller's o and, optionally, S, M
+    and vt tensors (all of them preallocated; this function creates no tensor either).  Returns `out`."""
+    lib = load_library()
+    B, T, H, dk, dv = _check_inputs(q, k, v, beta, alpha, mu, eta, S0, M0)
+    shape = make_shape(q, v, scale)
+    f32 = torch.float32
+    _expect("out['o']", out.get("o"), (B, T, H, dv), q.dtype, q)
+    _expect("out['S']", out.get("S"), (B, H, dk, dv), f32, q, optional=True)
+    _expect("out['M']", out.get("M"), (B, H, dk, dv), f32, q, optional=True)
+    _expect("out['vt']", out.get("vt"), (B, T, H, dv), q.dtype, q, optional=True)
+    rc = lib.mdn_chunk_fwd_noalloc(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _f32(beta, "beta"),
+                                   _f32(alpha, "alpha"), _f32(mu, "mu"), _f32(eta, "eta"), _f32(S0, "S0"), _f32(M0, "M0"),
+                                   _ptr(out["o"]), _ptr(out.get("S")), _ptr(out.get("M")), _ptr(out.get("vt")), _stream())
+    _check(rc, "mdn_chunk_fwd_noalloc")
+    return out
 
 
 def mdn_chunk_bwd(q, k, v, beta, alpha, mu, vt, dO, eta=None, S0=None, M0=None, states=None, operands=None,

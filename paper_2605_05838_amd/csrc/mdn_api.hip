@@ -51,7 +51,7 @@ FwdWs carve_fwd(const Dims &d, void *ws) {
     Carver c(ws);
     FwdWs w;
     w.coef = static_cast<float *>(c.take(nb * (size_t)(64 * kCoefBlockCols * sizeof(float))));
-    w.KT = c.take(nb * d.dk * 64 * es);
+    w.KT = scan_fwd_reads_KT(d) ? c.take(nb * d.dk * 64 * es) : nullptr; // (16-bit storage: made on chip from the k rows)
     w.Tm = c.take(nb * 4096 * es);
     w.Bm = c.take(nb * 4096 * es);
     // states handed from one segment of the sequence to the next when the call is split (see segments())
@@ -175,8 +175,11 @@ std::atomic<bool> g_profiling{false};
 std::mutex g_timed_mutex;
 std::vector<TimedLaunch> g_timed;
 
+// this thread is inside the entry point that must not allocate: no timing events, no second stream
+thread_local bool t_no_alloc = false;
+
 template <typename F> int timed(int id, hipStream_t s, F &&launch) {
-    if (!g_profiling.load(std::memory_order_relaxed)) return launch_status(launch());
+    if (t_no_alloc || !g_profiling.load(std::memory_order_relaxed)) return launch_status(launch());
     TimedLaunch t{id, nullptr, nullptr};
     if (hipEventCreate(&t.start) != hipSuccess || hipEventCreate(&t.stop) != hipSuccess) return MDN_ERR_LAUNCH;
     const bool r0 = hipEventRecord(t.start, s) == hipSuccess;
@@ -203,7 +206,7 @@ bool few_scan_workgroups(const Dims &d) { return 2 * scan_workgroups(d) <= num_c
 
 int segments(const Dims &d) {
     int k;
-    if (t_side_stream_taken) return 1;
+    if (t_side_stream_taken || t_no_alloc) return 1;
     const int forced = g_segments.load(std::memory_order_relaxed);
     if (forced > 0) {
         k = forced;
@@ -726,6 +729,27 @@ int packed_final_states(const Dims &d, const int32_t *cu, int n_seq, const FwdCa
     return run_fwd(dr, c, carve_fwd(dr, w.rest_rows), s);
 }
 
+// ---- the forward's workspace as a fixed array in device memory, for callers that cannot allocate.  Every GPU the
+// library runs on holds its own copy of the array (at its own address) until the process ends.  In host code the
+// array's name is only a handle for hipGetSymbolAddress: the address it returns, per device, is what is passed on.
+static __device__ __align__(256) unsigned char scratch[MDN_NOALLOC_SCRATCH_BYTES];
+
+// device address of `scratch` on the current device (asked for once per device, with that device current)
+int scratch_address(void **out) {
+    static std::mutex mutex;
+    static void *per_device[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MDN_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(mutex);
+    if (!per_device[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return MDN_ERR_DEVICE;
+        per_device[dev] = p;
+    }
+    *out = per_device[dev];
+    return MDN_OK;
+}
+
 template <typename P> P *at_token(P *base, size_t token, size_t bytes_per_token) {
     return base ? reinterpret_cast<P *>(reinterpret_cast<char *>(const_cast<typename std::remove_const<P>::type *>(base)) +
                                         token * bytes_per_token)
@@ -772,7 +796,7 @@ const char *mdn_strerror(int code) {
     case MDN_ERR_NULL: return "a required pointer is NULL";
     case MDN_ERR_SHAPE: return "unsupported shape (need dk = dv in {64,128}, C = 64, sizes >= 1)";
     case MDN_ERR_DTYPE: return "unsupported dtype";
-    case MDN_ERR_WORKSPACE: return "workspace too small";
+    case MDN_ERR_WORKSPACE: return "workspace too small (or, for mdn_chunk_fwd_noalloc, the shape needs more than its fixed scratch array)";
     case MDN_ERR_ALIGN: return "pointer not 16-byte aligned";
     case MDN_ERR_LAUNCH: return "kernel launch failed";
     case MDN_ERR_DEVICE: return "current device is not gfx950";
@@ -828,6 +852,30 @@ int mdn_chunk_fwd(const mdn_shape *shape, const void *q, const void *k, const vo
     hipStream_t s = static_cast<hipStream_t>(stream);
     FwdCall c = {q, k, v, beta, alpha, mu, eta, S0, M0, o, S_final, M_final, vt_saved, states_saved, operands_saved};
     return fwd_any(d, r, c, workspace, s);
+}
+
+int mdn_chunk_fwd_noalloc(const mdn_shape *shape, const void *q, const void *k, const void *v, const float *beta,
+                          const float *alpha, const float *mu, const float *eta, const float *S0, const float *M0,
+                          void *o, float *S_final, float *M_final, void *vt_saved, void *stream) {
+    Dims d;
+    int rc = check_shape(shape, true, &d);
+    if (rc) return rc;
+    if (!q || !k || !v || !beta || !alpha || !mu || !o) return MDN_ERR_NULL;
+    const void *ptrs[] = {q, k, v, beta, alpha, mu, eta, S0, M0, o, S_final, M_final, vt_saved};
+    for (const void *p : ptrs)
+        if (p && misaligned(p)) return MDN_ERR_ALIGN;
+    const int r = shape->T % 64;
+    if (fwd_ws_total(d, r) > (size_t)MDN_NOALLOC_SCRATCH_BYTES) return MDN_ERR_WORKSPACE;
+    void *ws = nullptr;
+    rc = scratch_address(&ws);
+    if (rc) return rc;
+    // Nothing in the forward's workspace has to start from zero: the chunk-local operands are written in full by the
+    // chunk-parallel kernel before the scan reads them, the padded copies of a partial chunk by the gather kernel.
+    FwdCall c = {q, k, v, beta, alpha, mu, eta, S0, M0, o, S_final, M_final, vt_saved, nullptr, nullptr};
+    t_no_alloc = true; // one stream, no timing events: nothing below creates a stream, an event or memory
+    rc = fwd_any(d, r, c, ws, static_cast<hipStream_t>(stream));
+    t_no_alloc = false;
+    return rc;
 }
 
 int mdn_chunk_bwd(const mdn_shape *shape, const void *q, const void *k, const void *v, const float *beta,
