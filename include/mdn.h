@@ -27,10 +27,13 @@
  *   - shape.dtype selects the storage type of q, k, v, o, dO, dq, dk, dv and of every
  *     intermediate the library stores: MDN_DTYPE_BF16 (bf16 MFMA operands, fp32 accumulation
  *     and fp32 states) or MDN_DTYPE_F32 (fp32 MFMA throughout).
- *   - All pointers must be 16-byte aligned.  dk, dv in {64, 128}; C = 64; any T >= 1: when T is not a
- *     multiple of C the last chunk is partial (Algorithm 1 pads it; here the padding tokens are exact
- *     identity steps, k = v = q = 0, alpha = mu = 1, beta = 0, on copies inside the workspace, so outputs,
- *     final states and gradients are those of the T tokens given).
+ *   - All pointers must be 16-byte aligned.  dk, dv in {64, 128}; C in {16, 32, 64} (Algorithm 1's chunk sizes);
+ *     any T >= 1: when T is not a multiple of C the last chunk is partial (Algorithm 1 pads it; here the padding
+ *     tokens are exact identity steps, k = v = q = 0, alpha = mu = 1, beta = 0, on copies inside the workspace, so
+ *     outputs, final states and gradients are those of the T tokens given).  C = 64 is the tuned path: the kernels
+ *     work on 64-token tiles, and a chunk of 16 or 32 tokens runs as one such tile filled up with identity steps
+ *     (the exact algorithm at that chunk size, at 64 / C times the work and workspace; results do not depend on C
+ *     beyond rounding).  The packed variable-length calls take C = 64 only.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
  *     ordered after what the stream already holds and is complete when the stream reaches the
  *     end of the call; no call synchronises.  When the serial scans would leave at least half
@@ -58,7 +61,7 @@ enum { MDN_DTYPE_BF16 = 0, MDN_DTYPE_F32 = 1 };
 enum {
     MDN_OK = 0,
     MDN_ERR_NULL = -1,      /* a required pointer is NULL */
-    MDN_ERR_SHAPE = -2,     /* unsupported B/T/H/dk/dv/C (dk or dv not in {64,128}, C != 64, sizes < 1, ...) */
+    MDN_ERR_SHAPE = -2,     /* unsupported B/T/H/dk/dv/C (dk or dv not in {64,128}, C not in {16,32,64}, sizes < 1, ...) */
     MDN_ERR_DTYPE = -3,     /* dtype is neither MDN_DTYPE_BF16 nor MDN_DTYPE_F32 */
     MDN_ERR_WORKSPACE = -4, /* workspace_bytes smaller than mdn_workspace_bytes() reports */
     MDN_ERR_ALIGN = -5,     /* a pointer is not 16-byte aligned */
@@ -71,7 +74,7 @@ enum { MDN_WS_FWD = 0, MDN_WS_BWD = 1, MDN_WS_BWD_STATE_ADJOINTS = 2 };
 typedef struct mdn_shape {
     int32_t B, T, H;  /* batch, sequence length, heads */
     int32_t dk, dv;   /* key / value head dimensions */
-    int32_t C;        /* chunk size (64); ignored by mdn_recurrent_step */
+    int32_t C;        /* chunk size: 64 (the tuned path), 32 or 16; ignored by mdn_recurrent_step */
     int32_t dtype;    /* MDN_DTYPE_* */
     float scale;      /* multiplies q; the paper's default is dk^-1/2 (Appendix E) */
 } mdn_shape;

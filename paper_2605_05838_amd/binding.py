@@ -220,11 +220,12 @@ def _workspace(shape, which, workspace, device):
 
 
 def mdn_chunk_fwd(q, k, v, beta, alpha, mu, eta=None, S0=None, M0=None, scale=None, save_vt=False,
-                  save_states=False, save_operands=False, output_final_state=True, workspace=None, out=None):
+                  save_states=False, save_operands=False, output_final_state=True, workspace=None, out=None,
+                  chunk_size=64):
     """Chunkwise forward.  Returns a dict: o, S, M (final states or None), vt, states, operands (or None)."""
     lib = load_library()
     B, T, H, dk, dv = _check_inputs(q, k, v, beta, alpha, mu, eta, S0, M0)
-    shape = make_shape(q, v, scale)
+    shape = make_shape(q, v, scale, chunk_size)
     out = {} if out is None else out
     dev = q.device
     o = out.get("o")
@@ -243,7 +244,7 @@ def mdn_chunk_fwd(q, k, v, beta, alpha, mu, eta=None, S0=None, M0=None, scale=No
     if save_states:
         states = out.get("states")
         if states is None:
-            states = torch.empty((B, H, -(-T // 64), 2, dk, dv), dtype=q.dtype, device=dev)  # opaque to the caller
+            states = torch.empty(saved_states_bytes(shape), dtype=torch.uint8, device=dev)  # opaque to the caller
     f32 = torch.float32
     _expect("out['o']", o, (B, T, H, dv), q.dtype, q)
     _expect("out['S']", S, (B, H, dk, dv), f32, q, optional=True)
@@ -262,12 +263,12 @@ def mdn_chunk_fwd(q, k, v, beta, alpha, mu, eta=None, S0=None, M0=None, scale=No
     return {"o": o, "S": S, "M": M, "vt": vt, "states": states, "operands": operands, "workspace": workspace}
 
 
-def mdn_chunk_fwd_noalloc(q, k, v, beta, alpha, mu, out, eta=None, S0=None, M0=None, scale=None):
+def mdn_chunk_fwd_noalloc(q, k, v, beta, alpha, mu, out, eta=None, S0=None, M0=None, scale=None, chunk_size=64):
     """mdn_chunk_fwd through the entry point that allocates nothing: `out` holds the caller's o and, optionally, S, M
     and vt tensors (all of them preallocated; this function creates no tensor either).  Returns `out`."""
     lib = load_library()
     B, T, H, dk, dv = _check_inputs(q, k, v, beta, alpha, mu, eta, S0, M0)
-    shape = make_shape(q, v, scale)
+    shape = make_shape(q, v, scale, chunk_size)
     f32 = torch.float32
     _expect("out['o']", out.get("o"), (B, T, H, dv), q.dtype, q)
     _expect("out['S']", out.get("S"), (B, H, dk, dv), f32, q, optional=True)
@@ -281,11 +282,13 @@ def mdn_chunk_fwd_noalloc(q, k, v, beta, alpha, mu, out, eta=None, S0=None, M0=N
 
 
 def mdn_chunk_bwd(q, k, v, beta, alpha, mu, vt, dO, eta=None, S0=None, M0=None, states=None, operands=None,
-                  dS_final=None, dM_final=None, scale=None, want_deta=False, want_dstates=True, workspace=None, out=None):
-    """Chunkwise backward.  Returns a dict: dq, dk, dv, dbeta, dalpha, dmu, deta, dS0, dM0."""
+                  dS_final=None, dM_final=None, scale=None, want_deta=False, want_dstates=True, workspace=None, out=None,
+                  chunk_size=64):
+    """Chunkwise backward (chunk_size as in the forward call whose vt, states, operands it takes).  Returns a dict:
+    dq, dk, dv, dbeta, dalpha, dmu, deta, dS0, dM0."""
     lib = load_library()
     B, T, H, dk, dv_ = _check_inputs(q, k, v, beta, alpha, mu, eta, S0, M0)
-    shape = make_shape(q, v, scale)
+    shape = make_shape(q, v, scale, chunk_size)
     out = {} if out is None else out
     dev = q.device
     _expect("vt", vt, (B, T, H, dv_), q.dtype, q)

@@ -22,8 +22,10 @@ int check_shape(const mdn_shape *s, bool chunked, Dims *d) {
     if (s->dtype != MDN_DTYPE_BF16 && s->dtype != MDN_DTYPE_F32) return MDN_ERR_DTYPE;
     if (s->B < 1 || s->T < 1 || s->H < 1) return MDN_ERR_SHAPE;
     if (!((s->dk == 64 && s->dv == 64) || (s->dk == 128 && s->dv == 128))) return MDN_ERR_SHAPE;
-    if (chunked && s->C != 64) return MDN_ERR_SHAPE;
-    if ((long long)s->B * s->H > (1 << 24) || (long long)s->B * s->T * s->H > (1LL << 31) - 1) return MDN_ERR_SHAPE;
+    if (chunked && s->C != 64 && s->C != 32 && s->C != 16) return MDN_ERR_SHAPE;
+    // (chunks of 16 or 32 tokens run as 64-token tiles: up to 4 rows per token)
+    const long long tile = chunked ? 64 / s->C : 1;
+    if ((long long)s->B * s->H > (1 << 24) || ((long long)s->B * s->T + 64) * s->H * tile > (1LL << 31) - 1) return MDN_ERR_SHAPE;
     d->B = s->B; d->T = s->T; d->H = s->H; d->N = s->T / 64; d->BH = s->B * s->H; // N: the FULL chunks
     d->n0 = 0; d->n1 = d->N;
     d->dk = s->dk; d->dv = s->dv; d->dtype = s->dtype; d->scale = s->scale;
@@ -525,12 +527,148 @@ int bwd_any(const Dims &d, int r, BwdCall c, void *workspace, hipStream_t s) {
     return launch_status(launch_tail_copy(out.c, false, s));
 }
 
+// ---- chunk sizes below 64 (Algorithm 1 lists C in {16, 32, 64}).  The kernels are built around 64-token tiles (four
+// waves of 16 tokens, 64-lane coefficient scans), so a chunk of C < 64 tokens runs as one such tile whose rows from C on
+// are identity steps of the recurrence (k = v = q = 0, alpha = mu = 1, beta = 0, dO = 0: they change no state and pass
+// every adjoint through, see the partial last chunk above): the chunk-local coefficients, the triangular solve and the
+// state hand-over are exactly those of Algorithm 1 at chunk size C, at 64 / C times the work of the C = 64 path.
+// The tokens are expanded into padded copies in the workspace and the results collected from them.
+Dims expanded_dims(const Dims &d, int C) {
+    Dims e = d;
+    const int NC = (d.T + C - 1) / C;
+    e.T = NC * 64; e.N = NC; e.n0 = 0; e.n1 = NC;
+    return e;
+}
+
+struct ExpBufs {
+    void *q, *k, *v, *o, *vt, *dO, *dq, *dk, *dv;
+    float *beta, *alpha, *mu, *eta, *dbeta, *dalpha, *dmu, *deta;
+    void *rest;
+    size_t total;
+};
+
+ExpBufs carve_exp(const Dims &e, bool backward, bool precise, void *p) {
+    const size_t es = elem_size(e), rows = (size_t)e.B * e.T * e.H;
+    Carver c(p);
+    ExpBufs x = {};
+    x.q = c.take(rows * e.dk * es);
+    x.k = c.take(rows * e.dk * es);
+    x.v = c.take(rows * e.dv * es);
+    x.vt = c.take(rows * e.dv * es);
+    x.beta = static_cast<float *>(c.take(rows * 4));
+    x.alpha = static_cast<float *>(c.take(rows * 4));
+    x.mu = static_cast<float *>(c.take(rows * 4));
+    x.eta = static_cast<float *>(c.take(rows * 4));
+    if (!backward) {
+        x.o = c.take(rows * e.dv * es);
+        x.rest = c.take(fwd_ws_total(e, 0));
+    } else {
+        x.dO = c.take(rows * e.dv * es);
+        x.dq = c.take(rows * e.dk * es);
+        x.dk = c.take(rows * e.dk * es);
+        x.dv = c.take(rows * e.dv * es);
+        x.dbeta = static_cast<float *>(c.take(rows * 4));
+        x.dalpha = static_cast<float *>(c.take(rows * 4));
+        x.dmu = static_cast<float *>(c.take(rows * 4));
+        x.deta = static_cast<float *>(c.take(rows * 4));
+        x.rest = c.take(bwd_ws_total(e, 0, precise));
+    }
+    x.total = c.off;
+    return x;
+}
+
+struct ChunkList {
+    ChunkCopy c;
+    ChunkList(const Dims &d, int C) {
+        c = {};
+        c.B = d.B; c.T = d.T; c.H = d.H; c.C = C; c.NC = (d.T + C - 1) / C;
+    }
+    void add(const void *full, void *padded, size_t row_bytes, float pad = 0.f) {
+        if (!full || !padded) return;
+        TailTensor &t = c.t[c.n++];
+        t.full = full; t.padded = padded; t.row_bytes = (int)row_bytes;
+        memcpy(&t.pad_word, &pad, 4);
+    }
+};
+
+int fwd_small_chunks(const Dims &d, int C, const FwdCall &c, void *workspace, hipStream_t s) {
+    const Dims e = expanded_dims(d, C);
+    const ExpBufs x = carve_exp(e, false, false, workspace);
+    const size_t es = elem_size(d);
+    ChunkList in(d, C);
+    in.add(c.q, x.q, d.dk * es);
+    in.add(c.k, x.k, d.dk * es);
+    in.add(c.v, x.v, d.dv * es);
+    in.add(c.beta, x.beta, 4, 0.f);
+    in.add(c.alpha, x.alpha, 4, 1.f);
+    in.add(c.mu, x.mu, 4, 1.f);
+    in.add(c.eta, x.eta, 4, 1.f);
+    int rc = launch_status(launch_chunk_copy(in.c, true, s));
+    if (rc) return rc;
+    const FwdCall ce = {x.q, x.k, x.v, x.beta, x.alpha, x.mu, c.eta ? x.eta : nullptr, c.S0, c.M0, x.o, c.S_final, c.M_final,
+                        c.vt_saved ? x.vt : nullptr, c.states_saved, c.operands_saved};
+    rc = run_fwd(e, ce, carve_fwd(e, x.rest), s);
+    if (rc) return rc;
+    ChunkList out(d, C);
+    out.add(c.o, x.o, d.dv * es);
+    out.add(c.vt_saved, x.vt, d.dv * es);
+    return launch_status(launch_chunk_copy(out.c, false, s));
+}
+
+int bwd_small_chunks(const Dims &d, int C, const BwdCall &c, void *workspace, hipStream_t s) {
+    const Dims e = expanded_dims(d, C);
+    const bool precise = precise_call(d, c);
+    const ExpBufs x = carve_exp(e, true, precise, workspace);
+    const size_t es = elem_size(d);
+    ChunkList in(d, C);
+    in.add(c.q, x.q, d.dk * es);
+    in.add(c.k, x.k, d.dk * es);
+    in.add(c.v, x.v, d.dv * es);
+    in.add(c.vt_saved, x.vt, d.dv * es);
+    in.add(c.dO, x.dO, d.dv * es);
+    in.add(c.beta, x.beta, 4, 0.f);
+    in.add(c.alpha, x.alpha, 4, 1.f);
+    in.add(c.mu, x.mu, 4, 1.f);
+    in.add(c.eta, x.eta, 4, 1.f);
+    int rc = launch_status(launch_chunk_copy(in.c, true, s));
+    if (rc) return rc;
+    const BwdCall ce = {x.q, x.k, x.v, x.beta, x.alpha, x.mu, c.eta ? x.eta : nullptr, c.S0, c.M0, x.vt, c.states_saved,
+                        c.operands_saved, x.dO, c.dS_final, c.dM_final, x.dq, x.dk, x.dv, x.dbeta, x.dalpha, x.dmu,
+                        c.deta ? x.deta : nullptr, c.dS0, c.dM0};
+    const BwdWs w = carve_bwd(e, x.rest, precise);
+    Prepared pm;
+    rc = bwd_prepare(e, ce, w, nullptr, nullptr, s, &pm, precise);
+    if (rc) return rc;
+    rc = bwd_run(e, ce, w, pm, s, precise);
+    if (rc) return rc;
+    ChunkList out(d, C);
+    out.add(c.dq, x.dq, d.dk * es);
+    out.add(c.dk, x.dk, d.dk * es);
+    out.add(c.dv, x.dv, d.dv * es);
+    out.add(c.dbeta, x.dbeta, 4);
+    out.add(c.dalpha, x.dalpha, 4);
+    out.add(c.dmu, x.dmu, 4);
+    out.add(c.deta, x.deta, 4);
+    return launch_status(launch_chunk_copy(out.c, false, s));
+}
+
+// workspace, kept states and kept operands of a call, whatever its chunk size
+size_t fwd_ws_call(const Dims &d, const mdn_shape *shape) {
+    if (shape->C == 64) return fwd_ws_total(d, shape->T % 64);
+    return carve_exp(expanded_dims(d, shape->C), false, false, nullptr).total;
+}
+size_t bwd_ws_call(const Dims &d, const mdn_shape *shape, bool precise) {
+    if (shape->C == 64) return bwd_ws_total(d, shape->T % 64, precise);
+    return carve_exp(expanded_dims(d, shape->C), true, precise, nullptr).total;
+}
+
 // ---- packed variable-length batches: the sequences lie one after another along T of a [1, T, H, *] tensor;
 // sequence i is tokens [cu[i], cu[i+1]).  Each sequence runs as a batch of one through the any-length path
 // (stream order makes the shared workspace safe).
 int check_varlen(const mdn_shape *shape, const int32_t *cu, int32_t n_seq, Dims *d) {
     const int rc = check_shape(shape, true, d);
     if (rc) return rc;
+    if (shape->C != 64) return MDN_ERR_SHAPE; // (packed batches: chunk size 64 only)
     if (!cu) return MDN_ERR_NULL;
     if (shape->B != 1 || n_seq < 1 || cu[0] != 0 || cu[n_seq] != shape->T) return MDN_ERR_SHAPE;
     for (int i = 0; i < n_seq; ++i)
@@ -794,7 +932,7 @@ const char *mdn_strerror(int code) {
     switch (code) {
     case MDN_OK: return "ok";
     case MDN_ERR_NULL: return "a required pointer is NULL";
-    case MDN_ERR_SHAPE: return "unsupported shape (need dk = dv in {64,128}, C = 64, sizes >= 1)";
+    case MDN_ERR_SHAPE: return "unsupported shape (need dk = dv in {64,128}, C in {16,32,64}, sizes >= 1)";
     case MDN_ERR_DTYPE: return "unsupported dtype";
     case MDN_ERR_WORKSPACE: return "workspace too small (or, for mdn_chunk_fwd_noalloc, the shape needs more than its fixed scratch array)";
     case MDN_ERR_ALIGN: return "pointer not 16-byte aligned";
@@ -809,9 +947,9 @@ int mdn_workspace_bytes(const mdn_shape *shape, int which, size_t *bytes_out) {
     if (!bytes_out) return MDN_ERR_NULL;
     int rc = check_shape(shape, true, &d);
     if (rc) return rc;
-    if (which == MDN_WS_FWD) *bytes_out = fwd_ws_total(d, shape->T % 64);
-    else if (which == MDN_WS_BWD) *bytes_out = bwd_ws_total(d, shape->T % 64, false);
-    else if (which == MDN_WS_BWD_STATE_ADJOINTS) *bytes_out = bwd_ws_total(d, shape->T % 64, d.dtype == MDN_DTYPE_BF16);
+    if (which == MDN_WS_FWD) *bytes_out = fwd_ws_call(d, shape);
+    else if (which == MDN_WS_BWD) *bytes_out = bwd_ws_call(d, shape, false);
+    else if (which == MDN_WS_BWD_STATE_ADJOINTS) *bytes_out = bwd_ws_call(d, shape, d.dtype == MDN_DTYPE_BF16);
     else return MDN_ERR_SHAPE;
     return MDN_OK;
 }
@@ -822,7 +960,8 @@ int mdn_saved_states_bytes(const mdn_shape *shape, size_t *bytes_out) {
     int rc = check_shape(shape, true, &d);
     if (rc) return rc;
     // the full chunks' blocks first, then (T % 64 != 0) one block per (batch, head) for the partial chunk
-    *bytes_out = saved_states_part(d) + (shape->T % 64 ? saved_states_part(tail_dims(d)) : 0);
+    if (shape->C != 64) *bytes_out = saved_states_part(expanded_dims(d, shape->C));
+    else *bytes_out = saved_states_part(d) + (shape->T % 64 ? saved_states_part(tail_dims(d)) : 0);
     return MDN_OK;
 }
 
@@ -831,7 +970,8 @@ int mdn_saved_operands_bytes(const mdn_shape *shape, size_t *bytes_out) {
     if (!bytes_out) return MDN_ERR_NULL;
     int rc = check_shape(shape, true, &d);
     if (rc) return rc;
-    *bytes_out = carve_rev(d, nullptr).total + (shape->T % 64 ? carve_rev(tail_dims(d), nullptr).total : 0);
+    if (shape->C != 64) *bytes_out = carve_rev(expanded_dims(d, shape->C), nullptr).total;
+    else *bytes_out = carve_rev(d, nullptr).total + (shape->T % 64 ? carve_rev(tail_dims(d), nullptr).total : 0);
     return MDN_OK;
 }
 
@@ -848,9 +988,10 @@ int mdn_chunk_fwd(const mdn_shape *shape, const void *q, const void *k, const vo
     for (const void *p : ptrs)
         if (p && misaligned(p)) return MDN_ERR_ALIGN;
     const int r = shape->T % 64;
-    if (workspace_bytes < fwd_ws_total(d, r)) return MDN_ERR_WORKSPACE;
+    if (workspace_bytes < fwd_ws_call(d, shape)) return MDN_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     FwdCall c = {q, k, v, beta, alpha, mu, eta, S0, M0, o, S_final, M_final, vt_saved, states_saved, operands_saved};
+    if (shape->C != 64) return fwd_small_chunks(d, shape->C, c, workspace, s);
     return fwd_any(d, r, c, workspace, s);
 }
 
@@ -865,7 +1006,7 @@ int mdn_chunk_fwd_noalloc(const mdn_shape *shape, const void *q, const void *k, 
     for (const void *p : ptrs)
         if (p && misaligned(p)) return MDN_ERR_ALIGN;
     const int r = shape->T % 64;
-    if (fwd_ws_total(d, r) > (size_t)MDN_NOALLOC_SCRATCH_BYTES) return MDN_ERR_WORKSPACE;
+    if (fwd_ws_call(d, shape) > (size_t)MDN_NOALLOC_SCRATCH_BYTES) return MDN_ERR_WORKSPACE;
     void *ws = nullptr;
     rc = scratch_address(&ws);
     if (rc) return rc;
@@ -873,7 +1014,8 @@ int mdn_chunk_fwd_noalloc(const mdn_shape *shape, const void *q, const void *k, 
     // chunk-parallel kernel before the scan reads them, the padded copies of a partial chunk by the gather kernel.
     FwdCall c = {q, k, v, beta, alpha, mu, eta, S0, M0, o, S_final, M_final, vt_saved, nullptr, nullptr};
     t_no_alloc = true; // one stream, no timing events: nothing below creates a stream, an event or memory
-    rc = fwd_any(d, r, c, ws, static_cast<hipStream_t>(stream));
+    rc = shape->C != 64 ? fwd_small_chunks(d, shape->C, c, ws, static_cast<hipStream_t>(stream))
+                        : fwd_any(d, r, c, ws, static_cast<hipStream_t>(stream));
     t_no_alloc = false;
     return rc;
 }
@@ -898,8 +1040,9 @@ int mdn_chunk_bwd(const mdn_shape *shape, const void *q, const void *k, const vo
     const int r = shape->T % 64;
     BwdCall c = {q, k, v, beta, alpha, mu, eta, S0, M0, vt_saved, states_saved, operands_saved, dO, dS_final, dM_final,
                  dq, dk, dv, dbeta, dalpha, dmu, deta, dS0, dM0};
-    if (workspace_bytes < bwd_ws_total(d, r, precise_call(d, c))) return MDN_ERR_WORKSPACE;
+    if (workspace_bytes < bwd_ws_call(d, shape, precise_call(d, c))) return MDN_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (shape->C != 64) return bwd_small_chunks(d, shape->C, c, workspace, s);
     return bwd_any(d, r, c, workspace, s);
 }
 

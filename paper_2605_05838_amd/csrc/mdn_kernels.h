@@ -130,6 +130,15 @@ struct TailCopy {
 };
 hipError_t launch_tail_copy(const TailCopy &c, bool gather, hipStream_t s);
 
+// Chunk sizes below 64 (Algorithm 1 lists C in {16, 32, 64}): every chunk of C tokens becomes one 64-token tile whose
+// rows from C on are padding (TailTensor::pad_word).  expand: [B,T,H,row] -> [B, ceil(T/C) * 64, H, row];
+// collect: the real rows back.
+struct ChunkCopy {
+    int B, T, H, C, NC, n; // NC = ceil(T / C) chunks, n tensors
+    TailTensor t[12];
+};
+hipError_t launch_chunk_copy(const ChunkCopy &c, bool expand, hipStream_t s);
+
 // Packed variable-length batches run as one stream of tokens whose state is cut at the first token of every
 // sequence but the first: x[t, h] = value for the listed tokens t of up to two [T, H] fp32 tensors (a, b; b may be
 // null).  The token list travels in the kernel arguments, kSeqStartsPerLaunch at a time.

@@ -37,6 +37,22 @@ __global__ __launch_bounds__(64) void tail_scatter_kernel(TailCopy c) {
     for (int x = threadIdx.x; x < words; x += 64) dst[x] = src[x];
 }
 
+// chunks of C < 64 tokens as 64-token tiles: blockIdx.y = tensor, blockIdx.x = (b, chunk, i, h) row of the padded tensor
+template <bool EXPAND> __global__ __launch_bounds__(64) void chunk_copy_kernel(ChunkCopy c) {
+    const TailTensor t = c.t[blockIdx.y];
+    const int row = blockIdx.x, h = row % c.H, i = (row / c.H) % 64, nc = (row / (c.H * 64)) % c.NC, b = row / (c.H * 64 * c.NC);
+    const int words = t.row_bytes / 4, tok = nc * c.C + i;
+    const bool real = i < c.C && tok < c.T;
+    uint32_t *pad = reinterpret_cast<uint32_t *>(static_cast<char *>(t.padded) + (size_t)row * t.row_bytes);
+    uint32_t *full = reinterpret_cast<uint32_t *>(static_cast<char *>(const_cast<void *>(t.full)) +
+                                                  (((size_t)b * c.T + (real ? tok : 0)) * c.H + h) * t.row_bytes);
+    if (EXPAND) {
+        for (int x = threadIdx.x; x < words; x += 64) pad[x] = real ? full[x] : t.pad_word;
+    } else if (real) {
+        for (int x = threadIdx.x; x < words; x += 64) full[x] = pad[x];
+    }
+}
+
 // blockIdx.x = entry of the token list; threads over the heads
 __global__ __launch_bounds__(64) void set_at_tokens_kernel(float *a, float *b, float value, SeqStarts st) {
     const size_t row = (size_t)st.t[blockIdx.x] * st.H;
@@ -109,6 +125,21 @@ hipError_t launch_set_at_tokens(float *a, float *b, float value, const SeqStarts
     if (st.n < 1) return hipSuccess;
     if (!a || st.n > kSeqStartsPerLaunch || st.H < 1) return hipErrorInvalidValue;
     hipLaunchKernelGGL(set_at_tokens_kernel, dim3(st.n), dim3(64), 0, s, a, b, value, st);
+    return hipGetLastError();
+}
+
+hipError_t launch_chunk_copy(const ChunkCopy &c, bool expand, hipStream_t s) {
+    if (c.n < 1) return hipSuccess;
+    if (c.n > 12 || c.B < 1 || c.H < 1 || c.T < 1 || (c.C != 16 && c.C != 32) || c.NC != (c.T + c.C - 1) / c.C) return hipErrorInvalidValue;
+    for (int k = 0; k < c.n; ++k)
+        if (!c.t[k].full || !c.t[k].padded || c.t[k].row_bytes < 4 || c.t[k].row_bytes % 4) return hipErrorInvalidValue;
+    const long long rows = (long long)c.B * c.NC * 64 * c.H;
+    if (rows > 0x7fffffffLL) return hipErrorInvalidValue;
+    dim3 grid((unsigned)rows, c.n), block(64);
+    if (expand)
+        hipLaunchKernelGGL(chunk_copy_kernel<true>, grid, block, 0, s, c);
+    else
+        hipLaunchKernelGGL(chunk_copy_kernel<false>, grid, block, 0, s, c);
     return hipGetLastError();
 }
 

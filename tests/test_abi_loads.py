@@ -50,7 +50,14 @@ def test_workspace_query_validates_shapes():
     assert lib.mdn_saved_states_bytes(ctypes.byref(shape(T=100)), ctypes.byref(n)) == 0
     assert n.value == 2 * 3 * 2 * 2 * 128 * 128 * 2                                           # ceil(100 / 64) chunks
     assert lib.mdn_workspace_bytes(ctypes.byref(shape(dk=96, dv=96)), 0, ctypes.byref(n)) == -2
-    assert lib.mdn_workspace_bytes(ctypes.byref(shape(C=32)), 0, ctypes.byref(n)) == -2
+    assert lib.mdn_workspace_bytes(ctypes.byref(shape(C=48)), 0, ctypes.byref(n)) == -2
+    # chunk sizes 32 and 16 (Algorithm 1): every chunk runs as a 64-token tile, so 2x / 4x the chunks' workspace plus
+    # the padded copies of the tokens; the kept states follow the number of chunks
+    for C in (32, 16):
+        assert lib.mdn_workspace_bytes(ctypes.byref(shape(C=C)), 0, ctypes.byref(n)) == 0 and n.value > (64 // C) * fwd
+        assert lib.mdn_saved_states_bytes(ctypes.byref(shape(C=C)), ctypes.byref(n)) == 0
+        assert n.value == 2 * 3 * (128 // C) * 2 * 128 * 128 * 2
+    assert lib.mdn_workspace_bytes_varlen(ctypes.byref(shape(B=1, C=32)), (ctypes.c_int32 * 2)(0, 128), 1, 0, ctypes.byref(n)) == -2
     assert lib.mdn_workspace_bytes(ctypes.byref(shape(dtype=7)), 0, ctypes.byref(n)) == -3
     assert lib.mdn_workspace_bytes(ctypes.byref(shape()), 0, None) == -1
     assert lib.mdn_workspace_bytes(None, 0, ctypes.byref(n)) == -1
