@@ -169,7 +169,8 @@ int mdn_chunk_bwd(const mdn_shape *shape, const void *q, const void *k, const vo
  * launches however many the sequences.  A forward with zero initial states that wants the final states (S0, M0 NULL,
  * S_final and M_final given: prefill of a batch of prompts) runs the same stream, keeps its chunk-start states in the
  * workspace and then runs, as one batch, the last chunk of every sequence once more from its start state up to the
- * sequence's end (with 16-bit storage those start states carry the storage rounding).  Any other call runs each
+ * sequence's end (with 16-bit storage the start states are kept as value + rounding remainder, so the final states
+ * start from fp32-accurate states as in mdn_chunk_fwd).  Any other call runs each
  * sequence by itself through the same kernels as
  * mdn_chunk_fwd / mdn_chunk_bwd, one after the other on the stream (exact, but a batch of many short sequences does
  * not fill the GPU).  The backward reconstructs the states and recomputes the operands (no states_saved /

@@ -263,6 +263,7 @@ struct FwdCall {
     void *o;
     float *S_final, *M_final;
     void *vt_saved, *states_saved, *operands_saved;
+    void *states_lo; // rounding remainders of states_saved (16-bit storage), or null; see packed_final_states
 };
 
 int run_fwd(const Dims &d, const FwdCall &c, const FwdWs &w, hipStream_t s) {
@@ -278,6 +279,7 @@ int run_fwd(const Dims &d, const FwdCall &c, const FwdWs &w, hipStream_t s) {
     ScanFwdArgs sa = {};
     sa.q = c.q; sa.k = c.k; sa.v = c.v; sa.coef = ia.coef; sa.KT = ia.KT; sa.Tm = w.Tm; sa.Bm = w.Bm;
     sa.S0 = c.S0; sa.M0 = c.M0; sa.o = c.o; sa.vt_saved = c.vt_saved; sa.states_saved = c.states_saved;
+    sa.states_lo = c.states_lo;
     sa.S_final = c.S_final; sa.M_final = c.M_final;
     // K^T for this forward alone: not written if its scan forms K^T out of the k rows itself
     if (!c.operands_saved && !scan_fwd_reads_KT(d)) ia.KT = nullptr, sa.KT = nullptr;
@@ -455,7 +457,7 @@ int fwd_any(const Dims &d, int r, FwdCall c, void *workspace, hipStream_t s) {
     FwdCall ct = {tb.q, tb.k, tb.v, tb.beta, tb.alpha, tb.mu, c.eta ? tb.eta : nullptr,
                   d.N > 0 ? tb.S_mid : c.S0, d.N > 0 ? tb.M_mid : c.M0, tb.o, S_final, M_final,
                   c.vt_saved ? tb.vt : nullptr, offset(c.states_saved, saved_states_part(d)),
-                  offset(c.operands_saved, carve_rev(d, nullptr).total)};
+                  offset(c.operands_saved, carve_rev(d, nullptr).total), offset(c.states_lo, saved_states_part(d))};
     rc = run_fwd(dt, ct, wt, s);
     if (rc) return rc;
     TailList out(d, r);
@@ -780,6 +782,7 @@ Dims rows_dims(const Dims &d, int n_seq) {
 struct StreamPiece {
     int seq0, seq1, t0, len;
     void *states; // its chunk-start states (full chunks, then the partial chunk's block)
+    void *states_lo; // 16-bit storage: what the rounding of `states` dropped (the final states start from hi + lo)
     void *rest;   // its forward workspace
 };
 
@@ -802,11 +805,13 @@ PackedFinalWs carve_packed_final(const Dims &d, const int32_t *cu, int n_seq, vo
     w.g.mu = static_cast<float *>(c.take((size_t)d.T * d.H * sizeof(float)));
     const int cut = packed_cut(d, cu, n_seq);
     w.npieces = cut ? 2 : 1;
-    w.piece[0] = {0, cut ? cut : n_seq, 0, cut ? cu[cut] : d.T, nullptr, nullptr};
-    w.piece[1] = {cut, n_seq, cut ? cu[cut] : 0, cut ? d.T - cu[cut] : 0, nullptr, nullptr};
+    w.piece[0] = {0, cut ? cut : n_seq, 0, cut ? cu[cut] : d.T, nullptr, nullptr, nullptr};
+    w.piece[1] = {cut, n_seq, cut ? cu[cut] : 0, cut ? d.T - cu[cut] : 0, nullptr, nullptr, nullptr};
     for (int p = 0; p < w.npieces; ++p) {
         const Dims dp = seq_dims(d, w.piece[p].len);
-        w.piece[p].states = c.take(saved_states_part(dp) + (dp.T % 64 ? saved_states_part(tail_dims(dp)) : 0));
+        const size_t sb = saved_states_part(dp) + (dp.T % 64 ? saved_states_part(tail_dims(dp)) : 0);
+        w.piece[p].states = c.take(sb);
+        w.piece[p].states_lo = d.dtype == MDN_DTYPE_BF16 ? c.take(sb) : nullptr;
         w.piece[p].rest = c.take(fwd_ws_total(dp, dp.T % 64));
     }
     w.k = c.take(rows * d.dk * es);
@@ -855,7 +860,8 @@ int packed_final_states(const Dims &d, const int32_t *cu, int n_seq, const FwdCa
             add(stream.mu, w.mu, 4, 1.f);
             add(stream.eta, w.eta, 4, 1.f);
             if (launch_gather_seq_rows(g, s) != hipSuccess) return MDN_ERR_LAUNCH;
-            if (launch_states_to_f32(pc.states, offset(pc.states, saved_states_part(dp)), sc, w.S0 + (size_t)i0 * st,
+            if (launch_states_to_f32(pc.states, offset(pc.states, saved_states_part(dp)), pc.states_lo,
+                                     offset(pc.states_lo, saved_states_part(dp)), sc, w.S0 + (size_t)i0 * st,
                                      w.M0 + (size_t)i0 * st, s) != hipSuccess)
                 return MDN_ERR_LAUNCH;
         }
@@ -1113,7 +1119,7 @@ int mdn_chunk_fwd_varlen(const mdn_shape *shape, const int32_t *cu_seqlens, int3
             const size_t t0 = (size_t)pc.t0;
             FwdCall c = {at_token(q, t0, rk), at_token(k, t0, rk), at_token(v, t0, rv), at_token(beta, t0, rg),
                          at_token(w.g.alpha, t0, rg), at_token(w.g.mu, t0, rg), at_token(eta, t0, rg), nullptr, nullptr,
-                         at_token(o, t0, rv), nullptr, nullptr, at_token(vt_saved, t0, rv), pc.states, nullptr};
+                         at_token(o, t0, rv), nullptr, nullptr, at_token(vt_saved, t0, rv), pc.states, nullptr, pc.states_lo};
             return fwd_any(seq_dims(d, pc.len), pc.len % 64, c, pc.rest, st);
         };
         rc = w.npieces == 1 ? part(w.piece[0], s)

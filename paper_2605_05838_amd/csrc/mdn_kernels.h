@@ -43,7 +43,7 @@ struct ScanFwdArgs {
     void *vt_saved;                         // [B,T,H,dv] or null
     void *states_saved;                     // [BH][N][2] x vblk [dk][dv], or null
     void *states_lo;                        // same layout, or null: what the 16-bit rounding of states_saved dropped
-                                            // (reconstruction only; see GradArgs)
+                                            // (see GradArgs, and the packed prefill in mdn_api.hip)
     float *S_final, *M_final;               // or null
 };
 
@@ -166,7 +166,8 @@ struct SeqChunks {
     int n, H, N, dk, dv, dtype;
     int chunk[kSeqRowsPerLaunch];
 };
-hipError_t launch_states_to_f32(const void *states_full, const void *states_tail, const SeqChunks &c, float *S, float *M,
-                                hipStream_t s);
+// (lo_full, lo_tail: the rounding remainders of the same blocks, or null)
+hipError_t launch_states_to_f32(const void *states_full, const void *states_tail, const void *lo_full, const void *lo_tail,
+                                const SeqChunks &c, float *S, float *M, hipStream_t s);
 
 } // namespace mdn

@@ -210,8 +210,10 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
                     sv[2 * nd + 1][mv] = narrow4<T>(accM[mv][nd]);
                 }
         }
-        // what that rounding dropped, rounded again (reconstruction with 16-bit storage, on request)
-        constexpr bool LO = REBUILD && sizeof(T) == 2;
+        // what that rounding dropped, rounded again (16-bit storage, on request: the reconstruction of a backward
+        // call that brings state adjoints in, and the forward of a packed batch of prompts, whose sequences' final
+        // states start from these chunk-start states)
+        constexpr bool LO = sizeof(T) == 2;
         typename Raw4<T>::type sl[LO ? NS : 1][MV];
         T *stl = static_cast<T *>(a.states_lo) + blk * (2 * DK * DV);
         if constexpr (LO) {

@@ -78,15 +78,18 @@ __global__ __launch_bounds__(64) void gather_seq_rows_kernel(SeqRows g) {
 }
 
 // blockIdx.x = entry, blockIdx.y = head, blockIdx.z = 0: S, 1: M
-template <typename T> __global__ __launch_bounds__(256) void states_to_f32_kernel(const T *full, const T *tail, SeqChunks c,
-                                                                                  float *S, float *M) {
+template <typename T> __global__ __launch_bounds__(256) void states_to_f32_kernel(const T *full, const T *tail, const T *lo_full,
+                                                                                  const T *lo_tail, SeqChunks c, float *S, float *M) {
     const int e = blockIdx.x, h = blockIdx.y, which = blockIdx.z, n = c.chunk[e];
     const size_t blk = (size_t)c.dk * c.dv;
-    const T *src = n < c.N ? full + (((size_t)h * c.N + n) * 2 + which) * blk : tail + ((size_t)h * 2 + which) * blk;
+    const size_t off = n < c.N ? (((size_t)h * c.N + n) * 2 + which) * blk : ((size_t)h * 2 + which) * blk;
+    const T *src = (n < c.N ? full : tail) + off;
+    const T *lo = (n < c.N ? lo_full : lo_tail);
     float *dst = (which ? M : S) + ((size_t)e * c.H + h) * blk;
     for (int x = threadIdx.x; x < c.dk * c.dv; x += 256) {
         const int row = x / c.dv, col = x % c.dv;
-        dst[x] = to_f32(src[vblk(c.dk, row, col)]);
+        const size_t i = vblk(c.dk, row, col);
+        dst[x] = to_f32(src[i]) + (lo ? to_f32(lo[off + i]) : 0.f);
     }
 }
 
@@ -103,8 +106,8 @@ hipError_t launch_gather_seq_rows(const SeqRows &g, hipStream_t s) {
     return hipGetLastError();
 }
 
-hipError_t launch_states_to_f32(const void *states_full, const void *states_tail, const SeqChunks &c, float *S, float *M,
-                                hipStream_t s) {
+hipError_t launch_states_to_f32(const void *states_full, const void *states_tail, const void *lo_full, const void *lo_tail,
+                                const SeqChunks &c, float *S, float *M, hipStream_t s) {
     if (c.n < 1) return hipSuccess;
     if (c.n > kSeqRowsPerLaunch || !S || !M || c.H < 1 || c.N < 0) return hipErrorInvalidValue;
     for (int e = 0; e < c.n; ++e) {
@@ -114,10 +117,12 @@ hipError_t launch_states_to_f32(const void *states_full, const void *states_tail
     const dim3 grid(c.n, c.H, 2), block(256);
     if (c.dtype == 1)
         hipLaunchKernelGGL(states_to_f32_kernel<float>, grid, block, 0, s, static_cast<const float *>(states_full),
-                           static_cast<const float *>(states_tail), c, S, M);
+                           static_cast<const float *>(states_tail), static_cast<const float *>(nullptr),
+                           static_cast<const float *>(nullptr), c, S, M);
     else
         hipLaunchKernelGGL(states_to_f32_kernel<bf16_t>, grid, block, 0, s, static_cast<const bf16_t *>(states_full),
-                           static_cast<const bf16_t *>(states_tail), c, S, M);
+                           static_cast<const bf16_t *>(states_tail), static_cast<const bf16_t *>(lo_full),
+                           static_cast<const bf16_t *>(lo_tail), c, S, M);
     return hipGetLastError();
 }
 
