@@ -227,6 +227,47 @@ def varlen_bench(args, torch, binding, synth):
         "by_batch": rows, "cpu_baseline": None}))
 
 
+def layer_ops_bench(args, torch, binding):
+    """The elementwise operations around the delta rule (gate parameterisation, front end, back end) and their adjoints
+    at the 1.3B layer shape: streaming kernels, HBM-bound.  Wall-clock rates here include the binding's output
+    allocations; `rocprofv3 --kernel-trace --stats` on this command gives the kernels' own durations."""
+    B, T, H, d = 4, 4096, 16, 128
+    g = torch.Generator(device="cuda").manual_seed(0)
+    r = lambda: torch.randn((B, T, H, d), device="cuda", generator=g).to(torch.bfloat16)
+    xq, xk, xv, dq, dk, dv, o, gg, dy = (r() for _ in range(9))
+    dh = torch.rand(H, device="cuda", generator=g)
+    w = torch.rand(d, device="cuda", generator=g) + 0.5
+    xs = [torch.randn((B, T, H), device="cuda", generator=g) for _ in range(8)]
+    par = [torch.rand(H, device="cuda", generator=g) + 0.2 for _ in range(4)]
+    row = B * T * H * d * 2
+    ops = (("frontend_fwd", lambda: binding.mdn_frontend_fwd(xq, xk, xv, dh), 6 * row),
+           ("frontend_bwd", lambda: binding.mdn_frontend_bwd(xq, xk, xv, dh, dq, dk, dv), 9 * row),
+           ("epilogue_fwd", lambda: binding.mdn_epilogue_fwd(o, gg, w), 3 * row),
+           ("epilogue_bwd", lambda: binding.mdn_epilogue_bwd(o, gg, w, dy), 5 * row),
+           ("gates_fwd", lambda: binding.mdn_gates_fwd(*xs[:4], *par, 0.8, 8.0), 8 * B * T * H * 4),
+           ("gates_bwd", lambda: binding.mdn_gates_bwd(*xs[:4], *par, 0.8, 8.0, *xs[4:]), 12 * B * T * H * 4))
+    rows = {}
+    for name, f, nbytes in ops:
+        for _ in range(args.warmup):
+            f()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            f()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        rows[name] = {"bytes": nbytes, "wall_ms": round(ms, 4), "wall_gbs": round(nbytes / ms / 1e6, 1)}
+    best = max(rows, key=lambda k: rows[k]["wall_gbs"])
+    print(json.dumps({
+        "metric": "MDN layer elementwise operations, streaming rate", "value": rows[best]["wall_gbs"], "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": rows[best]["wall_ms"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"layer_ops_B{B}_T{T}_H{H}_d{d}", "B": B, "T": T, "H": H, "d": d},
+        "roofline": {"kernel": best, "bound": "hbm", "achieved": rows[best]["wall_gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": round(rows[best]["wall_gbs"] / PEAK_HBM_GBS, 5), "traffic": None},
+        "by_op": rows, "cpu_baseline": None}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -248,6 +289,9 @@ def main():
                          "and 8 tokens per call); prints its own JSON line with the decode latency per context length")
     ap.add_argument("--varlen", type=int, default=0, metavar="TOKENS",
                     help="packed variable-length batches of TOKENS tokens in 8, 64, 256 equal sequences (16 heads, d = 128)")
+    ap.add_argument("--layer-ops", action="store_true",
+                    help="instead of the training step: the elementwise operations around the delta rule (gates, front end, "
+                         "back end) and their adjoints at B=4, T=4096, H=16, d=128")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="after the timed region, also run one plain device copy of this many MiB (the known-size "
                          "kernel that the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled by)")
@@ -265,6 +309,8 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
+    if args.layer_ops:
+        return layer_ops_bench(args, torch, binding)
     if args.decode:
         return decode_bench(args, torch, binding, synth)
     if args.varlen:

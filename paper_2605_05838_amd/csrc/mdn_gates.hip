@@ -45,6 +45,7 @@ __global__ __launch_bounds__(GT) void gates_bwd_kernel(GateArgs g, const float *
                                                         const float *deta, float *dxa, float *dxm, float *dxb, float *dxe,
                                                         float *dpar) {
     extern __shared__ float s_par[]; // [4][H]
+    const int lane = threadIdx.x & 63;
     for (int c = threadIdx.x; c < 4 * g.H; c += GT) s_par[c] = 0.f;
     __syncthreads();
     for (long long i = (long long)blockIdx.x * GT + threadIdx.x; i < g.n; i += (long long)gridDim.x * GT) {
@@ -64,10 +65,26 @@ __global__ __launch_bounds__(GT) void gates_bwd_kernel(GateArgs g, const float *
         dxb[i] = db * (u * u / den) * sb * (1.f - sb);
         dxe[i] = (deta[i] - da * decay * dmax + db * sb * dmax) * (1.f - th * th) / g.tau;
         if (dpar) {
-            atomicAdd(&s_par[0 * g.H + h], dfa * -spa);
-            atomicAdd(&s_par[1 * g.H + h], gxa);
-            atomicAdd(&s_par[2 * g.H + h], dfm * -spm);
-            atomicAdd(&s_par[3 * g.H + h], gxm);
+            // lanes 32 (16) apart hold the same head when H divides 32 (16): their contributions are summed across
+            // the wave's halves (rows) first, so that one lane per head and wave goes to the LDS atomics instead of four
+            // (a loop trip is taken by whole waves except in the last one, whose stragglers take the plain path)
+            float p0 = dfa * -spa, p1 = gxa, p2 = dfm * -spm, p3 = gxm;
+            const bool whole = i - lane + 63 < g.n;
+            int active = 64;
+            if (whole && 32 % g.H == 0) {
+                p0 = add_xor32(p0); p1 = add_xor32(p1); p2 = add_xor32(p2); p3 = add_xor32(p3);
+                active = 32;
+                if (16 % g.H == 0) {
+                    p0 = add_xor16(p0); p1 = add_xor16(p1); p2 = add_xor16(p2); p3 = add_xor16(p3);
+                    active = 16;
+                }
+            }
+            if (lane < active) {
+                atomicAdd(&s_par[0 * g.H + h], p0);
+                atomicAdd(&s_par[1 * g.H + h], p1);
+                atomicAdd(&s_par[2 * g.H + h], p2);
+                atomicAdd(&s_par[3 * g.H + h], p3);
+            }
         }
     }
     __syncthreads();
@@ -127,7 +144,10 @@ int mdn_gates_bwd(const mdn_gate_params *params, const float *x_alpha, const flo
     g.xa = x_alpha; g.xm = x_mu; g.xb = x_beta; g.xe = x_eta;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (dparams) hipLaunchKernelGGL(gates_zero_kernel, dim3(1), dim3(256), 0, s, dparams, 4 * g.H);
-    hipLaunchKernelGGL(gates_bwd_kernel, dim3(grid_for(g.n)), dim3(GT), 4 * g.H * sizeof(float), s, g, dalpha, dbeta, dmu,
+    // (with parameter gradients every workgroup ends in 4 H atomic adds on the same 4 H addresses, which the L2 takes one
+    //  after the other: few workgroups with many tokens each)
+    const int wgs = dparams ? (grid_for(g.n) < 256 ? grid_for(g.n) : 256) : grid_for(g.n);
+    hipLaunchKernelGGL(gates_bwd_kernel, dim3(wgs), dim3(GT), 4 * g.H * sizeof(float), s, g, dalpha, dbeta, dmu,
                        deta, dx_alpha, dx_mu, dx_beta, dx_eta, dparams);
     return hipGetLastError() == hipSuccess ? MDN_OK : MDN_ERR_LAUNCH;
 }
