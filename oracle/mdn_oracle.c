@@ -109,6 +109,7 @@ int mdn_oracle_forward(int B, int T, int H, int dk, int dv, double scale, const 
         double *M = (double *)malloc(n * sizeof(double));
         double *e = (double *)malloc((size_t)dv * sizeof(double));
         if (!S || !M || !e) {
+#pragma omp atomic write
             fail = 1;
         } else {
             init_state(in.S0, (size_t)bh, n, S);
@@ -185,6 +186,7 @@ int mdn_oracle_backward(int B, int T, int H, int dk, int dv, double scale, const
         double *g = (double *)malloc((size_t)dk * sizeof(double));
         double *de = (double *)malloc((size_t)dv * sizeof(double));
         if (!ckS || !ckM || !Ss || !Ms || !es || !dS || !dM || !g || !de) {
+#pragma omp atomic write
             fail = 1;
         } else {
             /* pass 1: forward, keeping one checkpoint per segment */

@@ -210,7 +210,6 @@ __device__ __forceinline__ bf16x8 tr_pair(const bf16_t *p_lo, const bf16_t *p_hi
     const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, v);
 }
-__device__ __forceinline__ f32x4 tr_pair(const float *, const float *) { return f32x4{0.f, 0.f, 0.f, 0.f}; } // (never used)
 __device__ __forceinline__ bf16x8 tr_frag(const bf16_t *t, int ld, int k0, int n0, int r, int kg) {
     const bf16_t *p = t + (k0 + kg * 8 + (r >> 2)) * ld + n0 + (r & 3) * 4;
     return tr_pair(p, p + 4 * ld);
@@ -258,8 +257,6 @@ template <int D> __device__ __forceinline__ bf16x8 token_tile_col_frag(const bf1
     const int row = s * 32 + kg * 8 + (r >> 2), c = ct * 2 + ((r & 3) >> 1), sub = ((r & 3) * 4) & 7;
     return tr_pair(tile + row * D + ((c ^ (row & XM)) * 8) + sub, tile + (row + 4) * D + ((c ^ ((row + 4) & XM)) * 8) + sub);
 }
-template <int D> __device__ __forceinline__ f32x4 token_tile_row_frag(const float *, int, int, int) { return f32x4{0.f, 0.f, 0.f, 0.f}; }
-template <int D> __device__ __forceinline__ f32x4 token_tile_col_frag(const float *, int, int, int, int) { return f32x4{0.f, 0.f, 0.f, 0.f}; }
 
 // Blocked layouts of the chunk-local tensors that the library itself produces and consumes.
 // kblk: a [R][K] MFMA operand (fragment = row, KSTEP consecutive k) is stored as [K/KSTEP][R][KSTEP],

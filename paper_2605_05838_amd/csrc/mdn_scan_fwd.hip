@@ -256,7 +256,9 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
             zero_acc(accOM);
 #pragma unroll
             for (int s = 0; s < CO::KS; ++s) {
-                const typename O::Frag fk = KTILE ? token_tile_row_frag<DK>(kc, i, s, kg) : cur.kr[s];
+                typename O::Frag fk;
+                if constexpr (KTILE) fk = token_tile_row_frag<DK>(kc, i, s, kg);
+                else fk = cur.kr[s];
 #pragma unroll
                 for (int mv = 0; mv < MV; ++mv) {
                     const typename O::Frag fs = TS::frag(sSt, mv, s * O::KSTEP, r, kg);
@@ -329,7 +331,10 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
         for (int s = 0; s < CO::KS2; ++s) {
             typename O::Frag fkt[ND];
 #pragma unroll
-            for (int nd = 0; nd < ND; ++nd) fkt[nd] = KTILE ? token_tile_col_frag<DK>(kc, w * ND + nd, s, r, kg) : cur.kt[nd][s];
+            for (int nd = 0; nd < ND; ++nd) {
+                if constexpr (KTILE) fkt[nd] = token_tile_col_frag<DK>(kc, w * ND + nd, s, r, kg);
+                else fkt[nd] = cur.kt[nd][s];
+            }
 #pragma unroll
             for (int mv = 0; mv < MV; ++mv) {
                 const typename O::Frag fg = TV::frag(sVg, mv, s * O::KSTEP, r, kg);
