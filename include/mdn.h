@@ -270,6 +270,14 @@ enum {
 };
 int mdn_profile_begin(void);
 int mdn_profile_end(float *ms, int *launches, int n);
+/* An event pair costs a few microseconds of GPU time (the next launch waits for the marker in front of it), so a
+ * benchmark that wants kernel durations out of its timed region without paying for a pair around every launch brackets
+ * only every period-th launch of the library (period >= 1; mdn_profile_begin() = period 1): with a period that shares no
+ * factor with the number of launches per step, the bracketed launch walks through the kernels step after step.
+ * mdn_profile_end() then returns the bracketed launches; mdn_profile_launch_counts() the number of ALL launches per kernel id
+ * since the last begin (host array of n entries; call it before or after mdn_profile_end). */
+int mdn_profile_begin_sampled(int period);
+int mdn_profile_launch_counts(int *launched, int n);
 
 /*
  * Number of segments mdn_chunk_fwd / mdn_chunk_bwd split the sequence into: k >= 1 forces k

@@ -19,7 +19,8 @@ MDN_WS_FWD, MDN_WS_BWD, MDN_WS_BWD_STATE_ADJOINTS = 0, 1, 2
 
 EXPORTS = ("mdn_version", "mdn_strerror", "mdn_workspace_bytes", "mdn_saved_states_bytes",
            "mdn_saved_operands_bytes", "mdn_chunk_fwd", "mdn_chunk_fwd_noalloc",
-           "mdn_chunk_bwd", "mdn_recurrent_step", "mdn_profile_begin", "mdn_profile_end", "mdn_set_segments",
+           "mdn_chunk_bwd", "mdn_recurrent_step", "mdn_profile_begin", "mdn_profile_end", "mdn_profile_begin_sampled",
+           "mdn_profile_launch_counts", "mdn_set_segments",
            "mdn_gates_fwd", "mdn_gates_bwd", "mdn_frontend_fwd", "mdn_frontend_bwd", "mdn_epilogue_fwd",
            "mdn_epilogue_bwd", "mdn_workspace_bytes_varlen", "mdn_chunk_fwd_varlen", "mdn_chunk_bwd_varlen")
 
@@ -72,6 +73,10 @@ def load_library():
     lib.mdn_recurrent_step.restype = ctypes.c_int
     lib.mdn_recurrent_step.argtypes = [sp] + [vp] * 3 + [fp] * 4 + [fp, fp, vp, vp]
     lib.mdn_profile_begin.restype = ctypes.c_int
+    lib.mdn_profile_begin_sampled.restype = ctypes.c_int
+    lib.mdn_profile_begin_sampled.argtypes = [ctypes.c_int]
+    lib.mdn_profile_launch_counts.restype = ctypes.c_int
+    lib.mdn_profile_launch_counts.argtypes = [ctypes.POINTER(ctypes.c_int), ctypes.c_int]
     lib.mdn_profile_end.restype = ctypes.c_int
     lib.mdn_profile_end.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int), ctypes.c_int]
     lib.mdn_set_segments.restype = ctypes.c_int
@@ -350,16 +355,22 @@ def set_segments(k):
     return int(load_library().mdn_set_segments(int(k)))
 
 
-def profile_begin():
-    _check(load_library().mdn_profile_begin(), "mdn_profile_begin")
+def profile_begin(period=1):
+    """Bracket every period-th launch of the library with an event pair (1 = every launch)."""
+    _check(load_library().mdn_profile_begin_sampled(int(period)), "mdn_profile_begin_sampled")
 
 
-def profile_end():
-    """Per-kernel {name: (total_ms, launches)} since profile_begin(); synchronises the recorded events."""
+def profile_end(with_launch_counts=False):
+    """Per-kernel {name: (total_ms, bracketed launches)} since profile_begin(), with_launch_counts: (total_ms, bracketed
+    launches, all launches); synchronises the recorded events."""
     n = len(KERNEL_NAMES)
     ms = (ctypes.c_float * n)()
     cnt = (ctypes.c_int * n)()
+    every = (ctypes.c_int * n)()
     _check(load_library().mdn_profile_end(ms, cnt, n), "mdn_profile_end")
+    _check(load_library().mdn_profile_launch_counts(every, n), "mdn_profile_launch_counts")
+    if with_launch_counts:
+        return {KERNEL_NAMES[i]: (float(ms[i]), int(cnt[i]), int(every[i])) for i in range(n)}
     return {KERNEL_NAMES[i]: (float(ms[i]), int(cnt[i])) for i in range(n)}
 
 

@@ -174,6 +174,9 @@ int launch_status(hipError_t e) { return e == hipSuccess ? MDN_OK : MDN_ERR_LAUN
 // all threads of the process and guarded by a mutex.
 struct TimedLaunch { int id; hipEvent_t start, stop; };
 std::atomic<bool> g_profiling{false};
+std::atomic<int> g_profile_period{1};          // every period-th launch is bracketed
+std::atomic<unsigned> g_profile_seen{0};       // launches since mdn_profile_begin
+std::atomic<int> g_launched[MDN_KERNEL_COUNT]; // all launches per kernel id since mdn_profile_begin
 std::mutex g_timed_mutex;
 std::vector<TimedLaunch> g_timed;
 
@@ -182,6 +185,9 @@ thread_local bool t_no_alloc = false;
 
 template <typename F> int timed(int id, hipStream_t s, F &&launch) {
     if (t_no_alloc || !g_profiling.load(std::memory_order_relaxed)) return launch_status(launch());
+    if (id >= 0 && id < MDN_KERNEL_COUNT) g_launched[id].fetch_add(1, std::memory_order_relaxed);
+    const unsigned seen = g_profile_seen.fetch_add(1, std::memory_order_relaxed);
+    if (seen % (unsigned)g_profile_period.load(std::memory_order_relaxed) != 0) return launch_status(launch());
     TimedLaunch t{id, nullptr, nullptr};
     if (hipEventCreate(&t.start) != hipSuccess || hipEventCreate(&t.stop) != hipSuccess) return MDN_ERR_LAUNCH;
     const bool r0 = hipEventRecord(t.start, s) == hipSuccess;
@@ -908,8 +914,20 @@ int mdn_version(void) { return 100; }
 
 int mdn_set_segments(int k) { return g_segments.exchange(k < 0 ? 0 : k); }
 
-int mdn_profile_begin(void) {
+int mdn_profile_begin_sampled(int period) {
+    if (period < 1) return MDN_ERR_SHAPE;
+    g_profile_period.store(period);
+    g_profile_seen.store(0);
+    for (auto &c : g_launched) c.store(0);
     g_profiling.store(true);
+    return MDN_OK;
+}
+
+int mdn_profile_begin(void) { return mdn_profile_begin_sampled(1); }
+
+int mdn_profile_launch_counts(int *launched, int n) {
+    if (!launched) return MDN_ERR_NULL;
+    for (int i = 0; i < n && i < MDN_KERNEL_COUNT; ++i) launched[i] = g_launched[i].load();
     return MDN_OK;
 }
 
