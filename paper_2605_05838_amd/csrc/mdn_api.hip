@@ -910,7 +910,7 @@ template <typename P> P *at_token(P *base, size_t token, size_t bytes_per_token)
 
 extern "C" {
 
-int mdn_version(void) { return 100; }
+int mdn_version(void) { return 200; }
 
 int mdn_set_segments(int k) { return g_segments.exchange(k < 0 ? 0 : k); }
 

@@ -130,3 +130,23 @@ def test_sequence_length_that_is_not_a_multiple_of_the_chunk_size(dtype, d, T):
 def test_lengths_around_the_chunk_boundaries(T):
     w = synth.custom(B=1, T=T, H=2, dk=64, dv=64, dtype="f32", seed=53, with_eta=True, s0_std=0.3)
     check_fwd(w)
+
+
+def test_sampled_kernel_timing_counts_every_launch_and_brackets_every_third():
+    """mdn_profile_begin_sampled(3): an event pair around every third launch of the library; the launch counts cover
+    all of them."""
+    w = synth.custom(B=1, T=256, H=2, dk=64, dv=64, dtype="bf16", seed=24)
+    t = to_dev(w)
+    binding.profile_begin(3)
+    for _ in range(6):
+        binding.mdn_chunk_fwd(t["q"], t["k"], t["v"], t["beta"], t["alpha"], t["mu"], scale=w.scale)
+    torch.cuda.synchronize()
+    k = binding.profile_end(with_launch_counts=True)
+    assert k["intra_fwd"][2] == 6 and k["scan_fwd"][2] == 6              # all launches
+    assert k["intra_fwd"][1] + k["scan_fwd"][1] == 4                      # launches 0, 3, 6, 9 of 12
+    assert k["intra_fwd"][1] == 2 and k["scan_fwd"][1] == 2               # (period 3 walks through the two kernels)
+    assert all(k[n][0] > 0 for n in ("intra_fwd", "scan_fwd"))
+    binding.profile_begin()
+    binding.mdn_chunk_fwd(t["q"], t["k"], t["v"], t["beta"], t["alpha"], t["mu"], scale=w.scale)
+    k = binding.profile_end()
+    assert k["intra_fwd"][1] == 1 and k["scan_fwd"][1] == 1
