@@ -54,14 +54,18 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
     constexpr int LDN = DK + O::PAD; // natural tiles
     constexpr int LDT = 64 + O::PAD; // transposed tiles (32-bit storage)
     constexpr int DX = BWD ? DK : 0; // second transposed tile: Q^T (reverse-pass operands only)
-    constexpr int REG_NAT = 2 * 64 * LDN, REG_TR = (DK + DX) * LDT;
+    // (16-bit storage reads the transposed tiles out of the natural ones and needs no space for them)
+    constexpr int REG_NAT = 2 * 64 * LDN, REG_TR = sizeof(T) == 2 ? 0 : (DK + DX) * LDT;
     constexpr int REGION = REG_NAT > REG_TR ? REG_NAT : REG_TR;
     constexpr int NVK = 64 * DK / E / kThreads, NVX = BWD ? NVK : 1; // 16-byte vectors per thread
 
     __shared__ __align__(16) T sR[REGION];
     // Gamma (row stride LDG); later scratch of the block inverse
     __shared__ __align__(16) float sG[64 * LDA];
-    __shared__ __align__(16) float sA[64 * LDA];
+    // A, then T: in the space of the K, Q tiles, once every wave is done with those (70 -> 53 KB of LDS for 16-bit
+    // storage at d = 128: three workgroups per CU instead of two)
+    static_assert(sizeof(T) * REGION >= sizeof(float) * 64 * LDA, "A does not fit the tile region");
+    float *sA = reinterpret_cast<float *>(sR);
     float *sTT = sG;
     __shared__ __align__(16) float s_al[64], s_be[64], s_et[64], s_a[64], s_b[64];
 
@@ -150,6 +154,26 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
     }
     __syncthreads();
 
+    // ---- K^T, Q^T first (they only need the tiles), so that the tile region is free once the products are done
+    if constexpr (TRT) {
+        // in the blocked layout, where asked for (the reverse scan and the state reconstruction read
+        // them; the forward scan makes K^T itself out of the k rows): (dk tile, 32-token step) blocks dealt over
+        // the waves; lane (r, kq) reads (dk = 16 dt + r, tokens 32 ks + 8 kq ..) and owns exactly that
+        // 16-byte piece of the blocked layout, so a wave stores 1 KB of consecutive bytes
+        if (a.KT || (BWD && a.QT)) {
+            const int r = lane & 15, kq = lane >> 4;
+            T *KTo = a.KT ? static_cast<T *>(a.KT) + blk * (DK * 64) : nullptr;
+            T *QTo = BWD && a.QT ? static_cast<T *>(a.QT) + blk * (DK * 64) : nullptr;
+#pragma unroll
+            for (int t = 0; t < (DK / 16) * 2 / 4; ++t) {
+                const int tt = w + 4 * t, dt = tt >> 1, ks = tt & 1;
+                const size_t o = kblk<T>(DK, dt * 16 + r, ks * 32 + kq * 8);
+                if (KTo) *reinterpret_cast<typename O::Frag *>(KTo + o) = tr_frag(sK, LDN, ks * 32, dt * 16, r, kq);
+                if (QTo) *reinterpret_cast<typename O::Frag *>(QTo + o) = tr_frag(sQ, LDN, ks * 32, dt * 16, r, kq);
+            }
+        }
+    }
+
     // ---- masked intra-chunk products: wave w owns rows i0..i0+15.
     //      The Q K^T product is formed in the orientation whose accumulator lanes hold 4 consecutive
     //      entries along the contraction index of the consumer (j for Bm, i for Bm^T).
@@ -159,25 +183,8 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
         zero_acc(kk);
         zero_acc(qk);
         mma_rows<T, 4, DK>(kk, sK + i0 * LDN, LDN, sK, LDN);
-        // K K^T is symmetric: element x of tile nt is read as k_i . k_j with i = nt*16 + r (row of A) and
-        // j = i0 + kq*4 + x, so that a lane holds 4 consecutive j of one row: eta and the row of A are one 16-byte
-        // LDS access each
-#pragma unroll
-        for (int nt = 0; nt < 4; ++nt) {
-            const int i = nt * 16 + r, j0 = i0 + kq * 4;
-            // (Gamma's rows have an odd stride, for the column accesses of the reverse-pass product below: its four
-            //  values are read one by one)
-            const float *gr = &sG[(i > 0 ? i - 1 : 0) * LDG + j0];
-            const f32x4 et = *reinterpret_cast<const f32x4 *>(&s_et[j0]);
-            const float al_i = s_al[i];
-            f32x4 v;
-#pragma unroll
-            for (int x = 0; x < 4; ++x) v[x] = (j0 + x < i) ? al_i * et[x] * gr[x] * kk[nt][x] : 0.f;
-            *reinterpret_cast<f32x4 *>(&sA[i * LDA + j0]) = v;
-        }
         if (BWD) {
             // qk[nt][x] = q_i . k_j, i = i0 + kq*4 + x, j = nt*16 + r  ->  Bm^T row j, k = i
-            zero_acc(qk);
             mma_rows<T, 4, DK>(qk, sQ + i0 * LDN, LDN, sK, LDN);
             T *out = static_cast<T *>(a.BmT) + blk * 4096;
 #pragma unroll
@@ -208,51 +215,52 @@ __global__ __launch_bounds__(kThreads) void intra_kernel(Dims d, IntraArgs a) {
                 store4(out + kblk<T>(64, i, i0 + kq * 4), v);
             }
         }
+        if constexpr (!TRT) {
+            // ---- 32-bit storage: the transposed tiles take the space of the K, Q tiles (dst[d][row] = src[row][d]),
+            //      go out from there, and only then does A move in
+            __syncthreads();
+#pragma unroll
+            for (int u = 0; u < NVK; ++u) {
+                const int c = tid + u * kThreads, row = c % 64, cc = c / 64;
+#pragma unroll
+                for (int e = 0; e < E; ++e) sKT[(cc * E + e) * LDT + row] = rkt[u].e[e];
+            }
+            if (BWD) {
+#pragma unroll
+                for (int u = 0; u < NVX; ++u) {
+                    const int c = tid + u * kThreads, row = c % 64, cc = c / 64;
+#pragma unroll
+                    for (int e = 0; e < E; ++e) sXT[(cc * E + e) * LDT + row] = rxt[u].e[e];
+                }
+            }
+            __syncthreads();
+            store_tile_64cols<T>(static_cast<T *>(a.KT) + blk * (DK * 64), sKT, LDT, DK, tid);
+            if (BWD) store_tile_64cols<T>(static_cast<T *>(a.QT) + blk * (DK * 64), sXT, LDT, DK, tid);
+        }
+        __syncthreads(); // every wave is done with the tiles: A takes their place
+        // K K^T is symmetric: element x of tile nt is read as k_i . k_j with i = nt*16 + r (row of A) and
+        // j = i0 + kq*4 + x, so that a lane holds 4 consecutive j of one row: eta and the row of A are one 16-byte
+        // LDS access each
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) {
+            const int i = nt * 16 + r, j0 = i0 + kq * 4;
+            // (Gamma's rows have an odd stride, for the column accesses of the reverse-pass product above: its four
+            //  values are read one by one)
+            const float *gr = &sG[(i > 0 ? i - 1 : 0) * LDG + j0];
+            const f32x4 et = *reinterpret_cast<const f32x4 *>(&s_et[j0]);
+            const float al_i = s_al[i];
+            f32x4 v;
+#pragma unroll
+            for (int x = 0; x < 4; ++x) v[x] = (j0 + x < i) ? al_i * et[x] * gr[x] * kk[nt][x] : 0.f;
+            *reinterpret_cast<f32x4 *>(&sA[i * LDA + j0]) = v;
+        }
     }
     __syncthreads();
 
-    if constexpr (TRT) {
-        // ---- K^T, Q^T in the blocked layout, where asked for (the reverse scan and the state reconstruction read
-        //      them; the forward scan makes K^T itself out of the k rows): (dk tile, 32-token step) blocks dealt over
-        //      the waves; lane (r, kq) reads (dk = 16 dt + r, tokens 32 ks + 8 kq ..) and owns exactly that
-        //      16-byte piece of the blocked layout, so a wave stores 1 KB of consecutive bytes
-        if (a.KT || (BWD && a.QT)) {
-            T *KTo = a.KT ? static_cast<T *>(a.KT) + blk * (DK * 64) : nullptr;
-            T *QTo = BWD && a.QT ? static_cast<T *>(a.QT) + blk * (DK * 64) : nullptr;
-#pragma unroll
-            for (int t = 0; t < (DK / 16) * 2 / 4; ++t) {
-                const int tt = w + 4 * t, dt = tt >> 1, ks = tt & 1;
-                const size_t o = kblk<T>(DK, dt * 16 + r, ks * 32 + kq * 8);
-                if (KTo) *reinterpret_cast<typename O::Frag *>(KTo + o) = tr_frag(sK, LDN, ks * 32, dt * 16, r, kq);
-                if (QTo) *reinterpret_cast<typename O::Frag *>(QTo + o) = tr_frag(sQ, LDN, ks * 32, dt * 16, r, kq);
-            }
-        }
-    } else {
-        // ---- transposed tiles into the space of the K, Q tiles (dst[d][row] = src[row][d])
-#pragma unroll
-        for (int u = 0; u < NVK; ++u) {
-            const int c = tid + u * kThreads, row = c % 64, cc = c / 64;
-#pragma unroll
-            for (int e = 0; e < E; ++e) sKT[(cc * E + e) * LDT + row] = rkt[u].e[e];
-        }
-        if (BWD) {
-#pragma unroll
-            for (int u = 0; u < NVX; ++u) {
-                const int c = tid + u * kThreads, row = c % 64, cc = c / 64;
-#pragma unroll
-                for (int e = 0; e < E; ++e) sXT[(cc * E + e) * LDT + row] = rxt[u].e[e];
-            }
-        }
-    }
     // ---- T = (I + A)^{-1} by 16x16 blocks, wave w = block row w
     tri_inverse_blocked(sA, sTT, LDA, w);
     __syncthreads();
 
-    // raw transposed copies for the scans
-    if constexpr (!TRT) {
-        store_tile_64cols<T>(static_cast<T *>(a.KT) + blk * (DK * 64), sKT, LDT, DK, tid);
-        if (BWD) store_tile_64cols<T>(static_cast<T *>(a.QT) + blk * (DK * 64), sXT, LDT, DK, tid);
-    }
     if (BWD) {
         T *tt = static_cast<T *>(a.TmT) + blk * 4096; // T^T: row j, k = i
         constexpr int E = O::EPL;
