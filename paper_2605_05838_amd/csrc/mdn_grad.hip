@@ -109,6 +109,7 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     __shared__ float sRowC[3 * 64]; // reverse scan: the three per-row coefficients
     __shared__ float s_gC[64], s_rC[64];
     __shared__ float s_ga[64], s_gb[64], s_gm[64];
+    __shared__ float s_da[64], s_de[64]; // wave 5's share of dalpha, and deta, for wave 4's final sums
     __shared__ float s_red[8][3];
 
     // Wave and lane indices, re-derived at the start of every chunk from values the compiler cannot see
@@ -536,7 +537,7 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
         }
     }
     RevScanRows rr;
-    float db = 0.f, da = 0.f, dm = 0.f, dalk = 0.f, detk = 0.f;
+    float db = 0.f, dm = 0.f;
     if (w < 4) {
         float dgc = 0.f, drc = 0.f;
         if (w == 3) {
@@ -545,33 +546,40 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
         }
         coef_scan_reverse_part1(g_al, g_be, g_mu, sDG1, sDG2, dgc, drc, LDG, w, rr, sTop, lane);
     }
-    if (w == 5) coef_scan_reverse_rowcoefs(g_al, g_be, g_mu, sRowC, lane); // (a wave with nothing else to do here)
+    if (w == 5) {
+        coef_scan_reverse_rowcoefs(g_al, g_be, g_mu, sRowC, lane);
+        // the vector chain of a (it does not meet those of b and m before the final sums): reverse of
+        // a_i = alpha_i a_{i-1} with a^-_i = a_{i-1}:  da_i = Da_i + Da^-_{i+1} + alpha_{i+1} da_{i+1}; its share of
+        // dalpha_i, da_i a_{i-1} + k_i.dP_i, and deta_i go to wave 4 through LDS
+        float dS_S = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < 8; ++ww) dS_S += s_red[ww][0];
+        const float t_da = total(P_DA), t_dam = total(P_DAM), t_dalk = total(P_DALK);
+        const int li = lane;
+        const float al_next = wave_down1(g_al, 0.f, lane), dam_dn = wave_down1(t_dam, 0.f, lane);
+        float ca = (li < 63) ? al_next : 0.f;
+        float da5 = t_da + ((li < 63) ? dam_dn : dS_S);
+        scan_affine_rev(ca, da5, lane);
+        s_da[li] = da5 * ((li > 0) ? s_a[li - 1] : 1.f) + t_dalk;
+        s_de[li] = total(P_DETK);
+    }
     if (w == 4) {
-        // vectors (lane i = token i): reverse of b_i = alpha_i b_{i-1} + beta_i m_i, a_i = alpha_i a_{i-1},
-        // m_i = mu_i m_{i-1}, with a^-_i = a_{i-1}, b^-_i = b_{i-1}:
-        //   db_i = Db_i + alpha_{i+1} db_{i+1},  da_i = Da_i + alpha_{i+1} da_{i+1},
-        //   dm_i = Dm_i + beta_i db_i + mu_{i+1} dm_{i+1}
-        float dS_S = 0.f, dS_M = 0.f, dM_M = 0.f;
+        // vectors (lane i = token i): reverse of b_i = alpha_i b_{i-1} + beta_i m_i, m_i = mu_i m_{i-1}, with
+        // b^-_i = b_{i-1}:
+        //   db_i = Db_i + Db^-_{i+1} + alpha_{i+1} db_{i+1},  dm_i = Dm_i + beta_i db_i + mu_{i+1} dm_{i+1}
+        float dS_M = 0.f, dM_M = 0.f;
 #pragma unroll
         for (int ww = 0; ww < 8; ++ww) {
-            dS_S += s_red[ww][0];
             dS_M += s_red[ww][1];
             dM_M += s_red[ww][2];
         }
-        const float t_da = total(P_DA), t_db = total(P_DB), t_dam = total(P_DAM), t_dbm = total(P_DBM);
-        dalk = total(P_DALK);
-        detk = total(P_DETK);
+        const float t_db = total(P_DB), t_dbm = total(P_DBM);
         const int li = lane;
         const float al_next = wave_down1(g_al, 0.f, lane), mu_next = wave_down1(g_mu, 0.f, lane);
-        const float dbm_dn = wave_down1(t_dbm, 0.f, lane), dam_dn = wave_down1(t_dam, 0.f, lane);
-        const float dbm_next = (li < 63) ? dbm_dn : -dS_M;
-        const float dam_next = (li < 63) ? dam_dn : dS_S;
+        const float dbm_dn = wave_down1(t_dbm, 0.f, lane);
         float cb = (li < 63) ? al_next : 0.f;
-        db = t_db + dbm_next;
+        db = t_db + ((li < 63) ? dbm_dn : -dS_M);
         scan_affine_rev(cb, db, lane);
-        float ca = (li < 63) ? al_next : 0.f;
-        da = t_da + dam_next;
-        scan_affine_rev(ca, da, lane);
         float cm = (li < 63) ? mu_next : 0.f;
         dm = (li == 63 ? dM_M : 0.f) + g_be * db;
         scan_affine_rev(cm, dm, lane);
@@ -616,13 +624,13 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     __syncthreads();
     if (w == 4) {
         const int li = lane;
-        const float aprev = wave_up1(pa, 1.f, lane), bprev = wave_up1(pb, 0.f, lane), mprev = wave_up1(pm, 1.f, lane);
-        const float a_prev = (li > 0) ? aprev : 1.f, b_prev = (li > 0) ? bprev : 0.f, m_prev = (li > 0) ? mprev : 1.f;
+        const float bprev = wave_up1(pb, 0.f, lane), mprev = wave_up1(pm, 1.f, lane);
+        const float b_prev = (li > 0) ? bprev : 0.f, m_prev = (li > 0) ? mprev : 1.f;
         const unsigned g = (unsigned)(li * d.H);
-        *at32(a.dalpha + tok0_cur, g) = s_ga[li] + db * b_prev + da * a_prev + dalk;
+        *at32(a.dalpha + tok0_cur, g) = s_ga[li] + db * b_prev + s_da[li];
         *at32(a.dbeta + tok0_cur, g) = s_gb[li] + db * pm;
         *at32(a.dmu + tok0_cur, g) = s_gm[li] + dm * m_prev;
-        if (a.deta) *at32(a.deta + tok0_cur, g) = detk;
+        if (a.deta) *at32(a.deta + tok0_cur, g) = s_de[li];
     }
     if (!has_next) break;
     chunk = next;
