@@ -123,6 +123,15 @@ __device__ __forceinline__ void store4_raw(bf16_t *p, bf16x4 v) { *reinterpret_c
 __device__ __forceinline__ void store4_raw(float *p, f32x4 v) { *reinterpret_cast<f32x4 *>(p) = v; }
 __device__ __forceinline__ f32x4 widen4(bf16x4 v) { return f32x4{(float)v[0], (float)v[1], (float)v[2], (float)v[3]}; }
 __device__ __forceinline__ f32x4 widen4(f32x4 v) { return v; }
+// widen4 of a value that was narrowed a moment ago, by shifts and masks of the packed words (so that the compiler
+// widens the PACKED value instead of rounding each fp32 source a second time, one conversion per element)
+__device__ __forceinline__ f32x4 widen4_packed(bf16x4 v) {
+    typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+    const u32x2 w = __builtin_bit_cast(u32x2, v);
+    return f32x4{__uint_as_float(w[0] << 16), __uint_as_float(w[0] & 0xffff0000u), __uint_as_float(w[1] << 16),
+                 __uint_as_float(w[1] & 0xffff0000u)};
+}
+__device__ __forceinline__ f32x4 widen4_packed(f32x4 v) { return v; }
 
 // A lane's MV accumulator vectors as MV*4 CONSECUTIVE storage elements at p (16-bit storage, MV = 2: one 16-byte
 // access instead of two of 8 bytes).  Which columns of a [.., dv] tensor a lane's accumulator rows stand for is
@@ -194,6 +203,7 @@ template <int M, int K> struct ATile<float, M, K> {
 #pragma unroll
         for (int x = 0; x < 4; ++x) t[(m0 + x) * LD + k] = v[x];
     }
+    static __device__ __forceinline__ void put4_raw(float *t, int m0, int k, f32x4 v) { put4(t, m0, k, v); }
     // fragment of row 16 mt + r, k = k0 + kg*EPL .. (k0 a multiple of KSTEP)
     static __device__ __forceinline__ O::Frag frag(const float *t, int mt, int k0, int r, int kg) {
         return O::load(t + (mt * 16 + r) * LD + k0 + kg * O::EPL);
@@ -218,6 +228,8 @@ template <int M, int K> struct ATile<bf16_t, M, K> {
     typedef Op<bf16_t> O;
     static constexpr int LD = M + 8, SIZE = K * LD;
     static __device__ __forceinline__ void put4(bf16_t *t, int m0, int k, f32x4 v) { store4(t + k * LD + m0, v); }
+    // the same four rows, already in storage form
+    static __device__ __forceinline__ void put4_raw(bf16_t *t, int m0, int k, bf16x4 v) { store4_raw(t + k * LD + m0, v); }
     static __device__ __forceinline__ O::Frag frag(const bf16_t *t, int mt, int k0, int r, int kg) {
         return tr_frag(t, LD, k0, mt * 16, r, kg);
     }

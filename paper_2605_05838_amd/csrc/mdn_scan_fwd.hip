@@ -180,10 +180,66 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
     if (KTILE) __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): this wave's part of the first two k tiles has landed
     __syncthreads();
 
+    // The chunk-start states leave for HBM out of a storage-type copy in registers.  Forward scan: narrowed ONCE at
+    // the end of the step that produced them, for the LDS copy and for HBM alike (one burst; the stores cost this
+    // kernel ~75 us whichever wave issues them and whenever).  Reconstruction, which does little else than store:
+    // in 8 portions spread over the step (109 against 127 us in one burst).
+    constexpr int NS = 2 * ND; // vector stores per lane: S and M, ND rows, MV * 4 consecutive columns each
+    constexpr bool LO = sizeof(T) == 2;
+    typename Raw4<T>::type sv[NS][MV];
+    typename Raw4<T>::type sl[LO ? NS : 1][MV];
+    // sv: the states in storage form; sl: what that rounding dropped, rounded again (16-bit storage, on request: the
+    // reconstruction of a backward call that brings state adjoints in, and the forward of a packed batch of prompts,
+    // whose sequences' final states start from these chunk-start states)
+    auto narrow_states = [&]() {
+#pragma unroll
+        for (int nd = 0; nd < ND; ++nd)
+#pragma unroll
+            for (int mv = 0; mv < MV; ++mv) {
+                sv[2 * nd][mv] = narrow4<T>(accS[mv][nd]);
+                sv[2 * nd + 1][mv] = narrow4<T>(accM[mv][nd]);
+            }
+        if constexpr (LO) {
+            if (a.states_lo) {
+#pragma unroll
+                for (int nd = 0; nd < ND; ++nd)
+#pragma unroll
+                    for (int mv = 0; mv < MV; ++mv) {
+                        sl[2 * nd][mv] = narrow4<T>(accS[mv][nd] - widen4_packed(sv[2 * nd][mv]));
+                        sl[2 * nd + 1][mv] = narrow4<T>(accM[mv][nd] - widen4_packed(sv[2 * nd + 1][mv]));
+                    }
+            }
+        }
+    };
+    // portion PORTION of the stores of sv (and sl) as the start states of chunk block sblk
+    size_t sblk = 0;
+    auto emit_states = [&](auto PORTION) {
+        if (!a.states_saved) return;
+        T *st = static_cast<T *>(a.states_saved) + sblk * (2 * DK * DV);
+        T *stl = static_cast<T *>(a.states_lo) + sblk * (2 * DK * DV);
+        static_for<NS>([&](auto IDX) {
+            constexpr int idx = decltype(IDX)::value, nd = idx >> 1;
+            if ((REBUILD ? idx * 8 / NS : 0) == decltype(PORTION)::value) {
+                const size_t off = vblk(DK, (w * ND + nd) * 16 + r, dv0 + kg * (4 * MV));
+                store_cols_raw<MV>(st + ((idx & 1) ? DK * DV : 0) + off, sv[idx]);
+                if constexpr (LO) {
+                    if (a.states_lo) store_cols_raw<MV>(stl + ((idx & 1) ? DK * DV : 0) + off, sl[idx]);
+                }
+            }
+        });
+        __builtin_amdgcn_sched_barrier(0);
+    };
     // one chunk: its operands are in `cur`; those of the next chunk go on their way into `nxt`, portion by portion.
     // The k tile of chunk n+2 is requested first of all; each wave waits for its part of that transfer before the
     // first barrier of the NEXT step (see the wait there), and that step's barriers publish the tile before chunk
     // n+2 begins.
+    if constexpr (!REBUILD) {
+        if (a.states_saved) { // the start states of the first chunk: what came in
+            narrow_states();
+            sblk = (size_t)bh * d.N + d.n0;
+            emit_states(std::integral_constant<int, 0>{});
+        }
+    }
     int slot = 0;
     auto step = [&](int n, const CO &cur, CO &nxt) {
         const size_t blk = (size_t)bh * d.N + n;
@@ -194,60 +250,21 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
         slot = slot == 2 ? 0 : slot + 1;
         fetch_part<T, DK, DV, DVB, REBUILD, 0, KTILE>(nxt, d, a, bh, b, h, nn, dv0);
 
-        // The chunk-start states leave for HBM out of a storage-type copy in registers: in one burst here in the
-        // forward scan, in 8 portions spread over the step in the reconstruction, which does little else than
-        // store (measured: forward 252 us burst / 256 us spread; reconstruction 127 us burst / 109 us spread).
-        // What the stores cost the forward scan (~75 us) does not depend on which wave issues them or when.
-        constexpr int NS = 2 * ND; // vector stores per lane: S and M, ND rows, MV * 4 consecutive columns each
-        typename Raw4<T>::type sv[NS][MV];
-        T *st = static_cast<T *>(a.states_saved) + blk * (2 * DK * DV);
-        if (a.states_saved) {
-#pragma unroll
-            for (int nd = 0; nd < ND; ++nd)
-#pragma unroll
-                for (int mv = 0; mv < MV; ++mv) {
-                    sv[2 * nd][mv] = narrow4<T>(accS[mv][nd]);
-                    sv[2 * nd + 1][mv] = narrow4<T>(accM[mv][nd]);
-                }
-        }
-        // what that rounding dropped, rounded again (16-bit storage, on request: the reconstruction of a backward
-        // call that brings state adjoints in, and the forward of a packed batch of prompts, whose sequences' final
-        // states start from these chunk-start states)
-        constexpr bool LO = sizeof(T) == 2;
-        typename Raw4<T>::type sl[LO ? NS : 1][MV];
-        T *stl = static_cast<T *>(a.states_lo) + blk * (2 * DK * DV);
-        if constexpr (LO) {
-            if (a.states_lo) {
-#pragma unroll
-                for (int nd = 0; nd < ND; ++nd)
-#pragma unroll
-                    for (int mv = 0; mv < MV; ++mv) {
-                        sl[2 * nd][mv] = narrow4<T>(accS[mv][nd] - widen4(sv[2 * nd][mv]));
-                        sl[2 * nd + 1][mv] = narrow4<T>(accM[mv][nd] - widen4(sv[2 * nd + 1][mv]));
-                    }
-            }
-        }
-        auto emit_states = [&](auto PORTION) {
-            if (!a.states_saved) return;
-            static_for<NS>([&](auto IDX) {
-                constexpr int idx = decltype(IDX)::value, nd = idx >> 1;
-                if ((REBUILD ? idx * 8 / NS : 0) == decltype(PORTION)::value) {
-                    const size_t off = vblk(DK, (w * ND + nd) * 16 + r, dv0 + kg * (4 * MV));
-                    store_cols_raw<MV>(st + ((idx & 1) ? DK * DV : 0) + off, sv[idx]);
-                    if constexpr (LO) {
-                        if (a.states_lo) store_cols_raw<MV>(stl + ((idx & 1) ? DK * DV : 0) + off, sl[idx]);
-                    }
-                }
-            });
-            __builtin_amdgcn_sched_barrier(0);
+        sblk = blk;
+        auto emit_in_step = [&](auto PORTION) {
+            if constexpr (REBUILD) emit_states(PORTION);
         };
-        emit_states(std::integral_constant<int, 0>{});
+        if constexpr (REBUILD) {
+            if (a.states_saved) narrow_states();
+        }
+        emit_in_step(std::integral_constant<int, 0>{});
 
         fetch_part<T, DK, DV, DVB, REBUILD, 4, KTILE>(nxt, d, a, bh, b, h, nn, dv0);
-        emit_states(std::integral_constant<int, 1>{});
+        emit_in_step(std::integral_constant<int, 1>{});
         // ---------------- stage 1: R^T = (V - a.(K S) + pb.(K M))^T and the inter-chunk read-outs for token i,
         //                  then V~^T = R^T T^T over all 64 tokens
         f32x4 accO[MV], vt[MV]; // vt = V~ rounded to the storage type
+        typename Raw4<T>::type vb[MV]; // (the same in storage form: narrowed once, for HBM, for LDS and for vt)
         if (!REBUILD) {
             f32x4 x1[MV], x2[MV], accOS[MV], accOM[MV];
             zero_acc(x1);
@@ -295,30 +312,34 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
                 for (int mv = 0; mv < MV; ++mv)
                     accV[mv] = O::mma(TV::frag(sRt, mv, s * O::KSTEP, r, kg), cur.tm[s], accV[mv]);
 #pragma unroll
-            for (int mv = 0; mv < MV; ++mv)
-#pragma unroll
-                for (int x = 0; x < 4; ++x) vt[mv][x] = rounded<T>(accV[mv][x]);
+            for (int mv = 0; mv < MV; ++mv) {
+                vb[mv] = narrow4<T>(accV[mv]);
+                vt[mv] = widen4_packed(vb[mv]);
+            }
             if (a.vt_saved) {
-                store_cols<T, MV>(static_cast<T *>(a.vt_saved) + tok * DV + dv0 + kg * (4 * MV), vt);
+                store_cols_raw<MV>(static_cast<T *>(a.vt_saved) + tok * DV + dv0 + kg * (4 * MV), vb);
             }
         } else {
 #pragma unroll
-            for (int mv = 0; mv < MV; ++mv) vt[mv] = widen4(cur.u[mv]);
+            for (int mv = 0; mv < MV; ++mv) {
+                vb[mv] = cur.u[mv];
+                vt[mv] = widen4(cur.u[mv]);
+            }
         }
-        emit_states(std::integral_constant<int, 2>{});
+        emit_in_step(std::integral_constant<int, 2>{});
         // V~^T to LDS in the three scalings of stage 2
 #pragma unroll
         for (int mv = 0; mv < MV; ++mv) {
-            if (!REBUILD) TV::put4(sV0, mv * 16 + kg * 4, i, vt[mv]);
+            if (!REBUILD) TV::put4_raw(sV0, mv * 16 + kg * 4, i, vb[mv]);
             TV::put4(sVg, mv * 16 + kg * 4, i, cur.c1[COEF_GC - 4] * vt[mv]);
             TV::put4(sVr, mv * 16 + kg * 4, i, -cur.c1[COEF_RC - 4] * vt[mv]);
         }
-        emit_states(std::integral_constant<int, 3>{});
+        emit_in_step(std::integral_constant<int, 3>{});
         __syncthreads();
 
         // ---------------- stage 2: intra-chunk output and the state update
         fetch_part<T, DK, DV, DVB, REBUILD, 2, KTILE>(nxt, d, a, bh, b, h, nn, dv0);
-        emit_states(std::integral_constant<int, 4>{});
+        emit_in_step(std::integral_constant<int, 4>{});
         const float aC = cur.c0[COEF_AC], bC = cur.c1[COEF_BC - 4], mC = cur.c1[COEF_MC - 4];
 #pragma unroll
         for (int mv = 0; mv < MV; ++mv)
@@ -349,14 +370,28 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
                 }
             }
         }
-        emit_states(std::integral_constant<int, 5>{});
+        emit_in_step(std::integral_constant<int, 5>{});
         fetch_part<T, DK, DV, DVB, REBUILD, 3, KTILE>(nxt, d, a, bh, b, h, nn, dv0);
-        emit_states(std::integral_constant<int, 6>{});
-        if (!REBUILD) {
-            publish_state<T, DK, MV>(sSt, accS, accM);
+        emit_in_step(std::integral_constant<int, 6>{});
+        if constexpr (!REBUILD) {
+            // the states after this chunk, narrowed once: the LDS copy for the next chunk's stage 1 and, in HBM, that
+            // chunk's start states
+            narrow_states();
+#pragma unroll
+            for (int mv = 0; mv < MV; ++mv)
+#pragma unroll
+                for (int nd = 0; nd < ND; ++nd) {
+                    const int dk = (w * ND + nd) * 16 + r;
+                    TS::put4_raw(sSt, mv * 16 + kg * 4, dk, sv[2 * nd][mv]);
+                    TS::put4_raw(sSt, mv * 16 + kg * 4, DK + dk, sv[2 * nd + 1][mv]);
+                }
+            if (n + 1 < d.n1) {
+                sblk = blk + 1;
+                emit_states(std::integral_constant<int, 0>{});
+            }
             store_cols<T, MV>(static_cast<T *>(a.o) + tok * DV + dv0 + kg * (4 * MV), accO);
         }
-        emit_states(std::integral_constant<int, 7>{});
+        emit_in_step(std::integral_constant<int, 7>{});
         __syncthreads();
     };
     // two operand sets used alternately: handing one set over to the other by assignment would touch every
