@@ -62,22 +62,25 @@ __device__ __forceinline__ void fetch_part(ChunkOps<T, DK, DVB / 16> &c, const D
     typedef Op<T> O;
     typedef ChunkOps<T, DK, DVB / 16> CO;
     const int lane = lane_id(), w = wave_id() & 3, r = lane & 15, kg = lane >> 4, i = w * 16 + r;
+    // every address is a wave-uniform 64-bit base (chunk, batch, head: scalar arithmetic) plus a 32-bit lane offset that
+    // does not change from chunk to chunk (at32: one address register per access, no vector 64-bit adds)
     const size_t blk = (size_t)bh * d.N + n;
-    const size_t tok = ((size_t)b * d.T + (size_t)n * 64 + i) * d.H + h;
+    const size_t tok0 = ((size_t)b * d.T + (size_t)n * 64) * d.H + h; // the chunk's first token of this head
+    const unsigned itok = (unsigned)(i * d.H);                        // this lane's token, in token rows
     if (P == 0) {
         // (through the vector path on purpose: a scalar load would share its wait counter with the LDS reads and
         //  make the first of those wait for memory)
-        const float *coef = a.coef + blk * (kCoefRows * 64) + i * kCoefRows;
-        c.c0 = *reinterpret_cast<const f32x4 *>(coef);
-        c.c1 = *reinterpret_cast<const f32x4 *>(coef + 4);
+        const float *coef = a.coef + blk * (kCoefRows * 64);
+        c.c0 = *reinterpret_cast<const f32x4 *>(at32(coef, (unsigned)(i * kCoefRows)));
+        c.c1 = *reinterpret_cast<const f32x4 *>(at32(coef, (unsigned)(i * kCoefRows + 4)));
         // the forward reads V, the reconstruction the saved V~
-        const T *vs = static_cast<const T *>(REBUILD ? a.vt_saved : a.v) + tok * DV + dv0 + kg * (DVB / 4);
-        load_cols_raw<DVB / 16>(vs, c.u);
+        const T *vs = static_cast<const T *>(REBUILD ? a.vt_saved : a.v) + tok0 * DV + dv0;
+        load_cols_raw<DVB / 16>(at32(vs, itok * DV + kg * (DVB / 4)), c.u);
     }
     if (P == 1 && !REBUILD) {
-        const T *Qg = static_cast<const T *>(a.q) + tok * DK + kg * O::EPL;
+        const T *Qg = static_cast<const T *>(a.q) + tok0 * DK;
 #pragma unroll
-        for (int s = 0; s < CO::KS; ++s) c.q[s] = O::load(Qg + s * O::KSTEP);
+        for (int s = 0; s < CO::KS; ++s) c.q[s] = O::load(at32(Qg, itok * DK + kg * O::EPL + s * O::KSTEP));
     }
     if (P == 2 && !KTILE) {
         const T *KTg = static_cast<const T *>(a.KT) + blk * (DK * 64);
@@ -85,20 +88,20 @@ __device__ __forceinline__ void fetch_part(ChunkOps<T, DK, DVB / 16> &c, const D
         for (int nd = 0; nd < CO::ND; ++nd)
 #pragma unroll
             for (int s = 0; s < CO::KS2; ++s)
-                c.kt[nd][s] = O::load(KTg + kblk<T>(DK, (w * CO::ND + nd) * 16 + r, s * O::KSTEP + kg * O::EPL));
+                c.kt[nd][s] = O::load(at32(KTg, (unsigned)kblk<T>(DK, (w * CO::ND + nd) * 16 + r, s * O::KSTEP + kg * O::EPL)));
     }
     if (P == 3 && !REBUILD) {
         const T *Bg = static_cast<const T *>(a.Bm) + blk * 4096, *Tg = static_cast<const T *>(a.Tm) + blk * 4096;
 #pragma unroll
         for (int s = 0; s < CO::KS2; ++s) {
-            c.tm[s] = O::load(Tg + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL));
-            c.bm[s] = O::load(Bg + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL));
+            c.tm[s] = O::load(at32(Tg, (unsigned)kblk<T>(64, i, s * O::KSTEP + kg * O::EPL)));
+            c.bm[s] = O::load(at32(Bg, (unsigned)kblk<T>(64, i, s * O::KSTEP + kg * O::EPL)));
         }
     }
     if (P == 4 && !REBUILD && !KTILE) {
-        const T *Kg = static_cast<const T *>(a.k) + tok * DK + kg * O::EPL;
+        const T *Kg = static_cast<const T *>(a.k) + tok0 * DK;
 #pragma unroll
-        for (int s = 0; s < CO::KS; ++s) c.kr[s] = O::load(Kg + s * O::KSTEP);
+        for (int s = 0; s < CO::KS; ++s) c.kr[s] = O::load(at32(Kg, itok * DK + kg * O::EPL + s * O::KSTEP));
     }
     __builtin_amdgcn_sched_barrier(0); // the portion leaves here, not where the scheduler would gather the loads
 }
@@ -220,10 +223,12 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
         static_for<NS>([&](auto IDX) {
             constexpr int idx = decltype(IDX)::value, nd = idx >> 1;
             if ((REBUILD ? idx * 8 / NS : 0) == decltype(PORTION)::value) {
-                const size_t off = vblk(DK, (w * ND + nd) * 16 + r, dv0 + kg * (4 * MV));
-                store_cols_raw<MV>(st + ((idx & 1) ? DK * DV : 0) + off, sv[idx]);
+                // (dv0 is a multiple of 16: the workgroup's first column block is part of the uniform base)
+                const unsigned off = (unsigned)vblk(DK, (w * ND + nd) * 16 + r, kg * (4 * MV));
+                const size_t base = ((idx & 1) ? DK * DV : 0) + vblk(DK, 0, dv0);
+                store_cols_raw<MV>(at32(st + base, off), sv[idx]);
                 if constexpr (LO) {
-                    if (a.states_lo) store_cols_raw<MV>(stl + ((idx & 1) ? DK * DV : 0) + off, sl[idx]);
+                    if (a.states_lo) store_cols_raw<MV>(at32(stl + base, off), sl[idx]);
                 }
             }
         });
@@ -243,7 +248,8 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
     int slot = 0;
     auto step = [&](int n, const CO &cur, CO &nxt) {
         const size_t blk = (size_t)bh * d.N + n;
-        const size_t tok = ((size_t)b * d.T + (size_t)n * 64 + i) * d.H + h;
+        const size_t tok0 = ((size_t)b * d.T + (size_t)n * 64) * d.H + h; // (uniform base + 32-bit lane offset, as in fetch_part)
+        const unsigned itok = (unsigned)(i * d.H);
         const int nn = (n + 1 < d.n1) ? n + 1 : n;
         const T *kc = sKr + slot * (64 * DK);
         if (n + 2 < d.n1) request_k(n + 2, slot >= 1 ? slot - 1 : 2);
@@ -317,7 +323,7 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
                 vt[mv] = widen4_packed(vb[mv]);
             }
             if (a.vt_saved) {
-                store_cols_raw<MV>(static_cast<T *>(a.vt_saved) + tok * DV + dv0 + kg * (4 * MV), vb);
+                store_cols_raw<MV>(at32(static_cast<T *>(a.vt_saved) + tok0 * DV + dv0, itok * DV + kg * (4 * MV)), vb);
             }
         } else {
 #pragma unroll
@@ -389,7 +395,7 @@ __global__ __launch_bounds__(kThreads) void scan_fwd_kernel(Dims d, ScanFwdArgs 
                 sblk = blk + 1;
                 emit_states(std::integral_constant<int, 0>{});
             }
-            store_cols<T, MV>(static_cast<T *>(a.o) + tok * DV + dv0 + kg * (4 * MV), accO);
+            store_cols<T, MV>(at32(static_cast<T *>(a.o) + tok0 * DV + dv0, itok * DV + kg * (4 * MV)), accO);
         }
         emit_in_step(std::integral_constant<int, 7>{});
         __syncthreads();
