@@ -50,27 +50,30 @@ __device__ __forceinline__ void fetch_part(RevOps<T, DK, DVB / 16> &c, const Dim
     typedef Op<T> O;
     typedef RevOps<T, DK, DVB / 16> CO;
     const int lane = lane_id(), w = wave_id(), r = lane & 15, kg = lane >> 4, i = w * 16 + r;
+    // every address is a wave-uniform 64-bit base (chunk, batch, head: scalar arithmetic) plus a 32-bit lane offset that
+    // does not change from chunk to chunk (at32: one address register per access, no vector 64-bit adds)
     const size_t blk = (size_t)bh * d.N + n;
-    const size_t tok = ((size_t)b * d.T + (size_t)n * 64 + i) * d.H + h;
+    const size_t tok0 = ((size_t)b * d.T + (size_t)n * 64) * d.H + h; // the chunk's first token of this head
+    const unsigned itok = (unsigned)(i * d.H);                        // this lane's token, in token rows
     if (P == 0) {
         // (through the vector path on purpose: a scalar load would share its wait counter with the LDS reads and
         //  make the first of those wait for memory)
-        const float *coef = a.coef + blk * (kCoefRows * 64) + i * kCoefRows;
-        c.c0 = *reinterpret_cast<const f32x4 *>(coef);
-        c.c1 = *reinterpret_cast<const f32x4 *>(coef + 4);
-        load_cols_raw<DVB / 16>(static_cast<const T *>(a.dO) + tok * DV + dv0 + kg * (DVB / 4), c.dO);
+        const float *coef = a.coef + blk * (kCoefRows * 64);
+        c.c0 = *reinterpret_cast<const f32x4 *>(at32(coef, (unsigned)(i * kCoefRows)));
+        c.c1 = *reinterpret_cast<const f32x4 *>(at32(coef, (unsigned)(i * kCoefRows + 4)));
+        load_cols_raw<DVB / 16>(at32(static_cast<const T *>(a.dO) + tok0 * DV + dv0, itok * DV + kg * (DVB / 4)), c.dO);
     }
     if (P == 1) {
-        const T *kp = static_cast<const T *>(a.k) + tok * DK + kg * O::EPL;
+        const T *kp = static_cast<const T *>(a.k) + tok0 * DK;
 #pragma unroll
-        for (int s = 0; s < CO::KS; ++s) c.k[s] = O::load(kp + s * O::KSTEP);
+        for (int s = 0; s < CO::KS; ++s) c.k[s] = O::load(at32(kp, itok * DK + kg * O::EPL + s * O::KSTEP));
     }
     if (P == 2) {
         const T *bp = static_cast<const T *>(a.BmT) + blk * 4096, *tp = static_cast<const T *>(a.TmT) + blk * 4096;
 #pragma unroll
         for (int s = 0; s < CO::KS2; ++s) {
-            c.bmT[s] = O::load(bp + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL));
-            c.tT[s] = O::load(tp + kblk<T>(64, i, s * O::KSTEP + kg * O::EPL));
+            c.bmT[s] = O::load(at32(bp, (unsigned)kblk<T>(64, i, s * O::KSTEP + kg * O::EPL)));
+            c.tT[s] = O::load(at32(tp, (unsigned)kblk<T>(64, i, s * O::KSTEP + kg * O::EPL)));
         }
     }
     if (P == 3 || P == 4) {
@@ -79,7 +82,8 @@ __device__ __forceinline__ void fetch_part(RevOps<T, DK, DVB / 16> &c, const Dim
         for (int nd = 0; nd < CO::ND; ++nd)
 #pragma unroll
             for (int s = 0; s < CO::KS2; ++s) {
-                const typename O::Frag f = O::load(src + kblk<T>(DK, (w * CO::ND + nd) * 16 + r, s * O::KSTEP + kg * O::EPL));
+                const typename O::Frag f =
+                    O::load(at32(src, (unsigned)kblk<T>(DK, (w * CO::ND + nd) * 16 + r, s * O::KSTEP + kg * O::EPL)));
                 if (P == 3) c.qT[nd][s] = f;
                 if (P == 4) c.kT[nd][s] = f;
             }
@@ -154,9 +158,10 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
                 }
 #pragma unroll
             for (int nd = 0; nd < ND; ++nd) {
-                const size_t off = vblk(DK, (w * ND + nd) * 16 + r, dv0 + kg * (4 * MV));
-                store_cols_raw<MV>(ds + off, sv[2 * nd]);
-                store_cols_raw<MV>(ds + DK * DV + off, sv[2 * nd + 1]);
+                // (dv0 is a multiple of 16: the workgroup's first column block is part of the uniform base)
+                const unsigned off = (unsigned)vblk(DK, (w * ND + nd) * 16 + r, kg * (4 * MV));
+                store_cols_raw<MV>(at32(ds + vblk(DK, 0, dv0), off), sv[2 * nd]);
+                store_cols_raw<MV>(at32(ds + DK * DV + vblk(DK, 0, dv0), off), sv[2 * nd + 1]);
             }
             if constexpr (sizeof(T) == 2) {
                 if (a.dstates_lo) { // what the rounding above dropped, rounded again (see GradArgs)
@@ -169,9 +174,9 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
                             ls[mv] = narrow4<T>(accS[mv][nd] - widen4(sv[2 * nd][mv]));
                             lm[mv] = narrow4<T>(accM[mv][nd] - widen4(sv[2 * nd + 1][mv]));
                         }
-                        const size_t off = vblk(DK, (w * ND + nd) * 16 + r, dv0 + kg * (4 * MV));
-                        store_cols_raw<MV>(dl + off, ls);
-                        store_cols_raw<MV>(dl + DK * DV + off, lm);
+                        const unsigned off = (unsigned)vblk(DK, (w * ND + nd) * 16 + r, kg * (4 * MV));
+                        store_cols_raw<MV>(at32(dl + vblk(DK, 0, dv0), off), ls);
+                        store_cols_raw<MV>(at32(dl + DK * DV + vblk(DK, 0, dv0), off), lm);
                     }
                 }
             }
@@ -224,8 +229,8 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
                 for (int mv = 0; mv < MV; ++mv)
                     dR[mv] = O::mma(TV::frag(sDV, mv, s * O::KSTEP, r, kg), cur.tT[s], dR[mv]);
             fetch_part<T, DK, DV, DVB, 4>(nxt, d, a, bh, b, h, nn, dv0);
-            const size_t tok = ((size_t)b * d.T + (size_t)n * 64 + i) * d.H + h;
-            store_cols<T, MV>(static_cast<T *>(a.dv) + tok * DV + dv0 + kg * (4 * MV), dR);
+            const size_t tok0 = ((size_t)b * d.T + (size_t)n * 64) * d.H + h;
+            store_cols<T, MV>(at32(static_cast<T *>(a.dv) + tok0 * DV + dv0, (unsigned)(i * d.H) * DV + kg * (4 * MV)), dR);
 #pragma unroll
             for (int mv = 0; mv < MV; ++mv) {
                 TV::put4(sRa, mv * 16 + kg * 4, i, -cur.c0[COEF_A] * dR[mv]);
