@@ -153,8 +153,8 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
                     const int dk = (w * ND + nd) * 16 + r;
                     sv[2 * nd][mv] = narrow4<T>(accS[mv][nd]);
                     sv[2 * nd + 1][mv] = narrow4<T>(accM[mv][nd]);
-                    TD::put4(sD, mv * 16 + kg * 4, dk, accS[mv][nd]);
-                    TD::put4(sD, mv * 16 + kg * 4, DK + dk, accM[mv][nd]);
+                    TD::put4_raw(sD, mv * 16 + kg * 4, dk, sv[2 * nd][mv]);
+                    TD::put4_raw(sD, mv * 16 + kg * 4, DK + dk, sv[2 * nd + 1][mv]);
                 }
 #pragma unroll
             for (int nd = 0; nd < ND; ++nd) {
@@ -171,8 +171,8 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
                         typename Raw4<T>::type ls[MV], lm[MV];
 #pragma unroll
                         for (int mv = 0; mv < MV; ++mv) {
-                            ls[mv] = narrow4<T>(accS[mv][nd] - widen4(sv[2 * nd][mv]));
-                            lm[mv] = narrow4<T>(accM[mv][nd] - widen4(sv[2 * nd + 1][mv]));
+                            ls[mv] = narrow4<T>(accS[mv][nd] - widen4_packed(sv[2 * nd][mv]));
+                            lm[mv] = narrow4<T>(accM[mv][nd] - widen4_packed(sv[2 * nd + 1][mv]));
                         }
                         const unsigned off = (unsigned)vblk(DK, (w * ND + nd) * 16 + r, kg * (4 * MV));
                         store_cols_raw<MV>(at32(dl + vblk(DK, 0, dv0), off), ls);
@@ -187,7 +187,7 @@ __global__ __launch_bounds__(kThreads) void scan_bwd_kernel(Dims d, ScanBwdArgs 
         for (int mv = 0; mv < MV; ++mv) {
             const f32x4 dOw = widen4(cur.dO[mv]);
             const float sa = d.scale * cur.c0[COEF_A], sb = d.scale * cur.c0[COEF_B];
-            TV::put4(sO0, mv * 16 + kg * 4, i, dOw);
+            TV::put4_raw(sO0, mv * 16 + kg * 4, i, cur.dO[mv]);
             TV::put4(sOa, mv * 16 + kg * 4, i, sa * dOw);
             TV::put4(sOb, mv * 16 + kg * 4, i, -sb * dOw);
         }
