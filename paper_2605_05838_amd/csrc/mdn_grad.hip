@@ -52,12 +52,26 @@ constexpr int GT = 512; // threads per workgroup: 8 waves
 // row-dot partial sums, one [dk tiles][64] block each
 enum { P_DA = 0, P_DB, P_DAM, P_DBM, P_DGC, P_DRC, P_DALK, P_DETK, P_COUNT };
 
-// sum over the 4 lanes (kg = 0..3) that hold the same token column r
-__device__ __forceinline__ float reduce_kg(float v) { return add_xor32(add_xor16(v)); }
+// this lane's share of the sum over the 16 dk of one accumulator tile of t^T[dk][i] * X[i][dk] for its token
+__device__ __forceinline__ float dot4(f32x4 t, f32x4 xv) { return t[0] * xv[0] + t[1] * xv[1] + t[2] * xv[2] + t[3] * xv[3]; }
 
-// sum over the 16 dk of one accumulator tile of t^T[dk][i] * X[i][dk] for this lane's token
-__device__ __forceinline__ float coldot(f32x4 t, f32x4 xv) {
-    return reduce_kg(t[0] * xv[0] + t[1] * xv[1] + t[2] * xv[2] + t[3] * xv[3]);
+// Sums over the 4 lane groups kg = 0..3 (lanes r, r + 16, r + 32, r + 48) of TT values at once: on return the lanes of
+// group kg (kg < TT) hold the complete sum of v[kg].  The row swaps exchange one value's odd rows for the other value's
+// even rows, so one swap and one add halve TWO values: 3 swaps + 3 adds for four sums instead of 8 + 8, in the same
+// association ((row 0 + row 1) + (row 2 + row 3)) as the sum of a single value by two exchanges.
+__device__ __forceinline__ float reduce_tiles(const float (&v)[4]) {
+    typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+    u32x2 p = __builtin_amdgcn_permlane16_swap(__float_as_uint(v[0]), __float_as_uint(v[1]), false, false);
+    const float s01 = __uint_as_float(p[0]) + __uint_as_float(p[1]); // rows 0, 2: halves of v0; rows 1, 3: of v1
+    p = __builtin_amdgcn_permlane16_swap(__float_as_uint(v[2]), __float_as_uint(v[3]), false, false);
+    const float s23 = __uint_as_float(p[0]) + __uint_as_float(p[1]);
+    p = __builtin_amdgcn_permlane32_swap(__float_as_uint(s01), __float_as_uint(s23), false, false);
+    return __uint_as_float(p[0]) + __uint_as_float(p[1]);
+}
+__device__ __forceinline__ float reduce_tiles(const float (&v)[2]) {
+    typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+    const u32x2 p = __builtin_amdgcn_permlane16_swap(__float_as_uint(v[0]), __float_as_uint(v[1]), false, false);
+    return add_xor32(__uint_as_float(p[0]) + __uint_as_float(p[1])); // rows 0, 2: v0; rows 1, 3: v1
 }
 
 // keeps the compiler from moving instructions across this point (used to stop the fragment loads of
@@ -434,18 +448,25 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     // C: S and M against dO
     if (!DEEP) load_state(fM, Mg);
     state_product2(fS, fM, tDO, t1, t2);
+    // the row dots of a phase: every lane's share per token tile first, then all token tiles' sums over the lane groups
+    // at once; group kg ends up with the sums of token tile kg and writes them
+    const int itg = (tg * TT + (kg & (TT - 1))) * 16 + r;
+    float ra[TT], rb[TT], rc[TT];
 #pragma unroll
     for (int t = 0; t < TT; ++t) {
         const int it = (tg * TT + t) * 16 + r;
         const f32x4 qw = widen4(qv[t]);
-        const float da = d.scale * coldot(t1[t], qw);
-        const float db = -d.scale * coldot(t2[t], qw);
-        if (kg == 0) {
-            part(P_DA, it) = da;
-            part(P_DB, it) = db;
-        }
+        ra[t] = dot4(t1[t], qw);
+        rb[t] = dot4(t2[t], qw);
         accQ[t] += s_a[it] * t1[t] - s_b[it] * t2[t];
         store4(at32(static_cast<T *>(a.dq) + tok0 * DK, it * rsk + kt * 16 + kg * 4), d.scale * accQ[t]);
+    }
+    {
+        const float da = d.scale * reduce_tiles(ra), db = -d.scale * reduce_tiles(rb);
+        if (kg < TT) {
+            part(P_DA, itg) = da;
+            part(P_DB, itg) = db;
+        }
     }
     // D: S and M against dR
     load_state(fdM, dMg);
@@ -455,15 +476,18 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     for (int t = 0; t < TT; ++t) {
         const int it = (tg * TT + t) * 16 + r;
         const f32x4 kw = widen4(kv[t]);
-        const float al_i = s_al[it];
-        const float dam = -al_i * coldot(t1[t], kw);
-        const float dbm = al_i * coldot(t2[t], kw);
+        ra[t] = dot4(t1[t], kw);
+        rb[t] = dot4(t2[t], kw);
         accP[t] += ((it > 0) ? s_b[it - 1] : 0.f) * t2[t] - ((it > 0) ? s_a[it - 1] : 1.f) * t1[t];
-        const float dalk = coldot(accP[t], kw);
-        if (kg == 0) {
-            part(P_DAM, it) = dam;
-            part(P_DBM, it) = dbm;
-            part(P_DALK, it) = dalk;
+        rc[t] = dot4(accP[t], kw);
+    }
+    {
+        const float al_i = s_al[itg];
+        const float dam = -al_i * reduce_tiles(ra), dbm = al_i * reduce_tiles(rb), dalk = reduce_tiles(rc);
+        if (kg < TT) {
+            part(P_DAM, itg) = dam;
+            part(P_DBM, itg) = dbm;
+            part(P_DALK, itg) = dalk;
         }
     }
     if (tg == 0) {
@@ -496,17 +520,20 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     for (int t = 0; t < TT; ++t) {
         const int it = (tg * TT + t) * 16 + r;
         const f32x4 kw = widen4(kv[t]);
-        const float et_i = s_et[it];
-        const float dgc = et_i * coldot(t1[t], kw);
-        const float drc = -et_i * coldot(t2[t], kw);
+        ra[t] = dot4(t1[t], kw);
+        rb[t] = dot4(t2[t], kw);
         accK[t] += s_gC[it] * t1[t] - s_rC[it] * t2[t];
-        const float detk = coldot(accK[t], kw);
-        if (kg == 0) {
-            part(P_DGC, it) = dgc;
-            part(P_DRC, it) = drc;
-            part(P_DETK, it) = detk;
+        rc[t] = dot4(accK[t], kw);
+        store4(at32(static_cast<T *>(a.dk) + tok0 * DK, it * rsk + kt * 16 + kg * 4), s_et[it] * accK[t] + s_al[it] * accP[t]);
+    }
+    {
+        const float et_i = s_et[itg];
+        const float dgc = et_i * reduce_tiles(ra), drc = -et_i * reduce_tiles(rb), detk = reduce_tiles(rc);
+        if (kg < TT) {
+            part(P_DGC, itg) = dgc;
+            part(P_DRC, itg) = drc;
+            part(P_DETK, itg) = detk;
         }
-        store4(at32(static_cast<T *>(a.dk) + tok0 * DK, it * rsk + kt * 16 + kg * 4), et_i * accK[t] + s_al[it] * accP[t]);
     }
     p1 = reduce64(p1);
     p2 = reduce64(p2);
