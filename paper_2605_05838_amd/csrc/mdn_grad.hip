@@ -140,7 +140,7 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
         wt = w & 3;
         hf = w >> 2;
         kt = w % NKW;
-        tg = w / NKW;
+        tg = TG == 1 ? 0 : w / NKW;
         int t = threadIdx.x;
         asm volatile("" : "+v"(t));
         tid = t;
@@ -409,15 +409,22 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     zero_acc(accQ);
     zero_acc(accP);
     zero_acc(accK);
+    // W1, W2 are lower triangular ([i][j], zero for j > i): a contraction step whose 32 source tokens all lie on the zero
+    // side of the token tile adds exact zeros and is left out (a quarter of the phase's products)
 #pragma unroll
     for (int s = 0; s < KS2; ++s)
 #pragma unroll
         for (int t = 0; t < TT; ++t) {
-            const int wo = ((tg * TT + t) * 16 + r) * LDW + s * O::KSTEP + kg * E;
-            accQ[t] = O::mma(aK[s], O::load(sW1e + wo), accQ[t]);
-            accP[t] = O::mma(aK[s], O::load(sW2e + wo), accP[t]);
-            accK[t] = O::mma(aQ[s], wt_frag(sW1T, (tg * TT + t) * 16, s), accK[t]);
-            accK[t] = O::mma(aK[s], wt_frag(sW2T, (tg * TT + t) * 16, s), accK[t]);
+            const int tile = tg * TT + t, j_lo = s * O::KSTEP, j_hi = j_lo + O::KSTEP - 1; // the step's source tokens
+            const int wo = (tile * 16 + r) * LDW + s * O::KSTEP + kg * E;
+            if (j_lo <= tile * 16 + 15) { // rows i of this tile against columns j of the step: some j <= i
+                accQ[t] = O::mma(aK[s], O::load(sW1e + wo), accQ[t]);
+                accP[t] = O::mma(aK[s], O::load(sW2e + wo), accP[t]);
+            }
+            if (j_hi >= tile * 16) { // columns j of this tile against rows i of the step: some i >= j
+                accK[t] = O::mma(aQ[s], wt_frag(sW1T, tile * 16, s), accK[t]);
+                accK[t] = O::mma(aK[s], wt_frag(sW2T, tile * 16, s), accK[t]);
+            }
         }
     __syncthreads(); // the W space is free for the partial sums
 
