@@ -130,15 +130,26 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
     // through: otherwise every address and every wave-uniform offset this kernel ever forms is hoisted out of
     // the chunk loop and kept in a register for its whole duration (hundreds of them, vector and scalar).
     int w;              // wave-uniform by construction (a scalar register): branches on it are scalar
-    int wt, hf, kt, tg; // phase A: token tile, half of the j tiles; phases B-F: dk tile, token group
+    // phase A: token tile wt (rows i of the 64 x 64 matrices), first column tile jA, whether the wave also forms column
+    // tile 1 (two waves do), and the column tiles of its rows that lie above the diagonal and are only zeroed (bit jt of
+    // zt).  Only the 10 tile pairs on or below the diagonal are multiplied out; they are dealt so that the two waves of a
+    // SIMD (w, w + 4) share at most three of them (by rows alone SIMD 3 would have four and SIMD 0 one):
+    //   w:  0  1  2    3    4  5  6  7
+    //   wt: 0  1  2    3    3  1  2  3
+    //   j:  0  0  0,1  0,1  3  1  2  2        zeroed: w0 -> 1, 2, 3; w1 -> 2; w5 -> 3; w6 -> 3
+    int wt, jA, zt;
+    bool hasB;
+    int kt, tg; // phases B-F: dk tile, token group
     int tid, lane, r, kg, i; // i: this lane's token (MFMA column) in phase A
     unsigned gl;
     auto refresh_ids = [&]() {
         int ws = __builtin_amdgcn_readfirstlane(wave_id());
         asm volatile("" : "+s"(ws));
         w = ws;
-        wt = w & 3;
-        hf = w >> 2;
+        wt = (0xE7E4 >> (2 * w)) & 3;       // 0 1 2 3 3 1 2 3
+        jA = (0xA700 >> (2 * w)) & 3;       // 0 0 0 0 3 1 2 2
+        hasB = w == 2 || w == 3;
+        zt = (0x0880004E >> (4 * w)) & 15;  // E 4 0 0 0 8 8 0
         kt = w % NKW;
         tg = TG == 1 ? 0 : w / NKW;
         int t = threadIdx.x;
@@ -314,8 +325,9 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
         }
 #pragma unroll
         for (int mh = 0; mh < 2; ++mh) {
-            const int j0 = (hf * 2 + mh) * 16 + r;
             accB[mh] = accA[mh] = accQK[mh] = accKK[mh] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (mh == 1 && !hasB) continue;
+            const int j0 = (mh == 0 ? jA : 1) * 16 + r;
 #pragma unroll
             for (int s = 0; s < KSV; ++s) {
                 const Frag fv = tfrag(tVt, ldV, j0, s);
@@ -349,7 +361,8 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
         const float al_i = s_al[i];
 #pragma unroll
         for (int mh = 0; mh < 2; ++mh) {
-            const int mt = hf * 2 + mh, j0 = mt * 16 + kg * 4;
+            if (mh == 1 && !hasB) continue;
+            const int mt = mh == 0 ? jA : 1, j0 = mt * 16 + kg * 4;
             const f32x4 gam = *reinterpret_cast<const f32x4 *>(&sG[i * LDG + j0]);
             const f32x4 gprev = (i > 0) ? *reinterpret_cast<const f32x4 *>(&sG[(i - 1) * LDG + j0]) : f32x4{0.f, 0.f, 0.f, 0.f};
             const f32x4 et = *reinterpret_cast<const f32x4 *>(&s_et[j0]);
@@ -379,6 +392,27 @@ __global__ __launch_bounds__(GT) void grad_kernel(Dims d, GradArgs a) {
                 for (int x = 0; x < 4; ++x) {
                     sW1T[(j0 + x) * LDW + i] = from_f32<T>(w1s[x]);
                     sW2T[(j0 + x) * LDW + i] = from_f32<T>(w2a[x]);
+                }
+            }
+        }
+        // the tiles of this wave's rows above the diagonal: zeros in all six matrices
+#pragma unroll
+        for (int mt = 1; mt < 4; ++mt) {
+            if (!((zt >> mt) & 1)) continue;
+            const int j0 = mt * 16 + kg * 4;
+            const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+            *reinterpret_cast<f32x4 *>(&sDG1[i * LDG + j0]) = z;
+            *reinterpret_cast<f32x4 *>(&sDG2[i * LDG + j0]) = z;
+            store4(sW1e + i * LDW + j0, z);
+            store4(sW2e + i * LDW + j0, z);
+            if (WTR) {
+                store4(sW1T + i * LDW + j0, z);
+                store4(sW2T + i * LDW + j0, z);
+            } else {
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    sW1T[(j0 + x) * LDW + i] = from_f32<T>(0.f);
+                    sW2T[(j0 + x) * LDW + i] = from_f32<T>(0.f);
                 }
             }
         }
